@@ -1,0 +1,162 @@
+"""Pins for the activation quantizer, the integer accumulation, the rescale and the backward
+products of the CPU oracle.
+
+Pins: numpy's IEEE fp32 arithmetic and int64 matmul, a brute-force fp64 product of the de-quantized
+operands, the N = M reduction to the plain BitLinear layer, and a float transcription of the layer
+(Appendix B listing, with the straight-through readings of Section 2.3) run through torch autograd.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import sbn_synth
+
+
+def gaussian(shape, seed, sigma=1.0):
+    return (np.random.default_rng(seed).standard_normal(shape) * sigma).astype(np.float32)
+
+
+# ----------------------------------------------------------------------------- activation quantizer
+def test_act_quant_against_numpy_fp32():
+    X = sbn_synth.activations(64, 384, 1).float().numpy()
+    xq, sx = oracle.act_quant(X)
+    amax = np.maximum(np.abs(X).max(axis=1), np.float32(1e-5))
+    s = (np.float32(127.0) / amax).astype(np.float32)
+    prod = X * s[:, None]
+    assert prod.dtype == np.float32
+    assert np.array_equal(sx, s)
+    assert np.array_equal(xq, np.clip(np.rint(prod), -128, 127).astype(np.int8))
+    assert (np.abs(xq.astype(np.int32)).max(axis=1) == 127).all()     # every non-zero row reaches 127
+
+
+def test_act_quant_edge_rows():
+    X = sbn_synth.adversarial_activations(8, 256, 2).float().numpy()
+    xq, sx = oracle.act_quant(X)
+    assert (xq[1] == 0).all() and sx[1] == np.float32(127.0) / np.float32(1e-5)   # zero row
+    assert sx[2] == np.float32(1.0)                                               # amax = 127
+    assert np.array_equal(xq[2], np.rint(X[2]).astype(np.int8))                   # .5 ties go to even
+    assert (np.rint(X[2]) != np.floor(X[2] + 0.5)).any()                          # the ties are really there
+    # power-of-two scaling leaves the integers unchanged
+    xq4, sx4 = oracle.act_quant(X * np.float32(4.0))
+    assert np.array_equal(xq4, xq) and np.array_equal(sx4[[0, 2, 3]], (sx / np.float32(4.0))[[0, 2, 3]])
+
+
+# ----------------------------------------------------------------------------- accumulate and rescale
+@pytest.mark.parametrize("N,M", [(2, 4), (1, 4), (2, 8), (6, 8), (4, 4)])
+def test_acc_is_integer_matmul_and_linear(N, M):
+    W = gaussian((96, 256), 3, 0.02)
+    Weff, _, _ = oracle.quantize_mask(W, N, M)
+    rng = np.random.default_rng(4)
+    xa = rng.integers(-128, 128, size=(12, 256)).astype(np.int8)
+    xb = rng.integers(-60, 60, size=(12, 256)).astype(np.int8)
+    a = oracle.acc(Weff, xa)
+    assert np.array_equal(a, (xa.astype(np.int64) @ Weff.astype(np.int64).T).astype(np.int32))
+    xs = (xa.astype(np.int32) // 2 + xb.astype(np.int32)).astype(np.int8)
+    assert np.array_equal(oracle.acc(Weff, xs),
+                          oracle.acc(Weff, (xa.astype(np.int32) // 2).astype(np.int8)) + oracle.acc(Weff, xb))
+
+
+def test_forward_matches_fp64_product_of_dequantized_operands():
+    W = sbn_synth.latent_weight(160, 256, 5).float().numpy()
+    X = sbn_synth.activations(24, 256, 6).float().numpy()
+    bias = gaussian((160,), 7, 0.1)
+    Weff, _, gamma = oracle.quantize_mask(W, 2, 4)
+    y, acc, xq, sx = oracle.sparse_ternary_linear(X, Weff, gamma, bias)
+    xhat = xq.astype(np.float64) / sx.astype(np.float64)[:, None]
+    ref = xhat @ (np.float64(gamma) * Weff.astype(np.float64)).T + bias.astype(np.float64)
+    assert np.allclose(y, ref, rtol=1e-12, atol=1e-12)
+    assert np.abs(acc).max() <= 128 * 256 * 2 // 4
+
+
+def test_n_equals_m_is_plain_bitlinear():
+    # Section 2.1: y ~ gamma * matmul(W_q, x~) / s_x with no mask at all
+    W = sbn_synth.latent_weight(64, 128, 8).float().numpy()
+    X = sbn_synth.activations(8, 128, 9).float().numpy()
+    Weff, _, gamma = oracle.quantize_mask(W, 8, 8)
+    y, *_ = oracle.sparse_ternary_linear(X, Weff, gamma)
+    g = np.float32(np.abs(W).astype(np.float64).mean())
+    Wq = np.clip(np.rint(W / g), -1, 1).astype(np.float64)
+    s = np.float32(127.0) / np.abs(X).max(axis=1)
+    Xq = np.clip(np.rint(X * s[:, None]), -128, 127).astype(np.float64)
+    ref = (Xq @ Wq.T) * np.float64(g) / s.astype(np.float64)[:, None]
+    assert np.allclose(y, ref, rtol=1e-12, atol=0)
+
+
+# ----------------------------------------------------------------------------- float transcription
+class _WeightQuantMasked(torch.autograd.Function):
+    """Appendix B listing, read as: mask from latent w, scale from the whole w, quantize, then mask;
+    the backward hands the incoming gradient to w unchanged (dual straight-through estimator)."""
+
+    @staticmethod
+    def forward(ctx, w, N, M):
+        d_out, d_in = w.shape
+        a = w.abs().reshape(d_out, d_in // M, M)
+        order = torch.argsort(a, dim=-1, descending=True, stable=True)
+        mask = torch.zeros_like(a)
+        mask.scatter_(-1, order[..., :N], 1.0)
+        mask = mask.reshape(d_out, d_in)
+        scale = w.abs().double().mean().float().clamp(min=1e-5)
+        w_q = (w / scale).round().clamp(-1, 1) * scale
+        return w_q * mask
+
+    @staticmethod
+    def backward(ctx, g_out):
+        return g_out, None, None
+
+
+def _listing_forward(x, w, N, M):
+    amax = x.abs().max(dim=-1, keepdim=True).values.clamp(min=1e-5)
+    # tensor / tensor is an IEEE fp32 division; the scalar / tensor form multiplies by a reciprocal,
+    # lands one ulp off in some rows and flips the rounding of products that sit next to a .5 tie
+    s_x = torch.full_like(amax, 127.0) / amax
+    x_q = (x * s_x).round().clamp(-128, 127) / s_x
+    xd = x.double()
+    x_q = xd + (x_q.double() - xd).detach()      # identity straight-through for the activation quantizer
+    w_q = _WeightQuantMasked.apply(w, N, M)
+    return torch.nn.functional.linear(x_q, w_q.double())
+
+
+@pytest.mark.parametrize("N,M", [(2, 4), (1, 4), (2, 8), (6, 8)])
+def test_forward_backward_against_autograd_transcription(N, M):
+    W = sbn_synth.latent_weight(96, 256, 10 + N).float()
+    X = sbn_synth.activations(32, 256, 20 + M).float()
+    dY = sbn_synth.grad_output(32, 96, 30).float()
+    w = W.clone().requires_grad_(True)
+    x = X.clone().requires_grad_(True)
+    y = _listing_forward(x, w, N, M)
+    y.backward(dY.double())
+
+    Weff, mask, gamma = oracle.quantize_mask(W.numpy(), N, M)
+    y_o, _, xq, sx = oracle.sparse_ternary_linear(X.numpy(), Weff, gamma)
+    dX = oracle.backward_dx(dY.numpy(), Weff, gamma)
+    dW = oracle.backward_dw(dY.numpy(), xq, sx)
+
+    def close(a, b, tol):
+        scale = np.sqrt(np.mean(b ** 2))
+        return np.abs(a - b).max() <= tol * scale
+
+    # the transcription rounds x~/s_x and w_q*scale to fp32 once each: 1e-6 relative to the tensor's rms
+    assert close(y_o, y.detach().numpy(), 1e-6)
+    assert close(dX, x.grad.double().numpy(), 1e-6)
+    assert close(dW, w.grad.double().numpy(), 1e-6)
+    # dense gradient: masked-out weights receive gradient too
+    assert (np.abs(dW[mask == 0]) > 0).mean() > 0.99
+
+
+def test_dw_does_not_depend_on_weights_or_mask():
+    X = sbn_synth.activations(16, 128, 40).float().numpy()
+    dY = sbn_synth.grad_output(16, 32, 41).float().numpy()
+    xq, sx = oracle.act_quant(X)
+    dW = oracle.backward_dw(dY, xq, sx)
+    ref = dY.astype(np.float64).T @ (xq.astype(np.float64) / sx.astype(np.float64)[:, None])
+    assert np.allclose(dW, ref, rtol=1e-12, atol=1e-15)
+
+
+def test_dx_brute_force():
+    W = sbn_synth.latent_weight(48, 128, 42).float().numpy()
+    dY = sbn_synth.grad_output(8, 48, 43).float().numpy()
+    Weff, _, gamma = oracle.quantize_mask(W, 2, 4)
+    dX = oracle.backward_dx(dY, Weff, gamma)
+    ref = np.float64(gamma) * (dY.astype(np.float64) @ Weff.astype(np.float64))
+    assert np.allclose(dX, ref, rtol=1e-12, atol=1e-15)
