@@ -1,0 +1,166 @@
+/*
+ * sbn.h - C ABI of libsbn: the N:M-sparse ternary linear layer of Sparse-BitNet
+ * (arxiv 2603.05168) for AMD MI355X (gfx950).
+ *
+ * Conventions for every entry point
+ *   - Pointers marked "device" are HIP device pointers owned by the caller; "host" are host
+ *     pointers.  The library never allocates, frees or synchronises: a call validates its
+ *     arguments on the host, then only enqueues kernels on `stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream) and returns.
+ *   - Matrices are row-major.  W is [d_out, d_in] with d_in contiguous; groups of M consecutive
+ *     weights of a row form the N:M groups (Section 2.1, N:M definition; Section 2.2, mask).
+ *   - Supported patterns: M in {2, 4, 8}, 1 <= N <= M, d_in % M == 0.
+ *   - Return value: SBN_OK or a negative sbn_status.  All argument errors are detected before
+ *     anything is launched.  After SBN_EHIP, sbn_last_error() returns the HIP error text.
+ *   - Inputs must be finite; the result for NaN/Inf inputs is unspecified.
+ *
+ * Packed weight layout (the paper asks only that the N:M metadata have a defined layout; this one
+ * is the library's).  b = log2(M) index bits per kept weight (none when N == M).  Each row is cut
+ * into chunks of 128 consecutive weights, the last chunk zero-padded (a padded group keeps its
+ * first N positions with value 0).  Inside a chunk the kept weights form S = 128*N/M slots, group
+ * after group, ascending position within a group; a slot = (position in its group, 2-bit two's
+ * complement ternary code: 0 -> 00, +1 -> 01, -1 -> 11; 10 never occurs).  A chunk is stored as
+ *     index field,  S*b/8 bytes: slot s at bits [s*b, s*b+b) of a little-endian bit string;
+ *     code field,   S/4 bytes = S/16 little-endian 32-bit words: slot s in word s/16, and with
+ *                   v = s%16 at bits [8*(v%4) + 2*(v/4), +2) of that word.
+ * Chunks of a row, then rows, follow one another without gaps.  For 2:4 a chunk is 32 bytes
+ * (2 bits per weight): four index words (one nibble per group: pos0 | pos1 << 2) and four code
+ * words; each (index word, code word) pair describes 32 consecutive weights and feeds one lane of
+ * a CDNA4 sparse MFMA directly.
+ */
+#ifndef SBN_H
+#define SBN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SBN_OK = 0,
+    SBN_EINVAL = -1,       /* null pointer, non-positive size, N/M out of range, d_in % M != 0 */
+    SBN_EUNSUPPORTED = -2, /* valid request this build has no kernel for (e.g. sparse MFMA path, pattern not 2:4) */
+    SBN_ESIZE = -3,        /* workspace too small */
+    SBN_EALIGN = -4,       /* pointer or leading dimension not aligned as documented */
+    SBN_EHIP = -5          /* a HIP call failed; see sbn_last_error() */
+} sbn_status;
+
+typedef enum { SBN_F32 = 0, SBN_BF16 = 1 } sbn_dtype;
+
+typedef enum {
+    SBN_PATH_AUTO = 0,       /* GEMV for tokens <= 16 (2:4), sparse MFMA GEMM for 2:4 otherwise, generic else */
+    SBN_PATH_GEMV = 1,       /* decode kernel: streams the packed weights once; tokens <= 16, 2:4 */
+    SBN_PATH_SMFMAC = 2,     /* prefill/training GEMM on sparse int8 MFMA (v_smfmac); 2:4 */
+    SBN_PATH_DENSE_MFMA = 3, /* comparison path: W_eff expanded to int8 with explicit zeros, dense int8 MFMA; 2:4 */
+    SBN_PATH_GENERIC = 4     /* any supported pattern, plain integer kernel (reference speed only) */
+} sbn_path;
+
+typedef enum {
+    SBN_OP_QUANTIZE_MASK_PACK = 0,
+    SBN_OP_LINEAR = 1,
+    SBN_OP_BACKWARD = 2
+} sbn_op;
+
+/* Bytes of the packed form of a [d_out, d_in] matrix at N:M.  Host only, no GPU needed. */
+sbn_status sbn_packed_bytes(int64_t d_out, int64_t d_in, int N, int M, size_t *bytes);
+
+/* Workspace (device scratch, 256-byte aligned, contents undefined on entry and exit) the given
+ * operation needs at these sizes.  For SBN_OP_QUANTIZE_MASK_PACK `tokens` is the number of matrices
+ * packed in one batched call (1 for the single call).  Host only. */
+sbn_status sbn_workspace_bytes(sbn_op op, int64_t tokens, int64_t d_out, int64_t d_in, int N, int M,
+                               size_t *bytes);
+
+/*
+ * Weight side of the layer, every training step (Section 2.2 mask generation and quant-and-mask;
+ * Section 2.3 per-step mask recomputation; Appendix B listing, weight function):
+ *   gamma = max(mean |W| over the whole matrix, 1e-5)     (sum in fp64, rounded to fp32 once)
+ *   mask  = top-N of every M consecutive |w| of the LATENT weights, ties to the lower index
+ *   W_eff = clip(round_half_even(w / gamma), -1, +1) at the kept positions, 0 elsewhere
+ * and packs W_eff with its positions into `packed` (layout above).
+ *   W_latent  device, [d_out, ld_w] elements of type wdt, ld_w >= d_in; read only
+ *   packed    device, sbn_packed_bytes() bytes, 16-byte aligned; written
+ *   gamma     device, one float; written
+ *   workspace device, >= sbn_workspace_bytes(SBN_OP_QUANTIZE_MASK_PACK, 1, ...) bytes
+ */
+sbn_status sbn_quantize_mask_pack(const void *W_latent, sbn_dtype wdt, int64_t d_out, int64_t d_in,
+                                  int64_t ld_w, int N, int M, void *packed, float *gamma,
+                                  void *workspace, size_t ws_bytes, void *stream);
+
+/*
+ * The same for `count` matrices in one enqueue (the per-step remask of all linear weights of a
+ * model: Section 2.3).  The arrays are HOST arrays of length count; W_latent[i], packed[i],
+ * gamma[i] are device pointers as above.  All matrices share wdt, N and M; ld_w[i] == d_in[i].
+ * workspace >= sbn_workspace_bytes(SBN_OP_QUANTIZE_MASK_PACK, count, max d_out, max d_in, N, M).
+ */
+sbn_status sbn_quantize_mask_pack_batched(int count, const void *const *W_latent, sbn_dtype wdt,
+                                          const int64_t *d_out, const int64_t *d_in, int N, int M,
+                                          void *const *packed, float *const *gamma,
+                                          void *workspace, size_t ws_bytes, void *stream);
+
+/*
+ * Forward of the layer (Section 2.1 activation quantizer; Section 2.2 forward-pass equation;
+ * Appendix B listing, forward()):
+ *   s_x[t]   = 127 / max(max_k |X[t,k]|, 1e-5)                       (fp32)
+ *   xq[t,k]  = clip(round_half_even(X[t,k] * s_x[t]), -128, 127)     (int8)
+ *   acc[t,o] = sum_k W_eff[o,k] * xq[t,k]                            (int32, exact)
+ *   Y[t,o]   = acc[t,o] * gamma / s_x[t] (+ bias[o])                 (fp32)
+ *   X        device, bf16 [tokens, d_in], 16-byte aligned, d_in % 16 == 0 for the MFMA paths
+ *   packed   device, from sbn_quantize_mask_pack with the same d_out, d_in, N, M
+ *   gamma    device, one float (stays on the device between the two calls: no host sync)
+ *   bias     device, fp32 [d_out], or NULL
+ *   Y        device, fp32 [tokens, d_out]; written
+ *   xq_out   device, int8 [tokens, d_in], or NULL; written (kept for the backward call)
+ *   sx_out   device, fp32 [tokens], or NULL; written
+ *   acc_out  device, int32 [tokens, d_out], or NULL; written (the exact accumulators, for checks)
+ *   workspace >= sbn_workspace_bytes(SBN_OP_LINEAR, tokens, d_out, d_in, N, M)
+ */
+sbn_status sbn_sparse_ternary_linear(const void *X, int64_t tokens, int64_t d_in, int64_t d_out,
+                                     int N, int M, const void *packed, const float *gamma,
+                                     const float *bias, float *Y, int8_t *xq_out, float *sx_out,
+                                     int32_t *acc_out, sbn_path path, void *workspace,
+                                     size_t ws_bytes, void *stream);
+
+/*
+ * `count` independent forward problems in one enqueue (decode: every projection that is ready at
+ * the same time; also used to stream many matrices through the GEMV kernel).  HOST arrays of
+ * device pointers / sizes; all problems share N, M and path; bias is not applied.
+ * workspace >= sum over problems of sbn_workspace_bytes(SBN_OP_LINEAR, ...).
+ */
+sbn_status sbn_sparse_ternary_linear_grouped(int count, const void *const *X, const int64_t *tokens,
+                                             const int64_t *d_in, const int64_t *d_out, int N, int M,
+                                             const void *const *packed, const float *const *gamma,
+                                             float *const *Y, sbn_path path, void *workspace,
+                                             size_t ws_bytes, void *stream);
+
+/*
+ * Backward products of the layer under the dual straight-through estimator (Section 2.3;
+ * Appendix B listing, backward()): the output is linear(xq / s_x, gamma * W_eff), so
+ *   dX[t,k] = gamma * sum_o dY[t,o] * W_eff[o,k]            (bf16 out, fp32 accumulation)
+ *   dW[o,k] = sum_t dY[t,o] * xq[t,k] / s_x[t]              (bf16 out, fp32 accumulation)
+ * dW is the gradient of the LATENT weight: dense, not multiplied by the mask, no clipping window.
+ *   dY       device, bf16 [tokens, d_out], 16-byte aligned
+ *   xq, sx   device, as written by the forward call (needed only when dW != NULL)
+ *   dX, dW   device, bf16 [tokens, d_in] / [d_out, d_in], or NULL to skip that product
+ *   accumulate != 0: dW += (read-modify-write in bf16), else dW is overwritten
+ *   workspace >= sbn_workspace_bytes(SBN_OP_BACKWARD, tokens, d_out, d_in, N, M)
+ */
+sbn_status sbn_sparse_ternary_linear_backward(const void *dY, int64_t tokens, int64_t d_in,
+                                              int64_t d_out, int N, int M, const void *packed,
+                                              const float *gamma, const int8_t *xq, const float *sx,
+                                              void *dX, void *dW, int accumulate, void *workspace,
+                                              size_t ws_bytes, void *stream);
+
+/* Test hook, not timed: expands `packed` to dense W_eff (int8 [d_out, d_in]) and the 0/1 mask
+ * (uint8 [d_out, d_in]); either output may be NULL. */
+sbn_status sbn_unpack(const void *packed, int64_t d_out, int64_t d_in, int N, int M,
+                      int8_t *W_eff, uint8_t *mask, void *stream);
+
+/* Text of the last HIP error seen by this thread ("" if none). */
+const char *sbn_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SBN_H */

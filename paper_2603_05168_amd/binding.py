@@ -1,0 +1,216 @@
+"""ctypes binding of libsbn.so: argument marshalling only (see include/sbn.h for semantics).
+
+Every function takes torch tensors (or raw integers) for device buffers, passes their data
+pointers and sizes straight to the C ABI on the current torch stream, and raises SbnError on a
+non-zero status.  No step of the method runs here.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libsbn.so")
+
+SBN_OK, SBN_EINVAL, SBN_EUNSUPPORTED, SBN_ESIZE, SBN_EALIGN, SBN_EHIP = 0, -1, -2, -3, -4, -5
+SBN_F32, SBN_BF16 = 0, 1
+SBN_PATH_AUTO, SBN_PATH_GEMV, SBN_PATH_SMFMAC, SBN_PATH_DENSE_MFMA, SBN_PATH_GENERIC = 0, 1, 2, 3, 4
+SBN_OP_QUANTIZE_MASK_PACK, SBN_OP_LINEAR, SBN_OP_BACKWARD = 0, 1, 2
+
+_STATUS_NAMES = {0: "SBN_OK", -1: "SBN_EINVAL", -2: "SBN_EUNSUPPORTED", -3: "SBN_ESIZE", -4: "SBN_EALIGN", -5: "SBN_EHIP"}
+
+
+class SbnError(RuntimeError):
+    def __init__(self, status: int, where: str, detail: str = ""):
+        self.status = status
+        super().__init__(f"{where}: {_STATUS_NAMES.get(status, status)} {detail}".strip())
+
+
+def _load():
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            f"{_LIB_PATH} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'` "
+            "(hipcc, gfx950).  There is no fallback path.")
+    lib = ctypes.CDLL(_LIB_PATH)
+    i64, cint, vp, sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
+    pp = ctypes.POINTER(ctypes.c_void_p)
+    pi64 = ctypes.POINTER(ctypes.c_int64)
+    lib.sbn_last_error.restype = ctypes.c_char_p
+    lib.sbn_last_error.argtypes = []
+    lib.sbn_packed_bytes.restype = cint
+    lib.sbn_packed_bytes.argtypes = [i64, i64, cint, cint, ctypes.POINTER(sz)]
+    lib.sbn_workspace_bytes.restype = cint
+    lib.sbn_workspace_bytes.argtypes = [cint, i64, i64, i64, cint, cint, ctypes.POINTER(sz)]
+    lib.sbn_quantize_mask_pack.restype = cint
+    lib.sbn_quantize_mask_pack.argtypes = [vp, cint, i64, i64, i64, cint, cint, vp, vp, vp, sz, vp]
+    lib.sbn_quantize_mask_pack_batched.restype = cint
+    lib.sbn_quantize_mask_pack_batched.argtypes = [cint, pp, cint, pi64, pi64, cint, cint, pp, pp, vp, sz, vp]
+    lib.sbn_sparse_ternary_linear.restype = cint
+    lib.sbn_sparse_ternary_linear.argtypes = [vp, i64, i64, i64, cint, cint, vp, vp, vp, vp, vp, vp, vp, cint, vp, sz, vp]
+    lib.sbn_sparse_ternary_linear_grouped.restype = cint
+    lib.sbn_sparse_ternary_linear_grouped.argtypes = [cint, pp, pi64, pi64, pi64, cint, cint, pp, pp, pp, cint, vp, sz, vp]
+    lib.sbn_sparse_ternary_linear_backward.restype = cint
+    lib.sbn_sparse_ternary_linear_backward.argtypes = [vp, i64, i64, i64, cint, cint, vp, vp, vp, vp, vp, vp, cint, vp, sz, vp]
+    lib.sbn_unpack.restype = cint
+    lib.sbn_unpack.argtypes = [vp, i64, i64, cint, cint, vp, vp, vp]
+    return lib
+
+
+_lib = _load()
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def _ptr(t):
+    """Device (or host) address of a tensor, an int address, or None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return ctypes.c_void_p(t)
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream) if torch.cuda.is_available() else None
+
+
+def _check(status: int, where: str):
+    if status != SBN_OK:
+        detail = _lib.sbn_last_error().decode() if status == SBN_EHIP else ""
+        raise SbnError(status, where, detail)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return SBN_BF16
+    if t.dtype == torch.float32:
+        return SBN_F32
+    raise TypeError("latent weights must be bf16 or fp32")
+
+
+def sbn_last_error() -> str:
+    return _lib.sbn_last_error().decode()
+
+
+def sbn_packed_bytes(d_out: int, d_in: int, N: int, M: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(_lib.sbn_packed_bytes(d_out, d_in, N, M, ctypes.byref(out)), "sbn_packed_bytes")
+    return out.value
+
+
+def sbn_workspace_bytes(op: int, tokens: int, d_out: int, d_in: int, N: int, M: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(_lib.sbn_workspace_bytes(op, tokens, d_out, d_in, N, M, ctypes.byref(out)), "sbn_workspace_bytes")
+    return out.value
+
+
+def sbn_quantize_mask_pack(W_latent, N: int, M: int, packed, gamma, workspace, ld_w: int | None = None):
+    d_out, d_in = W_latent.shape
+    ld = W_latent.stride(0) if ld_w is None else ld_w
+    _check(_lib.sbn_quantize_mask_pack(_ptr(W_latent), _dtype_code(W_latent), d_out, d_in, ld, N, M, _ptr(packed),
+                                       _ptr(gamma), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                       _stream()), "sbn_quantize_mask_pack")
+
+
+def _ptr_array(tensors):
+    arr = (ctypes.c_void_p * len(tensors))()
+    for i, t in enumerate(tensors):
+        arr[i] = t.data_ptr() if not isinstance(t, int) else t
+    return arr
+
+
+def _i64_array(values):
+    arr = (ctypes.c_int64 * len(values))()
+    for i, v in enumerate(values):
+        arr[i] = int(v)
+    return arr
+
+
+class PackBatch:
+    """Host-side argument arrays of sbn_quantize_mask_pack_batched, marshalled once and reusable."""
+
+    def __init__(self, W_list, N, M, packed_list, gamma_list, workspace):
+        self.count = len(W_list)
+        self.dtype = _dtype_code(W_list[0])
+        self.W = _ptr_array(W_list)
+        self.d_out = _i64_array([w.shape[0] for w in W_list])
+        self.d_in = _i64_array([w.shape[1] for w in W_list])
+        self.packed = _ptr_array(packed_list)
+        self.gamma = _ptr_array(gamma_list)
+        self.N, self.M = N, M
+        self.workspace = workspace
+        self.keep = (W_list, packed_list, gamma_list)
+
+    def run(self):
+        ws = self.workspace
+        _check(_lib.sbn_quantize_mask_pack_batched(self.count, self.W, self.dtype, self.d_out, self.d_in, self.N,
+                                                   self.M, self.packed, self.gamma, _ptr(ws),
+                                                   ws.numel() * ws.element_size(), _stream()),
+               "sbn_quantize_mask_pack_batched")
+
+
+def sbn_quantize_mask_pack_batched(W_list, N: int, M: int, packed_list, gamma_list, workspace):
+    PackBatch(W_list, N, M, packed_list, gamma_list, workspace).run()
+
+
+def sbn_sparse_ternary_linear(X, packed, gamma, Y, N: int, M: int, workspace, bias=None, xq_out=None, sx_out=None,
+                              acc_out=None, path: int = SBN_PATH_AUTO):
+    tokens, d_in = X.shape
+    d_out = Y.shape[1]
+    if X.dtype != torch.bfloat16 or Y.dtype != torch.float32:
+        raise TypeError("X must be bf16 and Y fp32")
+    _check(_lib.sbn_sparse_ternary_linear(_ptr(X), tokens, d_in, d_out, N, M, _ptr(packed), _ptr(gamma), _ptr(bias),
+                                          _ptr(Y), _ptr(xq_out), _ptr(sx_out), _ptr(acc_out), path, _ptr(workspace),
+                                          workspace.numel() * workspace.element_size(), _stream()),
+           "sbn_sparse_ternary_linear")
+
+
+class LinearGroup:
+    """Host-side argument arrays of sbn_sparse_ternary_linear_grouped, marshalled once and reusable."""
+
+    def __init__(self, X_list, packed_list, gamma_list, Y_list, N, M, workspace, path=SBN_PATH_AUTO):
+        self.count = len(X_list)
+        self.X = _ptr_array(X_list)
+        self.tokens = _i64_array([x.shape[0] for x in X_list])
+        self.d_in = _i64_array([x.shape[1] for x in X_list])
+        self.d_out = _i64_array([y.shape[1] for y in Y_list])
+        self.packed = _ptr_array(packed_list)
+        self.gamma = _ptr_array(gamma_list)
+        self.Y = _ptr_array(Y_list)
+        self.N, self.M, self.path, self.workspace = N, M, path, workspace
+        self.keep = (X_list, packed_list, gamma_list, Y_list)
+
+    def run(self):
+        ws = self.workspace
+        _check(_lib.sbn_sparse_ternary_linear_grouped(self.count, self.X, self.tokens, self.d_in, self.d_out, self.N,
+                                                      self.M, self.packed, self.gamma, self.Y, self.path, _ptr(ws),
+                                                      ws.numel() * ws.element_size(), _stream()),
+               "sbn_sparse_ternary_linear_grouped")
+
+
+def sbn_sparse_ternary_linear_grouped(X_list, packed_list, gamma_list, Y_list, N, M, workspace, path=SBN_PATH_AUTO):
+    LinearGroup(X_list, packed_list, gamma_list, Y_list, N, M, workspace, path).run()
+
+
+def sbn_sparse_ternary_linear_backward(dY, packed, gamma, xq, sx, N: int, M: int, workspace, d_in: int, dX=None, dW=None,
+                                       accumulate: bool = False):
+    tokens, d_out = dY.shape
+    if dY.dtype != torch.bfloat16:
+        raise TypeError("dY must be bf16")
+    _check(_lib.sbn_sparse_ternary_linear_backward(_ptr(dY), tokens, d_in, d_out, N, M, _ptr(packed), _ptr(gamma),
+                                                   _ptr(xq), _ptr(sx), _ptr(dX), _ptr(dW), int(accumulate),
+                                                   _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                                   _stream()), "sbn_sparse_ternary_linear_backward")
+
+
+def sbn_unpack(packed, d_out: int, d_in: int, N: int, M: int, W_eff=None, mask=None):
+    _check(_lib.sbn_unpack(_ptr(packed), d_out, d_in, N, M, _ptr(W_eff), _ptr(mask), _stream()), "sbn_unpack")
+
+
+def new_workspace(nbytes: int, device="cuda") -> torch.Tensor:
+    """Device scratch of at least nbytes (torch's allocator returns 512-byte aligned blocks)."""
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)

@@ -1,0 +1,252 @@
+// extern "C" entry points of libsbn: argument validation on the host, workspace carving, dispatch.
+// Nothing here allocates or synchronises; every check happens before the first launch.
+#include <string>
+#include <vector>
+
+#include "sbn_internal.hpp"
+
+namespace sbn {
+
+static thread_local std::string g_last_error;
+
+void set_hip_error(hipError_t e, const char *what)
+{
+    g_last_error = std::string(what) + ": " + hipGetErrorString(e);
+}
+
+sbn_status check_launch(const char *what)
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_hip_error(e, what);
+        return SBN_EHIP;
+    }
+    return SBN_OK;
+}
+
+static sbn_status check_shape(int64_t d_out, int64_t d_in, int N, int M, Pattern &pat)
+{
+    if (d_out <= 0 || d_in <= 0) return SBN_EINVAL;
+    if (!make_pattern(N, M, pat)) return SBN_EINVAL;
+    if (d_in % M != 0) return SBN_EINVAL;
+    // index arithmetic in the kernels is 32-bit per matrix in a few places
+    if (d_out * ceil_div(d_in, CHUNK) >= (int64_t)1 << 31) return SBN_EUNSUPPORTED;
+    return SBN_OK;
+}
+
+static sbn_path resolve_path(sbn_path path, int64_t tokens, const Pattern &pat)
+{
+    if (path != SBN_PATH_AUTO) return path;
+    const bool is24 = pat.N == 2 && pat.M == 4;
+    if (!is24) return SBN_PATH_GENERIC;
+    return tokens <= 16 ? SBN_PATH_GEMV : SBN_PATH_SMFMAC;
+}
+
+}  // namespace sbn
+
+using namespace sbn;
+
+extern "C" {
+
+const char *sbn_last_error(void) { return g_last_error.c_str(); }
+
+sbn_status sbn_packed_bytes(int64_t d_out, int64_t d_in, int N, int M, size_t *bytes)
+{
+    Pattern pat;
+    if (!bytes) return SBN_EINVAL;
+    sbn_status st = check_shape(d_out, d_in, N, M, pat);
+    if (st != SBN_OK) return st;
+    *bytes = (size_t)d_out * (size_t)ceil_div(d_in, CHUNK) * (size_t)pat.chunk_bytes;
+    return SBN_OK;
+}
+
+sbn_status sbn_workspace_bytes(sbn_op op, int64_t tokens, int64_t d_out, int64_t d_in, int N, int M, size_t *bytes)
+{
+    Pattern pat;
+    if (!bytes || tokens <= 0) return SBN_EINVAL;
+    sbn_status st = check_shape(d_out, d_in, N, M, pat);
+    if (st != SBN_OK) return st;
+    switch (op) {
+    case SBN_OP_QUANTIZE_MASK_PACK: *bytes = pack_workspace_bytes(tokens, d_out, d_in); return SBN_OK;
+    case SBN_OP_LINEAR: *bytes = linear_workspace_bytes(tokens, d_out, d_in); return SBN_OK;
+    case SBN_OP_BACKWARD: *bytes = backward_workspace_bytes(tokens, d_out, d_in); return SBN_OK;
+    }
+    return SBN_EINVAL;
+}
+
+sbn_status sbn_quantize_mask_pack(const void *W_latent, sbn_dtype wdt, int64_t d_out, int64_t d_in, int64_t ld_w,
+                                  int N, int M, void *packed, float *gamma, void *workspace, size_t ws_bytes,
+                                  void *stream)
+{
+    Pattern pat;
+    if (!W_latent || !packed || !gamma || !workspace) return SBN_EINVAL;
+    if (wdt != SBN_F32 && wdt != SBN_BF16) return SBN_EINVAL;
+    sbn_status st = check_shape(d_out, d_in, N, M, pat);
+    if (st != SBN_OK) return st;
+    if (ld_w < d_in) return SBN_EINVAL;
+    if (!aligned(packed, 16) || !aligned(gamma, 4) || !aligned(workspace, 256)) return SBN_EALIGN;
+    if (!aligned(W_latent, wdt == SBN_BF16 ? 2 : 4)) return SBN_EALIGN;
+    PackItem it{W_latent, static_cast<uint8_t *>(packed), gamma, d_out, d_in, ld_w};
+    return launch_pack(1, &it, wdt, pat, workspace, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+sbn_status sbn_quantize_mask_pack_batched(int count, const void *const *W_latent, sbn_dtype wdt, const int64_t *d_out,
+                                          const int64_t *d_in, int N, int M, void *const *packed,
+                                          float *const *gamma, void *workspace, size_t ws_bytes, void *stream)
+{
+    if (count <= 0 || count > 4096 || !W_latent || !d_out || !d_in || !packed || !gamma || !workspace) return SBN_EINVAL;
+    if (wdt != SBN_F32 && wdt != SBN_BF16) return SBN_EINVAL;
+    if (!aligned(workspace, 256)) return SBN_EALIGN;
+    Pattern pat;
+    static thread_local std::vector<PackItem> tl_items;   // host-side descriptor list, reused between calls
+    tl_items.resize(count);
+    for (int i = 0; i < count; ++i) {
+        if (!W_latent[i] || !packed[i] || !gamma[i]) return SBN_EINVAL;
+        sbn_status st = check_shape(d_out[i], d_in[i], N, M, pat);
+        if (st != SBN_OK) return st;
+        if (!aligned(packed[i], 16) || !aligned(gamma[i], 4)) return SBN_EALIGN;
+        if (!aligned(W_latent[i], wdt == SBN_BF16 ? 2 : 4)) return SBN_EALIGN;
+        tl_items[i] = PackItem{W_latent[i], static_cast<uint8_t *>(packed[i]), gamma[i], d_out[i], d_in[i], d_in[i]};
+    }
+    return launch_pack(count, tl_items.data(), wdt, pat, workspace, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+sbn_status sbn_unpack(const void *packed, int64_t d_out, int64_t d_in, int N, int M, int8_t *W_eff, uint8_t *mask,
+                      void *stream)
+{
+    Pattern pat;
+    if (!packed || (!W_eff && !mask)) return SBN_EINVAL;
+    sbn_status st = check_shape(d_out, d_in, N, M, pat);
+    if (st != SBN_OK) return st;
+    return launch_unpack(packed, d_out, d_in, pat, W_eff, mask, static_cast<hipStream_t>(stream));
+}
+
+static sbn_status linear_one(const LinearItem &it_in, const Pattern &pat, sbn_path path, void *workspace,
+                             size_t ws_bytes, hipStream_t stream)
+{
+    LinearItem it = it_in;
+    const bool is24 = pat.N == 2 && pat.M == 4;
+    path = resolve_path(path, it.tokens, pat);
+    if (path != SBN_PATH_GENERIC && !is24) return SBN_EUNSUPPORTED;
+    if (path == SBN_PATH_GEMV && it.tokens > 16) return SBN_EUNSUPPORTED;
+    if ((path == SBN_PATH_GEMV || path == SBN_PATH_SMFMAC || path == SBN_PATH_DENSE_MFMA) && it.d_in % CHUNK != 0)
+        return SBN_EUNSUPPORTED;
+    if (ws_bytes < linear_workspace_bytes(it.tokens, it.d_out, it.d_in)) return SBN_ESIZE;
+    // workspace: [xq int8 tokens*d_in][sx fp32 tokens][dense int8 W for the comparison path]
+    uint8_t *ws = static_cast<uint8_t *>(workspace);
+    const size_t xq_bytes = align_up((size_t)it.tokens * it.d_in, 256);
+    const size_t sx_bytes = align_up((size_t)it.tokens * sizeof(float), 256);
+    if (!it.xq) it.xq = reinterpret_cast<int8_t *>(ws);
+    if (!it.sx) it.sx = reinterpret_cast<float *>(ws + xq_bytes);
+    int8_t *w_dense = reinterpret_cast<int8_t *>(ws + xq_bytes + sx_bytes);
+
+    sbn_status st = launch_act_quant(it.X, it.tokens, it.d_in, it.xq, it.sx, stream);
+    if (st != SBN_OK) return st;
+    switch (path) {
+    case SBN_PATH_GEMV: return launch_gemv(1, &it, stream);
+    case SBN_PATH_SMFMAC: return launch_gemm_smfmac(it, stream);
+    case SBN_PATH_DENSE_MFMA: return launch_gemm_dense(it, w_dense, stream);
+    case SBN_PATH_GENERIC: return launch_linear_generic(it, pat, stream);
+    default: return SBN_EINVAL;
+    }
+}
+
+sbn_status sbn_sparse_ternary_linear(const void *X, int64_t tokens, int64_t d_in, int64_t d_out, int N, int M,
+                                     const void *packed, const float *gamma, const float *bias, float *Y,
+                                     int8_t *xq_out, float *sx_out, int32_t *acc_out, sbn_path path, void *workspace,
+                                     size_t ws_bytes, void *stream)
+{
+    Pattern pat;
+    if (!X || !packed || !gamma || !Y || !workspace || tokens <= 0) return SBN_EINVAL;
+    if (path < SBN_PATH_AUTO || path > SBN_PATH_GENERIC) return SBN_EINVAL;
+    sbn_status st = check_shape(d_out, d_in, N, M, pat);
+    if (st != SBN_OK) return st;
+    if (tokens * d_out >= (int64_t)1 << 40) return SBN_EUNSUPPORTED;
+    if (!aligned(X, 16) || !aligned(packed, 16) || !aligned(Y, 16) || !aligned(workspace, 256)) return SBN_EALIGN;
+    if (xq_out && !aligned(xq_out, 16)) return SBN_EALIGN;
+    if (acc_out && !aligned(acc_out, 16)) return SBN_EALIGN;
+    if (d_in % 8 != 0) return SBN_EUNSUPPORTED;   // bf16 rows are read in 16-byte vectors
+    LinearItem it{X, packed, gamma, bias, Y, xq_out, sx_out, acc_out, tokens, d_in, d_out};
+    return linear_one(it, pat, path, workspace, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+sbn_status sbn_sparse_ternary_linear_grouped(int count, const void *const *X, const int64_t *tokens,
+                                             const int64_t *d_in, const int64_t *d_out, int N, int M,
+                                             const void *const *packed, const float *const *gamma, float *const *Y,
+                                             sbn_path path, void *workspace, size_t ws_bytes, void *stream)
+{
+    if (count <= 0 || count > 4096 || !X || !tokens || !d_in || !d_out || !packed || !gamma || !Y || !workspace)
+        return SBN_EINVAL;
+    if (path < SBN_PATH_AUTO || path > SBN_PATH_GENERIC) return SBN_EINVAL;
+    if (!aligned(workspace, 256)) return SBN_EALIGN;
+    Pattern pat;
+    size_t need = 0;
+    bool all_gemv = true;
+    for (int i = 0; i < count; ++i) {
+        if (!X[i] || !packed[i] || !gamma[i] || !Y[i] || tokens[i] <= 0) return SBN_EINVAL;
+        sbn_status st = check_shape(d_out[i], d_in[i], N, M, pat);
+        if (st != SBN_OK) return st;
+        if (!aligned(X[i], 16) || !aligned(packed[i], 16) || !aligned(Y[i], 16)) return SBN_EALIGN;
+        if (d_in[i] % 8 != 0) return SBN_EUNSUPPORTED;
+        need += linear_workspace_bytes(tokens[i], d_out[i], d_in[i]);
+        if (resolve_path(path, tokens[i], pat) != SBN_PATH_GEMV || tokens[i] > 16 || d_in[i] % CHUNK != 0)
+            all_gemv = false;
+    }
+    if (ws_bytes < need) return SBN_ESIZE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint8_t *ws = static_cast<uint8_t *>(workspace);
+    if (!all_gemv) {
+        // no grouped kernel for the GEMM paths: one enqueue per problem
+        for (int i = 0; i < count; ++i) {
+            LinearItem it{X[i], packed[i], gamma[i], nullptr, Y[i], nullptr, nullptr, nullptr, tokens[i], d_in[i], d_out[i]};
+            const size_t wsz = linear_workspace_bytes(tokens[i], d_out[i], d_in[i]);
+            sbn_status st = linear_one(it, pat, path, ws, wsz, s);
+            if (st != SBN_OK) return st;
+            ws += wsz;
+        }
+        return SBN_OK;
+    }
+    static thread_local std::vector<LinearItem> tl_items;   // host-side descriptor list, reused between calls
+    tl_items.resize(count);
+    for (int i = 0; i < count; ++i) {
+        LinearItem &it = tl_items[i];
+        it = LinearItem{X[i], packed[i], gamma[i], nullptr, Y[i], nullptr, nullptr, nullptr, tokens[i], d_in[i], d_out[i]};
+        it.xq = reinterpret_cast<int8_t *>(ws);
+        it.sx = reinterpret_cast<float *>(ws + align_up((size_t)tokens[i] * d_in[i], 256));
+        ws += linear_workspace_bytes(tokens[i], d_out[i], d_in[i]);
+        // identical X pointers share one quantization
+        bool shared = false;
+        for (int j = 0; j < i && !shared; ++j)
+            if (X[j] == X[i] && tokens[j] == tokens[i] && d_in[j] == d_in[i]) {
+                it.xq = tl_items[j].xq;
+                it.sx = tl_items[j].sx;
+                shared = true;
+            }
+        if (!shared) {
+            sbn_status st = launch_act_quant(it.X, it.tokens, it.d_in, it.xq, it.sx, s);
+            if (st != SBN_OK) return st;
+        }
+    }
+    return launch_gemv(count, tl_items.data(), s);
+}
+
+sbn_status sbn_sparse_ternary_linear_backward(const void *dY, int64_t tokens, int64_t d_in, int64_t d_out, int N,
+                                              int M, const void *packed, const float *gamma, const int8_t *xq,
+                                              const float *sx, void *dX, void *dW, int accumulate, void *workspace,
+                                              size_t ws_bytes, void *stream)
+{
+    Pattern pat;
+    if (!dY || !workspace || tokens <= 0 || (!dX && !dW)) return SBN_EINVAL;
+    if (dX && (!packed || !gamma)) return SBN_EINVAL;
+    if (dW && (!xq || !sx)) return SBN_EINVAL;
+    sbn_status st = check_shape(d_out, d_in, N, M, pat);
+    if (st != SBN_OK) return st;
+    if (!aligned(dY, 16) || !aligned(workspace, 256)) return SBN_EALIGN;
+    if ((dX && !aligned(dX, 16)) || (dW && !aligned(dW, 16)) || (xq && !aligned(xq, 16))) return SBN_EALIGN;
+    if (d_in % 8 != 0 || d_out % 8 != 0) return SBN_EUNSUPPORTED;
+    if (ws_bytes < backward_workspace_bytes(tokens, d_out, d_in)) return SBN_ESIZE;
+    return launch_backward(dY, tokens, d_in, d_out, pat, packed, gamma, xq, sx, dX, dW, accumulate, workspace,
+                           ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

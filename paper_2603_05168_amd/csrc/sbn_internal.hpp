@@ -1,0 +1,87 @@
+// Internal declarations shared by the translation units of libsbn (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/sbn.h"
+
+namespace sbn {
+
+// Geometry of the packed layout for one N:M pattern (see include/sbn.h).
+struct Pattern {
+    int N, M;
+    int b;            // index bits per slot (0 when N == M)
+    int slots;        // slots per 128-weight chunk
+    int idx_bytes;    // bytes of the index field of a chunk
+    int code_bytes;   // bytes of the code field of a chunk
+    int chunk_bytes;  // idx_bytes + code_bytes
+};
+
+inline bool make_pattern(int N, int M, Pattern &p)
+{
+    int b = M == 2 ? 1 : M == 4 ? 2 : M == 8 ? 3 : -1;
+    if (b < 0 || N < 1 || N > M) return false;
+    if (N == M) b = 0;
+    p.N = N;
+    p.M = M;
+    p.b = b;
+    p.slots = 128 * N / M;
+    p.idx_bytes = p.slots * b / 8;
+    p.code_bytes = p.slots / 4;
+    p.chunk_bytes = p.idx_bytes + p.code_bytes;
+    return true;
+}
+
+constexpr int CHUNK = 128;  // weights per chunk of the packed layout
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+// error text of the last failed HIP call of this thread
+void set_hip_error(hipError_t e, const char *what);
+sbn_status check_launch(const char *what);
+
+// ---- pack (sbn_pack.hip) --------------------------------------------------------------------
+struct PackItem {
+    const void *W;
+    uint8_t *packed;
+    float *gamma;
+    int64_t d_out, d_in, ld;
+};
+constexpr int PACK_MAX_ITEMS = 48;     // matrices per launch (descriptor table travels as kernel argument)
+constexpr int64_t PACK_SUM_ELEMS = 16384;  // elements reduced by one block of the absmean pass
+size_t pack_workspace_bytes(int64_t count, int64_t d_out, int64_t d_in);
+sbn_status launch_pack(int count, const PackItem *items, sbn_dtype wdt, const Pattern &pat,
+                       void *workspace, size_t ws_bytes, hipStream_t stream);
+sbn_status launch_unpack(const void *packed, int64_t d_out, int64_t d_in, const Pattern &pat,
+                         int8_t *W_eff, uint8_t *mask, hipStream_t stream);
+
+// ---- forward (sbn_linear.hip) ----------------------------------------------------------------
+struct LinearItem {
+    const void *X;        // bf16 [tokens, d_in]
+    const void *packed;
+    const float *gamma;
+    const float *bias;    // may be null
+    float *Y;
+    int8_t *xq;           // int8 [tokens, d_in] (caller's buffer or workspace)
+    float *sx;            // fp32 [tokens]
+    int32_t *acc_out;     // may be null
+    int64_t tokens, d_in, d_out;
+};
+size_t linear_workspace_bytes(int64_t tokens, int64_t d_out, int64_t d_in);
+sbn_status launch_act_quant(const void *X, int64_t tokens, int64_t d_in, int8_t *xq, float *sx,
+                            hipStream_t stream);
+sbn_status launch_gemv(int count, const LinearItem *items, hipStream_t stream);
+sbn_status launch_gemm_smfmac(const LinearItem &it, hipStream_t stream);
+sbn_status launch_gemm_dense(const LinearItem &it, int8_t *w_dense, hipStream_t stream);
+sbn_status launch_linear_generic(const LinearItem &it, const Pattern &pat, hipStream_t stream);
+
+// ---- backward (sbn_backward.hip) ---------------------------------------------------------------
+size_t backward_workspace_bytes(int64_t tokens, int64_t d_out, int64_t d_in);
+sbn_status launch_backward(const void *dY, int64_t tokens, int64_t d_in, int64_t d_out,
+                           const Pattern &pat, const void *packed, const float *gamma,
+                           const int8_t *xq, const float *sx, void *dX, void *dW, int accumulate,
+                           void *workspace, size_t ws_bytes, hipStream_t stream);
+
+}  // namespace sbn

@@ -1,0 +1,246 @@
+// Forward of the N:M-sparse ternary linear layer: activation quantizer, decode GEMV, generic path.
+// Section 2.1 (per-token absmax int8 activations), Section 2.2 (forward-pass equation),
+// Appendix B listing (forward()).
+#include "sbn_internal.hpp"
+#include "sbn_mfma.hpp"
+
+namespace sbn {
+
+namespace {
+
+// ---- activation quantizer -----------------------------------------------------------------------
+// One wavefront per token.  Pass 1 takes the maximum magnitude on the bf16 bit patterns (exact),
+// pass 2 re-reads the row (cache resident) and writes int8.  s_x = 127 / max(amax, 1e-5) is one
+// IEEE fp32 division, x * s_x one fp32 multiply, rounding is half-to-even.
+__global__ void __launch_bounds__(256) act_quant_kernel(const uint4 *__restrict__ X, int64_t tokens, int nvec,
+                                                       int8_t *__restrict__ xq, float *__restrict__ sx)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= tokens) return;
+    const uint4 *row = X + t * nvec;
+    uint32_t m = 0;
+    for (int v = lane; v < nvec; v += 64) {
+        const uint4 d = row[v];
+        const uint32_t w[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t lo = w[i] & 0x7fffu, hi = (w[i] >> 16) & 0x7fffu;
+            m = lo > m ? lo : m;
+            m = hi > m ? hi : m;
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const uint32_t o = (uint32_t)__shfl_xor((int)m, off, 64);
+        m = o > m ? o : m;
+    }
+    float amax = __uint_as_float(m << 16);
+    amax = amax < 1e-5f ? 1e-5f : amax;
+    const float s = __fdiv_rn(127.0f, amax);
+    if (lane == 0) sx[t] = s;
+    uint2 *out = reinterpret_cast<uint2 *>(xq + t * (int64_t)nvec * 8);
+    for (int v = lane; v < nvec; v += 64) {
+        const uint4 d = row[v];
+        const uint32_t w[4] = {d.x, d.y, d.z, d.w};
+        uint32_t packed[2] = {0, 0};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const float x = __uint_as_float(h ? (w[i] & 0xffff0000u) : (w[i] << 16));
+                float q = rintf(__fmul_rn(x, s));
+                q = q > 127.0f ? 127.0f : q;
+                q = q < -128.0f ? -128.0f : q;
+                const uint32_t byte = (uint32_t)(int)q & 0xffu;
+                const int e = 2 * i + h;
+                packed[e >> 2] |= byte << (8 * (e & 3));
+            }
+        }
+        out[v] = make_uint2(packed[0], packed[1]);
+    }
+}
+
+// ---- decode GEMV on the sparse MFMA (tokens <= 16, 2:4) -----------------------------------------
+// A block owns 16 rows of W.  Its wavefronts split the input dimension in super-steps of 512
+// weights: for such a super-step a lane (row r = lane % 16, quarter c = lane / 16) loads the whole
+// 32-byte chunk c of its row (one 16-byte index load, one 16-byte code load; a wavefront reads
+// 128 contiguous bytes per row), then issues four v_smfmac_i32_16x16x128_i8, the j-th using index
+// word j and code word j.  The tokens are the B operand (16 columns; columns >= tokens are zero).
+// Partial accumulators of the wavefronts are summed through LDS, rescaled and stored.
+struct GemvItem {
+    const int8_t *xq;
+    const float *sx;
+    const uint8_t *packed;
+    const float *gamma;
+    const float *bias;
+    float *Y;
+    int32_t *acc_out;
+    int d_in, d_out, tokens, block0;
+};
+constexpr int GEMV_MAX_ITEMS = 48;
+struct GemvTable {
+    GemvItem it[GEMV_MAX_ITEMS];
+    int count;
+    int total_blocks;
+};
+
+__global__ void __launch_bounds__(1024) gemv_smfmac_kernel(GemvTable tab)
+{
+    __shared__ v4i red[16][64];
+    int item = 0;
+    while (item + 1 < tab.count && (int)blockIdx.x >= tab.it[item + 1].block0) ++item;
+    const GemvItem &it = tab.it[item];
+    const int row0 = ((int)blockIdx.x - it.block0) * 16;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    const int r = lane & 15, c4 = lane >> 4;
+    const int K = it.d_in, nchunks = K / CHUNK, nsuper = (nchunks + 3) / 4;
+    int row = row0 + r;
+    row = row < it.d_out ? row : it.d_out - 1;   // rows past the end are computed and dropped
+    const uint8_t *wrow = it.packed + (int64_t)row * nchunks * 32;
+    const bool tok_ok = r < it.tokens;           // as B operand the lane holds token r
+    const int8_t *xrow = it.xq + (int64_t)(tok_ok ? r : 0) * K;
+
+    v4i acc = {0, 0, 0, 0};
+    for (int s = wave; s < nsuper; s += nwaves) {
+        const int chunk = 4 * s + c4;
+        uint4 idx4 = make_uint4(0, 0, 0, 0), code4 = make_uint4(0, 0, 0, 0);
+        if (chunk < nchunks) {
+            idx4 = *reinterpret_cast<const uint4 *>(wrow + (int64_t)chunk * 32);
+            code4 = *reinterpret_cast<const uint4 *>(wrow + (int64_t)chunk * 32 + 16);
+        }
+        const uint32_t idxw[4] = {idx4.x, idx4.y, idx4.z, idx4.w};
+        const uint32_t codew[4] = {code4.x, code4.y, code4.z, code4.w};
+        // B operand: elements 0..15 pair with the A lanes of quarters 0/1, elements 16..31 with
+        // quarters 2/3 (measured operand layout of the instruction)
+        const int kb = s * 512 + 128 * (c4 >> 1) + 16 * (c4 & 1);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int k_lo = kb + 32 * j, k_hi = k_lo + 256;
+            uint4 blo = make_uint4(0, 0, 0, 0), bhi = make_uint4(0, 0, 0, 0);
+            if (tok_ok && k_lo < K) blo = *reinterpret_cast<const uint4 *>(xrow + k_lo);
+            if (tok_ok && k_hi < K) bhi = *reinterpret_cast<const uint4 *>(xrow + k_hi);
+            const v8i b = {(int)blo.x, (int)blo.y, (int)blo.z, (int)blo.w, (int)bhi.x, (int)bhi.y, (int)bhi.z, (int)bhi.w};
+            acc = __builtin_amdgcn_smfmac_i32_16x16x128_i8(expand_codes(codew[j]), b, acc, (int)idxw[j], 0, 0);
+        }
+    }
+    red[wave][lane] = acc;
+    __syncthreads();
+    if (wave == 0) {
+        for (int w = 1; w < nwaves; ++w) acc += red[w][lane];
+        // D layout: lane holds token (lane % 16), rows 4 * (lane / 16) + i
+        const int tok = lane & 15, rbase = row0 + 4 * (lane >> 4);
+        if (tok < it.tokens) {
+            const float scale = __fdiv_rn(*it.gamma, it.sx[tok]);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int o = rbase + i;
+                if (o < it.d_out) {
+                    float y = (float)acc[i] * scale;
+                    if (it.bias) y += it.bias[o];
+                    it.Y[(int64_t)tok * it.d_out + o] = y;
+                    if (it.acc_out) it.acc_out[(int64_t)tok * it.d_out + o] = acc[i];
+                }
+            }
+        }
+    }
+}
+
+// ---- generic path: any supported pattern, plain integer arithmetic ---------------------------------
+// One thread per output row, eight tokens per block row; decodes every slot of the packed row.
+__global__ void __launch_bounds__(128) linear_generic_kernel(const int8_t *__restrict__ xq, const float *__restrict__ sx,
+                                                            const uint8_t *__restrict__ packed, const float *gamma,
+                                                            const float *bias, float *Y, int32_t *acc_out,
+                                                            int64_t tokens, int d_in, int d_out, Pattern pat)
+{
+    const int o = blockIdx.x * 128 + threadIdx.x;
+    const int64_t t0 = (int64_t)blockIdx.y * 8;
+    if (o >= d_out) return;
+    const int nchunks = (d_in + CHUNK - 1) / CHUNK;
+    int acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int c = 0; c < nchunks; ++c) {
+        const uint8_t *idx_field = packed + ((int64_t)o * nchunks + c) * pat.chunk_bytes;
+        const uint8_t *code_field = idx_field + pat.idx_bytes;
+        for (int s = 0; s < pat.slots; ++s) {
+            const int v = s & 15;
+            const int cp = 32 * (s >> 4) + 8 * (v & 3) + 2 * (v >> 2);
+            const uint32_t code = (code_field[cp >> 3] >> (cp & 7)) & 3u;
+            if (code == 0) continue;
+            int j = s % pat.N;
+            if (pat.b) {
+                const int p = s * pat.b;
+                const uint32_t two = (uint32_t)idx_field[p >> 3] | ((uint32_t)idx_field[(p >> 3) + ((p >> 3) + 1 < pat.idx_bytes ? 1 : 0)] << 8);
+                j = (two >> (p & 7)) & ((1u << pat.b) - 1u);
+            }
+            const int col = c * CHUNK + (s / pat.N) * pat.M + j;
+            if (col >= d_in) continue;
+            const int w = code == 1u ? 1 : -1;
+#pragma unroll
+            for (int tt = 0; tt < 8; ++tt)
+                if (t0 + tt < tokens) acc[tt] += w * (int)xq[(t0 + tt) * d_in + col];
+        }
+    }
+    const float g = *gamma;
+#pragma unroll
+    for (int tt = 0; tt < 8; ++tt) {
+        if (t0 + tt >= tokens) break;
+        float y = (float)acc[tt] * __fdiv_rn(g, sx[t0 + tt]);
+        if (bias) y += bias[o];
+        Y[(t0 + tt) * d_out + o] = y;
+        if (acc_out) acc_out[(t0 + tt) * d_out + o] = acc[tt];
+    }
+}
+
+}  // namespace
+
+size_t linear_workspace_bytes(int64_t tokens, int64_t d_out, int64_t d_in)
+{
+    // int8 activations + per-token scales + dense int8 weights of the comparison path
+    return align_up((size_t)tokens * d_in, 256) + align_up((size_t)tokens * sizeof(float), 256) +
+           align_up((size_t)d_out * d_in, 256);
+}
+
+sbn_status launch_act_quant(const void *X, int64_t tokens, int64_t d_in, int8_t *xq, float *sx, hipStream_t stream)
+{
+    hipLaunchKernelGGL(act_quant_kernel, dim3((unsigned)ceil_div(tokens, 4)), dim3(256), 0, stream,
+                       static_cast<const uint4 *>(X), tokens, (int)(d_in / 8), xq, sx);
+    return check_launch("act_quant_kernel");
+}
+
+sbn_status launch_gemv(int count, const LinearItem *items, hipStream_t stream)
+{
+    for (int first = 0; first < count; first += GEMV_MAX_ITEMS) {
+        const int n = count - first < GEMV_MAX_ITEMS ? count - first : GEMV_MAX_ITEMS;
+        GemvTable tab;
+        tab.count = n;
+        int blocks = 0, max_super = 1;
+        for (int i = 0; i < n; ++i) {
+            const LinearItem &li = items[first + i];
+            GemvItem &g = tab.it[i];
+            g.xq = li.xq; g.sx = li.sx; g.packed = static_cast<const uint8_t *>(li.packed);
+            g.gamma = li.gamma; g.bias = li.bias; g.Y = li.Y; g.acc_out = li.acc_out;
+            g.d_in = (int)li.d_in; g.d_out = (int)li.d_out; g.tokens = (int)li.tokens; g.block0 = blocks;
+            blocks += (int)ceil_div(li.d_out, 16);
+            const int nsuper = (int)ceil_div(li.d_in / CHUNK, 4);
+            max_super = nsuper > max_super ? nsuper : max_super;
+        }
+        tab.total_blocks = blocks;
+        // one wavefront per super-step up to 16, so that every wavefront has loads in flight at once
+        const int nwaves = max_super < 16 ? max_super : 16;
+        hipLaunchKernelGGL(gemv_smfmac_kernel, dim3(blocks), dim3(64 * nwaves), 0, stream, tab);
+        sbn_status st = check_launch("gemv_smfmac_kernel");
+        if (st != SBN_OK) return st;
+    }
+    return SBN_OK;
+}
+
+sbn_status launch_linear_generic(const LinearItem &it, const Pattern &pat, hipStream_t stream)
+{
+    dim3 grid((unsigned)ceil_div(it.d_out, 128), (unsigned)ceil_div(it.tokens, 8));
+    hipLaunchKernelGGL(linear_generic_kernel, grid, dim3(128), 0, stream, it.xq, it.sx,
+                       static_cast<const uint8_t *>(it.packed), it.gamma, it.bias, it.Y, it.acc_out, it.tokens,
+                       (int)it.d_in, (int)it.d_out, pat);
+    return check_launch("linear_generic_kernel");
+}
+
+}  // namespace sbn

@@ -1,0 +1,395 @@
+// quantize_mask_pack: absmean scale, N:M magnitude mask, ternary codes, packed layout.
+//
+// Three enqueues per batch of up to PACK_MAX_ITEMS matrices:
+//   1. absmean_partial_kernel  one block per 16384 weights, |w| summed in fp64 (every term exact)
+//   2. absmean_finalize_kernel one block per matrix: fixed-order sum of the partials, gamma and
+//                              the rounding threshold theta
+//   3. pack_kernel             one block per 16 chunks (2048 weights): top-N per group, ternary
+//                              codes, fields assembled in LDS, one coalesced store
+// Section 2.1 (ternary quantizer), Section 2.2 (mask from latent weights, quantize then mask),
+// Section 2.3 (the mask is recomputed every step, so this is a hot kernel).
+#include "sbn_internal.hpp"
+
+namespace sbn {
+
+namespace {
+
+struct PackTable {
+    PackItem it[PACK_MAX_ITEMS];
+    int sum_block0[PACK_MAX_ITEMS + 1];   // first absmean block of each matrix
+    int pack_block0[PACK_MAX_ITEMS + 1];  // first pack block of each matrix
+    int count;
+};
+
+__device__ __forceinline__ int find_item(const int *prefix, int count, int block)
+{
+    int i = 0;
+    while (i + 1 < count && block >= prefix[i + 1]) ++i;
+    return i;
+}
+
+// raw bits of one latent weight; magnitude compare happens on the integer pattern, which orders
+// finite IEEE magnitudes exactly as the floats (and makes -0 tie with +0)
+template <typename WT> struct Raw;
+template <> struct Raw<float> {
+    static constexpr uint32_t MAG = 0x7fffffffu;
+    static constexpr int SIGN_SHIFT = 31;
+    __device__ static uint32_t load(const float *p) { return __float_as_uint(*p); }
+    __device__ static double abs_value(uint32_t raw) { return (double)__uint_as_float(raw & MAG); }
+    __device__ static uint32_t threshold(float theta) { return __float_as_uint(theta); }
+};
+template <> struct Raw<uint16_t> {  // bf16
+    static constexpr uint32_t MAG = 0x7fffu;
+    static constexpr int SIGN_SHIFT = 15;
+    __device__ static uint32_t load(const uint16_t *p) { return *p; }
+    __device__ static double abs_value(uint32_t raw) { return (double)__uint_as_float((raw & MAG) << 16); }
+    // smallest bf16 magnitude pattern whose value is >= theta
+    __device__ static uint32_t threshold(float theta) { return (__float_as_uint(theta) + 0xffffu) >> 16; }
+};
+
+template <typename WT>
+__device__ __forceinline__ void load8(const WT *p, bool vec, bool valid8, const bool valid[8], uint32_t raw[8])
+{
+    if (vec && valid8) {
+        if constexpr (sizeof(WT) == 2) {
+            uint4 v = *reinterpret_cast<const uint4 *>(p);
+            raw[0] = v.x & 0xffffu; raw[1] = v.x >> 16;
+            raw[2] = v.y & 0xffffu; raw[3] = v.y >> 16;
+            raw[4] = v.z & 0xffffu; raw[5] = v.z >> 16;
+            raw[6] = v.w & 0xffffu; raw[7] = v.w >> 16;
+        } else {
+            uint4 a = reinterpret_cast<const uint4 *>(p)[0];
+            uint4 b = reinterpret_cast<const uint4 *>(p)[1];
+            raw[0] = a.x; raw[1] = a.y; raw[2] = a.z; raw[3] = a.w;
+            raw[4] = b.x; raw[5] = b.y; raw[6] = b.z; raw[7] = b.w;
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) raw[j] = valid[j] ? Raw<WT>::load(p + j) : 0u;
+    }
+}
+
+__device__ __forceinline__ double block_sum(double v, double *lds)
+{
+    const int tid = threadIdx.x;
+    lds[tid] = v;
+    __syncthreads();
+#pragma unroll
+    for (int s = 128; s > 0; s >>= 1) {
+        if (tid < s) lds[tid] += lds[tid + s];
+        __syncthreads();
+    }
+    return lds[0];
+}
+
+// ---- pass 1: partial sums of |w| in fp64 ------------------------------------------------------
+template <typename WT>
+__global__ void __launch_bounds__(256) absmean_partial_kernel(PackTable tab, double *partials, int vec_ok)
+{
+    __shared__ double lds[256];
+    const int item = find_item(tab.sum_block0, tab.count, blockIdx.x);
+    const PackItem &it = tab.it[item];
+    const int64_t lb = blockIdx.x - tab.sum_block0[item];
+    const int64_t n = it.d_out * it.d_in;
+    const WT *W = static_cast<const WT *>(it.W);
+    const int64_t e0 = lb * PACK_SUM_ELEMS;
+    double acc = 0.0;
+    const bool flat = vec_ok && it.ld == it.d_in;
+#pragma unroll
+    for (int u = 0; u < PACK_SUM_ELEMS / (256 * 8); ++u) {
+        const int64_t e = e0 + ((int64_t)u * 256 + threadIdx.x) * 8;
+        if (e >= n) break;
+        uint32_t raw[8];
+        bool valid[8];
+        if (flat) {
+            // d_in % 8 == 0 here, so a vector never crosses the end of the matrix
+            load8<WT>(W + e, true, true, valid, raw);
+        } else {
+            const WT *p[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                valid[j] = e + j < n;
+                const int64_t row = (e + j) / it.d_in, col = (e + j) % it.d_in;
+                p[j] = W + row * it.ld + col;
+                raw[j] = valid[j] ? Raw<WT>::load(p[j]) : 0u;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc += Raw<WT>::abs_value(raw[j]);
+    }
+    const double total = block_sum(acc, lds);
+    if (threadIdx.x == 0) partials[blockIdx.x] = total;
+}
+
+// ---- pass 2: gamma and the rounding threshold --------------------------------------------------
+// theta is the smallest fp32 magnitude a with fl32(a / gamma) > 0.5.  Because fl32(a / gamma) is
+// monotone in a, clip(round_half_even(w / gamma), -1, 1) != 0  <=>  |w| >= theta, so the pack
+// kernel needs one integer compare per weight instead of a division.
+__global__ void __launch_bounds__(256) absmean_finalize_kernel(PackTable tab, const double *partials, float *theta)
+{
+    __shared__ double lds[256];
+    const int item = blockIdx.x;
+    const PackItem &it = tab.it[item];
+    const int b0 = tab.sum_block0[item], b1 = tab.sum_block0[item + 1];
+    double acc = 0.0;
+    for (int b = b0 + threadIdx.x; b < b1; b += 256) acc += partials[b];
+    const double total = block_sum(acc, lds);
+    if (threadIdx.x == 0) {
+        float g = (float)(total / (double)(it.d_out * it.d_in));
+        g = g < 1e-5f ? 1e-5f : g;
+        float a = 0.5f * g;
+        while (!(__fdiv_rn(a, g) > 0.5f)) a = __uint_as_float(__float_as_uint(a) + 1u);
+        *it.gamma = g;
+        theta[item] = a;
+    }
+}
+
+// ---- pass 3: mask, codes, packed fields --------------------------------------------------------
+// keep mask of 8 consecutive weights (8/M whole groups): element j is kept iff fewer than N
+// elements of its group beat it, where an equal magnitude at a lower position beats it.
+template <int N, int M>
+__device__ __forceinline__ uint32_t keep_mask8(const uint32_t mag[8])
+{
+    if constexpr (N == M) {
+        return 0xffu;
+    } else {
+        uint32_t keep = 0;
+#pragma unroll
+        for (int g = 0; g < 8 / M; ++g) {
+#pragma unroll
+            for (int j = 0; j < M; ++j) {
+                int beaten = 0;
+#pragma unroll
+                for (int jj = 0; jj < M; ++jj) {
+                    if (jj == j) continue;
+                    const uint32_t a = mag[g * M + jj], me = mag[g * M + j];
+                    beaten += (jj < j) ? (a >= me) : (a > me);
+                }
+                keep |= (uint32_t)(beaten < N) << (g * M + j);
+            }
+        }
+        return keep;
+    }
+}
+
+__device__ __forceinline__ void lds_or_merge(uint32_t *lds, int &cur_word, uint32_t &cur_bits, int word, uint32_t bits)
+{
+    if (word != cur_word) {
+        if (cur_bits) atomicOr(&lds[cur_word], cur_bits);
+        cur_word = word;
+        cur_bits = 0;
+    }
+    cur_bits |= bits;
+}
+
+template <typename WT, int N, int M>
+__global__ void __launch_bounds__(256) pack_kernel(PackTable tab, const float *theta, int vec_ok)
+{
+    constexpr int B = (N == M) ? 0 : (M == 2 ? 1 : M == 4 ? 2 : 3);
+    constexpr int SLOTS = 128 * N / M;
+    constexpr int IDX_BYTES = SLOTS * B / 8;
+    constexpr int CB = IDX_BYTES + SLOTS / 4;   // chunk bytes
+    constexpr int CNT = 8 * N / M;              // slots produced by one lane (8 weights)
+    constexpr int LDS_WORDS = (16 * CB + 3) / 4 + 1;
+    __shared__ uint32_t lds[LDS_WORDS];
+
+    const int item = find_item(tab.pack_block0, tab.count, blockIdx.x);
+    const PackItem &it = tab.it[item];
+    const int64_t lb = blockIdx.x - tab.pack_block0[item];
+    const int64_t nchunks = (it.d_in + CHUNK - 1) / CHUNK;
+    const int64_t total_chunks = it.d_out * nchunks;
+    const int tid = threadIdx.x;
+    const int ql = tid >> 4;    // chunk within the block
+    const int lane16 = tid & 15;  // 8-weight vector within the chunk
+    const int64_t q = lb * 16 + ql;
+
+    for (int w = tid; w < LDS_WORDS; w += 256) lds[w] = 0;
+    __syncthreads();
+
+    if (q < total_chunks) {
+        const WT *W = static_cast<const WT *>(it.W);
+        int64_t row, col;
+        if (it.ld == it.d_in && (it.d_in % CHUNK) == 0) {
+            row = 0;
+            col = q * CHUNK + lane16 * 8;   // flat offset: rows are contiguous and chunk-aligned
+        } else {
+            row = q / nchunks;
+            col = (q % nchunks) * CHUNK + lane16 * 8;
+        }
+        const int64_t row_end = (it.ld == it.d_in && (it.d_in % CHUNK) == 0) ? it.d_out * it.d_in : it.d_in;
+        bool valid[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) valid[j] = col + j < row_end;
+        uint32_t raw[8];
+        load8<WT>(W + row * it.ld + col, vec_ok != 0, col + 8 <= row_end, valid, raw);
+
+        const uint32_t th = Raw<WT>::threshold(theta[item]);
+        uint32_t mag[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) mag[j] = raw[j] & Raw<WT>::MAG;
+        const uint32_t keep = keep_mask8<N, M>(mag);
+
+        // this lane's slots are s0 .. s0 + CNT - 1 of the chunk
+        const int s0 = lane16 * CNT;
+        const int idx_bit0 = ql * CB * 8;
+        const int code_bit0 = (ql * CB + IDX_BYTES) * 8;
+        int iw = -1, cw = -1;
+        uint32_t ibits = 0, cbits = 0;
+        int s = s0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if ((keep >> j) & 1u) {
+                if constexpr (B > 0) {
+                    const uint32_t pos_in_group = j % M;
+                    const int p = idx_bit0 + s * B;
+                    lds_or_merge(lds, iw, ibits, p >> 5, pos_in_group << (p & 31));
+                    if ((p & 31) + B > 32)
+                        lds_or_merge(lds, iw, ibits, (p >> 5) + 1, pos_in_group >> (32 - (p & 31)));
+                }
+                const uint32_t nz = mag[j] >= th;
+                const uint32_t sign = (raw[j] >> Raw<WT>::SIGN_SHIFT) & 1u;
+                const uint32_t code = nz ? (sign ? 3u : 1u) : 0u;
+                const int v = s & 15;
+                const int p = code_bit0 + 32 * (s >> 4) + 8 * (v & 3) + 2 * (v >> 2);
+                lds_or_merge(lds, cw, cbits, p >> 5, code << (p & 31));
+                ++s;
+            }
+        }
+        if (ibits) atomicOr(&lds[iw], ibits);
+        if (cbits) atomicOr(&lds[cw], cbits);
+    }
+    __syncthreads();
+
+    // coalesced store of the block's chunks
+    const int64_t chunks_here = (total_chunks - lb * 16) < 16 ? (total_chunks - lb * 16) : 16;
+    const int bytes_here = (int)chunks_here * CB;
+    uint8_t *out = it.packed + lb * 16 * CB;
+    for (int w = tid; w * 4 < bytes_here; w += 256) {
+        if (w * 4 + 4 <= bytes_here) {
+            reinterpret_cast<uint32_t *>(out)[w] = lds[w];
+        } else {
+            for (int k = w * 4; k < bytes_here; ++k) out[k] = (uint8_t)(lds[w] >> (8 * (k & 3)));
+        }
+    }
+}
+
+// ---- test hook: packed -> dense W_eff and mask --------------------------------------------------
+__device__ __forceinline__ uint32_t get_bits(const uint8_t *field, int pos, int nbits)
+{
+    uint32_t v = 0;
+    for (int i = 0; i < nbits; ++i) v |= (uint32_t)((field[(pos + i) >> 3] >> ((pos + i) & 7)) & 1u) << i;
+    return v;
+}
+
+__global__ void __launch_bounds__(256) unpack_kernel(const uint8_t *packed, int64_t d_out, int64_t d_in, Pattern pat,
+                                                     int8_t *W_eff, uint8_t *mask)
+{
+    const int64_t nchunks = (d_in + CHUNK - 1) / CHUNK;
+    const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (q >= d_out * nchunks) return;
+    const int64_t row = q / nchunks, c = q % nchunks;
+    for (int j = 0; j < CHUNK; ++j) {
+        const int64_t col = c * CHUNK + j;
+        if (col < d_in) {
+            if (W_eff) W_eff[row * d_in + col] = 0;
+            if (mask) mask[row * d_in + col] = 0;
+        }
+    }
+    const uint8_t *idx_field = packed + q * pat.chunk_bytes;
+    const uint8_t *code_field = idx_field + pat.idx_bytes;
+    for (int s = 0; s < pat.slots; ++s) {
+        const int g = s / pat.N;
+        const int j = pat.b ? (int)get_bits(idx_field, s * pat.b, pat.b) : s % pat.N;
+        const int v = s & 15;
+        const uint32_t code = get_bits(code_field, 32 * (s >> 4) + 8 * (v & 3) + 2 * (v >> 2), 2);
+        const int64_t col = c * CHUNK + g * pat.M + j;
+        if (col >= d_in) continue;
+        if (mask) mask[row * d_in + col] = 1;
+        if (W_eff) W_eff[row * d_in + col] = code == 1u ? 1 : code == 3u ? -1 : 0;
+    }
+}
+
+template <typename WT>
+sbn_status launch_pack_kernel(const PackTable &tab, int nblocks, const float *theta, int vec_ok, const Pattern &pat,
+                              hipStream_t stream)
+{
+#define SBN_PACK_CASE(n, m)                                                                             \
+    if (pat.N == n && pat.M == m) {                                                                     \
+        hipLaunchKernelGGL((pack_kernel<WT, n, m>), dim3(nblocks), dim3(256), 0, stream, tab, theta, vec_ok); \
+        return check_launch("pack_kernel");                                                             \
+    }
+    SBN_PACK_CASE(1, 2) SBN_PACK_CASE(2, 2)
+    SBN_PACK_CASE(1, 4) SBN_PACK_CASE(2, 4) SBN_PACK_CASE(3, 4) SBN_PACK_CASE(4, 4)
+    SBN_PACK_CASE(1, 8) SBN_PACK_CASE(2, 8) SBN_PACK_CASE(3, 8) SBN_PACK_CASE(4, 8)
+    SBN_PACK_CASE(5, 8) SBN_PACK_CASE(6, 8) SBN_PACK_CASE(7, 8) SBN_PACK_CASE(8, 8)
+#undef SBN_PACK_CASE
+    return SBN_EUNSUPPORTED;
+}
+
+}  // namespace
+
+size_t pack_workspace_bytes(int64_t count, int64_t d_out, int64_t d_in)
+{
+    const int64_t blocks = ceil_div(d_out * d_in, PACK_SUM_ELEMS);
+    return align_up((size_t)count * (size_t)blocks * sizeof(double), 256) + align_up((size_t)count * sizeof(float), 256);
+}
+
+sbn_status launch_pack(int count, const PackItem *items, sbn_dtype wdt, const Pattern &pat, void *workspace,
+                       size_t ws_bytes, hipStream_t stream)
+{
+    // workspace: [partials: one double per absmean block of every matrix][theta: one float per matrix]
+    int64_t total_sum_blocks = 0;
+    for (int i = 0; i < count; ++i) total_sum_blocks += ceil_div(items[i].d_out * items[i].d_in, PACK_SUM_ELEMS);
+    const size_t need = align_up((size_t)total_sum_blocks * sizeof(double), 256) + align_up((size_t)count * sizeof(float), 256);
+    if (ws_bytes < need) return SBN_ESIZE;
+    double *partials = static_cast<double *>(workspace);
+    float *theta = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + align_up((size_t)total_sum_blocks * sizeof(double), 256));
+
+    const size_t esz = wdt == SBN_BF16 ? 2 : 4;
+    int64_t sum_base = 0;
+    for (int first = 0; first < count; first += PACK_MAX_ITEMS) {
+        const int n = count - first < PACK_MAX_ITEMS ? count - first : PACK_MAX_ITEMS;
+        PackTable tab;
+        tab.count = n;
+        int vec_ok = 1;
+        int sb = 0, pb = 0;
+        for (int i = 0; i < n; ++i) {
+            const PackItem &it = items[first + i];
+            tab.it[i] = it;
+            tab.sum_block0[i] = sb;
+            tab.pack_block0[i] = pb;
+            sb += (int)ceil_div(it.d_out * it.d_in, PACK_SUM_ELEMS);
+            pb += (int)ceil_div(it.d_out * ceil_div(it.d_in, CHUNK), 16);
+            if (!aligned(it.W, 16) || (it.ld * esz) % 16 != 0 || it.d_in % 8 != 0) vec_ok = 0;
+        }
+        tab.sum_block0[n] = sb;
+        tab.pack_block0[n] = pb;
+        double *part = partials + sum_base;
+        float *th = theta + first;
+        if (wdt == SBN_BF16)
+            hipLaunchKernelGGL(absmean_partial_kernel<uint16_t>, dim3(sb), dim3(256), 0, stream, tab, part, vec_ok);
+        else
+            hipLaunchKernelGGL(absmean_partial_kernel<float>, dim3(sb), dim3(256), 0, stream, tab, part, vec_ok);
+        sbn_status st = check_launch("absmean_partial_kernel");
+        if (st != SBN_OK) return st;
+        hipLaunchKernelGGL(absmean_finalize_kernel, dim3(n), dim3(256), 0, stream, tab, part, th);
+        st = check_launch("absmean_finalize_kernel");
+        if (st != SBN_OK) return st;
+        st = wdt == SBN_BF16 ? launch_pack_kernel<uint16_t>(tab, pb, th, vec_ok, pat, stream)
+                             : launch_pack_kernel<float>(tab, pb, th, vec_ok, pat, stream);
+        if (st != SBN_OK) return st;
+        sum_base += sb;
+    }
+    return SBN_OK;
+}
+
+sbn_status launch_unpack(const void *packed, int64_t d_out, int64_t d_in, const Pattern &pat, int8_t *W_eff,
+                         uint8_t *mask, hipStream_t stream)
+{
+    const int64_t total = d_out * ceil_div(d_in, CHUNK);
+    hipLaunchKernelGGL(unpack_kernel, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, stream,
+                       static_cast<const uint8_t *>(packed), d_out, d_in, pat, W_eff, mask);
+    return check_launch("unpack_kernel");
+}
+
+}  // namespace sbn

@@ -1,0 +1,90 @@
+"""GPU parity of sparse_ternary_linear against the CPU oracle: int8 activations, per-token scales
+and int32 accumulators bit-exact; Y within 1e-3 relative (Section 2.1 activation quantizer,
+Section 2.2 forward-pass equation)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import sbn_synth
+from gpu_util import DEV, assert_rel, hip_linear, hip_pack, oracle_pack, sbn
+
+pytestmark = pytest.mark.gpu
+Y_TOL = 1e-3
+
+
+def check_forward(W, X, N, M, path, bias=None, token_sample=None):
+    packed, gamma = hip_pack(W, N, M)
+    _, ref_gamma, Weff, _ = oracle_pack(W, N, M)
+    Y, acc, xq, sx = hip_linear(X, packed, gamma, W.shape[0], N, M, path, bias)
+    Xf = X.float().numpy()
+    r_xq, r_sx = oracle.act_quant(Xf)
+    assert np.array_equal(xq, r_xq), "int8 activations differ"
+    assert np.array_equal(sx, r_sx), "activation scales differ"
+    rows = np.arange(X.shape[0]) if token_sample is None else token_sample
+    r_acc = oracle.acc(Weff, r_xq[rows])
+    assert np.array_equal(acc[rows], r_acc), f"{(acc[rows] != r_acc).sum()} accumulators differ"
+    r_y = oracle.rescale(r_acc, ref_gamma, r_sx[rows], None if bias is None else bias.numpy())
+    assert_rel(Y[rows], r_y, Y_TOL, "Y")
+    return Y
+
+
+def test_config1_forward_all_paths():
+    # configs[0]: X 16x256 bf16, W 256x256 fp32, 2:4
+    s = sbn()
+    W = sbn_synth.latent_weight(256, 256, sbn_synth.seed_for(1, 0), dtype=torch.float32)
+    X = sbn_synth.activations(16, 256, sbn_synth.seed_for(1, 1))
+    for path in (s.SBN_PATH_GENERIC, s.SBN_PATH_GEMV, s.SBN_PATH_AUTO):
+        check_forward(W, X, 2, 4, path)
+
+
+@pytest.mark.parametrize("tokens", [1, 3, 8, 16])
+@pytest.mark.parametrize("shape", [(48, 128), (100, 640), (250, 1792), (16, 2560)])
+def test_gemv_shapes(tokens, shape):
+    s = sbn()
+    W = sbn_synth.latent_weight(shape[0], shape[1], 400 + shape[0])
+    X = sbn_synth.activations(tokens, shape[1], 500 + tokens)
+    bias = torch.randn(shape[0], generator=torch.Generator().manual_seed(7))
+    check_forward(W, X, 2, 4, s.SBN_PATH_GEMV, bias=bias)
+
+
+def test_gemv_adversarial_inputs():
+    s = sbn()
+    W = sbn_synth.adversarial_weight(64, 512, 410)
+    X = sbn_synth.adversarial_activations(8, 512, 411)
+    check_forward(W, X, 2, 4, s.SBN_PATH_GEMV)
+
+
+@pytest.mark.parametrize("tokens", [1, 8])
+@pytest.mark.parametrize("shape", [(6912, 2560), (2560, 6912)])
+def test_config2_decode_gemv_full_size(tokens, shape):
+    # configs[1]: FFN up (6912x2560) and down (2560x6912) projections, batch 1 and 8
+    s = sbn()
+    W = sbn_synth.latent_weight(shape[0], shape[1], sbn_synth.seed_for(2, shape[0]))
+    X = sbn_synth.activations(tokens, shape[1], sbn_synth.seed_for(2, 100 + tokens))
+    check_forward(W, X, 2, 4, s.SBN_PATH_GEMV)
+
+
+@pytest.mark.parametrize("N,M", [(2, 4), (1, 4), (2, 8), (6, 8), (4, 4), (1, 2), (3, 8)])
+def test_generic_path_all_patterns(N, M):
+    s = sbn()
+    W = sbn_synth.latent_weight(130, 392, 420 + N + M)
+    X = sbn_synth.activations(11, 392, 430)
+    check_forward(W, X, N, M, s.SBN_PATH_GENERIC)
+
+
+def test_grouped_gemv_matches_single():
+    s = sbn()
+    shapes = [(96, 640), (48, 128), (250, 1792)] * 20        # 60 problems: two launches
+    Ws = [sbn_synth.latent_weight(a, b, 600 + i) for i, (a, b) in enumerate(shapes)]
+    packs = [hip_pack(W, 2, 4) for W in Ws]
+    Xs = {k: sbn_synth.activations(8, k, 700 + k).to(DEV) for k in (640, 128, 1792)}
+    X_list = [Xs[b] for _, b in shapes]
+    Y_list = [torch.zeros(8, a, dtype=torch.float32, device=DEV) for a, _ in shapes]
+    need = sum(s.sbn_workspace_bytes(s.SBN_OP_LINEAR, 8, a, b, 2, 4) for a, b in shapes)
+    ws = s.new_workspace(need)
+    s.sbn_sparse_ternary_linear_grouped(X_list, [p for p, _ in packs], [g for _, g in packs], Y_list, 2, 4, ws)
+    torch.cuda.synchronize()
+    for i, (a, b) in enumerate(shapes):
+        Y1, *_ = hip_linear(X_list[i].cpu(), packs[i][0], packs[i][1], a, 2, 4, s.SBN_PATH_GEMV)
+        assert np.array_equal(Y_list[i].cpu().numpy(), Y1)

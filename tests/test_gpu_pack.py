@@ -1,0 +1,103 @@
+"""GPU parity of quantize_mask_pack (and the unpack hook) against the CPU oracle: packed bytes and
+gamma bit-exact.  Section 2.1 / 2.2 define the arithmetic; the byte layout is include/sbn.h's."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import sbn_synth
+from gpu_util import DEV, hip_pack, oracle_pack, sbn
+
+pytestmark = pytest.mark.gpu
+
+PATTERNS = [(2, 4), (1, 4), (2, 8), (6, 8), (4, 8), (1, 2), (3, 4), (8, 8), (4, 4), (1, 8), (7, 8), (2, 2), (3, 8), (5, 8)]
+
+
+def check(W, N, M):
+    packed, gamma = hip_pack(W, N, M)
+    ref_packed, ref_gamma, Weff, mask = oracle_pack(W, N, M)
+    assert gamma.cpu().numpy()[0] == ref_gamma, f"gamma {gamma.item()!r} vs {ref_gamma!r}"
+    got = packed.cpu().numpy()
+    assert got.size == ref_packed.size
+    assert np.array_equal(got, ref_packed), f"{(got != ref_packed).sum()} packed bytes differ"
+    return packed, Weff, mask
+
+
+@pytest.mark.parametrize("N,M", PATTERNS)
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_pack_small_shapes(N, M, dtype):
+    # 100 x 384: several blocks of 16 chunks and a ragged last block
+    check(sbn_synth.latent_weight(100, 384, 1 + N + 16 * M, dtype=dtype), N, M)
+
+
+@pytest.mark.parametrize("N,M", [(2, 4), (1, 4), (2, 8), (6, 8)])
+@pytest.mark.parametrize("shape", [(3, 8), (5, 136), (33, 200), (1, 128), (17, 1032)])
+def test_pack_ragged_tails(N, M, shape):
+    # d_in not a multiple of 128 (zero-padded last chunk) and not a multiple of 8 vectors
+    check(sbn_synth.latent_weight(shape[0], shape[1], 50 + N + M, dtype=torch.bfloat16), N, M)
+    check(sbn_synth.latent_weight(shape[0], shape[1], 60 + N + M, dtype=torch.float32), N, M)
+
+
+@pytest.mark.parametrize("N,M", [(2, 4), (1, 4), (2, 8), (6, 8), (4, 4)])
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_pack_adversarial_ties_and_zeros(N, M, dtype):
+    check(sbn_synth.adversarial_weight(64, 512, 70 + N, dtype=dtype), N, M)
+
+
+def test_pack_all_zero_matrix_clamps_gamma():
+    packed, gamma = hip_pack(torch.zeros(16, 256, dtype=torch.bfloat16), 2, 4)
+    assert gamma.item() == np.float32(1e-5)
+    ref, g, *_ = oracle_pack(torch.zeros(16, 256, dtype=torch.bfloat16), 2, 4)
+    assert np.array_equal(packed.cpu().numpy(), ref)
+
+
+def test_pack_strided_rows():
+    s = sbn()
+    base = sbn_synth.latent_weight(40, 512, 80)
+    view = base[:, 64:64 + 256]                      # ld = 512, d_in = 256
+    Wd = base.to(DEV)[:, 64:64 + 256]
+    packed = torch.zeros(s.sbn_packed_bytes(40, 256, 2, 4), dtype=torch.uint8, device=DEV)
+    gamma = torch.zeros(1, device=DEV)
+    ws = s.new_workspace(s.sbn_workspace_bytes(s.SBN_OP_QUANTIZE_MASK_PACK, 1, 40, 256, 2, 4))
+    s.sbn_quantize_mask_pack(Wd, 2, 4, packed, gamma, ws)
+    ref, g, *_ = oracle_pack(view.contiguous(), 2, 4)
+    assert gamma.item() == g and np.array_equal(packed.cpu().numpy(), ref)
+
+
+@pytest.mark.parametrize("N,M", [(2, 4), (1, 4), (2, 8), (6, 8), (8, 8)])
+def test_unpack_hook_matches_oracle(N, M):
+    s = sbn()
+    W = sbn_synth.latent_weight(70, 392, 90 + N)
+    packed, Weff, mask = check(W, N, M)
+    We = torch.full((70, 392), 9, dtype=torch.int8, device=DEV)
+    Mk = torch.full((70, 392), 9, dtype=torch.uint8, device=DEV)
+    s.sbn_unpack(packed, 70, 392, N, M, We, Mk)
+    assert np.array_equal(We.cpu().numpy(), Weff) and np.array_equal(Mk.cpu().numpy(), mask)
+
+
+def test_pack_config1_fp32():
+    # configs[0]: W 256x256 fp32 ~ N(0, 0.02), 2:4
+    check(sbn_synth.latent_weight(256, 256, sbn_synth.seed_for(1, 0), dtype=torch.float32), 2, 4)
+
+
+@pytest.mark.parametrize("N,M", [(2, 4), (1, 4), (2, 8)])
+@pytest.mark.parametrize("shape", [(2560, 2560), (6912, 2560), (2560, 6912)])
+def test_pack_full_size_matrices(N, M, shape):
+    # the three matrix shapes of the 30-layer sweep, at the sweep's three patterns
+    check(sbn_synth.latent_weight(shape[0], shape[1], sbn_synth.seed_for(4, shape[0] + N)), N, M)
+
+
+def test_pack_batched_equals_single():
+    s = sbn()
+    shapes = [(256, 256), (100, 384), (33, 200), (640, 1280)] * 14       # 56 matrices: two launches
+    Ws = [sbn_synth.latent_weight(a, b, 300 + i).to(DEV) for i, (a, b) in enumerate(shapes)]
+    packed = [torch.zeros(s.sbn_packed_bytes(a, b, 2, 4), dtype=torch.uint8, device=DEV) for a, b in shapes]
+    gammas = torch.zeros(len(shapes), dtype=torch.float32, device=DEV)
+    glist = [gammas[i:i + 1] for i in range(len(shapes))]
+    ws = s.new_workspace(s.sbn_workspace_bytes(s.SBN_OP_QUANTIZE_MASK_PACK, len(shapes), 640, 1280, 2, 4))
+    s.sbn_quantize_mask_pack_batched(Ws, 2, 4, packed, glist, ws)
+    torch.cuda.synchronize()
+    for i, W in enumerate(Ws):
+        ref, g, *_ = oracle_pack(W.cpu(), 2, 4)
+        assert gammas[i].item() == g
+        assert np.array_equal(packed[i].cpu().numpy(), ref)
