@@ -88,3 +88,45 @@ def test_grouped_gemv_matches_single():
     for i, (a, b) in enumerate(shapes):
         Y1, *_ = hip_linear(X_list[i].cpu(), packs[i][0], packs[i][1], a, 2, 4, s.SBN_PATH_GEMV)
         assert np.array_equal(Y_list[i].cpu().numpy(), Y1)
+
+
+@pytest.mark.parametrize("path_name", ["SBN_PATH_SMFMAC", "SBN_PATH_DENSE_MFMA"])
+@pytest.mark.parametrize("tokens,shape", [(16, (256, 256)), (200, (300, 384)), (129, (64, 128)), (513, (520, 640))])
+def test_gemm_paths_small(path_name, tokens, shape):
+    # several block tiles plus ragged edges in both tokens and rows
+    s = sbn()
+    W = sbn_synth.latent_weight(shape[0], shape[1], 800 + shape[0])
+    X = sbn_synth.activations(tokens, shape[1], 810 + tokens)
+    bias = torch.randn(shape[0], generator=torch.Generator().manual_seed(8))
+    check_forward(W, X, 2, 4, getattr(s, path_name), bias=bias)
+
+
+@pytest.mark.parametrize("path_name", ["SBN_PATH_SMFMAC", "SBN_PATH_DENSE_MFMA"])
+def test_gemm_adversarial_inputs(path_name):
+    s = sbn()
+    W = sbn_synth.adversarial_weight(256, 512, 820)
+    X = sbn_synth.adversarial_activations(64, 512, 821)
+    check_forward(W, X, 2, 4, getattr(s, path_name))
+
+
+@pytest.mark.parametrize("path_name", ["SBN_PATH_SMFMAC", "SBN_PATH_DENSE_MFMA"])
+@pytest.mark.parametrize("d_out", [2560, 6912])
+def test_config3_prefill_gemm_full_size(path_name, d_out):
+    # configs[2]: X 4096x2560 against 2560x2560 and 6912x2560; activations checked in full,
+    # accumulators and Y on 96 sampled token rows (each row is d_out exact dot products)
+    s = sbn()
+    W = sbn_synth.latent_weight(d_out, 2560, sbn_synth.seed_for(3, d_out))
+    X = sbn_synth.activations(4096, 2560, sbn_synth.seed_for(3, 1))
+    rows = np.sort(np.random.default_rng(3).choice(4096, size=96, replace=False))
+    rows[:3] = (0, 1, 4095)
+    check_forward(W, X, 2, 4, getattr(s, path_name), token_sample=np.unique(rows))
+
+
+def test_sparse_and_dense_paths_agree_bitwise_full_size():
+    s = sbn()
+    W = sbn_synth.latent_weight(2560, 2560, sbn_synth.seed_for(3, 7))
+    X = sbn_synth.activations(4096, 2560, sbn_synth.seed_for(3, 8))
+    packed, gamma = hip_pack(W, 2, 4)
+    Ya, acca, *_ = hip_linear(X, packed, gamma, 2560, 2, 4, s.SBN_PATH_SMFMAC)
+    Yb, accb, *_ = hip_linear(X, packed, gamma, 2560, 2, 4, s.SBN_PATH_DENSE_MFMA)
+    assert np.array_equal(acca, accb) and np.array_equal(Ya, Yb)
