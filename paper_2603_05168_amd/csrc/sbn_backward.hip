@@ -1,10 +1,334 @@
-// placeholder until the backward kernels land
+// Backward products of the sparse ternary linear layer under the dual straight-through estimator
+// (Section 2.3; Appendix B listing, backward()):
+//   dX[t,k] = gamma * sum_o dY[t,o] * W_eff[o,k]          contraction over d_out
+//   dW[o,k] = sum_t (dY[t,o] / s_x[t]) * xq[t,k]          contraction over tokens; dense, unmasked
+// Both run on the dense bf16 matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulation): the 2:4
+// structure lies along d_in, which is not the contracted dimension of either product, so the sparse
+// instruction does not apply.  One "NT" GEMM kernel serves both; small layout kernels put the
+// operands contraction-major first (ternary values and int8 activations are exact in bf16).
 #include "sbn_internal.hpp"
+#include "sbn_mfma.hpp"
+
 namespace sbn {
-size_t backward_workspace_bytes(int64_t, int64_t, int64_t) { return 256; }
-sbn_status launch_backward(const void *, int64_t, int64_t, int64_t, const Pattern &, const void *, const float *,
-                           const int8_t *, const float *, void *, void *, int, void *, size_t, hipStream_t)
+
+namespace {
+
+__device__ __forceinline__ uint32_t f32_to_bf16(float f)
 {
-    return SBN_EUNSUPPORTED;
+    const uint32_t u = __float_as_uint(f);
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;   // round to nearest even; inputs are finite
 }
+
+// ---- layout kernels -------------------------------------------------------------------------------
+constexpr int TP = 64 + 8;   // padded LDS row (bf16 elements) of the 64-wide transposition tiles
+
+// writes a [rows][64] bf16 LDS tile (row pitch TP) to dst[(r0 + row) * ld + c0 + 0..63], 16 bytes per thread
+__device__ __forceinline__ void write_tile_rows(const uint16_t *tile, int rows, uint16_t *dst, int64_t ld, int64_t r0,
+                                                int64_t c0, int64_t rmax, int64_t cmax)
+{
+    for (int v = threadIdx.x; v < rows * 8; v += 256) {
+        const int row = v >> 3, col = (v & 7) * 8;
+        if (r0 + row >= rmax) continue;
+        const uint16_t *s = tile + row * TP + col;
+        uint16_t *d = dst + (r0 + row) * ld + c0 + col;
+        if (c0 + col + 8 <= cmax) {
+            *reinterpret_cast<uint4 *>(d) = *reinterpret_cast<const uint4 *>(s);
+        } else {
+            for (int e = 0; e < 8; ++e)
+                if (c0 + col + e < cmax) d[e] = s[e];
+        }
+    }
 }
+
+// packed 2:4 weights -> W_eff^T as bf16 [d_in, ld] (ld >= d_out): block = 64 rows of W x one chunk
+__global__ void __launch_bounds__(256) unpack_transpose_kernel(const uint8_t *__restrict__ packed, int d_out, int d_in,
+                                                              uint16_t *__restrict__ wt, int64_t ld)
+{
+    __shared__ __attribute__((aligned(16))) uint16_t tile[128 * TP];
+    const int nchunks = d_in / CHUNK;
+    const int chunk = blockIdx.x, o0 = blockIdx.y * 64;
+    const int ro = threadIdx.x & 63, word = threadIdx.x >> 6;
+    const int o = o0 + ro;
+    for (int k = 0; k < 32; ++k) tile[(32 * word + k) * TP + ro] = 0;
+    if (o < d_out) {
+        const uint32_t *cw = reinterpret_cast<const uint32_t *>(packed + ((int64_t)o * nchunks + chunk) * 32);
+        const uint32_t idx = cw[word], codes = cw[4 + word];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int v = 2 * t + h;
+                const uint32_t code = (codes >> (8 * (v & 3) + 2 * (v >> 2))) & 3u;
+                const uint32_t pos = (idx >> (4 * t + 2 * h)) & 3u;
+                if (code) tile[(32 * word + 4 * t + pos) * TP + ro] = code == 1u ? 0x3f80u : 0xbf80u;
+            }
+        }
+    }
+    __syncthreads();
+    write_tile_rows(tile, 128, wt, ld, (int64_t)chunk * CHUNK, o0, d_in, ld);
+}
+
+// generic pattern: dense int8 W_eff [d_out, d_in] (from the unpack kernel) -> bf16 transposed
+__global__ void __launch_bounds__(256) transpose_i8_kernel(const int8_t *__restrict__ src, int64_t rows, int64_t cols,
+                                                          uint16_t *__restrict__ dst, int64_t ld)
+{
+    // src [rows, cols] int8 -> dst [cols, ld] bf16 (dst[c, r] = src[r, c]); tile 64 x 64
+    __shared__ __attribute__((aligned(16))) uint16_t tile[64 * TP];
+    const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
+    for (int e = threadIdx.x; e < 64 * 64; e += 256) {
+        const int r = e >> 6, c = e & 63;
+        int v = 0;
+        if (r0 + r < rows && c0 + c < cols) v = src[(r0 + r) * cols + c0 + c];
+        tile[c * TP + r] = (uint16_t)(__float_as_uint((float)v) >> 16);
+    }
+    __syncthreads();
+    write_tile_rows(tile, 64, dst, ld, c0, r0, cols, ld);
+}
+
+// dY [tokens, d_out] bf16 -> (dY[t,:] / s_x[t])^T as bf16 [d_out, ld]; tile 64 tokens x 64 outputs
+__global__ void __launch_bounds__(256) transpose_scale_dy_kernel(const uint16_t *__restrict__ dY, const float *__restrict__ sx,
+                                                                int64_t tokens, int64_t d_out, uint16_t *__restrict__ dst,
+                                                                int64_t ld)
+{
+    __shared__ __attribute__((aligned(16))) uint16_t tile[64 * TP];
+    const int64_t t0 = (int64_t)blockIdx.y * 64, o0 = (int64_t)blockIdx.x * 64;
+    for (int e = threadIdx.x; e < 64 * 64; e += 256) {
+        const int t = e >> 6, o = e & 63;
+        uint32_t out = 0;
+        if (t0 + t < tokens && o0 + o < d_out) {
+            const float dy = __uint_as_float((uint32_t)dY[(t0 + t) * d_out + o0 + o] << 16);
+            out = f32_to_bf16(__fdiv_rn(dy, sx[t0 + t]));
+        }
+        tile[o * TP + t] = (uint16_t)out;
+    }
+    __syncthreads();
+    write_tile_rows(tile, 64, dst, ld, o0, t0, d_out, ld);
+}
+
+// ---- bf16 "NT" GEMM ---------------------------------------------------------------------------------
+// C[m, n] (+)= alpha * sum_k Q[m, k] * P[n, k];  P is [N, ldp], Q is [M, ldq], both bf16 with k
+// contiguous; C is bf16 [M, ldc].  P supplies the rows of the MFMA result so that a lane ends up
+// with four consecutive n of one C row (one 8-byte store).
+// Block: 256 threads = 2 x 2 wavefronts, block tile 256 (n) x 128 (m), wave tile 128 (n) x 64 (m),
+// 64 k per iteration through a single LDS buffer with register prefetch of the next tile.
+constexpr int GB_N = 256, GB_M = 128, GB_K = 64;
+constexpr int GROW = GB_K * 2 + 16;   // LDS row pitch in bytes (128 data + 16 pad)
+
+struct GemmBf16Args {
+    const uint16_t *P;
+    const uint16_t *Q;
+    uint16_t *C;
+    const float *alpha;   // device scalar or null (= 1)
+    int64_t ldp, ldq, ldc;
+    int N, M, K;
+    int accumulate;
+    int tiles_n, tiles_m;
+};
+
+__global__ void __launch_bounds__(256, 2) gemm_bf16_nt_kernel(GemmBf16Args g)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t ldsP[GB_N * GROW];
+    __shared__ __attribute__((aligned(16))) uint8_t ldsQ[GB_M * GROW];
+    const int nb = g.tiles_n * g.tiles_m;
+    int id = blockIdx.x;
+    if ((nb & 7) == 0) id = (id & 7) * (nb >> 3) + (id >> 3);
+    const int tn = id % g.tiles_n, tm = id / g.tiles_n;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wn = wave & 1, wm = wave >> 1;
+    const int r = lane & 31, c = lane >> 5;
+    const int n0 = tn * GB_N, m0 = tm * GB_M;
+
+    // copy roles: 8 threads per row (16 bytes each), 32 rows per pass
+    const int cp_row = tid >> 3, cp_col = (tid & 7) * 8;   // column in elements
+    const uint16_t *psrc[8];
+    const uint16_t *qsrc[4];
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+        int n = n0 + cp_row + 32 * p;
+        n = n < g.N ? n : g.N - 1;
+        psrc[p] = g.P + (int64_t)n * g.ldp + cp_col;
+    }
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        int m = m0 + cp_row + 32 * p;
+        m = m < g.M ? m : g.M - 1;
+        qsrc[p] = g.Q + (int64_t)m * g.ldq + cp_col;
+    }
+
+    v16f acc[4][2];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
+
+    const int nk = (g.K + GB_K - 1) / GB_K;
+    uint4 preg[8], qreg[4];
+    auto load_tile = [&](int kt) {
+        const int k = kt * GB_K + cp_col;
+        const bool ok = k + 8 <= g.K;   // K % 8 == 0: a vector is entirely inside or outside
+#pragma unroll
+        for (int p = 0; p < 8; ++p) preg[p] = ok ? *reinterpret_cast<const uint4 *>(psrc[p] + kt * GB_K) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) qreg[p] = ok ? *reinterpret_cast<const uint4 *>(qsrc[p] + kt * GB_K) : make_uint4(0, 0, 0, 0);
+    };
+    auto store_tile_lds = [&]() {
+#pragma unroll
+        for (int p = 0; p < 8; ++p) *reinterpret_cast<uint4 *>(&ldsP[(cp_row + 32 * p) * GROW + cp_col * 2]) = preg[p];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) *reinterpret_cast<uint4 *>(&ldsQ[(cp_row + 32 * p) * GROW + cp_col * 2]) = qreg[p];
+    };
+
+    load_tile(0);
+    store_tile_lds();
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        if (kt + 1 < nk) load_tile(kt + 1);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            // lane (r, c) supplies k = 16u + 8c + 0..7 of the tile for both operands
+            v8bf pf[4], qf[2];
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+                pf[a] = *reinterpret_cast<const v8bf *>(&ldsP[(wn * 128 + 32 * a + r) * GROW + 32 * u + 16 * c]);
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+                qf[b] = *reinterpret_cast<const v8bf *>(&ldsQ[(wm * 64 + 32 * b + r) * GROW + 32 * u + 16 * c]);
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[a], qf[b], acc[a][b], 0, 0, 0);
+        }
+        __syncthreads();
+        if (kt + 1 < nk) {
+            store_tile_lds();
+            __syncthreads();
+        }
+    }
+
+    // result tile (a, b): lane holds m = column r, n = rows 8q + 4c + i
+    const float alpha = g.alpha ? *g.alpha : 1.0f;
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+        const int m = m0 + wm * 64 + 32 * b + r;
+        if (m >= g.M) continue;
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int n = n0 + wn * 128 + 32 * a + 8 * q + 4 * c;
+                uint16_t *dst = g.C + (int64_t)m * g.ldc + n;
+                float v[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] = acc[a][b][4 * q + i] * alpha;
+                if (n + 4 <= g.N && (g.ldc & 3) == 0) {
+                    if (g.accumulate) {
+                        const uint2 old = *reinterpret_cast<const uint2 *>(dst);
+                        v[0] += __uint_as_float(old.x << 16);
+                        v[1] += __uint_as_float(old.x & 0xffff0000u);
+                        v[2] += __uint_as_float(old.y << 16);
+                        v[3] += __uint_as_float(old.y & 0xffff0000u);
+                    }
+                    uint2 out;
+                    out.x = f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16);
+                    out.y = f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16);
+                    *reinterpret_cast<uint2 *>(dst) = out;
+                } else {
+                    for (int i = 0; i < 4; ++i) {
+                        if (n + i < g.N) {
+                            float x = v[i];
+                            if (g.accumulate) x += __uint_as_float((uint32_t)dst[i] << 16);
+                            dst[i] = (uint16_t)f32_to_bf16(x);
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+sbn_status launch_gemm_bf16(const uint16_t *P, int64_t ldp, int N, const uint16_t *Q, int64_t ldq, int M, int K,
+                            uint16_t *C, int64_t ldc, const float *alpha, int accumulate, hipStream_t stream)
+{
+    GemmBf16Args g;
+    g.P = P; g.Q = Q; g.C = C; g.alpha = alpha; g.ldp = ldp; g.ldq = ldq; g.ldc = ldc;
+    g.N = N; g.M = M; g.K = K; g.accumulate = accumulate;
+    g.tiles_n = (int)ceil_div(N, GB_N);
+    g.tiles_m = (int)ceil_div(M, GB_M);
+    hipLaunchKernelGGL(gemm_bf16_nt_kernel, dim3(g.tiles_n * g.tiles_m), dim3(256), 0, stream, g);
+    return check_launch("gemm_bf16_nt_kernel");
+}
+
+inline int64_t pad8(int64_t x) { return (x + 7) / 8 * 8; }
+
+}  // namespace
+
+size_t backward_workspace_bytes(int64_t tokens, int64_t d_out, int64_t d_in)
+{
+    // W_eff^T bf16 [d_in, pad8(d_out)] + int8 W_eff (generic patterns) + (dY/s_x)^T bf16 [d_out, pad8(tokens)]
+    // + xq^T bf16 [d_in, pad8(tokens)]
+    return align_up((size_t)d_in * pad8(d_out) * 2, 256) + align_up((size_t)d_out * d_in, 256) +
+           align_up((size_t)d_out * pad8(tokens) * 2, 256) + align_up((size_t)d_in * pad8(tokens) * 2, 256);
+}
+
+sbn_status launch_backward(const void *dY, int64_t tokens, int64_t d_in, int64_t d_out, const Pattern &pat,
+                           const void *packed, const float *gamma, const int8_t *xq, const float *sx, void *dX,
+                           void *dW, int accumulate, void *workspace, size_t ws_bytes, hipStream_t stream)
+{
+    (void)ws_bytes;
+    uint8_t *ws = static_cast<uint8_t *>(workspace);
+    uint16_t *wt = reinterpret_cast<uint16_t *>(ws);
+    ws += align_up((size_t)d_in * pad8(d_out) * 2, 256);
+    int8_t *w8 = reinterpret_cast<int8_t *>(ws);
+    ws += align_up((size_t)d_out * d_in, 256);
+    uint16_t *dyt = reinterpret_cast<uint16_t *>(ws);
+    ws += align_up((size_t)d_out * pad8(tokens) * 2, 256);
+    uint16_t *xt = reinterpret_cast<uint16_t *>(ws);
+    const uint16_t *dy = static_cast<const uint16_t *>(dY);
+    sbn_status st;
+
+    if (dX) {
+        const int64_t ldw = pad8(d_out);
+        if (pat.N == 2 && pat.M == 4 && d_in % CHUNK == 0) {
+            dim3 grid((unsigned)(d_in / CHUNK), (unsigned)ceil_div(d_out, 64));
+            hipLaunchKernelGGL(unpack_transpose_kernel, grid, dim3(256), 0, stream, static_cast<const uint8_t *>(packed),
+                               (int)d_out, (int)d_in, wt, ldw);
+            st = check_launch("unpack_transpose_kernel");
+        } else {
+            st = launch_unpack(packed, d_out, d_in, pat, w8, nullptr, stream);
+            if (st != SBN_OK) return st;
+            dim3 grid((unsigned)ceil_div(d_in, 64), (unsigned)ceil_div(d_out, 64));
+            hipLaunchKernelGGL(transpose_i8_kernel, grid, dim3(256), 0, stream, w8, d_out, d_in, wt, ldw);
+            st = check_launch("transpose_i8_kernel");
+        }
+        if (st != SBN_OK) return st;
+        // dX[t, k] = gamma * sum_o dY[t, o] * W_eff^T[k, o]
+        st = launch_gemm_bf16(wt, ldw, (int)d_in, dy, d_out, (int)tokens, (int)d_out, static_cast<uint16_t *>(dX), d_in,
+                              gamma, 0, stream);
+        if (st != SBN_OK) return st;
+    }
+    if (dW) {
+        const int64_t ldt = pad8(tokens);
+        {
+            dim3 grid((unsigned)ceil_div(d_out, 64), (unsigned)ceil_div(tokens, 64));
+            hipLaunchKernelGGL(transpose_scale_dy_kernel, grid, dim3(256), 0, stream, dy, sx, tokens, d_out, dyt, ldt);
+            st = check_launch("transpose_scale_dy_kernel");
+            if (st != SBN_OK) return st;
+        }
+        {
+            dim3 grid((unsigned)ceil_div(d_in, 64), (unsigned)ceil_div(tokens, 64));
+            hipLaunchKernelGGL(transpose_i8_kernel, grid, dim3(256), 0, stream, xq, tokens, d_in, xt, ldt);
+            st = check_launch("transpose_i8_kernel");
+            if (st != SBN_OK) return st;
+        }
+        // dW[o, k] = sum_t (dY/s_x)^T[o, t] * xq^T[k, t]; both operands are zero for t in [tokens, ldt)
+        st = launch_gemm_bf16(xt, ldt, (int)d_in, dyt, ldt, (int)d_out, (int)ldt, static_cast<uint16_t *>(dW), d_in,
+                              nullptr, accumulate, stream);
+        if (st != SBN_OK) return st;
+    }
+    return SBN_OK;
+}
+
+}  // namespace sbn
