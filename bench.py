@@ -1,0 +1,338 @@
+#!/usr/bin/env python3
+"""Benchmark of the MI355X-native N:M-sparse ternary linear layer (one GPU).
+
+A timed "step" is the prefill workload of benchmark configs[2]: X 4096x2560 bf16 through
+sbn_sparse_ternary_linear (activation quantizer + sparse-MFMA GEMM + rescale) against the packed
+2:4 ternary matrices 2560x2560 and 6912x2560.  `value` is its dense-equivalent throughput
+2*T*K*d_out / time in TOPS.  The other rows of the hot path are measured in the same run and
+reported under "rows": decode GEMV streaming rate (configs[1]), the quantize_mask_pack sweep
+(configs[3]), one block's training step (configs[4]) and the dense-ternary comparison path.
+Prints exactly one JSON line on stdout; progress goes to stderr.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
+INT8_DENSE_PEAK_TOPS = 5000.0   # dense int8 MFMA; the sparse instruction runs the same executed-op rate
+BF16_DENSE_PEAK_TFLOPS = 2500.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--sections", default="gemm,gemv,pack,train,dense,cpu",
+                    help="comma list of: gemm (always timed), gemv, pack, train, dense, cpu, copyref")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build measures one GPU only (the layer shards by rows of W, see DESIGN.md); "
+            "run with --gpus 1")
+        sys.exit(2)
+    sections = set(args.sections.split(","))
+
+    import torch
+    import paper_2603_05168_amd as sbn
+    import sbn_synth
+
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    N, M = 2, 4
+    H, F = sbn_synth.HIDDEN, sbn_synth.FFN
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    def timed(fn, reps, warm=2):
+        """Average milliseconds per call of fn over reps back-to-back calls (HIP events on the launch stream)."""
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = ev(), ev()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    def pack_one(W, n=N, m=M):
+        d_out, d_in = W.shape
+        packed = torch.empty(sbn.sbn_packed_bytes(d_out, d_in, n, m), dtype=torch.uint8, device=dev)
+        gamma = torch.empty(1, dtype=torch.float32, device=dev)
+        ws = sbn.new_workspace(sbn.sbn_workspace_bytes(sbn.SBN_OP_QUANTIZE_MASK_PACK, 1, d_out, d_in, n, m), dev)
+        sbn.sbn_quantize_mask_pack(W, n, m, packed, gamma, ws)
+        return packed, gamma
+
+    out = {}
+    rows = {}
+
+    # ------------------------------------------------------------------ configs[2]: prefill GEMM (the timed step)
+    T = 4096
+    NSETS = 4
+    shapes = [(H, H), (F, H)]
+    Wp = [pack_one(sbn_synth.latent_weight(a, b, sbn_synth.seed_for(3, a), device=dev)) for a, b in shapes]
+    Xs = [sbn_synth.activations(T, H, sbn_synth.seed_for(3, 10 + i), device=dev) for i in range(NSETS)]
+    Ys = [[torch.empty(T, a, dtype=torch.float32, device=dev) for a, _ in shapes] for _ in range(NSETS)]
+    xq = [torch.empty(T, H, dtype=torch.int8, device=dev) for _ in range(NSETS)]
+    sx = [torch.empty(T, dtype=torch.float32, device=dev) for _ in range(NSETS)]
+    ws_lin = sbn.new_workspace(sbn.sbn_workspace_bytes(sbn.SBN_OP_LINEAR, T, F, H, N, M), dev)
+    torch.cuda.synchronize()
+    counter = [0]
+
+    def step(path=sbn.SBN_PATH_SMFMAC):
+        i = counter[0] % NSETS
+        counter[0] += 1
+        for j, (a, b) in enumerate(shapes):
+            sbn.sbn_sparse_ternary_linear(Xs[i], Wp[j][0], Wp[j][1], Ys[i][j], N, M, ws_lin, path=path)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0, e1 = ev(), ev()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_step = e0.elapsed_time(e1) / args.steps
+    ops_step = sum(2.0 * T * b * a for a, b in shapes)
+    value = ops_step / (ms_step * 1e-3) / 1e12
+    log(f"[gemm] step {ms_step:.4f} ms (wall {wall_ms:.4f}) -> {value:.1f} TOPS dense-equivalent")
+
+    # dominant kernel alone: the sparse GEMM on pre-quantized activations, per shape
+    for i in range(NSETS):
+        sbn.sbn_act_quant(Xs[i], xq[i], sx[i])
+    gemm_rows = {}
+    for j, (a, b) in enumerate(shapes):
+        def gemm_only(j=j):
+            i = counter[0] % NSETS
+            counter[0] += 1
+            sbn.sbn_sparse_ternary_linear(None, Wp[j][0], Wp[j][1], Ys[i][j], N, M, ws_lin, xq_out=xq[i], sx_out=sx[i],
+                                          path=sbn.SBN_PATH_SMFMAC)
+        ms = timed(gemm_only, 40, 5)
+        executed = 1.0 * T * b * a               # executed int8 ops: half of the dense-equivalent 2*T*K*d_out
+        bytes_alg = T * b + a * b // 4 + 4 * T * a + 4 * T
+        gemm_rows[f"{a}x{b}"] = {"ms": ms, "tops_dense_equiv": 2 * executed / (ms * 1e-3) / 1e12,
+                                 "executed_tops": executed / (ms * 1e-3) / 1e12,
+                                 "frac_int8_mfma": executed / (ms * 1e-3) / 1e12 / INT8_DENSE_PEAK_TOPS,
+                                 "algorithmic_gbps": bytes_alg / (ms * 1e-3) / 1e9,
+                                 "frac_hbm": bytes_alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+        log(f"[gemm] sparse kernel {a}x{b}: {ms * 1e3:.1f} us, {gemm_rows[f'{a}x{b}']['tops_dense_equiv']:.0f} TOPS, "
+            f"{gemm_rows[f'{a}x{b}']['algorithmic_gbps']:.0f} GB/s")
+    ms_aq = timed(lambda: sbn.sbn_act_quant(Xs[counter[0] % NSETS], xq[0], sx[0]), 40, 5)
+    rows["act_quant_4096x2560"] = {"ms": ms_aq, "gbps": (3 * T * H + 4 * T) / (ms_aq * 1e-3) / 1e9}
+    rows["gemm_sparse"] = gemm_rows
+    big = gemm_rows[f"{F}x{H}"]
+    roofline = {"kernel": "gemm_smfmac_kernel", "workload": f"T={T} K={H} d_out={F}", "bound": "mfma",
+                "achieved": big["executed_tops"], "peak": INT8_DENSE_PEAK_TOPS, "unit": "TOP/s",
+                "frac": big["frac_int8_mfma"], "traffic": None,
+                "note": "executed int8 ops T*K*d_out (the 2:4 instruction skips half of 2*T*K*d_out); "
+                        "dense-equivalent TOPS / 10 POPS gives the same fraction"}
+
+    # ------------------------------------------------------------------ dense-ternary comparison path
+    if "dense" in sections:
+        dense_rows = {}
+        for j, (a, b) in enumerate(shapes):
+            def dense_call(j=j):
+                i = counter[0] % NSETS
+                counter[0] += 1
+                sbn.sbn_sparse_ternary_linear(None, Wp[j][0], Wp[j][1], Ys[i][j], N, M, ws_lin, xq_out=xq[i],
+                                              sx_out=sx[i], path=sbn.SBN_PATH_DENSE_MFMA)
+            ms = timed(dense_call, 20, 3)
+            dense_rows[f"{a}x{b}"] = {"ms_with_expand": ms, "tops": 2.0 * T * a * b / (ms * 1e-3) / 1e12,
+                                      "sparse_speedup": ms / gemm_rows[f"{a}x{b}"]["ms"]}
+            log(f"[dense] {a}x{b}: {ms * 1e3:.1f} us -> sparse path is {ms / gemm_rows[f'{a}x{b}']['ms']:.2f}x faster")
+        rows["gemm_dense_ternary"] = dense_rows
+    del Ys, Xs
+    torch.cuda.empty_cache()
+
+    # ------------------------------------------------------------------ configs[1]: decode GEMV, streamed over R copies
+    roofline_gemv = None
+    if "gemv" in sections:
+        R = 64
+        gemv_rows = {}
+        for name, (a, b) in (("up_6912x2560", (F, H)), ("down_2560x6912", (H, F))):
+            packs = [pack_one(sbn_synth.latent_weight(a, b, sbn_synth.seed_for(2, 100 * r + a % 7), device=dev)) for r in range(R)]
+            pbytes = sbn.sbn_packed_bytes(a, b, N, M)
+            for tok in (1, 8):
+                X = sbn_synth.activations(tok, b, sbn_synth.seed_for(2, tok), device=dev)
+                Yl = [torch.empty(tok, a, dtype=torch.float32, device=dev) for _ in range(R)]
+                ws = sbn.new_workspace(R * sbn.sbn_workspace_bytes(sbn.SBN_OP_LINEAR, tok, a, b, N, M), dev)
+                grp = sbn.LinearGroup([X] * R, [p for p, _ in packs], [g for _, g in packs], Yl, N, M, ws, sbn.SBN_PATH_GEMV)
+                ms = timed(grp.run, 20, 3)
+                ws1 = sbn.new_workspace(sbn.sbn_workspace_bytes(sbn.SBN_OP_LINEAR, tok, a, b, N, M), dev)
+                k = [0]
+
+                def single():
+                    r = k[0] % R
+                    k[0] += 1
+                    sbn.sbn_sparse_ternary_linear(X, packs[r][0], packs[r][1], Yl[r], N, M, ws1, path=sbn.SBN_PATH_GEMV)
+                ms1 = timed(single, 64, 8)
+                gbps = R * pbytes / (ms * 1e-3) / 1e9
+                gemv_rows[f"{name}_T{tok}"] = {"stream_ms_per_matrix": ms / R, "stream_gbps": gbps,
+                                               "frac_hbm": gbps / HBM_PEAK_GBPS, "single_call_us": ms1 * 1e3,
+                                               "packed_bytes": pbytes, "copies": R}
+                log(f"[gemv] {name} T={tok}: stream {gbps:.0f} GB/s ({gbps / HBM_PEAK_GBPS:.1%} of HBM peak), "
+                    f"single call {ms1 * 1e3:.1f} us")
+                del Yl, ws, grp
+            del packs
+            torch.cuda.empty_cache()
+        rows["gemv"] = gemv_rows
+        best = gemv_rows["up_6912x2560_T8"]
+        roofline_gemv = {"kernel": "gemv_smfmac_kernel", "workload": "64 x (6912x2560 packed 2:4), T=8, grouped",
+                         "bound": "hbm", "achieved": best["stream_gbps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                         "frac": best["frac_hbm"], "traffic": None}
+
+    # ------------------------------------------------------------------ configs[3]: quantize_mask_pack sweep, 210 matrices
+    if "pack" in sections:
+        Wl = []
+        for layer in range(sbn_synth.LAYERS):
+            for mi, (_, a, b) in enumerate(sbn_synth.BLOCK_MATRICES):
+                Wl.append(sbn_synth.latent_weight(a, b, sbn_synth.seed_for(4, 10 * layer + mi), device=dev))
+        nweights = sum(w.numel() for w in Wl)
+        gam = torch.empty(len(Wl), dtype=torch.float32, device=dev)
+        glist = [gam[i:i + 1] for i in range(len(Wl))]
+        wsp = sbn.new_workspace(sbn.sbn_workspace_bytes(sbn.SBN_OP_QUANTIZE_MASK_PACK, len(Wl), F, H, N, M), dev)
+        pack_rows = {}
+        for n, m in ((2, 4), (1, 4), (2, 8)):
+            pl = [torch.empty(sbn.sbn_packed_bytes(w.shape[0], w.shape[1], n, m), dtype=torch.uint8, device=dev) for w in Wl]
+            batch = sbn.PackBatch(Wl, n, m, pl, glist, wsp)
+            ms = timed(batch.run, 5, 1)
+            bytes_alg = 2 * nweights + sum(p.numel() for p in pl) + 4 * len(Wl)
+            pack_rows[f"{n}:{m}"] = {"sweep_ms": ms, "algorithmic_gb": bytes_alg / 1e9,
+                                     "gbps": bytes_alg / (ms * 1e-3) / 1e9,
+                                     "frac_hbm": bytes_alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+            log(f"[pack] {n}:{m} sweep of {len(Wl)} matrices: {ms:.3f} ms, {pack_rows[f'{n}:{m}']['gbps']:.0f} GB/s "
+                f"on single-read bytes")
+            del pl, batch
+        rows["quantize_mask_pack"] = pack_rows
+        del Wl
+        torch.cuda.empty_cache()
+
+    # ------------------------------------------------------------------ configs[4]: one block's training step
+    if "train" in sections:
+        Tt = 8 * 2048
+        mats = sbn_synth.BLOCK_MATRICES
+        Wt = [sbn_synth.latent_weight(a, b, sbn_synth.seed_for(5, i), device=dev) for i, (_, a, b) in enumerate(mats)]
+        Xh = sbn_synth.activations(Tt, H, sbn_synth.seed_for(5, 20), device=dev)
+        Xo = sbn_synth.activations(Tt, H, sbn_synth.seed_for(5, 21), device=dev)
+        Xf = sbn_synth.activations(Tt, F, sbn_synth.seed_for(5, 22), device=dev)
+        xin = [Xh, Xh, Xh, Xo, Xh, Xh, Xf]
+        dYh = sbn_synth.grad_output(Tt, H, sbn_synth.seed_for(5, 30), device=dev)
+        dYf = sbn_synth.grad_output(Tt, F, sbn_synth.seed_for(5, 31), device=dev)
+        pk = [torch.empty(sbn.sbn_packed_bytes(a, b, N, M), dtype=torch.uint8, device=dev) for _, a, b in mats]
+        gm = torch.empty(len(mats), dtype=torch.float32, device=dev)
+        gl = [gm[i:i + 1] for i in range(len(mats))]
+        wsp = sbn.new_workspace(sbn.sbn_workspace_bytes(sbn.SBN_OP_QUANTIZE_MASK_PACK, len(mats), F, H, N, M), dev)
+        batch = sbn.PackBatch(Wt, N, M, pk, gl, wsp)
+        Yh = torch.empty(Tt, H, dtype=torch.float32, device=dev)
+        Yf = torch.empty(Tt, F, dtype=torch.float32, device=dev)
+        xqh = torch.empty(Tt, H, dtype=torch.int8, device=dev)
+        xqf = torch.empty(Tt, F, dtype=torch.int8, device=dev)
+        sxb = torch.empty(Tt, dtype=torch.float32, device=dev)
+        dXh = torch.empty(Tt, H, dtype=torch.bfloat16, device=dev)
+        dXf = torch.empty(Tt, F, dtype=torch.bfloat16, device=dev)
+        dWl = [torch.empty(a, b, dtype=torch.bfloat16, device=dev) for _, a, b in mats]
+        wsl = sbn.new_workspace(sbn.sbn_workspace_bytes(sbn.SBN_OP_LINEAR, Tt, F, F, N, M), dev)
+        wsb = sbn.new_workspace(sbn.sbn_workspace_bytes(sbn.SBN_OP_BACKWARD, Tt, F, F, N, M), dev)
+
+        def remask():
+            batch.run()
+
+        def forward_backward(do_fwd=True, do_bwd=True):
+            for i, (_, a, b) in enumerate(mats):
+                Y = Yf if a == F else Yh
+                xq_ = xqf if b == F else xqh
+                if do_fwd:
+                    sbn.sbn_sparse_ternary_linear(xin[i], pk[i], gl[i], Y, N, M, wsl, xq_out=xq_, sx_out=sxb,
+                                                  path=sbn.SBN_PATH_SMFMAC)
+                if do_bwd:
+                    sbn.sbn_sparse_ternary_linear_backward(dYf if a == F else dYh, pk[i], gl[i], xq_, sxb, N, M, wsb, b,
+                                                           dX=dXf if b == F else dXh, dW=dWl[i])
+
+        def train_step():
+            remask()
+            forward_backward()
+
+        ms_all = timed(train_step, 3, 1)
+        ms_pack = timed(remask, 5, 1)
+        ms_fwd = timed(lambda: forward_backward(True, False), 3, 1)
+        ms_bwd = timed(lambda: forward_backward(False, True), 3, 1)
+        wsum = sum(a * b for _, a, b in mats)
+        rows["train_step_block"] = {
+            "tokens": Tt, "ms": ms_all, "remask_pack_ms": ms_pack, "forward_ms": ms_fwd, "backward_ms": ms_bwd,
+            "forward_tops_dense_equiv": 2.0 * Tt * wsum / (ms_fwd * 1e-3) / 1e12,
+            "backward_tflops": 4.0 * Tt * wsum / (ms_bwd * 1e-3) / 1e12,
+            "backward_frac_bf16_mfma": 4.0 * Tt * wsum / (ms_bwd * 1e-3) / 1e12 / BF16_DENSE_PEAK_TFLOPS,
+            "step_tops_total": 6.0 * Tt * wsum / (ms_all * 1e-3) / 1e12}
+        log(f"[train] block step {ms_all:.2f} ms (pack {ms_pack:.3f}, fwd {ms_fwd:.2f}, bwd {ms_bwd:.2f}); "
+            f"bwd {rows['train_step_block']['backward_tflops']:.0f} TFLOP/s")
+        del Wt, Xh, Xo, Xf, dYh, dYf, Yh, Yf, dXh, dXf, dWl, wsl, wsb
+        torch.cuda.empty_cache()
+
+    # ------------------------------------------------------------------ plain copy of known size (scale of the HBM counters)
+    if "copyref" in sections:
+        a = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+        b = torch.empty_like(a)
+        ms = timed(lambda: b.copy_(a), 5, 1)
+        rows["copyref_1GiB"] = {"ms": ms, "gbps": 2 * (1 << 30) / (ms * 1e-3) / 1e9}
+        del a, b
+
+    # ------------------------------------------------------------------ CPU oracle on a bounded sample of the same workload
+    cpu_baseline = None
+    if "cpu" in sections:
+        import numpy as np
+        import oracle
+        Wc = sbn_synth.latent_weight(F, H, sbn_synth.seed_for(3, F)).float().numpy()
+        t1 = time.perf_counter()
+        Weff, mask, g = oracle.quantize_mask(Wc, N, M)
+        pack_s = time.perf_counter() - t1
+        sample = 32
+        Xc = sbn_synth.activations(sample, H, sbn_synth.seed_for(3, 10)).float().numpy()
+        t1 = time.perf_counter()
+        oracle.sparse_ternary_linear(Xc, Weff, g)
+        dt = time.perf_counter() - t1
+        sample = int(min(T, max(sample, sample * 12.0 / max(dt, 1e-3))))     # aim at ~12 s of oracle time
+        Xc = sbn_synth.activations(sample, H, sbn_synth.seed_for(3, 10)).float().numpy()
+        t1 = time.perf_counter()
+        oracle.sparse_ternary_linear(Xc, Weff, g)
+        dt = time.perf_counter() - t1
+        cpu_baseline = {"value": 2.0 * sample * F * H / dt / 1e12, "unit": "TOPS", "cores": oracle.threads(),
+                        "kind": "oracle",
+                        "sample": f"forward of {sample} of {T} tokens against the {F}x{H} matrix "
+                                  f"(dense brute-force accumulate) in {dt:.1f} s; weight side (mask, quantize) of that "
+                                  f"matrix took {pack_s:.2f} s"}
+        log(f"[cpu] oracle: {cpu_baseline['value']:.4f} TOPS on {cpu_baseline['cores']} threads ({cpu_baseline['sample']})")
+
+    out = {
+        "metric": "N:M ternary GEMM TOPS + decode GEMV GB/s (% of MI355X roofline)",
+        "value": value, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "configs[2] prefill: X 4096x2560 bf16 -> act-quant + 2:4 sparse-MFMA GEMM + rescale "
+                               "against packed ternary 2560x2560 and 6912x2560, fp32 Y; ops counted dense-equivalent "
+                               "2*T*K*d_out", "tokens": T, "pattern": "2:4", "rotating_buffer_sets": NSETS},
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+        "gemv_gbps": None if roofline_gemv is None else roofline_gemv["achieved"],
+        "roofline_gemv": roofline_gemv,
+        "rows": rows,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -100,13 +100,24 @@ sbn_status sbn_quantize_mask_pack_batched(int count, const void *const *W_latent
                                           void *workspace, size_t ws_bytes, void *stream);
 
 /*
+ * Activation quantizer alone (Section 2.1, absmax int8 activations; Appendix B listing, forward()):
+ *   s_x[t] = 127 / max(max_k |X[t,k]|, 1e-5),  xq[t,k] = clip(round_half_even(X[t,k] * s_x[t]), -128, 127)
+ *   X  device, bf16 [tokens, d_in], 16-byte aligned, d_in % 8 == 0;  xq device int8 [tokens, d_in], 16-byte
+ *   aligned; sx device fp32 [tokens].  The forward call below runs this itself; it is exported for callers
+ *   that quantize once and feed several layers (Q/K/V, up/gate).
+ */
+sbn_status sbn_act_quant(const void *X, int64_t tokens, int64_t d_in, int8_t *xq, float *sx, void *stream);
+
+/*
  * Forward of the layer (Section 2.1 activation quantizer; Section 2.2 forward-pass equation;
  * Appendix B listing, forward()):
  *   s_x[t]   = 127 / max(max_k |X[t,k]|, 1e-5)                       (fp32)
  *   xq[t,k]  = clip(round_half_even(X[t,k] * s_x[t]), -128, 127)     (int8)
  *   acc[t,o] = sum_k W_eff[o,k] * xq[t,k]                            (int32, exact)
  *   Y[t,o]   = acc[t,o] * gamma / s_x[t] (+ bias[o])                 (fp32)
- *   X        device, bf16 [tokens, d_in], 16-byte aligned, d_in % 16 == 0 for the MFMA paths
+ *   X        device, bf16 [tokens, d_in], 16-byte aligned, d_in % 8 == 0 (d_in % 128 == 0 for the MFMA paths);
+ *            or NULL: then xq_out and sx_out are INPUTS holding activations already quantized by
+ *            sbn_act_quant, and the quantizer is skipped
  *   packed   device, from sbn_quantize_mask_pack with the same d_out, d_in, N, M
  *   gamma    device, one float (stays on the device between the two calls: no host sync)
  *   bias     device, fp32 [d_out], or NULL

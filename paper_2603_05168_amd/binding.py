@@ -47,6 +47,8 @@ def _load():
     lib.sbn_quantize_mask_pack.argtypes = [vp, cint, i64, i64, i64, cint, cint, vp, vp, vp, sz, vp]
     lib.sbn_quantize_mask_pack_batched.restype = cint
     lib.sbn_quantize_mask_pack_batched.argtypes = [cint, pp, cint, pi64, pi64, cint, cint, pp, pp, vp, sz, vp]
+    lib.sbn_act_quant.restype = cint
+    lib.sbn_act_quant.argtypes = [vp, i64, i64, vp, vp, vp]
     lib.sbn_sparse_ternary_linear.restype = cint
     lib.sbn_sparse_ternary_linear.argtypes = [vp, i64, i64, i64, cint, cint, vp, vp, vp, vp, vp, vp, vp, cint, vp, sz, vp]
     lib.sbn_sparse_ternary_linear_grouped.restype = cint
@@ -157,11 +159,19 @@ def sbn_quantize_mask_pack_batched(W_list, N: int, M: int, packed_list, gamma_li
     PackBatch(W_list, N, M, packed_list, gamma_list, workspace).run()
 
 
+def sbn_act_quant(X, xq, sx):
+    tokens, d_in = X.shape
+    if X.dtype != torch.bfloat16:
+        raise TypeError("X must be bf16")
+    _check(_lib.sbn_act_quant(_ptr(X), tokens, d_in, _ptr(xq), _ptr(sx), _stream()), "sbn_act_quant")
+
+
 def sbn_sparse_ternary_linear(X, packed, gamma, Y, N: int, M: int, workspace, bias=None, xq_out=None, sx_out=None,
                               acc_out=None, path: int = SBN_PATH_AUTO):
-    tokens, d_in = X.shape
+    """X = None runs on activations already quantized into xq_out / sx_out (then inputs)."""
+    tokens, d_in = X.shape if X is not None else xq_out.shape
     d_out = Y.shape[1]
-    if X.dtype != torch.bfloat16 or Y.dtype != torch.float32:
+    if (X is not None and X.dtype != torch.bfloat16) or Y.dtype != torch.float32:
         raise TypeError("X must be bf16 and Y fp32")
     _check(_lib.sbn_sparse_ternary_linear(_ptr(X), tokens, d_in, d_out, N, M, _ptr(packed), _ptr(gamma), _ptr(bias),
                                           _ptr(Y), _ptr(xq_out), _ptr(sx_out), _ptr(acc_out), path, _ptr(workspace),

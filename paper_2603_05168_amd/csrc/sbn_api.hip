@@ -121,6 +121,14 @@ sbn_status sbn_unpack(const void *packed, int64_t d_out, int64_t d_in, int N, in
     return launch_unpack(packed, d_out, d_in, pat, W_eff, mask, static_cast<hipStream_t>(stream));
 }
 
+sbn_status sbn_act_quant(const void *X, int64_t tokens, int64_t d_in, int8_t *xq, float *sx, void *stream)
+{
+    if (!X || !xq || !sx || tokens <= 0 || d_in <= 0) return SBN_EINVAL;
+    if (d_in % 8 != 0) return SBN_EUNSUPPORTED;
+    if (!aligned(X, 16) || !aligned(xq, 16) || !aligned(sx, 4)) return SBN_EALIGN;
+    return launch_act_quant(X, tokens, d_in, xq, sx, static_cast<hipStream_t>(stream));
+}
+
 static sbn_status linear_one(const LinearItem &it_in, const Pattern &pat, sbn_path path, void *workspace,
                              size_t ws_bytes, hipStream_t stream)
 {
@@ -140,7 +148,8 @@ static sbn_status linear_one(const LinearItem &it_in, const Pattern &pat, sbn_pa
     if (!it.sx) it.sx = reinterpret_cast<float *>(ws + xq_bytes);
     int8_t *w_dense = reinterpret_cast<int8_t *>(ws + xq_bytes + sx_bytes);
 
-    sbn_status st = launch_act_quant(it.X, it.tokens, it.d_in, it.xq, it.sx, stream);
+    sbn_status st = SBN_OK;
+    if (it.X) st = launch_act_quant(it.X, it.tokens, it.d_in, it.xq, it.sx, stream);
     if (st != SBN_OK) return st;
     switch (path) {
     case SBN_PATH_GEMV: return launch_gemv(1, &it, stream);
@@ -157,7 +166,8 @@ sbn_status sbn_sparse_ternary_linear(const void *X, int64_t tokens, int64_t d_in
                                      size_t ws_bytes, void *stream)
 {
     Pattern pat;
-    if (!X || !packed || !gamma || !Y || !workspace || tokens <= 0) return SBN_EINVAL;
+    if (!packed || !gamma || !Y || !workspace || tokens <= 0) return SBN_EINVAL;
+    if (!X && (!xq_out || !sx_out)) return SBN_EINVAL;   // pre-quantized mode needs both inputs
     if (path < SBN_PATH_AUTO || path > SBN_PATH_GENERIC) return SBN_EINVAL;
     sbn_status st = check_shape(d_out, d_in, N, M, pat);
     if (st != SBN_OK) return st;

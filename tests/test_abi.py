@@ -1,0 +1,108 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, answers the size queries, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "sbn.h")
+
+
+@pytest.fixture(scope="module")
+def sbn():
+    import paper_2603_05168_amd as m
+    return m
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sbn_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_boundary():
+    names = declared_functions()
+    for must in ("sbn_quantize_mask_pack", "sbn_sparse_ternary_linear", "sbn_sparse_ternary_linear_backward",
+                 "sbn_packed_bytes", "sbn_workspace_bytes", "sbn_unpack", "sbn_last_error"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol(sbn):
+    lib = ctypes.CDLL(sbn.lib_path())
+    for name in declared_functions():
+        assert hasattr(lib, name), f"{name} is declared in include/sbn.h but not exported"
+    for name in declared_functions():
+        assert hasattr(sbn, name), f"{name} has no Python binding of the same name"
+
+
+def test_packed_bytes(sbn):
+    assert sbn.sbn_packed_bytes(6912, 2560, 2, 4) == 6912 * 2560 // 4
+    assert sbn.sbn_packed_bytes(6912, 2560, 1, 4) == 6912 * 2560 // 8
+    assert sbn.sbn_packed_bytes(2560, 6912, 2, 8) == 2560 * 6912 * 5 // 32
+    assert sbn.sbn_packed_bytes(3, 8, 2, 4) == 3 * 32            # one zero-padded chunk per row
+    assert sbn.sbn_packed_bytes(16, 256, 8, 8) == 16 * 256 // 4  # dense ternary: 2 bits per weight, no indices
+
+
+def test_packed_bytes_matches_oracle_layout(sbn):
+    import oracle
+    for N, M in ((2, 4), (1, 4), (2, 8), (6, 8), (4, 4), (1, 2), (7, 8)):
+        for d_in in (8, 128, 136, 2560):
+            assert sbn.sbn_packed_bytes(24, d_in, N, M) == oracle.packed_bytes(24, d_in, N, M)
+
+
+@pytest.mark.parametrize("args", [(0, 256, 2, 4), (16, 0, 2, 4), (16, 130, 2, 4), (16, 256, 0, 4), (16, 256, 5, 4),
+                                  (16, 256, 2, 3), (16, 256, 2, 16)])
+def test_bad_shapes_are_einval(sbn, args):
+    with pytest.raises(sbn.SbnError) as e:
+        sbn.sbn_packed_bytes(*args)
+    assert e.value.status == sbn.SBN_EINVAL
+
+
+def test_workspace_queries(sbn):
+    for op in (sbn.SBN_OP_QUANTIZE_MASK_PACK, sbn.SBN_OP_LINEAR, sbn.SBN_OP_BACKWARD):
+        assert sbn.sbn_workspace_bytes(op, 16, 256, 256, 2, 4) > 0
+    with pytest.raises(sbn.SbnError):
+        sbn.sbn_workspace_bytes(7, 16, 256, 256, 2, 4)
+    with pytest.raises(sbn.SbnError):
+        sbn.sbn_workspace_bytes(sbn.SBN_OP_LINEAR, 0, 256, 256, 2, 4)
+
+
+def test_argument_errors_come_before_any_launch(sbn):
+    """Null and misaligned pointers, short workspaces and unsupported requests return their status
+    on the host; no GPU is present here, so reaching a launch would fail differently."""
+    lib = ctypes.CDLL(sbn.lib_path())
+    lib.sbn_quantize_mask_pack.restype = ctypes.c_int
+    lib.sbn_sparse_ternary_linear.restype = ctypes.c_int
+    lib.sbn_sparse_ternary_linear_backward.restype = ctypes.c_int
+    vp, i64, ci, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t
+    A = 0x10000  # fake, aligned, never dereferenced on the host
+    # null packed
+    assert lib.sbn_quantize_mask_pack(vp(A), ci(1), i64(16), i64(256), i64(256), ci(2), ci(4), vp(0), vp(A), vp(A),
+                                      sz(1 << 20), vp(0)) == sbn.SBN_EINVAL
+    # ld_w < d_in
+    assert lib.sbn_quantize_mask_pack(vp(A), ci(1), i64(16), i64(256), i64(128), ci(2), ci(4), vp(A), vp(A), vp(A),
+                                      sz(1 << 20), vp(0)) == sbn.SBN_EINVAL
+    # misaligned packed
+    assert lib.sbn_quantize_mask_pack(vp(A), ci(1), i64(16), i64(256), i64(256), ci(2), ci(4), vp(A + 4), vp(A), vp(A),
+                                      sz(1 << 20), vp(0)) == sbn.SBN_EALIGN
+    # workspace too small
+    assert lib.sbn_quantize_mask_pack(vp(A), ci(1), i64(16), i64(256), i64(256), ci(2), ci(4), vp(A), vp(A), vp(A),
+                                      sz(8), vp(0)) == sbn.SBN_ESIZE
+    lin = lambda **kw: lib.sbn_sparse_ternary_linear(  # noqa: E731
+        vp(kw.get("X", A)), i64(kw.get("tokens", 8)), i64(kw.get("d_in", 256)), i64(256), ci(kw.get("N", 2)),
+        ci(kw.get("M", 4)), vp(A), vp(A), vp(0), vp(kw.get("Y", A)), vp(0), vp(0), vp(0), ci(kw.get("path", 0)), vp(A),
+        sz(kw.get("ws", 1 << 24)), vp(0))
+    assert lin(Y=0) == sbn.SBN_EINVAL
+    assert lin(X=0) == sbn.SBN_EINVAL                       # no X and no pre-quantized inputs
+    assert lin(X=A + 2) == sbn.SBN_EALIGN
+    assert lin(path=9) == sbn.SBN_EINVAL
+    assert lin(ws=16) == sbn.SBN_ESIZE
+    assert lin(N=1, path=sbn.SBN_PATH_SMFMAC) == sbn.SBN_EUNSUPPORTED      # sparse MFMA path is 2:4 only
+    assert lin(tokens=64, path=sbn.SBN_PATH_GEMV) == sbn.SBN_EUNSUPPORTED  # decode kernel takes <= 16 tokens
+    assert lin(d_in=200, path=sbn.SBN_PATH_SMFMAC) == sbn.SBN_EUNSUPPORTED
+    # backward: nothing requested
+    assert lib.sbn_sparse_ternary_linear_backward(vp(A), i64(8), i64(256), i64(256), ci(2), ci(4), vp(A), vp(A), vp(A),
+                                                  vp(A), vp(0), vp(0), ci(0), vp(A), sz(1 << 24), vp(0)) == sbn.SBN_EINVAL
+    assert sbn.sbn_last_error() == ""
