@@ -76,22 +76,19 @@ struct GemvItem {
     const float *bias;
     float *Y;
     int32_t *acc_out;
-    int d_in, d_out, tokens, block0;
+    int d_in, d_out, tokens, pad;
 };
 constexpr int GEMV_MAX_ITEMS = 48;
 struct GemvTable {
-    GemvItem it[GEMV_MAX_ITEMS];
-    int count;
-    int total_blocks;
+    GemvItem it[GEMV_MAX_ITEMS];   // problem = blockIdx.y; row tile = blockIdx.x (surplus blocks exit at once)
 };
 
 __global__ void __launch_bounds__(1024) gemv_smfmac_kernel(GemvTable tab)
 {
     __shared__ v4i red[16][64];
-    int item = 0;
-    while (item + 1 < tab.count && (int)blockIdx.x >= tab.it[item + 1].block0) ++item;
-    const GemvItem &it = tab.it[item];
-    const int row0 = ((int)blockIdx.x - it.block0) * 16;
+    const GemvItem &it = tab.it[blockIdx.y];
+    const int row0 = (int)blockIdx.x * 16;
+    if (row0 >= it.d_out) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
     const int r = lane & 15, c4 = lane >> 4;
     const int K = it.d_in, nchunks = K / CHUNK, nsuper = (nchunks + 3) / 4;
@@ -140,6 +137,127 @@ __global__ void __launch_bounds__(1024) gemv_smfmac_kernel(GemvTable tab)
                     if (it.bias) y += it.bias[o];
                     it.Y[(int64_t)tok * it.d_out + o] = y;
                     if (it.acc_out) it.acc_out[(int64_t)tok * it.d_out + o] = acc[i];
+                }
+            }
+        }
+    }
+}
+
+// ---- streaming decode GEMV for grouped calls ---------------------------------------------------
+// Persistent blocks: the rows of all problems are cut into units of 16*RT rows x the whole input
+// dimension; every block takes a contiguous run of units and its four wavefronts split that run,
+// so each wavefront reads one contiguous range of packed bytes.  The int8 activations of the
+// current problem (tokens x d_in) are staged in LDS once per block and problem; the packed weights
+// go straight from HBM to registers through a queue of DEPTH super-steps (512 weights each) per
+// wavefront, so that several 16-byte loads per lane are always in flight.  No cross-wave reduction.
+struct GemvStreamItem {
+    const int8_t *xq;
+    const float *sx;
+    const uint8_t *packed;
+    const float *gamma;
+    float *Y;
+    int d_in, d_out, tokens, pad;
+};
+constexpr int GEMV_STREAM_MAX = 64;
+struct GemvStreamTable {
+    GemvStreamItem it[GEMV_STREAM_MAX];
+    int unit0[GEMV_STREAM_MAX + 1];   // first unit of each problem
+    int count;
+};
+
+template <int RT, int DEPTH>
+__global__ void __launch_bounds__(256) gemv_stream_kernel(GemvStreamTable tab)
+{
+    extern __shared__ __attribute__((aligned(16))) int8_t xlds[];   // [tokens][d_in + 16]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int total = tab.unit0[tab.count];
+    const int b0 = (int)((int64_t)total * blockIdx.x / gridDim.x), b1 = (int)((int64_t)total * (blockIdx.x + 1) / gridDim.x);
+    const int r = lane & 15, c4 = lane >> 4;
+    int item = 0;
+    int u = b0;
+    while (u < b1) {
+        while (u >= tab.unit0[item + 1]) ++item;
+        const GemvStreamItem &it = tab.it[item];
+        const int seg_end = b1 < tab.unit0[item + 1] ? b1 : tab.unit0[item + 1];
+        const int ua = u - tab.unit0[item], ub = seg_end - tab.unit0[item];   // units of this problem for the block
+        u = seg_end;
+        const int K = it.d_in, nchunks = K / CHUNK, nsuper = (nchunks + 3) / 4, pitch = K + 16;
+
+        __syncthreads();   // the previous problem's activations are no longer read
+        for (int v = threadIdx.x; v < it.tokens * (K / 16); v += 256) {
+            const int t = v / (K / 16), k = (v % (K / 16)) * 16;
+            *reinterpret_cast<uint4 *>(&xlds[t * pitch + k]) = *reinterpret_cast<const uint4 *>(it.xq + (int64_t)t * K + k);
+        }
+        const bool tok_ok = r < it.tokens;
+        const float scale = tok_ok ? __fdiv_rn(*it.gamma, it.sx[r]) : 0.0f;
+        __syncthreads();
+
+        const int wa = ua + (int)((int64_t)(ub - ua) * wave / 4), wb = ua + (int)((int64_t)(ub - ua) * (wave + 1) / 4);
+        const int nsteps = (wb - wa) * nsuper;
+        const int xoff = (tok_ok ? r : 0) * pitch + 128 * (c4 >> 1) + 16 * (c4 & 1);
+        int iu = wa, is = 0, cu = wa, cs = 0;
+        uint4 qi[DEPTH][RT], qc[DEPTH][RT];
+        auto issue = [&](uint4(&ib)[RT], uint4(&cb)[RT]) {
+            const bool a_ok = 4 * is + c4 < nchunks;
+#pragma unroll
+            for (int a = 0; a < RT; ++a) {
+                int row = iu * 16 * RT + 16 * a + r;
+                row = row < it.d_out ? row : it.d_out - 1;
+                const uint8_t *p = it.packed + ((int64_t)row * nchunks + 4 * is + c4) * 32;
+                ib[a] = a_ok ? *reinterpret_cast<const uint4 *>(p) : make_uint4(0, 0, 0, 0);
+                cb[a] = a_ok ? *reinterpret_cast<const uint4 *>(p + 16) : make_uint4(0, 0, 0, 0);
+            }
+            if (++is == nsuper) { is = 0; ++iu; }
+        };
+        v4i acc[RT];
+#pragma unroll
+        for (int a = 0; a < RT; ++a) acc[a] = v4i{0, 0, 0, 0};
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d)
+            if (d < nsteps) issue(qi[d], qc[d]);
+        for (int q = 0; q < nsteps; q += DEPTH) {
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) {
+                if (q + d < nsteps) {
+                    uint4 ic[RT], cc[RT];
+#pragma unroll
+                    for (int a = 0; a < RT; ++a) { ic[a] = qi[d][a]; cc[a] = qc[d][a]; }
+                    if (q + d + DEPTH < nsteps) issue(qi[d], qc[d]);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int k_lo = cs * 512 + 128 * (c4 >> 1) + 16 * (c4 & 1) + 32 * j, k_hi = k_lo + 256;
+                        uint4 blo = make_uint4(0, 0, 0, 0), bhi = make_uint4(0, 0, 0, 0);
+                        if (tok_ok && k_lo < K) blo = *reinterpret_cast<const uint4 *>(&xlds[xoff + cs * 512 + 32 * j]);
+                        if (tok_ok && k_hi < K) bhi = *reinterpret_cast<const uint4 *>(&xlds[xoff + cs * 512 + 32 * j + 256]);
+                        const v8i b = {(int)blo.x, (int)blo.y, (int)blo.z, (int)blo.w, (int)bhi.x, (int)bhi.y, (int)bhi.z, (int)bhi.w};
+#pragma unroll
+                        for (int a = 0; a < RT; ++a) {
+                            const uint32_t cw = j == 0 ? cc[a].x : j == 1 ? cc[a].y : j == 2 ? cc[a].z : cc[a].w;
+                            const uint32_t iw = j == 0 ? ic[a].x : j == 1 ? ic[a].y : j == 2 ? ic[a].z : ic[a].w;
+                            acc[a] = __builtin_amdgcn_smfmac_i32_16x16x128_i8(expand_codes(cw), b, acc[a], (int)iw, 0, 0);
+                        }
+                    }
+                    if (++cs == nsuper) {
+                        // unit cu complete: lane holds token r, rows 4 * c4 + i of each row tile
+                        if (tok_ok) {
+#pragma unroll
+                            for (int a = 0; a < RT; ++a) {
+                                const int o = cu * 16 * RT + 16 * a + 4 * c4;
+                                if (o + 3 < it.d_out && (it.d_out & 3) == 0) {
+                                    *reinterpret_cast<float4 *>(it.Y + (int64_t)r * it.d_out + o) =
+                                        make_float4((float)acc[a][0] * scale, (float)acc[a][1] * scale,
+                                                    (float)acc[a][2] * scale, (float)acc[a][3] * scale);
+                                } else {
+                                    for (int i = 0; i < 4; ++i)
+                                        if (o + i < it.d_out) it.Y[(int64_t)r * it.d_out + o + i] = (float)acc[a][i] * scale;
+                                }
+                            }
+                        }
+#pragma unroll
+                        for (int a = 0; a < RT; ++a) acc[a] = v4i{0, 0, 0, 0};
+                        cs = 0;
+                        ++cu;
+                    }
                 }
             }
         }
@@ -207,29 +325,91 @@ sbn_status launch_act_quant(const void *X, int64_t tokens, int64_t d_in, int8_t 
     return check_launch("act_quant_kernel");
 }
 
+static void fill_gemv_item(GemvItem &g, const LinearItem &li)
+{
+    g.xq = li.xq; g.sx = li.sx; g.packed = static_cast<const uint8_t *>(li.packed);
+    g.gamma = li.gamma; g.bias = li.bias; g.Y = li.Y; g.acc_out = li.acc_out;
+    g.d_in = (int)li.d_in; g.d_out = (int)li.d_out; g.tokens = (int)li.tokens; g.pad = 0;
+}
+
+// multiprocessors of the current device (cached per thread)
+static int device_cus()
+{
+    static thread_local int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) cus = prop.multiProcessorCount;
+        if (cus <= 0) cus = 256;
+    }
+    return cus;
+}
+
 sbn_status launch_gemv(int count, const LinearItem *items, hipStream_t stream)
 {
-    for (int first = 0; first < count; first += GEMV_MAX_ITEMS) {
-        const int n = count - first < GEMV_MAX_ITEMS ? count - first : GEMV_MAX_ITEMS;
+    constexpr int RT = 2;
+    int first = 0;
+    while (first < count) {
+        // --- persistent streaming kernel when a run of problems holds enough rows to keep every block busy
+        int n = count - first < GEMV_STREAM_MAX ? count - first : GEMV_STREAM_MAX;
+        int64_t units = 0, lds_need = 16;
+        bool plain = true;
+        for (int i = 0; i < n; ++i) {
+            const LinearItem &li = items[first + i];
+            units += ceil_div(li.d_out, 16 * RT);
+            const int64_t b = li.tokens * (li.d_in + 16);
+            lds_need = b > lds_need ? b : lds_need;
+            if (li.bias || li.acc_out) plain = false;
+        }
+        int bpc = (int)(160 * 1024 / lds_need);   // blocks per multiprocessor the staged activations leave room for
+        bpc = bpc > 4 ? 4 : bpc;
+        const int nblocks = device_cus() * bpc;
+        if (plain && bpc >= 1 && units >= 4 * (int64_t)nblocks) {
+            GemvStreamTable tab;
+            tab.count = n;
+            int u = 0;
+            for (int i = 0; i < n; ++i) {
+                const LinearItem &li = items[first + i];
+                GemvStreamItem &g = tab.it[i];
+                g.xq = li.xq; g.sx = li.sx; g.packed = static_cast<const uint8_t *>(li.packed); g.gamma = li.gamma; g.Y = li.Y;
+                g.d_in = (int)li.d_in; g.d_out = (int)li.d_out; g.tokens = (int)li.tokens; g.pad = 0;
+                tab.unit0[i] = u;
+                u += (int)ceil_div(li.d_out, 16 * RT);
+            }
+            tab.unit0[n] = u;
+            if (lds_need > 64 * 1024) {
+                static thread_local bool raised = false;
+                if (!raised) {
+                    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemv_stream_kernel<RT, 4>),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+                    if (e != hipSuccess) { set_hip_error(e, "hipFuncSetAttribute"); return SBN_EHIP; }
+                    raised = true;
+                }
+            }
+            hipLaunchKernelGGL((gemv_stream_kernel<RT, 4>), dim3(nblocks), dim3(256), (size_t)lds_need, stream, tab);
+            sbn_status st = check_launch("gemv_stream_kernel");
+            if (st != SBN_OK) return st;
+            first += n;
+            continue;
+        }
+        // --- otherwise: one block per 16 rows, wavefronts split the input dimension (lowest latency)
+        n = count - first < GEMV_MAX_ITEMS ? count - first : GEMV_MAX_ITEMS;
         GemvTable tab;
-        tab.count = n;
         int blocks = 0, max_super = 1;
         for (int i = 0; i < n; ++i) {
             const LinearItem &li = items[first + i];
-            GemvItem &g = tab.it[i];
-            g.xq = li.xq; g.sx = li.sx; g.packed = static_cast<const uint8_t *>(li.packed);
-            g.gamma = li.gamma; g.bias = li.bias; g.Y = li.Y; g.acc_out = li.acc_out;
-            g.d_in = (int)li.d_in; g.d_out = (int)li.d_out; g.tokens = (int)li.tokens; g.block0 = blocks;
-            blocks += (int)ceil_div(li.d_out, 16);
+            fill_gemv_item(tab.it[i], li);
+            const int nb = (int)ceil_div(li.d_out, 16);
+            blocks = nb > blocks ? nb : blocks;
             const int nsuper = (int)ceil_div(li.d_in / CHUNK, 4);
             max_super = nsuper > max_super ? nsuper : max_super;
         }
-        tab.total_blocks = blocks;
         // one wavefront per super-step up to 16, so that every wavefront has loads in flight at once
         const int nwaves = max_super < 16 ? max_super : 16;
-        hipLaunchKernelGGL(gemv_smfmac_kernel, dim3(blocks), dim3(64 * nwaves), 0, stream, tab);
+        hipLaunchKernelGGL(gemv_smfmac_kernel, dim3(blocks, n), dim3(64 * nwaves), 0, stream, tab);
         sbn_status st = check_launch("gemv_smfmac_kernel");
         if (st != SBN_OK) return st;
+        first += n;
     }
     return SBN_OK;
 }

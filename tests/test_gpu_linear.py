@@ -130,3 +130,28 @@ def test_sparse_and_dense_paths_agree_bitwise_full_size():
     Ya, acca, *_ = hip_linear(X, packed, gamma, 2560, 2, 4, s.SBN_PATH_SMFMAC)
     Yb, accb, *_ = hip_linear(X, packed, gamma, 2560, 2, 4, s.SBN_PATH_DENSE_MFMA)
     assert np.array_equal(acca, accb) and np.array_equal(Ya, Yb)
+
+
+@pytest.mark.parametrize("tokens", [1, 8, 16])
+def test_grouped_streaming_gemv_against_oracle(tokens):
+    # enough rows in one grouped call to take the persistent streaming kernel; shapes with ragged
+    # row counts and a partial last super-step (K = 768 = 6 chunks)
+    s = sbn()
+    shapes = [(4100, 768), (4096, 256), (5000, 640)] * 14
+    Ws = {sh: sbn_synth.latent_weight(sh[0], sh[1], 650 + sh[0]) for sh in set(shapes)}
+    packs = {sh: hip_pack(W, 2, 4) for sh, W in Ws.items()}
+    Xs = {k: sbn_synth.activations(tokens, k, 750 + k) for k in (768, 256, 640)}
+    Xd = {k: x.to(DEV) for k, x in Xs.items()}
+    Y_list = [torch.full((tokens, a), float("nan"), dtype=torch.float32, device=DEV) for a, _ in shapes]
+    need = sum(s.sbn_workspace_bytes(s.SBN_OP_LINEAR, tokens, a, b, 2, 4) for a, b in shapes)
+    ws = s.new_workspace(need)
+    s.sbn_sparse_ternary_linear_grouped([Xd[b] for _, b in shapes], [packs[sh][0] for sh in shapes],
+                                        [packs[sh][1] for sh in shapes], Y_list, 2, 4, ws, path=s.SBN_PATH_GEMV)
+    torch.cuda.synchronize()
+    ref = {}
+    for sh, W in Ws.items():
+        _, g, Weff, _ = oracle_pack(W, 2, 4)
+        y, *_ = oracle.sparse_ternary_linear(Xs[sh[1]].float().numpy(), Weff, g)
+        ref[sh] = y
+    for i, sh in enumerate(shapes):
+        assert_rel(Y_list[i].cpu().numpy(), ref[sh], Y_TOL, f"Y of problem {i}")
