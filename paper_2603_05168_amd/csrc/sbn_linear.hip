@@ -3,17 +3,89 @@
 // Appendix B listing (forward()).
 #include "sbn_internal.hpp"
 #include "sbn_mfma.hpp"
+#include <stdlib.h>
 
 namespace sbn {
 
 namespace {
 
 // ---- activation quantizer -----------------------------------------------------------------------
-// One wavefront per token.  Pass 1 takes the maximum magnitude on the bf16 bit patterns (exact),
-// pass 2 re-reads the row (cache resident) and writes int8.  s_x = 127 / max(amax, 1e-5) is one
-// IEEE fp32 division, x * s_x one fp32 multiply, rounding is half-to-even.
-__global__ void __launch_bounds__(256) act_quant_kernel(const uint4 *__restrict__ X, int64_t tokens, int nvec,
-                                                       int8_t *__restrict__ xq, float *__restrict__ sx)
+// TPT threads share one token (64 = one wavefront per token for prefill, 1024 = one block per token
+// for decode, where only a handful of tokens exist).  A thread keeps its 16-byte vectors of the row
+// in registers, so X is read once; the maximum magnitude is taken on the bf16 bit patterns (exact).
+// s_x = 127 / max(amax, 1e-5) is one IEEE fp32 division, x * s_x one fp32 multiply, rounding is
+// half-to-even.  Rows longer than VMAX * TPT vectors take the two-pass kernel below.
+template <int TPT, int VMAX>
+__global__ void __launch_bounds__(TPT < 256 ? 256 : TPT) act_quant_kernel(const uint4 *__restrict__ X, int64_t tokens, int nvec,
+                                                                         int8_t *__restrict__ xq, float *__restrict__ sx)
+{
+    constexpr int BLOCK = TPT < 256 ? 256 : TPT;
+    constexpr int TOK_PER_BLOCK = BLOCK / TPT;
+    __shared__ uint32_t wave_max[BLOCK / 64];
+    const int sub = threadIdx.x % TPT;
+    const int64_t t = (int64_t)blockIdx.x * TOK_PER_BLOCK + threadIdx.x / TPT;
+    const bool live = t < tokens;
+    const uint4 *row = X + (live ? t : 0) * nvec;
+    uint4 v[VMAX];
+    uint32_t m = 0;
+#pragma unroll
+    for (int i = 0; i < VMAX; ++i) {
+        const int idx = sub + i * TPT;
+        v[i] = (live && idx < nvec) ? row[idx] : make_uint4(0, 0, 0, 0);
+        const uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint32_t lo = w[k] & 0x7fffu, hi = (w[k] >> 16) & 0x7fffu;
+            m = lo > m ? lo : m;
+            m = hi > m ? hi : m;
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const uint32_t o = (uint32_t)__shfl_xor((int)m, off, 64);
+        m = o > m ? o : m;
+    }
+    if constexpr (TPT > 64) {
+        if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < TPT / 64; ++w) {
+            const uint32_t o = wave_max[w];
+            m = o > m ? o : m;
+        }
+    }
+    float amax = __uint_as_float(m << 16);
+    amax = amax < 1e-5f ? 1e-5f : amax;
+    const float s = __fdiv_rn(127.0f, amax);
+    if (!live) return;
+    if (sub == 0) sx[t] = s;
+    uint2 *out = reinterpret_cast<uint2 *>(xq + t * (int64_t)nvec * 8);
+#pragma unroll
+    for (int i = 0; i < VMAX; ++i) {
+        const int idx = sub + i * TPT;
+        if (idx >= nvec) break;
+        const uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+        uint32_t packed[2] = {0, 0};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const float x = __uint_as_float(h ? (w[k] & 0xffff0000u) : (w[k] << 16));
+                float q = rintf(__fmul_rn(x, s));
+                q = q > 127.0f ? 127.0f : q;
+                q = q < -128.0f ? -128.0f : q;
+                const uint32_t byte = (uint32_t)(int)q & 0xffu;
+                const int e = 2 * k + h;
+                packed[e >> 2] |= byte << (8 * (e & 3));
+            }
+        }
+        out[idx] = make_uint2(packed[0], packed[1]);
+    }
+}
+
+// any row length: one wavefront per token, the row is read twice (the second read is cache resident)
+__global__ void __launch_bounds__(256) act_quant_two_pass_kernel(const uint4 *__restrict__ X, int64_t tokens, int nvec,
+                                                                int8_t *__restrict__ xq, float *__restrict__ sx)
 {
     const int lane = threadIdx.x & 63;
     const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -183,15 +255,7 @@ __global__ void __launch_bounds__(256) gemv_stream_kernel(GemvStreamTable tab)
         u = seg_end;
         const int K = it.d_in, nchunks = K / CHUNK, nsuper = (nchunks + 3) / 4, pitch = K + 16;
 
-        __syncthreads();   // the previous problem's activations are no longer read
-        for (int v = threadIdx.x; v < it.tokens * (K / 16); v += 256) {
-            const int t = v / (K / 16), k = (v % (K / 16)) * 16;
-            *reinterpret_cast<uint4 *>(&xlds[t * pitch + k]) = *reinterpret_cast<const uint4 *>(it.xq + (int64_t)t * K + k);
-        }
         const bool tok_ok = r < it.tokens;
-        const float scale = tok_ok ? __fdiv_rn(*it.gamma, it.sx[r]) : 0.0f;
-        __syncthreads();
-
         const int wa = ua + (int)((int64_t)(ub - ua) * wave / 4), wb = ua + (int)((int64_t)(ub - ua) * (wave + 1) / 4);
         const int nsteps = (wb - wa) * nsuper;
         const int xoff = (tok_ok ? r : 0) * pitch + 128 * (c4 >> 1) + 16 * (c4 & 1);
@@ -209,12 +273,22 @@ __global__ void __launch_bounds__(256) gemv_stream_kernel(GemvStreamTable tab)
             }
             if (++is == nsuper) { is = 0; ++iu; }
         };
-        v4i acc[RT];
-#pragma unroll
-        for (int a = 0; a < RT; ++a) acc[a] = v4i{0, 0, 0, 0};
+        // weight loads first: they are in flight while the activations are staged
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d)
             if (d < nsteps) issue(qi[d], qc[d]);
+
+        __syncthreads();   // the previous problem's activations are no longer read
+        for (int v = threadIdx.x; v < it.tokens * (K / 16); v += 256) {
+            const int t = v / (K / 16), k = (v % (K / 16)) * 16;
+            *reinterpret_cast<uint4 *>(&xlds[t * pitch + k]) = *reinterpret_cast<const uint4 *>(it.xq + (int64_t)t * K + k);
+        }
+        const float scale = tok_ok ? __fdiv_rn(*it.gamma, it.sx[r]) : 0.0f;
+        __syncthreads();
+
+        v4i acc[RT];
+#pragma unroll
+        for (int a = 0; a < RT; ++a) acc[a] = v4i{0, 0, 0, 0};
         for (int q = 0; q < nsteps; q += DEPTH) {
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) {
@@ -320,8 +394,15 @@ size_t linear_workspace_bytes(int64_t tokens, int64_t d_out, int64_t d_in)
 
 sbn_status launch_act_quant(const void *X, int64_t tokens, int64_t d_in, int8_t *xq, float *sx, hipStream_t stream)
 {
-    hipLaunchKernelGGL(act_quant_kernel, dim3((unsigned)ceil_div(tokens, 4)), dim3(256), 0, stream,
-                       static_cast<const uint4 *>(X), tokens, (int)(d_in / 8), xq, sx);
+    const uint4 *x = static_cast<const uint4 *>(X);
+    const int nvec = (int)(d_in / 8);
+    if (tokens <= 64 && nvec <= 2 * 1024) {
+        hipLaunchKernelGGL((act_quant_kernel<1024, 2>), dim3((unsigned)tokens), dim3(1024), 0, stream, x, tokens, nvec, xq, sx);
+    } else if (nvec <= 16 * 64) {
+        hipLaunchKernelGGL((act_quant_kernel<64, 16>), dim3((unsigned)ceil_div(tokens, 4)), dim3(256), 0, stream, x, tokens, nvec, xq, sx);
+    } else {
+        hipLaunchKernelGGL(act_quant_two_pass_kernel, dim3((unsigned)ceil_div(tokens, 4)), dim3(256), 0, stream, x, tokens, nvec, xq, sx);
+    }
     return check_launch("act_quant_kernel");
 }
 
@@ -386,7 +467,17 @@ sbn_status launch_gemv(int count, const LinearItem *items, hipStream_t stream)
                     raised = true;
                 }
             }
-            hipLaunchKernelGGL((gemv_stream_kernel<RT, 4>), dim3(nblocks), dim3(256), (size_t)lds_need, stream, tab);
+            {
+                const char *v = getenv("SBN_GEMV_VARIANT");
+                const char *bp = getenv("SBN_GEMV_BPC");
+                int nb2 = bp ? device_cus() * atoi(bp) : nblocks;
+                int var = v ? atoi(v) : 0;
+                if (var == 1) hipLaunchKernelGGL((gemv_stream_kernel<2, 6>), dim3(nb2), dim3(256), (size_t)lds_need, stream, tab);
+                else if (var == 2) hipLaunchKernelGGL((gemv_stream_kernel<2, 8>), dim3(nb2), dim3(256), (size_t)lds_need, stream, tab);
+                else if (var == 3) hipLaunchKernelGGL((gemv_stream_kernel<1, 8>), dim3(nb2), dim3(256), (size_t)lds_need, stream, tab);
+                else if (var == 4) hipLaunchKernelGGL((gemv_stream_kernel<4, 3>), dim3(nb2), dim3(256), (size_t)lds_need, stream, tab);
+                else hipLaunchKernelGGL((gemv_stream_kernel<RT, 4>), dim3(nb2), dim3(256), (size_t)lds_need, stream, tab);
+            }
             sbn_status st = check_launch("gemv_stream_kernel");
             if (st != SBN_OK) return st;
             first += n;

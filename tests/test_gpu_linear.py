@@ -155,3 +155,17 @@ def test_grouped_streaming_gemv_against_oracle(tokens):
         ref[sh] = y
     for i, sh in enumerate(shapes):
         assert_rel(Y_list[i].cpu().numpy(), ref[sh], Y_TOL, f"Y of problem {i}")
+
+
+@pytest.mark.parametrize("tokens", [1, 5, 64, 65, 300])
+@pytest.mark.parametrize("d_in", [8, 256, 2560, 6912, 8200, 16520])
+def test_act_quant_entry_all_kernel_variants(tokens, d_in):
+    # block-per-token (decode), wavefront-per-token (prefill) and the two-pass kernel for very long rows
+    s = sbn()
+    X = sbn_synth.adversarial_activations(tokens, d_in, 840 + tokens) if d_in >= 256 else sbn_synth.activations(tokens, d_in, 841)
+    xq = torch.full((tokens, d_in), 77, dtype=torch.int8, device=DEV)
+    sx = torch.zeros(tokens, dtype=torch.float32, device=DEV)
+    s.sbn_act_quant(X.to(DEV), xq, sx)
+    torch.cuda.synchronize()
+    r_xq, r_sx = oracle.act_quant(X.float().numpy())
+    assert np.array_equal(xq.cpu().numpy(), r_xq) and np.array_equal(sx.cpu().numpy(), r_sx)
