@@ -78,37 +78,89 @@ __device__ __forceinline__ void store_tile(const GemmArgs &g, const v16i &acc, i
 
 // ---- sparse path --------------------------------------------------------------------------------
 // 4 wavefronts as 2 (rows) x 2 (tokens); each owns 128 rows x 64 tokens = 4 x 2 tiles of 32x32.
-// Per iteration (one 128-weight chunk) a lane (row r = lane % 32, half c = lane / 32) loads, for
-// each of its four row tiles, index words 2c, 2c+1 and code words 2c, 2c+1 of its row's chunk
-// (two 8-byte loads) straight from global memory; sub-step u = 0, 1 uses word 2c + u, i.e. the
-// lane supplies weights [64c + 32u, +32) of the chunk.  The token tile goes through LDS.
+// Both operands reach LDS through the LDS-DMA load (global_load_lds_dwordx4: lane l of a wavefront
+// deposits its 16 bytes at base + 16*l), so no staging registers are needed and every wavefront
+// load instruction reads whole cache lines:
+//   tokens   128 tokens x 128 int8 per iteration, ring of 3 stages; one instruction fills 8 token
+//            rows of 128 bytes; the 16-byte column a lane fetches is XOR-swizzled with
+//            (row >> 1) & 7 so that 16-byte reads of 16 consecutive rows fall in distinct banks;
+//   weights  256 rows x 64 bytes (two 32-byte chunks = two iterations) per refill, ring of 2 slots;
+//            one instruction fills 16 rows; 16-byte granules swizzled with (row >> 2) & 3.
+// A lane (row r = lane % 32, half c = lane / 32) reads index words 2c, 2c+1 and code words 2c, 2c+1
+// of its row's chunk (two 8-byte LDS reads per row tile); sub-step u = 0, 1 uses word 2c + u, i.e.
+// the lane supplies weights [64c + 32u, +32) of the chunk.
+constexpr int STAGES = 3;
+constexpr int STAGE_BYTES = BT * KSTEP;   // 16 KB
+constexpr int WSLOT_BYTES = BO * 64;      // 16 KB: two chunks of every row of the block
+
+// wait until at most n vector-memory operations of this wavefront are outstanding (gfx9 encoding:
+// vmcnt in bits [3:0] and [15:14]; expcnt and lgkmcnt fields left at "no wait")
+#define SBN_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xf) | (((n) >> 4) << 14) | 0x0f70)
+
 __global__ void __launch_bounds__(256, 2) gemm_smfmac_kernel(GemmArgs g)
 {
-    __shared__ __attribute__((aligned(16))) int8_t lds[2][BT * LDS_ROW];
+    __shared__ __attribute__((aligned(1024))) int8_t lds[STAGES * STAGE_BYTES + 2 * WSLOT_BYTES];
+    int8_t *const wlds = lds + STAGES * STAGE_BYTES;
     int to, tt;
     tile_of_block(g, to, tt);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wo = wave & 1, wt = wave >> 1;
     const int r = lane & 31, c = lane >> 5;
-    const int K = g.d_in, nchunks = K / KSTEP;
-    const int o0 = to * BO + wo * 128, t0 = tt * BT;
+    const int K = g.d_in, nchunks = K / KSTEP, npairs = (nchunks + 1) / 2;
+    const int o0 = to * BO, t0 = tt * BT;
 
-    // global -> LDS copy of the token tile: thread i moves 16 bytes of row i/8 (+32 per pass)
-    const int cp_row = tid >> 3, cp_col = (tid & 7) * 16;
+    // token DMA: instruction i (0..3) of this wavefront fills tile rows (4*wave + i)*8 .. +7
     const int8_t *xsrc[4];
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        int t = t0 + cp_row + 32 * p;
+    for (int i = 0; i < 4; ++i) {
+        const int row = (4 * wave + i) * 8 + (lane >> 3);
+        int t = t0 + row;
         t = t < g.tokens ? t : g.tokens - 1;
-        xsrc[p] = g.xq + (int64_t)t * K + cp_col;
+        xsrc[i] = g.xq + (int64_t)t * K + 16 * ((lane & 7) ^ ((row >> 1) & 7));
     }
-    // packed rows of the four row tiles
+    auto dma_tokens = [&](int kc) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(xsrc[i] + (int64_t)kc * KSTEP),
+                                             (__attribute__((address_space(3))) void *)(lds + (kc % STAGES) * STAGE_BYTES + (4 * wave + i) * 1024),
+                                             16, 0, 0);
+    };
+    // weight DMA: instruction i (0..3) of this wavefront fills block rows (4*wave + i)*16 .. +15
     const uint8_t *wsrc[4];
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
-        int o = o0 + 32 * a + r;
+    for (int i = 0; i < 4; ++i) {
+        const int row = (4 * wave + i) * 16 + (lane >> 2);
+        int o = o0 + row;
         o = o < g.d_out ? o : g.d_out - 1;
-        wsrc[a] = g.packed + (int64_t)o * nchunks * 32 + 8 * c;
+        wsrc[i] = g.packed + (int64_t)o * nchunks * 32 + 16 * ((lane & 3) ^ ((row >> 2) & 3));
+    }
+    const bool odd_tail = (nchunks & 1) != 0;   // the last pair then holds one chunk: its second half is never read
+    auto dma_weights = [&](int pair) {
+        const bool clip = odd_tail && pair == npairs - 1;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint8_t *src = wsrc[i] + (int64_t)pair * 64;
+            // granules 2, 3 of a clipped pair lie past the row: fetch granule 0/1 again instead (never read)
+            if (clip && (((lane & 3) ^ (((4 * wave + i) * 16 + (lane >> 2)) >> 2 & 3)) >= 2)) src -= 32;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                             (__attribute__((address_space(3))) void *)(wlds + (pair & 1) * WSLOT_BYTES + (4 * wave + i) * 1024),
+                                             16, 0, 0);
+        }
+    };
+    // LDS read offsets.  tokens: row * 128 + 16 * (chunk16 ^ swizzle); weights: row * 64 + 16 * (granule ^ swizzle) + 8c
+    int boff[2], bsw[2];
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+        const int row = wt * 64 + 32 * b + r;
+        boff[b] = row * KSTEP;
+        bsw[b] = (row >> 1) & 7;
+    }
+    int aoff[4], asw[4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        const int row = wo * 128 + 32 * a + r;
+        aoff[a] = row * 64 + 8 * c;
+        asw[a] = (row >> 2) & 3;
     }
 
     v16i acc[4][2];
@@ -119,43 +171,38 @@ __global__ void __launch_bounds__(256, 2) gemm_smfmac_kernel(GemmArgs g)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0;
 
-    uint4 xreg[4];
-    uint2 ireg[4], creg[4];
-#pragma unroll
-    for (int p = 0; p < 4; ++p) xreg[p] = *reinterpret_cast<const uint4 *>(xsrc[p]);
-#pragma unroll
-    for (int a = 0; a < 4; ++a) {
-        ireg[a] = *reinterpret_cast<const uint2 *>(wsrc[a]);
-        creg[a] = *reinterpret_cast<const uint2 *>(wsrc[a] + 16);
-    }
-#pragma unroll
-    for (int p = 0; p < 4; ++p)
-        *reinterpret_cast<uint4 *>(&lds[0][(cp_row + 32 * p) * LDS_ROW + cp_col]) = xreg[p];
-    __syncthreads();
+    // prologue: weight pairs 0 and 1, token tiles 0 and 1
+    dma_weights(0);
+    dma_tokens(0);
+    if (npairs > 1) dma_weights(1);
+    if (nchunks > 1) dma_tokens(1);
 
     for (int kc = 0; kc < nchunks; ++kc) {
-        const int cur = kc & 1;
+        // needed now: token tile kc and weight pair kc/2.  Still allowed in flight: what the previous
+        // iteration issued for later use (token tile kc+1: 4 loads; for odd kc also a weight pair: 4 more)
+        if (kc + 2 >= nchunks || kc == 0) SBN_WAIT_VMCNT(0);
+        else if (kc & 1) SBN_WAIT_VMCNT(8);
+        else SBN_WAIT_VMCNT(4);
+        __syncthreads();   // every wavefront's share has landed; stage (kc+2)%3 and, for even kc, weight slot (kc/2+1)%2 are free
+        if ((kc & 1) == 0 && kc >= 2 && kc / 2 + 1 < npairs) dma_weights(kc / 2 + 1);
+        if (kc + 2 < nchunks) dma_tokens(kc + 2);
+
+        const int8_t *bt = lds + (kc % STAGES) * STAGE_BYTES;
+        const int8_t *wt_ = wlds + ((kc >> 1) & 1) * WSLOT_BYTES;
+        const int h = kc & 1;   // chunk of the pair
         uint2 icur[4], ccur[4];
 #pragma unroll
-        for (int a = 0; a < 4; ++a) { icur[a] = ireg[a]; ccur[a] = creg[a]; }
-        if (kc + 1 < nchunks) {
-#pragma unroll
-            for (int p = 0; p < 4; ++p) xreg[p] = *reinterpret_cast<const uint4 *>(xsrc[p] + (kc + 1) * KSTEP);
-#pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                ireg[a] = *reinterpret_cast<const uint2 *>(wsrc[a] + (int64_t)(kc + 1) * 32);
-                creg[a] = *reinterpret_cast<const uint2 *>(wsrc[a] + (int64_t)(kc + 1) * 32 + 16);
-            }
+        for (int a = 0; a < 4; ++a) {
+            icur[a] = *reinterpret_cast<const uint2 *>(wt_ + aoff[a] + 16 * ((2 * h) ^ asw[a]));
+            ccur[a] = *reinterpret_cast<const uint2 *>(wt_ + aoff[a] + 16 * ((2 * h + 1) ^ asw[a]));
         }
-        const int8_t *bt = &lds[cur][0];
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             v8i bfrag[2];
 #pragma unroll
             for (int b = 0; b < 2; ++b) {
-                const int8_t *p = bt + (wt * 64 + 32 * b + r) * LDS_ROW + 32 * u + 16 * c;
-                const uint4 lo = *reinterpret_cast<const uint4 *>(p);
-                const uint4 hi = *reinterpret_cast<const uint4 *>(p + 64);
+                const uint4 lo = *reinterpret_cast<const uint4 *>(bt + boff[b] + 16 * ((2 * u + c) ^ bsw[b]));
+                const uint4 hi = *reinterpret_cast<const uint4 *>(bt + boff[b] + 16 * ((4 + 2 * u + c) ^ bsw[b]));
                 bfrag[b] = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
             }
 #pragma unroll
@@ -167,12 +214,6 @@ __global__ void __launch_bounds__(256, 2) gemm_smfmac_kernel(GemmArgs g)
                     acc[a][b] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(av, bfrag[b], acc[a][b], iv, 0, 0);
             }
         }
-        if (kc + 1 < nchunks) {
-#pragma unroll
-            for (int p = 0; p < 4; ++p)
-                *reinterpret_cast<uint4 *>(&lds[cur ^ 1][(cp_row + 32 * p) * LDS_ROW + cp_col]) = xreg[p];
-        }
-        __syncthreads();
     }
 
     const float gam = *g.gamma;
@@ -181,7 +222,7 @@ __global__ void __launch_bounds__(256, 2) gemm_smfmac_kernel(GemmArgs g)
         const int t = t0 + wt * 64 + 32 * b + r;
         const float scale = t < g.tokens ? __fdiv_rn(gam, g.sx[t]) : 0.0f;
 #pragma unroll
-        for (int a = 0; a < 4; ++a) store_tile(g, acc[a][b], o0 + 32 * a + 4 * c, t, scale);
+        for (int a = 0; a < 4; ++a) store_tile(g, acc[a][b], o0 + wo * 128 + 32 * a + 4 * c, t, scale);
     }
 }
 

@@ -25,16 +25,21 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
 // 16 two-bit ternary codes of one code word -> 16 int8 values in 4 registers.  The code of value v
-// sits at bits 8*(v%4) + 2*(v/4), so register q is a byte-wise table lookup of (word >> 2q):
-// code 0 -> 0x00, 1 -> 0x01, 3 -> 0xff.
+// sits at bits 8*(v%4) + 2*(v/4), so register q is a byte-wise table lookup (v_perm_b32) of the
+// bit pairs 2q, 2q+1 of every byte: code 0 -> 0x00, 1 -> 0x01, 3 -> 0xff.
+// v_perm_b32 selector bytes: 0..3 pick a byte of the second source, 4..7 of the first, 12 gives
+// 0x00 and 13 or more 0xff.  Even q: selector = code (0, 1, 3).  Odd q: selector = code << 2 | 1
+// (1, 5, 13), which needs no shift: byte 1 of the second source is 0x00, byte 1 of the first 0x01,
+// and 13 is the constant 0xff.  Nine VALU operations per 16 values.
 __device__ __forceinline__ v4i expand_codes(uint32_t cw)
 {
     const uint32_t lut = 0xff000100u;
+    const uint32_t t = cw >> 4;
     v4i a;
     a[0] = (int)__builtin_amdgcn_perm(lut, lut, cw & 0x03030303u);
-    a[1] = (int)__builtin_amdgcn_perm(lut, lut, (cw >> 2) & 0x03030303u);
-    a[2] = (int)__builtin_amdgcn_perm(lut, lut, (cw >> 4) & 0x03030303u);
-    a[3] = (int)__builtin_amdgcn_perm(lut, lut, (cw >> 6) & 0x03030303u);
+    a[1] = (int)__builtin_amdgcn_perm(0x00000100u, 0u, (cw & 0x0c0c0c0cu) | 0x01010101u);
+    a[2] = (int)__builtin_amdgcn_perm(lut, lut, t & 0x03030303u);
+    a[3] = (int)__builtin_amdgcn_perm(0x00000100u, 0u, (t & 0x0c0c0c0cu) | 0x01010101u);
     return a;
 }
 
