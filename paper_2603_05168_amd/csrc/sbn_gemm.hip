@@ -90,84 +90,103 @@ __device__ __forceinline__ void store_tile(const GemmArgs &g, const v16i &acc, i
 // of its row's chunk (two 8-byte LDS reads per row tile); sub-step u = 0, 1 uses word 2c + u, i.e.
 // the lane supplies weights [64c + 32u, +32) of the chunk.
 constexpr int STAGES = 3;
-constexpr int STAGE_BYTES = BT * KSTEP;   // 16 KB
 constexpr int WSLOT_BYTES = BO * 64;      // 16 KB: two chunks of every row of the block
 
 // wait until at most n vector-memory operations of this wavefront are outstanding (gfx9 encoding:
 // vmcnt in bits [3:0] and [15:14]; expcnt and lgkmcnt fields left at "no wait")
 #define SBN_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xf) | (((n) >> 4) << 14) | 0x0f70)
 
-__global__ void __launch_bounds__(256, 2) gemm_smfmac_kernel(GemmArgs g)
+// NB = token tiles of 32 per wavefront: 2 (block of 128 tokens, two blocks per multiprocessor) or
+// 4 (block of 256 tokens, 256 accumulator registers, one wavefront per SIMD: the code expansion is
+// then shared by four MFMAs instead of two).
+template <int NB>
+__global__ void __launch_bounds__(256, NB == 2 ? 2 : 1) gemm_smfmac_kernel(GemmArgs g)
 {
+    constexpr int BTK = 64 * NB;                 // tokens per block
+    constexpr int STAGE_BYTES = BTK * KSTEP;     // 16 or 32 KB
+    constexpr int NDT = BTK / 32;                // token DMA instructions per wavefront and stage
     __shared__ __attribute__((aligned(1024))) int8_t lds[STAGES * STAGE_BYTES + 2 * WSLOT_BYTES];
     int8_t *const wlds = lds + STAGES * STAGE_BYTES;
     int to, tt;
     tile_of_block(g, to, tt);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wo = wave & 1, wt = wave >> 1;
     const int r = lane & 31, c = lane >> 5;
     const int K = g.d_in, nchunks = K / KSTEP, npairs = (nchunks + 1) / 2;
-    const int o0 = to * BO, t0 = tt * BT;
+    const int o0 = to * BO, t0 = tt * BTK;
 
-    // token DMA: instruction i (0..3) of this wavefront fills tile rows (4*wave + i)*8 .. +7
-    const int8_t *xsrc[4];
+    // DMA sources as uniform base + 32-bit lane offset, so the per-iteration advance is scalar arithmetic.
+    // tokens: instruction i (0..NDT-1) of this wavefront fills tile rows (NDT*wave + i)*8 .. +7
+    const int8_t *const xbase = g.xq + (int64_t)t0 * K;
+    uint32_t xoff[NDT];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = (4 * wave + i) * 8 + (lane >> 3);
-        int t = t0 + row;
-        t = t < g.tokens ? t : g.tokens - 1;
-        xsrc[i] = g.xq + (int64_t)t * K + 16 * ((lane & 7) ^ ((row >> 1) & 7));
+    for (int i = 0; i < NDT; ++i) {
+        const int row = (NDT * wave + i) * 8 + (lane >> 3);
+        const int t = t0 + row < g.tokens ? row : g.tokens - 1 - t0;
+        xoff[i] = (uint32_t)t * (uint32_t)K + 16u * ((lane & 7) ^ ((row >> 1) & 7));
     }
     auto dma_tokens = [&](int kc) {
+        const int8_t *src = xbase + (int64_t)kc * KSTEP;
+        int8_t *dst = lds + (kc % STAGES) * STAGE_BYTES + wave * (NDT * 1024);
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(xsrc[i] + (int64_t)kc * KSTEP),
-                                             (__attribute__((address_space(3))) void *)(lds + (kc % STAGES) * STAGE_BYTES + (4 * wave + i) * 1024),
-                                             16, 0, 0);
+        for (int i = 0; i < NDT; ++i)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + xoff[i]),
+                                             (__attribute__((address_space(3))) void *)(dst + i * 1024), 16, 0, 0);
     };
-    // weight DMA: instruction i (0..3) of this wavefront fills block rows (4*wave + i)*16 .. +15
-    const uint8_t *wsrc[4];
+    // weights: instruction i (0..3) of this wavefront fills block rows (4*wave + i)*16 .. +15
+    const uint8_t *const wbase = g.packed + (int64_t)o0 * nchunks * 32;
+    uint32_t woff[4];
+    bool wclip[4];
+    const bool odd_tail = (nchunks & 1) != 0;   // the last pair then holds one chunk: its second half is never read
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int row = (4 * wave + i) * 16 + (lane >> 2);
-        int o = o0 + row;
-        o = o < g.d_out ? o : g.d_out - 1;
-        wsrc[i] = g.packed + (int64_t)o * nchunks * 32 + 16 * ((lane & 3) ^ ((row >> 2) & 3));
+        const int o = o0 + row < g.d_out ? row : g.d_out - 1 - o0;
+        const int gran = (lane & 3) ^ ((row >> 2) & 3);
+        woff[i] = (uint32_t)o * (uint32_t)(nchunks * 32) + 16u * gran;
+        wclip[i] = odd_tail && gran >= 2;
     }
-    const bool odd_tail = (nchunks & 1) != 0;   // the last pair then holds one chunk: its second half is never read
     auto dma_weights = [&](int pair) {
-        const bool clip = odd_tail && pair == npairs - 1;
+        const uint8_t *src = wbase + (int64_t)pair * 64;
+        int8_t *dst = wlds + (pair & 1) * WSLOT_BYTES + wave * 4096;
+        const bool last = pair == npairs - 1;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const uint8_t *src = wsrc[i] + (int64_t)pair * 64;
             // granules 2, 3 of a clipped pair lie past the row: fetch granule 0/1 again instead (never read)
-            if (clip && (((lane & 3) ^ (((4 * wave + i) * 16 + (lane >> 2)) >> 2 & 3)) >= 2)) src -= 32;
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                             (__attribute__((address_space(3))) void *)(wlds + (pair & 1) * WSLOT_BYTES + (4 * wave + i) * 1024),
-                                             16, 0, 0);
+            const uint32_t off = (last && wclip[i]) ? woff[i] - 32u : woff[i];
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + off),
+                                             (__attribute__((address_space(3))) void *)(dst + i * 1024), 16, 0, 0);
         }
     };
-    // LDS read offsets.  tokens: row * 128 + 16 * (chunk16 ^ swizzle); weights: row * 64 + 16 * (granule ^ swizzle) + 8c
-    int boff[2], bsw[2];
+    // LDS read offsets, swizzles folded in.  tokens: row * 128 + 16 * (chunk16 ^ ((row >> 1) & 7));
+    // weights: row * 64 + 16 * (granule ^ ((row >> 2) & 3)) + 8c
+    int b_lo[2][NB], b_hi[2][NB];   // [sub-step][token tile]
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
-        const int row = wt * 64 + 32 * b + r;
-        boff[b] = row * KSTEP;
-        bsw[b] = (row >> 1) & 7;
+    for (int b = 0; b < NB; ++b) {
+        const int row = wt * 32 * NB + 32 * b + r, sw = (row >> 1) & 7;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            b_lo[u][b] = row * KSTEP + 16 * ((2 * u + c) ^ sw);
+            b_hi[u][b] = row * KSTEP + 16 * ((4 + 2 * u + c) ^ sw);
+        }
     }
-    int aoff[4], asw[4];
+    int a_idx[2][4], a_code[2][4];   // [chunk of the pair][row tile]
 #pragma unroll
     for (int a = 0; a < 4; ++a) {
-        const int row = wo * 128 + 32 * a + r;
-        aoff[a] = row * 64 + 8 * c;
-        asw[a] = (row >> 2) & 3;
+        const int row = wo * 128 + 32 * a + r, sw = (row >> 2) & 3;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            a_idx[h][a] = row * 64 + 8 * c + 16 * ((2 * h) ^ sw);
+            a_code[h][a] = row * 64 + 8 * c + 16 * ((2 * h + 1) ^ sw);
+        }
     }
 
-    v16i acc[4][2];
+    v16i acc[4][NB];
 #pragma unroll
     for (int a = 0; a < 4; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < NB; ++b)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0;
 
@@ -177,49 +196,70 @@ __global__ void __launch_bounds__(256, 2) gemm_smfmac_kernel(GemmArgs g)
     if (npairs > 1) dma_weights(1);
     if (nchunks > 1) dma_tokens(1);
 
-    for (int kc = 0; kc < nchunks; ++kc) {
+    auto iteration = [&](int kc, const int h) {
         // needed now: token tile kc and weight pair kc/2.  Still allowed in flight: what the previous
-        // iteration issued for later use (token tile kc+1: 4 loads; for odd kc also a weight pair: 4 more)
+        // iteration issued for later use (token tile kc+1: NDT loads; for odd kc also a weight pair: 4 more)
         if (kc + 2 >= nchunks || kc == 0) SBN_WAIT_VMCNT(0);
-        else if (kc & 1) SBN_WAIT_VMCNT(8);
-        else SBN_WAIT_VMCNT(4);
+        else if (h) SBN_WAIT_VMCNT(NDT + 4);
+        else SBN_WAIT_VMCNT(NDT);
         __syncthreads();   // every wavefront's share has landed; stage (kc+2)%3 and, for even kc, weight slot (kc/2+1)%2 are free
-        if ((kc & 1) == 0 && kc >= 2 && kc / 2 + 1 < npairs) dma_weights(kc / 2 + 1);
+        if (h == 0 && kc >= 2 && kc / 2 + 1 < npairs) dma_weights(kc / 2 + 1);
         if (kc + 2 < nchunks) dma_tokens(kc + 2);
 
         const int8_t *bt = lds + (kc % STAGES) * STAGE_BYTES;
         const int8_t *wt_ = wlds + ((kc >> 1) & 1) * WSLOT_BYTES;
-        const int h = kc & 1;   // chunk of the pair
         uint2 icur[4], ccur[4];
+        v8i bfrag[2][NB];
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
-            icur[a] = *reinterpret_cast<const uint2 *>(wt_ + aoff[a] + 16 * ((2 * h) ^ asw[a]));
-            ccur[a] = *reinterpret_cast<const uint2 *>(wt_ + aoff[a] + 16 * ((2 * h + 1) ^ asw[a]));
+            icur[a] = *reinterpret_cast<const uint2 *>(wt_ + a_idx[h][a]);
+            ccur[a] = *reinterpret_cast<const uint2 *>(wt_ + a_code[h][a]);
         }
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            v8i bfrag[2];
+        for (int u = 0; u < 2; ++u)
 #pragma unroll
-            for (int b = 0; b < 2; ++b) {
-                const uint4 lo = *reinterpret_cast<const uint4 *>(bt + boff[b] + 16 * ((2 * u + c) ^ bsw[b]));
-                const uint4 hi = *reinterpret_cast<const uint4 *>(bt + boff[b] + 16 * ((4 + 2 * u + c) ^ bsw[b]));
-                bfrag[b] = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+            for (int b = 0; b < NB; ++b) {
+                bfrag[u][b].lo = *reinterpret_cast<const v4i *>(bt + b_lo[u][b]);
+                bfrag[u][b].hi = *reinterpret_cast<const v4i *>(bt + b_hi[u][b]);
+            }
+        // software pipeline over the 8 (sub-step, row tile) pairs: the code words of pair s+1 are expanded
+        // between the MFMAs of pair s, so the VALU work of one wavefront runs under its own (and the
+        // other resident wavefront's) matrix instructions instead of clustering in front of them
+        v4i av = expand_codes(ccur[0].x);
+#pragma unroll
+        for (int sidx = 0; sidx < 8; ++sidx) {
+            const int u = sidx >> 2, a = sidx & 3;
+            const int iv = (int)(u ? icur[a].y : icur[a].x);
+            v4i av_next = av;
+            if (sidx + 1 < 8) {
+                const int un = (sidx + 1) >> 2, an = (sidx + 1) & 3;
+                av_next = expand_codes(un ? ccur[an].y : ccur[an].x);
             }
 #pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                const v4i av = expand_codes(u ? ccur[a].y : ccur[a].x);
-                const int iv = (int)(u ? icur[a].y : icur[a].x);
+            for (int b = 0; b < NB; ++b)
+                acc[a][b] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(av, bfrag[u][b], acc[a][b], iv, 0, 0);
+            av = av_next;
+        }
 #pragma unroll
-                for (int b = 0; b < 2; ++b)
-                    acc[a][b] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(av, bfrag[b], acc[a][b], iv, 0, 0);
+        for (int sidx = 0; sidx < 7; ++sidx) {
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);              // one MFMA
+                __builtin_amdgcn_sched_group_barrier(0x002, NB == 2 ? 5 : 3, 0);  // a slice of the next expansion
             }
         }
+    };
+    int kc = 0;
+    for (; kc + 1 < nchunks; kc += 2) {
+        iteration(kc, 0);
+        iteration(kc + 1, 1);
     }
+    if (kc < nchunks) iteration(kc, 0);
 
     const float gam = *g.gamma;
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
-        const int t = t0 + wt * 64 + 32 * b + r;
+    for (int b = 0; b < NB; ++b) {
+        const int t = t0 + wt * 32 * NB + 32 * b + r;
         const float scale = t < g.tokens ? __fdiv_rn(gam, g.sx[t]) : 0.0f;
 #pragma unroll
         for (int a = 0; a < 4; ++a) store_tile(g, acc[a][b], o0 + wo * 128 + 32 * a + 4 * c, t, scale);
@@ -337,14 +377,14 @@ __global__ void __launch_bounds__(256, 2) gemm_dense_kernel(GemmArgs g)
     }
 }
 
-GemmArgs make_args(const LinearItem &it)
+GemmArgs make_args(const LinearItem &it, int block_tokens = BT)
 {
     GemmArgs g;
     g.xq = it.xq; g.sx = it.sx; g.packed = static_cast<const uint8_t *>(it.packed); g.w_dense = nullptr;
     g.gamma = it.gamma; g.bias = it.bias; g.Y = it.Y; g.acc_out = it.acc_out;
     g.tokens = (int)it.tokens; g.d_in = (int)it.d_in; g.d_out = (int)it.d_out;
     g.tiles_o = (int)ceil_div(it.d_out, BO);
-    g.tiles_t = (int)ceil_div(it.tokens, BT);
+    g.tiles_t = (int)ceil_div(it.tokens, block_tokens);
     return g;
 }
 
@@ -352,8 +392,11 @@ GemmArgs make_args(const LinearItem &it)
 
 sbn_status launch_gemm_smfmac(const LinearItem &it, hipStream_t stream)
 {
-    GemmArgs g = make_args(it);
-    hipLaunchKernelGGL(gemm_smfmac_kernel, dim3(g.tiles_o * g.tiles_t), dim3(256), 0, stream, g);
+    // two token tiles per wavefront (block of 128 tokens, two blocks per multiprocessor); the four-tile
+    // variant (one wavefront per SIMD) measured slower: the compiler's schedule leaves the matrix pipe
+    // idle behind LDS reads and code expansion when no second wavefront is resident
+    GemmArgs g = make_args(it, 128);
+    hipLaunchKernelGGL(gemm_smfmac_kernel<2>, dim3(g.tiles_o * g.tiles_t), dim3(256), 0, stream, g);
     return check_launch("gemm_smfmac_kernel");
 }
 

@@ -3,7 +3,6 @@
 // Appendix B listing (forward()).
 #include "sbn_internal.hpp"
 #include "sbn_mfma.hpp"
-#include <stdlib.h>
 
 namespace sbn {
 
@@ -467,17 +466,7 @@ sbn_status launch_gemv(int count, const LinearItem *items, hipStream_t stream)
                     raised = true;
                 }
             }
-            {
-                const char *v = getenv("SBN_GEMV_VARIANT");
-                const char *bp = getenv("SBN_GEMV_BPC");
-                int nb2 = bp ? device_cus() * atoi(bp) : nblocks;
-                int var = v ? atoi(v) : 0;
-                if (var == 1) hipLaunchKernelGGL((gemv_stream_kernel<2, 6>), dim3(nb2), dim3(256), (size_t)lds_need, stream, tab);
-                else if (var == 2) hipLaunchKernelGGL((gemv_stream_kernel<2, 8>), dim3(nb2), dim3(256), (size_t)lds_need, stream, tab);
-                else if (var == 3) hipLaunchKernelGGL((gemv_stream_kernel<1, 8>), dim3(nb2), dim3(256), (size_t)lds_need, stream, tab);
-                else if (var == 4) hipLaunchKernelGGL((gemv_stream_kernel<4, 3>), dim3(nb2), dim3(256), (size_t)lds_need, stream, tab);
-                else hipLaunchKernelGGL((gemv_stream_kernel<RT, 4>), dim3(nb2), dim3(256), (size_t)lds_need, stream, tab);
-            }
+            hipLaunchKernelGGL((gemv_stream_kernel<RT, 4>), dim3(nblocks), dim3(256), (size_t)lds_need, stream, tab);
             sbn_status st = check_launch("gemv_stream_kernel");
             if (st != SBN_OK) return st;
             first += n;
