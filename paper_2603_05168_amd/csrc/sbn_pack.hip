@@ -21,11 +21,15 @@ struct PackTable {
     int count;
 };
 
+// problem a block belongs to: largest i with prefix[i] <= block (binary search, scalar loads)
 __device__ __forceinline__ int find_item(const int *prefix, int count, int block)
 {
-    int i = 0;
-    while (i + 1 < count && block >= prefix[i + 1]) ++i;
-    return i;
+    int lo = 0, hi = count;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (block >= prefix[mid]) lo = mid; else hi = mid;
+    }
+    return lo;
 }
 
 // raw bits of one latent weight; magnitude compare happens on the integer pattern, which orders
@@ -273,6 +277,155 @@ __global__ void __launch_bounds__(256) pack_kernel(PackTable tab, const float *t
     }
 }
 
+// ---- fast pack kernels: bf16, rows contiguous, d_in % 128 == 0, patterns 2:4, 1:4, 2:8 ----------------
+// A lane owns 8 consecutive weights (one 16-byte load).  Selection runs on integer keys
+// (magnitude << 3 | 7 - position): unique within a group, and the larger key is the larger magnitude or,
+// among equals, the lower position, so max/min networks give the top-N with the tie rule built in.
+// The words of a chunk are OR-reduced across lanes with DPP (a DPP row = 16 lanes = one chunk), the
+// group leaders drop them into LDS, and the block stores its chunks with 16 bytes per thread.
+template <int CTRL> __device__ __forceinline__ uint32_t dpp_or_t(uint32_t x)
+{
+    return x | (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xf, 0xf, true);
+}
+// OR over aligned groups of 4, 8 or 16 lanes; every lane of the group ends with the result
+template <int LANES> __device__ __forceinline__ uint32_t group_or(uint32_t x)
+{
+    x = dpp_or_t<0xB1>(x);                              // quad_perm [1,0,3,2]
+    x = dpp_or_t<0x4E>(x);                              // quad_perm [2,3,0,1]
+    if constexpr (LANES >= 8) x = dpp_or_t<0x141>(x);   // row_half_mirror: quad 0 <-> 1, 2 <-> 3
+    if constexpr (LANES >= 16) x = dpp_or_t<0x140>(x);  // row_mirror: half 0 <-> 1
+    return x;
+}
+
+__device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
+__device__ __forceinline__ uint32_t umin(uint32_t a, uint32_t b) { return a < b ? a : b; }
+
+// ternary code of the element behind a key: nonzero iff magnitude >= threshold, sign from the raw bits
+__device__ __forceinline__ uint32_t code_of(uint32_t key, uint32_t th_key, uint32_t signs, uint32_t pos)
+{
+    const uint32_t nz = key >= th_key;
+    const uint32_t sg = (signs >> pos) & 1u;
+    return nz ? (1u | (sg << 1)) : 0u;
+}
+
+struct Top2 { uint32_t first, second; };
+// largest and second largest of four unique keys
+__device__ __forceinline__ Top2 top2_of4(uint32_t k0, uint32_t k1, uint32_t k2, uint32_t k3)
+{
+    const uint32_t h01 = umax(k0, k1), l01 = umin(k0, k1), h23 = umax(k2, k3), l23 = umin(k2, k3);
+    Top2 t;
+    t.first = umax(h01, h23);
+    t.second = umax(umin(h01, h23), umax(l01, l23));
+    return t;
+}
+
+template <int N, int M>
+__global__ void __launch_bounds__(256) pack_fast_kernel(PackTable tab, const float *theta)
+{
+    constexpr int U = 8;                                         // block = U x 16 chunks = 16384 weights
+    constexpr int CBW = (M == 4 && N == 2) ? 8 : (M == 4 ? 4 : 5);   // dwords per chunk: 32, 16, 20 bytes
+    __shared__ __attribute__((aligned(16))) uint32_t lds[U * 16 * CBW];
+    const int lo = find_item(tab.pack_block0, tab.count, blockIdx.x);
+    const PackItem &it = tab.it[lo];
+    const int64_t lb = (int)blockIdx.x - tab.pack_block0[lo];
+    const int64_t total_chunks = it.d_out * (it.d_in / CHUNK);
+    const uint16_t *W = static_cast<const uint16_t *>(it.W);
+    const int tid = threadIdx.x, ql = tid >> 4, l16 = tid & 15;
+    const uint32_t th_key = ((__float_as_uint(theta[lo]) + 0xffffu) >> 16) << 3;   // bf16 threshold pattern, key scale
+
+    uint4 v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t q = (lb * U + u) * 16 + ql;
+        v[u] = q < total_chunks ? *reinterpret_cast<const uint4 *>(W + q * CHUNK + l16 * 8) : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint32_t d[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+        uint32_t key[8], signs = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t raw = (j & 1) ? (d[j >> 1] >> 16) : (d[j >> 1] & 0xffffu);
+            key[j] = ((raw & 0x7fffu) << 3) | (uint32_t)(7 - (j % M));
+            signs |= (raw >> 15) << j;
+        }
+        uint32_t *out = lds + (u * 16 + ql) * CBW;
+        if constexpr (N == 2 && M == 4) {
+            uint32_t idxb = 0, codeb = 0;
+#pragma unroll
+            for (int g = 0; g < 2; ++g) {
+                const Top2 t = top2_of4(key[4 * g], key[4 * g + 1], key[4 * g + 2], key[4 * g + 3]);
+                const uint32_t p1 = 7u - (t.first & 7u), p2 = 7u - (t.second & 7u);
+                const bool first_lo = p1 < p2;
+                const uint32_t plo = first_lo ? p1 : p2, phi = first_lo ? p2 : p1;
+                const uint32_t klo = first_lo ? t.first : t.second, khi = first_lo ? t.second : t.first;
+                idxb |= (plo | (phi << 2)) << (4 * g);
+                codeb |= code_of(klo, th_key, signs >> (4 * g), plo) << (16 * g);
+                codeb |= code_of(khi, th_key, signs >> (4 * g), phi) << (16 * g + 8);
+            }
+            const int L = l16 & 3;
+            const uint32_t idxw = group_or<4>(idxb << (8 * L));
+            const uint32_t codew = group_or<4>(codeb << (2 * L));
+            if (L == 0) {
+                out[l16 >> 2] = idxw;
+                out[4 + (l16 >> 2)] = codew;
+            }
+        } else if constexpr (N == 1 && M == 4) {
+            uint32_t idxb = 0, codeb = 0;
+#pragma unroll
+            for (int g = 0; g < 2; ++g) {
+                const uint32_t top = umax(umax(key[4 * g], key[4 * g + 1]), umax(key[4 * g + 2], key[4 * g + 3]));
+                const uint32_t pos = 7u - (top & 7u);
+                idxb |= pos << (2 * g);
+                codeb |= code_of(top, th_key, signs >> (4 * g), pos) << (8 * g);
+            }
+            const int L8 = l16 & 7;
+            const uint32_t idxw = group_or<8>(idxb << (4 * L8));
+            const uint32_t codew = group_or<8>(codeb << (16 * (L8 & 1) + 2 * (L8 >> 1)));
+            if (L8 == 0) {
+                out[l16 >> 3] = idxw;
+                out[2 + (l16 >> 3)] = codew;
+            }
+        } else {   // 2:8
+            const Top2 ta = top2_of4(key[0], key[1], key[2], key[3]);
+            const Top2 tb = top2_of4(key[4], key[5], key[6], key[7]);
+            // keys of the second half carry positions 4..7 in their low bits (7 - j with j % 8)
+            const uint32_t first = umax(ta.first, tb.first);
+            const uint32_t second = umax(umin(ta.first, tb.first), umax(ta.second, tb.second));
+            const uint32_t p1 = 7u - (first & 7u), p2 = 7u - (second & 7u);
+            const bool first_lo = p1 < p2;
+            const uint32_t plo = first_lo ? p1 : p2, phi = first_lo ? p2 : p1;
+            const uint32_t klo = first_lo ? first : second, khi = first_lo ? second : first;
+            const uint32_t codeb = code_of(klo, th_key, signs, plo) | (code_of(khi, th_key, signs, phi) << 8);
+            const int L8 = l16 & 7;
+            const uint32_t codew = group_or<8>(codeb << (16 * (L8 & 1) + 2 * (L8 >> 1)));
+            // two 3-bit positions at bit 6 * l16 of the 96-bit index field
+            const uint32_t off = 6u * (uint32_t)l16, w0 = off >> 5;
+            const uint64_t bits = (uint64_t)(plo | (phi << 3)) << (off & 31u);
+            const uint32_t blo = (uint32_t)bits, bhi = (uint32_t)(bits >> 32);
+            const uint32_t i0 = group_or<16>(w0 == 0 ? blo : 0u);
+            const uint32_t i1 = group_or<16>((w0 == 1 ? blo : 0u) | (w0 == 0 ? bhi : 0u));
+            const uint32_t i2 = group_or<16>((w0 == 2 ? blo : 0u) | (w0 == 1 ? bhi : 0u));
+            if (l16 == 0) { out[0] = i0; out[1] = i1; out[2] = i2; }
+            if (L8 == 0) out[3 + (l16 >> 3)] = codew;
+        }
+    }
+    __syncthreads();
+    // the block's chunks are contiguous in the packed buffer
+    const int64_t chunk0 = lb * U * 16;
+    int64_t nch = total_chunks - chunk0;
+    nch = nch > U * 16 ? U * 16 : nch;
+    const int ndw = (int)nch * CBW;
+    uint32_t *dst = reinterpret_cast<uint32_t *>(it.packed) + chunk0 * CBW;
+    for (int w = tid * 4; w < ndw; w += 1024) {
+        if (w + 4 <= ndw) {
+            *reinterpret_cast<uint4 *>(dst + w) = *reinterpret_cast<const uint4 *>(lds + w);
+        } else {
+            for (int k = w; k < ndw; ++k) dst[k] = lds[k];
+        }
+    }
+}
+
 // ---- test hook: packed -> dense W_eff and mask --------------------------------------------------
 __device__ __forceinline__ uint32_t get_bits(const uint8_t *field, int pos, int nbits)
 {
@@ -352,12 +505,17 @@ sbn_status launch_pack(int count, const PackItem *items, sbn_dtype wdt, const Pa
         PackTable tab;
         tab.count = n;
         int vec_ok = 1;
+        bool flat_ok = true;            // every matrix: contiguous rows of whole chunks, 16-byte aligned
+        int fb[PACK_MAX_ITEMS + 1];     // block prefix of the fast pack kernel (128 chunks per block)
         int sb = 0, pb = 0;
+        fb[0] = 0;
         for (int i = 0; i < n; ++i) {
             const PackItem &it = items[first + i];
             tab.it[i] = it;
             tab.sum_block0[i] = sb;
             tab.pack_block0[i] = pb;
+            if (it.ld != it.d_in || it.d_in % CHUNK != 0 || !aligned(it.W, 16)) flat_ok = false;
+            fb[i + 1] = fb[i] + (int)ceil_div(it.d_out * ceil_div(it.d_in, CHUNK), 128);
             sb += (int)ceil_div(it.d_out * it.d_in, PACK_SUM_ELEMS);
             pb += (int)ceil_div(it.d_out * ceil_div(it.d_in, CHUNK), 16);
             if (!aligned(it.W, 16) || (it.ld * esz) % 16 != 0 || it.d_in % 8 != 0) vec_ok = 0;
@@ -375,8 +533,18 @@ sbn_status launch_pack(int count, const PackItem *items, sbn_dtype wdt, const Pa
         hipLaunchKernelGGL(absmean_finalize_kernel, dim3(n), dim3(256), 0, stream, tab, part, th);
         st = check_launch("absmean_finalize_kernel");
         if (st != SBN_OK) return st;
-        st = wdt == SBN_BF16 ? launch_pack_kernel<uint16_t>(tab, pb, th, vec_ok, pat, stream)
-                             : launch_pack_kernel<float>(tab, pb, th, vec_ok, pat, stream);
+        const bool fast_pattern = (pat.M == 4 && (pat.N == 1 || pat.N == 2)) || (pat.M == 8 && pat.N == 2);
+        if (wdt == SBN_BF16 && fast_pattern && flat_ok) {
+            for (int i = 0; i < n; ++i) tab.pack_block0[i] = fb[i];
+            tab.pack_block0[n] = fb[n];
+            if (pat.M == 4 && pat.N == 2) hipLaunchKernelGGL((pack_fast_kernel<2, 4>), dim3(fb[n]), dim3(256), 0, stream, tab, th);
+            else if (pat.M == 4) hipLaunchKernelGGL((pack_fast_kernel<1, 4>), dim3(fb[n]), dim3(256), 0, stream, tab, th);
+            else hipLaunchKernelGGL((pack_fast_kernel<2, 8>), dim3(fb[n]), dim3(256), 0, stream, tab, th);
+            st = check_launch("pack_fast_kernel");
+        } else {
+            st = wdt == SBN_BF16 ? launch_pack_kernel<uint16_t>(tab, pb, th, vec_ok, pat, stream)
+                                 : launch_pack_kernel<float>(tab, pb, th, vec_ok, pat, stream);
+        }
         if (st != SBN_OK) return st;
         sum_base += sb;
     }
