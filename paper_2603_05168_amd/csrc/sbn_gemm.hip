@@ -96,15 +96,20 @@ constexpr int WSLOT_BYTES = BO * 64;      // 16 KB: two chunks of every row of t
 // vmcnt in bits [3:0] and [15:14]; expcnt and lgkmcnt fields left at "no wait")
 #define SBN_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xf) | (((n) >> 4) << 14) | 0x0f70)
 
-// NB = token tiles of 32 per wavefront: 2 (block of 128 tokens, two blocks per multiprocessor) or
-// 4 (block of 256 tokens, 256 accumulator registers, one wavefront per SIMD: the code expansion is
-// then shared by four MFMAs instead of two).
-template <int NB>
-__global__ void __launch_bounds__(256, NB == 2 ? 2 : 1) gemm_smfmac_kernel(GemmArgs g)
+// NB = token tiles of 32 per wavefront, WT = wavefronts along the tokens (two along the rows always).
+//   <2, 2>: 4 wavefronts, 128 accumulator registers each, two wavefronts per SIMD;
+//   <4, 1>: 2 wavefronts, 256 accumulator registers each, one wavefront per SIMD: one code expansion
+//           feeds four MFMAs instead of two.  VALU work does not overlap matrix instructions on this
+//           part (measured: their times add), so the expansion cost per MFMA decides the utilisation.
+// Both cover a block of 256 rows x 128 tokens and fit two blocks per multiprocessor (80 KB LDS).
+template <int NB, int WT>
+__global__ void __launch_bounds__(128 * WT, NB == 2 ? 2 : 1) gemm_smfmac_kernel(GemmArgs g)
 {
-    constexpr int BTK = 64 * NB;                 // tokens per block
-    constexpr int STAGE_BYTES = BTK * KSTEP;     // 16 or 32 KB
-    constexpr int NDT = BTK / 32;                // token DMA instructions per wavefront and stage
+    constexpr int NWAVES = 2 * WT;
+    constexpr int BTK = 32 * NB * WT;            // tokens per block
+    constexpr int STAGE_BYTES = BTK * KSTEP;     // 16 KB
+    constexpr int NDT = BTK / 8 / NWAVES;        // token DMA instructions per wavefront and stage
+    constexpr int NDW = 16 / NWAVES;             // weight DMA instructions per wavefront and pair
     __shared__ __attribute__((aligned(1024))) int8_t lds[STAGES * STAGE_BYTES + 2 * WSLOT_BYTES];
     int8_t *const wlds = lds + STAGES * STAGE_BYTES;
     int to, tt;
@@ -134,14 +139,14 @@ __global__ void __launch_bounds__(256, NB == 2 ? 2 : 1) gemm_smfmac_kernel(GemmA
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + xoff[i]),
                                              (__attribute__((address_space(3))) void *)(dst + i * 1024), 16, 0, 0);
     };
-    // weights: instruction i (0..3) of this wavefront fills block rows (4*wave + i)*16 .. +15
+    // weights: instruction i (0..NDW-1) of this wavefront fills block rows (NDW*wave + i)*16 .. +15
     const uint8_t *const wbase = g.packed + (int64_t)o0 * nchunks * 32;
-    uint32_t woff[4];
-    bool wclip[4];
+    uint32_t woff[NDW];
+    bool wclip[NDW];
     const bool odd_tail = (nchunks & 1) != 0;   // the last pair then holds one chunk: its second half is never read
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = (4 * wave + i) * 16 + (lane >> 2);
+    for (int i = 0; i < NDW; ++i) {
+        const int row = (NDW * wave + i) * 16 + (lane >> 2);
         const int o = o0 + row < g.d_out ? row : g.d_out - 1 - o0;
         const int gran = (lane & 3) ^ ((row >> 2) & 3);
         woff[i] = (uint32_t)o * (uint32_t)(nchunks * 32) + 16u * gran;
@@ -149,10 +154,10 @@ __global__ void __launch_bounds__(256, NB == 2 ? 2 : 1) gemm_smfmac_kernel(GemmA
     }
     auto dma_weights = [&](int pair) {
         const uint8_t *src = wbase + (int64_t)pair * 64;
-        int8_t *dst = wlds + (pair & 1) * WSLOT_BYTES + wave * 4096;
+        int8_t *dst = wlds + (pair & 1) * WSLOT_BYTES + wave * (NDW * 1024);
         const bool last = pair == npairs - 1;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < NDW; ++i) {
             // granules 2, 3 of a clipped pair lie past the row: fetch granule 0/1 again instead (never read)
             const uint32_t off = (last && wclip[i]) ? woff[i] - 32u : woff[i];
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + off),
@@ -198,9 +203,9 @@ __global__ void __launch_bounds__(256, NB == 2 ? 2 : 1) gemm_smfmac_kernel(GemmA
 
     auto iteration = [&](int kc, const int h) {
         // needed now: token tile kc and weight pair kc/2.  Still allowed in flight: what the previous
-        // iteration issued for later use (token tile kc+1: NDT loads; for odd kc also a weight pair: 4 more)
+        // iteration issued for later use (token tile kc+1: NDT loads; for odd kc also a weight pair: NDW more)
         if (kc + 2 >= nchunks || kc == 0) SBN_WAIT_VMCNT(0);
-        else if (h) SBN_WAIT_VMCNT(NDT + 4);
+        else if (h) SBN_WAIT_VMCNT(NDT + NDW);
         else SBN_WAIT_VMCNT(NDT);
         __syncthreads();   // every wavefront's share has landed; stage (kc+2)%3 and, for even kc, weight slot (kc/2+1)%2 are free
         if (h == 0 && kc >= 2 && kc / 2 + 1 < npairs) dma_weights(kc / 2 + 1);
@@ -222,31 +227,15 @@ __global__ void __launch_bounds__(256, NB == 2 ? 2 : 1) gemm_smfmac_kernel(GemmA
                 bfrag[u][b].lo = *reinterpret_cast<const v4i *>(bt + b_lo[u][b]);
                 bfrag[u][b].hi = *reinterpret_cast<const v4i *>(bt + b_hi[u][b]);
             }
-        // software pipeline over the 8 (sub-step, row tile) pairs: the code words of pair s+1 are expanded
-        // between the MFMAs of pair s, so the VALU work of one wavefront runs under its own (and the
-        // other resident wavefront's) matrix instructions instead of clustering in front of them
-        v4i av = expand_codes(ccur[0].x);
+        // the 8 (sub-step, row tile) pairs in turn: expand 16 codes, then NB MFMAs on them
 #pragma unroll
         for (int sidx = 0; sidx < 8; ++sidx) {
             const int u = sidx >> 2, a = sidx & 3;
             const int iv = (int)(u ? icur[a].y : icur[a].x);
-            v4i av_next = av;
-            if (sidx + 1 < 8) {
-                const int un = (sidx + 1) >> 2, an = (sidx + 1) & 3;
-                av_next = expand_codes(un ? ccur[an].y : ccur[an].x);
-            }
+            const v4i av = expand_codes(u ? ccur[a].y : ccur[a].x);
 #pragma unroll
             for (int b = 0; b < NB; ++b)
                 acc[a][b] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(av, bfrag[u][b], acc[a][b], iv, 0, 0);
-            av = av_next;
-        }
-#pragma unroll
-        for (int sidx = 0; sidx < 7; ++sidx) {
-#pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);              // one MFMA
-                __builtin_amdgcn_sched_group_barrier(0x002, NB == 2 ? 5 : 3, 0);  // a slice of the next expansion
-            }
         }
     };
     int kc = 0;
@@ -392,11 +381,11 @@ GemmArgs make_args(const LinearItem &it, int block_tokens = BT)
 
 sbn_status launch_gemm_smfmac(const LinearItem &it, hipStream_t stream)
 {
-    // two token tiles per wavefront (block of 128 tokens, two blocks per multiprocessor); the four-tile
-    // variant (one wavefront per SIMD) measured slower: the compiler's schedule leaves the matrix pipe
-    // idle behind LDS reads and code expansion when no second wavefront is resident
+    // <2, 2> is the measured best.  <4, 1> (one wavefront per SIMD, 256 accumulators) halves the
+    // expansion work per MFMA but ran 1.6x slower: with a single resident wavefront nothing hides the
+    // LDS, barrier and DMA waits of the compiler's schedule.
     GemmArgs g = make_args(it, 128);
-    hipLaunchKernelGGL(gemm_smfmac_kernel<2>, dim3(g.tiles_o * g.tiles_t), dim3(256), 0, stream, g);
+    hipLaunchKernelGGL((gemm_smfmac_kernel<2, 2>), dim3(g.tiles_o * g.tiles_t), dim3(256), 0, stream, g);
     return check_launch("gemm_smfmac_kernel");
 }
 
