@@ -249,146 +249,6 @@ __global__ void __launch_bounds__(256, 2) gemm_bf16_nt_kernel(GemmBf16Args g)
     }
 }
 
-// ---- the same product with both operands streamed through LDS by the LDS-DMA load -------------------
-// K % 32 == 0.  Stage = 32 k of the 256 P rows and 128 Q rows (64-byte rows, 24 KB), ring of 3 stages
-// (72 KB: two blocks per multiprocessor).  One global_load_lds_dwordx4 fills 16 rows; the 16-byte
-// granule a lane fetches is XOR-swizzled with (row >> 2) & 3 so that the fragment reads of 16
-// consecutive rows fall in distinct banks.  No staging registers, one barrier per iteration.
-constexpr int DK = 32;                       // k per stage
-constexpr int DSTAGE = (GB_N + GB_M) * DK * 2;   // bytes per stage
-constexpr int DSTAGES = 3;
-#define SBN_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xf) | (((n) >> 4) << 14) | 0x0f70)
-
-__global__ void __launch_bounds__(256, 2) gemm_bf16_nt_dma_kernel(GemmBf16Args g)
-{
-    __shared__ __attribute__((aligned(1024))) uint8_t lds[DSTAGES * DSTAGE];
-    const int nb = g.tiles_n * g.tiles_m;
-    int id = blockIdx.x;
-    if ((nb & 7) == 0) id = (id & 7) * (nb >> 3) + (id >> 3);
-    const int tn = id % g.tiles_n, tm = id / g.tiles_n;
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wn = wave & 1, wm = wave >> 1;
-    const int r = lane & 31, c = lane >> 5;
-    const int n0 = tn * GB_N, m0 = tm * GB_M;
-
-    // DMA roles: P rows (4*wave + i)*16 .. +15 for i = 0..3; Q rows (2*wave + i)*16 .. +15 for i = 0..1
-    const uint8_t *const pbase = reinterpret_cast<const uint8_t *>(g.P + (int64_t)n0 * g.ldp);
-    const uint8_t *const qbase = reinterpret_cast<const uint8_t *>(g.Q + (int64_t)m0 * g.ldq);
-    uint32_t poff[4], qoff[2];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = (4 * wave + i) * 16 + (lane >> 2);
-        const int n = n0 + row < g.N ? row : g.N - 1 - n0;
-        poff[i] = (uint32_t)n * (uint32_t)(g.ldp * 2) + 16u * ((lane & 3) ^ ((row >> 2) & 3));
-    }
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int row = (2 * wave + i) * 16 + (lane >> 2);
-        const int m = m0 + row < g.M ? row : g.M - 1 - m0;
-        qoff[i] = (uint32_t)m * (uint32_t)(g.ldq * 2) + 16u * ((lane & 3) ^ ((row >> 2) & 3));
-    }
-    auto dma = [&](int kt) {
-        uint8_t *dst = lds + (kt % DSTAGES) * DSTAGE;
-        const uint8_t *ps = pbase + (int64_t)kt * DK * 2, *qs = qbase + (int64_t)kt * DK * 2;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(ps + poff[i]),
-                                             (__attribute__((address_space(3))) void *)(dst + (4 * wave + i) * 1024), 16, 0, 0);
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(qs + qoff[i]),
-                                             (__attribute__((address_space(3))) void *)(dst + GB_N * DK * 2 + (2 * wave + i) * 1024), 16, 0, 0);
-    };
-    // fragment read offsets inside a stage: lane (r, c) supplies k = 16u + 8c + 0..7 = granule 2u + c
-    int pa[2][4], qa[2][2];
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-#pragma unroll
-        for (int a = 0; a < 4; ++a) {
-            const int row = wn * 128 + 32 * a + r;
-            pa[u][a] = row * 64 + 16 * ((2 * u + c) ^ ((row >> 2) & 3));
-        }
-#pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            const int row = wm * 64 + 32 * b + r;
-            qa[u][b] = GB_N * DK * 2 + row * 64 + 16 * ((2 * u + c) ^ ((row >> 2) & 3));
-        }
-    }
-
-    v16f acc[4][2];
-#pragma unroll
-    for (int a = 0; a < 4; ++a)
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
-
-    const int nk = g.K / DK;
-    dma(0);
-    if (nk > 1) dma(1);
-    for (int kt = 0; kt < nk; ++kt) {
-        if (kt + 1 < nk) SBN_WAIT_VMCNT(6); else SBN_WAIT_VMCNT(0);   // tile kt landed; tile kt+1 (6 loads) may be in flight
-        __syncthreads();
-        if (kt + 2 < nk) dma(kt + 2);
-        const uint8_t *st = lds + (kt % DSTAGES) * DSTAGE;
-        v8bf pf[2][4], qf[2][2];
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-#pragma unroll
-            for (int a = 0; a < 4; ++a) pf[u][a] = *reinterpret_cast<const v8bf *>(st + pa[u][a]);
-#pragma unroll
-            for (int b = 0; b < 2; ++b) qf[u][b] = *reinterpret_cast<const v8bf *>(st + qa[u][b]);
-        }
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-            for (int a = 0; a < 4; ++a)
-#pragma unroll
-                for (int b = 0; b < 2; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[u][a], qf[u][b], acc[a][b], 0, 0, 0);
-    }
-
-    const float alpha = g.alpha ? *g.alpha : 1.0f;
-#pragma unroll
-    for (int b = 0; b < 2; ++b) {
-        const int m = m0 + wm * 64 + 32 * b + r;
-        if (m >= g.M) continue;
-#pragma unroll
-        for (int a = 0; a < 4; ++a) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int n = n0 + wn * 128 + 32 * a + 8 * q + 4 * c;
-                uint16_t *dst = g.C + (int64_t)m * g.ldc + n;
-                float v[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) v[i] = acc[a][b][4 * q + i] * alpha;
-                if (n + 4 <= g.N && (g.ldc & 3) == 0) {
-                    if (g.accumulate) {
-                        const uint2 old = *reinterpret_cast<const uint2 *>(dst);
-                        v[0] += __uint_as_float(old.x << 16);
-                        v[1] += __uint_as_float(old.x & 0xffff0000u);
-                        v[2] += __uint_as_float(old.y << 16);
-                        v[3] += __uint_as_float(old.y & 0xffff0000u);
-                    }
-                    uint2 out;
-                    out.x = f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16);
-                    out.y = f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16);
-                    *reinterpret_cast<uint2 *>(dst) = out;
-                } else {
-                    for (int i = 0; i < 4; ++i) {
-                        if (n + i < g.N) {
-                            float x = v[i];
-                            if (g.accumulate) x += __uint_as_float((uint32_t)dst[i] << 16);
-                            dst[i] = (uint16_t)f32_to_bf16(x);
-                        }
-                    }
-                }
-            }
-        }
-    }
-}
-
 sbn_status launch_gemm_bf16(const uint16_t *P, int64_t ldp, int N, const uint16_t *Q, int64_t ldq, int M, int K,
                             uint16_t *C, int64_t ldc, const float *alpha, int accumulate, hipStream_t stream)
 {
@@ -397,27 +257,20 @@ sbn_status launch_gemm_bf16(const uint16_t *P, int64_t ldp, int N, const uint16_
     g.N = N; g.M = M; g.K = K; g.accumulate = accumulate;
     g.tiles_n = (int)ceil_div(N, GB_N);
     g.tiles_m = (int)ceil_div(M, GB_M);
-    const bool dma_ok = K % DK == 0 && ldp % 8 == 0 && ldq % 8 == 0 && aligned(P, 16) && aligned(Q, 16) &&
-                        (int64_t)GB_N * ldp * 2 < ((int64_t)1 << 31) && (int64_t)GB_M * ldq * 2 < ((int64_t)1 << 31);
-    if (dma_ok) {
-        hipLaunchKernelGGL(gemm_bf16_nt_dma_kernel, dim3(g.tiles_n * g.tiles_m), dim3(256), 0, stream, g);
-        return check_launch("gemm_bf16_nt_dma_kernel");
-    }
     hipLaunchKernelGGL(gemm_bf16_nt_kernel, dim3(g.tiles_n * g.tiles_m), dim3(256), 0, stream, g);
     return check_launch("gemm_bf16_nt_kernel");
 }
 
 inline int64_t pad8(int64_t x) { return (x + 7) / 8 * 8; }
-inline int64_t pad32(int64_t x) { return (x + 31) / 32 * 32; }
 
 }  // namespace
 
 size_t backward_workspace_bytes(int64_t tokens, int64_t d_out, int64_t d_in)
 {
-    // W_eff^T bf16 [d_in, pad8(d_out)] + int8 W_eff (generic patterns) + (dY/s_x)^T bf16 [d_out, pad32(tokens)]
-    // + xq^T bf16 [d_in, pad32(tokens)]
+    // W_eff^T bf16 [d_in, pad8(d_out)] + int8 W_eff (generic patterns) + (dY/s_x)^T bf16 [d_out, pad8(tokens)]
+    // + xq^T bf16 [d_in, pad8(tokens)]
     return align_up((size_t)d_in * pad8(d_out) * 2, 256) + align_up((size_t)d_out * d_in, 256) +
-           align_up((size_t)d_out * pad32(tokens) * 2, 256) + align_up((size_t)d_in * pad32(tokens) * 2, 256);
+           align_up((size_t)d_out * pad8(tokens) * 2, 256) + align_up((size_t)d_in * pad8(tokens) * 2, 256);
 }
 
 sbn_status launch_backward(const void *dY, int64_t tokens, int64_t d_in, int64_t d_out, const Pattern &pat,
@@ -431,7 +284,7 @@ sbn_status launch_backward(const void *dY, int64_t tokens, int64_t d_in, int64_t
     int8_t *w8 = reinterpret_cast<int8_t *>(ws);
     ws += align_up((size_t)d_out * d_in, 256);
     uint16_t *dyt = reinterpret_cast<uint16_t *>(ws);
-    ws += align_up((size_t)d_out * pad32(tokens) * 2, 256);
+    ws += align_up((size_t)d_out * pad8(tokens) * 2, 256);
     uint16_t *xt = reinterpret_cast<uint16_t *>(ws);
     const uint16_t *dy = static_cast<const uint16_t *>(dY);
     sbn_status st;
@@ -457,7 +310,7 @@ sbn_status launch_backward(const void *dY, int64_t tokens, int64_t d_in, int64_t
         if (st != SBN_OK) return st;
     }
     if (dW) {
-        const int64_t ldt = pad32(tokens);
+        const int64_t ldt = pad8(tokens);
         {
             dim3 grid((unsigned)ceil_div(d_out, 64), (unsigned)ceil_div(tokens, 64));
             hipLaunchKernelGGL(transpose_scale_dy_kernel, grid, dim3(256), 0, stream, dy, sx, tokens, d_out, dyt, ldt);
