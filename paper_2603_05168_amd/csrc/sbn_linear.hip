@@ -237,7 +237,7 @@ struct GemvStreamTable {
 };
 
 template <int RT, int DEPTH>
-__global__ void __launch_bounds__(256) gemv_stream_kernel(GemvStreamTable tab)
+__global__ void __launch_bounds__(256, 4) gemv_stream_kernel(GemvStreamTable tab)
 {
     extern __shared__ __attribute__((aligned(16))) int8_t xlds[];   // [tokens][d_in + 16]
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -246,6 +246,8 @@ __global__ void __launch_bounds__(256) gemv_stream_kernel(GemvStreamTable tab)
     const int r = lane & 15, c4 = lane >> 4;
     int item = 0;
     int u = b0;
+    const int8_t *staged_xq = nullptr;   // what the LDS copy currently holds (block-uniform)
+    int staged_tokens = 0, staged_k = 0;
     while (u < b1) {
         while (u >= tab.unit0[item + 1]) ++item;
         const GemvStreamItem &it = tab.it[item];
@@ -276,14 +278,20 @@ __global__ void __launch_bounds__(256) gemv_stream_kernel(GemvStreamTable tab)
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d)
             if (d < nsteps) issue(qi[d], qc[d]);
-
-        __syncthreads();   // the previous problem's activations are no longer read
-        for (int v = threadIdx.x; v < it.tokens * (K / 16); v += 256) {
-            const int t = v / (K / 16), k = (v % (K / 16)) * 16;
-            *reinterpret_cast<uint4 *>(&xlds[t * pitch + k]) = *reinterpret_cast<const uint4 *>(it.xq + (int64_t)t * K + k);
+        // Activations are staged only when they differ from what the block already holds (projections
+        // that share an input, Q/K/V or up/gate, come one after the other).
+        if (it.xq != staged_xq || it.tokens != staged_tokens || K != staged_k) {
+            __syncthreads();   // the previous problem's activations are no longer read
+            for (int v = threadIdx.x; v < it.tokens * (K / 16); v += 256) {
+                const int t = v / (K / 16), k = (v % (K / 16)) * 16;
+                *reinterpret_cast<uint4 *>(&xlds[t * pitch + k]) = *reinterpret_cast<const uint4 *>(it.xq + (int64_t)t * K + k);
+            }
+            staged_xq = it.xq;
+            staged_tokens = it.tokens;
+            staged_k = K;
+            __syncthreads();
         }
         const float scale = tok_ok ? __fdiv_rn(*it.gamma, it.sx[r]) : 0.0f;
-        __syncthreads();
 
         v4i acc[RT];
 #pragma unroll
