@@ -32,7 +32,7 @@ def oracle_pack(W: torch.Tensor, N: int, M: int):
     return oracle.pack(Weff, mask, N, M), gamma, Weff, mask
 
 
-def hip_linear(X: torch.Tensor, packed, gamma, d_out: int, N: int, M: int, path: int, bias=None):
+def hip_linear(X: torch.Tensor, packed, gamma, d_out: int, N: int, M: int, path: int, bias=None, want_acc=True):
     s = sbn()
     Xd = X.to(DEV)
     T, K = X.shape
@@ -42,7 +42,7 @@ def hip_linear(X: torch.Tensor, packed, gamma, d_out: int, N: int, M: int, path:
     sx = torch.zeros(T, dtype=torch.float32, device=DEV)
     ws = s.new_workspace(s.sbn_workspace_bytes(s.SBN_OP_LINEAR, T, d_out, K, N, M))
     s.sbn_sparse_ternary_linear(Xd, packed, gamma, Y, N, M, ws, bias=None if bias is None else bias.to(DEV),
-                                xq_out=xq, sx_out=sx, acc_out=acc, path=path)
+                                xq_out=xq, sx_out=sx, acc_out=acc if want_acc else None, path=path)
     torch.cuda.synchronize()
     return Y.cpu().numpy(), acc.cpu().numpy(), xq.cpu().numpy(), sx.cpu().numpy()
 

@@ -169,3 +169,22 @@ def test_act_quant_entry_all_kernel_variants(tokens, d_in):
     torch.cuda.synchronize()
     r_xq, r_sx = oracle.act_quant(X.float().numpy())
     assert np.array_equal(xq.cpu().numpy(), r_xq) and np.array_equal(sx.cpu().numpy(), r_sx)
+
+
+@pytest.mark.parametrize("tokens,shape", [(200, (512, 384)), (4096, (2560, 2560)), (130, (768, 128))])
+def test_gemm_sparse_without_accumulator_output(tokens, shape):
+    # without acc_out the sparse GEMM takes its LDS-transposed full-row epilogue: same Y, bias included
+    s = sbn()
+    W = sbn_synth.latent_weight(shape[0], shape[1], 860 + shape[0])
+    X = sbn_synth.activations(tokens, shape[1], 861 + tokens)
+    bias = torch.randn(shape[0], generator=torch.Generator().manual_seed(9))
+    packed, gamma = hip_pack(W, 2, 4)
+    Y_ref, *_ = hip_linear(X, packed, gamma, shape[0], 2, 4, s.SBN_PATH_SMFMAC, bias)
+    Y, *_ = hip_linear(X, packed, gamma, shape[0], 2, 4, s.SBN_PATH_SMFMAC, bias, want_acc=False)
+    assert np.array_equal(Y, Y_ref)
+    _, g, Weff, _ = oracle_pack(W, 2, 4)
+    rows = np.unique(np.random.default_rng(1).choice(tokens, size=min(tokens, 48), replace=False))
+    # with a bias the sum can cancel, so the bound is taken relative to the two terms, not to their sum
+    y_nb, *_ = oracle.sparse_ternary_linear(X.float().numpy(), Weff, g)
+    ref = y_nb[rows] + bias.numpy().astype(np.float64)
+    assert (np.abs(Y[rows] - ref) <= 1e-3 * (np.abs(y_nb[rows]) + np.abs(bias.numpy()))).all()
