@@ -30,15 +30,26 @@ struct GemmArgs {
     int tiles_o, tiles_t;
 };
 
-// blocks are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of tiles (row tile
-// fastest) so the blocks sharing an L2 reuse the same token tile
+// Blocks are dealt round-robin to the 8 XCDs, each with its own 4 MB L2.  XCD x takes the token
+// tiles [x, x+1) * tiles_t/8 and walks them in groups of four: inside a group the token tile is the
+// fastest index, then the row tile.  The 64 blocks an XCD runs at a time then share four token tiles
+// (1.3 MB, resident for the whole group) while the packed weights stream through its L2 once per
+// group, instead of every row tile being re-fetched for every token tile (measured: L2 miss traffic
+// 15x the unique input bytes with the row tile fastest).
 __device__ __forceinline__ void tile_of_block(const GemmArgs &g, int &to, int &tt)
 {
-    const int nb = g.tiles_o * g.tiles_t;
-    int id = blockIdx.x;
-    if ((nb & 7) == 0) id = (id & 7) * (nb >> 3) + (id >> 3);
-    to = id % g.tiles_o;
-    tt = id / g.tiles_o;
+    const int id = blockIdx.x;
+    const int tpx = g.tiles_t >> 3;   // token tiles per XCD
+    if ((g.tiles_t & 7) == 0 && (tpx % 4 == 0 || tpx < 4)) {
+        const int tg = tpx < 4 ? tpx : 4;
+        const int x = id & 7, j = id >> 3;
+        const int group = j / (g.tiles_o * tg), rem = j % (g.tiles_o * tg);
+        to = rem / tg;
+        tt = x * tpx + group * tg + rem % tg;
+    } else {
+        to = id % g.tiles_o;
+        tt = id / g.tiles_o;
+    }
 }
 
 __device__ __forceinline__ void store_tile(const GemmArgs &g, const v16i &acc, int o_base, int t, float scale)
