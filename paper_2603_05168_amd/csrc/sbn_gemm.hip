@@ -15,7 +15,6 @@ namespace {
 constexpr int BO = 256;        // output rows (of W) per block
 constexpr int BT = 128;        // tokens per block
 constexpr int KSTEP = 128;     // input features per main-loop iteration = one packed chunk
-constexpr int LDS_ROW = KSTEP + 16;   // padded row of the token tile: 16-byte reads of 32 rows hit distinct banks
 
 struct GemmArgs {
     const int8_t *xq;
@@ -84,6 +83,61 @@ __device__ __forceinline__ void store_tile(const GemmArgs &g, const v16i &acc, i
                 }
             }
         }
+    }
+}
+
+// Epilogue of both GEMM kernels.  A lane holds one token and rows 8q + 4c + i of each 32-row tile,
+// so a direct store would put only 32 contiguous bytes per token into each instruction (measured:
+// 1.5x the algorithmic write traffic).  The accumulators are rescaled, transposed through the now
+// idle LDS ring (32 tokens x 128 rows of fp32 per wavefront and pass) and leave as whole 512-byte
+// rows.  Ragged row edges and the int32 accumulator output take the plain per-lane stores.
+template <int NB>
+__device__ __forceinline__ void block_epilogue(const GemmArgs &g, v16i (&acc)[4][NB], int8_t *lds, int o0, int t0,
+                                               int wave, int wo, int wt, int lane)
+{
+    const int r = lane & 31, c = lane >> 5;
+    const float gam = *g.gamma;
+    const bool fast_store = (g.d_out & 3) == 0 && o0 + BO <= g.d_out && !g.acc_out;
+    if (fast_store) {
+        constexpr int EROW = 128 * 4 + 16;   // bytes per staged token row (padded)
+        int8_t *const est = lds + wave * (32 * EROW);
+        const int ocol = o0 + wo * 128;
+        __syncthreads();   // every wavefront has left the main loop: the ring can be overwritten
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const int t = t0 + wt * 32 * NB + 32 * b + r;
+            const float scale = t < g.tokens ? __fdiv_rn(gam, g.sx[t]) : 0.0f;
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    float4 y;
+                    y.x = (float)acc[a][b][4 * q + 0] * scale;
+                    y.y = (float)acc[a][b][4 * q + 1] * scale;
+                    y.z = (float)acc[a][b][4 * q + 2] * scale;
+                    y.w = (float)acc[a][b][4 * q + 3] * scale;
+                    *reinterpret_cast<float4 *>(est + r * EROW + (32 * a + 8 * q + 4 * c) * 4) = y;
+                }
+            // the wavefront reads back what it wrote itself: its LDS operations complete in order
+            float4 bias4 = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (g.bias) bias4 = *reinterpret_cast<const float4 *>(g.bias + ocol + 4 * (lane & 31));
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const int row = 2 * j + (lane >> 5);
+                const int tt2 = t0 + wt * 32 * NB + 32 * b + row;
+                float4 y = *reinterpret_cast<const float4 *>(est + row * EROW + (lane & 31) * 16);
+                y.x += bias4.x; y.y += bias4.y; y.z += bias4.z; y.w += bias4.w;
+                if (tt2 < g.tokens) *reinterpret_cast<float4 *>(g.Y + (int64_t)tt2 * g.d_out + ocol + 4 * (lane & 31)) = y;
+            }
+        }
+        return;
+    }
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        const int t = t0 + wt * 32 * NB + 32 * b + r;
+        const float scale = t < g.tokens ? __fdiv_rn(gam, g.sx[t]) : 0.0f;
+#pragma unroll
+        for (int a = 0; a < 4; ++a) store_tile(g, acc[a][b], o0 + wo * 128 + 32 * a + 4 * c, t, scale);
     }
 }
 
@@ -256,53 +310,7 @@ __global__ void __launch_bounds__(128 * WT, NB == 2 ? 2 : 1) gemm_smfmac_kernel(
     }
     if (kc < nchunks) iteration(kc, 0);
 
-    // Epilogue.  A lane holds one token and rows 8q + 4c + i of each 32-row tile, so a direct store
-    // would put only 32 contiguous bytes per token into each instruction (measured: 1.5x the
-    // algorithmic write traffic).  The accumulators are rescaled, transposed through the now idle
-    // LDS ring (32 tokens x 128 rows of fp32 per wavefront and pass) and leave as whole 512-byte rows.
-    const float gam = *g.gamma;
-    const bool fast_store = (g.d_out & 3) == 0 && o0 + BO <= g.d_out && !g.acc_out;
-    if (fast_store) {
-        constexpr int EROW = 128 * 4 + 16;   // bytes per staged token row (padded)
-        float *const est = reinterpret_cast<float *>(lds + wave * (32 * EROW));
-        const int ocol = o0 + wo * 128;
-        __syncthreads();   // every wavefront has left the main loop: the ring can be overwritten
-#pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            const int t = t0 + wt * 32 * NB + 32 * b + r;
-            const float scale = t < g.tokens ? __fdiv_rn(gam, g.sx[t]) : 0.0f;
-#pragma unroll
-            for (int a = 0; a < 4; ++a)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    float4 y;
-                    y.x = (float)acc[a][b][4 * q + 0] * scale;
-                    y.y = (float)acc[a][b][4 * q + 1] * scale;
-                    y.z = (float)acc[a][b][4 * q + 2] * scale;
-                    y.w = (float)acc[a][b][4 * q + 3] * scale;
-                    *reinterpret_cast<float4 *>(reinterpret_cast<int8_t *>(est) + r * EROW + (32 * a + 8 * q + 4 * c) * 4) = y;
-                }
-            // same wavefront reads back what it wrote: LDS operations of a wavefront complete in order
-            float4 bias4 = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (g.bias) bias4 = *reinterpret_cast<const float4 *>(g.bias + ocol + 4 * (lane & 31));
-#pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                const int row = 2 * j + (lane >> 5);
-                const int tt2 = t0 + wt * 32 * NB + 32 * b + row;
-                float4 y = *reinterpret_cast<const float4 *>(reinterpret_cast<const int8_t *>(est) + row * EROW + (lane & 31) * 16);
-                y.x += bias4.x; y.y += bias4.y; y.z += bias4.z; y.w += bias4.w;
-                if (tt2 < g.tokens) *reinterpret_cast<float4 *>(g.Y + (int64_t)tt2 * g.d_out + ocol + 4 * (lane & 31)) = y;
-            }
-        }
-        return;
-    }
-#pragma unroll
-    for (int b = 0; b < NB; ++b) {
-        const int t = t0 + wt * 32 * NB + 32 * b + r;
-        const float scale = t < g.tokens ? __fdiv_rn(gam, g.sx[t]) : 0.0f;
-#pragma unroll
-        for (int a = 0; a < 4; ++a) store_tile(g, acc[a][b], o0 + wo * 128 + 32 * a + 4 * c, t, scale);
-    }
+    block_epilogue<NB>(g, acc, lds, o0, t0, wave, wo, wt, lane);
 }
 
 // ---- dense comparison path ---------------------------------------------------------------------
@@ -329,33 +337,67 @@ __global__ void __launch_bounds__(256) expand_dense_kernel(const uint8_t *__rest
     reinterpret_cast<uint32_t *>(w)[gidx] = out;
 }
 
-// Same tiling as the sparse kernel; A fragments are 16 dense int8 per lane read from global
-// memory (lane (r, c) supplies weights [64c + 16u, +16) of the chunk in sub-step u = 0..3).
+// Same block and wave shapes as the sparse kernel and the same LDS-DMA machinery, so that the two
+// paths differ only in what the matrix instruction is fed: dense int8 rows with explicit zeros
+// (no index register, no code expansion) into v_mfma_i32_32x32x32_i8, twice as many of them.
+// Stage = 64 k of the 256 weight rows and 128 token rows (64-byte rows, 24 KB), ring of 3 stages;
+// one DMA instruction fills 16 rows, 16-byte granules swizzled with (row >> 2) & 3.
+constexpr int DK = 64;
+constexpr int DSTAGE = (BO + BT) * DK;   // 24 KB
+
 __global__ void __launch_bounds__(256, 2) gemm_dense_kernel(GemmArgs g)
 {
-    __shared__ __attribute__((aligned(16))) int8_t lds[2][BT * LDS_ROW];
+    __shared__ __attribute__((aligned(1024))) int8_t lds[STAGES * DSTAGE];
     int to, tt;
     tile_of_block(g, to, tt);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wo = wave & 1, wt = wave >> 1;
     const int r = lane & 31, c = lane >> 5;
-    const int K = g.d_in, nchunks = K / KSTEP;
-    const int o0 = to * BO + wo * 128, t0 = tt * BT;
+    const int K = g.d_in, nk = K / DK;
+    const int o0 = to * BO, t0 = tt * BT;
 
-    const int cp_row = tid >> 3, cp_col = (tid & 7) * 16;
-    const int8_t *xsrc[4];
+    const int8_t *const wbase = g.w_dense + (int64_t)o0 * K;
+    const int8_t *const xbase = g.xq + (int64_t)t0 * K;
+    uint32_t woff[4], xoff[2];
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        int t = t0 + cp_row + 32 * p;
-        t = t < g.tokens ? t : g.tokens - 1;
-        xsrc[p] = g.xq + (int64_t)t * K + cp_col;
+    for (int i = 0; i < 4; ++i) {
+        const int row = (4 * wave + i) * 16 + (lane >> 2);
+        const int o = o0 + row < g.d_out ? row : g.d_out - 1 - o0;
+        woff[i] = (uint32_t)o * (uint32_t)K + 16u * ((lane & 3) ^ ((row >> 2) & 3));
     }
-    const int8_t *wsrc[4];
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
-        int o = o0 + 32 * a + r;
-        o = o < g.d_out ? o : g.d_out - 1;
-        wsrc[a] = g.w_dense + (int64_t)o * K + 64 * c;
+    for (int i = 0; i < 2; ++i) {
+        const int row = (2 * wave + i) * 16 + (lane >> 2);
+        const int t = t0 + row < g.tokens ? row : g.tokens - 1 - t0;
+        xoff[i] = (uint32_t)t * (uint32_t)K + 16u * ((lane & 3) ^ ((row >> 2) & 3));
+    }
+    auto dma = [&](int kt) {
+        int8_t *dst = lds + (kt % STAGES) * DSTAGE;
+        const int8_t *ws = wbase + (int64_t)kt * DK, *xs = xbase + (int64_t)kt * DK;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(ws + woff[i]),
+                                             (__attribute__((address_space(3))) void *)(dst + (4 * wave + i) * 1024), 16, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(xs + xoff[i]),
+                                             (__attribute__((address_space(3))) void *)(dst + BO * DK + (2 * wave + i) * 1024), 16, 0, 0);
+    };
+    // lane (r, c) supplies k = 32u + 16c + 0..15 of the stage = granule 2u + c, for both operands
+    int aoff[2][4], boff[2][2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            const int row = wo * 128 + 32 * a + r;
+            aoff[u][a] = row * DK + 16 * ((2 * u + c) ^ ((row >> 2) & 3));
+        }
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            const int row = wt * 64 + 32 * b + r;
+            boff[u][b] = BO * DK + row * DK + 16 * ((2 * u + c) ^ ((row >> 2) & 3));
+        }
     }
 
     v16i acc[4][2];
@@ -366,54 +408,31 @@ __global__ void __launch_bounds__(256, 2) gemm_dense_kernel(GemmArgs g)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0;
 
-    uint4 xreg[4];
-#pragma unroll
-    for (int p = 0; p < 4; ++p) xreg[p] = *reinterpret_cast<const uint4 *>(xsrc[p]);
-#pragma unroll
-    for (int p = 0; p < 4; ++p)
-        *reinterpret_cast<uint4 *>(&lds[0][(cp_row + 32 * p) * LDS_ROW + cp_col]) = xreg[p];
-    __syncthreads();
-
-    for (int kc = 0; kc < nchunks; ++kc) {
-        const int cur = kc & 1;
-        if (kc + 1 < nchunks) {
-#pragma unroll
-            for (int p = 0; p < 4; ++p) xreg[p] = *reinterpret_cast<const uint4 *>(xsrc[p] + (kc + 1) * KSTEP);
-        }
-        const int8_t *bt = &lds[cur][0];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            v4i afrag[4];
-#pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                const uint4 w = *reinterpret_cast<const uint4 *>(wsrc[a] + (int64_t)kc * KSTEP + 16 * u);
-                afrag[a] = v4i{(int)w.x, (int)w.y, (int)w.z, (int)w.w};
-            }
-#pragma unroll
-            for (int b = 0; b < 2; ++b) {
-                const uint4 x = *reinterpret_cast<const uint4 *>(bt + (wt * 64 + 32 * b + r) * LDS_ROW + 64 * c + 16 * u);
-                const v4i bfrag = v4i{(int)x.x, (int)x.y, (int)x.z, (int)x.w};
-#pragma unroll
-                for (int a = 0; a < 4; ++a)
-                    acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(afrag[a], bfrag, acc[a][b], 0, 0, 0);
-            }
-        }
-        if (kc + 1 < nchunks) {
-#pragma unroll
-            for (int p = 0; p < 4; ++p)
-                *reinterpret_cast<uint4 *>(&lds[cur ^ 1][(cp_row + 32 * p) * LDS_ROW + cp_col]) = xreg[p];
-        }
+    dma(0);
+    if (nk > 1) dma(1);
+    for (int kt = 0; kt < nk; ++kt) {
+        if (kt + 1 < nk) SBN_WAIT_VMCNT(6); else SBN_WAIT_VMCNT(0);   // stage kt landed; stage kt+1 (6 loads) may be in flight
         __syncthreads();
+        if (kt + 2 < nk) dma(kt + 2);
+        const int8_t *st = lds + (kt % STAGES) * DSTAGE;
+        v4i af[2][4], bf[2][2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+#pragma unroll
+            for (int a = 0; a < 4; ++a) af[u][a] = *reinterpret_cast<const v4i *>(st + aoff[u][a]);
+#pragma unroll
+            for (int b = 0; b < 2; ++b) bf[u][b] = *reinterpret_cast<const v4i *>(st + boff[u][b]);
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[u][a], bf[u][b], acc[a][b], 0, 0, 0);
     }
 
-    const float gam = *g.gamma;
-#pragma unroll
-    for (int b = 0; b < 2; ++b) {
-        const int t = t0 + wt * 64 + 32 * b + r;
-        const float scale = t < g.tokens ? __fdiv_rn(gam, g.sx[t]) : 0.0f;
-#pragma unroll
-        for (int a = 0; a < 4; ++a) store_tile(g, acc[a][b], o0 + 32 * a + 4 * c, t, scale);
-    }
+    block_epilogue<2>(g, acc, lds, o0, t0, wave, wo, wt, lane);
 }
 
 GemmArgs make_args(const LinearItem &it, int block_tokens = BT)
