@@ -27,6 +27,20 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def measured_traffic(kernel, workload):
+    """HBM bytes per launch (fetch + write) from the rocprofv3 --pmc summary committed under profiles/
+    (FETCH_SIZE and WRITE_SIZE, each scaled by what the same counter reads for a plain copy), or None."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_pmc.txt")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) >= 5 and f[0] == "TRAFFIC" and f[1] == kernel and f[2] == workload:
+                return float(f[3]) + float(f[4])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -138,7 +152,8 @@ def main():
     big = gemm_rows[f"{F}x{H}"]
     roofline = {"kernel": "gemm_smfmac_kernel", "workload": f"T={T} K={H} d_out={F}", "bound": "mfma",
                 "achieved": big["executed_tops"], "peak": INT8_DENSE_PEAK_TOPS, "unit": "TOP/s",
-                "frac": big["frac_int8_mfma"], "traffic": None,
+                "frac": big["frac_int8_mfma"], "traffic": measured_traffic("gemm_smfmac_kernel", f"{F}x{H}"),
+                "algorithmic_bytes": T * H + F * H // 4 + 4 * T * F + 4 * T,
                 "note": "executed int8 ops T*K*d_out (the 2:4 instruction skips half of 2*T*K*d_out); "
                         "dense-equivalent TOPS / 10 POPS gives the same fraction"}
 
@@ -153,6 +168,7 @@ def main():
                                               sx_out=sx[i], path=sbn.SBN_PATH_DENSE_MFMA)
             ms = timed(dense_call, 20, 3)
             dense_rows[f"{a}x{b}"] = {"ms_with_expand": ms, "tops": 2.0 * T * a * b / (ms * 1e-3) / 1e12,
+                                      "frac_int8_mfma": 2.0 * T * a * b / (ms * 1e-3) / 1e12 / INT8_DENSE_PEAK_TOPS,
                                       "sparse_speedup": ms / gemm_rows[f"{a}x{b}"]["ms"]}
             log(f"[dense] {a}x{b}: {ms * 1e3:.1f} us -> sparse path is {ms / gemm_rows[f'{a}x{b}']['ms']:.2f}x faster")
         rows["gemm_dense_ternary"] = dense_rows
@@ -194,7 +210,8 @@ def main():
         best = gemv_rows["up_6912x2560_T8"]
         roofline_gemv = {"kernel": "gemv_smfmac_kernel", "workload": "64 x (6912x2560 packed 2:4), T=8, grouped",
                          "bound": "hbm", "achieved": best["stream_gbps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                         "frac": best["frac_hbm"], "traffic": None}
+                         "frac": best["frac_hbm"], "traffic": measured_traffic("gemv_stream_kernel", "64x6912x2560"),
+                         "algorithmic_bytes": R * best["packed_bytes"]}
 
     # ------------------------------------------------------------------ configs[3]: quantize_mask_pack sweep, 210 matrices
     if "pack" in sections:
@@ -296,25 +313,22 @@ def main():
     if "cpu" in sections:
         import numpy as np
         import oracle
-        Wc = sbn_synth.latent_weight(F, H, sbn_synth.seed_for(3, F)).float().numpy()
+        # the oracle runs the whole timed step once: both matrices, all 4096 tokens (a few seconds on the box)
+        Xc = sbn_synth.activations(T, H, sbn_synth.seed_for(3, 10)).float().numpy()
+        weights = []
         t1 = time.perf_counter()
-        Weff, mask, g = oracle.quantize_mask(Wc, N, M)
+        for a, b in shapes:
+            Wc = sbn_synth.latent_weight(a, b, sbn_synth.seed_for(3, a)).float().numpy()
+            weights.append(oracle.quantize_mask(Wc, N, M))
         pack_s = time.perf_counter() - t1
-        sample = 32
-        Xc = sbn_synth.activations(sample, H, sbn_synth.seed_for(3, 10)).float().numpy()
         t1 = time.perf_counter()
-        oracle.sparse_ternary_linear(Xc, Weff, g)
+        for Weff, mask, g in weights:
+            oracle.sparse_ternary_linear(Xc, Weff, g)
         dt = time.perf_counter() - t1
-        sample = int(min(T, max(sample, sample * 12.0 / max(dt, 1e-3))))     # aim at ~12 s of oracle time
-        Xc = sbn_synth.activations(sample, H, sbn_synth.seed_for(3, 10)).float().numpy()
-        t1 = time.perf_counter()
-        oracle.sparse_ternary_linear(Xc, Weff, g)
-        dt = time.perf_counter() - t1
-        cpu_baseline = {"value": 2.0 * sample * F * H / dt / 1e12, "unit": "TOPS", "cores": oracle.threads(),
-                        "kind": "oracle",
-                        "sample": f"forward of {sample} of {T} tokens against the {F}x{H} matrix "
-                                  f"(dense brute-force accumulate) in {dt:.1f} s; weight side (mask, quantize) of that "
-                                  f"matrix took {pack_s:.2f} s"}
+        cpu_baseline = {"value": ops_step / dt / 1e12, "unit": "TOPS", "cores": oracle.threads(), "kind": "oracle",
+                        "sample": f"the whole timed step once: forward of all {T} tokens against both matrices "
+                                  f"(activation quantizer, dense brute-force accumulate, rescale) in {dt:.1f} s; "
+                                  f"the untimed weight side (mask, quantize) of both matrices took {pack_s:.2f} s"}
         log(f"[cpu] oracle: {cpu_baseline['value']:.4f} TOPS on {cpu_baseline['cores']} threads ({cpu_baseline['sample']})")
 
     out = {
