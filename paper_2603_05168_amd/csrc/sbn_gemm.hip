@@ -86,29 +86,34 @@ __device__ __forceinline__ void store_tile(const GemmArgs &g, const v16i &acc, i
     }
 }
 
-// Epilogue of both GEMM kernels.  A lane holds one token and rows 8q + 4c + i of each 32-row tile,
-// so a direct store would put only 32 contiguous bytes per token into each instruction (measured:
-// 1.5x the algorithmic write traffic).  The accumulators are rescaled, transposed through the now
-// idle LDS ring (32 tokens x 128 rows of fp32 per wavefront and pass) and leave as whole 512-byte
-// rows.  Ragged row edges and the int32 accumulator output take the plain per-lane stores.
-template <int NB>
-__device__ __forceinline__ void block_epilogue(const GemmArgs &g, v16i (&acc)[4][NB], int8_t *lds, int o0, int t0,
-                                               int wave, int wo, int wt, int lane)
+// Epilogue of both GEMM kernels.  A wavefront owns RA row tiles x TB token tiles of 32x32; a lane
+// holds one token and rows 8q + 4c + i of each row tile, so a direct store would put only 32
+// contiguous bytes per token into each instruction (measured: 1.5x the algorithmic write traffic).
+// The accumulators are rescaled, transposed through the now idle LDS ring (32 tokens x 32*RA rows of
+// fp32 per wavefront and pass) and leave as whole rows of 128*RA bytes.  Ragged row edges and the
+// int32 accumulator output take the plain per-lane stores.
+//   orow = first output row of the wavefront, tok0 = its first token
+template <int RA, int TB>
+__device__ __forceinline__ void block_epilogue(const GemmArgs &g, v16i (&acc)[RA][TB], int8_t *lds, int o0, int orow,
+                                               int tok0, int wave, int lane)
 {
     const int r = lane & 31, c = lane >> 5;
     const float gam = *g.gamma;
     const bool fast_store = (g.d_out & 3) == 0 && o0 + BO <= g.d_out && !g.acc_out;
     if (fast_store) {
-        constexpr int EROW = 128 * 4 + 16;   // bytes per staged token row (padded)
+        constexpr int EROW = 128 * RA + 16;     // bytes per staged token row (padded)
+        constexpr int LPR = 8 * RA;             // lanes (float4) per token row
+        constexpr int RPI = 64 / LPR;           // token rows per store instruction
         int8_t *const est = lds + wave * (32 * EROW);
-        const int ocol = o0 + wo * 128;
         __syncthreads();   // every wavefront has left the main loop: the ring can be overwritten
+        float4 bias4 = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (g.bias) bias4 = *reinterpret_cast<const float4 *>(g.bias + orow + 4 * (lane % LPR));
 #pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            const int t = t0 + wt * 32 * NB + 32 * b + r;
+        for (int b = 0; b < TB; ++b) {
+            const int t = tok0 + 32 * b + r;
             const float scale = t < g.tokens ? __fdiv_rn(gam, g.sx[t]) : 0.0f;
 #pragma unroll
-            for (int a = 0; a < 4; ++a)
+            for (int a = 0; a < RA; ++a)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     float4 y;
@@ -119,33 +124,75 @@ __device__ __forceinline__ void block_epilogue(const GemmArgs &g, v16i (&acc)[4]
                     *reinterpret_cast<float4 *>(est + r * EROW + (32 * a + 8 * q + 4 * c) * 4) = y;
                 }
             // the wavefront reads back what it wrote itself: its LDS operations complete in order
-            float4 bias4 = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (g.bias) bias4 = *reinterpret_cast<const float4 *>(g.bias + ocol + 4 * (lane & 31));
 #pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                const int row = 2 * j + (lane >> 5);
-                const int tt2 = t0 + wt * 32 * NB + 32 * b + row;
-                float4 y = *reinterpret_cast<const float4 *>(est + row * EROW + (lane & 31) * 16);
+            for (int j = 0; j < 32 / RPI; ++j) {
+                const int row = RPI * j + lane / LPR;
+                const int tt2 = tok0 + 32 * b + row;
+                float4 y = *reinterpret_cast<const float4 *>(est + row * EROW + (lane % LPR) * 16);
                 y.x += bias4.x; y.y += bias4.y; y.z += bias4.z; y.w += bias4.w;
-                if (tt2 < g.tokens) *reinterpret_cast<float4 *>(g.Y + (int64_t)tt2 * g.d_out + ocol + 4 * (lane & 31)) = y;
+                if (tt2 < g.tokens)
+                    *reinterpret_cast<float4 *>(g.Y + (int64_t)tt2 * g.d_out + orow + 4 * (lane % LPR)) = y;
             }
         }
         return;
     }
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
-        const int t = t0 + wt * 32 * NB + 32 * b + r;
+    for (int b = 0; b < TB; ++b) {
+        const int t = tok0 + 32 * b + r;
         const float scale = t < g.tokens ? __fdiv_rn(gam, g.sx[t]) : 0.0f;
 #pragma unroll
-        for (int a = 0; a < 4; ++a) store_tile(g, acc[a][b], o0 + wo * 128 + 32 * a + 4 * c, t, scale);
+        for (int a = 0; a < RA; ++a) store_tile(g, acc[a][b], orow + 32 * a + 4 * c, t, scale);
     }
 }
 
+// One LDS-DMA load: lane l of the wavefront fetches 16 bytes at base + voff and the hardware
+// deposits them at LDS byte address lds_addr + 16*l (M0 carries the LDS address).  Written as
+// inline assembly on purpose: after the compiler's own LDS-DMA builtin every later LDS read is
+// preceded by a wait for ALL outstanding vector-memory operations (it cannot tell which LDS bytes
+// a DMA writes), which serialises the prefetch ring with the loads it has just issued.  With the
+// load opaque to the compiler the kernels below count the outstanding DMA operations themselves
+// (SBN_WAIT_VMCNT) and order LDS reads against them with the block barrier.
+__device__ __forceinline__ void lds_dma16(const void *base, uint32_t voff, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(base)
+                 : "memory", "m0");
+}
+
+__device__ __forceinline__ uint32_t lds_address(const void *p)
+{
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
+}
+
+// wait until at most n vector-memory operations of this wavefront are outstanding (gfx9 encoding:
+// vmcnt in bits [3:0] and [15:14]; expcnt and lgkmcnt fields left at "no wait")
+#define SBN_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xf) | (((n) >> 4) << 14) | 0x0f70)
+
+// 16 two-bit codes -> 16 int8 values with the odd registers' selector built by one v_and_or_b32
+// (mask in a scalar register, 0x01010101 in a vector register): 9 VALU operations.  VALU work does
+// not overlap matrix instructions on this part (measured: their times add), so every operation
+// saved here is matrix-pipe time gained.
+__device__ __forceinline__ v4i expand_codes9(uint32_t cw, uint32_t ones)
+{
+    const uint32_t lut = 0xff000100u;
+    const uint32_t t = cw >> 4;
+    uint32_t s1, s3;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(s1) : "v"(cw), "s"(0x0c0c0c0cu), "v"(ones));
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(s3) : "v"(t), "s"(0x0c0c0c0cu), "v"(ones));
+    v4i a;
+    a[0] = (int)__builtin_amdgcn_perm(lut, lut, cw & 0x03030303u);
+    a[1] = (int)__builtin_amdgcn_perm(0x00000100u, 0u, s1);
+    a[2] = (int)__builtin_amdgcn_perm(lut, lut, t & 0x03030303u);
+    a[3] = (int)__builtin_amdgcn_perm(0x00000100u, 0u, s3);
+    return a;
+}
+
 // ---- sparse path --------------------------------------------------------------------------------
-// 4 wavefronts as 2 (rows) x 2 (tokens); each owns 128 rows x 64 tokens = 4 x 2 tiles of 32x32.
-// Both operands reach LDS through the LDS-DMA load (global_load_lds_dwordx4: lane l of a wavefront
-// deposits its 16 bytes at base + 16*l), so no staging registers are needed and every wavefront
-// load instruction reads whole cache lines:
+// 4 wavefronts, one per 64 rows of the block; each owns 64 rows x 128 tokens = 2 x 4 tiles of 32x32,
+// so one code expansion (VALU) feeds four matrix instructions.
+// Both operands reach LDS through LDS-DMA loads (lane l of a wavefront deposits its 16 bytes at
+// base + 16*l), so no staging registers are needed and every load instruction reads whole cache lines:
 //   tokens   128 tokens x 128 int8 per iteration, ring of 3 stages; one instruction fills 8 token
 //            rows of 128 bytes; the 16-byte column a lane fetches is XOR-swizzled with
 //            (row >> 1) & 7 so that 16-byte reads of 16 consecutive rows fall in distinct banks;
@@ -156,35 +203,25 @@ __device__ __forceinline__ void block_epilogue(const GemmArgs &g, v16i (&acc)[4]
 // the lane supplies weights [64c + 32u, +32) of the chunk.
 constexpr int STAGES = 3;
 constexpr int WSLOT_BYTES = BO * 64;      // 16 KB: two chunks of every row of the block
+constexpr int RA = 2;                     // row tiles per wavefront
+constexpr int TB = BT / 32;               // token tiles per wavefront: all of the block's
 
-// wait until at most n vector-memory operations of this wavefront are outstanding (gfx9 encoding:
-// vmcnt in bits [3:0] and [15:14]; expcnt and lgkmcnt fields left at "no wait")
-#define SBN_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xf) | (((n) >> 4) << 14) | 0x0f70)
-
-// NB = token tiles of 32 per wavefront, WT = wavefronts along the tokens (two along the rows always).
-//   <2, 2>: 4 wavefronts, 128 accumulator registers each, two wavefronts per SIMD;
-//   <4, 1>: 2 wavefronts, 256 accumulator registers each, one wavefront per SIMD: one code expansion
-//           feeds four MFMAs instead of two.  VALU work does not overlap matrix instructions on this
-//           part (measured: their times add), so the expansion cost per MFMA decides the utilisation.
-// Both cover a block of 256 rows x 128 tokens and fit two blocks per multiprocessor (80 KB LDS).
-template <int NB, int WT>
-__global__ void __launch_bounds__(128 * WT, NB == 2 ? 2 : 1) gemm_smfmac_kernel(GemmArgs g)
+__global__ void __launch_bounds__(256, 2) gemm_smfmac_kernel(GemmArgs g)
 {
-    constexpr int NWAVES = 2 * WT;
-    constexpr int BTK = 32 * NB * WT;            // tokens per block
-    constexpr int STAGE_BYTES = BTK * KSTEP;     // 16 KB
-    constexpr int NDT = BTK / 8 / NWAVES;        // token DMA instructions per wavefront and stage
+    constexpr int NWAVES = 4;
+    constexpr int STAGE_BYTES = BT * KSTEP;      // 16 KB
+    constexpr int NDT = BT / 8 / NWAVES;         // token DMA instructions per wavefront and stage
     constexpr int NDW = 16 / NWAVES;             // weight DMA instructions per wavefront and pair
     __shared__ __attribute__((aligned(1024))) int8_t lds[STAGES * STAGE_BYTES + 2 * WSLOT_BYTES];
     int8_t *const wlds = lds + STAGES * STAGE_BYTES;
+    const uint32_t lds0 = lds_address(lds), wlds0 = lds0 + STAGES * STAGE_BYTES;
     int to, tt;
     tile_of_block(g, to, tt);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wo = wave & 1, wt = wave >> 1;
     const int r = lane & 31, c = lane >> 5;
     const int K = g.d_in, nchunks = K / KSTEP, npairs = (nchunks + 1) / 2;
-    const int o0 = to * BO, t0 = tt * BTK;
+    const int o0 = to * BO, t0 = tt * BT;
 
     // DMA sources as uniform base + 32-bit lane offset, so the per-iteration advance is scalar arithmetic.
     // tokens: instruction i (0..NDT-1) of this wavefront fills tile rows (NDT*wave + i)*8 .. +7
@@ -198,11 +235,9 @@ __global__ void __launch_bounds__(128 * WT, NB == 2 ? 2 : 1) gemm_smfmac_kernel(
     }
     auto dma_tokens = [&](int kc) {
         const int8_t *src = xbase + (int64_t)kc * KSTEP;
-        int8_t *dst = lds + (kc % STAGES) * STAGE_BYTES + wave * (NDT * 1024);
+        const uint32_t dst = lds0 + (kc % STAGES) * STAGE_BYTES + wave * (NDT * 1024);
 #pragma unroll
-        for (int i = 0; i < NDT; ++i)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + xoff[i]),
-                                             (__attribute__((address_space(3))) void *)(dst + i * 1024), 16, 0, 0);
+        for (int i = 0; i < NDT; ++i) lds_dma16(src, xoff[i], dst + i * 1024);
     };
     // weights: instruction i (0..NDW-1) of this wavefront fills block rows (NDW*wave + i)*16 .. +15
     const uint8_t *const wbase = g.packed + (int64_t)o0 * nchunks * 32;
@@ -219,89 +254,122 @@ __global__ void __launch_bounds__(128 * WT, NB == 2 ? 2 : 1) gemm_smfmac_kernel(
     }
     auto dma_weights = [&](int pair) {
         const uint8_t *src = wbase + (int64_t)pair * 64;
-        int8_t *dst = wlds + (pair & 1) * WSLOT_BYTES + wave * (NDW * 1024);
+        const uint32_t dst = wlds0 + (pair & 1) * WSLOT_BYTES + wave * (NDW * 1024);
         const bool last = pair == npairs - 1;
 #pragma unroll
         for (int i = 0; i < NDW; ++i) {
             // granules 2, 3 of a clipped pair lie past the row: fetch granule 0/1 again instead (never read)
             const uint32_t off = (last && wclip[i]) ? woff[i] - 32u : woff[i];
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + off),
-                                             (__attribute__((address_space(3))) void *)(dst + i * 1024), 16, 0, 0);
+            lds_dma16(src, off, dst + i * 1024);
         }
     };
     // LDS read offsets, swizzles folded in.  tokens: row * 128 + 16 * (chunk16 ^ ((row >> 1) & 7));
     // weights: row * 64 + 16 * (granule ^ ((row >> 2) & 3)) + 8c
-    int b_lo[2][NB], b_hi[2][NB];   // [sub-step][token tile]
+    int b_lo[2][TB], b_hi[2][TB];   // [sub-step][token tile]
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
-        const int row = wt * 32 * NB + 32 * b + r, sw = (row >> 1) & 7;
+    for (int b = 0; b < TB; ++b) {
+        const int row = 32 * b + r, sw = (row >> 1) & 7;
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             b_lo[u][b] = row * KSTEP + 16 * ((2 * u + c) ^ sw);
             b_hi[u][b] = row * KSTEP + 16 * ((4 + 2 * u + c) ^ sw);
         }
     }
-    int a_idx[2][4], a_code[2][4];   // [chunk of the pair][row tile]
+    int a_idx[2][RA], a_code[2][RA];   // [chunk of the pair][row tile]
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
-        const int row = wo * 128 + 32 * a + r, sw = (row >> 2) & 3;
+    for (int a = 0; a < RA; ++a) {
+        const int row = wave * (32 * RA) + 32 * a + r, sw = (row >> 2) & 3;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             a_idx[h][a] = row * 64 + 8 * c + 16 * ((2 * h) ^ sw);
             a_code[h][a] = row * 64 + 8 * c + 16 * ((2 * h + 1) ^ sw);
         }
     }
+    uint32_t ones;
+    asm volatile("v_mov_b32 %0, 0x01010101" : "=v"(ones));   // kept in a vector register for v_and_or_b32
 
-    v16i acc[4][NB];
+    v16i acc[RA][TB];
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+    for (int a = 0; a < RA; ++a)
 #pragma unroll
-        for (int b = 0; b < NB; ++b)
+        for (int b = 0; b < TB; ++b)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0;
 
-    // prologue: weight pairs 0 and 1, token tiles 0 and 1
+    // Software pipeline, one barrier per iteration placed between its two sub-steps:
+    //   sub-step 0 of iteration kc   issue the LDS reads of the tokens of (kc, 1), compute (kc, 0);
+    //   middle                       wait for token stage kc+1 (and, for odd kc, the weight pair of
+    //                                kc+1), barrier.  Every wavefront now holds all of stage kc in
+    //                                registers, so the DMA of token stage kc+3 goes into its slot
+    //                                and, for odd kc, weight pair (kc+1)/2 + 1 into the slot of
+    //                                pair (kc-1)/2;
+    //   sub-step 1                   issue the LDS reads of the weights and tokens of (kc+1, 0),
+    //                                compute (kc, 1).
+    // So every matrix instruction works on registers loaded half an iteration earlier, and a DMA has
+    // two iterations to land.  DMA issue order at a middle: tokens, then weights; the wait counts
+    // below rely on vector-memory operations of a wavefront completing in issue order.
     dma_weights(0);
     dma_tokens(0);
     if (npairs > 1) dma_weights(1);
     if (nchunks > 1) dma_tokens(1);
+    if (nchunks > 2) dma_tokens(2);
 
-    auto iteration = [&](int kc, const int h) {
-        // needed now: token tile kc and weight pair kc/2.  Still allowed in flight: what the previous
-        // iteration issued for later use (token tile kc+1: NDT loads; for odd kc also a weight pair: NDW more)
-        if (kc + 2 >= nchunks || kc == 0) SBN_WAIT_VMCNT(0);
-        else if (h) SBN_WAIT_VMCNT(NDT + NDW);
-        else SBN_WAIT_VMCNT(NDT);
-        __syncthreads();   // every wavefront's share has landed; stage (kc+2)%3 and, for even kc, weight slot (kc/2+1)%2 are free
-        if (h == 0 && kc >= 2 && kc / 2 + 1 < npairs) dma_weights(kc / 2 + 1);
-        if (kc + 2 < nchunks) dma_tokens(kc + 2);
-
-        const int8_t *bt = lds + (kc % STAGES) * STAGE_BYTES;
+    uint2 icur[RA], ccur[RA], inext[RA], cnext[RA];
+    v8i bq[2][TB];
+    auto read_weights = [&](int kc, const int h, uint2 (&iv)[RA], uint2 (&cv)[RA]) {   // h = kc & 1
         const int8_t *wt_ = wlds + ((kc >> 1) & 1) * WSLOT_BYTES;
-        uint2 icur[4], ccur[4];
-        v8i bfrag[2][NB];
 #pragma unroll
-        for (int a = 0; a < 4; ++a) {
-            icur[a] = *reinterpret_cast<const uint2 *>(wt_ + a_idx[h][a]);
-            ccur[a] = *reinterpret_cast<const uint2 *>(wt_ + a_code[h][a]);
+        for (int a = 0; a < RA; ++a) {
+            iv[a] = *reinterpret_cast<const uint2 *>(wt_ + a_idx[h][a]);
+            cv[a] = *reinterpret_cast<const uint2 *>(wt_ + a_code[h][a]);
         }
+    };
+    auto read_tokens = [&](int kc, const int u, v8i (&bf)[TB]) {
+        const int8_t *bt = lds + (kc % STAGES) * STAGE_BYTES;
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
+        for (int b = 0; b < TB; ++b) {
+            bf[b].lo = *reinterpret_cast<const v4i *>(bt + b_lo[u][b]);
+            bf[b].hi = *reinterpret_cast<const v4i *>(bt + b_hi[u][b]);
+        }
+    };
+    auto compute = [&](const int u, const v8i (&bf)[TB]) {
 #pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                bfrag[u][b].lo = *reinterpret_cast<const v4i *>(bt + b_lo[u][b]);
-                bfrag[u][b].hi = *reinterpret_cast<const v4i *>(bt + b_hi[u][b]);
-            }
-        // the 8 (sub-step, row tile) pairs in turn: expand 16 codes, then NB MFMAs on them
-#pragma unroll
-        for (int sidx = 0; sidx < 8; ++sidx) {
-            const int u = sidx >> 2, a = sidx & 3;
+        for (int a = 0; a < RA; ++a) {
             const int iv = (int)(u ? icur[a].y : icur[a].x);
-            const v4i av = expand_codes(u ? ccur[a].y : ccur[a].x);
+            const v4i av = expand_codes9(u ? ccur[a].y : ccur[a].x, ones);
 #pragma unroll
-            for (int b = 0; b < NB; ++b)
-                acc[a][b] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(av, bfrag[u][b], acc[a][b], iv, 0, 0);
+            for (int b = 0; b < TB; ++b)
+                acc[a][b] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(av, bf[b], acc[a][b], iv, 0, 0);
         }
+    };
+
+    SBN_WAIT_VMCNT(0);
+    __syncthreads();
+    read_weights(0, 0, icur, ccur);
+    read_tokens(0, 0, bq[0]);
+    auto iteration = [&](int kc, const int h) {   // h = kc & 1
+        read_tokens(kc, 1, bq[1]);
+        __builtin_amdgcn_sched_barrier(0);   // keep the reads ahead of the matrix work they overlap with
+        compute(0, bq[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        if (kc + 1 < nchunks) {
+            // still allowed in flight: what the previous middle issued
+            const bool t_fly = kc >= 1 && kc + 2 < nchunks;               // token stage kc+2, issued at the previous middle
+            const bool w_fly = h == 0 && kc >= 2 && kc / 2 + 1 < npairs;   // and the weight pair issued after it
+            if (t_fly && w_fly) SBN_WAIT_VMCNT(NDT + NDW);
+            else if (t_fly) SBN_WAIT_VMCNT(NDT);
+            else SBN_WAIT_VMCNT(0);
+            __syncthreads();
+            if (kc + 3 < nchunks) dma_tokens(kc + 3);
+            if (h == 1 && (kc + 1) / 2 + 1 < npairs) dma_weights((kc + 1) / 2 + 1);
+            read_weights(kc + 1, h ^ 1, inext, cnext);
+            read_tokens(kc + 1, 0, bq[0]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        compute(1, bq[1]);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int a = 0; a < RA; ++a) { icur[a] = inext[a]; ccur[a] = cnext[a]; }
     };
     int kc = 0;
     for (; kc + 1 < nchunks; kc += 2) {
@@ -310,7 +378,7 @@ __global__ void __launch_bounds__(128 * WT, NB == 2 ? 2 : 1) gemm_smfmac_kernel(
     }
     if (kc < nchunks) iteration(kc, 0);
 
-    block_epilogue<NB>(g, acc, lds, o0, t0, wave, wo, wt, lane);
+    block_epilogue<RA, TB>(g, acc, lds, o0, o0 + wave * (32 * RA), t0, wave, lane);
 }
 
 // ---- dense comparison path ---------------------------------------------------------------------
@@ -348,6 +416,7 @@ constexpr int DSTAGE = (BO + BT) * DK;   // 24 KB
 __global__ void __launch_bounds__(256, 2) gemm_dense_kernel(GemmArgs g)
 {
     __shared__ __attribute__((aligned(1024))) int8_t lds[STAGES * DSTAGE];
+    const uint32_t lds0 = lds_address(lds);
     int to, tt;
     tile_of_block(g, to, tt);
     const int tid = threadIdx.x, lane = tid & 63;
@@ -373,16 +442,12 @@ __global__ void __launch_bounds__(256, 2) gemm_dense_kernel(GemmArgs g)
         xoff[i] = (uint32_t)t * (uint32_t)K + 16u * ((lane & 3) ^ ((row >> 2) & 3));
     }
     auto dma = [&](int kt) {
-        int8_t *dst = lds + (kt % STAGES) * DSTAGE;
+        const uint32_t dst = lds0 + (kt % STAGES) * DSTAGE;
         const int8_t *ws = wbase + (int64_t)kt * DK, *xs = xbase + (int64_t)kt * DK;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(ws + woff[i]),
-                                             (__attribute__((address_space(3))) void *)(dst + (4 * wave + i) * 1024), 16, 0, 0);
+        for (int i = 0; i < 4; ++i) lds_dma16(ws, woff[i], dst + (4 * wave + i) * 1024);
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(xs + xoff[i]),
-                                             (__attribute__((address_space(3))) void *)(dst + BO * DK + (2 * wave + i) * 1024), 16, 0, 0);
+        for (int i = 0; i < 2; ++i) lds_dma16(xs, xoff[i], dst + BO * DK + (2 * wave + i) * 1024);
     };
     // lane (r, c) supplies k = 32u + 16c + 0..15 of the stage = granule 2u + c, for both operands
     int aoff[2][4], boff[2][2];
@@ -432,7 +497,7 @@ __global__ void __launch_bounds__(256, 2) gemm_dense_kernel(GemmArgs g)
                     acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[u][a], bf[u][b], acc[a][b], 0, 0, 0);
     }
 
-    block_epilogue<2>(g, acc, lds, o0, t0, wave, wo, wt, lane);
+    block_epilogue<4, 2>(g, acc, lds, o0, o0 + wo * 128, t0 + wt * 64, wave, lane);
 }
 
 GemmArgs make_args(const LinearItem &it, int block_tokens = BT)
@@ -450,11 +515,8 @@ GemmArgs make_args(const LinearItem &it, int block_tokens = BT)
 
 sbn_status launch_gemm_smfmac(const LinearItem &it, hipStream_t stream)
 {
-    // <2, 2> is the measured best.  <4, 1> (one wavefront per SIMD, 256 accumulators) halves the
-    // expansion work per MFMA but ran 1.6x slower: with a single resident wavefront nothing hides the
-    // LDS, barrier and DMA waits of the compiler's schedule.
-    GemmArgs g = make_args(it, 128);
-    hipLaunchKernelGGL((gemm_smfmac_kernel<2, 2>), dim3(g.tiles_o * g.tiles_t), dim3(256), 0, stream, g);
+    GemmArgs g = make_args(it);
+    hipLaunchKernelGGL(gemm_smfmac_kernel, dim3(g.tiles_o * g.tiles_t), dim3(256), 0, stream, g);
     return check_launch("gemm_smfmac_kernel");
 }
 
