@@ -215,10 +215,10 @@ __global__ void __launch_bounds__(1024) gemv_smfmac_kernel(GemvTable tab)
 }
 
 // ---- streaming decode GEMV for grouped calls ---------------------------------------------------
-// Persistent blocks: the rows of all problems are cut into units of 16*RT rows x the whole input
-// dimension; every block takes a contiguous run of units and its four wavefronts split that run,
-// so each wavefront reads one contiguous range of packed bytes.  The int8 activations of the
-// current problem (tokens x d_in) are staged in LDS once per block and problem; the packed weights
+// Persistent blocks, one per multiprocessor: the rows of all problems are cut into units of 16*RT
+// rows x the whole input dimension (a contiguous range of packed bytes); every block takes a
+// contiguous run of units and hands them to its NW wavefronts one at a time.  The int8 activations
+// of the current problem (tokens x d_in) are staged in LDS once per block and problem; the packed weights
 // go straight from HBM to registers through a queue of DEPTH super-steps (512 weights each) per
 // wavefront, so that several 16-byte loads per lane are always in flight.  No cross-wave reduction.
 struct GemvStreamItem {
@@ -236,11 +236,12 @@ struct GemvStreamTable {
     int count;
 };
 
-template <int RT, int DEPTH>
-__global__ void __launch_bounds__(256, 4) gemv_stream_kernel(GemvStreamTable tab)
+template <int RT, int DEPTH, int NW>
+__global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable tab)
 {
     extern __shared__ __attribute__((aligned(16))) int8_t xlds[];   // [tokens][d_in + 16]
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __shared__ int unit_ctr;                                        // next unit of the current problem nobody has taken
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int total = tab.unit0[tab.count];
     const int b0 = (int)((int64_t)total * blockIdx.x / gridDim.x), b1 = (int)((int64_t)total * (blockIdx.x + 1) / gridDim.x);
     const int r = lane & 15, c4 = lane >> 4;
@@ -255,90 +256,120 @@ __global__ void __launch_bounds__(256, 4) gemv_stream_kernel(GemvStreamTable tab
         const int ua = u - tab.unit0[item], ub = seg_end - tab.unit0[item];   // units of this problem for the block
         u = seg_end;
         const int K = it.d_in, nchunks = K / CHUNK, nsuper = (nchunks + 3) / 4, pitch = K + 16;
-
         const bool tok_ok = r < it.tokens;
-        const int wa = ua + (int)((int64_t)(ub - ua) * wave / 4), wb = ua + (int)((int64_t)(ub - ua) * (wave + 1) / 4);
-        const int nsteps = (wb - wa) * nsuper;
         const int xoff = (tok_ok ? r : 0) * pitch + 128 * (c4 >> 1) + 16 * (c4 & 1);
-        int iu = wa, is = 0, cu = wa, cs = 0;
+        const bool ragged = (nchunks & 3) != 0;   // the last super-step of a unit then covers fewer than four chunks
+
+        // Wavefronts of a block advance at very different speeds (measured: the first one to finish
+        // an equal share is done in half the time of the last), so the units of the block are handed
+        // out one at a time from a counter in LDS: wavefront w starts with unit ua + w and takes the
+        // next free one whenever its load stream reaches the end of a unit.  The loads run DEPTH
+        // super-steps ahead of the arithmetic; with nsuper > DEPTH they are at most one unit ahead,
+        // so one register (nu) carries the unit number from the load side to the arithmetic.  Shorter
+        // rows fall back to equal contiguous shares.
+        const bool dyn = nsuper > DEPTH;
+        const int wa = dyn ? ua + wave : ua + (int)((int64_t)(ub - ua) * wave / NW);
+        const int wb = dyn ? ub : ua + (int)((int64_t)(ub - ua) * (wave + 1) / NW);   // first unit number that is not this wavefront's
+        __syncthreads();   // nobody still uses the previous problem's counter or activations
+        if (threadIdx.x == 0) unit_ctr = ua + NW;
+        int iu = wa, is = 0, cu = wa, cs = 0, nu = wb;
+        int grabbed = wb;   // prefetched from the counter one unit ahead of its use
         uint4 qi[DEPTH][RT], qc[DEPTH][RT];
+        // Every load is unconditional, so the loop below is straight-line code and the wait the
+        // compiler places before a slot is consumed leaves the DEPTH - 1 younger super-steps in
+        // flight (a load inside a branch makes it wait for everything).  Past the end of the
+        // wavefront's work the last unit is fetched again (cache hits, no HBM traffic) and ignored.
         auto issue = [&](uint4(&ib)[RT], uint4(&cb)[RT]) {
-            const bool a_ok = 4 * is + c4 < nchunks;
+            int ch = 4 * is + c4;
+            ch = ch < nchunks ? ch : nchunks - 1;
+            const int unit = iu < wb ? iu : ub - 1;
 #pragma unroll
             for (int a = 0; a < RT; ++a) {
-                int row = iu * 16 * RT + 16 * a + r;
+                int row = unit * 16 * RT + 16 * a + r;
                 row = row < it.d_out ? row : it.d_out - 1;
-                const uint8_t *p = it.packed + ((int64_t)row * nchunks + 4 * is + c4) * 32;
-                ib[a] = a_ok ? *reinterpret_cast<const uint4 *>(p) : make_uint4(0, 0, 0, 0);
-                cb[a] = a_ok ? *reinterpret_cast<const uint4 *>(p + 16) : make_uint4(0, 0, 0, 0);
+                const uint8_t *p = it.packed + ((int64_t)row * nchunks + ch) * 32;
+                ib[a] = *reinterpret_cast<const uint4 *>(p);
+                cb[a] = *reinterpret_cast<const uint4 *>(p + 16);
             }
-            if (++is == nsuper) { is = 0; ++iu; }
+            if (++is == nsuper) {
+                is = 0;
+                if (dyn) {
+                    iu = nu = __builtin_amdgcn_readfirstlane(grabbed);
+                    if (lane == 0) grabbed = atomicAdd(&unit_ctr, 1);
+                } else {
+                    ++iu;
+                }
+            }
         };
-        // weight loads first: they are in flight while the activations are staged
-#pragma unroll
-        for (int d = 0; d < DEPTH; ++d)
-            if (d < nsteps) issue(qi[d], qc[d]);
         // Activations are staged only when they differ from what the block already holds (projections
         // that share an input, Q/K/V or up/gate, come one after the other).
-        if (it.xq != staged_xq || it.tokens != staged_tokens || K != staged_k) {
-            __syncthreads();   // the previous problem's activations are no longer read
-            for (int v = threadIdx.x; v < it.tokens * (K / 16); v += 256) {
+        const bool restage = it.xq != staged_xq || it.tokens != staged_tokens || K != staged_k;
+        if (restage) {
+            for (int v = threadIdx.x; v < it.tokens * (K / 16); v += 64 * NW) {
                 const int t = v / (K / 16), k = (v % (K / 16)) * 16;
                 *reinterpret_cast<uint4 *>(&xlds[t * pitch + k]) = *reinterpret_cast<const uint4 *>(it.xq + (int64_t)t * K + k);
             }
             staged_xq = it.xq;
             staged_tokens = it.tokens;
             staged_k = K;
-            __syncthreads();
+        }
+        __syncthreads();   // counter and activations in place
+        if (dyn && lane == 0) grabbed = atomicAdd(&unit_ctr, 1);
+        if (wa < wb) {
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) issue(qi[d], qc[d]);
         }
         const float scale = tok_ok ? __fdiv_rn(*it.gamma, it.sx[r]) : 0.0f;
 
         v4i acc[RT];
 #pragma unroll
         for (int a = 0; a < RT; ++a) acc[a] = v4i{0, 0, 0, 0};
-        for (int q = 0; q < nsteps; q += DEPTH) {
+        // Lanes of absent tokens read token 0's activations (their accumulator columns are never
+        // stored); activations past the input dimension are read from the slack behind the staged
+        // rows and meet zero codes.
+        while (cu < wb) {
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) {
-                if (q + d < nsteps) {
-                    uint4 ic[RT], cc[RT];
+                uint4 ic[RT], cc[RT];
 #pragma unroll
-                    for (int a = 0; a < RT; ++a) { ic[a] = qi[d][a]; cc[a] = qc[d][a]; }
-                    if (q + d + DEPTH < nsteps) issue(qi[d], qc[d]);
+                for (int a = 0; a < RT; ++a) { ic[a] = qi[d][a]; cc[a] = qc[d][a]; }
+                issue(qi[d], qc[d]);
+                if ((ragged && cs == nsuper - 1 && 4 * cs + c4 >= nchunks) || cu >= wb) {
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int k_lo = cs * 512 + 128 * (c4 >> 1) + 16 * (c4 & 1) + 32 * j, k_hi = k_lo + 256;
-                        uint4 blo = make_uint4(0, 0, 0, 0), bhi = make_uint4(0, 0, 0, 0);
-                        if (tok_ok && k_lo < K) blo = *reinterpret_cast<const uint4 *>(&xlds[xoff + cs * 512 + 32 * j]);
-                        if (tok_ok && k_hi < K) bhi = *reinterpret_cast<const uint4 *>(&xlds[xoff + cs * 512 + 32 * j + 256]);
-                        const v8i b = {(int)blo.x, (int)blo.y, (int)blo.z, (int)blo.w, (int)bhi.x, (int)bhi.y, (int)bhi.z, (int)bhi.w};
+                    for (int a = 0; a < RT; ++a) cc[a] = make_uint4(0, 0, 0, 0);
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint4 blo = *reinterpret_cast<const uint4 *>(&xlds[xoff + cs * 512 + 32 * j]);
+                    const uint4 bhi = *reinterpret_cast<const uint4 *>(&xlds[xoff + cs * 512 + 32 * j + 256]);
+                    const v8i b = {(int)blo.x, (int)blo.y, (int)blo.z, (int)blo.w, (int)bhi.x, (int)bhi.y, (int)bhi.z, (int)bhi.w};
+#pragma unroll
+                    for (int a = 0; a < RT; ++a) {
+                        const uint32_t cw = j == 0 ? cc[a].x : j == 1 ? cc[a].y : j == 2 ? cc[a].z : cc[a].w;
+                        const uint32_t iw = j == 0 ? ic[a].x : j == 1 ? ic[a].y : j == 2 ? ic[a].z : ic[a].w;
+                        acc[a] = __builtin_amdgcn_smfmac_i32_16x16x128_i8(expand_codes(cw), b, acc[a], (int)iw, 0, 0);
+                    }
+                }
+                if (++cs == nsuper) {
+                    // unit cu complete: lane holds token r, rows 4 * c4 + i of each row tile
+                    if (tok_ok && cu < wb) {
 #pragma unroll
                         for (int a = 0; a < RT; ++a) {
-                            const uint32_t cw = j == 0 ? cc[a].x : j == 1 ? cc[a].y : j == 2 ? cc[a].z : cc[a].w;
-                            const uint32_t iw = j == 0 ? ic[a].x : j == 1 ? ic[a].y : j == 2 ? ic[a].z : ic[a].w;
-                            acc[a] = __builtin_amdgcn_smfmac_i32_16x16x128_i8(expand_codes(cw), b, acc[a], (int)iw, 0, 0);
-                        }
-                    }
-                    if (++cs == nsuper) {
-                        // unit cu complete: lane holds token r, rows 4 * c4 + i of each row tile
-                        if (tok_ok) {
-#pragma unroll
-                            for (int a = 0; a < RT; ++a) {
-                                const int o = cu * 16 * RT + 16 * a + 4 * c4;
-                                if (o + 3 < it.d_out && (it.d_out & 3) == 0) {
-                                    *reinterpret_cast<float4 *>(it.Y + (int64_t)r * it.d_out + o) =
-                                        make_float4((float)acc[a][0] * scale, (float)acc[a][1] * scale,
-                                                    (float)acc[a][2] * scale, (float)acc[a][3] * scale);
-                                } else {
-                                    for (int i = 0; i < 4; ++i)
-                                        if (o + i < it.d_out) it.Y[(int64_t)r * it.d_out + o + i] = (float)acc[a][i] * scale;
-                                }
+                            const int o = cu * 16 * RT + 16 * a + 4 * c4;
+                            if (o + 3 < it.d_out && (it.d_out & 3) == 0) {
+                                *reinterpret_cast<float4 *>(it.Y + (int64_t)r * it.d_out + o) =
+                                    make_float4((float)acc[a][0] * scale, (float)acc[a][1] * scale,
+                                                (float)acc[a][2] * scale, (float)acc[a][3] * scale);
+                            } else {
+                                for (int i = 0; i < 4; ++i)
+                                    if (o + i < it.d_out) it.Y[(int64_t)r * it.d_out + o + i] = (float)acc[a][i] * scale;
                             }
                         }
-#pragma unroll
-                        for (int a = 0; a < RT; ++a) acc[a] = v4i{0, 0, 0, 0};
-                        cs = 0;
-                        ++cu;
                     }
+#pragma unroll
+                    for (int a = 0; a < RT; ++a) acc[a] = v4i{0, 0, 0, 0};
+                    cs = 0;
+                    cu = dyn ? nu : cu + 1;
                 }
             }
         }
@@ -445,14 +476,14 @@ sbn_status launch_gemv(int count, const LinearItem *items, hipStream_t stream)
         for (int i = 0; i < n; ++i) {
             const LinearItem &li = items[first + i];
             units += ceil_div(li.d_out, 16 * RT);
-            const int64_t b = li.tokens * (li.d_in + 16);
+            const int64_t b = li.tokens * (li.d_in + 16) + 512;   // slack: reads past a ragged input dimension stay inside
             lds_need = b > lds_need ? b : lds_need;
             if (li.bias || li.acc_out) plain = false;
         }
-        int bpc = (int)(160 * 1024 / lds_need);   // blocks per multiprocessor the staged activations leave room for
-        bpc = bpc > 4 ? 4 : bpc;
-        const int nblocks = device_cus() * bpc;
-        if (plain && bpc >= 1 && units >= 4 * (int64_t)nblocks) {
+        // one block of NW wavefronts per multiprocessor, sharing one staged copy of the activations
+        const int nblocks = device_cus();
+        constexpr int GEMV_STREAM_LDS = 160 * 1024 - 64;   // the kernel's unit counter takes a little static LDS
+        if (plain && lds_need <= GEMV_STREAM_LDS && units >= 16 * (int64_t)nblocks) {
             GemvStreamTable tab;
             tab.count = n;
             int u = 0;
@@ -465,16 +496,17 @@ sbn_status launch_gemv(int count, const LinearItem *items, hipStream_t stream)
                 u += (int)ceil_div(li.d_out, 16 * RT);
             }
             tab.unit0[n] = u;
-            if (lds_need > 64 * 1024) {
-                static thread_local bool raised = false;
-                if (!raised) {
-                    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemv_stream_kernel<RT, 4>),
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-                    if (e != hipSuccess) { set_hip_error(e, "hipFuncSetAttribute"); return SBN_EHIP; }
-                    raised = true;
-                }
+            // DEPTH 4 with 8 wavefronts per block measured best among depths 2..8 and 4..16 wavefronts
+            // (more wavefronts finish their shares further apart, fewer leave too few loads in flight)
+            constexpr int DEPTH = 4, NW = 8;
+            static thread_local bool raised = false;
+            if (!raised) {
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemv_stream_kernel<RT, DEPTH, NW>),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, GEMV_STREAM_LDS);
+                if (e != hipSuccess) { set_hip_error(e, "hipFuncSetAttribute"); return SBN_EHIP; }
+                raised = true;
             }
-            hipLaunchKernelGGL((gemv_stream_kernel<RT, 4>), dim3(nblocks), dim3(256), (size_t)lds_need, stream, tab);
+            hipLaunchKernelGGL((gemv_stream_kernel<RT, DEPTH, NW>), dim3(nblocks), dim3(64 * NW), (size_t)lds_need, stream, tab);
             sbn_status st = check_launch("gemv_stream_kernel");
             if (st != SBN_OK) return st;
             first += n;
