@@ -101,14 +101,19 @@ def main():
     xq = [torch.empty(T, H, dtype=torch.int8, device=dev) for _ in range(NSETS)]
     sx = [torch.empty(T, dtype=torch.float32, device=dev) for _ in range(NSETS)]
     ws_lin = sbn.new_workspace(sbn.sbn_workspace_bytes(sbn.SBN_OP_LINEAR, T, F, H, N, M), dev)
+    ws_grp = sbn.new_workspace(sum(sbn.sbn_workspace_bytes(sbn.SBN_OP_LINEAR, T, a, b, N, M) for a, b in shapes), dev)
+    # one grouped call per step: the projections share X, so it is quantized once and all their
+    # tiles go out in one launch (largest problem first)
+    order = sorted(range(len(shapes)), key=lambda j: -shapes[j][0])
+    groups = [sbn.LinearGroup([Xs[i]] * len(shapes), [Wp[j][0] for j in order], [Wp[j][1] for j in order],
+                              [Ys[i][j] for j in order], N, M, ws_grp, sbn.SBN_PATH_SMFMAC) for i in range(NSETS)]
     torch.cuda.synchronize()
     counter = [0]
 
-    def step(path=sbn.SBN_PATH_SMFMAC):
+    def step():
         i = counter[0] % NSETS
         counter[0] += 1
-        for j, (a, b) in enumerate(shapes):
-            sbn.sbn_sparse_ternary_linear(Xs[i], Wp[j][0], Wp[j][1], Ys[i][j], N, M, ws_lin, path=path)
+        groups[i].run()
 
     for _ in range(args.warmup):
         step()

@@ -153,7 +153,7 @@ static sbn_status linear_one(const LinearItem &it_in, const Pattern &pat, sbn_pa
     if (st != SBN_OK) return st;
     switch (path) {
     case SBN_PATH_GEMV: return launch_gemv(1, &it, stream);
-    case SBN_PATH_SMFMAC: return launch_gemm_smfmac(it, stream);
+    case SBN_PATH_SMFMAC: return launch_gemm_smfmac(1, &it, stream);
     case SBN_PATH_DENSE_MFMA: return launch_gemm_dense(it, w_dense, stream);
     case SBN_PATH_GENERIC: return launch_linear_generic(it, pat, stream);
     default: return SBN_EINVAL;
@@ -191,7 +191,7 @@ sbn_status sbn_sparse_ternary_linear_grouped(int count, const void *const *X, co
     if (!aligned(workspace, 256)) return SBN_EALIGN;
     Pattern pat;
     size_t need = 0;
-    bool all_gemv = true;
+    bool all_gemv = true, all_smfmac = true;
     for (int i = 0; i < count; ++i) {
         if (!X[i] || !packed[i] || !gamma[i] || !Y[i] || tokens[i] <= 0) return SBN_EINVAL;
         sbn_status st = check_shape(d_out[i], d_in[i], N, M, pat);
@@ -199,14 +199,18 @@ sbn_status sbn_sparse_ternary_linear_grouped(int count, const void *const *X, co
         if (!aligned(X[i], 16) || !aligned(packed[i], 16) || !aligned(Y[i], 16)) return SBN_EALIGN;
         if (d_in[i] % 8 != 0) return SBN_EUNSUPPORTED;
         need += linear_workspace_bytes(tokens[i], d_out[i], d_in[i]);
-        if (resolve_path(path, tokens[i], pat) != SBN_PATH_GEMV || tokens[i] > 16 || d_in[i] % CHUNK != 0)
+        const bool is24 = pat.N == 2 && pat.M == 4;
+        if (resolve_path(path, tokens[i], pat) != SBN_PATH_GEMV || !is24 || tokens[i] > 16 || d_in[i] % CHUNK != 0)
             all_gemv = false;
+        if (resolve_path(path, tokens[i], pat) != SBN_PATH_SMFMAC || !is24 || d_in[i] % CHUNK != 0 ||
+            tokens[i] * d_out[i] >= (int64_t)1 << 40)
+            all_smfmac = false;
     }
     if (ws_bytes < need) return SBN_ESIZE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint8_t *ws = static_cast<uint8_t *>(workspace);
-    if (!all_gemv) {
-        // no grouped kernel for the GEMM paths: one enqueue per problem
+    if (!all_gemv && !all_smfmac) {
+        // mixed paths: one enqueue per problem
         for (int i = 0; i < count; ++i) {
             LinearItem it{X[i], packed[i], gamma[i], nullptr, Y[i], nullptr, nullptr, nullptr, tokens[i], d_in[i], d_out[i]};
             const size_t wsz = linear_workspace_bytes(tokens[i], d_out[i], d_in[i]);
@@ -237,7 +241,7 @@ sbn_status sbn_sparse_ternary_linear_grouped(int count, const void *const *X, co
             if (st != SBN_OK) return st;
         }
     }
-    return launch_gemv(count, tl_items.data(), s);
+    return all_gemv ? launch_gemv(count, tl_items.data(), s) : launch_gemm_smfmac(count, tl_items.data(), s);
 }
 
 sbn_status sbn_sparse_ternary_linear_backward(const void *dY, int64_t tokens, int64_t d_in, int64_t d_out, int N,

@@ -29,15 +29,25 @@ struct GemmArgs {
     int tiles_o, tiles_t;
 };
 
+// A grouped launch covers the tiles of up to GEMM_GROUP_MAX problems: problem p owns the blocks
+// [block0[p], block0[p+1]); every block0 is a multiple of 8 so that a problem's block i still runs on
+// XCD i % 8 (blocks beyond a problem's last tile exit at once).  Problems that share tokens run
+// back to back: the tail of one fills the machine together with the head of the next.
+constexpr int GEMM_GROUP_MAX = 8;
+struct GemmGroup {
+    GemmArgs g[GEMM_GROUP_MAX];
+    int block0[GEMM_GROUP_MAX + 1];
+    int count;
+};
+
 // Blocks are dealt round-robin to the 8 XCDs, each with its own 4 MB L2.  XCD x takes the token
 // tiles [x, x+1) * tiles_t/8 and walks them in groups of four: inside a group the token tile is the
 // fastest index, then the row tile.  The 64 blocks an XCD runs at a time then share four token tiles
 // (1.3 MB, resident for the whole group) while the packed weights stream through its L2 once per
 // group, instead of every row tile being re-fetched for every token tile (measured: L2 miss traffic
 // 15x the unique input bytes with the row tile fastest).
-__device__ __forceinline__ void tile_of_block(const GemmArgs &g, int &to, int &tt)
+__device__ __forceinline__ void tile_of_block(const GemmArgs &g, int id, int &to, int &tt)
 {
-    const int id = blockIdx.x;
     const int tpx = g.tiles_t >> 3;   // token tiles per XCD
     if ((g.tiles_t & 7) == 0 && (tpx % 4 == 0 || tpx < 4)) {
         const int tg = tpx < 4 ? tpx : 4;
@@ -94,11 +104,10 @@ __device__ __forceinline__ void store_tile(const GemmArgs &g, const v16i &acc, i
 // int32 accumulator output take the plain per-lane stores.
 //   orow = first output row of the wavefront, tok0 = its first token
 template <int RA, int TB>
-__device__ __forceinline__ void block_epilogue(const GemmArgs &g, v16i (&acc)[RA][TB], int8_t *lds, int o0, int orow,
-                                               int tok0, int wave, int lane)
+__device__ __forceinline__ void block_epilogue(const GemmArgs &g, v16i (&acc)[RA][TB], const float (&scales)[TB],
+                                               int8_t *lds, int o0, int orow, int tok0, int wave, int lane)
 {
     const int r = lane & 31, c = lane >> 5;
-    const float gam = *g.gamma;
     const bool fast_store = (g.d_out & 3) == 0 && o0 + BO <= g.d_out && !g.acc_out;
     if (fast_store) {
         constexpr int EROW = 128 * RA + 16;     // bytes per staged token row (padded)
@@ -110,8 +119,7 @@ __device__ __forceinline__ void block_epilogue(const GemmArgs &g, v16i (&acc)[RA
         if (g.bias) bias4 = *reinterpret_cast<const float4 *>(g.bias + orow + 4 * (lane % LPR));
 #pragma unroll
         for (int b = 0; b < TB; ++b) {
-            const int t = tok0 + 32 * b + r;
-            const float scale = t < g.tokens ? __fdiv_rn(gam, g.sx[t]) : 0.0f;
+            const float scale = scales[b];
 #pragma unroll
             for (int a = 0; a < RA; ++a)
 #pragma unroll
@@ -130,8 +138,11 @@ __device__ __forceinline__ void block_epilogue(const GemmArgs &g, v16i (&acc)[RA
                 const int tt2 = tok0 + 32 * b + row;
                 float4 y = *reinterpret_cast<const float4 *>(est + row * EROW + (lane % LPR) * 16);
                 y.x += bias4.x; y.y += bias4.y; y.z += bias4.z; y.w += bias4.w;
-                if (tt2 < g.tokens)
-                    *reinterpret_cast<float4 *>(g.Y + (int64_t)tt2 * g.d_out + orow + 4 * (lane % LPR)) = y;
+                if (tt2 < g.tokens) {
+                    // streaming store: Y is not read again here and must not push the operands out of L2
+                    const v4f yv = {y.x, y.y, y.z, y.w};
+                    __builtin_nontemporal_store(yv, reinterpret_cast<v4f *>(g.Y + (int64_t)tt2 * g.d_out + orow + 4 * (lane % LPR)));
+                }
             }
         }
         return;
@@ -139,9 +150,21 @@ __device__ __forceinline__ void block_epilogue(const GemmArgs &g, v16i (&acc)[RA
 #pragma unroll
     for (int b = 0; b < TB; ++b) {
         const int t = tok0 + 32 * b + r;
-        const float scale = t < g.tokens ? __fdiv_rn(gam, g.sx[t]) : 0.0f;
 #pragma unroll
-        for (int a = 0; a < RA; ++a) store_tile(g, acc[a][b], orow + 32 * a + 4 * c, t, scale);
+        for (int a = 0; a < RA; ++a) store_tile(g, acc[a][b], orow + 32 * a + 4 * c, t, scales[b]);
+    }
+}
+
+// gamma / s_x[t] of the TB tokens a lane holds (token tile b: tok0 + 32 b + lane % 32); loaded ahead of
+// the main loop so that the epilogue does not start with a chain of dependent global loads
+template <int TB>
+__device__ __forceinline__ void load_scales(const GemmArgs &g, int tok0, int lane, float (&scales)[TB])
+{
+    const float gam = *g.gamma;
+#pragma unroll
+    for (int b = 0; b < TB; ++b) {
+        const int t = tok0 + 32 * b + (lane & 31);
+        scales[b] = t < g.tokens ? __fdiv_rn(gam, g.sx[t]) : 0.0f;
     }
 }
 
@@ -206,17 +229,23 @@ constexpr int WSLOT_BYTES = BO * 64;      // 16 KB: two chunks of every row of t
 constexpr int RA = 2;                     // row tiles per wavefront
 constexpr int TB = BT / 32;               // token tiles per wavefront: all of the block's
 
-__global__ void __launch_bounds__(256, 2) gemm_smfmac_kernel(GemmArgs g)
+__global__ void __launch_bounds__(256, 2) gemm_smfmac_kernel(GemmGroup grp)
 {
+    int prob = 0;
+    while (prob + 1 < grp.count && (int)blockIdx.x >= grp.block0[prob + 1]) ++prob;
+    const GemmArgs &g = grp.g[prob];
+    const int local_id = blockIdx.x - grp.block0[prob];
+    if (local_id >= g.tiles_o * g.tiles_t) return;   // padding block
     constexpr int NWAVES = 4;
     constexpr int STAGE_BYTES = BT * KSTEP;      // 16 KB
     constexpr int NDT = BT / 8 / NWAVES;         // token DMA instructions per wavefront and stage
     constexpr int NDW = 16 / NWAVES;             // weight DMA instructions per wavefront and pair
+    static_assert(NDT == TB, "one token DMA instruction is issued under each matrix instruction of a row tile");
     __shared__ __attribute__((aligned(1024))) int8_t lds[STAGES * STAGE_BYTES + 2 * WSLOT_BYTES];
     int8_t *const wlds = lds + STAGES * STAGE_BYTES;
     const uint32_t lds0 = lds_address(lds), wlds0 = lds0 + STAGES * STAGE_BYTES;
     int to, tt;
-    tile_of_block(g, to, tt);
+    tile_of_block(g, local_id, to, tt);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 31, c = lane >> 5;
@@ -314,6 +343,9 @@ __global__ void __launch_bounds__(256, 2) gemm_smfmac_kernel(GemmArgs g)
     if (nchunks > 1) dma_tokens(1);
     if (nchunks > 2) dma_tokens(2);
 
+    float scales[TB];
+    load_scales<TB>(g, t0, lane, scales);
+
     uint2 icur[RA], ccur[RA], inext[RA], cnext[RA];
     v8i bq[2][TB];
     auto read_weights = [&](int kc, const int h, uint2 (&iv)[RA], uint2 (&cv)[RA]) {   // h = kc & 1
@@ -332,14 +364,24 @@ __global__ void __launch_bounds__(256, 2) gemm_smfmac_kernel(GemmArgs g)
             bf[b].hi = *reinterpret_cast<const v4i *>(bt + b_hi[u][b]);
         }
     };
-    auto compute = [&](const int u, const v8i (&bf)[TB]) {
+    // A wavefront issues at most one instruction every few cycles, so LDS reads, DMA issue and
+    // address arithmetic placed between matrix instructions cost nothing while the matrix pipe is
+    // busy, and a block of them placed after the matrix instructions leaves the pipe idle.  The
+    // source order below is the intended issue order; a scheduling barrier after every matrix
+    // instruction keeps the compiler from regrouping it.
+    auto token_read = [&](int kc, const int u, const int b, v8i &bf) {
+        const int8_t *bt = lds + (kc % STAGES) * STAGE_BYTES;
+        bf.lo = *reinterpret_cast<const v4i *>(bt + b_lo[u][b]);
+        bf.hi = *reinterpret_cast<const v4i *>(bt + b_hi[u][b]);
+    };
+    auto mma_row = [&](const int u, const int a, const v8i (&bf)[TB], auto &&between) {
+        const int iv = (int)(u ? icur[a].y : icur[a].x);
+        const v4i av = expand_codes9(u ? ccur[a].y : ccur[a].x, ones);
 #pragma unroll
-        for (int a = 0; a < RA; ++a) {
-            const int iv = (int)(u ? icur[a].y : icur[a].x);
-            const v4i av = expand_codes9(u ? ccur[a].y : ccur[a].x, ones);
-#pragma unroll
-            for (int b = 0; b < TB; ++b)
-                acc[a][b] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(av, bf[b], acc[a][b], iv, 0, 0);
+        for (int b = 0; b < TB; ++b) {
+            acc[a][b] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(av, bf[b], acc[a][b], iv, 0, 0);
+            between(b);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
@@ -348,11 +390,11 @@ __global__ void __launch_bounds__(256, 2) gemm_smfmac_kernel(GemmArgs g)
     read_weights(0, 0, icur, ccur);
     read_tokens(0, 0, bq[0]);
     auto iteration = [&](int kc, const int h) {   // h = kc & 1
-        read_tokens(kc, 1, bq[1]);
-        __builtin_amdgcn_sched_barrier(0);   // keep the reads ahead of the matrix work they overlap with
-        compute(0, bq[0]);
-        __builtin_amdgcn_sched_barrier(0);
-        if (kc + 1 < nchunks) {
+        const bool more = kc + 1 < nchunks;
+        // sub-step 0: tokens of (kc, 1) are fetched under the first four matrix instructions
+        mma_row(0, 0, bq[0], [&](const int b) { token_read(kc, 1, b, bq[1][b]); });
+        mma_row(0, 1, bq[0], [&](const int) {});
+        if (more) {
             // still allowed in flight: what the previous middle issued
             const bool t_fly = kc >= 1 && kc + 2 < nchunks;               // token stage kc+2, issued at the previous middle
             const bool w_fly = h == 0 && kc >= 2 && kc / 2 + 1 < npairs;   // and the weight pair issued after it
@@ -360,14 +402,22 @@ __global__ void __launch_bounds__(256, 2) gemm_smfmac_kernel(GemmArgs g)
             else if (t_fly) SBN_WAIT_VMCNT(NDT);
             else SBN_WAIT_VMCNT(0);
             __syncthreads();
-            if (kc + 3 < nchunks) dma_tokens(kc + 3);
-            if (h == 1 && (kc + 1) / 2 + 1 < npairs) dma_weights((kc + 1) / 2 + 1);
             read_weights(kc + 1, h ^ 1, inext, cnext);
-            read_tokens(kc + 1, 0, bq[0]);
         }
         __builtin_amdgcn_sched_barrier(0);
-        compute(1, bq[1]);
-        __builtin_amdgcn_sched_barrier(0);
+        // sub-step 1: under its matrix instructions go the DMA of token stage kc+3 (one instruction
+        // per matrix instruction), the weight pair (odd kc) and the tokens of (kc+1, 0)
+        const bool dma_t = more && kc + 3 < nchunks;
+        const bool dma_w = more && h == 1 && (kc + 1) / 2 + 1 < npairs;
+        const int8_t *tsrc = xbase + (int64_t)(kc + 3) * KSTEP;
+        const uint32_t tdst = lds0 + ((kc + 3) % STAGES) * STAGE_BYTES + wave * (NDT * 1024);
+        mma_row(1, 0, bq[1], [&](const int b) {
+            if (dma_t) lds_dma16(tsrc, xoff[b], tdst + b * 1024);
+        });
+        if (dma_w) dma_weights((kc + 1) / 2 + 1);
+        mma_row(1, 1, bq[1], [&](const int b) {
+            if (more) token_read(kc + 1, 0, b, bq[0][b]);
+        });
 #pragma unroll
         for (int a = 0; a < RA; ++a) { icur[a] = inext[a]; ccur[a] = cnext[a]; }
     };
@@ -378,7 +428,7 @@ __global__ void __launch_bounds__(256, 2) gemm_smfmac_kernel(GemmArgs g)
     }
     if (kc < nchunks) iteration(kc, 0);
 
-    block_epilogue<RA, TB>(g, acc, lds, o0, o0 + wave * (32 * RA), t0, wave, lane);
+    block_epilogue<RA, TB>(g, acc, scales, lds, o0, o0 + wave * (32 * RA), t0, wave, lane);
 }
 
 // ---- dense comparison path ---------------------------------------------------------------------
@@ -418,7 +468,7 @@ __global__ void __launch_bounds__(256, 2) gemm_dense_kernel(GemmArgs g)
     __shared__ __attribute__((aligned(1024))) int8_t lds[STAGES * DSTAGE];
     const uint32_t lds0 = lds_address(lds);
     int to, tt;
-    tile_of_block(g, to, tt);
+    tile_of_block(g, blockIdx.x, to, tt);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wo = wave & 1, wt = wave >> 1;
@@ -497,7 +547,9 @@ __global__ void __launch_bounds__(256, 2) gemm_dense_kernel(GemmArgs g)
                     acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[u][a], bf[u][b], acc[a][b], 0, 0, 0);
     }
 
-    block_epilogue<4, 2>(g, acc, lds, o0, o0 + wo * 128, t0 + wt * 64, wave, lane);
+    float scales[2];
+    load_scales<2>(g, t0 + wt * 64, lane, scales);
+    block_epilogue<4, 2>(g, acc, scales, lds, o0, o0 + wo * 128, t0 + wt * 64, wave, lane);
 }
 
 GemmArgs make_args(const LinearItem &it, int block_tokens = BT)
@@ -513,11 +565,23 @@ GemmArgs make_args(const LinearItem &it, int block_tokens = BT)
 
 }  // namespace
 
-sbn_status launch_gemm_smfmac(const LinearItem &it, hipStream_t stream)
+sbn_status launch_gemm_smfmac(int count, const LinearItem *items, hipStream_t stream)
 {
-    GemmArgs g = make_args(it);
-    hipLaunchKernelGGL(gemm_smfmac_kernel, dim3(g.tiles_o * g.tiles_t), dim3(256), 0, stream, g);
-    return check_launch("gemm_smfmac_kernel");
+    for (int first = 0; first < count; first += GEMM_GROUP_MAX) {
+        GemmGroup grp;
+        grp.count = count - first < GEMM_GROUP_MAX ? count - first : GEMM_GROUP_MAX;
+        int blocks = 0;
+        for (int i = 0; i < grp.count; ++i) {
+            grp.g[i] = make_args(items[first + i]);
+            grp.block0[i] = blocks;
+            blocks += (grp.g[i].tiles_o * grp.g[i].tiles_t + 7) & ~7;
+        }
+        grp.block0[grp.count] = blocks;
+        hipLaunchKernelGGL(gemm_smfmac_kernel, dim3(blocks), dim3(256), 0, stream, grp);
+        sbn_status st = check_launch("gemm_smfmac_kernel");
+        if (st != SBN_OK) return st;
+    }
+    return SBN_OK;
 }
 
 sbn_status launch_gemm_dense(const LinearItem &it, int8_t *w_dense, hipStream_t stream)

@@ -73,7 +73,7 @@ size_t linear_workspace_bytes(int64_t tokens, int64_t d_out, int64_t d_in);
 sbn_status launch_act_quant(const void *X, int64_t tokens, int64_t d_in, int8_t *xq, float *sx,
                             hipStream_t stream);
 sbn_status launch_gemv(int count, const LinearItem *items, hipStream_t stream);
-sbn_status launch_gemm_smfmac(const LinearItem &it, hipStream_t stream);
+sbn_status launch_gemm_smfmac(int count, const LinearItem *items, hipStream_t stream);
 sbn_status launch_gemm_dense(const LinearItem &it, int8_t *w_dense, hipStream_t stream);
 sbn_status launch_linear_generic(const LinearItem &it, const Pattern &pat, hipStream_t stream);
 

@@ -157,6 +157,28 @@ def test_grouped_streaming_gemv_against_oracle(tokens):
         assert_rel(Y_list[i].cpu().numpy(), ref[sh], Y_TOL, f"Y of problem {i}")
 
 
+def test_grouped_sparse_gemm_against_oracle():
+    # prefill-sized grouped call: all problems take the sparse-MFMA path, their tiles share one launch
+    # (ragged token and row counts, two problems sharing one input, more problems than one launch holds)
+    s = sbn()
+    shapes = [(300, 384), (512, 384), (130, 128), (700, 256), (256, 256), (64, 128), (257, 384), (96, 256), (160, 128), (40, 384)]
+    tokens = {384: 200, 128: 33, 256: 130}
+    Ws = [sbn_synth.latent_weight(a, b, 900 + i) for i, (a, b) in enumerate(shapes)]
+    packs = [hip_pack(W, 2, 4) for W in Ws]
+    Xs = {k: sbn_synth.activations(t, k, 950 + k) for k, t in tokens.items()}
+    Xd = {k: x.to(DEV) for k, x in Xs.items()}
+    Y_list = [torch.full((tokens[b], a), float("nan"), dtype=torch.float32, device=DEV) for a, b in shapes]
+    need = sum(s.sbn_workspace_bytes(s.SBN_OP_LINEAR, tokens[b], a, b, 2, 4) for a, b in shapes)
+    ws = s.new_workspace(need)
+    s.sbn_sparse_ternary_linear_grouped([Xd[b] for _, b in shapes], [p for p, _ in packs], [g for _, g in packs],
+                                        Y_list, 2, 4, ws, path=s.SBN_PATH_SMFMAC)
+    torch.cuda.synchronize()
+    for i, ((a, b), W) in enumerate(zip(shapes, Ws)):
+        _, g, Weff, _ = oracle_pack(W, 2, 4)
+        y, *_ = oracle.sparse_ternary_linear(Xs[b].float().numpy(), Weff, g)
+        assert_rel(Y_list[i].cpu().numpy(), y, Y_TOL, f"Y of problem {i}")
+
+
 @pytest.mark.parametrize("tokens", [1, 5, 64, 65, 300])
 @pytest.mark.parametrize("d_in", [8, 256, 2560, 6912, 8200, 16520])
 def test_act_quant_entry_all_kernel_variants(tokens, d_in):
