@@ -262,9 +262,9 @@ __global__ void __launch_bounds__(256, 2) gemm_smfmac_kernel(GemmGroup grp)
         const int t = t0 + row < g.tokens ? row : g.tokens - 1 - t0;
         xoff[i] = (uint32_t)t * (uint32_t)K + 16u * ((lane & 7) ^ ((row >> 1) & 7));
     }
-    auto dma_tokens = [&](int kc) {
+    auto dma_tokens = [&](int kc, int stage) {
         const int8_t *src = xbase + (int64_t)kc * KSTEP;
-        const uint32_t dst = lds0 + (kc % STAGES) * STAGE_BYTES + wave * (NDT * 1024);
+        const uint32_t dst = lds0 + stage * STAGE_BYTES + wave * (NDT * 1024);
 #pragma unroll
         for (int i = 0; i < NDT; ++i) lds_dma16(src, xoff[i], dst + i * 1024);
     };
@@ -281,9 +281,9 @@ __global__ void __launch_bounds__(256, 2) gemm_smfmac_kernel(GemmGroup grp)
         woff[i] = (uint32_t)o * (uint32_t)(nchunks * 32) + 16u * gran;
         wclip[i] = odd_tail && gran >= 2;
     }
-    auto dma_weights = [&](int pair) {
+    auto dma_weights = [&](int pair, int slot) {
         const uint8_t *src = wbase + (int64_t)pair * 64;
-        const uint32_t dst = wlds0 + (pair & 1) * WSLOT_BYTES + wave * (NDW * 1024);
+        const uint32_t dst = wlds0 + slot * WSLOT_BYTES + wave * (NDW * 1024);
         const bool last = pair == npairs - 1;
 #pragma unroll
         for (int i = 0; i < NDW; ++i) {
@@ -292,28 +292,32 @@ __global__ void __launch_bounds__(256, 2) gemm_smfmac_kernel(GemmGroup grp)
             lds_dma16(src, off, dst + i * 1024);
         }
     };
-    // LDS read offsets, swizzles folded in.  tokens: row * 128 + 16 * (chunk16 ^ ((row >> 1) & 7));
-    // weights: row * 64 + 16 * (granule ^ ((row >> 2) & 3)) + 8c
-    int b_lo[2][TB], b_hi[2][TB];   // [sub-step][token tile]
-#pragma unroll
-    for (int b = 0; b < TB; ++b) {
-        const int row = 32 * b + r, sw = (row >> 1) & 7;
+    // LDS read addresses, swizzles folded in.  tokens: row * 128 + 16 * (chunk16 ^ ((row >> 1) & 7));
+    // the row's swizzle does not depend on the token tile (32 b), so tile and ring stage are immediate
+    // offsets of four lane addresses.  weights: row * 64 + 16 * (granule ^ ((row >> 2) & 3)) + 8c,
+    // eight lane addresses that are moved to the other slot once per pair.
+    uint32_t b_lo[2], b_hi[2];   // [sub-step]
+    {
+        const int sw = (r >> 1) & 7;
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-            b_lo[u][b] = row * KSTEP + 16 * ((2 * u + c) ^ sw);
-            b_hi[u][b] = row * KSTEP + 16 * ((4 + 2 * u + c) ^ sw);
+            b_lo[u] = lds0 + r * KSTEP + 16 * ((2 * u + c) ^ sw);
+            b_hi[u] = lds0 + r * KSTEP + 16 * ((4 + 2 * u + c) ^ sw);
         }
     }
-    int a_idx[2][RA], a_code[2][RA];   // [chunk of the pair][row tile]
+    uint32_t a_idx[2][RA], a_code[2][RA];   // [chunk of the pair][row tile], in the slot of the pair being read
 #pragma unroll
     for (int a = 0; a < RA; ++a) {
         const int row = wave * (32 * RA) + 32 * a + r, sw = (row >> 2) & 3;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            a_idx[h][a] = row * 64 + 8 * c + 16 * ((2 * h) ^ sw);
-            a_code[h][a] = row * 64 + 8 * c + 16 * ((2 * h + 1) ^ sw);
+            a_idx[h][a] = wlds0 + row * 64 + 8 * c + 16 * ((2 * h) ^ sw);
+            a_code[h][a] = wlds0 + row * 64 + 8 * c + 16 * ((2 * h + 1) ^ sw);
         }
     }
+    typedef __attribute__((address_space(3))) const v4i *lds_v4i;
+    typedef unsigned v2u __attribute__((ext_vector_type(2)));
+    typedef __attribute__((address_space(3))) const v2u *lds_u2;
     uint32_t ones;
     asm volatile("v_mov_b32 %0, 0x01010101" : "=v"(ones));   // kept in a vector register for v_and_or_b32
 
@@ -326,53 +330,42 @@ __global__ void __launch_bounds__(256, 2) gemm_smfmac_kernel(GemmGroup grp)
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0;
 
     // Software pipeline, one barrier per iteration placed between its two sub-steps:
-    //   sub-step 0 of iteration kc   issue the LDS reads of the tokens of (kc, 1), compute (kc, 0);
+    //   sub-step 0 of iteration kc   compute (kc, 0); the LDS reads of the tokens of (kc, 1) go out
+    //                                under its first matrix instructions;
     //   middle                       wait for token stage kc+1 (and, for odd kc, the weight pair of
     //                                kc+1), barrier.  Every wavefront now holds all of stage kc in
-    //                                registers, so the DMA of token stage kc+3 goes into its slot
-    //                                and, for odd kc, weight pair (kc+1)/2 + 1 into the slot of
-    //                                pair (kc-1)/2;
-    //   sub-step 1                   issue the LDS reads of the weights and tokens of (kc+1, 0),
-    //                                compute (kc, 1).
-    // So every matrix instruction works on registers loaded half an iteration earlier, and a DMA has
-    // two iterations to land.  DMA issue order at a middle: tokens, then weights; the wait counts
-    // below rely on vector-memory operations of a wavefront completing in issue order.
-    dma_weights(0);
-    dma_tokens(0);
-    if (npairs > 1) dma_weights(1);
-    if (nchunks > 1) dma_tokens(1);
-    if (nchunks > 2) dma_tokens(2);
+    //                                registers, so its slot can take token stage kc+3 and, for odd
+    //                                kc, the slot of pair (kc-1)/2 can take pair (kc+1)/2 + 1;
+    //   sub-step 1                   compute (kc, 1); under its matrix instructions go those DMA
+    //                                instructions and the LDS reads of the weights and tokens of (kc+1, 0).
+    // A wavefront issues at most one instruction every few cycles, so what is placed between matrix
+    // instructions is free while the matrix pipe is busy, and a block of other instructions after
+    // them leaves the pipe idle: the source order is the intended issue order and a scheduling
+    // barrier after every matrix instruction keeps it.  The DMA is unconditional (past the end it
+    // fetches the last chunk again into a slot nobody reads), so the loop body has no branches and
+    // the wait counts are the same every iteration; they rely on vector-memory operations of a
+    // wavefront completing in issue order (tokens are issued before weights).
+    dma_weights(0, 0);
+    dma_tokens(0, 0);
+    dma_weights(npairs > 1 ? 1 : 0, 1);
+    dma_tokens(nchunks > 1 ? 1 : 0, 1);
+    dma_tokens(nchunks > 2 ? 2 : nchunks - 1, 2);
 
     float scales[TB];
     load_scales<TB>(g, t0, lane, scales);
 
-    uint2 icur[RA], ccur[RA], inext[RA], cnext[RA];
+    v2u icur[RA], ccur[RA], inext[RA], cnext[RA];
     v8i bq[2][TB];
-    auto read_weights = [&](int kc, const int h, uint2 (&iv)[RA], uint2 (&cv)[RA]) {   // h = kc & 1
-        const int8_t *wt_ = wlds + ((kc >> 1) & 1) * WSLOT_BYTES;
+    auto read_weights = [&](const int h, v2u (&iv)[RA], v2u (&cv)[RA]) {
 #pragma unroll
         for (int a = 0; a < RA; ++a) {
-            iv[a] = *reinterpret_cast<const uint2 *>(wt_ + a_idx[h][a]);
-            cv[a] = *reinterpret_cast<const uint2 *>(wt_ + a_code[h][a]);
+            iv[a] = *(lds_u2)(uintptr_t)a_idx[h][a];
+            cv[a] = *(lds_u2)(uintptr_t)a_code[h][a];
         }
     };
-    auto read_tokens = [&](int kc, const int u, v8i (&bf)[TB]) {
-        const int8_t *bt = lds + (kc % STAGES) * STAGE_BYTES;
-#pragma unroll
-        for (int b = 0; b < TB; ++b) {
-            bf[b].lo = *reinterpret_cast<const v4i *>(bt + b_lo[u][b]);
-            bf[b].hi = *reinterpret_cast<const v4i *>(bt + b_hi[u][b]);
-        }
-    };
-    // A wavefront issues at most one instruction every few cycles, so LDS reads, DMA issue and
-    // address arithmetic placed between matrix instructions cost nothing while the matrix pipe is
-    // busy, and a block of them placed after the matrix instructions leaves the pipe idle.  The
-    // source order below is the intended issue order; a scheduling barrier after every matrix
-    // instruction keeps the compiler from regrouping it.
-    auto token_read = [&](int kc, const int u, const int b, v8i &bf) {
-        const int8_t *bt = lds + (kc % STAGES) * STAGE_BYTES;
-        bf.lo = *reinterpret_cast<const v4i *>(bt + b_lo[u][b]);
-        bf.hi = *reinterpret_cast<const v4i *>(bt + b_hi[u][b]);
+    auto token_read = [&](const int stage, const int u, const int b, v8i &bf) {
+        bf.lo = *(lds_v4i)(uintptr_t)(b_lo[u] + stage * STAGE_BYTES + 32 * b * KSTEP);
+        bf.hi = *(lds_v4i)(uintptr_t)(b_hi[u] + stage * STAGE_BYTES + 32 * b * KSTEP);
     };
     auto mma_row = [&](const int u, const int a, const v8i (&bf)[TB], auto &&between) {
         const int iv = (int)(u ? icur[a].y : icur[a].x);
@@ -387,46 +380,66 @@ __global__ void __launch_bounds__(256, 2) gemm_smfmac_kernel(GemmGroup grp)
 
     SBN_WAIT_VMCNT(0);
     __syncthreads();
-    read_weights(0, 0, icur, ccur);
-    read_tokens(0, 0, bq[0]);
-    auto iteration = [&](int kc, const int h) {   // h = kc & 1
-        const bool more = kc + 1 < nchunks;
-        // sub-step 0: tokens of (kc, 1) are fetched under the first four matrix instructions
-        mma_row(0, 0, bq[0], [&](const int b) { token_read(kc, 1, b, bq[1][b]); });
+    read_weights(0, icur, ccur);
+#pragma unroll
+    for (int b = 0; b < TB; ++b) token_read(0, 0, b, bq[0][b]);
+    // one iteration that has a successor; stage = kc % 3 and h = kc & 1 are literals at every call
+    auto iteration = [&](const int kc, const int stage, const int h) {
+        mma_row(0, 0, bq[0], [&](const int b) { token_read(stage, 1, b, bq[1][b]); });
         mma_row(0, 1, bq[0], [&](const int) {});
-        if (more) {
-            // still allowed in flight: what the previous middle issued
-            const bool t_fly = kc >= 1 && kc + 2 < nchunks;               // token stage kc+2, issued at the previous middle
-            const bool w_fly = h == 0 && kc >= 2 && kc / 2 + 1 < npairs;   // and the weight pair issued after it
-            if (t_fly && w_fly) SBN_WAIT_VMCNT(NDT + NDW);
-            else if (t_fly) SBN_WAIT_VMCNT(NDT);
-            else SBN_WAIT_VMCNT(0);
-            __syncthreads();
-            read_weights(kc + 1, h ^ 1, inext, cnext);
+        if (h == 0) SBN_WAIT_VMCNT(NDT + NDW); else SBN_WAIT_VMCNT(NDT);   // what the previous iteration issued may still fly
+        __syncthreads();
+        if (h == 1) {   // the reads below start a new pair: move the lane addresses to its slot
+            const uint32_t delta = (((kc + 1) >> 1) & 1) ? (uint32_t)WSLOT_BYTES : (uint32_t)-WSLOT_BYTES;
+#pragma unroll
+            for (int a = 0; a < RA; ++a) {
+                a_idx[0][a] += delta; a_idx[1][a] += delta; a_code[0][a] += delta; a_code[1][a] += delta;
+            }
         }
+        read_weights(h ^ 1, inext, cnext);
         __builtin_amdgcn_sched_barrier(0);
-        // sub-step 1: under its matrix instructions go the DMA of token stage kc+3 (one instruction
-        // per matrix instruction), the weight pair (odd kc) and the tokens of (kc+1, 0)
-        const bool dma_t = more && kc + 3 < nchunks;
-        const bool dma_w = more && h == 1 && (kc + 1) / 2 + 1 < npairs;
-        const int8_t *tsrc = xbase + (int64_t)(kc + 3) * KSTEP;
-        const uint32_t tdst = lds0 + ((kc + 3) % STAGES) * STAGE_BYTES + wave * (NDT * 1024);
-        mma_row(1, 0, bq[1], [&](const int b) {
-            if (dma_t) lds_dma16(tsrc, xoff[b], tdst + b * 1024);
-        });
-        if (dma_w) dma_weights((kc + 1) / 2 + 1);
-        mma_row(1, 1, bq[1], [&](const int b) {
-            if (more) token_read(kc + 1, 0, b, bq[0][b]);
-        });
+        const int kt = kc + 3 < nchunks ? kc + 3 : nchunks - 1;
+        const int8_t *tsrc = xbase + (int64_t)kt * KSTEP;
+        const uint32_t tdst = lds0 + stage * STAGE_BYTES + wave * (NDT * 1024);
+        mma_row(1, 0, bq[1], [&](const int b) { lds_dma16(tsrc, xoff[b], tdst + b * 1024); });
+        if (h == 1) {
+            const int pw = (kc + 1) / 2 + 1;
+            dma_weights(pw < npairs ? pw : npairs - 1, pw & 1);
+        }
+        mma_row(1, 1, bq[1], [&](const int b) { token_read(stage == 2 ? 0 : stage + 1, 0, b, bq[0][b]); });
 #pragma unroll
         for (int a = 0; a < RA; ++a) { icur[a] = inext[a]; ccur[a] = cnext[a]; }
     };
+    const int nsteady = nchunks - 1;   // iterations with a successor
     int kc = 0;
-    for (; kc + 1 < nchunks; kc += 2) {
-        iteration(kc, 0);
-        iteration(kc + 1, 1);
+    for (; kc + 6 <= nsteady; kc += 6) {
+        iteration(kc, 0, 0);
+        iteration(kc + 1, 1, 1);
+        iteration(kc + 2, 2, 0);
+        iteration(kc + 3, 0, 1);
+        iteration(kc + 4, 1, 0);
+        iteration(kc + 5, 2, 1);
     }
-    if (kc < nchunks) iteration(kc, 0);
+    // up to five more, selected so that stage and h stay literals (kc is a multiple of 6 here)
+    if (kc < nsteady) { iteration(kc, 0, 0); ++kc; }
+    if (kc < nsteady) { iteration(kc, 1, 1); ++kc; }
+    if (kc < nsteady) { iteration(kc, 2, 0); ++kc; }
+    if (kc < nsteady) { iteration(kc, 0, 1); ++kc; }
+    if (kc < nsteady) { iteration(kc, 1, 0); ++kc; }
+    // last chunk: nothing left to fetch
+    {
+        const int stage = kc % STAGES;
+#pragma unroll
+        for (int b = 0; b < TB; ++b) {
+            bq[1][b].lo = *(lds_v4i)(uintptr_t)(b_lo[1] + stage * STAGE_BYTES + 32 * b * KSTEP);
+            bq[1][b].hi = *(lds_v4i)(uintptr_t)(b_hi[1] + stage * STAGE_BYTES + 32 * b * KSTEP);
+        }
+        mma_row(0, 0, bq[0], [&](const int) {});
+        mma_row(0, 1, bq[0], [&](const int) {});
+        mma_row(1, 0, bq[1], [&](const int) {});
+        mma_row(1, 1, bq[1], [&](const int) {});
+    }
+    SBN_WAIT_VMCNT(0);   // surplus DMA of the last iterations must not land in the epilogue's staging area
 
     block_epilogue<RA, TB>(g, acc, scales, lds, o0, o0 + wave * (32 * RA), t0, wave, lane);
 }
