@@ -104,7 +104,7 @@ __device__ __forceinline__ void store_tile(const GemmArgs &g, const v16i &acc, i
 // int32 accumulator output take the plain per-lane stores.
 //   orow = first output row of the wavefront, tok0 = its first token
 template <int RA, int TB>
-__device__ __forceinline__ void block_epilogue(const GemmArgs &g, v16i (&acc)[RA][TB], const float (&scales)[TB],
+__device__ __forceinline__ void block_epilogue(const GemmArgs &g, v16i (&acc)[RA][TB], const float (&sxv)[TB + 1],
                                                int8_t *lds, int o0, int orow, int tok0, int wave, int lane)
 {
     const int r = lane & 31, c = lane >> 5;
@@ -119,7 +119,7 @@ __device__ __forceinline__ void block_epilogue(const GemmArgs &g, v16i (&acc)[RA
         if (g.bias) bias4 = *reinterpret_cast<const float4 *>(g.bias + orow + 4 * (lane % LPR));
 #pragma unroll
         for (int b = 0; b < TB; ++b) {
-            const float scale = scales[b];
+            const float scale = __fdiv_rn(sxv[TB], sxv[b]);
 #pragma unroll
             for (int a = 0; a < RA; ++a)
 #pragma unroll
@@ -151,20 +151,21 @@ __device__ __forceinline__ void block_epilogue(const GemmArgs &g, v16i (&acc)[RA
     for (int b = 0; b < TB; ++b) {
         const int t = tok0 + 32 * b + r;
 #pragma unroll
-        for (int a = 0; a < RA; ++a) store_tile(g, acc[a][b], orow + 32 * a + 4 * c, t, scales[b]);
+        for (int a = 0; a < RA; ++a) store_tile(g, acc[a][b], orow + 32 * a + 4 * c, t, __fdiv_rn(sxv[TB], sxv[b]));
     }
 }
 
-// gamma / s_x[t] of the TB tokens a lane holds (token tile b: tok0 + 32 b + lane % 32); loaded ahead of
-// the main loop so that the epilogue does not start with a chain of dependent global loads
+// gamma and s_x[t] of the TB tokens a lane holds (token tile b: tok0 + 32 b + lane % 32), fetched
+// before the first DMA so that they are long there when the epilogue divides them (a chain of
+// dependent global loads at the start of the epilogue otherwise); absent tokens read the last token
 template <int TB>
-__device__ __forceinline__ void load_scales(const GemmArgs &g, int tok0, int lane, float (&scales)[TB])
+__device__ __forceinline__ void load_scales(const GemmArgs &g, int tok0, int lane, float (&sxv)[TB + 1])
 {
-    const float gam = *g.gamma;
+    sxv[TB] = *g.gamma;
 #pragma unroll
     for (int b = 0; b < TB; ++b) {
         const int t = tok0 + 32 * b + (lane & 31);
-        scales[b] = t < g.tokens ? __fdiv_rn(gam, g.sx[t]) : 0.0f;
+        sxv[b] = g.sx[t < g.tokens ? t : g.tokens - 1];
     }
 }
 
@@ -345,14 +346,15 @@ __global__ void __launch_bounds__(256, 2) gemm_smfmac_kernel(GemmGroup grp)
     // fetches the last chunk again into a slot nobody reads), so the loop body has no branches and
     // the wait counts are the same every iteration; they rely on vector-memory operations of a
     // wavefront completing in issue order (tokens are issued before weights).
+    float sxv[TB + 1];
+    load_scales<TB>(g, t0, lane, sxv);
+    // prologue in an order that leaves the ring in the state the loop's wait counts assume: behind
+    // token stage 1 only token stage 2 and weight pair 1 are younger
     dma_weights(0, 0);
     dma_tokens(0, 0);
-    dma_weights(npairs > 1 ? 1 : 0, 1);
     dma_tokens(nchunks > 1 ? 1 : 0, 1);
     dma_tokens(nchunks > 2 ? 2 : nchunks - 1, 2);
-
-    float scales[TB];
-    load_scales<TB>(g, t0, lane, scales);
+    dma_weights(npairs > 1 ? 1 : 0, 1);
 
     v2u icur[RA], ccur[RA], inext[RA], cnext[RA];
     v8i bq[2][TB];
@@ -378,7 +380,7 @@ __global__ void __launch_bounds__(256, 2) gemm_smfmac_kernel(GemmGroup grp)
         }
     };
 
-    SBN_WAIT_VMCNT(0);
+    SBN_WAIT_VMCNT(NDW + 2 * NDT);   // weight pair 0 and token stage 0 are in; the three younger groups may fly
     __syncthreads();
     read_weights(0, icur, ccur);
 #pragma unroll
@@ -441,7 +443,7 @@ __global__ void __launch_bounds__(256, 2) gemm_smfmac_kernel(GemmGroup grp)
     }
     SBN_WAIT_VMCNT(0);   // surplus DMA of the last iterations must not land in the epilogue's staging area
 
-    block_epilogue<RA, TB>(g, acc, scales, lds, o0, o0 + wave * (32 * RA), t0, wave, lane);
+    block_epilogue<RA, TB>(g, acc, sxv, lds, o0, o0 + wave * (32 * RA), t0, wave, lane);
 }
 
 // ---- dense comparison path ---------------------------------------------------------------------
@@ -560,9 +562,9 @@ __global__ void __launch_bounds__(256, 2) gemm_dense_kernel(GemmArgs g)
                     acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[u][a], bf[u][b], acc[a][b], 0, 0, 0);
     }
 
-    float scales[2];
-    load_scales<2>(g, t0 + wt * 64, lane, scales);
-    block_epilogue<4, 2>(g, acc, scales, lds, o0, o0 + wo * 128, t0 + wt * 64, wave, lane);
+    float sxv[3];
+    load_scales<2>(g, t0 + wt * 64, lane, sxv);
+    block_epilogue<4, 2>(g, acc, sxv, lds, o0, o0 + wo * 128, t0 + wt * 64, wave, lane);
 }
 
 GemmArgs make_args(const LinearItem &it, int block_tokens = BT)
