@@ -506,28 +506,15 @@ __global__ void __launch_bounds__(256, 2) gemm_dense_kernel(GemmArgs g)
         const int t = t0 + row < g.tokens ? row : g.tokens - 1 - t0;
         xoff[i] = (uint32_t)t * (uint32_t)K + 16u * ((lane & 3) ^ ((row >> 2) & 3));
     }
-    auto dma = [&](int kt) {
-        const uint32_t dst = lds0 + (kt % STAGES) * DSTAGE;
-        const int8_t *ws = wbase + (int64_t)kt * DK, *xs = xbase + (int64_t)kt * DK;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) lds_dma16(ws, woff[i], dst + (4 * wave + i) * 1024);
-#pragma unroll
-        for (int i = 0; i < 2; ++i) lds_dma16(xs, xoff[i], dst + BO * DK + (2 * wave + i) * 1024);
-    };
-    // lane (r, c) supplies k = 32u + 16c + 0..15 of the stage = granule 2u + c, for both operands
-    int aoff[2][4], boff[2][2];
+    // lane (r, c) supplies k = 32u + 16c + 0..15 of the stage = granule 2u + c, for both operands;
+    // row tile and ring stage are immediate offsets of the lane addresses below
+    typedef __attribute__((address_space(3))) const v4i *lds_v4i;
+    uint32_t aaddr[2], baddr[2];
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
-#pragma unroll
-        for (int a = 0; a < 4; ++a) {
-            const int row = wo * 128 + 32 * a + r;
-            aoff[u][a] = row * DK + 16 * ((2 * u + c) ^ ((row >> 2) & 3));
-        }
-#pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            const int row = wt * 64 + 32 * b + r;
-            boff[u][b] = BO * DK + row * DK + 16 * ((2 * u + c) ^ ((row >> 2) & 3));
-        }
+        const int sw = (r >> 2) & 3;   // (row >> 2) & 3 with row = 32 a + r + a multiple of 64
+        aaddr[u] = lds0 + (wo * 128 + r) * DK + 16 * ((2 * u + c) ^ sw);
+        baddr[u] = lds0 + BO * DK + (wt * 64 + r) * DK + 16 * ((2 * u + c) ^ sw);
     }
 
     v16i acc[4][2];
@@ -538,32 +525,82 @@ __global__ void __launch_bounds__(256, 2) gemm_dense_kernel(GemmArgs g)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0;
 
-    dma(0);
-    if (nk > 1) dma(1);
-    for (int kt = 0; kt < nk; ++kt) {
-        if (kt + 1 < nk) SBN_WAIT_VMCNT(6); else SBN_WAIT_VMCNT(0);   // stage kt landed; stage kt+1 (6 loads) may be in flight
-        __syncthreads();
-        if (kt + 2 < nk) dma(kt + 2);
-        const int8_t *st = lds + (kt % STAGES) * DSTAGE;
-        v4i af[2][4], bf[2][2];
+    float sxv[3];
+    load_scales<2>(g, t0 + wt * 64, lane, sxv);
+    // Same software pipeline as the sparse kernel: ring of 3 stages, one barrier per iteration
+    // between its two sub-steps, the DMA of stage kt+3 and the LDS reads of the next sub-step issued
+    // between the matrix instructions, unconditional clamped DMA, stage as a literal.
+    auto dma_one = [&](int kt, int stage, const int i) {   // i = 0..5: four weight and two token instructions
+        const uint32_t dst = lds0 + stage * DSTAGE;
+        if (i < 4) lds_dma16(wbase + (int64_t)kt * DK, woff[i], dst + (4 * wave + i) * 1024);
+        else lds_dma16(xbase + (int64_t)kt * DK, xoff[i - 4], dst + BO * DK + (2 * wave + i - 4) * 1024);
+    };
+    auto dma = [&](int kt, int stage) {
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
+        for (int i = 0; i < 6; ++i) dma_one(kt, stage, i);
+    };
+    v4i af[2][4], bf[2][2];
+    auto read_a = [&](const int stage, const int u, const int a) {
+        af[u][a] = *(lds_v4i)(uintptr_t)(aaddr[u] + stage * DSTAGE + 32 * a * DK);
+    };
+    auto read_b = [&](const int stage, const int u, const int b) {
+        bf[u][b] = *(lds_v4i)(uintptr_t)(baddr[u] + stage * DSTAGE + 32 * b * DK);
+    };
+    auto mma = [&](const int u, const int a, const int b) {
+        acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[u][a], bf[u][b], acc[a][b], 0, 0, 0);
+    };
+    dma(0, 0);
+    dma(nk > 1 ? 1 : 0, 1);
+    dma(nk > 2 ? 2 : nk - 1, 2);
+    SBN_WAIT_VMCNT(12);   // stage 0 is in
+    __syncthreads();
 #pragma unroll
-            for (int a = 0; a < 4; ++a) af[u][a] = *reinterpret_cast<const v4i *>(st + aoff[u][a]);
+    for (int a = 0; a < 4; ++a) read_a(0, 0, a);
 #pragma unroll
-            for (int b = 0; b < 2; ++b) bf[u][b] = *reinterpret_cast<const v4i *>(st + boff[u][b]);
+    for (int b = 0; b < 2; ++b) read_b(0, 0, b);
+    auto iteration = [&](const int kt, const int stage) {   // stage = kt % 3 as a literal
+        // sub-step 0; the six reads of sub-step 1 go out under its first matrix instructions
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            mma(0, i >> 1, i & 1);
+            if (i < 4) read_a(stage, 1, i);
+            else if (i < 6) read_b(stage, 1, i - 4);
+            __builtin_amdgcn_sched_barrier(0);
         }
+        SBN_WAIT_VMCNT(6);   // stage kt+1 is in; stage kt+2 may fly
+        __syncthreads();
+        const int kf = kt + 3 < nk ? kt + 3 : nk - 1;
+        const int nstage = stage == 2 ? 0 : stage + 1;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            mma(1, i >> 1, i & 1);
+            if (i < 6) dma_one(kf, stage, i);
+            if (i >= 2 && i < 6) read_a(nstage, 0, i - 2);
+            else if (i >= 6) read_b(nstage, 0, i - 6);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    const int nsteady = nk - 1;
+    int kt = 0;
+    for (; kt + 3 <= nsteady; kt += 3) {
+        iteration(kt, 0);
+        iteration(kt + 1, 1);
+        iteration(kt + 2, 2);
+    }
+    if (kt < nsteady) { iteration(kt, 0); ++kt; }
+    if (kt < nsteady) { iteration(kt, 1); ++kt; }
+    {
+        const int stage = kt % STAGES;
+#pragma unroll
+        for (int a = 0; a < 4; ++a) af[1][a] = *(lds_v4i)(uintptr_t)(aaddr[1] + stage * DSTAGE + 32 * a * DK);
+#pragma unroll
+        for (int b = 0; b < 2; ++b) bf[1][b] = *(lds_v4i)(uintptr_t)(baddr[1] + stage * DSTAGE + 32 * b * DK);
 #pragma unroll
         for (int u = 0; u < 2; ++u)
 #pragma unroll
-            for (int a = 0; a < 4; ++a)
-#pragma unroll
-                for (int b = 0; b < 2; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[u][a], bf[u][b], acc[a][b], 0, 0, 0);
+            for (int i = 0; i < 8; ++i) mma(u, i >> 1, i & 1);
     }
-
-    float sxv[3];
-    load_scales<2>(g, t0 + wt * 64, lane, sxv);
+    SBN_WAIT_VMCNT(0);   // surplus DMA of the last iterations must not land in the epilogue's staging area
     block_epilogue<4, 2>(g, acc, sxv, lds, o0, o0 + wo * 128, t0 + wt * 64, wave, lane);
 }
 
