@@ -169,49 +169,6 @@ __device__ __forceinline__ void load_scales(const GemmArgs &g, int tok0, int lan
     }
 }
 
-// One LDS-DMA load: lane l of the wavefront fetches 16 bytes at base + voff and the hardware
-// deposits them at LDS byte address lds_addr + 16*l (M0 carries the LDS address).  Written as
-// inline assembly on purpose: after the compiler's own LDS-DMA builtin every later LDS read is
-// preceded by a wait for ALL outstanding vector-memory operations (it cannot tell which LDS bytes
-// a DMA writes), which serialises the prefetch ring with the loads it has just issued.  With the
-// load opaque to the compiler the kernels below count the outstanding DMA operations themselves
-// (SBN_WAIT_VMCNT) and order LDS reads against them with the block barrier.
-__device__ __forceinline__ void lds_dma16(const void *base, uint32_t voff, uint32_t lds_addr)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :
-                 : "s"(lds_addr), "v"(voff), "s"(base)
-                 : "memory", "m0");
-}
-
-__device__ __forceinline__ uint32_t lds_address(const void *p)
-{
-    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
-}
-
-// wait until at most n vector-memory operations of this wavefront are outstanding (gfx9 encoding:
-// vmcnt in bits [3:0] and [15:14]; expcnt and lgkmcnt fields left at "no wait")
-#define SBN_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xf) | (((n) >> 4) << 14) | 0x0f70)
-
-// 16 two-bit codes -> 16 int8 values with the odd registers' selector built by one v_and_or_b32
-// (mask in a scalar register, 0x01010101 in a vector register): 9 VALU operations.  VALU work does
-// not overlap matrix instructions on this part (measured: their times add), so every operation
-// saved here is matrix-pipe time gained.
-__device__ __forceinline__ v4i expand_codes9(uint32_t cw, uint32_t ones)
-{
-    const uint32_t lut = 0xff000100u;
-    const uint32_t t = cw >> 4;
-    uint32_t s1, s3;
-    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(s1) : "v"(cw), "s"(0x0c0c0c0cu), "v"(ones));
-    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(s3) : "v"(t), "s"(0x0c0c0c0cu), "v"(ones));
-    v4i a;
-    a[0] = (int)__builtin_amdgcn_perm(lut, lut, cw & 0x03030303u);
-    a[1] = (int)__builtin_amdgcn_perm(0x00000100u, 0u, s1);
-    a[2] = (int)__builtin_amdgcn_perm(lut, lut, t & 0x03030303u);
-    a[3] = (int)__builtin_amdgcn_perm(0x00000100u, 0u, s3);
-    return a;
-}
-
 // ---- sparse path --------------------------------------------------------------------------------
 // 4 wavefronts, one per 64 rows of the block; each owns 64 rows x 128 tokens = 2 x 4 tiles of 32x32,
 // so one code expansion (VALU) feeds four matrix instructions.
@@ -319,8 +276,7 @@ __global__ void __launch_bounds__(256, 2) gemm_smfmac_kernel(GemmGroup grp)
     typedef __attribute__((address_space(3))) const v4i *lds_v4i;
     typedef unsigned v2u __attribute__((ext_vector_type(2)));
     typedef __attribute__((address_space(3))) const v2u *lds_u2;
-    uint32_t ones;
-    asm volatile("v_mov_b32 %0, 0x01010101" : "=v"(ones));   // kept in a vector register for v_and_or_b32
+    const uint32_t ones = vgpr_ones();
 
     v16i acc[RA][TB];
 #pragma unroll
@@ -371,7 +327,7 @@ __global__ void __launch_bounds__(256, 2) gemm_smfmac_kernel(GemmGroup grp)
     };
     auto mma_row = [&](const int u, const int a, const v8i (&bf)[TB], auto &&between) {
         const int iv = (int)(u ? icur[a].y : icur[a].x);
-        const v4i av = expand_codes9(u ? ccur[a].y : ccur[a].x, ones);
+        const v4i av = expand_codes(u ? ccur[a].y : ccur[a].x, ones);
 #pragma unroll
         for (int b = 0; b < TB; ++b) {
             acc[a][b] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(av, bf[b], acc[a][b], iv, 0, 0);

@@ -162,6 +162,7 @@ __global__ void __launch_bounds__(1024) gemv_smfmac_kernel(GemvTable tab)
     if (row0 >= it.d_out) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
     const int r = lane & 15, c4 = lane >> 4;
+    const uint32_t ones = vgpr_ones();
     const int K = it.d_in, nchunks = K / CHUNK, nsuper = (nchunks + 3) / 4;
     int row = row0 + r;
     row = row < it.d_out ? row : it.d_out - 1;   // rows past the end are computed and dropped
@@ -189,7 +190,7 @@ __global__ void __launch_bounds__(1024) gemv_smfmac_kernel(GemvTable tab)
             if (tok_ok && k_lo < K) blo = *reinterpret_cast<const uint4 *>(xrow + k_lo);
             if (tok_ok && k_hi < K) bhi = *reinterpret_cast<const uint4 *>(xrow + k_hi);
             const v8i b = {(int)blo.x, (int)blo.y, (int)blo.z, (int)blo.w, (int)bhi.x, (int)bhi.y, (int)bhi.z, (int)bhi.w};
-            acc = __builtin_amdgcn_smfmac_i32_16x16x128_i8(expand_codes(codew[j]), b, acc, (int)idxw[j], 0, 0);
+            acc = __builtin_amdgcn_smfmac_i32_16x16x128_i8(expand_codes(codew[j], ones), b, acc, (int)idxw[j], 0, 0);
         }
     }
     red[wave][lane] = acc;
@@ -245,6 +246,7 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
     const int total = tab.unit0[tab.count];
     const int b0 = (int)((int64_t)total * blockIdx.x / gridDim.x), b1 = (int)((int64_t)total * (blockIdx.x + 1) / gridDim.x);
     const int r = lane & 15, c4 = lane >> 4;
+    const uint32_t ones = vgpr_ones();
     int item = 0;
     int u = b0;
     const int8_t *staged_xq = nullptr;   // what the LDS copy currently holds (block-uniform)
@@ -347,7 +349,7 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
                     for (int a = 0; a < RT; ++a) {
                         const uint32_t cw = j == 0 ? cc[a].x : j == 1 ? cc[a].y : j == 2 ? cc[a].z : cc[a].w;
                         const uint32_t iw = j == 0 ? ic[a].x : j == 1 ? ic[a].y : j == 2 ? ic[a].z : ic[a].w;
-                        acc[a] = __builtin_amdgcn_smfmac_i32_16x16x128_i8(expand_codes(cw), b, acc[a], (int)iw, 0, 0);
+                        acc[a] = __builtin_amdgcn_smfmac_i32_16x16x128_i8(expand_codes(cw, ones), b, acc[a], (int)iw, 0, 0);
                     }
                 }
                 if (++cs == nsuper) {

@@ -30,17 +30,54 @@ typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 // v_perm_b32 selector bytes: 0..3 pick a byte of the second source, 4..7 of the first, 12 gives
 // 0x00 and 13 or more 0xff.  Even q: selector = code (0, 1, 3).  Odd q: selector = code << 2 | 1
 // (1, 5, 13), which needs no shift: byte 1 of the second source is 0x00, byte 1 of the first 0x01,
-// and 13 is the constant 0xff.  Nine VALU operations per 16 values.
-__device__ __forceinline__ v4i expand_codes(uint32_t cw)
+// and 13 is the constant 0xff; mask and OR are one v_and_or_b32 (mask in a scalar register,
+// 0x01010101 in the vector register `ones`).  Nine VALU operations per 16 values; VALU work does
+// not overlap matrix instructions on this part (measured: their times add), so every operation
+// saved here is matrix-pipe time gained.
+__device__ __forceinline__ uint32_t vgpr_ones()
+{
+    uint32_t ones;
+    asm volatile("v_mov_b32 %0, 0x01010101" : "=v"(ones));   // opaque, so that it stays in a vector register
+    return ones;
+}
+
+__device__ __forceinline__ v4i expand_codes(uint32_t cw, uint32_t ones)
 {
     const uint32_t lut = 0xff000100u;
     const uint32_t t = cw >> 4;
+    uint32_t s1, s3;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(s1) : "v"(cw), "s"(0x0c0c0c0cu), "v"(ones));
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(s3) : "v"(t), "s"(0x0c0c0c0cu), "v"(ones));
     v4i a;
     a[0] = (int)__builtin_amdgcn_perm(lut, lut, cw & 0x03030303u);
-    a[1] = (int)__builtin_amdgcn_perm(0x00000100u, 0u, (cw & 0x0c0c0c0cu) | 0x01010101u);
+    a[1] = (int)__builtin_amdgcn_perm(0x00000100u, 0u, s1);
     a[2] = (int)__builtin_amdgcn_perm(lut, lut, t & 0x03030303u);
-    a[3] = (int)__builtin_amdgcn_perm(0x00000100u, 0u, (t & 0x0c0c0c0cu) | 0x01010101u);
+    a[3] = (int)__builtin_amdgcn_perm(0x00000100u, 0u, s3);
     return a;
 }
+
+// One LDS-DMA load: lane l of the wavefront fetches 16 bytes at base + voff and the hardware
+// deposits them at LDS byte address lds_addr + 16*l (M0 carries the LDS address).  Written as
+// inline assembly on purpose: after the compiler's own LDS-DMA builtin every later LDS read is
+// preceded by a wait for ALL outstanding vector-memory operations (it cannot tell which LDS bytes
+// a DMA writes), which serialises the prefetch ring with the loads it has just issued.  With the
+// load opaque to the compiler the kernels that use it count the outstanding DMA operations themselves
+// (SBN_WAIT_VMCNT) and order LDS reads against them with the block barrier.
+__device__ __forceinline__ void lds_dma16(const void *base, uint32_t voff, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(base)
+                 : "memory", "m0");
+}
+
+__device__ __forceinline__ uint32_t lds_address(const void *p)
+{
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
+}
+
+// wait until at most n vector-memory operations of this wavefront are outstanding (gfx9 encoding:
+// vmcnt in bits [3:0] and [15:14]; expcnt and lgkmcnt fields left at "no wait")
+#define SBN_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xf) | (((n) >> 4) << 14) | 0x0f70)
 
 }  // namespace sbn
