@@ -115,8 +115,12 @@ __device__ __forceinline__ void block_epilogue(const GemmArgs &g, v16i (&acc)[RA
         constexpr int RPI = 64 / LPR;           // token rows per store instruction
         int8_t *const est = lds + wave * (32 * EROW);
         __syncthreads();   // every wavefront has left the main loop: the ring can be overwritten
-        float4 bias4 = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (g.bias) bias4 = *reinterpret_cast<const float4 *>(g.bias + orow + 4 * (lane % LPR));
+        v4f bias4 = {0.f, 0.f, 0.f, 0.f};
+        if (g.bias) bias4 = *reinterpret_cast<const v4f *>(g.bias + orow + 4 * (lane % LPR));
+        const int tokens = g.tokens;
+        const int64_t d_out = g.d_out;
+        const bool all_tokens = tok0 + 32 * TB <= tokens;
+        float *const ybase = g.Y + (int64_t)(tok0 + lane / LPR) * d_out + orow + 4 * (lane % LPR);
 #pragma unroll
         for (int b = 0; b < TB; ++b) {
             const float scale = __fdiv_rn(sxv[TB], sxv[b]);
@@ -131,18 +135,18 @@ __device__ __forceinline__ void block_epilogue(const GemmArgs &g, v16i (&acc)[RA
                     y.w = (float)acc[a][b][4 * q + 3] * scale;
                     *reinterpret_cast<float4 *>(est + r * EROW + (32 * a + 8 * q + 4 * c) * 4) = y;
                 }
-            // the wavefront reads back what it wrote itself: its LDS operations complete in order
+            // the wavefront reads back what it wrote itself (its LDS operations complete in order):
+            // all reads of the pass first, then the stores, so that the LDS latency is paid once
+            v4f yv[32 / RPI];
+#pragma unroll
+            for (int j = 0; j < 32 / RPI; ++j)
+                yv[j] = *reinterpret_cast<const v4f *>(est + (RPI * j + lane / LPR) * EROW + (lane % LPR) * 16);
 #pragma unroll
             for (int j = 0; j < 32 / RPI; ++j) {
-                const int row = RPI * j + lane / LPR;
-                const int tt2 = tok0 + 32 * b + row;
-                float4 y = *reinterpret_cast<const float4 *>(est + row * EROW + (lane % LPR) * 16);
-                y.x += bias4.x; y.y += bias4.y; y.z += bias4.z; y.w += bias4.w;
-                if (tt2 < g.tokens) {
-                    // streaming store: Y is not read again here and must not push the operands out of L2
-                    const v4f yv = {y.x, y.y, y.z, y.w};
-                    __builtin_nontemporal_store(yv, reinterpret_cast<v4f *>(g.Y + (int64_t)tt2 * g.d_out + orow + 4 * (lane % LPR)));
-                }
+                yv[j] += bias4;
+                // streaming store: Y is not read again here and must not push the operands out of L2
+                if (all_tokens || tok0 + 32 * b + RPI * j + lane / LPR < tokens)
+                    __builtin_nontemporal_store(yv[j], reinterpret_cast<v4f *>(ybase + (int64_t)(32 * b + RPI * j) * d_out));
             }
         }
         return;
