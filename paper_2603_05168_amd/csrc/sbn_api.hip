@@ -34,11 +34,13 @@ static sbn_status check_shape(int64_t d_out, int64_t d_in, int N, int M, Pattern
     return SBN_OK;
 }
 
-static sbn_path resolve_path(sbn_path path, int64_t tokens, const Pattern &pat)
+static sbn_path resolve_path(sbn_path path, int64_t tokens, int64_t d_in, const Pattern &pat)
 {
     if (path != SBN_PATH_AUTO) return path;
     const bool is24 = pat.N == 2 && pat.M == 4;
-    if (!is24) return SBN_PATH_GENERIC;
+    // other patterns (the paper's 6:8 among them) have no sparse matrix instruction on this part: beyond
+    // decode sizes they run on the dense int8 matrix cores with explicit zeros
+    if (!is24 || d_in % CHUNK != 0) return tokens > 16 && d_in % 64 == 0 ? SBN_PATH_DENSE_MFMA : SBN_PATH_GENERIC;
     return tokens <= 16 ? SBN_PATH_GEMV : SBN_PATH_SMFMAC;
 }
 
@@ -134,11 +136,11 @@ static sbn_status linear_one(const LinearItem &it_in, const Pattern &pat, sbn_pa
 {
     LinearItem it = it_in;
     const bool is24 = pat.N == 2 && pat.M == 4;
-    path = resolve_path(path, it.tokens, pat);
-    if (path != SBN_PATH_GENERIC && !is24) return SBN_EUNSUPPORTED;
+    path = resolve_path(path, it.tokens, it.d_in, pat);
+    if (path != SBN_PATH_GENERIC && path != SBN_PATH_DENSE_MFMA && !is24) return SBN_EUNSUPPORTED;
     if (path == SBN_PATH_GEMV && it.tokens > 16) return SBN_EUNSUPPORTED;
-    if ((path == SBN_PATH_GEMV || path == SBN_PATH_SMFMAC || path == SBN_PATH_DENSE_MFMA) && it.d_in % CHUNK != 0)
-        return SBN_EUNSUPPORTED;
+    if ((path == SBN_PATH_GEMV || path == SBN_PATH_SMFMAC) && it.d_in % CHUNK != 0) return SBN_EUNSUPPORTED;
+    if (path == SBN_PATH_DENSE_MFMA && it.d_in % 64 != 0) return SBN_EUNSUPPORTED;
     if (ws_bytes < linear_workspace_bytes(it.tokens, it.d_out, it.d_in)) return SBN_ESIZE;
     // workspace: [xq int8 tokens*d_in][sx fp32 tokens][dense int8 W for the comparison path]
     uint8_t *ws = static_cast<uint8_t *>(workspace);
@@ -154,7 +156,7 @@ static sbn_status linear_one(const LinearItem &it_in, const Pattern &pat, sbn_pa
     switch (path) {
     case SBN_PATH_GEMV: return launch_gemv(1, &it, stream);
     case SBN_PATH_SMFMAC: return launch_gemm_smfmac(1, &it, stream);
-    case SBN_PATH_DENSE_MFMA: return launch_gemm_dense(it, w_dense, stream);
+    case SBN_PATH_DENSE_MFMA: return launch_gemm_dense(it, pat, w_dense, stream);
     case SBN_PATH_GENERIC: return launch_linear_generic(it, pat, stream);
     default: return SBN_EINVAL;
     }
@@ -200,9 +202,9 @@ sbn_status sbn_sparse_ternary_linear_grouped(int count, const void *const *X, co
         if (d_in[i] % 8 != 0) return SBN_EUNSUPPORTED;
         need += linear_workspace_bytes(tokens[i], d_out[i], d_in[i]);
         const bool is24 = pat.N == 2 && pat.M == 4;
-        if (resolve_path(path, tokens[i], pat) != SBN_PATH_GEMV || !is24 || tokens[i] > 16 || d_in[i] % CHUNK != 0)
+        if (resolve_path(path, tokens[i], d_in[i], pat) != SBN_PATH_GEMV || !is24 || tokens[i] > 16 || d_in[i] % CHUNK != 0)
             all_gemv = false;
-        if (resolve_path(path, tokens[i], pat) != SBN_PATH_SMFMAC || !is24 || d_in[i] % CHUNK != 0 ||
+        if (resolve_path(path, tokens[i], d_in[i], pat) != SBN_PATH_SMFMAC || !is24 || d_in[i] % CHUNK != 0 ||
             tokens[i] * d_out[i] >= (int64_t)1 << 40)
             all_smfmac = false;
     }

@@ -297,7 +297,7 @@ sbn_status launch_backward(const void *dY, int64_t tokens, int64_t d_in, int64_t
                                (int)d_out, (int)d_in, wt, ldw);
             st = check_launch("unpack_transpose_kernel");
         } else {
-            st = launch_unpack(packed, d_out, d_in, pat, w8, nullptr, stream);
+            st = launch_expand_groups(packed, d_out, d_in, pat, w8, stream);
             if (st != SBN_OK) return st;
             dim3 grid((unsigned)ceil_div(d_in, 64), (unsigned)ceil_div(d_out, 64));
             hipLaunchKernelGGL(transpose_i8_kernel, grid, dim3(256), 0, stream, w8, d_out, d_in, wt, ldw);

@@ -596,12 +596,18 @@ sbn_status launch_gemm_smfmac(int count, const LinearItem *items, hipStream_t st
     return SBN_OK;
 }
 
-sbn_status launch_gemm_dense(const LinearItem &it, int8_t *w_dense, hipStream_t stream)
+sbn_status launch_gemm_dense(const LinearItem &it, const Pattern &pat, int8_t *w_dense, hipStream_t stream)
 {
-    const int64_t ngroups = it.d_out * it.d_in / 4;
-    hipLaunchKernelGGL(expand_dense_kernel, dim3((unsigned)ceil_div(ngroups, 256)), dim3(256), 0, stream,
-                       static_cast<const uint8_t *>(it.packed), w_dense, ngroups);
-    sbn_status st = check_launch("expand_dense_kernel");
+    sbn_status st;
+    if (pat.N == 2 && pat.M == 4 && it.d_in % CHUNK == 0) {
+        const int64_t ngroups = it.d_out * it.d_in / 4;
+        hipLaunchKernelGGL(expand_dense_kernel, dim3((unsigned)ceil_div(ngroups, 256)), dim3(256), 0, stream,
+                           static_cast<const uint8_t *>(it.packed), w_dense, ngroups);
+        st = check_launch("expand_dense_kernel");
+    } else {
+        // any other pattern (6:8, 2:8, 1:4, ...): the format-generic group decoder writes the same int8 W_eff
+        st = launch_expand_groups(it.packed, it.d_out, it.d_in, pat, w_dense, stream);
+    }
     if (st != SBN_OK) return st;
     GemmArgs g = make_args(it);
     g.w_dense = w_dense;

@@ -54,6 +54,8 @@ constexpr int64_t PACK_SUM_ELEMS = 16384;  // elements reduced by one block of t
 size_t pack_workspace_bytes(int64_t count, int64_t d_out, int64_t d_in);
 sbn_status launch_pack(int count, const PackItem *items, sbn_dtype wdt, const Pattern &pat,
                        void *workspace, size_t ws_bytes, hipStream_t stream);
+sbn_status launch_expand_groups(const void *packed, int64_t d_out, int64_t d_in, const Pattern &pat, int8_t *W_eff,
+                                hipStream_t stream);
 sbn_status launch_unpack(const void *packed, int64_t d_out, int64_t d_in, const Pattern &pat,
                          int8_t *W_eff, uint8_t *mask, hipStream_t stream);
 
@@ -74,7 +76,7 @@ sbn_status launch_act_quant(const void *X, int64_t tokens, int64_t d_in, int8_t 
                             hipStream_t stream);
 sbn_status launch_gemv(int count, const LinearItem *items, hipStream_t stream);
 sbn_status launch_gemm_smfmac(int count, const LinearItem *items, hipStream_t stream);
-sbn_status launch_gemm_dense(const LinearItem &it, int8_t *w_dense, hipStream_t stream);
+sbn_status launch_gemm_dense(const LinearItem &it, const Pattern &pat, int8_t *w_dense, hipStream_t stream);
 sbn_status launch_linear_generic(const LinearItem &it, const Pattern &pat, hipStream_t stream);
 
 // ---- backward (sbn_backward.hip) ---------------------------------------------------------------

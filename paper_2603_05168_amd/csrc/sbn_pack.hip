@@ -462,6 +462,43 @@ __global__ void __launch_bounds__(256) unpack_kernel(const uint8_t *packed, int6
     }
 }
 
+// packed -> int8 W_eff with explicit zeros for any pattern, one thread per group of M weights (the
+// operand of the dense matrix path for patterns that have no sparse matrix instruction): the N slots
+// of the group are decoded into an M-byte word and stored at once
+__global__ void __launch_bounds__(256) expand_groups_kernel(const uint8_t *__restrict__ packed, int64_t d_out, int64_t d_in,
+                                                            Pattern pat, int8_t *__restrict__ W_eff)
+{
+    const int64_t gpr = d_in / pat.M;   // groups per row
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (gid >= d_out * gpr) return;
+    const int64_t row = gid / gpr;
+    const int gr = (int)(gid % gpr);
+    const int gpc = CHUNK / pat.M;      // groups per chunk
+    const int64_t nchunks = (d_in + CHUNK - 1) / CHUNK;
+    const int c = gr / gpc, g = gr % gpc;
+    const uint8_t *idx_field = packed + (row * nchunks + c) * pat.chunk_bytes;
+    const uint8_t *code_field = idx_field + pat.idx_bytes;
+    uint64_t out = 0;
+    for (int s = 0; s < pat.N; ++s) {
+        const int slot = g * pat.N + s;
+        int j = s;
+        if (pat.b) {
+            const int p = slot * pat.b;
+            const uint32_t two = (uint32_t)idx_field[p >> 3] | ((uint32_t)idx_field[(p >> 3) + 1] << 8);   // the next byte is still inside the chunk
+            j = (int)((two >> (p & 7)) & ((1u << pat.b) - 1u));
+        }
+        const int v = slot & 15;
+        const int cp = 32 * (slot >> 4) + 8 * (v & 3) + 2 * (v >> 2);
+        const uint32_t code = (code_field[cp >> 3] >> (cp & 7)) & 3u;
+        const uint64_t byte = code == 1u ? 0x01u : code == 3u ? 0xffu : 0u;
+        out |= byte << (8 * j);
+    }
+    int8_t *dst = W_eff + row * d_in + (int64_t)gr * pat.M;
+    if (pat.M == 8) *reinterpret_cast<uint2 *>(dst) = make_uint2((uint32_t)out, (uint32_t)(out >> 32));
+    else if (pat.M == 4) *reinterpret_cast<uint32_t *>(dst) = (uint32_t)out;
+    else *reinterpret_cast<uint16_t *>(dst) = (uint16_t)out;
+}
+
 template <typename WT>
 sbn_status launch_pack_kernel(const PackTable &tab, int nblocks, const float *theta, int vec_ok, const Pattern &pat,
                               hipStream_t stream)
@@ -558,6 +595,15 @@ sbn_status launch_unpack(const void *packed, int64_t d_out, int64_t d_in, const 
     hipLaunchKernelGGL(unpack_kernel, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, stream,
                        static_cast<const uint8_t *>(packed), d_out, d_in, pat, W_eff, mask);
     return check_launch("unpack_kernel");
+}
+
+sbn_status launch_expand_groups(const void *packed, int64_t d_out, int64_t d_in, const Pattern &pat, int8_t *W_eff,
+                                hipStream_t stream)
+{
+    const int64_t total = d_out * (d_in / pat.M);
+    hipLaunchKernelGGL(expand_groups_kernel, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, stream,
+                       static_cast<const uint8_t *>(packed), d_out, d_in, pat, W_eff);
+    return check_launch("expand_groups_kernel");
 }
 
 }  // namespace sbn
