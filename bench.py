@@ -269,6 +269,15 @@ def main():
                 f"on single-read bytes")
             del pl, batch
         rows["quantize_mask_pack"] = pack_rows
+        # mask flips between two packed forms of the largest matrix (ablation study, mask flip rate equation)
+        pa = pack_one(Wl[4])
+        pb = pack_one((Wl[4].float() + 0.25 * Wl[5].float()).to(torch.bfloat16))
+        flips = torch.zeros(1, dtype=torch.int64, device=dev)
+        wsf = sbn.new_workspace(sbn.sbn_workspace_bytes(sbn.SBN_OP_MASK_FLIPS, 1, F, H, N, M), dev)
+        ms = timed(lambda: sbn.sbn_mask_flips(pa[0], pb[0], F, H, N, M, flips, wsf), 100, 3)
+        rows["mask_flips_6912x2560"] = {"us": ms * 1e3, "flip_rate": flips.item() / (F * H),
+                                        "gbps_index_bytes": 2 * (F * H // 8) / (ms * 1e-3) / 1e9}
+        log(f"[flips] 6912x2560 2:4: {ms * 1e3:.1f} us, flip rate {flips.item() / (F * H):.4f}")
         del Wl
         torch.cuda.empty_cache()
 

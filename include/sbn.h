@@ -50,17 +50,20 @@ typedef enum {
 typedef enum { SBN_F32 = 0, SBN_BF16 = 1 } sbn_dtype;
 
 typedef enum {
-    SBN_PATH_AUTO = 0,       /* GEMV for tokens <= 16 (2:4), sparse MFMA GEMM for 2:4 otherwise, generic else */
+    SBN_PATH_AUTO = 0,       /* 2:4 with d_in % 128 == 0: GEMV for tokens <= 16, sparse MFMA GEMM otherwise; any other
+                                pattern: dense MFMA for tokens > 16 and d_in % 64 == 0, generic else */
     SBN_PATH_GEMV = 1,       /* decode kernel: streams the packed weights once; tokens <= 16, 2:4 */
     SBN_PATH_SMFMAC = 2,     /* prefill/training GEMM on sparse int8 MFMA (v_smfmac); 2:4 */
-    SBN_PATH_DENSE_MFMA = 3, /* comparison path: W_eff expanded to int8 with explicit zeros, dense int8 MFMA; 2:4 */
+    SBN_PATH_DENSE_MFMA = 3, /* W_eff expanded to int8 with explicit zeros, dense int8 MFMA: the comparison path for 2:4
+                                and the matrix-core path of every other pattern (6:8, N:8, 1:4, ...); d_in % 64 == 0 */
     SBN_PATH_GENERIC = 4     /* any supported pattern, plain integer kernel (reference speed only) */
 } sbn_path;
 
 typedef enum {
     SBN_OP_QUANTIZE_MASK_PACK = 0,
     SBN_OP_LINEAR = 1,
-    SBN_OP_BACKWARD = 2
+    SBN_OP_BACKWARD = 2,
+    SBN_OP_MASK_FLIPS = 3
 } sbn_op;
 
 /* Bytes of the packed form of a [d_out, d_in] matrix at N:M.  Host only, no GPU needed. */
@@ -167,6 +170,18 @@ sbn_status sbn_sparse_ternary_linear_backward(const void *dY, int64_t tokens, in
  * (uint8 [d_out, d_in]); either output may be NULL. */
 sbn_status sbn_unpack(const void *packed, int64_t d_out, int64_t d_in, int N, int M,
                       int8_t *W_eff, uint8_t *mask, void *stream);
+
+/*
+ * Mask dynamics (ablation study, mask flip rate equation): the number of positions at which the N:M
+ * masks of two packed forms of the same [d_out, d_in] matrix at the same N:M differ,
+ *   flips = || m(W_t) - m(W_{t-1}) ||_1,   flip rate r_t = flips / (d_out * d_in)  (the caller divides).
+ * Only the index fields of the packed forms are read (N == M: always 0).
+ *   packed_a, packed_b  device, as written by sbn_quantize_mask_pack, 16-byte aligned
+ *   flips_out           device, one uint64, overwritten
+ *   workspace >= sbn_workspace_bytes(SBN_OP_MASK_FLIPS, 0, d_out, d_in, N, M); enqueues two kernels, deterministic
+ */
+sbn_status sbn_mask_flips(const void *packed_a, const void *packed_b, int64_t d_out, int64_t d_in, int N,
+                          int M, uint64_t *flips_out, void *workspace, size_t ws_bytes, void *stream);
 
 /* Text of the last HIP error seen by this thread ("" if none). */
 const char *sbn_last_error(void);

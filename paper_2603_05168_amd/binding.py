@@ -17,7 +17,7 @@ _LIB_PATH = os.path.join(_HERE, "libsbn.so")
 SBN_OK, SBN_EINVAL, SBN_EUNSUPPORTED, SBN_ESIZE, SBN_EALIGN, SBN_EHIP = 0, -1, -2, -3, -4, -5
 SBN_F32, SBN_BF16 = 0, 1
 SBN_PATH_AUTO, SBN_PATH_GEMV, SBN_PATH_SMFMAC, SBN_PATH_DENSE_MFMA, SBN_PATH_GENERIC = 0, 1, 2, 3, 4
-SBN_OP_QUANTIZE_MASK_PACK, SBN_OP_LINEAR, SBN_OP_BACKWARD = 0, 1, 2
+SBN_OP_QUANTIZE_MASK_PACK, SBN_OP_LINEAR, SBN_OP_BACKWARD, SBN_OP_MASK_FLIPS = 0, 1, 2, 3
 
 _STATUS_NAMES = {0: "SBN_OK", -1: "SBN_EINVAL", -2: "SBN_EUNSUPPORTED", -3: "SBN_ESIZE", -4: "SBN_EALIGN", -5: "SBN_EHIP"}
 
@@ -57,6 +57,8 @@ def _load():
     lib.sbn_sparse_ternary_linear_backward.argtypes = [vp, i64, i64, i64, cint, cint, vp, vp, vp, vp, vp, vp, cint, vp, sz, vp]
     lib.sbn_unpack.restype = cint
     lib.sbn_unpack.argtypes = [vp, i64, i64, cint, cint, vp, vp, vp]
+    lib.sbn_mask_flips.restype = cint
+    lib.sbn_mask_flips.argtypes = [vp, vp, i64, i64, cint, cint, vp, vp, sz, vp]
     return lib
 
 
@@ -219,6 +221,12 @@ def sbn_sparse_ternary_linear_backward(dY, packed, gamma, xq, sx, N: int, M: int
 
 def sbn_unpack(packed, d_out: int, d_in: int, N: int, M: int, W_eff=None, mask=None):
     _check(_lib.sbn_unpack(_ptr(packed), d_out, d_in, N, M, _ptr(W_eff), _ptr(mask), _stream()), "sbn_unpack")
+
+
+def sbn_mask_flips(packed_a, packed_b, d_out: int, d_in: int, N: int, M: int, flips_out, workspace):
+    """flips_out: int64 device tensor of one element (the count is non-negative and below 2**63)."""
+    _check(_lib.sbn_mask_flips(_ptr(packed_a), _ptr(packed_b), d_out, d_in, N, M, _ptr(flips_out), _ptr(workspace),
+                               workspace.numel() * workspace.element_size(), _stream()), "sbn_mask_flips")
 
 
 def new_workspace(nbytes: int, device="cuda") -> torch.Tensor:

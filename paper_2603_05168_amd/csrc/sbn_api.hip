@@ -65,13 +65,14 @@ sbn_status sbn_packed_bytes(int64_t d_out, int64_t d_in, int N, int M, size_t *b
 sbn_status sbn_workspace_bytes(sbn_op op, int64_t tokens, int64_t d_out, int64_t d_in, int N, int M, size_t *bytes)
 {
     Pattern pat;
-    if (!bytes || tokens <= 0) return SBN_EINVAL;
+    if (!bytes || (tokens <= 0 && op != SBN_OP_MASK_FLIPS)) return SBN_EINVAL;
     sbn_status st = check_shape(d_out, d_in, N, M, pat);
     if (st != SBN_OK) return st;
     switch (op) {
     case SBN_OP_QUANTIZE_MASK_PACK: *bytes = pack_workspace_bytes(tokens, d_out, d_in); return SBN_OK;
     case SBN_OP_LINEAR: *bytes = linear_workspace_bytes(tokens, d_out, d_in); return SBN_OK;
     case SBN_OP_BACKWARD: *bytes = backward_workspace_bytes(tokens, d_out, d_in); return SBN_OK;
+    case SBN_OP_MASK_FLIPS: *bytes = mask_flips_workspace_bytes(d_out, d_in, M); return SBN_OK;
     }
     return SBN_EINVAL;
 }
@@ -263,6 +264,18 @@ sbn_status sbn_sparse_ternary_linear_backward(const void *dY, int64_t tokens, in
     if (ws_bytes < backward_workspace_bytes(tokens, d_out, d_in)) return SBN_ESIZE;
     return launch_backward(dY, tokens, d_in, d_out, pat, packed, gamma, xq, sx, dX, dW, accumulate, workspace,
                            ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+sbn_status sbn_mask_flips(const void *packed_a, const void *packed_b, int64_t d_out, int64_t d_in, int N, int M,
+                          uint64_t *flips_out, void *workspace, size_t ws_bytes, void *stream)
+{
+    Pattern pat;
+    if (!packed_a || !packed_b || !flips_out || !workspace) return SBN_EINVAL;
+    sbn_status st = check_shape(d_out, d_in, N, M, pat);
+    if (st != SBN_OK) return st;
+    if (!aligned(packed_a, 16) || !aligned(packed_b, 16) || !aligned(flips_out, 8) || !aligned(workspace, 256)) return SBN_EALIGN;
+    if (ws_bytes < mask_flips_workspace_bytes(d_out, d_in, M)) return SBN_ESIZE;
+    return launch_mask_flips(packed_a, packed_b, d_out, d_in, pat, flips_out, workspace, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

@@ -499,6 +499,62 @@ __global__ void __launch_bounds__(256) expand_groups_kernel(const uint8_t *__res
     else *reinterpret_cast<uint16_t *>(dst) = (uint16_t)out;
 }
 
+// ---- mask flips between two packed forms (ablation study, mask flip rate equation) ---------------
+// one thread per group: the kept positions of both forms as M-bit sets, popcount of their XOR;
+// block sums go to the workspace and are added in a fixed order by the finalize kernel
+constexpr int FLIP_GROUPS_PER_THREAD = 8;
+
+__device__ __forceinline__ uint32_t group_mask_bits(const uint8_t *idx_field, int g, const Pattern &pat)
+{
+    uint32_t m = 0;
+    for (int s = 0; s < pat.N; ++s) {
+        const int p = (g * pat.N + s) * pat.b;
+        const uint32_t two = (uint32_t)idx_field[p >> 3] | ((uint32_t)idx_field[(p >> 3) + 1] << 8);   // next byte: still in the chunk
+        m |= 1u << ((two >> (p & 7)) & ((1u << pat.b) - 1u));
+    }
+    return m;
+}
+
+__global__ void __launch_bounds__(256) mask_flips_kernel(const uint8_t *__restrict__ pa, const uint8_t *__restrict__ pb,
+                                                         int64_t d_out, int64_t d_in, Pattern pat,
+                                                         unsigned long long *__restrict__ partial)
+{
+    __shared__ unsigned int wave_sum[4];
+    const int64_t gpr = d_in / pat.M, total = d_out * gpr;
+    const int gpc = CHUNK / pat.M;
+    const int64_t nchunks = (d_in + CHUNK - 1) / CHUNK;
+    unsigned int flips = 0;
+    const int64_t base = ((int64_t)blockIdx.x * 256 + threadIdx.x) * FLIP_GROUPS_PER_THREAD;
+    for (int i = 0; i < FLIP_GROUPS_PER_THREAD; ++i) {
+        const int64_t gid = base + i;
+        if (gid >= total) break;
+        const int64_t row = gid / gpr;
+        const int gr = (int)(gid % gpr);
+        const int64_t off = (row * nchunks + gr / gpc) * pat.chunk_bytes;
+        flips += __popc(group_mask_bits(pa + off, gr % gpc, pat) ^ group_mask_bits(pb + off, gr % gpc, pat));
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) flips += __shfl_xor((int)flips, o, 64);
+    if ((threadIdx.x & 63) == 0) wave_sum[threadIdx.x >> 6] = flips;
+    __syncthreads();
+    if (threadIdx.x == 0) partial[blockIdx.x] = (unsigned long long)wave_sum[0] + wave_sum[1] + wave_sum[2] + wave_sum[3];
+}
+
+__global__ void __launch_bounds__(256) mask_flips_finalize_kernel(const unsigned long long *__restrict__ partial, int64_t n,
+                                                                  unsigned long long *__restrict__ out)
+{
+    __shared__ unsigned long long sums[256];
+    unsigned long long s = 0;
+    for (int64_t i = threadIdx.x; i < n; i += 256) s += partial[i];
+    sums[threadIdx.x] = s;
+    __syncthreads();
+    for (int step = 128; step > 0; step >>= 1) {
+        if ((int)threadIdx.x < step) sums[threadIdx.x] += sums[threadIdx.x + step];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *out = sums[0];
+}
+
 template <typename WT>
 sbn_status launch_pack_kernel(const PackTable &tab, int nblocks, const float *theta, int vec_ok, const Pattern &pat,
                               hipStream_t stream)
@@ -595,6 +651,30 @@ sbn_status launch_unpack(const void *packed, int64_t d_out, int64_t d_in, const 
     hipLaunchKernelGGL(unpack_kernel, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, stream,
                        static_cast<const uint8_t *>(packed), d_out, d_in, pat, W_eff, mask);
     return check_launch("unpack_kernel");
+}
+
+size_t mask_flips_workspace_bytes(int64_t d_out, int64_t d_in, int M)
+{
+    const int64_t groups = d_out * (d_in / M);
+    return align_up((size_t)ceil_div(groups, 256 * FLIP_GROUPS_PER_THREAD) * sizeof(unsigned long long), 256);
+}
+
+sbn_status launch_mask_flips(const void *packed_a, const void *packed_b, int64_t d_out, int64_t d_in, const Pattern &pat,
+                             uint64_t *flips_out, void *workspace, hipStream_t stream)
+{
+    unsigned long long *out = reinterpret_cast<unsigned long long *>(flips_out);
+    unsigned long long *partial = static_cast<unsigned long long *>(workspace);
+    if (pat.b == 0) {   // N == M: every position is kept in both forms
+        hipLaunchKernelGGL(mask_flips_finalize_kernel, dim3(1), dim3(256), 0, stream, partial, (int64_t)0, out);
+        return check_launch("mask_flips_finalize_kernel");
+    }
+    const int64_t nblocks = ceil_div(d_out * (d_in / pat.M), 256 * FLIP_GROUPS_PER_THREAD);
+    hipLaunchKernelGGL(mask_flips_kernel, dim3((unsigned)nblocks), dim3(256), 0, stream, static_cast<const uint8_t *>(packed_a),
+                       static_cast<const uint8_t *>(packed_b), d_out, d_in, pat, partial);
+    sbn_status st = check_launch("mask_flips_kernel");
+    if (st != SBN_OK) return st;
+    hipLaunchKernelGGL(mask_flips_finalize_kernel, dim3(1), dim3(256), 0, stream, partial, nblocks, out);
+    return check_launch("mask_flips_finalize_kernel");
 }
 
 sbn_status launch_expand_groups(const void *packed, int64_t d_out, int64_t d_in, const Pattern &pat, int8_t *W_eff,

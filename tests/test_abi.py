@@ -61,7 +61,7 @@ def test_bad_shapes_are_einval(sbn, args):
 
 
 def test_workspace_queries(sbn):
-    for op in (sbn.SBN_OP_QUANTIZE_MASK_PACK, sbn.SBN_OP_LINEAR, sbn.SBN_OP_BACKWARD):
+    for op in (sbn.SBN_OP_QUANTIZE_MASK_PACK, sbn.SBN_OP_LINEAR, sbn.SBN_OP_BACKWARD, sbn.SBN_OP_MASK_FLIPS):
         assert sbn.sbn_workspace_bytes(op, 16, 256, 256, 2, 4) > 0
     with pytest.raises(sbn.SbnError):
         sbn.sbn_workspace_bytes(7, 16, 256, 256, 2, 4)
@@ -105,4 +105,12 @@ def test_argument_errors_come_before_any_launch(sbn):
     # backward: nothing requested
     assert lib.sbn_sparse_ternary_linear_backward(vp(A), i64(8), i64(256), i64(256), ci(2), ci(4), vp(A), vp(A), vp(A),
                                                   vp(A), vp(0), vp(0), ci(0), vp(A), sz(1 << 24), vp(0)) == sbn.SBN_EINVAL
+    assert lin(d_in=200, path=sbn.SBN_PATH_DENSE_MFMA) == sbn.SBN_EUNSUPPORTED   # dense MFMA rows are multiples of 64
+    # mask flips: null input, misaligned count, short workspace
+    lib.sbn_mask_flips.restype = ctypes.c_int
+    flips = lambda **kw: lib.sbn_mask_flips(  # noqa: E731
+        vp(kw.get("a", A)), vp(A), i64(64), i64(256), ci(2), ci(4), vp(kw.get("out", A)), vp(A), sz(kw.get("ws", 1 << 16)), vp(0))
+    assert flips(a=0) == sbn.SBN_EINVAL
+    assert flips(out=A + 4) == sbn.SBN_EALIGN
+    assert flips(ws=8) == sbn.SBN_ESIZE
     assert sbn.sbn_last_error() == ""

@@ -101,3 +101,30 @@ def test_pack_batched_equals_single():
         ref, g, *_ = oracle_pack(W.cpu(), 2, 4)
         assert gammas[i].item() == g
         assert np.array_equal(packed[i].cpu().numpy(), ref)
+
+
+@pytest.mark.parametrize("N,M", [(2, 4), (1, 4), (2, 8), (6, 8), (3, 8), (1, 2), (4, 4)])
+@pytest.mark.parametrize("shape", [(37, 392), (256, 1280)])
+def test_mask_flips_between_two_steps(N, M, shape):
+    # ablation study, mask flip rate equation: || m(W_t) - m(W_{t-1}) ||_1 from the packed index fields
+    # of two steps, against the oracle's masks of the same two weight tensors (ragged last chunk included)
+    s = sbn()
+    W0 = sbn_synth.latent_weight(shape[0], shape[1], 900 + N + M)
+    step = sbn_synth.latent_weight(shape[0], shape[1], 901 + N + M)
+    W1 = (W0.float() + 0.25 * step.float()).to(torch.bfloat16)      # a noisy update: some masks flip, most stay
+    p0, _ = hip_pack(W0, N, M)
+    p1, _ = hip_pack(W1, N, M)
+    flips = torch.full((1,), -5, dtype=torch.int64, device=DEV)
+    ws = s.new_workspace(s.sbn_workspace_bytes(s.SBN_OP_MASK_FLIPS, 1, shape[0], shape[1], N, M))
+    s.sbn_mask_flips(p0, p1, shape[0], shape[1], N, M, flips, ws)
+    torch.cuda.synchronize()
+    m0 = oracle.nm_mask(W0.float().numpy(), N, M)
+    m1 = oracle.nm_mask(W1.float().numpy(), N, M)
+    expected = int((m0 != m1).sum())
+    assert flips.item() == expected
+    assert oracle.flip_rate(m0, m1) == expected / m0.size
+    if N < M:
+        assert expected > 0
+    s.sbn_mask_flips(p0, p0, shape[0], shape[1], N, M, flips, ws)
+    torch.cuda.synchronize()
+    assert flips.item() == 0
