@@ -188,23 +188,25 @@ def main():
                                       "sparse_speedup": ms / gemm_rows[f"{a}x{b}"]["ms"]}
             log(f"[dense] {a}x{b}: {ms * 1e3:.1f} us -> sparse path is {ms / gemm_rows[f'{a}x{b}']['ms']:.2f}x faster")
         rows["gemm_dense_ternary"] = dense_rows
-        # the paper's main pattern, 6:8: no sparse matrix instruction applies, automatic selection runs it
-        # on the dense int8 matrix cores (unpack to int8 + the same dense GEMM)
-        rows68 = {}
-        for j, (a, b) in enumerate(shapes):
-            p68 = pack_one(sbn_synth.latent_weight(a, b, sbn_synth.seed_for(3, a), device=dev), 6, 8)
+        # other patterns through automatic path selection: the paper's main pattern 6:8 has no sparse matrix
+        # instruction (dense int8 matrix cores after an expansion to int8); 2:8 is an instance of 2:4
+        # (rewritten into the 2:4 operand form, then the sparse kernel)
+        for (n8, m8, key) in ((6, 8, "gemm_6of8_dense_mfma"), (2, 8, "gemm_2of8_sparse_mfma")):
+            rows_p = {}
+            for j, (a, b) in enumerate(shapes):
+                pk = pack_one(sbn_synth.latent_weight(a, b, sbn_synth.seed_for(3, a), device=dev), n8, m8)
 
-            def call68(j=j, p68=p68):
-                i = counter[0] % NSETS
-                counter[0] += 1
-                sbn.sbn_sparse_ternary_linear(None, p68[0], p68[1], Ys[i][j], 6, 8, ws_lin, xq_out=xq[i], sx_out=sx[i],
-                                              path=sbn.SBN_PATH_AUTO)
-            ms = timed(call68, 100, 3)
-            rows68[f"{a}x{b}"] = {"ms_with_unpack": ms, "tops": 2.0 * T * a * b / (ms * 1e-3) / 1e12,
-                                  "vs_2of4_sparse": ms / gemm_rows[f"{a}x{b}"]["ms"]}
-            log(f"[6:8] {a}x{b}: {ms * 1e3:.1f} us on the dense int8 path ({rows68[f'{a}x{b}']['tops']:.0f} TOPS)")
-            del p68
-        rows["gemm_6of8_dense_mfma"] = rows68
+                def call_p(j=j, pk=pk, n8=n8, m8=m8):
+                    i = counter[0] % NSETS
+                    counter[0] += 1
+                    sbn.sbn_sparse_ternary_linear(None, pk[0], pk[1], Ys[i][j], n8, m8, ws_lin, xq_out=xq[i], sx_out=sx[i],
+                                                  path=sbn.SBN_PATH_AUTO)
+                ms = timed(call_p, 100, 3)
+                rows_p[f"{a}x{b}"] = {"ms_with_operand_rewrite": ms, "tops": 2.0 * T * a * b / (ms * 1e-3) / 1e12,
+                                      "vs_2of4_sparse": ms / gemm_rows[f"{a}x{b}"]["ms"]}
+                log(f"[{n8}:{m8}] {a}x{b}: {ms * 1e3:.1f} us ({rows_p[f'{a}x{b}']['tops']:.0f} TOPS dense-equivalent)")
+                del pk
+            rows[key] = rows_p
     del Ys, Xs
     torch.cuda.empty_cache()
 

@@ -57,6 +57,10 @@ sbn_status launch_pack(int count, const PackItem *items, sbn_dtype wdt, const Pa
 size_t mask_flips_workspace_bytes(int64_t d_out, int64_t d_in, int M);
 sbn_status launch_mask_flips(const void *packed_a, const void *packed_b, int64_t d_out, int64_t d_in, const Pattern &pat,
                              uint64_t *flips_out, void *workspace, hipStream_t stream);
+// N:M patterns that are instances of 2:4: at most two kept weights in every aligned group of four
+inline bool embeds_in_2of4(const Pattern &p) { return (p.M == 2 && p.N == 1) || (p.M >= 4 && p.N <= 2); }
+sbn_status launch_repack_2of4(const void *packed, int64_t d_out, int64_t d_in, const Pattern &pat, uint8_t *out24,
+                              hipStream_t stream);
 sbn_status launch_expand_groups(const void *packed, int64_t d_out, int64_t d_in, const Pattern &pat, int8_t *W_eff,
                                 hipStream_t stream);
 sbn_status launch_unpack(const void *packed, int64_t d_out, int64_t d_in, const Pattern &pat,

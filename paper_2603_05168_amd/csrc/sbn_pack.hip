@@ -499,6 +499,70 @@ __global__ void __launch_bounds__(256) expand_groups_kernel(const uint8_t *__res
     else *reinterpret_cast<uint16_t *>(dst) = (uint16_t)out;
 }
 
+// Patterns that never keep more than two weights in an aligned group of four (1:2, 1:4, 2:4 itself,
+// 1:8, 2:8) are instances of 2:4, so the sparse matrix instruction can run them.  This kernel rewrites
+// such a packed matrix as the 2:4 operand form the sparse GEMM reads (32-byte chunks: four index
+// words, four code words): one thread per 32 weights = one index word and one code word.  Groups
+// with fewer than two kept weights get padding slots with code 0 (their index is irrelevant).
+__global__ void __launch_bounds__(256) repack_2of4_kernel(const uint8_t *__restrict__ packed, int64_t d_out, int64_t d_in,
+                                                          Pattern pat, uint8_t *__restrict__ out24)
+{
+    const int64_t nchunks = d_in / CHUNK;   // the caller guarantees whole chunks
+    const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (q >= d_out * nchunks * 4) return;
+    const int64_t chunk = q >> 2;
+    const int w = (int)(q & 3);             // which 32-weight quarter of the chunk
+    const uint8_t *idx_field = packed + chunk * pat.chunk_bytes;
+    const uint8_t *code_field = idx_field + pat.idx_bytes;
+    // state of the eight target groups in registers: iw takes the positions as they arrive (low two bits
+    // of nibble t first, then the high two), cw the codes at their final place, cntw two bits of count
+    uint32_t iw = 0, cw = 0, cntw = 0;
+    const int gps = 32 / pat.M;             // source groups in this quarter
+    for (int gs = 0; gs < gps; ++gs) {
+        const int g = w * gps + gs;
+        for (int s = 0; s < pat.N; ++s) {
+            const int slot = g * pat.N + s;
+            int j = s;
+            if (pat.b) {
+                const int p = slot * pat.b;
+                const uint32_t two = (uint32_t)idx_field[p >> 3] | ((uint32_t)idx_field[(p >> 3) + 1] << 8);
+                j = (int)((two >> (p & 7)) & ((1u << pat.b) - 1u));
+            }
+            const int sv = slot & 15;
+            const int cp = 32 * (slot >> 4) + 8 * (sv & 3) + 2 * (sv >> 2);
+            const uint32_t c = (code_field[cp >> 3] >> (cp & 7)) & 3u;
+            const int k = gs * pat.M + j;   // weight inside the quarter; slots of a group come in ascending index
+            const int t = k >> 2;
+            const uint32_t n = (cntw >> (2 * t)) & 3u;   // 0 or 1 for an instance of 2:4
+            iw |= (uint32_t)(k & 3) << (4 * t + 2 * n);
+            const int v = 2 * t + (int)n;   // value index inside the code word
+            cw |= c << (8 * (v & 3) + 2 * (v >> 2));
+            cntw += 1u << (2 * t);
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        const uint32_t n = (cntw >> (2 * t)) & 3u;
+        const uint32_t p0 = (iw >> (4 * t)) & 3u;
+        if (n == 0) {
+            iw |= 1u << (4 * t + 2);                           // positions (0, 1), both codes 0
+        } else if (n == 1) {
+            if (p0 < 3) {
+                iw |= 3u << (4 * t + 2);                       // (p, 3): padding last
+            } else {                                           // (0, 3): padding first, the kept value moves to the second slot
+                const int v0 = 2 * t, v1 = 2 * t + 1;
+                const uint32_t c = (cw >> (8 * (v0 & 3) + 2 * (v0 >> 2))) & 3u;
+                cw &= ~(3u << (8 * (v0 & 3) + 2 * (v0 >> 2)));
+                cw |= c << (8 * (v1 & 3) + 2 * (v1 >> 2));
+                iw = (iw & ~(0xfu << (4 * t))) | (0xcu << (4 * t));
+            }
+        }
+    }
+    uint32_t *o = reinterpret_cast<uint32_t *>(out24 + chunk * 32);
+    o[w] = iw;
+    o[4 + w] = cw;
+}
+
 // ---- mask flips between two packed forms (ablation study, mask flip rate equation) ---------------
 // one thread per group: the kept positions of both forms as M-bit sets, popcount of their XOR;
 // block sums go to the workspace and are added in a fixed order by the finalize kernel
@@ -675,6 +739,15 @@ sbn_status launch_mask_flips(const void *packed_a, const void *packed_b, int64_t
     if (st != SBN_OK) return st;
     hipLaunchKernelGGL(mask_flips_finalize_kernel, dim3(1), dim3(256), 0, stream, partial, nblocks, out);
     return check_launch("mask_flips_finalize_kernel");
+}
+
+sbn_status launch_repack_2of4(const void *packed, int64_t d_out, int64_t d_in, const Pattern &pat, uint8_t *out24,
+                              hipStream_t stream)
+{
+    const int64_t total = d_out * (d_in / CHUNK) * 4;
+    hipLaunchKernelGGL(repack_2of4_kernel, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, stream,
+                       static_cast<const uint8_t *>(packed), d_out, d_in, pat, out24);
+    return check_launch("repack_2of4_kernel");
 }
 
 sbn_status launch_expand_groups(const void *packed, int64_t d_out, int64_t d_in, const Pattern &pat, int8_t *W_eff,

@@ -93,6 +93,26 @@ def test_dense_mfma_path_other_patterns(N, M, tokens, shape):
     check_forward(W, X, N, M, s.SBN_PATH_AUTO)
 
 
+@pytest.mark.parametrize("N,M", [(1, 4), (2, 8), (1, 8), (1, 2)])
+@pytest.mark.parametrize("tokens,shape", [(40, (130, 384)), (300, (520, 1280))])
+def test_sparse_mfma_path_instances_of_2of4(N, M, tokens, shape):
+    # patterns that never keep more than two of an aligned four are rewritten into the 2:4 operand form and
+    # run on the sparse matrix instruction: same integers as the oracle, explicitly and through path selection
+    s = sbn()
+    W = sbn_synth.latent_weight(shape[0], shape[1], 470 + N + M)
+    X = sbn_synth.activations(tokens, shape[1], 480 + tokens)
+    check_forward(W, X, N, M, s.SBN_PATH_SMFMAC)
+    check_forward(W, X, N, M, s.SBN_PATH_AUTO)
+
+
+def test_sparse_mfma_path_adversarial_2of8():
+    s = sbn()
+    W = sbn_synth.adversarial_weight(64, 512, 472)
+    X = sbn_synth.adversarial_activations(33, 512, 473)
+    check_forward(W, X, 2, 8, s.SBN_PATH_SMFMAC)
+    check_forward(W, X, 1, 4, s.SBN_PATH_SMFMAC)
+
+
 def test_dense_mfma_path_ragged_2of4():
     # 2:4 with an input dimension that is not a whole number of 128-weight chunks: automatic selection
     # takes the dense matrix path (multiple of 64) or the generic kernel
