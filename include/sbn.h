@@ -50,10 +50,10 @@ typedef enum {
 typedef enum { SBN_F32 = 0, SBN_BF16 = 1 } sbn_dtype;
 
 typedef enum {
-    SBN_PATH_AUTO = 0,       /* 2:4 with d_in % 128 == 0: GEMV for tokens <= 16, sparse MFMA GEMM otherwise; other patterns
-                                with tokens > 16: sparse MFMA if the pattern is an instance of 2:4 (1:2, 1:4, 1:8, 2:8),
-                                dense MFMA if d_in % 64 == 0; generic else */
-    SBN_PATH_GEMV = 1,       /* decode kernel: streams the packed weights once; tokens <= 16, 2:4 */
+    SBN_PATH_AUTO = 0,       /* 2:4 and its instances (1:2, 1:4, 1:8, 2:8) with d_in % 128 == 0: GEMV for tokens <= 16,
+                                sparse MFMA GEMM otherwise; any other case: dense MFMA if d_in % 64 == 0, generic else */
+    SBN_PATH_GEMV = 1,       /* decode kernel: streams the packed weights once; tokens <= 16, 2:4 (instances of 2:4 are
+                                rewritten into the 2:4 form first, which costs a pass over the packed weights) */
     SBN_PATH_SMFMAC = 2,     /* prefill/training GEMM on sparse int8 MFMA (v_smfmac); 2:4 and its instances, d_in % 128 == 0 */
     SBN_PATH_DENSE_MFMA = 3, /* W_eff expanded to int8 with explicit zeros, dense int8 MFMA: the comparison path for 2:4
                                 and the matrix-core path of every other pattern (6:8, N:8, 1:4, ...); d_in % 64 == 0 */

@@ -40,10 +40,8 @@ static sbn_path resolve_path(sbn_path path, int64_t tokens, int64_t d_in, const 
     const bool is24 = pat.N == 2 && pat.M == 4;
     // other patterns (the paper's 6:8 among them) have no sparse matrix instruction on this part: beyond
     // decode sizes they run on the dense int8 matrix cores with explicit zeros
-    if (is24 && d_in % CHUNK == 0) return tokens <= 16 ? SBN_PATH_GEMV : SBN_PATH_SMFMAC;
-    if (tokens <= 16) return SBN_PATH_GENERIC;
-    // instances of 2:4 (1:4, 2:8, ...) are rewritten into the 2:4 operand form and take the sparse instruction
-    if (embeds_in_2of4(pat) && d_in % CHUNK == 0) return SBN_PATH_SMFMAC;
+    // 2:4 and its instances (1:4, 2:8, ...: rewritten into the 2:4 operand form first) take the sparse instruction
+    if ((is24 || embeds_in_2of4(pat)) && d_in % CHUNK == 0) return tokens <= 16 ? SBN_PATH_GEMV : SBN_PATH_SMFMAC;
     return d_in % 64 == 0 ? SBN_PATH_DENSE_MFMA : SBN_PATH_GENERIC;
 }
 
@@ -141,8 +139,7 @@ static sbn_status linear_one(const LinearItem &it_in, const Pattern &pat, sbn_pa
     LinearItem it = it_in;
     const bool is24 = pat.N == 2 && pat.M == 4;
     path = resolve_path(path, it.tokens, it.d_in, pat);
-    if (path != SBN_PATH_GENERIC && path != SBN_PATH_DENSE_MFMA && !is24 && !(path == SBN_PATH_SMFMAC && embeds_in_2of4(pat)))
-        return SBN_EUNSUPPORTED;
+    if (path != SBN_PATH_GENERIC && path != SBN_PATH_DENSE_MFMA && !is24 && !embeds_in_2of4(pat)) return SBN_EUNSUPPORTED;
     if (path == SBN_PATH_GEMV && it.tokens > 16) return SBN_EUNSUPPORTED;
     if ((path == SBN_PATH_GEMV || path == SBN_PATH_SMFMAC) && it.d_in % CHUNK != 0) return SBN_EUNSUPPORTED;
     if (path == SBN_PATH_DENSE_MFMA && it.d_in % 64 != 0) return SBN_EUNSUPPORTED;
@@ -158,15 +155,15 @@ static sbn_status linear_one(const LinearItem &it_in, const Pattern &pat, sbn_pa
     sbn_status st = SBN_OK;
     if (it.X) st = launch_act_quant(it.X, it.tokens, it.d_in, it.xq, it.sx, stream);
     if (st != SBN_OK) return st;
+    if ((path == SBN_PATH_GEMV || path == SBN_PATH_SMFMAC) && !is24) {
+        // an instance of 2:4: the dense-weight region of the workspace takes its 2:4 operand form (a quarter of the size)
+        st = launch_repack_2of4(it.packed, it.d_out, it.d_in, pat, reinterpret_cast<uint8_t *>(w_dense), stream);
+        if (st != SBN_OK) return st;
+        it.packed = w_dense;
+    }
     switch (path) {
     case SBN_PATH_GEMV: return launch_gemv(1, &it, stream);
-    case SBN_PATH_SMFMAC:
-        if (!is24) {   // the dense-weight region of the workspace holds the 2:4 operand form (a quarter of its size)
-            st = launch_repack_2of4(it.packed, it.d_out, it.d_in, pat, reinterpret_cast<uint8_t *>(w_dense), stream);
-            if (st != SBN_OK) return st;
-            it.packed = w_dense;
-        }
-        return launch_gemm_smfmac(1, &it, stream);
+    case SBN_PATH_SMFMAC: return launch_gemm_smfmac(1, &it, stream);
     case SBN_PATH_DENSE_MFMA: return launch_gemm_dense(it, pat, w_dense, stream);
     case SBN_PATH_GENERIC: return launch_linear_generic(it, pat, stream);
     default: return SBN_EINVAL;

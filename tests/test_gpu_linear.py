@@ -105,6 +105,19 @@ def test_sparse_mfma_path_instances_of_2of4(N, M, tokens, shape):
     check_forward(W, X, N, M, s.SBN_PATH_AUTO)
 
 
+@pytest.mark.parametrize("N,M", [(1, 4), (2, 8), (6, 8), (3, 8)])
+@pytest.mark.parametrize("tokens", [1, 8, 16])
+def test_decode_sizes_other_patterns_through_path_selection(N, M, tokens):
+    # decode batches of other patterns: instances of 2:4 take the decode kernel after the operand rewrite,
+    # the rest the dense matrix path; never the scalar reference kernel when a matrix path applies
+    s = sbn()
+    W = sbn_synth.latent_weight(200, 640, 490 + N + M)
+    X = sbn_synth.activations(tokens, 640, 491 + tokens)
+    check_forward(W, X, N, M, s.SBN_PATH_AUTO)
+    if N <= 2:
+        check_forward(W, X, N, M, s.SBN_PATH_GEMV)
+
+
 def test_sparse_mfma_path_adversarial_2of8():
     s = sbn()
     W = sbn_synth.adversarial_weight(64, 512, 472)
