@@ -243,7 +243,7 @@ def main():
             torch.cuda.empty_cache()
         rows["gemv"] = gemv_rows
         best = gemv_rows["up_6912x2560_T8"]
-        roofline_gemv = {"kernel": "gemv_smfmac_kernel", "workload": "64 x (6912x2560 packed 2:4), T=8, grouped",
+        roofline_gemv = {"kernel": "gemv_stream_kernel", "workload": "64 x (6912x2560 packed 2:4), T=8, grouped",
                          "bound": "hbm", "achieved": best["stream_gbps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                          "frac": best["frac_hbm"], "traffic": measured_traffic("gemv_stream_kernel", "64x6912x2560"),
                          "algorithmic_bytes": R * best["packed_bytes"]}
