@@ -185,6 +185,31 @@ def test_config3_prefill_gemm_full_size(path_name, d_out):
     check_forward(W, X, 2, 4, getattr(s, path_name), token_sample=np.unique(rows))
 
 
+def test_config3_grouped_step_full_size_as_timed():
+    # the launch configuration the benchmark times: one grouped call for X 4096x2560 against 6912x2560 and
+    # 2560x2560 (largest first), one quantization, one sparse GEMM launch, LDS-transposed epilogue.
+    # Y on 64 sampled token rows of both outputs; Y of the grouped call equals the single calls bit for bit.
+    s = sbn()
+    shapes = [(6912, 2560), (2560, 2560)]
+    Ws = [sbn_synth.latent_weight(a, b, sbn_synth.seed_for(3, a)) for a, b in shapes]
+    X = sbn_synth.activations(4096, 2560, sbn_synth.seed_for(3, 1))
+    packs = [hip_pack(W, 2, 4) for W in Ws]
+    Xd = X.to(DEV)
+    Ys = [torch.full((4096, a), float("nan"), dtype=torch.float32, device=DEV) for a, _ in shapes]
+    ws = s.new_workspace(sum(s.sbn_workspace_bytes(s.SBN_OP_LINEAR, 4096, a, b, 2, 4) for a, b in shapes))
+    s.sbn_sparse_ternary_linear_grouped([Xd, Xd], [p for p, _ in packs], [g for _, g in packs], Ys, 2, 4, ws,
+                                        path=s.SBN_PATH_SMFMAC)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([[0, 1, 127, 128, 4095], np.random.default_rng(5).choice(4096, size=59, replace=False)]))
+    Xf = X.float().numpy()
+    for (a, b), W, (packed, gamma), Y in zip(shapes, Ws, packs, Ys):
+        _, g, Weff, _ = oracle_pack(W, 2, 4)
+        y, *_ = oracle.sparse_ternary_linear(Xf[rows], Weff, g)
+        assert_rel(Y.cpu().numpy()[rows], y, Y_TOL, f"grouped Y {a}x{b}")
+        Y1, *_ = hip_linear(X, packed, gamma, a, 2, 4, s.SBN_PATH_SMFMAC, want_acc=False)
+        assert np.array_equal(Y.cpu().numpy(), Y1)
+
+
 def test_sparse_and_dense_paths_agree_bitwise_full_size():
     s = sbn()
     W = sbn_synth.latent_weight(2560, 2560, sbn_synth.seed_for(3, 7))
