@@ -267,6 +267,30 @@ def test_grouped_sparse_gemm_against_oracle():
         assert_rel(Y_list[i].cpu().numpy(), y, Y_TOL, f"Y of problem {i}")
 
 
+@pytest.mark.parametrize("tokens,shape", [(8, (6912, 2560)), (1, (2560, 6912))])
+def test_config2_streaming_decode_full_size_as_timed(tokens, shape):
+    # the launch configuration the benchmark times for decode: independently seeded copies of a full-size
+    # matrix in one grouped call on the persistent streaming kernel (20 copies: enough rows to select it),
+    # every output of every copy against the oracle
+    s = sbn()
+    a, b = shape
+    R = 20
+    Ws = [sbn_synth.latent_weight(a, b, sbn_synth.seed_for(2, 100 * r + a % 7)) for r in range(R)]
+    packs = [hip_pack(W, 2, 4) for W in Ws]
+    X = sbn_synth.activations(tokens, b, sbn_synth.seed_for(2, tokens))
+    Xd = X.to(DEV)
+    Ys = [torch.full((tokens, a), float("nan"), dtype=torch.float32, device=DEV) for _ in range(R)]
+    ws = s.new_workspace(R * s.sbn_workspace_bytes(s.SBN_OP_LINEAR, tokens, a, b, 2, 4))
+    s.sbn_sparse_ternary_linear_grouped([Xd] * R, [p for p, _ in packs], [g for _, g in packs], Ys, 2, 4, ws,
+                                        path=s.SBN_PATH_GEMV)
+    torch.cuda.synchronize()
+    Xf = X.float().numpy()
+    for r in range(R):
+        _, g, Weff, _ = oracle_pack(Ws[r], 2, 4)
+        y, *_ = oracle.sparse_ternary_linear(Xf, Weff, g)
+        assert_rel(Ys[r].cpu().numpy(), y, Y_TOL, f"Y of copy {r}")
+
+
 @pytest.mark.parametrize("tokens", [1, 5, 64, 65, 300])
 @pytest.mark.parametrize("d_in", [8, 256, 2560, 6912, 8200, 16520])
 def test_act_quant_entry_all_kernel_variants(tokens, d_in):
