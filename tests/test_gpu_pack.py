@@ -103,6 +103,26 @@ def test_pack_batched_equals_single():
         assert np.array_equal(packed[i].cpu().numpy(), ref)
 
 
+@pytest.mark.parametrize("N,M", [(2, 4), (1, 4), (2, 8)])
+def test_config4_sweep_batched_as_timed(N, M):
+    # the launch configuration the benchmark times for the sweep: one batched call over full-size
+    # matrices (two transformer blocks = 14 matrices here, the sweep's three shapes), every byte and gamma
+    s = sbn()
+    shapes = [(a, b) for _, a, b in sbn_synth.BLOCK_MATRICES] * 2
+    Ws = [sbn_synth.latent_weight(a, b, sbn_synth.seed_for(4, 10 * (i // 7) + i % 7)) for i, (a, b) in enumerate(shapes)]
+    Wd = [W.to(DEV) for W in Ws]
+    packed = [torch.zeros(s.sbn_packed_bytes(a, b, N, M), dtype=torch.uint8, device=DEV) for a, b in shapes]
+    gammas = torch.zeros(len(shapes), dtype=torch.float32, device=DEV)
+    glist = [gammas[i:i + 1] for i in range(len(shapes))]
+    ws = s.new_workspace(s.sbn_workspace_bytes(s.SBN_OP_QUANTIZE_MASK_PACK, len(shapes), 6912, 2560, N, M))
+    s.sbn_quantize_mask_pack_batched(Wd, N, M, packed, glist, ws)
+    torch.cuda.synchronize()
+    for i, W in enumerate(Ws):
+        ref, g, *_ = oracle_pack(W, N, M)
+        assert gammas[i].item() == g, f"gamma of matrix {i}"
+        assert np.array_equal(packed[i].cpu().numpy(), ref), f"packed bytes of matrix {i}"
+
+
 @pytest.mark.parametrize("N,M", [(2, 4), (1, 4), (2, 8), (6, 8), (3, 8), (1, 2), (4, 4)])
 @pytest.mark.parametrize("shape", [(37, 392), (256, 1280)])
 def test_mask_flips_between_two_steps(N, M, shape):
