@@ -50,8 +50,8 @@ def main():
                     help="comma list of: gemm (always timed), gemv, pack, train, dense, cpu, copyref")
     args = ap.parse_args()
     if args.gpus != 1:
-        log("bench.py: this build measures one GPU only (the layer shards by rows of W, see DESIGN.md); "
-            "run with --gpus 1")
+        log("bench.py: this build measures one GPU only (across GPUs the layer would shard by rows of W, with "
+            "one scalar all-reduce for the weight scale); run with --gpus 1")
         sys.exit(2)
     sections = set(args.sections.split(","))
 
