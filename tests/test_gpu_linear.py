@@ -245,6 +245,39 @@ def test_grouped_streaming_gemv_against_oracle(tokens):
         assert_rel(Y_list[i].cpu().numpy(), ref[sh], Y_TOL, f"Y of problem {i}")
 
 
+def test_streaming_gemv_workspace_reuse_and_many_inputs():
+    # (a) the same workspace serves calls with different inputs one after the other: every call
+    # must see its own quantized activations; (b) six distinct inputs interleaved over the problems
+    # of one call on the streaming kernel, which restages its activations whenever the input changes
+    s = sbn()
+    tokens = 4
+    shapes = [(8192, 512)] * 24
+    Ws = [sbn_synth.latent_weight(a, b, 1300 + i) for i, (a, b) in enumerate(shapes)]
+    packs = [hip_pack(W, 2, 4) for W in Ws]
+    refs = [oracle_pack(W, 2, 4) for W in Ws]
+    need = sum(s.sbn_workspace_bytes(s.SBN_OP_LINEAR, tokens, a, b, 2, 4) for a, b in shapes)
+    ws = s.new_workspace(need)
+    for call in range(3):
+        X = sbn_synth.activations(tokens, 512, 1350 + call)
+        Xd = X.to(DEV)
+        Ys = [torch.full((tokens, a), float("nan"), dtype=torch.float32, device=DEV) for a, _ in shapes]
+        s.sbn_sparse_ternary_linear_grouped([Xd] * len(shapes), [p for p, _ in packs], [g for _, g in packs], Ys, 2, 4, ws,
+                                            path=s.SBN_PATH_GEMV)
+        torch.cuda.synchronize()
+        for i in (0, 11, 23):
+            y, *_ = oracle.sparse_ternary_linear(X.float().numpy(), refs[i][2], refs[i][1])
+            assert_rel(Ys[i].cpu().numpy(), y, Y_TOL, f"call {call}, problem {i}")
+    Xs = [sbn_synth.activations(tokens, 512, 1400 + i) for i in range(6)]
+    Xd = [x.to(DEV) for x in Xs]
+    Ys = [torch.full((tokens, a), float("nan"), dtype=torch.float32, device=DEV) for a, _ in shapes]
+    s.sbn_sparse_ternary_linear_grouped([Xd[i % 6] for i in range(len(shapes))], [p for p, _ in packs],
+                                        [g for _, g in packs], Ys, 2, 4, ws, path=s.SBN_PATH_GEMV)
+    torch.cuda.synchronize()
+    for i in range(len(shapes)):
+        y, *_ = oracle.sparse_ternary_linear(Xs[i % 6].float().numpy(), refs[i][2], refs[i][1])
+        assert_rel(Ys[i].cpu().numpy(), y, Y_TOL, f"six inputs, problem {i}")
+
+
 def test_grouped_sparse_gemm_against_oracle():
     # prefill-sized grouped call: all problems take the sparse-MFMA path, their tiles share one launch
     # (ragged token and row counts, two problems sharing one input, more problems than one launch holds)
