@@ -242,6 +242,60 @@ def main():
             del packs
             torch.cuda.empty_cache()
         rows["gemv"] = gemv_rows
+        # decode of other patterns at 6912x2560, T = 8, through automatic path selection: instances of 2:4 are
+        # rewritten into the 2:4 operand form per call, everything else into dense 2-bit codes (6:8 is the
+        # paper's main pattern); N = M is stored as dense codes, so it also streams in a grouped call
+        other = {}
+        X8 = sbn_synth.activations(8, H, sbn_synth.seed_for(2, 8), device=dev)
+        Y8 = [torch.empty(8, F, dtype=torch.float32, device=dev) for _ in range(8)]
+        for (n8, m8) in ((6, 8), (2, 8), (1, 4), (8, 8)):
+            pk = [pack_one(sbn_synth.latent_weight(F, H, sbn_synth.seed_for(2, 300 + r), device=dev), n8, m8) for r in range(8)]
+            ws1 = sbn.new_workspace(sbn.sbn_workspace_bytes(sbn.SBN_OP_LINEAR, 8, F, H, n8, m8), dev)
+            k = [0]
+
+            def single_p(pk=pk, n8=n8, m8=m8, ws1=ws1):
+                r = k[0] % 8
+                k[0] += 1
+                sbn.sbn_sparse_ternary_linear(X8, pk[r][0], pk[r][1], Y8[r], n8, m8, ws1, path=sbn.SBN_PATH_AUTO)
+            us = timed(single_p, 256, 8) * 1e3
+            other[f"{n8}of{m8}"] = {"single_call_us_with_rewrite": us, "packed_bytes": sbn.sbn_packed_bytes(F, H, n8, m8)}
+            log(f"[gemv] {n8}:{m8} 6912x2560 T=8 single call {us:.1f} us")
+            del pk, ws1
+        packs = [pack_one(sbn_synth.latent_weight(F, H, sbn_synth.seed_for(2, 400 + r), device=dev), 8, 8) for r in range(R)]
+        pbytes = sbn.sbn_packed_bytes(F, H, 8, 8)
+        Yl = [torch.empty(8, F, dtype=torch.float32, device=dev) for _ in range(R)]
+        ws = sbn.new_workspace(R * sbn.sbn_workspace_bytes(sbn.SBN_OP_LINEAR, 8, F, H, 8, 8), dev)
+        grp = sbn.LinearGroup([X8] * R, [p for p, _ in packs], [g for _, g in packs], Yl, 8, 8, ws, sbn.SBN_PATH_GEMV)
+        ms = timed(grp.run, 100, 3)
+        gbps = R * pbytes / (ms * 1e-3) / 1e9
+        other["8of8"].update({"stream_gbps": gbps, "frac_hbm": gbps / HBM_PEAK_GBPS, "copies": R})
+        log(f"[gemv] 8:8 (dense 2-bit codes) 6912x2560 T=8: stream {gbps:.0f} GB/s ({gbps / HBM_PEAK_GBPS:.1%} of HBM peak)")
+        del packs, grp
+        # 6:8 converted once into dense codes (sbn_convert_packed), then streamed like any pre-packed weight
+        convs = []
+        for r in range(R):
+            p68, g68 = pack_one(sbn_synth.latent_weight(F, H, sbn_synth.seed_for(2, 500 + r), device=dev), 6, 8)
+            c = torch.empty(pbytes, dtype=torch.uint8, device=dev)
+            sbn.sbn_convert_packed(p68, F, H, 6, 8, 8, 8, c)
+            convs.append((c, g68))
+        torch.cuda.synchronize()
+        grp = sbn.LinearGroup([X8] * R, [c for c, _ in convs], [g for _, g in convs], Yl, 8, 8, ws, sbn.SBN_PATH_GEMV)
+        ms = timed(grp.run, 100, 3)
+        gbps = R * pbytes / (ms * 1e-3) / 1e9
+        k = [0]
+
+        def single_c():
+            r = k[0] % R
+            k[0] += 1
+            sbn.sbn_sparse_ternary_linear(X8, convs[r][0], convs[r][1], Yl[r], 8, 8, ws, path=sbn.SBN_PATH_GEMV)
+        us = timed(single_c, 256, 8) * 1e3
+        other["6of8"].update({"converted_once_stream_gbps": gbps, "converted_once_frac_hbm": gbps / HBM_PEAK_GBPS,
+                              "converted_once_single_call_us": us, "converted_bytes": pbytes})
+        log(f"[gemv] 6:8 converted once to dense codes: stream {gbps:.0f} GB/s ({gbps / HBM_PEAK_GBPS:.1%} of HBM peak), "
+            f"single call {us:.1f} us")
+        del convs, Yl, ws, grp, Y8
+        torch.cuda.empty_cache()
+        rows["gemv_other_patterns"] = other
         best = gemv_rows["up_6912x2560_T8"]
         roofline_gemv = {"kernel": "gemv_stream_kernel", "workload": "64 x (6912x2560 packed 2:4), T=8, grouped",
                          "bound": "hbm", "achieved": best["stream_gbps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",

@@ -50,10 +50,13 @@ typedef enum {
 typedef enum { SBN_F32 = 0, SBN_BF16 = 1 } sbn_dtype;
 
 typedef enum {
-    SBN_PATH_AUTO = 0,       /* 2:4 and its instances (1:2, 1:4, 1:8, 2:8) with d_in % 128 == 0: GEMV for tokens <= 16,
-                                sparse MFMA GEMM otherwise; any other case: dense MFMA if d_in % 64 == 0, generic else */
-    SBN_PATH_GEMV = 1,       /* decode kernel: streams the packed weights once; tokens <= 16, 2:4 (instances of 2:4 are
-                                rewritten into the 2:4 form first, which costs a pass over the packed weights) */
+    SBN_PATH_AUTO = 0,       /* d_in % 128 == 0 and tokens <= 16: GEMV.  2:4 and its instances (1:2, 1:4, 1:8, 2:8) with
+                                d_in % 128 == 0 and more tokens: sparse MFMA GEMM.  Any other case: dense MFMA if
+                                d_in % 64 == 0, generic else */
+    SBN_PATH_GEMV = 1,       /* decode kernel: streams the packed weights once; tokens <= 16, d_in % 128 == 0.  2:4 runs
+                                on the sparse instruction and N = M (dense 2-bit codes) on the dense one as stored; other
+                                patterns are rewritten per call into one of the two (a pass over the packed weights:
+                                sbn_convert_packed does it once instead) */
     SBN_PATH_SMFMAC = 2,     /* prefill/training GEMM on sparse int8 MFMA (v_smfmac); 2:4 and its instances, d_in % 128 == 0 */
     SBN_PATH_DENSE_MFMA = 3, /* W_eff expanded to int8 with explicit zeros, dense int8 MFMA: the comparison path for 2:4
                                 and the matrix-core path of every other pattern (6:8, N:8, 1:4, ...); d_in % 64 == 0 */
@@ -183,6 +186,25 @@ sbn_status sbn_unpack(const void *packed, int64_t d_out, int64_t d_in, int N, in
  */
 sbn_status sbn_mask_flips(const void *packed_a, const void *packed_b, int64_t d_out, int64_t d_in, int N,
                           int M, uint64_t *flips_out, void *workspace, size_t ws_bytes, void *stream);
+
+/*
+ * Rewrites a packed N:M matrix into the packed form of another pattern that can hold the same
+ * W_eff, so that decode calls stream the weights as stored instead of rewriting them per call
+ * ("weights pre-packed once"; Section 4.3 measures decode on the 6:8 model):
+ *   to_N:to_M = 2:4  for patterns that keep at most two weights of every aligned four (1:2, 1:4, 1:8, 2:8):
+ *                    the operand form of the sparse matrix instruction, with zero-code padding slots;
+ *   to_N == to_M     for any pattern: dense 2-bit codes with explicit zeros at the dropped positions
+ *                    (2 bits per weight; 6:8's own packed form is 3.75).
+ * The result is used with N = to_N, M = to_M in sbn_sparse_ternary_linear[_grouped] and gives the same
+ * accumulators and Y as the original; it no longer tells kept zeros from dropped weights, so it serves
+ * the forward only (sbn_mask_flips and the backward want the original).
+ *   packed  device, as written by sbn_quantize_mask_pack at N:M, 16-byte aligned; d_in % 128 == 0
+ *   out     device, sbn_packed_bytes(d_out, d_in, to_N, to_M) bytes, 16-byte aligned, overwritten
+ * Errors: SBN_EINVAL (null, bad sizes), SBN_EUNSUPPORTED (target cannot hold the pattern, target equal
+ * to the source, ragged d_in), SBN_EALIGN, SBN_EHIP.  Enqueues one kernel.
+ */
+sbn_status sbn_convert_packed(const void *packed, int64_t d_out, int64_t d_in, int N, int M, int to_N, int to_M,
+                              void *out, void *stream);
 
 /* Text of the last HIP error seen by this thread ("" if none). */
 const char *sbn_last_error(void);

@@ -57,6 +57,8 @@ def _load():
     lib.sbn_sparse_ternary_linear_backward.argtypes = [vp, i64, i64, i64, cint, cint, vp, vp, vp, vp, vp, vp, cint, vp, sz, vp]
     lib.sbn_unpack.restype = cint
     lib.sbn_unpack.argtypes = [vp, i64, i64, cint, cint, vp, vp, vp]
+    lib.sbn_convert_packed.restype = cint
+    lib.sbn_convert_packed.argtypes = [vp, i64, i64, cint, cint, cint, cint, vp, vp]
     lib.sbn_mask_flips.restype = cint
     lib.sbn_mask_flips.argtypes = [vp, vp, i64, i64, cint, cint, vp, vp, sz, vp]
     return lib
@@ -221,6 +223,11 @@ def sbn_sparse_ternary_linear_backward(dY, packed, gamma, xq, sx, N: int, M: int
 
 def sbn_unpack(packed, d_out: int, d_in: int, N: int, M: int, W_eff=None, mask=None):
     _check(_lib.sbn_unpack(_ptr(packed), d_out, d_in, N, M, _ptr(W_eff), _ptr(mask), _stream()), "sbn_unpack")
+
+
+def sbn_convert_packed(packed, d_out: int, d_in: int, N: int, M: int, to_N: int, to_M: int, out):
+    """Rewrite a packed N:M matrix into the packed form of to_N:to_M (2:4 or M:M) for decode."""
+    _check(_lib.sbn_convert_packed(_ptr(packed), d_out, d_in, N, M, to_N, to_M, _ptr(out), _stream()), "sbn_convert_packed")
 
 
 def sbn_mask_flips(packed_a, packed_b, d_out: int, d_in: int, N: int, M: int, flips_out, workspace):

@@ -42,6 +42,7 @@ static sbn_path resolve_path(sbn_path path, int64_t tokens, int64_t d_in, const 
     // decode sizes they run on the dense int8 matrix cores with explicit zeros
     // 2:4 and its instances (1:4, 2:8, ...: rewritten into the 2:4 operand form first) take the sparse instruction
     if ((is24 || embeds_in_2of4(pat)) && d_in % CHUNK == 0) return tokens <= 16 ? SBN_PATH_GEMV : SBN_PATH_SMFMAC;
+    if (tokens <= 16 && d_in % CHUNK == 0) return SBN_PATH_GEMV;   // decode of every other pattern: dense 2-bit codes
     return d_in % 64 == 0 ? SBN_PATH_DENSE_MFMA : SBN_PATH_GENERIC;
 }
 
@@ -139,7 +140,8 @@ static sbn_status linear_one(const LinearItem &it_in, const Pattern &pat, sbn_pa
     LinearItem it = it_in;
     const bool is24 = pat.N == 2 && pat.M == 4;
     path = resolve_path(path, it.tokens, it.d_in, pat);
-    if (path != SBN_PATH_GENERIC && path != SBN_PATH_DENSE_MFMA && !is24 && !embeds_in_2of4(pat)) return SBN_EUNSUPPORTED;
+    const bool sparse_form = is24 || embeds_in_2of4(pat);   // runs on the sparse instruction (after a rewrite unless 2:4)
+    if (path == SBN_PATH_SMFMAC && !sparse_form) return SBN_EUNSUPPORTED;
     if (path == SBN_PATH_GEMV && it.tokens > 16) return SBN_EUNSUPPORTED;
     if ((path == SBN_PATH_GEMV || path == SBN_PATH_SMFMAC) && it.d_in % CHUNK != 0) return SBN_EUNSUPPORTED;
     if (path == SBN_PATH_DENSE_MFMA && it.d_in % 64 != 0) return SBN_EUNSUPPORTED;
@@ -155,14 +157,20 @@ static sbn_status linear_one(const LinearItem &it_in, const Pattern &pat, sbn_pa
     sbn_status st = SBN_OK;
     if (it.X) st = launch_act_quant(it.X, it.tokens, it.d_in, it.xq, it.sx, stream);
     if (st != SBN_OK) return st;
-    if ((path == SBN_PATH_GEMV || path == SBN_PATH_SMFMAC) && !is24) {
+    if ((path == SBN_PATH_GEMV || path == SBN_PATH_SMFMAC) && !is24 && sparse_form) {
         // an instance of 2:4: the dense-weight region of the workspace takes its 2:4 operand form (a quarter of the size)
         st = launch_repack_2of4(it.packed, it.d_out, it.d_in, pat, reinterpret_cast<uint8_t *>(w_dense), stream);
         if (st != SBN_OK) return st;
         it.packed = w_dense;
     }
+    if (path == SBN_PATH_GEMV && !sparse_form && pat.N != pat.M) {
+        // no sparse instruction for this pattern: decode streams dense 2-bit codes (N = M is stored that way already)
+        st = launch_repack_dense_codes(it.packed, it.d_out, it.d_in, pat, reinterpret_cast<uint8_t *>(w_dense), stream);
+        if (st != SBN_OK) return st;
+        it.packed = w_dense;
+    }
     switch (path) {
-    case SBN_PATH_GEMV: return launch_gemv(1, &it, stream);
+    case SBN_PATH_GEMV: return launch_gemv(1, &it, !sparse_form, stream);
     case SBN_PATH_SMFMAC: return launch_gemm_smfmac(1, &it, stream);
     case SBN_PATH_DENSE_MFMA: return launch_gemm_dense(it, pat, w_dense, stream);
     case SBN_PATH_GENERIC: return launch_linear_generic(it, pat, stream);
@@ -210,8 +218,9 @@ sbn_status sbn_sparse_ternary_linear_grouped(int count, const void *const *X, co
         if (d_in[i] % 8 != 0) return SBN_EUNSUPPORTED;
         need += linear_workspace_bytes(tokens[i], d_out[i], d_in[i]);
         const bool is24 = pat.N == 2 && pat.M == 4;
-        if (resolve_path(path, tokens[i], d_in[i], pat) != SBN_PATH_GEMV || !is24 || tokens[i] > 16 || d_in[i] % CHUNK != 0)
-            all_gemv = false;
+        if (resolve_path(path, tokens[i], d_in[i], pat) != SBN_PATH_GEMV || !(is24 || pat.N == pat.M) || tokens[i] > 16 ||
+            d_in[i] % CHUNK != 0)
+            all_gemv = false;   // one launch streams 2:4 or dense-code (N = M) weights as stored; other patterns need a rewrite each
         if (resolve_path(path, tokens[i], d_in[i], pat) != SBN_PATH_SMFMAC || !is24 || d_in[i] % CHUNK != 0 ||
             tokens[i] * d_out[i] >= (int64_t)1 << 40)
             all_smfmac = false;
@@ -251,7 +260,7 @@ sbn_status sbn_sparse_ternary_linear_grouped(int count, const void *const *X, co
             if (st != SBN_OK) return st;
         }
     }
-    return all_gemv ? launch_gemv(count, tl_items.data(), s) : launch_gemm_smfmac(count, tl_items.data(), s);
+    return all_gemv ? launch_gemv(count, tl_items.data(), pat.N == pat.M, s) : launch_gemm_smfmac(count, tl_items.data(), s);
 }
 
 sbn_status sbn_sparse_ternary_linear_backward(const void *dY, int64_t tokens, int64_t d_in, int64_t d_out, int N,
@@ -283,6 +292,23 @@ sbn_status sbn_mask_flips(const void *packed_a, const void *packed_b, int64_t d_
     if (!aligned(packed_a, 16) || !aligned(packed_b, 16) || !aligned(flips_out, 8) || !aligned(workspace, 256)) return SBN_EALIGN;
     if (ws_bytes < mask_flips_workspace_bytes(d_out, d_in, M)) return SBN_ESIZE;
     return launch_mask_flips(packed_a, packed_b, d_out, d_in, pat, flips_out, workspace, static_cast<hipStream_t>(stream));
+}
+
+sbn_status sbn_convert_packed(const void *packed, int64_t d_out, int64_t d_in, int N, int M, int to_N, int to_M, void *out,
+                              void *stream)
+{
+    Pattern pat, to;
+    if (!packed || !out) return SBN_EINVAL;
+    sbn_status st = check_shape(d_out, d_in, N, M, pat);
+    if (st != SBN_OK) return st;
+    st = check_shape(d_out, d_in, to_N, to_M, to);
+    if (st != SBN_OK) return st;
+    if (!aligned(packed, 16) || !aligned(out, 16)) return SBN_EALIGN;
+    if (d_in % CHUNK != 0 || (N == to_N && M == to_M)) return SBN_EUNSUPPORTED;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (to_N == 2 && to_M == 4 && embeds_in_2of4(pat)) return launch_repack_2of4(packed, d_out, d_in, pat, static_cast<uint8_t *>(out), s);
+    if (to_N == to_M) return launch_repack_dense_codes(packed, d_out, d_in, pat, static_cast<uint8_t *>(out), s);
+    return SBN_EUNSUPPORTED;
 }
 
 }  // extern "C"

@@ -61,6 +61,9 @@ sbn_status launch_mask_flips(const void *packed_a, const void *packed_b, int64_t
 inline bool embeds_in_2of4(const Pattern &p) { return (p.M == 2 && p.N == 1) || (p.M >= 4 && p.N <= 2); }
 sbn_status launch_repack_2of4(const void *packed, int64_t d_out, int64_t d_in, const Pattern &pat, uint8_t *out24,
                               hipStream_t stream);
+// any pattern -> dense 2-bit codes (the packed form of N = M), explicit zero codes at the dropped positions
+sbn_status launch_repack_dense_codes(const void *packed, int64_t d_out, int64_t d_in, const Pattern &pat, uint8_t *out,
+                                     hipStream_t stream);
 sbn_status launch_expand_groups(const void *packed, int64_t d_out, int64_t d_in, const Pattern &pat, int8_t *W_eff,
                                 hipStream_t stream);
 sbn_status launch_unpack(const void *packed, int64_t d_out, int64_t d_in, const Pattern &pat,
@@ -81,7 +84,8 @@ struct LinearItem {
 size_t linear_workspace_bytes(int64_t tokens, int64_t d_out, int64_t d_in);
 sbn_status launch_act_quant(const void *X, int64_t tokens, int64_t d_in, int8_t *xq, float *sx,
                             hipStream_t stream);
-sbn_status launch_gemv(int count, const LinearItem *items, hipStream_t stream);
+// dense_codes: the weights are dense 2-bit codes (packed form of N = M) instead of the 2:4 form
+sbn_status launch_gemv(int count, const LinearItem *items, bool dense_codes, hipStream_t stream);
 sbn_status launch_gemm_smfmac(int count, const LinearItem *items, hipStream_t stream);
 sbn_status launch_gemm_dense(const LinearItem &it, const Pattern &pat, int8_t *w_dense, hipStream_t stream);
 sbn_status launch_linear_generic(const LinearItem &it, const Pattern &pat, hipStream_t stream);

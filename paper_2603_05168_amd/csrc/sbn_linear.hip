@@ -154,6 +154,11 @@ struct GemvTable {
     GemvItem it[GEMV_MAX_ITEMS];   // problem = blockIdx.y; row tile = blockIdx.x (surplus blocks exit at once)
 };
 
+// DENSE = true is the same kernel for weights stored as dense 2-bit codes (the packed form of
+// N = M, and what other patterns are rewritten to for decode): a chunk is eight code words, every
+// word is the A operand of one v_mfma_i32_16x16x64_i8 (lane quarter c holds k = 16c .. 16c+15 of
+// the instruction on both operands), so a super-step is eight dense instructions instead of four sparse.
+template <bool DENSE>
 __global__ void __launch_bounds__(1024) gemv_smfmac_kernel(GemvTable tab)
 {
     __shared__ v4i red[16][64];
@@ -182,6 +187,18 @@ __global__ void __launch_bounds__(1024) gemv_smfmac_kernel(GemvTable tab)
         const uint32_t codew[4] = {code4.x, code4.y, code4.z, code4.w};
         // B operand: elements 0..15 pair with the A lanes of quarters 0/1, elements 16..31 with
         // quarters 2/3 (measured operand layout of the instruction)
+        if constexpr (DENSE) {
+            const uint32_t w8[8] = {idx4.x, idx4.y, idx4.z, idx4.w, code4.x, code4.y, code4.z, code4.w};
+            const int kd = s * 512 + 128 * c4;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                uint4 bv = make_uint4(0, 0, 0, 0);
+                if (tok_ok && kd + 16 * j < K) bv = *reinterpret_cast<const uint4 *>(xrow + kd + 16 * j);
+                const v4i b = {(int)bv.x, (int)bv.y, (int)bv.z, (int)bv.w};
+                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(expand_codes(w8[j], ones), b, acc, 0, 0, 0);
+            }
+            continue;
+        }
         const int kb = s * 512 + 128 * (c4 >> 1) + 16 * (c4 & 1);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -237,7 +254,7 @@ struct GemvStreamTable {
     int count;
 };
 
-template <int RT, int DEPTH, int NW>
+template <int RT, int DEPTH, int NW, bool DENSE>
 __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable tab)
 {
     extern __shared__ __attribute__((aligned(16))) int8_t xlds[];   // [tokens][d_in + 16]
@@ -259,7 +276,7 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
         u = seg_end;
         const int K = it.d_in, nchunks = K / CHUNK, nsuper = (nchunks + 3) / 4, pitch = K + 16;
         const bool tok_ok = r < it.tokens;
-        const int xoff = (tok_ok ? r : 0) * pitch + 128 * (c4 >> 1) + 16 * (c4 & 1);
+        const int xoff = (tok_ok ? r : 0) * pitch + (DENSE ? 128 * c4 : 128 * (c4 >> 1) + 16 * (c4 & 1));
         const bool ragged = (nchunks & 3) != 0;   // the last super-step of a unit then covers fewer than four chunks
 
         // Wavefronts of a block advance at very different speeds (measured: the first one to finish
@@ -338,10 +355,25 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
                 issue(qi[d], qc[d]);
                 if ((ragged && cs == nsuper - 1 && 4 * cs + c4 >= nchunks) || cu >= wb) {
 #pragma unroll
-                    for (int a = 0; a < RT; ++a) cc[a] = make_uint4(0, 0, 0, 0);
+                    for (int a = 0; a < RT; ++a) {
+                        cc[a] = make_uint4(0, 0, 0, 0);
+                        if constexpr (DENSE) ic[a] = make_uint4(0, 0, 0, 0);   // all eight words are codes
+                    }
+                }
+                if constexpr (DENSE) {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const v4i b = *reinterpret_cast<const v4i *>(&xlds[xoff + cs * 512 + 16 * j]);
+#pragma unroll
+                        for (int a = 0; a < RT; ++a) {
+                            const uint4 &half = j < 4 ? ic[a] : cc[a];
+                            const uint32_t cw = (j & 3) == 0 ? half.x : (j & 3) == 1 ? half.y : (j & 3) == 2 ? half.z : half.w;
+                            acc[a] = __builtin_amdgcn_mfma_i32_16x16x64_i8(expand_codes(cw, ones), b, acc[a], 0, 0, 0);
+                        }
+                    }
                 }
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
+                for (int j = 0; j < (DENSE ? 0 : 4); ++j) {
                     const uint4 blo = *reinterpret_cast<const uint4 *>(&xlds[xoff + cs * 512 + 32 * j]);
                     const uint4 bhi = *reinterpret_cast<const uint4 *>(&xlds[xoff + cs * 512 + 32 * j + 256]);
                     const v8i b = {(int)blo.x, (int)blo.y, (int)blo.z, (int)blo.w, (int)bhi.x, (int)bhi.y, (int)bhi.z, (int)bhi.w};
@@ -466,7 +498,16 @@ static int device_cus()
     return cus;
 }
 
-sbn_status launch_gemv(int count, const LinearItem *items, hipStream_t stream)
+template <bool DENSE>
+static sbn_status launch_gemv_as(int count, const LinearItem *items, hipStream_t stream);
+
+sbn_status launch_gemv(int count, const LinearItem *items, bool dense_codes, hipStream_t stream)
+{
+    return dense_codes ? launch_gemv_as<true>(count, items, stream) : launch_gemv_as<false>(count, items, stream);
+}
+
+template <bool DENSE>
+static sbn_status launch_gemv_as(int count, const LinearItem *items, hipStream_t stream)
 {
     constexpr int RT = 2;
     int first = 0;
@@ -503,12 +544,12 @@ sbn_status launch_gemv(int count, const LinearItem *items, hipStream_t stream)
             constexpr int DEPTH = 4, NW = 8;
             static thread_local bool raised = false;
             if (!raised) {
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemv_stream_kernel<RT, DEPTH, NW>),
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemv_stream_kernel<RT, DEPTH, NW, DENSE>),
                                                    hipFuncAttributeMaxDynamicSharedMemorySize, GEMV_STREAM_LDS);
                 if (e != hipSuccess) { set_hip_error(e, "hipFuncSetAttribute"); return SBN_EHIP; }
                 raised = true;
             }
-            hipLaunchKernelGGL((gemv_stream_kernel<RT, DEPTH, NW>), dim3(nblocks), dim3(64 * NW), (size_t)lds_need, stream, tab);
+            hipLaunchKernelGGL((gemv_stream_kernel<RT, DEPTH, NW, DENSE>), dim3(nblocks), dim3(64 * NW), (size_t)lds_need, stream, tab);
             sbn_status st = check_launch("gemv_stream_kernel");
             if (st != SBN_OK) return st;
             first += n;
@@ -528,7 +569,7 @@ sbn_status launch_gemv(int count, const LinearItem *items, hipStream_t stream)
         }
         // one wavefront per super-step up to 16, so that every wavefront has loads in flight at once
         const int nwaves = max_super < 16 ? max_super : 16;
-        hipLaunchKernelGGL(gemv_smfmac_kernel, dim3(blocks, n), dim3(64 * nwaves), 0, stream, tab);
+        hipLaunchKernelGGL(gemv_smfmac_kernel<DENSE>, dim3(blocks, n), dim3(64 * nwaves), 0, stream, tab);
         sbn_status st = check_launch("gemv_smfmac_kernel");
         if (st != SBN_OK) return st;
         first += n;

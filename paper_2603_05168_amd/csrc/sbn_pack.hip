@@ -750,6 +750,48 @@ sbn_status launch_repack_2of4(const void *packed, int64_t d_out, int64_t d_in, c
     return check_launch("repack_2of4_kernel");
 }
 
+// Any pattern -> dense 2-bit codes (the packed form of N = M: eight code words per 128-weight chunk,
+// weight p of the chunk in word p / 16 at bits 8 * (p % 4) + 2 * ((p % 16) / 4)), zero codes at the
+// dropped positions.  One thread per output word (16 weights = 16 / M groups).  Whole chunks only.
+__global__ void __launch_bounds__(256) repack_dense_codes_kernel(const uint8_t *__restrict__ packed, int64_t nwords, Pattern pat,
+                                                                 uint32_t *__restrict__ out)
+{
+    const int64_t wid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (wid >= nwords) return;
+    const int64_t chunk = wid >> 3;
+    const int w = (int)(wid & 7);
+    const uint8_t *idx_field = packed + chunk * pat.chunk_bytes;
+    const uint8_t *code_field = idx_field + pat.idx_bytes;
+    const int gpw = 16 / pat.M;   // groups per word
+    uint32_t word = 0;
+    for (int gl = 0; gl < gpw; ++gl) {
+        for (int n = 0; n < pat.N; ++n) {
+            const int slot = (w * gpw + gl) * pat.N + n;
+            int j = n;
+            if (pat.b) {
+                const int p = slot * pat.b;
+                const uint32_t two = (uint32_t)idx_field[p >> 3] | ((uint32_t)idx_field[(p >> 3) + 1] << 8);   // the next byte is still inside the chunk
+                j = (int)((two >> (p & 7)) & ((1u << pat.b) - 1u));
+            }
+            const int sv = slot & 15;
+            const int cp = 32 * (slot >> 4) + 8 * (sv & 3) + 2 * (sv >> 2);
+            const uint32_t code = (code_field[cp >> 3] >> (cp & 7)) & 3u;
+            const int v = gl * pat.M + j;
+            word |= code << (8 * (v & 3) + 2 * (v >> 2));
+        }
+    }
+    out[wid] = word;
+}
+
+sbn_status launch_repack_dense_codes(const void *packed, int64_t d_out, int64_t d_in, const Pattern &pat, uint8_t *out,
+                                     hipStream_t stream)
+{
+    const int64_t nwords = d_out * (d_in / CHUNK) * 8;
+    hipLaunchKernelGGL(repack_dense_codes_kernel, dim3((unsigned)ceil_div(nwords, 256)), dim3(256), 0, stream,
+                       static_cast<const uint8_t *>(packed), nwords, pat, reinterpret_cast<uint32_t *>(out));
+    return check_launch("repack_dense_codes_kernel");
+}
+
 sbn_status launch_expand_groups(const void *packed, int64_t d_out, int64_t d_in, const Pattern &pat, int8_t *W_eff,
                                 hipStream_t stream)
 {

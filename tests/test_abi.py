@@ -113,4 +113,16 @@ def test_argument_errors_come_before_any_launch(sbn):
     assert flips(a=0) == sbn.SBN_EINVAL
     assert flips(out=A + 4) == sbn.SBN_EALIGN
     assert flips(ws=8) == sbn.SBN_ESIZE
+    # conversion of packed forms: null, target that cannot hold the pattern, same form, ragged rows
+    lib.sbn_convert_packed.restype = ctypes.c_int
+    conv = lambda **kw: lib.sbn_convert_packed(  # noqa: E731
+        vp(kw.get("src", A)), i64(64), i64(kw.get("d_in", 256)), ci(kw.get("N", 6)), ci(kw.get("M", 8)),
+        ci(kw.get("to_N", 8)), ci(kw.get("to_M", 8)), vp(kw.get("out", A)), vp(0))
+    assert conv(src=0) == sbn.SBN_EINVAL
+    assert conv(out=A + 4) == sbn.SBN_EALIGN
+    assert conv(to_N=2, to_M=4) == sbn.SBN_EUNSUPPORTED          # 6:8 keeps more than two of an aligned four
+    assert conv(N=2, M=4, to_N=2, to_M=4) == sbn.SBN_EUNSUPPORTED  # already in that form
+    assert conv(to_N=1, to_M=4) == sbn.SBN_EUNSUPPORTED          # only 2:4 and N = M are decode forms
+    assert conv(d_in=200) == sbn.SBN_EUNSUPPORTED                # whole 128-weight chunks only
+    assert conv(to_N=9, to_M=8) == sbn.SBN_EINVAL
     assert sbn.sbn_last_error() == ""

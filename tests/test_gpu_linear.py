@@ -108,14 +108,62 @@ def test_sparse_mfma_path_instances_of_2of4(N, M, tokens, shape):
 @pytest.mark.parametrize("N,M", [(1, 4), (2, 8), (6, 8), (3, 8)])
 @pytest.mark.parametrize("tokens", [1, 8, 16])
 def test_decode_sizes_other_patterns_through_path_selection(N, M, tokens):
-    # decode batches of other patterns: instances of 2:4 take the decode kernel after the operand rewrite,
-    # the rest the dense matrix path; never the scalar reference kernel when a matrix path applies
+    # decode batches of other patterns: instances of 2:4 take the decode kernel after the rewrite into the
+    # 2:4 operand form, the rest after the rewrite into dense 2-bit codes (dense matrix instruction)
     s = sbn()
     W = sbn_synth.latent_weight(200, 640, 490 + N + M)
     X = sbn_synth.activations(tokens, 640, 491 + tokens)
     check_forward(W, X, N, M, s.SBN_PATH_AUTO)
-    if N <= 2:
-        check_forward(W, X, N, M, s.SBN_PATH_GEMV)
+    check_forward(W, X, N, M, s.SBN_PATH_GEMV)
+
+
+@pytest.mark.parametrize("N,M", [(6, 8), (3, 8), (7, 8), (5, 8), (4, 8), (3, 4), (8, 8), (4, 4), (2, 2)])
+@pytest.mark.parametrize("tokens,shape", [(1, (48, 128)), (5, (100, 640)), (16, (250, 1792)), (8, (33, 2560))])
+def test_decode_dense_codes_shapes(N, M, tokens, shape):
+    # the decode kernel on dense 2-bit codes: ragged row counts, a partial last super-step (640 = 5 chunks,
+    # 1792 = 14), bias; N = M is stored as dense codes and needs no rewrite
+    s = sbn()
+    W = sbn_synth.latent_weight(shape[0], shape[1], 1500 + 10 * N + M)
+    X = sbn_synth.activations(tokens, shape[1], 1501 + tokens)
+    bias = torch.randn(shape[0], generator=torch.Generator().manual_seed(11))
+    check_forward(W, X, N, M, s.SBN_PATH_GEMV, bias=bias)
+
+
+def test_decode_dense_codes_adversarial_and_full_size():
+    s = sbn()
+    W = sbn_synth.adversarial_weight(64, 512, 1510)
+    X = sbn_synth.adversarial_activations(8, 512, 1511)
+    check_forward(W, X, 6, 8, s.SBN_PATH_GEMV)
+    check_forward(W, X, 8, 8, s.SBN_PATH_GEMV)
+    # the paper's main pattern at the decode shapes of configs[1]
+    for shape, tokens in (((6912, 2560), 8), ((2560, 6912), 1)):
+        W = sbn_synth.latent_weight(shape[0], shape[1], sbn_synth.seed_for(2, 68 + shape[0]))
+        X = sbn_synth.activations(tokens, shape[1], sbn_synth.seed_for(2, 168 + tokens))
+        check_forward(W, X, 6, 8, s.SBN_PATH_AUTO)
+
+
+@pytest.mark.parametrize("tokens", [1, 8, 16])
+def test_grouped_streaming_dense_codes_against_oracle(tokens):
+    # N = M (plain ternary weights, no mask) in one grouped call: the persistent streaming kernel on dense codes
+    s = sbn()
+    shapes = [(4100, 768), (4096, 256), (5000, 640)] * 14
+    Ws = {sh: sbn_synth.latent_weight(sh[0], sh[1], 1550 + sh[0]) for sh in set(shapes)}
+    packs = {sh: hip_pack(W, 8, 8) for sh, W in Ws.items()}
+    Xs = {k: sbn_synth.activations(tokens, k, 1560 + k) for k in (768, 256, 640)}
+    Xd = {k: x.to(DEV) for k, x in Xs.items()}
+    Y_list = [torch.full((tokens, a), float("nan"), dtype=torch.float32, device=DEV) for a, _ in shapes]
+    need = sum(s.sbn_workspace_bytes(s.SBN_OP_LINEAR, tokens, a, b, 8, 8) for a, b in shapes)
+    ws = s.new_workspace(need)
+    s.sbn_sparse_ternary_linear_grouped([Xd[b] for _, b in shapes], [packs[sh][0] for sh in shapes],
+                                        [packs[sh][1] for sh in shapes], Y_list, 8, 8, ws, path=s.SBN_PATH_GEMV)
+    torch.cuda.synchronize()
+    ref = {}
+    for sh, W in Ws.items():
+        _, g, Weff, _ = oracle_pack(W, 8, 8)
+        y, *_ = oracle.sparse_ternary_linear(Xs[sh[1]].float().numpy(), Weff, g)
+        ref[sh] = y
+    for i, sh in enumerate(shapes):
+        assert_rel(Y_list[i].cpu().numpy(), ref[sh], Y_TOL, f"Y of problem {i}")
 
 
 def test_sparse_mfma_path_adversarial_2of8():
@@ -355,3 +403,49 @@ def test_gemm_sparse_without_accumulator_output(tokens, shape):
     y_nb, *_ = oracle.sparse_ternary_linear(X.float().numpy(), Weff, g)
     ref = y_nb[rows] + bias.numpy().astype(np.float64)
     assert (np.abs(Y[rows] - ref) <= 1e-3 * (np.abs(y_nb[rows]) + np.abs(bias.numpy()))).all()
+
+
+@pytest.mark.parametrize("N,M,to", [(6, 8, (8, 8)), (3, 8, (8, 8)), (3, 4, (4, 4)), (2, 8, (2, 4)), (1, 4, (2, 4)), (1, 8, (8, 8)), (2, 4, (4, 4))])
+def test_convert_packed_once_then_decode(N, M, to):
+    # weights rewritten once into a form the decode kernel streams as stored: the rewritten matrix unpacks to
+    # the oracle's W_eff, and the layer on it (pattern = the target's) gives the oracle's integers and Y
+    s = sbn()
+    d_out, d_in, tokens = 200, 640, 8
+    W = sbn_synth.latent_weight(d_out, d_in, 1600 + 10 * N + M)
+    X = sbn_synth.activations(tokens, d_in, 1601)
+    packed, gamma = hip_pack(W, N, M)
+    _, ref_gamma, Weff, _ = oracle_pack(W, N, M)
+    conv = torch.full((s.sbn_packed_bytes(d_out, d_in, *to),), 0xA5, dtype=torch.uint8, device=DEV)
+    s.sbn_convert_packed(packed, d_out, d_in, N, M, to[0], to[1], conv)
+    We = torch.full((d_out, d_in), 9, dtype=torch.int8, device=DEV)
+    s.sbn_unpack(conv, d_out, d_in, to[0], to[1], We, None)
+    assert np.array_equal(We.cpu().numpy(), Weff)
+    Y, acc, xq, sx = hip_linear(X, conv, gamma, d_out, to[0], to[1], s.SBN_PATH_GEMV)
+    r_xq, r_sx = oracle.act_quant(X.float().numpy())
+    r_acc = oracle.acc(Weff, r_xq)
+    assert np.array_equal(acc, r_acc)
+    assert_rel(Y, oracle.rescale(r_acc, ref_gamma, r_sx, None), Y_TOL, "Y")
+
+
+def test_convert_packed_6of8_full_size_streaming():
+    # the paper's main pattern, decode shape of configs[1], converted once and streamed in one grouped call
+    s = sbn()
+    a, b, tokens, R = 6912, 2560, 8, 20
+    Ws = [sbn_synth.latent_weight(a, b, sbn_synth.seed_for(2, 680 + r)) for r in range(R)]
+    X = sbn_synth.activations(tokens, b, sbn_synth.seed_for(2, 688))
+    convs, gammas = [], []
+    for W in Ws:
+        packed, gamma = hip_pack(W, 6, 8)
+        conv = torch.empty(s.sbn_packed_bytes(a, b, 8, 8), dtype=torch.uint8, device=DEV)
+        s.sbn_convert_packed(packed, a, b, 6, 8, 8, 8, conv)
+        convs.append(conv)
+        gammas.append(gamma)
+    Ys = [torch.full((tokens, a), float("nan"), dtype=torch.float32, device=DEV) for _ in range(R)]
+    ws = s.new_workspace(R * s.sbn_workspace_bytes(s.SBN_OP_LINEAR, tokens, a, b, 8, 8))
+    s.sbn_sparse_ternary_linear_grouped([X.to(DEV)] * R, convs, gammas, Ys, 8, 8, ws, path=s.SBN_PATH_GEMV)
+    torch.cuda.synchronize()
+    Xf = X.float().numpy()
+    for r in (0, 7, 19):
+        _, g, Weff, _ = oracle_pack(Ws[r], 6, 8)
+        y, *_ = oracle.sparse_ternary_linear(Xf, Weff, g)
+        assert_rel(Ys[r].cpu().numpy(), y, Y_TOL, f"Y of copy {r}")
