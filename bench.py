@@ -46,8 +46,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=100)
-    ap.add_argument("--sections", default="gemm,gemv,pack,train,dense,cpu",
-                    help="comma list of: gemm (always timed), gemv, pack, train, dense, cpu, copyref")
+    ap.add_argument("--sections", default="gemm,gemv,pack,train,dense,ceil,cpu",
+                    help="comma list of: gemm (always timed), gemv, pack, train, dense, ceil, cpu, copyref")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build measures one GPU only (across GPUs the layer would shard by rows of W, with "
@@ -406,6 +406,34 @@ def main():
         rows["copyref_1GiB"] = {"ms": ms, "gbps": 2 * (1 << 30) / (ms * 1e-3) / 1e9}
         del a, b
 
+    # ------------------------------------------------------------------ ceilings this board sustains, next to the datasheet peaks
+    ceilings = None
+    if "ceil" in sections:
+        buf = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)   # 1 GiB: four times the Infinity Cache
+        ceilings = {}
+        for key, kind, iters, unit in (("smfmac_i8_dense_equiv", sbn.SBN_CEIL_SMFMAC_I8, 100, 1e12),
+                                       ("mfma_i8", sbn.SBN_CEIL_MFMA_I8, 100, 1e12),
+                                       ("mfma_bf16", sbn.SBN_CEIL_MFMA_BF16, 100, 1e12),
+                                       ("hbm_read", sbn.SBN_CEIL_HBM_READ, 1, 1e9),
+                                       ("hbm_write", sbn.SBN_CEIL_HBM_WRITE, 1, 1e9)):
+            work = [0.0]
+
+            def probe(kind=kind, iters=iters):
+                work[0] = sbn.sbn_ceiling_probe(kind, buf, iters)
+            ms = timed(probe, 200 if unit == 1e12 else 20, 2)
+            ceilings[key] = work[0] / (ms * 1e-3) / unit
+        ceilings["units"] = "TOP/s or TFLOP/s with random operands (matrix kinds), GB/s over 1 GiB (stream kinds)"
+        log("[ceil] sustained on this board: sparse int8 MFMA %.0f TOPS dense-equivalent, int8 MFMA %.0f TOPS, bf16 MFMA %.0f "
+            "TFLOP/s, HBM read %.0f GB/s, write %.0f GB/s" % (ceilings["smfmac_i8_dense_equiv"], ceilings["mfma_i8"],
+                                                             ceilings["mfma_bf16"], ceilings["hbm_read"], ceilings["hbm_write"]))
+        del buf
+        torch.cuda.empty_cache()
+        roofline["measured_ceiling"] = ceilings["smfmac_i8_dense_equiv"] / 2.0   # executed ops, like `achieved`
+        roofline["frac_of_measured_ceiling"] = roofline["achieved"] / roofline["measured_ceiling"]
+        if roofline_gemv is not None:
+            roofline_gemv["measured_ceiling"] = ceilings["hbm_read"]
+            roofline_gemv["frac_of_measured_ceiling"] = roofline_gemv["achieved"] / ceilings["hbm_read"]
+
     # ------------------------------------------------------------------ CPU oracle on a bounded sample of the same workload
     cpu_baseline = None
     if "cpu" in sections:
@@ -441,6 +469,7 @@ def main():
         "cpu_baseline": cpu_baseline,
         "gemv_gbps": None if roofline_gemv is None else roofline_gemv["achieved"],
         "roofline_gemv": roofline_gemv,
+        "ceilings": ceilings,
         "rows": rows,
     }
     print(json.dumps(out), flush=True)

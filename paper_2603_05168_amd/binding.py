@@ -59,6 +59,8 @@ def _load():
     lib.sbn_unpack.argtypes = [vp, i64, i64, cint, cint, vp, vp, vp]
     lib.sbn_convert_packed.restype = cint
     lib.sbn_convert_packed.argtypes = [vp, i64, i64, cint, cint, cint, cint, vp, vp]
+    lib.sbn_ceiling_probe.restype = cint
+    lib.sbn_ceiling_probe.argtypes = [cint, vp, sz, cint, ctypes.POINTER(ctypes.c_double), vp]
     lib.sbn_mask_flips.restype = cint
     lib.sbn_mask_flips.argtypes = [vp, vp, i64, i64, cint, cint, vp, vp, sz, vp]
     return lib
@@ -228,6 +230,17 @@ def sbn_unpack(packed, d_out: int, d_in: int, N: int, M: int, W_eff=None, mask=N
 def sbn_convert_packed(packed, d_out: int, d_in: int, N: int, M: int, to_N: int, to_M: int, out):
     """Rewrite a packed N:M matrix into the packed form of to_N:to_M (2:4 or M:M) for decode."""
     _check(_lib.sbn_convert_packed(_ptr(packed), d_out, d_in, N, M, to_N, to_M, _ptr(out), _stream()), "sbn_convert_packed")
+
+
+SBN_CEIL_SMFMAC_I8, SBN_CEIL_MFMA_I8, SBN_CEIL_MFMA_BF16, SBN_CEIL_HBM_READ, SBN_CEIL_HBM_WRITE = range(5)
+
+
+def sbn_ceiling_probe(kind: int, buf, iters: int = 1) -> float:
+    """Enqueue one ceiling-probe kernel; returns the operations or bytes it performs."""
+    work = ctypes.c_double(0.0)
+    _check(_lib.sbn_ceiling_probe(kind, _ptr(buf), buf.numel() * buf.element_size(), iters, ctypes.byref(work), _stream()),
+           "sbn_ceiling_probe")
+    return work.value
 
 
 def sbn_mask_flips(packed_a, packed_b, d_out: int, d_in: int, N: int, M: int, flips_out, workspace):

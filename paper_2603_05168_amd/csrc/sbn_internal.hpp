@@ -90,6 +90,11 @@ sbn_status launch_gemm_smfmac(int count, const LinearItem *items, hipStream_t st
 sbn_status launch_gemm_dense(const LinearItem &it, const Pattern &pat, int8_t *w_dense, hipStream_t stream);
 sbn_status launch_linear_generic(const LinearItem &it, const Pattern &pat, hipStream_t stream);
 
+int device_cus();   // multiprocessors of the current device
+
+// ---- ceiling probes (sbn_probe.hip) ---------------------------------------------------------------
+sbn_status launch_ceiling_probe(int kind, void *buf, size_t bytes, int iters, double *work_out, hipStream_t stream);
+
 // ---- backward (sbn_backward.hip) ---------------------------------------------------------------
 size_t backward_workspace_bytes(int64_t tokens, int64_t d_out, int64_t d_in);
 sbn_status launch_backward(const void *dY, int64_t tokens, int64_t d_in, int64_t d_out,

@@ -486,7 +486,7 @@ static void fill_gemv_item(GemvItem &g, const LinearItem &li)
 }
 
 // multiprocessors of the current device (cached per thread)
-static int device_cus()
+int device_cus()
 {
     static thread_local int cus = 0;
     if (cus == 0) {

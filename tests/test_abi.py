@@ -125,4 +125,12 @@ def test_argument_errors_come_before_any_launch(sbn):
     assert conv(to_N=1, to_M=4) == sbn.SBN_EUNSUPPORTED          # only 2:4 and N = M are decode forms
     assert conv(d_in=200) == sbn.SBN_EUNSUPPORTED                # whole 128-weight chunks only
     assert conv(to_N=9, to_M=8) == sbn.SBN_EINVAL
+    # ceiling probe: unknown kind, missing host output, buffer too small to stream
+    lib.sbn_ceiling_probe.restype = ctypes.c_int
+    work = ctypes.c_double(0.0)
+    assert lib.sbn_ceiling_probe(ci(7), vp(A), sz(1 << 22), ci(1), ctypes.byref(work), vp(0)) == sbn.SBN_EINVAL
+    assert lib.sbn_ceiling_probe(ci(0), vp(A), sz(1 << 22), ci(1), vp(0), vp(0)) == sbn.SBN_EINVAL
+    assert lib.sbn_ceiling_probe(ci(0), vp(A), sz(1 << 22), ci(0), ctypes.byref(work), vp(0)) == sbn.SBN_EINVAL
+    assert lib.sbn_ceiling_probe(ci(3), vp(A), sz(4096), ci(1), ctypes.byref(work), vp(0)) == sbn.SBN_EINVAL
+    assert lib.sbn_ceiling_probe(ci(3), vp(A + 16), sz(1 << 22), ci(1), ctypes.byref(work), vp(0)) == sbn.SBN_EALIGN
     assert sbn.sbn_last_error() == ""
