@@ -125,12 +125,26 @@ struct GemmBf16Args {
     int tiles_n, tiles_m;
 };
 
-__global__ void __launch_bounds__(256, 2) gemm_bf16_nt_kernel(GemmBf16Args g)
+// Up to two products share one launch (dW and dX of a layer): the block index space is the
+// concatenation of their tiles, the product with the longer contraction first, so that the short
+// tiles of the second fill the multiprocessors the first leaves idle in its last round (dW of a
+// 2560 x 2560 layer is 200 tiles for 512 block slots).  Each range starts at a multiple of 8 (the
+// blocks in between exit at once), which keeps block index mod 8 = XCD for the tile order below.
+struct GemmBf16Group {
+    GemmBf16Args g[2];
+    int block0[3];
+    int count;
+};
+
+__global__ void __launch_bounds__(256, 2) gemm_bf16_nt_kernel(GemmBf16Group grp)
 {
     __shared__ __attribute__((aligned(16))) uint8_t ldsP[GB_N * GROW];
     __shared__ __attribute__((aligned(16))) uint8_t ldsQ[GB_M * GROW];
+    const int prob = (grp.count > 1 && (int)blockIdx.x >= grp.block0[1]) ? 1 : 0;
+    const GemmBf16Args &g = grp.g[prob];
     const int nb = g.tiles_n * g.tiles_m;
-    int id = blockIdx.x;
+    int id = (int)blockIdx.x - grp.block0[prob];
+    if (id >= nb) return;   // padding between the two ranges
     if ((nb & 7) == 0) id = (id & 7) * (nb >> 3) + (id >> 3);
     const int tn = id % g.tiles_n, tm = id / g.tiles_n;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -249,15 +263,33 @@ __global__ void __launch_bounds__(256, 2) gemm_bf16_nt_kernel(GemmBf16Args g)
     }
 }
 
-sbn_status launch_gemm_bf16(const uint16_t *P, int64_t ldp, int N, const uint16_t *Q, int64_t ldq, int M, int K,
-                            uint16_t *C, int64_t ldc, const float *alpha, int accumulate, hipStream_t stream)
+GemmBf16Args make_bf16_args(const uint16_t *P, int64_t ldp, int N, const uint16_t *Q, int64_t ldq, int M, int K, uint16_t *C,
+                            int64_t ldc, const float *alpha, int accumulate)
 {
     GemmBf16Args g;
     g.P = P; g.Q = Q; g.C = C; g.alpha = alpha; g.ldp = ldp; g.ldq = ldq; g.ldc = ldc;
     g.N = N; g.M = M; g.K = K; g.accumulate = accumulate;
     g.tiles_n = (int)ceil_div(N, GB_N);
     g.tiles_m = (int)ceil_div(M, GB_M);
-    hipLaunchKernelGGL(gemm_bf16_nt_kernel, dim3(g.tiles_n * g.tiles_m), dim3(256), 0, stream, g);
+    return g;
+}
+
+// one launch for one or two products; the one with the longer contraction goes first
+sbn_status launch_gemm_bf16(int count, const GemmBf16Args *args, hipStream_t stream)
+{
+    GemmBf16Group grp;
+    grp.count = count;
+    const bool swap = count == 2 && args[1].K > args[0].K;
+    int blocks = 0;
+    for (int i = 0; i < count; ++i) {
+        grp.g[i] = args[swap ? 1 - i : i];
+        grp.block0[i] = blocks;
+        blocks += grp.g[i].tiles_n * grp.g[i].tiles_m;
+        if (i + 1 < count) blocks = (blocks + 7) / 8 * 8;
+    }
+    for (int i = count; i < 3; ++i) grp.block0[i] = blocks;
+    if (count == 1) grp.g[1] = grp.g[0];
+    hipLaunchKernelGGL(gemm_bf16_nt_kernel, dim3(blocks), dim3(256), 0, stream, grp);
     return check_launch("gemm_bf16_nt_kernel");
 }
 
@@ -289,6 +321,8 @@ sbn_status launch_backward(const void *dY, int64_t tokens, int64_t d_in, int64_t
     const uint16_t *dy = static_cast<const uint16_t *>(dY);
     sbn_status st;
 
+    GemmBf16Args products[2];
+    int nprod = 0;
     if (dX) {
         const int64_t ldw = pad8(d_out);
         if (pat.N == 2 && pat.M == 4 && d_in % CHUNK == 0) {
@@ -305,9 +339,8 @@ sbn_status launch_backward(const void *dY, int64_t tokens, int64_t d_in, int64_t
         }
         if (st != SBN_OK) return st;
         // dX[t, k] = gamma * sum_o dY[t, o] * W_eff^T[k, o]
-        st = launch_gemm_bf16(wt, ldw, (int)d_in, dy, d_out, (int)tokens, (int)d_out, static_cast<uint16_t *>(dX), d_in,
-                              gamma, 0, stream);
-        if (st != SBN_OK) return st;
+        products[nprod++] = make_bf16_args(wt, ldw, (int)d_in, dy, d_out, (int)tokens, (int)d_out, static_cast<uint16_t *>(dX),
+                                           d_in, gamma, 0);
     }
     if (dW) {
         const int64_t ldt = pad8(tokens);
@@ -324,10 +357,12 @@ sbn_status launch_backward(const void *dY, int64_t tokens, int64_t d_in, int64_t
             if (st != SBN_OK) return st;
         }
         // dW[o, k] = sum_t (dY/s_x)^T[o, t] * xq^T[k, t]; both operands are zero for t in [tokens, ldt)
-        st = launch_gemm_bf16(xt, ldt, (int)d_in, dyt, ldt, (int)d_out, (int)ldt, static_cast<uint16_t *>(dW), d_in,
-                              nullptr, accumulate, stream);
-        if (st != SBN_OK) return st;
+        products[nprod++] = make_bf16_args(xt, ldt, (int)d_in, dyt, ldt, (int)d_out, (int)ldt, static_cast<uint16_t *>(dW), d_in,
+                                           nullptr, accumulate);
     }
+    // both products in one launch: they are independent (dX reads W_eff^T and dY, dW reads the two transposes)
+    st = launch_gemm_bf16(nprod, products, stream);
+    if (st != SBN_OK) return st;
     return SBN_OK;
 }
 
