@@ -68,41 +68,86 @@ __global__ void __launch_bounds__(256) unpack_transpose_kernel(const uint8_t *__
     write_tile_rows(tile, 128, wt, ld, (int64_t)chunk * CHUNK, o0, d_in, ld);
 }
 
-// generic pattern: dense int8 W_eff [d_out, d_in] (from the unpack kernel) -> bf16 transposed
+// Transposition of a 64 x 64 bf16 tile through LDS: rows go in as they are read (vector loads along
+// the source's contiguous dimension), come out as eight values of one column per thread
+// (ds_read_u16 with a pitch of 33 words: the 64 lanes of a read hit 32 different banks, two lanes
+// per word), and leave as 16-byte stores, eight lanes per 128-byte line of the destination.
+constexpr int TQ = 66;   // LDS row pitch of these tiles in bf16 elements (33 words)
+
+// tile[a][b] (a = source row, b = source column) -> dst[(c0 + b) * ld + r0 + a]
+__device__ __forceinline__ void write_tile_transposed(const uint16_t *tile, uint16_t *dst, int64_t ld, int64_t c0, int64_t r0,
+                                                      int64_t cmax, int64_t rmax)
+{
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int v = threadIdx.x + 256 * h;
+        const int b = v >> 3, av = (v & 7) * 8;
+        if (c0 + b >= cmax) continue;
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            w[i] = (uint32_t)tile[(av + 2 * i) * TQ + b] | ((uint32_t)tile[(av + 2 * i + 1) * TQ + b] << 16);
+        uint16_t *d = dst + (c0 + b) * ld + r0 + av;
+        if (r0 + av + 8 <= rmax && (ld & 7) == 0) {
+            *reinterpret_cast<uint4 *>(d) = make_uint4(w[0], w[1], w[2], w[3]);
+        } else {
+            for (int e = 0; e < 8; ++e)
+                if (r0 + av + e < rmax) d[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+        }
+    }
+}
+
+// int8 [rows, cols] -> bf16 transposed: dst [cols, ld] with dst[c, r] = src[r, c], zeros for r in [rows, ld)
 __global__ void __launch_bounds__(256) transpose_i8_kernel(const int8_t *__restrict__ src, int64_t rows, int64_t cols,
                                                           uint16_t *__restrict__ dst, int64_t ld)
 {
-    // src [rows, cols] int8 -> dst [cols, ld] bf16 (dst[c, r] = src[r, c]); tile 64 x 64
-    __shared__ __attribute__((aligned(16))) uint16_t tile[64 * TP];
+    __shared__ __attribute__((aligned(16))) uint16_t tile[64 * TQ];
     const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
-    for (int e = threadIdx.x; e < 64 * 64; e += 256) {
-        const int r = e >> 6, c = e & 63;
-        int v = 0;
-        if (r0 + r < rows && c0 + c < cols) v = src[(r0 + r) * cols + c0 + c];
-        tile[c * TP + r] = (uint16_t)(__float_as_uint((float)v) >> 16);
+    const int r = threadIdx.x >> 2, cv = (threadIdx.x & 3) * 16;   // one 16-byte vector of a source row per thread
+    __attribute__((aligned(16))) int8_t q[16];
+    const bool row_ok = r0 + r < rows;
+    if (row_ok && c0 + cv + 16 <= cols && (cols & 15) == 0) {
+        *reinterpret_cast<uint4 *>(q) = *reinterpret_cast<const uint4 *>(src + (r0 + r) * cols + c0 + cv);
+    } else {
+        for (int e = 0; e < 16; ++e) q[e] = (row_ok && c0 + cv + e < cols) ? src[(r0 + r) * cols + c0 + cv + e] : (int8_t)0;
+    }
+#pragma unroll
+    for (int e = 0; e < 16; e += 2) {
+        const uint32_t lo = __float_as_uint((float)q[e]) >> 16, hi = __float_as_uint((float)q[e + 1]) & 0xffff0000u;
+        *reinterpret_cast<uint32_t *>(&tile[r * TQ + cv + e]) = lo | hi;   // |q| <= 128: exact in bf16
     }
     __syncthreads();
-    write_tile_rows(tile, 64, dst, ld, c0, r0, cols, ld);
+    write_tile_transposed(tile, dst, ld, c0, r0, cols, ld);
 }
 
-// dY [tokens, d_out] bf16 -> (dY[t,:] / s_x[t])^T as bf16 [d_out, ld]; tile 64 tokens x 64 outputs
+// dY [tokens, d_out] bf16 -> (dY[t,:] / s_x[t])^T as bf16 [d_out, ld], zeros for t in [tokens, ld)
 __global__ void __launch_bounds__(256) transpose_scale_dy_kernel(const uint16_t *__restrict__ dY, const float *__restrict__ sx,
                                                                 int64_t tokens, int64_t d_out, uint16_t *__restrict__ dst,
                                                                 int64_t ld)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t tile[64 * TP];
+    __shared__ __attribute__((aligned(16))) uint16_t tile[64 * TQ];
     const int64_t t0 = (int64_t)blockIdx.y * 64, o0 = (int64_t)blockIdx.x * 64;
-    for (int e = threadIdx.x; e < 64 * 64; e += 256) {
-        const int t = e >> 6, o = e & 63;
-        uint32_t out = 0;
-        if (t0 + t < tokens && o0 + o < d_out) {
-            const float dy = __uint_as_float((uint32_t)dY[(t0 + t) * d_out + o0 + o] << 16);
-            out = f32_to_bf16(__fdiv_rn(dy, sx[t0 + t]));
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int v = threadIdx.x + 256 * h;
+        const int t = v >> 3, ov = (v & 7) * 8;
+        __attribute__((aligned(16))) uint16_t q[8];
+        const bool row_ok = t0 + t < tokens;
+        if (row_ok && o0 + ov + 8 <= d_out && (d_out & 7) == 0) {
+            *reinterpret_cast<uint4 *>(q) = *reinterpret_cast<const uint4 *>(dY + (t0 + t) * d_out + o0 + ov);
+        } else {
+            for (int e = 0; e < 8; ++e) q[e] = (row_ok && o0 + ov + e < d_out) ? dY[(t0 + t) * d_out + o0 + ov + e] : (uint16_t)0;
         }
-        tile[o * TP + t] = (uint16_t)out;
+        const float s = row_ok ? sx[t0 + t] : 1.0f;
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+            const uint32_t lo = f32_to_bf16(__fdiv_rn(__uint_as_float((uint32_t)q[e] << 16), s));
+            const uint32_t hi = f32_to_bf16(__fdiv_rn(__uint_as_float((uint32_t)q[e + 1] << 16), s));
+            *reinterpret_cast<uint32_t *>(&tile[t * TQ + ov + e]) = lo | (hi << 16);
+        }
     }
     __syncthreads();
-    write_tile_rows(tile, 64, dst, ld, o0, t0, d_out, ld);
+    write_tile_transposed(tile, dst, ld, o0, t0, d_out, ld);
 }
 
 // ---- bf16 "NT" GEMM ---------------------------------------------------------------------------------

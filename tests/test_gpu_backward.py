@@ -38,7 +38,7 @@ def hip_forward_backward(W, X, dY, N, M, want_dx=True, want_dw=True, accumulate_
 
 
 @pytest.mark.parametrize("N,M", [(2, 4), (1, 4), (2, 8), (6, 8)])
-@pytest.mark.parametrize("tokens,shape", [(16, (256, 256)), (200, (136, 384)), (77, (520, 128))])
+@pytest.mark.parametrize("tokens,shape", [(16, (256, 256)), (200, (136, 384)), (77, (520, 128)), (50, (104, 136))])
 def test_backward_small(N, M, tokens, shape):
     W = sbn_synth.latent_weight(shape[0], shape[1], 900 + shape[0])
     X = sbn_synth.activations(tokens, shape[1], 910 + tokens)
