@@ -34,6 +34,8 @@ def _L():
         lib.sbn_oracle_act_quant.restype = None
         lib.sbn_oracle_act_quant.argtypes = [vp, i64, i64, vp, vp]
         lib.sbn_oracle_acc.restype = None
+        lib.sbn_oracle_rmsnorm.argtypes = [vp, vp, f32, i64, i64, vp]
+        lib.sbn_oracle_rmsnorm.restype = None
         lib.sbn_oracle_acc.argtypes = [vp, vp, i64, i64, i64, vp]
         lib.sbn_oracle_rescale.restype = None
         lib.sbn_oracle_rescale.argtypes = [vp, f32, vp, vp, i64, i64, vp]
@@ -152,6 +154,22 @@ def act_quant(X):
     sx = np.empty(X.shape[0], dtype=np.float32)
     _L().sbn_oracle_act_quant(_p(X), X.shape[0], X.shape[1], _p(xq), _p(sx))
     return xq, sx
+
+
+def rmsnorm(X, gain=None, eps: float = 1e-6) -> np.ndarray:
+    """Algorithm 1's Norm(x), read as RMS normalisation with gain; values are bf16-representable floats."""
+    X = _f32(X)
+    g = None if gain is None else _f32(gain)
+    Xn = np.empty(X.shape, dtype=np.float32)
+    _L().sbn_oracle_rmsnorm(_p(X), None if g is None else _p(g), np.float32(eps), X.shape[0], X.shape[1], _p(Xn))
+    return Xn
+
+
+def rmsnorm_act_quant(X, gain=None, eps: float = 1e-6):
+    """x~, s_x = Q_a(Norm(x)) (Algorithm 1); also returns the normalised activations."""
+    Xn = rmsnorm(X, gain, eps)
+    xq, sx = act_quant(Xn)
+    return xq, sx, Xn
 
 
 def acc(Weff: np.ndarray, xq: np.ndarray) -> np.ndarray:

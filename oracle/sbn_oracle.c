@@ -118,6 +118,40 @@ void sbn_oracle_act_quant(const float *X, int64_t T, int64_t K, int8_t *xq, floa
 }
 
 /* ---------------------------------------------------------------------------------------------
+ * Algorithm 1, the line that forms the layer input: x~ <- Q_a(Norm(x)).  The paper does not say
+ * which normalisation; reading: the RMS normalisation BitNet-style models place in front of every
+ * quantised linear layer, per token over the last dimension, with a learnable gain and no bias:
+ *   n[k] = x[k] / sqrt(mean_k(x^2) + eps) * g[k].
+ * Arithmetic fixed here so that the int8 codes that follow are well defined: the mean of squares in
+ * double over exactly up-converted inputs, in order; r = 1/sqrt(mean + eps) in double, rounded to
+ * fp32 once; x * r and then * g as two fp32 multiplies; the result rounded to bf16 (the model's
+ * activation type, round-to-nearest-even), returned as float.  gain == NULL means g = 1 (no multiply).
+ * ------------------------------------------------------------------------------------------- */
+static float round_to_bf16(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    u = (u + 0x7fffu + ((u >> 16) & 1u)) & 0xffff0000u;   /* finite inputs only */
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+void sbn_oracle_rmsnorm(const float *X, const float *gain, float eps, int64_t T, int64_t K, float *Xn)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t) {
+        double ssq = 0.0;
+        for (int64_t k = 0; k < K; ++k) ssq += (double)X[t * K + k] * (double)X[t * K + k];
+        const float r = (float)(1.0 / sqrt(ssq / (double)K + (double)eps));
+        for (int64_t k = 0; k < K; ++k) {
+            volatile float y = X[t * K + k] * r;
+            if (gain) y = y * gain[k];
+            Xn[t * K + k] = round_to_bf16(y);
+        }
+    }
+}
+
+/* ---------------------------------------------------------------------------------------------
  * Section 2.2, forward pass, the integer part of  y ~ s * (W_eff x~):
  *   acc[t, o] = sum_k W_eff[o, k] * x~[t, k]   in int32 (dense brute force over every k).
  * ------------------------------------------------------------------------------------------- */
