@@ -164,6 +164,12 @@ def main():
             f"{gemm_rows[f'{a}x{b}']['algorithmic_gbps']:.0f} GB/s")
     ms_aq = timed(lambda: sbn.sbn_act_quant(Xs[counter[0] % NSETS], xq[0], sx[0]), 200, 5)
     rows["act_quant_4096x2560"] = {"ms": ms_aq, "gbps": (3 * T * H + 4 * T) / (ms_aq * 1e-3) / 1e9}
+    # Algorithm 1's Q_a(Norm(x)) in one pass: RMS normalisation with gain fused in front of the quantizer
+    gain_n = (1.0 + 0.25 * torch.randn(H, generator=torch.Generator().manual_seed(3))).to(dev)
+    ms_nq = timed(lambda: sbn.sbn_rmsnorm_act_quant(Xs[counter[0] % NSETS], xq[0], sx[0], gain_n, 1e-6), 200, 5)
+    rows["rmsnorm_act_quant_4096x2560"] = {"ms": ms_nq, "gbps": (3 * T * H + 4 * T + 4 * H) / (ms_nq * 1e-3) / 1e9}
+    log(f"[gemm] act_quant {ms_aq * 1e3:.1f} us ({rows['act_quant_4096x2560']['gbps']:.0f} GB/s); with RMS norm fused "
+        f"{ms_nq * 1e3:.1f} us ({rows['rmsnorm_act_quant_4096x2560']['gbps']:.0f} GB/s)")
     rows["gemm_sparse"] = gemm_rows
     big = gemm_rows[f"{F}x{H}"]
     roofline = {"kernel": "gemm_smfmac_kernel", "workload": f"T={T} K={H} d_out={F}", "bound": "mfma",

@@ -107,6 +107,21 @@ sbn_status sbn_quantize_mask_pack_batched(int count, const void *const *W_latent
                                           void *workspace, size_t ws_bytes, void *stream);
 
 /*
+ * Algorithm 1, x~ <- Q_a(Norm(x)): RMS normalisation (the paper names no particular Norm; this is the
+ * one BitNet-style models put in front of every quantised linear layer) fused with the activation
+ * quantizer of Section 2.1, X read once:
+ *   r = fp32(1 / sqrt(mean_k x[t,k]^2 + eps))   mean in double
+ *   n[t,k] = bf16( fp32(x[t,k] * r) * gain[k] )  two fp32 multiplies, one rounding to bf16 (gain NULL: 1)
+ *   s_x[t], x~[t,:] = the activation quantizer of sbn_act_quant applied to n[t,:]
+ * The result feeds sbn_sparse_ternary_linear in its pre-quantized mode (X = NULL, xq_out / sx_out given).
+ *   X bf16 [tokens, d_in] device, 16-byte aligned; gain fp32 [d_in] device, 16-byte aligned, or NULL
+ *   xq int8 [tokens, d_in], sx fp32 [tokens]: device, overwritten; xn_out bf16 [tokens, d_in] or NULL
+ * Errors: SBN_EINVAL, SBN_EALIGN, SBN_EUNSUPPORTED (d_in % 8 != 0 or d_in > 16384), SBN_EHIP.  One kernel.
+ */
+sbn_status sbn_rmsnorm_act_quant(const void *X, int64_t tokens, int64_t d_in, const float *gain, float eps, int8_t *xq,
+                                 float *sx, void *xn_out, void *stream);
+
+/*
  * Activation quantizer alone (Section 2.1, absmax int8 activations; Appendix B listing, forward()):
  *   s_x[t] = 127 / max(max_k |X[t,k]|, 1e-5),  xq[t,k] = clip(round_half_even(X[t,k] * s_x[t]), -128, 127)
  *   X  device, bf16 [tokens, d_in], 16-byte aligned, d_in % 8 == 0;  xq device int8 [tokens, d_in], 16-byte

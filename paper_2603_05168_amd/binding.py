@@ -59,6 +59,8 @@ def _load():
     lib.sbn_unpack.argtypes = [vp, i64, i64, cint, cint, vp, vp, vp]
     lib.sbn_convert_packed.restype = cint
     lib.sbn_convert_packed.argtypes = [vp, i64, i64, cint, cint, cint, cint, vp, vp]
+    lib.sbn_rmsnorm_act_quant.restype = cint
+    lib.sbn_rmsnorm_act_quant.argtypes = [vp, i64, i64, vp, ctypes.c_float, vp, vp, vp, vp]
     lib.sbn_ceiling_probe.restype = cint
     lib.sbn_ceiling_probe.argtypes = [cint, vp, sz, cint, ctypes.POINTER(ctypes.c_double), vp]
     lib.sbn_mask_flips.restype = cint
@@ -225,6 +227,13 @@ def sbn_sparse_ternary_linear_backward(dY, packed, gamma, xq, sx, N: int, M: int
 
 def sbn_unpack(packed, d_out: int, d_in: int, N: int, M: int, W_eff=None, mask=None):
     _check(_lib.sbn_unpack(_ptr(packed), d_out, d_in, N, M, _ptr(W_eff), _ptr(mask), _stream()), "sbn_unpack")
+
+
+def sbn_rmsnorm_act_quant(X, xq, sx, gain=None, eps: float = 1e-6, xn_out=None):
+    """x~, s_x = Q_a(Norm(x)); X bf16 [tokens, d_in]; gain fp32 [d_in] or None; xn_out bf16 or None."""
+    tokens, d_in = X.shape
+    _check(_lib.sbn_rmsnorm_act_quant(_ptr(X), tokens, d_in, _ptr(gain), eps, _ptr(xq), _ptr(sx), _ptr(xn_out), _stream()),
+           "sbn_rmsnorm_act_quant")
 
 
 def sbn_convert_packed(packed, d_out: int, d_in: int, N: int, M: int, to_N: int, to_M: int, out):

@@ -134,6 +134,16 @@ sbn_status sbn_act_quant(const void *X, int64_t tokens, int64_t d_in, int8_t *xq
     return launch_act_quant(X, tokens, d_in, xq, sx, static_cast<hipStream_t>(stream));
 }
 
+sbn_status sbn_rmsnorm_act_quant(const void *X, int64_t tokens, int64_t d_in, const float *gain, float eps, int8_t *xq, float *sx,
+                                 void *xn_out, void *stream)
+{
+    if (!X || !xq || !sx || tokens <= 0 || d_in <= 0 || !(eps >= 0.0f)) return SBN_EINVAL;
+    if (d_in % 8 != 0 || d_in > 16384) return SBN_EUNSUPPORTED;
+    if (!aligned(X, 16) || !aligned(xq, 16) || !aligned(sx, 4) || (gain && !aligned(gain, 16)) || (xn_out && !aligned(xn_out, 16)))
+        return SBN_EALIGN;
+    return launch_rmsnorm_act_quant(X, gain, eps, tokens, d_in, xq, sx, xn_out, static_cast<hipStream_t>(stream));
+}
+
 static sbn_status linear_one(const LinearItem &it_in, const Pattern &pat, sbn_path path, void *workspace,
                              size_t ws_bytes, hipStream_t stream)
 {

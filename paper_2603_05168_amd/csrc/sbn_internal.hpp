@@ -84,6 +84,8 @@ struct LinearItem {
 size_t linear_workspace_bytes(int64_t tokens, int64_t d_out, int64_t d_in);
 sbn_status launch_act_quant(const void *X, int64_t tokens, int64_t d_in, int8_t *xq, float *sx,
                             hipStream_t stream);
+sbn_status launch_rmsnorm_act_quant(const void *X, const float *gain, float eps, int64_t tokens, int64_t d_in, int8_t *xq,
+                                    float *sx, void *xn, hipStream_t stream);
 // dense_codes: the weights are dense 2-bit codes (packed form of N = M) instead of the 2:4 form
 sbn_status launch_gemv(int count, const LinearItem *items, bool dense_codes, hipStream_t stream);
 sbn_status launch_gemm_smfmac(int count, const LinearItem *items, hipStream_t stream);

@@ -8,6 +8,49 @@ namespace sbn {
 
 namespace {
 
+// ---- pieces of the activation quantizer shared by its kernels -------------------------------------
+// largest 15-bit magnitude pattern among eight bf16 values and a running maximum (bf16 magnitudes order like integers)
+__device__ __forceinline__ uint32_t absmax_bits_bf16x8(const uint4 &d, uint32_t m)
+{
+    const uint32_t w[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const uint32_t lo = w[k] & 0x7fffu, hi = (w[k] >> 16) & 0x7fffu;
+        m = lo > m ? lo : m;
+        m = hi > m ? hi : m;
+    }
+    return m;
+}
+
+// s_x from the largest magnitude pattern: 127 / max(amax, 1e-5), one IEEE division
+__device__ __forceinline__ float scale_from_absmax_bits(uint32_t m)
+{
+    float amax = __uint_as_float(m << 16);
+    amax = amax < 1e-5f ? 1e-5f : amax;
+    return __fdiv_rn(127.0f, amax);
+}
+
+// eight bf16 values -> eight int8: clip(rint(x * s)) with one fp32 multiply and half-to-even rounding
+__device__ __forceinline__ uint2 quantize_bf16x8(const uint4 &d, float s)
+{
+    const uint32_t w[4] = {d.x, d.y, d.z, d.w};
+    uint32_t packed[2] = {0, 0};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const float x = __uint_as_float(h ? (w[k] & 0xffff0000u) : (w[k] << 16));
+            float q = rintf(__fmul_rn(x, s));
+            q = q > 127.0f ? 127.0f : q;
+            q = q < -128.0f ? -128.0f : q;
+            const uint32_t byte = (uint32_t)(int)q & 0xffu;
+            const int e = 2 * k + h;
+            packed[e >> 2] |= byte << (8 * (e & 3));
+        }
+    }
+    return make_uint2(packed[0], packed[1]);
+}
+
 // ---- activation quantizer -----------------------------------------------------------------------
 // TPT threads share one token (64 = one wavefront per token for prefill, 1024 = one block per token
 // for decode, where only a handful of tokens exist).  A thread keeps its 16-byte vectors of the row
@@ -31,13 +74,7 @@ __global__ void __launch_bounds__(TPT < 256 ? 256 : TPT) act_quant_kernel(const 
     for (int i = 0; i < VMAX; ++i) {
         const int idx = sub + i * TPT;
         v[i] = (live && idx < nvec) ? row[idx] : make_uint4(0, 0, 0, 0);
-        const uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const uint32_t lo = w[k] & 0x7fffu, hi = (w[k] >> 16) & 0x7fffu;
-            m = lo > m ? lo : m;
-            m = hi > m ? hi : m;
-        }
+        m = absmax_bits_bf16x8(v[i], m);
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
@@ -53,9 +90,7 @@ __global__ void __launch_bounds__(TPT < 256 ? 256 : TPT) act_quant_kernel(const 
             m = o > m ? o : m;
         }
     }
-    float amax = __uint_as_float(m << 16);
-    amax = amax < 1e-5f ? 1e-5f : amax;
-    const float s = __fdiv_rn(127.0f, amax);
+    const float s = scale_from_absmax_bits(m);
     if (!live) return;
     if (sub == 0) sx[t] = s;
     uint2 *out = reinterpret_cast<uint2 *>(xq + t * (int64_t)nvec * 8);
@@ -63,22 +98,7 @@ __global__ void __launch_bounds__(TPT < 256 ? 256 : TPT) act_quant_kernel(const 
     for (int i = 0; i < VMAX; ++i) {
         const int idx = sub + i * TPT;
         if (idx >= nvec) break;
-        const uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
-        uint32_t packed[2] = {0, 0};
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const float x = __uint_as_float(h ? (w[k] & 0xffff0000u) : (w[k] << 16));
-                float q = rintf(__fmul_rn(x, s));
-                q = q > 127.0f ? 127.0f : q;
-                q = q < -128.0f ? -128.0f : q;
-                const uint32_t byte = (uint32_t)(int)q & 0xffu;
-                const int e = 2 * k + h;
-                packed[e >> 2] |= byte << (8 * (e & 3));
-            }
-        }
-        out[idx] = make_uint2(packed[0], packed[1]);
+        out[idx] = quantize_bf16x8(v[i], s);
     }
 }
 
@@ -92,43 +112,115 @@ __global__ void __launch_bounds__(256) act_quant_two_pass_kernel(const uint4 *__
     const uint4 *row = X + t * nvec;
     uint32_t m = 0;
     for (int v = lane; v < nvec; v += 64) {
-        const uint4 d = row[v];
-        const uint32_t w[4] = {d.x, d.y, d.z, d.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint32_t lo = w[i] & 0x7fffu, hi = (w[i] >> 16) & 0x7fffu;
-            m = lo > m ? lo : m;
-            m = hi > m ? hi : m;
-        }
+        m = absmax_bits_bf16x8(row[v], m);
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
         const uint32_t o = (uint32_t)__shfl_xor((int)m, off, 64);
         m = o > m ? o : m;
     }
-    float amax = __uint_as_float(m << 16);
-    amax = amax < 1e-5f ? 1e-5f : amax;
-    const float s = __fdiv_rn(127.0f, amax);
+    const float s = scale_from_absmax_bits(m);
     if (lane == 0) sx[t] = s;
     uint2 *out = reinterpret_cast<uint2 *>(xq + t * (int64_t)nvec * 8);
-    for (int v = lane; v < nvec; v += 64) {
-        const uint4 d = row[v];
-        const uint32_t w[4] = {d.x, d.y, d.z, d.w};
-        uint32_t packed[2] = {0, 0};
+    for (int v = lane; v < nvec; v += 64) out[v] = quantize_bf16x8(row[v], s);
+}
+
+// ---- RMS normalisation fused in front of the quantizer (Algorithm 1: x~ <- Q_a(Norm(x))) ---------
+// Same ownership of a token row as act_quant_kernel, the row held in registers throughout, X read
+// once.  The mean of squares is summed in double (every square of a bf16 value is exact), r =
+// 1/sqrt(mean + eps) is rounded to fp32 once, n = bf16(fp32(x * r) * g) replaces the row in the
+// registers, and the quantizer runs on it as it would on a stored bf16 tensor.
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
+{
+    const uint32_t u = __float_as_uint(f);
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;   // round to nearest even; finite inputs
+}
+
+template <int TPT, int VMAX>
+__global__ void __launch_bounds__(TPT < 256 ? 256 : TPT) rmsnorm_act_quant_kernel(const uint4 *__restrict__ X, const float *__restrict__ gain,
+                                                                                 float eps, int64_t tokens, int nvec, int8_t *__restrict__ xq,
+                                                                                 float *__restrict__ sx, uint4 *__restrict__ xn)
+{
+    constexpr int BLOCK = TPT < 256 ? 256 : TPT;
+    constexpr int TOK_PER_BLOCK = BLOCK / TPT;
+    __shared__ double wave_ssq[BLOCK / 64];
+    __shared__ uint32_t wave_max[BLOCK / 64];
+    const int sub = threadIdx.x % TPT;
+    const int64_t t = (int64_t)blockIdx.x * TOK_PER_BLOCK + threadIdx.x / TPT;
+    const bool live = t < tokens;
+    const uint4 *row = X + (live ? t : 0) * nvec;
+    uint4 v[VMAX];
+    double ssq = 0.0;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < VMAX; ++i) {
+        const int idx = sub + i * TPT;
+        v[i] = (live && idx < nvec) ? row[idx] : make_uint4(0, 0, 0, 0);
+        const uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const float x = __uint_as_float(h ? (w[i] & 0xffff0000u) : (w[i] << 16));
-                float q = rintf(__fmul_rn(x, s));
-                q = q > 127.0f ? 127.0f : q;
-                q = q < -128.0f ? -128.0f : q;
-                const uint32_t byte = (uint32_t)(int)q & 0xffu;
-                const int e = 2 * i + h;
-                packed[e >> 2] |= byte << (8 * (e & 3));
-            }
+        for (int k = 0; k < 4; ++k) {
+            const double lo = (double)__uint_as_float(w[k] << 16), hi = (double)__uint_as_float(w[k] & 0xffff0000u);
+            ssq += lo * lo;
+            ssq += hi * hi;
         }
-        out[v] = make_uint2(packed[0], packed[1]);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) ssq += __shfl_xor(ssq, off, 64);
+    if constexpr (TPT > 64) {
+        if ((threadIdx.x & 63) == 0) wave_ssq[threadIdx.x >> 6] = ssq;
+        __syncthreads();
+        ssq = 0.0;
+#pragma unroll
+        for (int w = 0; w < TPT / 64; ++w) ssq += wave_ssq[w];
+    }
+    const float r = (float)(1.0 / sqrt(ssq / (double)(nvec * 8) + (double)eps));
+    uint32_t m = 0;
+#pragma unroll
+    for (int i = 0; i < VMAX; ++i) {
+        const int idx = sub + i * TPT;
+        if (idx >= nvec) break;
+        float g[8];
+        if (gain) {
+            const float4 g0 = *reinterpret_cast<const float4 *>(gain + (int64_t)idx * 8);
+            const float4 g1 = *reinterpret_cast<const float4 *>(gain + (int64_t)idx * 8 + 4);
+            g[0] = g0.x; g[1] = g0.y; g[2] = g0.z; g[3] = g0.w; g[4] = g1.x; g[5] = g1.y; g[6] = g1.z; g[7] = g1.w;
+        }
+        uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            float lo = __fmul_rn(__uint_as_float(w[k] << 16), r), hi = __fmul_rn(__uint_as_float(w[k] & 0xffff0000u), r);
+            if (gain) {
+                lo = __fmul_rn(lo, g[2 * k]);
+                hi = __fmul_rn(hi, g[2 * k + 1]);
+            }
+            w[k] = f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+        }
+        v[i] = make_uint4(w[0], w[1], w[2], w[3]);
+        m = absmax_bits_bf16x8(v[i], m);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const uint32_t o = (uint32_t)__shfl_xor((int)m, off, 64);
+        m = o > m ? o : m;
+    }
+    if constexpr (TPT > 64) {
+        if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < TPT / 64; ++w) {
+            const uint32_t o = wave_max[w];
+            m = o > m ? o : m;
+        }
+    }
+    const float s = scale_from_absmax_bits(m);
+    if (!live) return;
+    if (sub == 0) sx[t] = s;
+    uint2 *out = reinterpret_cast<uint2 *>(xq + t * (int64_t)nvec * 8);
+#pragma unroll
+    for (int i = 0; i < VMAX; ++i) {
+        const int idx = sub + i * TPT;
+        if (idx >= nvec) break;
+        out[idx] = quantize_bf16x8(v[i], s);
+        if (xn) xn[t * nvec + idx] = v[i];
     }
 }
 
@@ -476,6 +568,24 @@ sbn_status launch_act_quant(const void *X, int64_t tokens, int64_t d_in, int8_t 
         hipLaunchKernelGGL(act_quant_two_pass_kernel, dim3((unsigned)ceil_div(tokens, 4)), dim3(256), 0, stream, x, tokens, nvec, xq, sx);
     }
     return check_launch("act_quant_kernel");
+}
+
+sbn_status launch_rmsnorm_act_quant(const void *X, const float *gain, float eps, int64_t tokens, int64_t d_in, int8_t *xq,
+                                    float *sx, void *xn, hipStream_t stream)
+{
+    const uint4 *x = static_cast<const uint4 *>(X);
+    uint4 *n = static_cast<uint4 *>(xn);
+    const int nvec = (int)(d_in / 8);
+    if (nvec <= 16 * 64 && tokens > 64) {
+        hipLaunchKernelGGL((rmsnorm_act_quant_kernel<64, 16>), dim3((unsigned)ceil_div(tokens, 4)), dim3(256), 0, stream, x, gain, eps,
+                           tokens, nvec, xq, sx, n);
+    } else if (nvec <= 2 * 1024) {
+        hipLaunchKernelGGL((rmsnorm_act_quant_kernel<1024, 2>), dim3((unsigned)tokens), dim3(1024), 0, stream, x, gain, eps, tokens,
+                           nvec, xq, sx, n);
+    } else {
+        return SBN_EUNSUPPORTED;   // rows longer than 16384 do not fit the registers of a block
+    }
+    return check_launch("rmsnorm_act_quant_kernel");
 }
 
 static void fill_gemv_item(GemvItem &g, const LinearItem &li)
