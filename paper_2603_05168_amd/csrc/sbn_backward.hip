@@ -197,21 +197,24 @@ __global__ void __launch_bounds__(256, 2) gemm_bf16_nt_kernel(GemmBf16Group grp)
     const int r = lane & 31, c = lane >> 5;
     const int n0 = tn * GB_N, m0 = tm * GB_M;
 
-    // copy roles: 8 threads per row (16 bytes each), 32 rows per pass
+    // copy roles: 8 threads per row (16 bytes each), 32 rows per pass.  Addresses are a uniform tile base
+    // (scalar registers, advanced by 128 bytes per k step) plus a 32-bit byte offset per thread and pass,
+    // rows past the end clamped to the last one: the loads of the loop need no vector arithmetic.
     const int cp_row = tid >> 3, cp_col = (tid & 7) * 8;   // column in elements
-    const uint16_t *psrc[8];
-    const uint16_t *qsrc[4];
+    const char *pbase = reinterpret_cast<const char *>(g.P + (int64_t)n0 * g.ldp);
+    const char *qbase = reinterpret_cast<const char *>(g.Q + (int64_t)m0 * g.ldq);
+    uint32_t poff[8], qoff[4];
 #pragma unroll
     for (int p = 0; p < 8; ++p) {
         int n = n0 + cp_row + 32 * p;
-        n = n < g.N ? n : g.N - 1;
-        psrc[p] = g.P + (int64_t)n * g.ldp + cp_col;
+        n = (n < g.N ? n : g.N - 1) - n0;
+        poff[p] = (uint32_t)(((int64_t)n * g.ldp + cp_col) * 2);
     }
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
         int m = m0 + cp_row + 32 * p;
-        m = m < g.M ? m : g.M - 1;
-        qsrc[p] = g.Q + (int64_t)m * g.ldq + cp_col;
+        m = (m < g.M ? m : g.M - 1) - m0;
+        qoff[p] = (uint32_t)(((int64_t)m * g.ldq + cp_col) * 2);
     }
 
     v16f acc[4][2];
@@ -222,15 +225,25 @@ __global__ void __launch_bounds__(256, 2) gemm_bf16_nt_kernel(GemmBf16Group grp)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
 
+    // k steps that lie entirely inside K load unconditionally (straight-line loop body); a ragged last
+    // step (K % 8 == 0: a 16-byte vector is entirely inside or outside) masks its loads
+    const int nk_full = g.K / GB_K;
     const int nk = (g.K + GB_K - 1) / GB_K;
     uint4 preg[8], qreg[4];
-    auto load_tile = [&](int kt) {
-        const int k = kt * GB_K + cp_col;
-        const bool ok = k + 8 <= g.K;   // K % 8 == 0: a vector is entirely inside or outside
+    auto load_full = [&](int kt) {
+        const char *pb = pbase + (int64_t)kt * (GB_K * 2), *qb = qbase + (int64_t)kt * (GB_K * 2);
 #pragma unroll
-        for (int p = 0; p < 8; ++p) preg[p] = ok ? *reinterpret_cast<const uint4 *>(psrc[p] + kt * GB_K) : make_uint4(0, 0, 0, 0);
+        for (int p = 0; p < 8; ++p) preg[p] = *reinterpret_cast<const uint4 *>(pb + poff[p]);
 #pragma unroll
-        for (int p = 0; p < 4; ++p) qreg[p] = ok ? *reinterpret_cast<const uint4 *>(qsrc[p] + kt * GB_K) : make_uint4(0, 0, 0, 0);
+        for (int p = 0; p < 4; ++p) qreg[p] = *reinterpret_cast<const uint4 *>(qb + qoff[p]);
+    };
+    auto load_ragged = [&](int kt) {
+        const char *pb = pbase + (int64_t)kt * (GB_K * 2), *qb = qbase + (int64_t)kt * (GB_K * 2);
+        const bool ok = kt * GB_K + cp_col + 8 <= g.K;
+#pragma unroll
+        for (int p = 0; p < 8; ++p) preg[p] = ok ? *reinterpret_cast<const uint4 *>(pb + poff[p]) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) qreg[p] = ok ? *reinterpret_cast<const uint4 *>(qb + qoff[p]) : make_uint4(0, 0, 0, 0);
     };
     auto store_tile_lds = [&]() {
 #pragma unroll
@@ -238,12 +251,7 @@ __global__ void __launch_bounds__(256, 2) gemm_bf16_nt_kernel(GemmBf16Group grp)
 #pragma unroll
         for (int p = 0; p < 4; ++p) *reinterpret_cast<uint4 *>(&ldsQ[(cp_row + 32 * p) * GROW + cp_col * 2]) = qreg[p];
     };
-
-    load_tile(0);
-    store_tile_lds();
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        if (kt + 1 < nk) load_tile(kt + 1);
+    auto multiply_tile = [&]() {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             // lane (r, c) supplies k = 16u + 8c + 0..7 of the tile for both operands
@@ -260,12 +268,27 @@ __global__ void __launch_bounds__(256, 2) gemm_bf16_nt_kernel(GemmBf16Group grp)
                 for (int b = 0; b < 2; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[a], qf[b], acc[a][b], 0, 0, 0);
         }
+    };
+
+    if (nk_full > 0) load_full(0); else load_ragged(0);
+    store_tile_lds();
+    __syncthreads();
+    int kt = 0;
+    for (; kt + 1 < nk_full; ++kt) {   // the next step is a full one
+        load_full(kt + 1);
+        multiply_tile();
         __syncthreads();
-        if (kt + 1 < nk) {
-            store_tile_lds();
-            __syncthreads();
-        }
+        store_tile_lds();
+        __syncthreads();
     }
+    if (kt + 1 < nk) {                 // one ragged step follows
+        load_ragged(kt + 1);
+        multiply_tile();
+        __syncthreads();
+        store_tile_lds();
+        __syncthreads();
+    }
+    multiply_tile();                   // last step: nothing left to fetch
 
     // result tile (a, b): lane holds m = column r, n = rows 8q + 4c + i
     const float alpha = g.alpha ? *g.alpha : 1.0f;
