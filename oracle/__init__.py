@@ -226,6 +226,21 @@ def backward_dw(dY, xq: np.ndarray, sx: np.ndarray) -> np.ndarray:
     return dW
 
 
+def backward_dw_gradient_masked(dY, xq: np.ndarray, sx: np.ndarray, mask: np.ndarray) -> np.ndarray:
+    """The ablation study's "gradient masking" variant (Section 2.3 names it as what other N:M methods
+    do): dL/dW ~ M (.) dL/dW_eff, i.e. the dense gradient with the entries of masked-out weights
+    blocked.  Same forward pass; only the weights of the current mask receive an update."""
+    dW = backward_dw(dY, xq, sx)
+    mask = np.ascontiguousarray(mask)
+    assert mask.shape == dW.shape
+    out = np.zeros_like(dW)
+    for o in range(dW.shape[0]):
+        for k in range(dW.shape[1]):
+            if mask[o, k]:
+                out[o, k] = dW[o, k]
+    return out
+
+
 def flip_rate(mask_a: np.ndarray, mask_b: np.ndarray) -> float:
     a = np.ascontiguousarray(mask_a, dtype=np.uint8)
     b = np.ascontiguousarray(mask_b, dtype=np.uint8)

@@ -160,3 +160,28 @@ def test_dx_brute_force():
     dX = oracle.backward_dx(dY, Weff, gamma)
     ref = np.float64(gamma) * (dY.astype(np.float64) @ Weff.astype(np.float64))
     assert np.allclose(dX, ref, rtol=1e-12, atol=1e-15)
+
+
+def test_gradient_masked_variant_against_autograd():
+    # ablation study, "gradient masking": the gradient of the latent weight when the mask multiplies the
+    # weight inside the graph (w_eff = w_q * m, straight-through for the quantizer only): autograd then
+    # delivers m * dL/dw_eff.  Checked on a float transcription of the layer, exactly N entries per group survive.
+    N, M = 2, 4
+    W = sbn_synth.latent_weight(24, 64, 77).float()
+    X = sbn_synth.activations(9, 64, 78).float()
+    dY = sbn_synth.grad_output(9, 24, 79).float()
+    Weff, mask, gamma = oracle.quantize_mask(W.numpy(), N, M)
+    xq, sx = oracle.act_quant(X.numpy())
+    w = W.clone().double().requires_grad_(True)
+    m = torch.from_numpy(mask.astype(np.float64))
+    wq = torch.from_numpy((Weff.astype(np.float64) * float(gamma)))
+    w_ste = w + (wq - w).detach()                                    # value of the quantized weight, identity gradient
+    w_eff = w_ste * m                                                # the mask gates value and gradient
+    x_hat = torch.from_numpy(xq.astype(np.float64) / sx.astype(np.float64)[:, None])
+    y = x_hat @ w_eff.t()
+    y.backward(dY.double())
+    got = oracle.backward_dw_gradient_masked(dY.numpy(), xq, sx, mask)
+    assert np.allclose(got, w.grad.numpy(), rtol=1e-12, atol=1e-15)
+    assert ((got != 0).reshape(24, 16, 4).sum(axis=2) <= N).all() and (got[mask == 0] == 0).all()
+    dense = oracle.backward_dw(dY.numpy(), xq, sx)
+    assert np.array_equal(got[mask == 1], dense[mask == 1]) and (dense[mask == 0] != 0).any()
