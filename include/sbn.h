@@ -176,13 +176,16 @@ sbn_status sbn_sparse_ternary_linear_grouped(int count, const void *const *X, co
  *   dY       device, bf16 [tokens, d_out], 16-byte aligned
  *   xq, sx   device, as written by the forward call (needed only when dW != NULL)
  *   dX, dW   device, bf16 [tokens, d_in] / [d_out, d_in], or NULL to skip that product
- *   accumulate != 0: dW += (read-modify-write in bf16), else dW is overwritten
+ *   flags    SBN_BWD_ACCUMULATE: dW += (read-modify-write in bf16), else dW is overwritten;
+ *            SBN_BWD_MASK_DW: the ablation study's "gradient masking" variant, dW = M (.) dense dW (only the
+ *            weights of the current mask receive the term; needs `packed`); the paper's method leaves it off
  *   workspace >= sbn_workspace_bytes(SBN_OP_BACKWARD, tokens, d_out, d_in, N, M)
  */
+enum { SBN_BWD_ACCUMULATE = 1, SBN_BWD_MASK_DW = 2 };
 sbn_status sbn_sparse_ternary_linear_backward(const void *dY, int64_t tokens, int64_t d_in,
                                               int64_t d_out, int N, int M, const void *packed,
                                               const float *gamma, const int8_t *xq, const float *sx,
-                                              void *dX, void *dW, int accumulate, void *workspace,
+                                              void *dX, void *dW, int flags, void *workspace,
                                               size_t ws_bytes, void *stream);
 
 /* Test hook, not timed: expands `packed` to dense W_eff (int8 [d_out, d_in]) and the 0/1 mask

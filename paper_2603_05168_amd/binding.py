@@ -214,13 +214,17 @@ def sbn_sparse_ternary_linear_grouped(X_list, packed_list, gamma_list, Y_list, N
     LinearGroup(X_list, packed_list, gamma_list, Y_list, N, M, workspace, path).run()
 
 
+SBN_BWD_ACCUMULATE, SBN_BWD_MASK_DW = 1, 2
+
+
 def sbn_sparse_ternary_linear_backward(dY, packed, gamma, xq, sx, N: int, M: int, workspace, d_in: int, dX=None, dW=None,
-                                       accumulate: bool = False):
+                                       accumulate: bool = False, mask_dw: bool = False):
     tokens, d_out = dY.shape
     if dY.dtype != torch.bfloat16:
         raise TypeError("dY must be bf16")
     _check(_lib.sbn_sparse_ternary_linear_backward(_ptr(dY), tokens, d_in, d_out, N, M, _ptr(packed), _ptr(gamma),
-                                                   _ptr(xq), _ptr(sx), _ptr(dX), _ptr(dW), int(accumulate),
+                                                   _ptr(xq), _ptr(sx), _ptr(dX), _ptr(dW),
+                                                   (SBN_BWD_ACCUMULATE if accumulate else 0) | (SBN_BWD_MASK_DW if mask_dw else 0),
                                                    _ptr(workspace), workspace.numel() * workspace.element_size(),
                                                    _stream()), "sbn_sparse_ternary_linear_backward")
 

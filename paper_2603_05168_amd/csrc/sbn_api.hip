@@ -275,20 +275,22 @@ sbn_status sbn_sparse_ternary_linear_grouped(int count, const void *const *X, co
 
 sbn_status sbn_sparse_ternary_linear_backward(const void *dY, int64_t tokens, int64_t d_in, int64_t d_out, int N,
                                               int M, const void *packed, const float *gamma, const int8_t *xq,
-                                              const float *sx, void *dX, void *dW, int accumulate, void *workspace,
+                                              const float *sx, void *dX, void *dW, int flags, void *workspace,
                                               size_t ws_bytes, void *stream)
 {
     Pattern pat;
     if (!dY || !workspace || tokens <= 0 || (!dX && !dW)) return SBN_EINVAL;
     if (dX && (!packed || !gamma)) return SBN_EINVAL;
     if (dW && (!xq || !sx)) return SBN_EINVAL;
+    if (flags & ~(SBN_BWD_ACCUMULATE | SBN_BWD_MASK_DW)) return SBN_EINVAL;
+    if ((flags & SBN_BWD_MASK_DW) && dW && !packed) return SBN_EINVAL;
     sbn_status st = check_shape(d_out, d_in, N, M, pat);
     if (st != SBN_OK) return st;
     if (!aligned(dY, 16) || !aligned(workspace, 256)) return SBN_EALIGN;
     if ((dX && !aligned(dX, 16)) || (dW && !aligned(dW, 16)) || (xq && !aligned(xq, 16))) return SBN_EALIGN;
     if (d_in % 8 != 0 || d_out % 8 != 0) return SBN_EUNSUPPORTED;
     if (ws_bytes < backward_workspace_bytes(tokens, d_out, d_in)) return SBN_ESIZE;
-    return launch_backward(dY, tokens, d_in, d_out, pat, packed, gamma, xq, sx, dX, dW, accumulate, workspace,
+    return launch_backward(dY, tokens, d_in, d_out, pat, packed, gamma, xq, sx, dX, dW, flags, workspace,
                            ws_bytes, static_cast<hipStream_t>(stream));
 }
 

@@ -168,6 +168,8 @@ struct GemmBf16Args {
     int N, M, K;
     int accumulate;
     int tiles_n, tiles_m;
+    const uint32_t *mask;   // null, or one bit per element of C (rows of mask_wpr words): zero bits block the new term
+    int mask_wpr;
 };
 
 // Up to two products share one launch (dW and dX of a layer): the block index space is the
@@ -322,6 +324,11 @@ __global__ void __launch_bounds__(256, 2) gemm_bf16_nt_kernel(GemmBf16Group grp)
                 float v[4];
 #pragma unroll
                 for (int i = 0; i < 4; ++i) v[i] = acc[a][b][4 * q + i] * alpha;
+                if (g.mask && n < g.N) {   // n is a multiple of 4: its four mask bits sit in one word
+                    const uint32_t mb = g.mask[(int64_t)m * g.mask_wpr + (n >> 5)] >> (n & 31);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) v[i] = (mb >> i) & 1u ? v[i] : 0.0f;
+                }
                 if (n + 4 <= g.N && (g.ldc & 3) == 0) {
                     if (g.accumulate) {
                         const uint2 old = *reinterpret_cast<const uint2 *>(dst);
@@ -356,6 +363,8 @@ GemmBf16Args make_bf16_args(const uint16_t *P, int64_t ldp, int N, const uint16_
     g.N = N; g.M = M; g.K = K; g.accumulate = accumulate;
     g.tiles_n = (int)ceil_div(N, GB_N);
     g.tiles_m = (int)ceil_div(M, GB_M);
+    g.mask = nullptr;
+    g.mask_wpr = 0;
     return g;
 }
 
@@ -385,13 +394,15 @@ size_t backward_workspace_bytes(int64_t tokens, int64_t d_out, int64_t d_in)
 {
     // W_eff^T bf16 [d_in, pad8(d_out)] + int8 W_eff (generic patterns) + (dY/s_x)^T bf16 [d_out, pad8(tokens)]
     // + xq^T bf16 [d_in, pad8(tokens)]
+    // + the mask bit plane of the gradient-masked variant
     return align_up((size_t)d_in * pad8(d_out) * 2, 256) + align_up((size_t)d_out * d_in, 256) +
-           align_up((size_t)d_out * pad8(tokens) * 2, 256) + align_up((size_t)d_in * pad8(tokens) * 2, 256);
+           align_up((size_t)d_out * pad8(tokens) * 2, 256) + align_up((size_t)d_in * pad8(tokens) * 2, 256) +
+           align_up((size_t)d_out * ((d_in + 31) / 32) * 4, 256);
 }
 
 sbn_status launch_backward(const void *dY, int64_t tokens, int64_t d_in, int64_t d_out, const Pattern &pat,
                            const void *packed, const float *gamma, const int8_t *xq, const float *sx, void *dX,
-                           void *dW, int accumulate, void *workspace, size_t ws_bytes, hipStream_t stream)
+                           void *dW, int flags, void *workspace, size_t ws_bytes, hipStream_t stream)
 {
     (void)ws_bytes;
     uint8_t *ws = static_cast<uint8_t *>(workspace);
@@ -402,6 +413,9 @@ sbn_status launch_backward(const void *dY, int64_t tokens, int64_t d_in, int64_t
     uint16_t *dyt = reinterpret_cast<uint16_t *>(ws);
     ws += align_up((size_t)d_out * pad8(tokens) * 2, 256);
     uint16_t *xt = reinterpret_cast<uint16_t *>(ws);
+    ws += align_up((size_t)d_in * pad8(tokens) * 2, 256);
+    uint32_t *mask_bits = reinterpret_cast<uint32_t *>(ws);
+    const int accumulate = (flags & SBN_BWD_ACCUMULATE) != 0;
     const uint16_t *dy = static_cast<const uint16_t *>(dY);
     sbn_status st;
 
@@ -441,8 +455,16 @@ sbn_status launch_backward(const void *dY, int64_t tokens, int64_t d_in, int64_t
             if (st != SBN_OK) return st;
         }
         // dW[o, k] = sum_t (dY/s_x)^T[o, t] * xq^T[k, t]; both operands are zero for t in [tokens, ldt)
-        products[nprod++] = make_bf16_args(xt, ldt, (int)d_in, dyt, ldt, (int)d_out, (int)ldt, static_cast<uint16_t *>(dW), d_in,
-                                           nullptr, accumulate);
+        products[nprod] = make_bf16_args(xt, ldt, (int)d_in, dyt, ldt, (int)d_out, (int)ldt, static_cast<uint16_t *>(dW), d_in,
+                                         nullptr, accumulate);
+        if (flags & SBN_BWD_MASK_DW) {
+            // ablation variant: only the weights of the current mask receive the new gradient term
+            st = launch_mask_bitplane(packed, d_out, d_in, pat, mask_bits, stream);
+            if (st != SBN_OK) return st;
+            products[nprod].mask = mask_bits;
+            products[nprod].mask_wpr = (int)((d_in + 31) / 32);
+        }
+        ++nprod;
     }
     // both products in one launch: they are independent (dX reads W_eff^T and dY, dW reads the two transposes)
     st = launch_gemm_bf16(nprod, products, stream);

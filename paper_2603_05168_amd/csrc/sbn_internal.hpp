@@ -64,6 +64,9 @@ sbn_status launch_repack_2of4(const void *packed, int64_t d_out, int64_t d_in, c
 // any pattern -> dense 2-bit codes (the packed form of N = M), explicit zero codes at the dropped positions
 sbn_status launch_repack_dense_codes(const void *packed, int64_t d_out, int64_t d_in, const Pattern &pat, uint8_t *out,
                                      hipStream_t stream);
+// the N:M mask of a packed matrix as one bit per weight, rows of ceil(d_in / 32) words
+sbn_status launch_mask_bitplane(const void *packed, int64_t d_out, int64_t d_in, const Pattern &pat, uint32_t *bits,
+                                hipStream_t stream);
 sbn_status launch_expand_groups(const void *packed, int64_t d_out, int64_t d_in, const Pattern &pat, int8_t *W_eff,
                                 hipStream_t stream);
 sbn_status launch_unpack(const void *packed, int64_t d_out, int64_t d_in, const Pattern &pat,
@@ -101,7 +104,7 @@ sbn_status launch_ceiling_probe(int kind, void *buf, size_t bytes, int iters, do
 size_t backward_workspace_bytes(int64_t tokens, int64_t d_out, int64_t d_in);
 sbn_status launch_backward(const void *dY, int64_t tokens, int64_t d_in, int64_t d_out,
                            const Pattern &pat, const void *packed, const float *gamma,
-                           const int8_t *xq, const float *sx, void *dX, void *dW, int accumulate,
+                           const int8_t *xq, const float *sx, void *dX, void *dW, int flags,
                            void *workspace, size_t ws_bytes, hipStream_t stream);
 
 }  // namespace sbn

@@ -579,6 +579,29 @@ __device__ __forceinline__ uint32_t group_mask_bits(const uint8_t *idx_field, in
     return m;
 }
 
+// N:M mask as a bit plane: word (row, j) holds the mask of weights 32 j .. 32 j + 31 of the row (bit = position);
+// one thread per word.  Rows are d_in / 32 words, rounded up (positions past d_in read as zero).
+__global__ void __launch_bounds__(256) mask_bitplane_kernel(const uint8_t *__restrict__ packed, int64_t d_out, int64_t d_in,
+                                                            Pattern pat, uint32_t *__restrict__ bits)
+{
+    const int64_t wpr = (d_in + 31) / 32;
+    const int64_t wid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (wid >= d_out * wpr) return;
+    const int64_t row = wid / wpr;
+    const int j = (int)(wid % wpr);
+    const int64_t nchunks = (d_in + CHUNK - 1) / CHUNK;
+    const uint8_t *idx_field = packed + (row * nchunks + j / 4) * pat.chunk_bytes;
+    const int gpw = 32 / pat.M;          // groups per word
+    const int g0 = (j % 4) * gpw;        // first group of the word inside its chunk
+    uint32_t word = 0;
+    for (int gl = 0; gl < gpw; ++gl) {
+        if ((int64_t)j * 32 + (int64_t)gl * pat.M >= d_in) break;
+        const uint32_t gm = pat.b ? group_mask_bits(idx_field, g0 + gl, pat) : (1u << pat.M) - 1u;
+        word |= gm << (gl * pat.M);
+    }
+    bits[wid] = word;
+}
+
 __global__ void __launch_bounds__(256) mask_flips_kernel(const uint8_t *__restrict__ pa, const uint8_t *__restrict__ pb,
                                                          int64_t d_out, int64_t d_in, Pattern pat,
                                                          unsigned long long *__restrict__ partial)
@@ -781,6 +804,15 @@ __global__ void __launch_bounds__(256) repack_dense_codes_kernel(const uint8_t *
         }
     }
     out[wid] = word;
+}
+
+sbn_status launch_mask_bitplane(const void *packed, int64_t d_out, int64_t d_in, const Pattern &pat, uint32_t *bits,
+                                hipStream_t stream)
+{
+    const int64_t words = d_out * ((d_in + 31) / 32);
+    hipLaunchKernelGGL(mask_bitplane_kernel, dim3((unsigned)ceil_div(words, 256)), dim3(256), 0, stream,
+                       static_cast<const uint8_t *>(packed), d_out, d_in, pat, bits);
+    return check_launch("mask_bitplane_kernel");
 }
 
 sbn_status launch_repack_dense_codes(const void *packed, int64_t d_out, int64_t d_in, const Pattern &pat, uint8_t *out,

@@ -105,6 +105,9 @@ def test_argument_errors_come_before_any_launch(sbn):
     # backward: nothing requested
     assert lib.sbn_sparse_ternary_linear_backward(vp(A), i64(8), i64(256), i64(256), ci(2), ci(4), vp(A), vp(A), vp(A),
                                                   vp(A), vp(0), vp(0), ci(0), vp(A), sz(1 << 24), vp(0)) == sbn.SBN_EINVAL
+    # backward: unknown flag bit
+    assert lib.sbn_sparse_ternary_linear_backward(vp(A), i64(8), i64(256), i64(256), ci(2), ci(4), vp(A), vp(A), vp(A),
+                                                  vp(A), vp(A), vp(A), ci(4), vp(A), sz(1 << 24), vp(0)) == sbn.SBN_EINVAL
     assert lin(d_in=200, path=sbn.SBN_PATH_DENSE_MFMA) == sbn.SBN_EUNSUPPORTED   # dense MFMA rows are multiples of 64
     # mask flips: null input, misaligned count, short workspace
     lib.sbn_mask_flips.restype = ctypes.c_int

@@ -13,7 +13,7 @@ pytestmark = pytest.mark.gpu
 BWD_TOL = 2e-2
 
 
-def hip_forward_backward(W, X, dY, N, M, want_dx=True, want_dw=True, accumulate_into=None):
+def hip_forward_backward(W, X, dY, N, M, want_dx=True, want_dw=True, accumulate_into=None, mask_dw=False):
     s = sbn()
     d_out, d_in = W.shape
     T = X.shape[0]
@@ -31,7 +31,7 @@ def hip_forward_backward(W, X, dY, N, M, want_dx=True, want_dw=True, accumulate_
         dW = torch.full((d_out, d_in), float("nan"), dtype=torch.bfloat16, device=DEV) if want_dw else None
     wsb = s.new_workspace(s.sbn_workspace_bytes(s.SBN_OP_BACKWARD, T, d_out, d_in, N, M))
     s.sbn_sparse_ternary_linear_backward(dYd, packed, gamma, xq, sx, N, M, wsb, d_in, dX=dX, dW=dW,
-                                         accumulate=accumulate_into is not None)
+                                         accumulate=accumulate_into is not None, mask_dw=mask_dw)
     torch.cuda.synchronize()
     return (None if dX is None else dX.float().cpu().numpy(), None if dW is None else dW.float().cpu().numpy(),
             xq.cpu().numpy(), sx.cpu().numpy())
@@ -63,6 +63,27 @@ def test_backward_accumulate_and_partial_outputs():
     assert_rel_rms(dW, r_dw, BWD_TOL, "dW accumulate")
     dX, dW, *_ = hip_forward_backward(W, X, dY, 2, 4, want_dw=False)
     assert dW is None and np.isfinite(dX).all()
+
+
+@pytest.mark.parametrize("N,M", [(2, 4), (1, 4), (2, 8), (6, 8), (4, 4)])
+@pytest.mark.parametrize("tokens,shape", [(64, (256, 256)), (77, (104, 136)), (130, (520, 392))])
+def test_backward_gradient_masked_variant(N, M, tokens, shape):
+    # ablation study, "gradient masking": dW = M (.) dense dW; entries outside the mask are exactly zero
+    # (or, when accumulating, exactly what the buffer held), dX is unaffected
+    W = sbn_synth.latent_weight(shape[0], shape[1], 940 + shape[0])
+    X = sbn_synth.activations(tokens, shape[1], 941 + tokens)
+    dY = sbn_synth.grad_output(tokens, shape[0], 942)
+    _, gamma, Weff, mask = oracle_pack(W, N, M)
+    dX, dW, xq, sx = hip_forward_backward(W, X, dY, N, M, mask_dw=True)
+    r_dw = oracle.backward_dw_gradient_masked(dY.float().numpy(), xq, sx, mask)
+    assert (dW[mask == 0] == 0).all()
+    assert_rel_rms(dW, r_dw, BWD_TOL, "masked dW")
+    assert_rel_rms(dX, oracle.backward_dx(dY.float().numpy(), Weff, gamma), BWD_TOL, "dX")
+    base = (torch.randn(*shape, generator=torch.Generator().manual_seed(6)) * 0.1).to(torch.bfloat16)
+    _, dWa, *_ = hip_forward_backward(W, X, dY, N, M, want_dx=False, accumulate_into=base.clone(), mask_dw=True)
+    basef = base.float().numpy()
+    assert np.array_equal(dWa[mask == 0], basef[mask == 0])
+    assert_rel_rms(dWa, r_dw + basef.astype(np.float64), BWD_TOL, "masked dW accumulate")
 
 
 def test_config5_training_step_block_matrices():
