@@ -69,3 +69,12 @@ def test_norm_then_layer_end_to_end():
     r_xq, r_sx, _ = oracle.rmsnorm_act_quant(X.float().numpy(), gain.numpy(), 1e-5)
     r_y = oracle.rescale(oracle.acc(Weff, r_xq), g, r_sx, None)
     assert_rel(Y.cpu().numpy(), r_y, 1e-3, "Y")
+
+
+def test_rmsnorm_act_quant_full_size_as_timed():
+    # the shape and launch configuration the benchmark times: 4096 tokens x 2560, gain, eps 1e-6
+    X = sbn_synth.activations(4096, 2560, sbn_synth.seed_for(3, 10))
+    gain = 1.0 + 0.25 * torch.randn(2560, generator=torch.Generator().manual_seed(3))
+    xq, sx, xn = run(X, gain, 1e-6)
+    r_xq, r_sx, r_xn = oracle.rmsnorm_act_quant(X.float().numpy(), gain.numpy(), 1e-6)
+    assert np.array_equal(xn, r_xn) and np.array_equal(sx, r_sx) and np.array_equal(xq, r_xq)
