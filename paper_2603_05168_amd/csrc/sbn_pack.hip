@@ -1,6 +1,9 @@
 // quantize_mask_pack: absmean scale, N:M magnitude mask, ternary codes, packed layout.
 //
-// Three enqueues per batch of up to PACK_MAX_ITEMS matrices:
+// bf16 matrices of whole chunks at 2:4, 1:4 or 2:8 take the single-read form: one kernel
+// (pack_fast_kernel<N, M, true>, after a small clear of its counters) whose blocks keep their 16384
+// weights in registers between the |w| sum and the packing, so that W crosses HBM once.
+// Everything else takes three enqueues per batch of up to PACK_MAX_ITEMS matrices:
 //   1. absmean_partial_kernel  one block per 16384 weights, |w| summed in fp64 (every term exact)
 //   2. absmean_finalize_kernel one block per matrix: fixed-order sum of the partials, gamma and
 //                              the rounding threshold theta
@@ -8,6 +11,8 @@
 //                              codes, fields assembled in LDS, one coalesced store
 // Section 2.1 (ternary quantizer), Section 2.2 (mask from latent weights, quantize then mask),
 // Section 2.3 (the mask is recomputed every step, so this is a hot kernel).
+#include <cstdlib>
+
 #include "sbn_internal.hpp"
 
 namespace sbn {
@@ -129,6 +134,17 @@ __global__ void __launch_bounds__(256) absmean_partial_kernel(PackTable tab, dou
 // theta is the smallest fp32 magnitude a with fl32(a / gamma) > 0.5.  Because fl32(a / gamma) is
 // monotone in a, clip(round_half_even(w / gamma), -1, 1) != 0  <=>  |w| >= theta, so the pack
 // kernel needs one integer compare per weight instead of a division.
+// gamma and theta from the fp64 total of |w|
+__device__ __forceinline__ float gamma_theta(double total, int64_t count, float &theta)
+{
+    float g = (float)(total / (double)count);
+    g = g < 1e-5f ? 1e-5f : g;
+    float a = 0.5f * g;
+    while (!(__fdiv_rn(a, g) > 0.5f)) a = __uint_as_float(__float_as_uint(a) + 1u);
+    theta = a;
+    return g;
+}
+
 __global__ void __launch_bounds__(256) absmean_finalize_kernel(PackTable tab, const double *partials, float *theta)
 {
     __shared__ double lds[256];
@@ -139,11 +155,8 @@ __global__ void __launch_bounds__(256) absmean_finalize_kernel(PackTable tab, co
     for (int b = b0 + threadIdx.x; b < b1; b += 256) acc += partials[b];
     const double total = block_sum(acc, lds);
     if (threadIdx.x == 0) {
-        float g = (float)(total / (double)(it.d_out * it.d_in));
-        g = g < 1e-5f ? 1e-5f : g;
-        float a = 0.5f * g;
-        while (!(__fdiv_rn(a, g) > 0.5f)) a = __uint_as_float(__float_as_uint(a) + 1u);
-        *it.gamma = g;
+        float a;
+        *it.gamma = gamma_theta(total, it.d_out * it.d_in, a);
         theta[item] = a;
     }
 }
@@ -319,8 +332,32 @@ __device__ __forceinline__ Top2 top2_of4(uint32_t k0, uint32_t k1, uint32_t k2, 
     return t;
 }
 
-template <int N, int M>
-__global__ void __launch_bounds__(256) pack_fast_kernel(PackTable tab, const float *theta)
+// What the blocks of the single-read form share through the workspace
+// Same-address device-scope atomics cost tens of nanoseconds each and serialise, so the ~1000 blocks of a
+// matrix arrive in two levels: block lb on the counter of group lb % 32, the last block of a group on the
+// matrix's top counter; the matrix's last block raises one ready word per group and the blocks of a
+// group poll theirs.  Every counter and ready word has a 64-byte line of its own.
+constexpr int PACK_SYNC_GROUPS = 32;
+constexpr int PACK_SYNC_STRIDE = 16;                                            // words between two sync words
+constexpr int PACK_SYNC_WORDS = PACK_SYNC_STRIDE * (1 + 2 * PACK_SYNC_GROUPS);  // per matrix: top, group counters, ready words
+struct PackSync {
+    double *partials;     // one per block, as in the absmean pass
+    float *theta;         // one per matrix
+    unsigned *words;      // PACK_SYNC_WORDS per matrix, cleared before the launch
+    int spin_limit;       // polls a block spends waiting for its ready word before it derives theta on its own
+};
+
+// FUSED = false: third kernel of the three-pass form, theta comes from the finalize kernel.
+// FUSED = true: the single-read form.  A block keeps its 16384 weights in registers, publishes
+// their |w| sum, and waits until the matrix's last block has summed all partials (same fixed
+// order as the finalize kernel) and published gamma and theta; then it packs from the registers.
+// W is read from HBM once.  Blocks are dispatched in index order and a matrix's blocks are
+// contiguous, so when a block waits, every block it waits for is already running or done; the
+// host takes this form only for matrices whose blocks all fit on the device at once.  The wait is
+// bounded all the same: a block that runs out of polls recomputes every partial sum of its matrix
+// itself (same arithmetic, same order, same theta) and goes on.
+template <int N, int M, bool FUSED>
+__global__ void __launch_bounds__(256) pack_fast_kernel(PackTable tab, const float *theta, PackSync sync)
 {
     constexpr int U = 8;                                         // block = U x 16 chunks = 16384 weights
     constexpr int CBW = (M == 4 && N == 2) ? 8 : (M == 4 ? 4 : 5);   // dwords per chunk: 32, 16, 20 bytes
@@ -331,7 +368,6 @@ __global__ void __launch_bounds__(256) pack_fast_kernel(PackTable tab, const flo
     const int64_t total_chunks = it.d_out * (it.d_in / CHUNK);
     const uint16_t *W = static_cast<const uint16_t *>(it.W);
     const int tid = threadIdx.x, ql = tid >> 4, l16 = tid & 15;
-    const uint32_t th_key = ((__float_as_uint(theta[lo]) + 0xffffu) >> 16) << 3;   // bf16 threshold pattern, key scale
 
     uint4 v[U];
 #pragma unroll
@@ -339,6 +375,104 @@ __global__ void __launch_bounds__(256) pack_fast_kernel(PackTable tab, const flo
         const int64_t q = (lb * U + u) * 16 + ql;
         v[u] = q < total_chunks ? *reinterpret_cast<const uint4 *>(W + q * CHUNK + l16 * 8) : make_uint4(0, 0, 0, 0);
     }
+    float th_val;
+    if constexpr (FUSED) {
+        __shared__ double red[256];
+        __shared__ int role_s;      // 0: wait for theta, 1: this block arrived last and finalizes, 2: waited in vain
+        __shared__ float th_s;
+        // |w| of eight bf16 values of a vector, in element order (the order of the absmean pass)
+        auto abs8 = [](const uint4 &d, double acc) {
+            const uint32_t w[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                acc += Raw<uint16_t>::abs_value(w[k] & 0xffffu);
+                acc += Raw<uint16_t>::abs_value(w[k] >> 16);
+            }
+            return acc;
+        };
+        double acc = 0.0;
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc = abs8(v[u], acc);
+        const double mine = block_sum(acc, red);
+        const int nblk = tab.pack_block0[lo + 1] - tab.pack_block0[lo];
+        double *const part = sync.partials + tab.sum_block0[lo];
+        const int64_t count = it.d_out * it.d_in;
+        unsigned *const top = sync.words + (int64_t)lo * PACK_SYNC_WORDS;
+        unsigned *const grp = top + PACK_SYNC_STRIDE, *const rdy = grp + PACK_SYNC_STRIDE * PACK_SYNC_GROUPS;
+        const int ngroups = nblk < PACK_SYNC_GROUPS ? nblk : PACK_SYNC_GROUPS;
+        const int mygroup = (int)(lb % PACK_SYNC_GROUPS);
+        // Everything the blocks exchange (partials, theta, counters, ready words) moves through device-scope
+        // atomic accesses, which are served at the level where the eight L2s meet, and a block orders its
+        // own accesses by waiting for the store to be acknowledged.  Release/acquire fences would do the
+        // same with cache write-backs and invalidations, a thousand per matrix (measured: 43 us per matrix).
+        unsigned long long *const part_bits = reinterpret_cast<unsigned long long *>(part);
+        unsigned *const theta_bits = reinterpret_cast<unsigned *>(sync.theta) + lo;
+        if (tid == 0) {
+            __hip_atomic_store(&part_bits[lb], (unsigned long long)__double_as_longlong(mine), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the partial is in place before the arrival is counted
+            const int gsize = (nblk - mygroup + PACK_SYNC_GROUPS - 1) / PACK_SYNC_GROUPS;
+            int last = 0;
+            if (atomicAdd(&grp[PACK_SYNC_STRIDE * mygroup], 1u) == (unsigned)(gsize - 1))
+                last = atomicAdd(top, 1u) == (unsigned)(ngroups - 1);
+            role_s = last;
+        }
+        __syncthreads();
+        if (role_s == 1) {
+            double a2 = 0.0;
+            for (int b = tid; b < nblk; b += 256)
+                a2 += __longlong_as_double((long long)__hip_atomic_load(&part_bits[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            const double total = block_sum(a2, red);
+            if (tid == 0) {
+                float th;
+                *it.gamma = gamma_theta(total, count, th);
+                *theta_bits = __float_as_uint(th);
+                th_s = th;
+            }
+            __syncthreads();
+            // the ready word of a group IS theta (its bit pattern is never zero: theta >= 0.5e-5)
+            if (tid < ngroups)
+                __hip_atomic_store(&rdy[PACK_SYNC_STRIDE * tid], __float_as_uint(th_s), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else {
+            if (tid == 0) {
+                int spins = 0, ok = sync.spin_limit >= 0;
+                unsigned word = 0u;
+                while (ok && (word = __hip_atomic_load(&rdy[PACK_SYNC_STRIDE * mygroup], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) == 0u) {
+                    if (++spins > sync.spin_limit) ok = 0;
+                    else __builtin_amdgcn_s_sleep(4);
+                }
+                if (ok) th_s = __uint_as_float(word);
+                else role_s = 2;
+            }
+            __syncthreads();
+            if (role_s == 2) {
+                // every partial sum of the matrix from HBM, added up in the finalize order: thread b % 256 takes partial b
+                double a2 = 0.0;
+                for (int b = 0; b < nblk; ++b) {
+                    double pa = 0.0;
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const int64_t q = ((int64_t)b * U + u) * 16 + ql;
+                        if (q < total_chunks) pa = abs8(*reinterpret_cast<const uint4 *>(W + q * CHUNK + l16 * 8), pa);
+                    }
+                    const double pb = block_sum(pa, red);
+                    if ((b & 255) == tid) a2 += pb;
+                    __syncthreads();   // red is reused by the next round
+                }
+                const double total = block_sum(a2, red);
+                if (tid == 0) {
+                    float th;
+                    gamma_theta(total, count, th);
+                    th_s = th;
+                }
+            }
+        }
+        __syncthreads();
+        th_val = th_s;
+    } else {
+        th_val = theta[lo];
+    }
+    const uint32_t th_key = ((__float_as_uint(th_val) + 0xffffu) >> 16) << 3;   // bf16 threshold pattern, key scale
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const uint32_t d[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
@@ -664,7 +798,35 @@ sbn_status launch_pack_kernel(const PackTable &tab, int nblocks, const float *th
 size_t pack_workspace_bytes(int64_t count, int64_t d_out, int64_t d_in)
 {
     const int64_t blocks = ceil_div(d_out * d_in, PACK_SUM_ELEMS);
-    return align_up((size_t)count * (size_t)blocks * sizeof(double), 256) + align_up((size_t)count * sizeof(float), 256);
+    return align_up((size_t)count * (size_t)blocks * sizeof(double), 256) + align_up((size_t)count * sizeof(float), 256) +
+           align_up((size_t)count * PACK_SYNC_WORDS * sizeof(unsigned), 256);
+}
+
+__global__ void __launch_bounds__(256) pack_sync_clear_kernel(unsigned *words, int n)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) words[i] = 0u;
+}
+
+// blocks of the single-read pack kernel the device holds at once (per instantiation, cached per thread)
+template <int N, int M>
+static int fused_capacity()
+{
+    static thread_local int cap = 0;
+    if (cap == 0) {
+        int per_cu = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, pack_fast_kernel<N, M, true>, 256, 0) != hipSuccess) per_cu = 0;
+        cap = per_cu > 0 ? per_cu * device_cus() : -1;
+    }
+    return cap;
+}
+
+// polls a block of the single-read form spends on the matrix's "ready" word before it derives theta alone;
+// SBN_PACK_SPIN_LIMIT overrides (negative: never look, every block derives theta alone: exercised by the tests)
+static int pack_spin_limit()
+{
+    const char *e = getenv("SBN_PACK_SPIN_LIMIT");
+    return e && *e ? atoi(e) : 1 << 18;
 }
 
 sbn_status launch_pack(int count, const PackItem *items, sbn_dtype wdt, const Pattern &pat, void *workspace,
@@ -673,10 +835,13 @@ sbn_status launch_pack(int count, const PackItem *items, sbn_dtype wdt, const Pa
     // workspace: [partials: one double per absmean block of every matrix][theta: one float per matrix]
     int64_t total_sum_blocks = 0;
     for (int i = 0; i < count; ++i) total_sum_blocks += ceil_div(items[i].d_out * items[i].d_in, PACK_SUM_ELEMS);
-    const size_t need = align_up((size_t)total_sum_blocks * sizeof(double), 256) + align_up((size_t)count * sizeof(float), 256);
+    // + [arrival counters and ready words of the single-read form: PACK_SYNC_WORDS per matrix]
+    const size_t need = align_up((size_t)total_sum_blocks * sizeof(double), 256) + align_up((size_t)count * sizeof(float), 256) +
+                        align_up((size_t)count * PACK_SYNC_WORDS * sizeof(unsigned), 256);
     if (ws_bytes < need) return SBN_ESIZE;
     double *partials = static_cast<double *>(workspace);
     float *theta = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + align_up((size_t)total_sum_blocks * sizeof(double), 256));
+    unsigned *sync_words = reinterpret_cast<unsigned *>(reinterpret_cast<uint8_t *>(theta) + align_up((size_t)count * sizeof(float), 256));
 
     const size_t esz = wdt == SBN_BF16 ? 2 : 4;
     int64_t sum_base = 0;
@@ -704,22 +869,48 @@ sbn_status launch_pack(int count, const PackItem *items, sbn_dtype wdt, const Pa
         tab.pack_block0[n] = pb;
         double *part = partials + sum_base;
         float *th = theta + first;
+        const bool fast_pattern = (pat.M == 4 && (pat.N == 1 || pat.N == 2)) || (pat.M == 8 && pat.N == 2);
+        const bool fast = wdt == SBN_BF16 && fast_pattern && flat_ok;
+        sbn_status st = SBN_OK;
+        // single-read form: every matrix's blocks must fit on the device together (see pack_fast_kernel)
+        bool fused = fast;
+        if (fast) {
+            const int cap = pat.M == 4 && pat.N == 2 ? fused_capacity<2, 4>() : pat.M == 4 ? fused_capacity<1, 4>() : fused_capacity<2, 8>();
+            for (int i = 0; i < n; ++i) fused = fused && fb[i + 1] - fb[i] <= cap;
+        }
+        if (fused) {
+            for (int i = 0; i < n; ++i) tab.pack_block0[i] = fb[i];
+            tab.pack_block0[n] = fb[n];
+            unsigned *words = sync_words + (size_t)PACK_SYNC_WORDS * first;
+            hipLaunchKernelGGL(pack_sync_clear_kernel, dim3((n * PACK_SYNC_WORDS + 255) / 256), dim3(256), 0, stream, words,
+                               n * PACK_SYNC_WORDS);
+            st = check_launch("pack_sync_clear_kernel");
+            if (st != SBN_OK) return st;
+            PackSync sync{part, th, words, pack_spin_limit()};
+            if (pat.M == 4 && pat.N == 2) hipLaunchKernelGGL((pack_fast_kernel<2, 4, true>), dim3(fb[n]), dim3(256), 0, stream, tab, th, sync);
+            else if (pat.M == 4) hipLaunchKernelGGL((pack_fast_kernel<1, 4, true>), dim3(fb[n]), dim3(256), 0, stream, tab, th, sync);
+            else hipLaunchKernelGGL((pack_fast_kernel<2, 8, true>), dim3(fb[n]), dim3(256), 0, stream, tab, th, sync);
+            st = check_launch("pack_fast_kernel");
+            if (st != SBN_OK) return st;
+            sum_base += sb;
+            continue;
+        }
         if (wdt == SBN_BF16)
             hipLaunchKernelGGL(absmean_partial_kernel<uint16_t>, dim3(sb), dim3(256), 0, stream, tab, part, vec_ok);
         else
             hipLaunchKernelGGL(absmean_partial_kernel<float>, dim3(sb), dim3(256), 0, stream, tab, part, vec_ok);
-        sbn_status st = check_launch("absmean_partial_kernel");
+        st = check_launch("absmean_partial_kernel");
         if (st != SBN_OK) return st;
         hipLaunchKernelGGL(absmean_finalize_kernel, dim3(n), dim3(256), 0, stream, tab, part, th);
         st = check_launch("absmean_finalize_kernel");
         if (st != SBN_OK) return st;
-        const bool fast_pattern = (pat.M == 4 && (pat.N == 1 || pat.N == 2)) || (pat.M == 8 && pat.N == 2);
-        if (wdt == SBN_BF16 && fast_pattern && flat_ok) {
+        if (fast) {
             for (int i = 0; i < n; ++i) tab.pack_block0[i] = fb[i];
             tab.pack_block0[n] = fb[n];
-            if (pat.M == 4 && pat.N == 2) hipLaunchKernelGGL((pack_fast_kernel<2, 4>), dim3(fb[n]), dim3(256), 0, stream, tab, th);
-            else if (pat.M == 4) hipLaunchKernelGGL((pack_fast_kernel<1, 4>), dim3(fb[n]), dim3(256), 0, stream, tab, th);
-            else hipLaunchKernelGGL((pack_fast_kernel<2, 8>), dim3(fb[n]), dim3(256), 0, stream, tab, th);
+            const PackSync none{};
+            if (pat.M == 4 && pat.N == 2) hipLaunchKernelGGL((pack_fast_kernel<2, 4, false>), dim3(fb[n]), dim3(256), 0, stream, tab, th, none);
+            else if (pat.M == 4) hipLaunchKernelGGL((pack_fast_kernel<1, 4, false>), dim3(fb[n]), dim3(256), 0, stream, tab, th, none);
+            else hipLaunchKernelGGL((pack_fast_kernel<2, 8, false>), dim3(fb[n]), dim3(256), 0, stream, tab, th, none);
             st = check_launch("pack_fast_kernel");
         } else {
             st = wdt == SBN_BF16 ? launch_pack_kernel<uint16_t>(tab, pb, th, vec_ok, pat, stream)

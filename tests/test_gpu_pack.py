@@ -148,3 +148,27 @@ def test_mask_flips_between_two_steps(N, M, shape):
     s.sbn_mask_flips(p0, p0, shape[0], shape[1], N, M, flips, ws)
     torch.cuda.synchronize()
     assert flips.item() == 0
+
+
+@pytest.mark.parametrize("spin_limit", ["-1", "0", "3"])
+@pytest.mark.parametrize("N,M", [(2, 4), (1, 4), (2, 8)])
+def test_single_read_pack_when_blocks_do_not_wait(N, M, spin_limit, monkeypatch):
+    # the single-read form of the pack kernel with its wait cut short: -1 = no block waits for the matrix's
+    # last block (each derives the threshold from HBM itself), 0 and 3 = a few polls, then the same;
+    # bytes and gamma must not depend on which way a block took
+    monkeypatch.setenv("SBN_PACK_SPIN_LIMIT", spin_limit)
+    s = sbn()
+    shapes = [(640, 1280), (100, 384), (256, 256), (1024, 2560)]
+    Ws = [sbn_synth.latent_weight(a, b, 1800 + i) for i, (a, b) in enumerate(shapes)]
+    Wd = [W.to(DEV) for W in Ws]
+    packed = [torch.zeros(s.sbn_packed_bytes(a, b, N, M), dtype=torch.uint8, device=DEV) for a, b in shapes]
+    gammas = torch.zeros(len(shapes), dtype=torch.float32, device=DEV)
+    glist = [gammas[i:i + 1] for i in range(len(shapes))]
+    ws = s.new_workspace(s.sbn_workspace_bytes(s.SBN_OP_QUANTIZE_MASK_PACK, len(shapes), 1024, 2560, N, M))
+    for _ in range(2):   # twice through the same workspace: counters and flags start clean every call
+        s.sbn_quantize_mask_pack_batched(Wd, N, M, packed, glist, ws)
+        torch.cuda.synchronize()
+        for i, W in enumerate(Ws):
+            ref, g, *_ = oracle_pack(W, N, M)
+            assert gammas[i].item() == g
+            assert np.array_equal(packed[i].cpu().numpy(), ref)
