@@ -449,3 +449,14 @@ def test_convert_packed_6of8_full_size_streaming():
         _, g, Weff, _ = oracle_pack(Ws[r], 6, 8)
         y, *_ = oracle.sparse_ternary_linear(Xf, Weff, g)
         assert_rel(Ys[r].cpu().numpy(), y, Y_TOL, f"Y of copy {r}")
+
+
+@pytest.mark.parametrize("tokens,d_out", [(7000, 2560), (6980, 2500)])
+def test_sparse_gemm_more_tiles_than_block_slots_ragged(tokens, d_out):
+    # more tiles than the device has block slots (a second, partial round of blocks), ragged last token
+    # tile, ragged rows; accumulators bit-exact on sampled tokens from both ends and the middle
+    s = sbn()
+    W = sbn_synth.latent_weight(d_out, 256, 2000 + d_out)
+    X = sbn_synth.activations(tokens, 256, 2001)
+    sample = np.unique(np.concatenate([np.arange(0, 200), np.arange(tokens - 400, tokens), np.arange(3000, 3100)]))
+    check_forward(W, X, 2, 4, s.SBN_PATH_SMFMAC, token_sample=sample)
