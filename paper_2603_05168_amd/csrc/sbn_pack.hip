@@ -1,8 +1,8 @@
 // quantize_mask_pack: absmean scale, N:M magnitude mask, ternary codes, packed layout.
 //
-// bf16 matrices of whole chunks at 2:4, 1:4 or 2:8 take the single-read form: one kernel
-// (pack_fast_kernel<N, M, true>, after a small clear of its counters) whose blocks keep their 16384
-// weights in registers between the |w| sum and the packing, so that W crosses HBM once.
+// bf16 matrices of whole chunks at 2:4, 1:4 or 2:8 take the single-read form: one persistent kernel
+// (pack_stream_kernel<N, M>, after a small clear of its counters) whose blocks keep 16384 weights
+// in registers between the |w| sum and the packing, so that W crosses HBM once.
 // Everything else takes three enqueues per batch of up to PACK_MAX_ITEMS matrices:
 //   1. absmean_partial_kernel  one block per 16384 weights, |w| summed in fp64 (every term exact)
 //   2. absmean_finalize_kernel one block per matrix: fixed-order sum of the partials, gamma and
@@ -347,131 +347,43 @@ struct PackSync {
     int spin_limit;       // polls a block spends waiting for its ready word before it derives theta on its own
 };
 
-// FUSED = false: third kernel of the three-pass form, theta comes from the finalize kernel.
-// FUSED = true: the single-read form.  A block keeps its 16384 weights in registers, publishes
-// their |w| sum, and waits until the matrix's last block has summed all partials (same fixed
-// order as the finalize kernel) and published gamma and theta; then it packs from the registers.
-// W is read from HBM once.  Blocks are dispatched in index order and a matrix's blocks are
-// contiguous, so when a block waits, every block it waits for is already running or done; the
-// host takes this form only for matrices whose blocks all fit on the device at once.  The wait is
-// bounded all the same: a block that runs out of polls recomputes every partial sum of its matrix
-// itself (same arithmetic, same order, same theta) and goes on.
-template <int N, int M, bool FUSED>
-__global__ void __launch_bounds__(256) pack_fast_kernel(PackTable tab, const float *theta, PackSync sync)
+constexpr int PACK_U = 8;   // 16-byte vectors per thread: a unit = 256 threads x 8 vectors = 128 chunks = 16384 weights
+
+// the unit's weights into registers: thread (ql = tid / 16, l16 = tid % 16) takes vector l16 of chunk 16 u + ql
+__device__ __forceinline__ void load_unit(const PackItem &it, int64_t lb, uint4 (&v)[PACK_U])
 {
-    constexpr int U = 8;                                         // block = U x 16 chunks = 16384 weights
-    constexpr int CBW = (M == 4 && N == 2) ? 8 : (M == 4 ? 4 : 5);   // dwords per chunk: 32, 16, 20 bytes
-    __shared__ __attribute__((aligned(16))) uint32_t lds[U * 16 * CBW];
-    const int lo = find_item(tab.pack_block0, tab.count, blockIdx.x);
-    const PackItem &it = tab.it[lo];
-    const int64_t lb = (int)blockIdx.x - tab.pack_block0[lo];
     const int64_t total_chunks = it.d_out * (it.d_in / CHUNK);
     const uint16_t *W = static_cast<const uint16_t *>(it.W);
-    const int tid = threadIdx.x, ql = tid >> 4, l16 = tid & 15;
-
-    uint4 v[U];
+    const int ql = threadIdx.x >> 4, l16 = threadIdx.x & 15;
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int64_t q = (lb * U + u) * 16 + ql;
+    for (int u = 0; u < PACK_U; ++u) {
+        const int64_t q = (lb * PACK_U + u) * 16 + ql;
         v[u] = q < total_chunks ? *reinterpret_cast<const uint4 *>(W + q * CHUNK + l16 * 8) : make_uint4(0, 0, 0, 0);
     }
-    float th_val;
-    if constexpr (FUSED) {
-        __shared__ double red[256];
-        __shared__ int role_s;      // 0: wait for theta, 1: this block arrived last and finalizes, 2: waited in vain
-        __shared__ float th_s;
-        // |w| of eight bf16 values of a vector, in element order (the order of the absmean pass)
-        auto abs8 = [](const uint4 &d, double acc) {
-            const uint32_t w[4] = {d.x, d.y, d.z, d.w};
+}
+
+// |w| of the eight bf16 values of a vector added to acc in element order (the order of the absmean pass)
+__device__ __forceinline__ double abs8(const uint4 &d, double acc)
+{
+    const uint32_t w[4] = {d.x, d.y, d.z, d.w};
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                acc += Raw<uint16_t>::abs_value(w[k] & 0xffffu);
-                acc += Raw<uint16_t>::abs_value(w[k] >> 16);
-            }
-            return acc;
-        };
-        double acc = 0.0;
-#pragma unroll
-        for (int u = 0; u < U; ++u) acc = abs8(v[u], acc);
-        const double mine = block_sum(acc, red);
-        const int nblk = tab.pack_block0[lo + 1] - tab.pack_block0[lo];
-        double *const part = sync.partials + tab.sum_block0[lo];
-        const int64_t count = it.d_out * it.d_in;
-        unsigned *const top = sync.words + (int64_t)lo * PACK_SYNC_WORDS;
-        unsigned *const grp = top + PACK_SYNC_STRIDE, *const rdy = grp + PACK_SYNC_STRIDE * PACK_SYNC_GROUPS;
-        const int ngroups = nblk < PACK_SYNC_GROUPS ? nblk : PACK_SYNC_GROUPS;
-        const int mygroup = (int)(lb % PACK_SYNC_GROUPS);
-        // Everything the blocks exchange (partials, theta, counters, ready words) moves through device-scope
-        // atomic accesses, which are served at the level where the eight L2s meet, and a block orders its
-        // own accesses by waiting for the store to be acknowledged.  Release/acquire fences would do the
-        // same with cache write-backs and invalidations, a thousand per matrix (measured: 43 us per matrix).
-        unsigned long long *const part_bits = reinterpret_cast<unsigned long long *>(part);
-        unsigned *const theta_bits = reinterpret_cast<unsigned *>(sync.theta) + lo;
-        if (tid == 0) {
-            __hip_atomic_store(&part_bits[lb], (unsigned long long)__double_as_longlong(mine), __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the partial is in place before the arrival is counted
-            const int gsize = (nblk - mygroup + PACK_SYNC_GROUPS - 1) / PACK_SYNC_GROUPS;
-            int last = 0;
-            if (atomicAdd(&grp[PACK_SYNC_STRIDE * mygroup], 1u) == (unsigned)(gsize - 1))
-                last = atomicAdd(top, 1u) == (unsigned)(ngroups - 1);
-            role_s = last;
-        }
-        __syncthreads();
-        if (role_s == 1) {
-            double a2 = 0.0;
-            for (int b = tid; b < nblk; b += 256)
-                a2 += __longlong_as_double((long long)__hip_atomic_load(&part_bits[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-            const double total = block_sum(a2, red);
-            if (tid == 0) {
-                float th;
-                *it.gamma = gamma_theta(total, count, th);
-                *theta_bits = __float_as_uint(th);
-                th_s = th;
-            }
-            __syncthreads();
-            // the ready word of a group IS theta (its bit pattern is never zero: theta >= 0.5e-5)
-            if (tid < ngroups)
-                __hip_atomic_store(&rdy[PACK_SYNC_STRIDE * tid], __float_as_uint(th_s), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        } else {
-            if (tid == 0) {
-                int spins = 0, ok = sync.spin_limit >= 0;
-                unsigned word = 0u;
-                while (ok && (word = __hip_atomic_load(&rdy[PACK_SYNC_STRIDE * mygroup], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) == 0u) {
-                    if (++spins > sync.spin_limit) ok = 0;
-                    else __builtin_amdgcn_s_sleep(4);
-                }
-                if (ok) th_s = __uint_as_float(word);
-                else role_s = 2;
-            }
-            __syncthreads();
-            if (role_s == 2) {
-                // every partial sum of the matrix from HBM, added up in the finalize order: thread b % 256 takes partial b
-                double a2 = 0.0;
-                for (int b = 0; b < nblk; ++b) {
-                    double pa = 0.0;
-#pragma unroll
-                    for (int u = 0; u < U; ++u) {
-                        const int64_t q = ((int64_t)b * U + u) * 16 + ql;
-                        if (q < total_chunks) pa = abs8(*reinterpret_cast<const uint4 *>(W + q * CHUNK + l16 * 8), pa);
-                    }
-                    const double pb = block_sum(pa, red);
-                    if ((b & 255) == tid) a2 += pb;
-                    __syncthreads();   // red is reused by the next round
-                }
-                const double total = block_sum(a2, red);
-                if (tid == 0) {
-                    float th;
-                    gamma_theta(total, count, th);
-                    th_s = th;
-                }
-            }
-        }
-        __syncthreads();
-        th_val = th_s;
-    } else {
-        th_val = theta[lo];
+    for (int k = 0; k < 4; ++k) {
+        acc += Raw<uint16_t>::abs_value(w[k] & 0xffffu);
+        acc += Raw<uint16_t>::abs_value(w[k] >> 16);
     }
+    return acc;
+}
+
+// Packs the unit held in v with threshold th_val and stores its 128 chunks (contiguous in the packed buffer).
+// lds: PACK_U * 16 * CBW words of staging; ends with the block's stores issued, LDS free after the next barrier.
+template <int N, int M>
+__device__ __forceinline__ void pack_unit(const PackItem &it, const int64_t lb, const uint4 (&v)[PACK_U], const float th_val,
+                                          uint32_t *lds)
+{
+    constexpr int U = PACK_U;
+    constexpr int CBW = (M == 4 && N == 2) ? 8 : (M == 4 ? 4 : 5);   // dwords per chunk: 32, 16, 20 bytes
+    const int64_t total_chunks = it.d_out * (it.d_in / CHUNK);
+    const int tid = threadIdx.x, ql = tid >> 4, l16 = tid & 15;
     const uint32_t th_key = ((__float_as_uint(th_val) + 0xffffu) >> 16) << 3;   // bf16 threshold pattern, key scale
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -557,6 +469,178 @@ __global__ void __launch_bounds__(256) pack_fast_kernel(PackTable tab, const flo
         } else {
             for (int k = w; k < ndw; ++k) dst[k] = lds[k];
         }
+    }
+}
+
+// third kernel of the three-pass form: theta comes from the finalize kernel
+template <int N, int M>
+__global__ void __launch_bounds__(256) pack_fast_kernel(PackTable tab, const float *theta)
+{
+    constexpr int CBW = (M == 4 && N == 2) ? 8 : (M == 4 ? 4 : 5);
+    __shared__ __attribute__((aligned(16))) uint32_t lds[PACK_U * 16 * CBW];
+    const int lo = find_item(tab.pack_block0, tab.count, blockIdx.x);
+    const PackItem &it = tab.it[lo];
+    const int64_t lb = (int)blockIdx.x - tab.pack_block0[lo];
+    uint4 v[PACK_U];
+    load_unit(it, lb, v);
+    pack_unit<N, M>(it, lb, v, theta[lo], lds);
+}
+
+// ---- single-read form ---------------------------------------------------------------------------
+// Persistent blocks, as many as the device holds at once.  The units of the batch (16384 weights each,
+// matrix after matrix) are dealt round-robin: block b takes units b, b + B, b + 2B, ...  For every unit a
+// block loads the weights into registers, publishes their |w| sum and arrives on the matrix's two-level
+// counter; the block whose arrival completes a matrix adds the partials in the fixed order of the
+// finalize kernel, derives gamma and theta and raises the matrix's ready words (they carry theta).  A
+// block packs a unit from its registers once the unit's matrix is ready - and before it waits for
+// that, it has already loaded and published its NEXT unit into a second set of registers, so the
+// hand-over of one matrix (four device-scope hops of about 1.5 us) runs under the loads of the
+// following one.  W crosses HBM once.
+// Waits always end: a unit's matrix becomes ready once all its units are published; a block publishes
+// unit k + 1 before it waits for unit k, and the units of a matrix (at most as many as there are
+// blocks: the host checks) all lie within one deal of the round-robin, so every wait depends only on
+// publications that are earlier in the deal order.  The wait is bounded all the same (the grid might
+// not be fully resident when the device is shared): a block out of polls recomputes every partial of
+// the matrix from HBM itself - same arithmetic, same order, same theta - and goes on.
+template <int N, int M>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5, 5))) pack_stream_kernel(PackTable tab, PackSync sync)
+{
+    constexpr int CBW = (M == 4 && N == 2) ? 8 : (M == 4 ? 4 : 5);
+    __shared__ __attribute__((aligned(16))) uint32_t lds[PACK_U * 16 * CBW];
+    __shared__ double red[256];
+    __shared__ int role_s;      // 1: this block's arrival completed the matrix, 2: waited in vain
+    __shared__ float th_s;
+    const int tid = threadIdx.x;
+    const int total_units = tab.pack_block0[tab.count];
+    const int B = (int)gridDim.x;
+
+    struct Unit { int lo; int64_t lb; float theta; };   // theta != 0: already known to this block (it finalized the matrix)
+    auto sync_words = [&](int lo, unsigned *&top, unsigned *&grp, unsigned *&rdy) {
+        top = sync.words + (int64_t)lo * PACK_SYNC_WORDS;
+        grp = top + PACK_SYNC_STRIDE;
+        rdy = grp + PACK_SYNC_STRIDE * PACK_SYNC_GROUPS;
+    };
+    // load unit g, publish its partial sum, finalize its matrix if this arrival completes it
+    auto load_publish = [&](int g, uint4 (&v)[PACK_U]) -> Unit {
+        Unit un;
+        un.lo = find_item(tab.pack_block0, tab.count, g);
+        un.lb = g - tab.pack_block0[un.lo];
+        un.theta = 0.0f;
+        const PackItem &it = tab.it[un.lo];
+        load_unit(it, un.lb, v);
+        double acc = 0.0;
+#pragma unroll
+        for (int u = 0; u < PACK_U; ++u) acc = abs8(v[u], acc);
+        const double mine = block_sum(acc, red);
+        const int nblk = tab.pack_block0[un.lo + 1] - tab.pack_block0[un.lo];
+        unsigned long long *const part_bits = reinterpret_cast<unsigned long long *>(sync.partials + tab.sum_block0[un.lo]);
+        unsigned *top, *grp, *rdy;
+        sync_words(un.lo, top, grp, rdy);
+        const int ngroups = nblk < PACK_SYNC_GROUPS ? nblk : PACK_SYNC_GROUPS;
+        const int mygroup = (int)(un.lb % PACK_SYNC_GROUPS);
+        // Everything the blocks exchange (partials, theta, counters, ready words) moves through device-scope
+        // atomic accesses, which are served where the eight L2s meet, and a block orders its own accesses by
+        // waiting for the store to be acknowledged.  Release/acquire fences would do the same with a cache
+        // write-back or invalidation each, a thousand per matrix (measured: 43 us per matrix).
+        if (tid == 0) {
+            __hip_atomic_store(&part_bits[un.lb], (unsigned long long)__double_as_longlong(mine), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the partial is in place before the arrival is counted
+            const int gsize = (nblk - mygroup + PACK_SYNC_GROUPS - 1) / PACK_SYNC_GROUPS;
+            int last = 0;
+            if (atomicAdd(&grp[PACK_SYNC_STRIDE * mygroup], 1u) == (unsigned)(gsize - 1))
+                last = atomicAdd(top, 1u) == (unsigned)(ngroups - 1);
+            role_s = last;
+        }
+        __syncthreads();
+        if (role_s == 1) {
+            double a2 = 0.0;
+            for (int b = tid; b < nblk; b += 256)
+                a2 += __longlong_as_double((long long)__hip_atomic_load(&part_bits[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            const double total = block_sum(a2, red);
+            if (tid == 0) {
+                float th;
+                *it.gamma = gamma_theta(total, it.d_out * it.d_in, th);
+                sync.theta[un.lo] = th;
+                th_s = th;
+            }
+            __syncthreads();
+            // the ready word of a group IS theta (its bit pattern is never zero: theta >= 0.5e-5)
+            if (tid < ngroups)
+                __hip_atomic_store(&rdy[PACK_SYNC_STRIDE * tid], __float_as_uint(th_s), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            un.theta = th_s;
+        }
+        __syncthreads();   // red, role_s and th_s are free again
+        return un;
+    };
+    // theta of the unit's matrix: known, or polled from the group's ready word, or recomputed
+    auto theta_of = [&](const Unit &un) -> float {
+        if (un.theta != 0.0f) return un.theta;   // block-uniform
+        const PackItem &it = tab.it[un.lo];
+        const int nblk = tab.pack_block0[un.lo + 1] - tab.pack_block0[un.lo];
+        unsigned *top, *grp, *rdy;
+        sync_words(un.lo, top, grp, rdy);
+        if (tid == 0) {
+            int spins = 0, ok = sync.spin_limit >= 0;
+            unsigned word = 0u;
+            while (ok && (word = __hip_atomic_load(&rdy[PACK_SYNC_STRIDE * (un.lb % PACK_SYNC_GROUPS)], __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT)) == 0u) {
+                if (++spins > sync.spin_limit) ok = 0;
+                else __builtin_amdgcn_s_sleep(4);
+            }
+            role_s = ok ? 0 : 2;
+            th_s = __uint_as_float(word);
+        }
+        __syncthreads();
+        if (role_s == 2) {
+            // every partial sum of the matrix from HBM, added up in the finalize order: thread b % 256 takes partial b
+            const int64_t total_chunks = it.d_out * (it.d_in / CHUNK);
+            const uint16_t *W = static_cast<const uint16_t *>(it.W);
+            const int ql = tid >> 4, l16 = tid & 15;
+            double a2 = 0.0;
+            for (int b = 0; b < nblk; ++b) {
+                double pa = 0.0;
+#pragma unroll
+                for (int u = 0; u < PACK_U; ++u) {
+                    const int64_t q = ((int64_t)b * PACK_U + u) * 16 + ql;
+                    if (q < total_chunks) pa = abs8(*reinterpret_cast<const uint4 *>(W + q * CHUNK + l16 * 8), pa);
+                }
+                const double pb = block_sum(pa, red);
+                if ((b & 255) == tid) a2 += pb;
+                __syncthreads();   // red is reused by the next round
+            }
+            const double total = block_sum(a2, red);
+            if (tid == 0) {
+                float th;
+                gamma_theta(total, it.d_out * it.d_in, th);
+                th_s = th;
+            }
+            __syncthreads();
+        }
+        const float th = th_s;
+        __syncthreads();   // th_s may be rewritten by the next publication
+        return th;
+    };
+    auto pack = [&](const Unit &un, const uint4 (&v)[PACK_U]) {
+        const float th = theta_of(un);
+        pack_unit<N, M>(tab.it[un.lo], un.lb, v, th, lds);
+        __syncthreads();   // the staging area is free for the next unit
+    };
+
+    uint4 va[PACK_U], vb[PACK_U];
+    int g = (int)blockIdx.x;
+    if (g >= total_units) return;
+    Unit ua = load_publish(g, va), ub;
+    while (true) {
+        const int g1 = g + B;
+        if (g1 < total_units) ub = load_publish(g1, vb);
+        pack(ua, va);
+        if (g1 >= total_units) break;
+        const int g2 = g1 + B;
+        if (g2 < total_units) ua = load_publish(g2, va);
+        pack(ub, vb);
+        if (g2 >= total_units) break;
+        g = g2;
     }
 }
 
@@ -808,14 +892,14 @@ __global__ void __launch_bounds__(256) pack_sync_clear_kernel(unsigned *words, i
     if (i < n) words[i] = 0u;
 }
 
-// blocks of the single-read pack kernel the device holds at once (per instantiation, cached per thread)
+// blocks of the single-read pack kernel the device holds at once = its grid (per instantiation, cached per thread)
 template <int N, int M>
 static int fused_capacity()
 {
     static thread_local int cap = 0;
     if (cap == 0) {
         int per_cu = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, pack_fast_kernel<N, M, true>, 256, 0) != hipSuccess) per_cu = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, pack_stream_kernel<N, M>, 256, 0) != hipSuccess) per_cu = 0;
         cap = per_cu > 0 ? per_cu * device_cus() : -1;
     }
     return cap;
@@ -872,10 +956,11 @@ sbn_status launch_pack(int count, const PackItem *items, sbn_dtype wdt, const Pa
         const bool fast_pattern = (pat.M == 4 && (pat.N == 1 || pat.N == 2)) || (pat.M == 8 && pat.N == 2);
         const bool fast = wdt == SBN_BF16 && fast_pattern && flat_ok;
         sbn_status st = SBN_OK;
-        // single-read form: every matrix's blocks must fit on the device together (see pack_fast_kernel)
+        // single-read form: persistent grid of as many blocks as the device holds; no matrix may have more units than that
         bool fused = fast;
+        int cap = 0;
         if (fast) {
-            const int cap = pat.M == 4 && pat.N == 2 ? fused_capacity<2, 4>() : pat.M == 4 ? fused_capacity<1, 4>() : fused_capacity<2, 8>();
+            cap = pat.M == 4 && pat.N == 2 ? fused_capacity<2, 4>() : pat.M == 4 ? fused_capacity<1, 4>() : fused_capacity<2, 8>();
             for (int i = 0; i < n; ++i) fused = fused && fb[i + 1] - fb[i] <= cap;
         }
         if (fused) {
@@ -887,10 +972,11 @@ sbn_status launch_pack(int count, const PackItem *items, sbn_dtype wdt, const Pa
             st = check_launch("pack_sync_clear_kernel");
             if (st != SBN_OK) return st;
             PackSync sync{part, th, words, pack_spin_limit()};
-            if (pat.M == 4 && pat.N == 2) hipLaunchKernelGGL((pack_fast_kernel<2, 4, true>), dim3(fb[n]), dim3(256), 0, stream, tab, th, sync);
-            else if (pat.M == 4) hipLaunchKernelGGL((pack_fast_kernel<1, 4, true>), dim3(fb[n]), dim3(256), 0, stream, tab, th, sync);
-            else hipLaunchKernelGGL((pack_fast_kernel<2, 8, true>), dim3(fb[n]), dim3(256), 0, stream, tab, th, sync);
-            st = check_launch("pack_fast_kernel");
+            const int grid = fb[n] < cap ? fb[n] : cap;
+            if (pat.M == 4 && pat.N == 2) hipLaunchKernelGGL((pack_stream_kernel<2, 4>), dim3(grid), dim3(256), 0, stream, tab, sync);
+            else if (pat.M == 4) hipLaunchKernelGGL((pack_stream_kernel<1, 4>), dim3(grid), dim3(256), 0, stream, tab, sync);
+            else hipLaunchKernelGGL((pack_stream_kernel<2, 8>), dim3(grid), dim3(256), 0, stream, tab, sync);
+            st = check_launch("pack_stream_kernel");
             if (st != SBN_OK) return st;
             sum_base += sb;
             continue;
@@ -907,10 +993,9 @@ sbn_status launch_pack(int count, const PackItem *items, sbn_dtype wdt, const Pa
         if (fast) {
             for (int i = 0; i < n; ++i) tab.pack_block0[i] = fb[i];
             tab.pack_block0[n] = fb[n];
-            const PackSync none{};
-            if (pat.M == 4 && pat.N == 2) hipLaunchKernelGGL((pack_fast_kernel<2, 4, false>), dim3(fb[n]), dim3(256), 0, stream, tab, th, none);
-            else if (pat.M == 4) hipLaunchKernelGGL((pack_fast_kernel<1, 4, false>), dim3(fb[n]), dim3(256), 0, stream, tab, th, none);
-            else hipLaunchKernelGGL((pack_fast_kernel<2, 8, false>), dim3(fb[n]), dim3(256), 0, stream, tab, th, none);
+            if (pat.M == 4 && pat.N == 2) hipLaunchKernelGGL((pack_fast_kernel<2, 4>), dim3(fb[n]), dim3(256), 0, stream, tab, th);
+            else if (pat.M == 4) hipLaunchKernelGGL((pack_fast_kernel<1, 4>), dim3(fb[n]), dim3(256), 0, stream, tab, th);
+            else hipLaunchKernelGGL((pack_fast_kernel<2, 8>), dim3(fb[n]), dim3(256), 0, stream, tab, th);
             st = check_launch("pack_fast_kernel");
         } else {
             st = wdt == SBN_BF16 ? launch_pack_kernel<uint16_t>(tab, pb, th, vec_ok, pat, stream)
