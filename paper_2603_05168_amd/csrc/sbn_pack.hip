@@ -332,14 +332,14 @@ __device__ __forceinline__ Top2 top2_of4(uint32_t k0, uint32_t k1, uint32_t k2, 
     return t;
 }
 
-// What the blocks of the single-read form share through the workspace
-// Same-address device-scope atomics cost tens of nanoseconds each and serialise, so the ~1000 blocks of a
-// matrix arrive in two levels: block lb on the counter of group lb % 32, the last block of a group on the
-// matrix's top counter; the matrix's last block raises one ready word per group and the blocks of a
-// group poll theirs.  Every counter and ready word has a 64-byte line of its own.
+// What the blocks of the single-read form share through the workspace.
+// Same-address device-scope atomics serialise (one counter per matrix: 2.4 ms for the sweep instead of
+// 1.7), so the units of a matrix count themselves on 32 group counters (unit lb on counter lb % 32) and
+// the finalizing block raises one ready word per group, polled by the units of that group.  Every counter
+// and ready word has a 64-byte line of its own.
 constexpr int PACK_SYNC_GROUPS = 32;
 constexpr int PACK_SYNC_STRIDE = 16;                                            // words between two sync words
-constexpr int PACK_SYNC_WORDS = PACK_SYNC_STRIDE * (1 + 2 * PACK_SYNC_GROUPS);  // per matrix: top, group counters, ready words
+constexpr int PACK_SYNC_WORDS = PACK_SYNC_STRIDE * 2 * PACK_SYNC_GROUPS;        // per matrix: group counters, ready words
 struct PackSync {
     double *partials;     // one per block, as in the absmean pass
     float *theta;         // one per matrix
@@ -489,9 +489,10 @@ __global__ void __launch_bounds__(256) pack_fast_kernel(PackTable tab, const flo
 // ---- single-read form ---------------------------------------------------------------------------
 // Persistent blocks, as many as the device holds at once.  The units of the batch (16384 weights each,
 // matrix after matrix) are dealt round-robin: block b takes units b, b + B, b + 2B, ...  For every unit a
-// block loads the weights into registers, publishes their |w| sum and arrives on the matrix's two-level
-// counter; the block whose arrival completes a matrix adds the partials in the fixed order of the
-// finalize kernel, derives gamma and theta and raises the matrix's ready words (they carry theta).  A
+// block loads the weights into registers, publishes their |w| sum and counts itself on one of the matrix's
+// 32 group counters (fire and forget); the block that holds the matrix's first unit waits for the
+// counters, adds the partials in the fixed order of the finalize kernel, derives gamma and theta and
+// raises the matrix's ready words (they carry theta).  A
 // block packs a unit from its registers once the unit's matrix is ready - and before it waits for
 // that, it has already loaded and published its NEXT unit into a second set of registers, so the
 // hand-over of one matrix (four device-scope hops of about 1.5 us) runs under the loads of the
@@ -508,16 +509,15 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5, 5))
     constexpr int CBW = (M == 4 && N == 2) ? 8 : (M == 4 ? 4 : 5);
     __shared__ __attribute__((aligned(16))) uint32_t lds[PACK_U * 16 * CBW];
     __shared__ double red[256];
-    __shared__ int role_s;      // 1: this block's arrival completed the matrix, 2: waited in vain
+    __shared__ int role_s;      // 2: waited in vain
     __shared__ float th_s;
     const int tid = threadIdx.x;
     const int total_units = tab.pack_block0[tab.count];
     const int B = (int)gridDim.x;
 
-    struct Unit { int lo; int64_t lb; float theta; };   // theta != 0: already known to this block (it finalized the matrix)
-    auto sync_words = [&](int lo, unsigned *&top, unsigned *&grp, unsigned *&rdy) {
-        top = sync.words + (int64_t)lo * PACK_SYNC_WORDS;
-        grp = top + PACK_SYNC_STRIDE;
+    struct Unit { int lo; int64_t lb; };
+    auto sync_words = [&](int lo, unsigned *&grp, unsigned *&rdy) {
+        grp = sync.words + (int64_t)lo * PACK_SYNC_WORDS;
         rdy = grp + PACK_SYNC_STRIDE * PACK_SYNC_GROUPS;
     };
     // load unit g, publish its partial sum, finalize its matrix if this arrival completes it
@@ -525,7 +525,6 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5, 5))
         Unit un;
         un.lo = find_item(tab.pack_block0, tab.count, g);
         un.lb = g - tab.pack_block0[un.lo];
-        un.theta = 0.0f;
         const PackItem &it = tab.it[un.lo];
         load_unit(it, un.lb, v);
         double acc = 0.0;
@@ -534,9 +533,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5, 5))
         const double mine = block_sum(acc, red);
         const int nblk = tab.pack_block0[un.lo + 1] - tab.pack_block0[un.lo];
         unsigned long long *const part_bits = reinterpret_cast<unsigned long long *>(sync.partials + tab.sum_block0[un.lo]);
-        unsigned *top, *grp, *rdy;
-        sync_words(un.lo, top, grp, rdy);
-        const int ngroups = nblk < PACK_SYNC_GROUPS ? nblk : PACK_SYNC_GROUPS;
+        unsigned *grp, *rdy;
+        sync_words(un.lo, grp, rdy);
         const int mygroup = (int)(un.lb % PACK_SYNC_GROUPS);
         // Everything the blocks exchange (partials, theta, counters, ready words) moves through device-scope
         // atomic accesses, which are served where the eight L2s meet, and a block orders its own accesses by
@@ -546,41 +544,36 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5, 5))
             __hip_atomic_store(&part_bits[un.lb], (unsigned long long)__double_as_longlong(mine), __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_AGENT);
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the partial is in place before the arrival is counted
-            const int gsize = (nblk - mygroup + PACK_SYNC_GROUPS - 1) / PACK_SYNC_GROUPS;
-            int last = 0;
-            if (atomicAdd(&grp[PACK_SYNC_STRIDE * mygroup], 1u) == (unsigned)(gsize - 1))
-                last = atomicAdd(top, 1u) == (unsigned)(ngroups - 1);
-            role_s = last;
+            atomicAdd(&grp[PACK_SYNC_STRIDE * mygroup], 1u);     // nobody waits for its return
         }
-        __syncthreads();
-        if (role_s == 1) {
-            double a2 = 0.0;
-            for (int b = tid; b < nblk; b += 256)
-                a2 += __longlong_as_double((long long)__hip_atomic_load(&part_bits[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-            const double total = block_sum(a2, red);
-            if (tid == 0) {
-                float th;
-                *it.gamma = gamma_theta(total, it.d_out * it.d_in, th);
-                sync.theta[un.lo] = th;
-                th_s = th;
-            }
-            __syncthreads();
-            // the ready word of a group IS theta (its bit pattern is never zero: theta >= 0.5e-5)
-            if (tid < ngroups)
-                __hip_atomic_store(&rdy[PACK_SYNC_STRIDE * tid], __float_as_uint(th_s), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            un.theta = th_s;
-        }
-        __syncthreads();   // red, role_s and th_s are free again
+        __syncthreads();   // red is free again
         return un;
     };
     // theta of the unit's matrix: known, or polled from the group's ready word, or recomputed
+    // theta of the unit's matrix.  The block that holds the matrix's first unit finalizes it: it waits until
+    // every group counter is complete, adds the partials in the finalize order, writes gamma and raises the
+    // ready words; every other block polls its group's ready word.  Out of polls, either kind recomputes the
+    // partials from HBM (the finalizing block still publishes the result).
     auto theta_of = [&](const Unit &un) -> float {
-        if (un.theta != 0.0f) return un.theta;   // block-uniform
         const PackItem &it = tab.it[un.lo];
         const int nblk = tab.pack_block0[un.lo + 1] - tab.pack_block0[un.lo];
-        unsigned *top, *grp, *rdy;
-        sync_words(un.lo, top, grp, rdy);
-        if (tid == 0) {
+        const int ngroups = nblk < PACK_SYNC_GROUPS ? nblk : PACK_SYNC_GROUPS;
+        const bool finalizer = un.lb == 0;
+        unsigned *grp, *rdy;
+        sync_words(un.lo, grp, rdy);
+        if (tid == 0) role_s = 0;
+        __syncthreads();
+        if (finalizer) {
+            if (tid < ngroups) {
+                const unsigned want = (unsigned)((nblk - tid + PACK_SYNC_GROUPS - 1) / PACK_SYNC_GROUPS);
+                int spins = 0, ok = sync.spin_limit >= 0;
+                while (ok && __hip_atomic_load(&grp[PACK_SYNC_STRIDE * tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != want) {
+                    if (++spins > sync.spin_limit) ok = 0;
+                    else __builtin_amdgcn_s_sleep(4);
+                }
+                if (!ok) role_s = 2;   // several threads may write the same value
+            }
+        } else if (tid == 0) {
             int spins = 0, ok = sync.spin_limit >= 0;
             unsigned word = 0u;
             while (ok && (word = __hip_atomic_load(&rdy[PACK_SYNC_STRIDE * (un.lb % PACK_SYNC_GROUPS)], __ATOMIC_RELAXED,
@@ -588,11 +581,13 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5, 5))
                 if (++spins > sync.spin_limit) ok = 0;
                 else __builtin_amdgcn_s_sleep(4);
             }
-            role_s = ok ? 0 : 2;
+            if (!ok) role_s = 2;
             th_s = __uint_as_float(word);
         }
         __syncthreads();
-        if (role_s == 2) {
+        const bool alone = role_s == 2;
+        double total = 0.0;
+        if (alone) {
             // every partial sum of the matrix from HBM, added up in the finalize order: thread b % 256 takes partial b
             const int64_t total_chunks = it.d_out * (it.d_in / CHUNK);
             const uint16_t *W = static_cast<const uint16_t *>(it.W);
@@ -609,16 +604,31 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5, 5))
                 if ((b & 255) == tid) a2 += pb;
                 __syncthreads();   // red is reused by the next round
             }
-            const double total = block_sum(a2, red);
+            total = block_sum(a2, red);
+        } else if (finalizer) {
+            const unsigned long long *part_bits = reinterpret_cast<const unsigned long long *>(sync.partials + tab.sum_block0[un.lo]);
+            double a2 = 0.0;
+            for (int b = tid; b < nblk; b += 256)
+                a2 += __longlong_as_double((long long)__hip_atomic_load(&part_bits[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            total = block_sum(a2, red);
+        }
+        if (alone || finalizer) {
             if (tid == 0) {
                 float th;
-                gamma_theta(total, it.d_out * it.d_in, th);
+                const float g = gamma_theta(total, it.d_out * it.d_in, th);
+                if (finalizer) {
+                    *it.gamma = g;
+                    sync.theta[un.lo] = th;
+                }
                 th_s = th;
             }
             __syncthreads();
+            // the ready word of a group IS theta (its bit pattern is never zero: theta >= 0.5e-5)
+            if (finalizer && tid < ngroups)
+                __hip_atomic_store(&rdy[PACK_SYNC_STRIDE * tid], __float_as_uint(th_s), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         const float th = th_s;
-        __syncthreads();   // th_s may be rewritten by the next publication
+        __syncthreads();   // th_s, role_s and red may be rewritten by what follows
         return th;
     };
     auto pack = [&](const Unit &un, const uint4 (&v)[PACK_U]) {
