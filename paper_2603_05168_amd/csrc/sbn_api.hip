@@ -165,7 +165,11 @@ static sbn_status linear_one(const LinearItem &it_in, const Pattern &pat, sbn_pa
     int8_t *w_dense = reinterpret_cast<int8_t *>(ws + xq_bytes + sx_bytes);
 
     sbn_status st = SBN_OK;
-    if (it.X) st = launch_act_quant(it.X, it.tokens, it.d_in, it.xq, it.sx, stream);
+    // the decode path derives the quantized activations itself (inside its kernel when it can) unless the
+    // caller wants them back in its own buffers
+    const bool defer = path == SBN_PATH_GEMV && it.X && !it_in.xq && !it_in.sx;
+    it.quantized = !defer;
+    if (it.X && !defer) st = launch_act_quant(it.X, it.tokens, it.d_in, it.xq, it.sx, stream);
     if (st != SBN_OK) return st;
     if ((path == SBN_PATH_GEMV || path == SBN_PATH_SMFMAC) && !is24 && sparse_form) {
         // an instance of 2:4: the dense-weight region of the workspace takes its 2:4 operand form (a quarter of the size)
@@ -265,7 +269,8 @@ sbn_status sbn_sparse_ternary_linear_grouped(int count, const void *const *X, co
                 it.sx = tl_items[j].sx;
                 shared = true;
             }
-        if (!shared) {
+        it.quantized = !all_gemv;   // the decode path derives the quantized activations itself
+        if (!shared && !all_gemv) {
             sbn_status st = launch_act_quant(it.X, it.tokens, it.d_in, it.xq, it.sx, s);
             if (st != SBN_OK) return st;
         }

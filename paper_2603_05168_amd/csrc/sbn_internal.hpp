@@ -83,6 +83,7 @@ struct LinearItem {
     float *sx;            // fp32 [tokens]
     int32_t *acc_out;     // may be null
     int64_t tokens, d_in, d_out;
+    bool quantized = true;   // xq / sx already hold the quantized activations (false: launch_gemv derives them from X)
 };
 size_t linear_workspace_bytes(int64_t tokens, int64_t d_out, int64_t d_in);
 sbn_status launch_act_quant(const void *X, int64_t tokens, int64_t d_in, int8_t *xq, float *sx,

@@ -1,6 +1,11 @@
 // Forward of the N:M-sparse ternary linear layer: activation quantizer, decode GEMV, generic path.
 // Section 2.1 (per-token absmax int8 activations), Section 2.2 (forward-pass equation),
 // Appendix B listing (forward()).
+#include <algorithm>
+#include <atomic>
+#include <cstdlib>
+#include <vector>
+
 #include "sbn_internal.hpp"
 #include "sbn_mfma.hpp"
 
@@ -337,21 +342,103 @@ struct GemvStreamItem {
     const uint8_t *packed;
     const float *gamma;
     float *Y;
-    int d_in, d_out, tokens, pad;
+    int d_in, d_out, tokens;
+    int input;   // index into GemvStreamTable::in when the kernel quantizes the activations itself, else -1
+};
+// A distinct activation matrix of the call that the kernel quantizes itself: the first blocks of the
+// grid take one token row each (same arithmetic as the quantizer kernels), write the int8 row and its
+// scale to the workspace and raise a per-token flag; every block waits for the flags of an input, with
+// its first weight loads already in flight, before it stages that input - the quantizer then costs no
+// launch of its own.  Rows, scales and flags move through device-scope atomic accesses (served where
+// the eight L2s meet) ordered by waiting for the stores' acknowledgement: with release/acquire fences,
+// an L2 write-back or invalidation each, the same scheme was slower than the separate launch.
+// The wait is bounded: a block out of polls quantizes the rows itself into LDS (same result).
+struct GemvStreamInput {
+    const uint4 *X;              // bf16 [tokens, d_in]
+    unsigned long long *xq;      // workspace, int8 [tokens, d_in] as 8-byte words
+    unsigned *sx;                // workspace, fp32 bits [tokens]
+    unsigned long long *flags;   // workspace, one per token
+    int tokens, d_in;
 };
 constexpr int GEMV_STREAM_MAX = 64;
+constexpr int GEMV_STREAM_INPUTS = 4;
+constexpr int GEMV_QUANT_VEC = 4;    // 16-byte vectors of a row per thread when a block quantizes it
 struct GemvStreamTable {
     GemvStreamItem it[GEMV_STREAM_MAX];
     int unit0[GEMV_STREAM_MAX + 1];   // first unit of each problem
     int count;
+    GemvStreamInput in[GEMV_STREAM_INPUTS];
+    int tok0[GEMV_STREAM_INPUTS + 1]; // first producer block of each input
+    int nin;
+    unsigned epoch;                   // distinguishes this launch's flags from whatever the workspace held
+    int spin_limit;
 };
+static_assert(sizeof(GemvStreamTable) <= 4096, "the table travels as a kernel argument");
+
+__device__ __forceinline__ unsigned long long gemv_flag_value(unsigned epoch, int t)
+{
+    return ((unsigned long long)epoch << 32) | (0x5bd1e995u ^ (unsigned)t);
+}
 
 template <int RT, int DEPTH, int NW, bool DENSE>
 __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable tab)
 {
     extern __shared__ __attribute__((aligned(16))) int8_t xlds[];   // [tokens][d_in + 16]
     __shared__ int unit_ctr;                                        // next unit of the current problem nobody has taken
+    __shared__ float sx_lds[16];                                    // s_x of the staged tokens of a self-quantized input
+    __shared__ uint32_t wave_amax[NW];
+    __shared__ int stage_ok;
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // quantize token row t of an input with the whole block: to the workspace (publish) or to the LDS copy
+    auto quantize_row = [&](const GemvStreamInput &in, int t, int8_t *lds_row, bool publish) {
+        const int nvec = in.d_in / 8;
+        const uint4 *row = in.X + (int64_t)t * nvec;
+        uint4 v[GEMV_QUANT_VEC];
+        uint32_t m = 0;
+#pragma unroll
+        for (int i = 0; i < GEMV_QUANT_VEC; ++i) {
+            const int idx = threadIdx.x + i * 64 * NW;
+            v[i] = idx < nvec ? row[idx] : make_uint4(0, 0, 0, 0);
+            m = absmax_bits_bf16x8(v[i], m);
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            const uint32_t o = (uint32_t)__shfl_xor((int)m, off, 64);
+            m = o > m ? o : m;
+        }
+        __syncthreads();   // wave_amax is free again
+        if (lane == 0) wave_amax[wave] = m;
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < NW; ++w) m = wave_amax[w] > m ? wave_amax[w] : m;
+        const float s = scale_from_absmax_bits(m);
+        if (threadIdx.x == 0) {
+            if (publish) __hip_atomic_store(&in.sx[t], __float_as_uint(s), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            else sx_lds[t] = s;
+        }
+#pragma unroll
+        for (int i = 0; i < GEMV_QUANT_VEC; ++i) {
+            const int idx = threadIdx.x + i * 64 * NW;
+            if (idx >= nvec) continue;
+            const uint2 q = quantize_bf16x8(v[i], s);
+            if (publish)
+                __hip_atomic_store(&in.xq[(int64_t)t * nvec + idx], ((unsigned long long)q.y << 32) | q.x, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            else
+                reinterpret_cast<uint2 *>(lds_row)[idx] = q;
+        }
+    };
+    if ((int)blockIdx.x < tab.tok0[tab.nin]) {   // producer role: one token row of one input
+        int j = 0;
+        while ((int)blockIdx.x >= tab.tok0[j + 1]) ++j;
+        const GemvStreamInput &in = tab.in[j];
+        const int t = (int)blockIdx.x - tab.tok0[j];
+        quantize_row(in, t, nullptr, true);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's part of the row is in place ...
+        __syncthreads();
+        if (threadIdx.x == 0)                                // ... before the flag is raised
+            __hip_atomic_store(&in.flags[t], gemv_flag_value(tab.epoch, t), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     const int total = tab.unit0[tab.count];
     const int b0 = (int)((int64_t)total * blockIdx.x / gridDim.x), b1 = (int)((int64_t)total * (blockIdx.x + 1) / gridDim.x);
     const int r = lane & 15, c4 = lane >> 4;
@@ -415,14 +502,12 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
         // Activations are staged only when they differ from what the block already holds (projections
         // that share an input, Q/K/V or up/gate, come one after the other).
         const bool restage = it.xq != staged_xq || it.tokens != staged_tokens || K != staged_k;
-        if (restage) {
+        const bool self_quant = it.input >= 0;
+        if (restage && !self_quant) {
             for (int v = threadIdx.x; v < it.tokens * (K / 16); v += 64 * NW) {
                 const int t = v / (K / 16), k = (v % (K / 16)) * 16;
                 *reinterpret_cast<uint4 *>(&xlds[t * pitch + k]) = *reinterpret_cast<const uint4 *>(it.xq + (int64_t)t * K + k);
             }
-            staged_xq = it.xq;
-            staged_tokens = it.tokens;
-            staged_k = K;
         }
         __syncthreads();   // counter and activations in place
         if (dyn && lane == 0) grabbed = atomicAdd(&unit_ctr, 1);
@@ -430,7 +515,40 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) issue(qi[d], qc[d]);
         }
-        const float scale = tok_ok ? __fdiv_rn(*it.gamma, it.sx[r]) : 0.0f;
+        if (restage && self_quant) {
+            // the first weight loads are in flight; now wait (bounded) for the blocks that quantize this input
+            const GemvStreamInput &in = tab.in[it.input];
+            if (threadIdx.x == 0) stage_ok = 1;
+            __syncthreads();
+            if ((int)threadIdx.x < in.tokens) {
+                const unsigned long long want = gemv_flag_value(tab.epoch, threadIdx.x);
+                int spins = 0, ok = tab.spin_limit >= 0;
+                while (ok && __hip_atomic_load(&in.flags[threadIdx.x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != want) {
+                    if (++spins > tab.spin_limit) ok = 0;
+                    else __builtin_amdgcn_s_sleep(4);
+                }
+                if (!ok) stage_ok = 0;   // several lanes may write the same value
+            }
+            __syncthreads();
+            if (!stage_ok) {   // out of patience: quantize the rows here, straight into LDS (same arithmetic, same result)
+                for (int t = 0; t < in.tokens; ++t) quantize_row(in, t, xlds + t * pitch, false);
+            } else {
+                if ((int)threadIdx.x < in.tokens)
+                    sx_lds[threadIdx.x] = __uint_as_float(__hip_atomic_load(&in.sx[threadIdx.x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+                for (int v = threadIdx.x; v < in.tokens * (K / 8); v += 64 * NW) {
+                    const int t = v / (K / 8), k = (v % (K / 8)) * 8;
+                    const unsigned long long q = __hip_atomic_load(&in.xq[v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    *reinterpret_cast<uint2 *>(&xlds[t * pitch + k]) = make_uint2((uint32_t)q, (uint32_t)(q >> 32));
+                }
+            }
+            __syncthreads();
+        }
+        if (restage) {
+            staged_xq = it.xq;
+            staged_tokens = it.tokens;
+            staged_k = K;
+        }
+        const float scale = tok_ok ? __fdiv_rn(*it.gamma, self_quant ? sx_lds[r] : it.sx[r]) : 0.0f;
 
         v4i acc[RT];
 #pragma unroll
@@ -616,10 +734,32 @@ sbn_status launch_gemv(int count, const LinearItem *items, bool dense_codes, hip
     return dense_codes ? launch_gemv_as<true>(count, items, stream) : launch_gemv_as<false>(count, items, stream);
 }
 
+// Polls a block of the streaming kernel spends on the flags of an input before it quantizes the rows itself.
+// SBN_GEMV_SPIN_LIMIT overrides; negative: never look (the tests use it to exercise that branch).
+static int gemv_spin_limit()
+{
+    const char *e = getenv("SBN_GEMV_SPIN_LIMIT");
+    return e && *e ? atoi(e) : 1 << 16;
+}
+
 template <bool DENSE>
 static sbn_status launch_gemv_as(int count, const LinearItem *items, hipStream_t stream)
 {
     constexpr int RT = 2;
+    static std::atomic<unsigned> epoch{1};
+    static thread_local std::vector<const int8_t *> written;   // xq buffers a quantizer kernel of this call has filled
+    written.clear();
+    // quantizer launches for the problems first .. first + n - 1 that still need one (shared inputs once)
+    auto quantize_run = [&](int first, int n) -> sbn_status {
+        for (int i = 0; i < n; ++i) {
+            const LinearItem &li = items[first + i];
+            if (li.quantized || std::find(written.begin(), written.end(), li.xq) != written.end()) continue;
+            sbn_status st = launch_act_quant(li.X, li.tokens, li.d_in, li.xq, li.sx, stream);
+            if (st != SBN_OK) return st;
+            written.push_back(li.xq);
+        }
+        return SBN_OK;
+    };
     int first = 0;
     while (first < count) {
         // --- persistent streaming kernel when a run of problems holds enough rows to keep every block busy
@@ -635,23 +775,63 @@ static sbn_status launch_gemv_as(int count, const LinearItem *items, hipStream_t
         }
         // one block of NW wavefronts per multiprocessor, sharing one staged copy of the activations
         const int nblocks = device_cus();
-        constexpr int GEMV_STREAM_LDS = 160 * 1024 - 64;   // the kernel's unit counter takes a little static LDS
+        constexpr int GEMV_STREAM_LDS = 160 * 1024 - 256;   // the kernel's counter and scales take a little static LDS
         if (plain && lds_need <= GEMV_STREAM_LDS && units >= 16 * (int64_t)nblocks) {
+            // DEPTH 4 with 8 wavefronts per block measured best among depths 2..8 and 4..16 wavefronts
+            // (more wavefronts finish their shares further apart, fewer leave too few loads in flight)
+            constexpr int DEPTH = 4, NW = 8;
             GemvStreamTable tab;
             tab.count = n;
+            tab.nin = 0;
+            for (int j = 0; j <= GEMV_STREAM_INPUTS; ++j) tab.tok0[j] = 0;
+            // the kernel quantizes up to GEMV_STREAM_INPUTS distinct inputs itself; more than that (or rows too
+            // long for one block's registers) go through the quantizer kernel first
+            bool fuse = true;
+            int nin = 0;
+            const int8_t *in_xq[GEMV_STREAM_INPUTS];
+            for (int i = 0; i < n && fuse; ++i) {
+                const LinearItem &li = items[first + i];
+                if (li.quantized || std::find(written.begin(), written.end(), li.xq) != written.end()) continue;
+                if (li.d_in > 8 * GEMV_QUANT_VEC * 64 * NW || li.tokens > 16) { fuse = false; break; }
+                bool seen = false;
+                for (int j = 0; j < nin; ++j) seen = seen || in_xq[j] == li.xq;
+                if (seen) continue;
+                if (nin == GEMV_STREAM_INPUTS) { fuse = false; break; }
+                in_xq[nin++] = li.xq;
+            }
+            if (!fuse) {
+                sbn_status st = quantize_run(first, n);
+                if (st != SBN_OK) return st;
+                nin = 0;
+            }
             int u = 0;
             for (int i = 0; i < n; ++i) {
                 const LinearItem &li = items[first + i];
                 GemvStreamItem &g = tab.it[i];
                 g.xq = li.xq; g.sx = li.sx; g.packed = static_cast<const uint8_t *>(li.packed); g.gamma = li.gamma; g.Y = li.Y;
-                g.d_in = (int)li.d_in; g.d_out = (int)li.d_out; g.tokens = (int)li.tokens; g.pad = 0;
+                g.d_in = (int)li.d_in; g.d_out = (int)li.d_out; g.tokens = (int)li.tokens; g.input = -1;
+                for (int j = 0; j < nin; ++j)
+                    if (in_xq[j] == li.xq) {
+                        g.input = j;
+                        if (j == tab.nin) {   // first problem with this input: describe it
+                            GemvStreamInput &in = tab.in[j];
+                            in.X = static_cast<const uint4 *>(li.X);
+                            in.xq = reinterpret_cast<unsigned long long *>(li.xq);
+                            in.sx = reinterpret_cast<unsigned *>(li.sx);
+                            // the scales of at most 16 tokens fill 64 bytes of their 256-byte region; the flags take its second half
+                            in.flags = reinterpret_cast<unsigned long long *>(reinterpret_cast<uint8_t *>(li.sx) + 128);
+                            in.tokens = (int)li.tokens; in.d_in = (int)li.d_in;
+                            tab.tok0[j + 1] = tab.tok0[j] + in.tokens;
+                            ++tab.nin;
+                        }
+                    }
                 tab.unit0[i] = u;
                 u += (int)ceil_div(li.d_out, 16 * RT);
             }
             tab.unit0[n] = u;
-            // DEPTH 4 with 8 wavefronts per block measured best among depths 2..8 and 4..16 wavefronts
-            // (more wavefronts finish their shares further apart, fewer leave too few loads in flight)
-            constexpr int DEPTH = 4, NW = 8;
+            for (int j = tab.nin; j < GEMV_STREAM_INPUTS; ++j) tab.tok0[j + 1] = tab.tok0[tab.nin];
+            tab.epoch = epoch.fetch_add(1, std::memory_order_relaxed);
+            tab.spin_limit = gemv_spin_limit();
             static thread_local bool raised = false;
             if (!raised) {
                 hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemv_stream_kernel<RT, DEPTH, NW, DENSE>),
@@ -667,6 +847,10 @@ static sbn_status launch_gemv_as(int count, const LinearItem *items, hipStream_t
         }
         // --- otherwise: one block per 16 rows, wavefronts split the input dimension (lowest latency)
         n = count - first < GEMV_MAX_ITEMS ? count - first : GEMV_MAX_ITEMS;
+        {
+            sbn_status st = quantize_run(first, n);
+            if (st != SBN_OK) return st;
+        }
         GemvTable tab;
         int blocks = 0, max_super = 1;
         for (int i = 0; i < n; ++i) {

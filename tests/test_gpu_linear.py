@@ -268,11 +268,16 @@ def test_sparse_and_dense_paths_agree_bitwise_full_size():
     assert np.array_equal(acca, accb) and np.array_equal(Ya, Yb)
 
 
+@pytest.mark.parametrize("spin_limit", [None, "-1", "0"])
 @pytest.mark.parametrize("tokens", [1, 8, 16])
-def test_grouped_streaming_gemv_against_oracle(tokens):
+def test_grouped_streaming_gemv_against_oracle(tokens, spin_limit, monkeypatch):
     # enough rows in one grouped call to take the persistent streaming kernel; shapes with ragged
-    # row counts and a partial last super-step (K = 768 = 6 chunks)
+    # row counts and a partial last super-step (K = 768 = 6 chunks).  The kernel quantizes the three
+    # inputs itself: its first blocks publish the rows, the others wait for them; spin limit -1 makes
+    # every block quantize for itself without looking, 0 allows one look (either branch may run)
     s = sbn()
+    if spin_limit is not None:
+        monkeypatch.setenv("SBN_GEMV_SPIN_LIMIT", spin_limit)
     shapes = [(4100, 768), (4096, 256), (5000, 640)] * 14
     Ws = {sh: sbn_synth.latent_weight(sh[0], sh[1], 650 + sh[0]) for sh in set(shapes)}
     packs = {sh: hip_pack(W, 2, 4) for sh, W in Ws.items()}
