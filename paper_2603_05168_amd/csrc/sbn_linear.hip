@@ -244,12 +244,14 @@ struct GemvItem {
     const float *bias;
     float *Y;
     int32_t *acc_out;
+    const uint4 *X;   // bf16 activations when the block quantizes them itself (then xq and sx are unused), else null
     int d_in, d_out, tokens, pad;
 };
-constexpr int GEMV_MAX_ITEMS = 48;
+constexpr int GEMV_MAX_ITEMS = 40;
 struct GemvTable {
     GemvItem it[GEMV_MAX_ITEMS];   // problem = blockIdx.y; row tile = blockIdx.x (surplus blocks exit at once)
 };
+static_assert(sizeof(GemvTable) <= 4096, "the table travels as a kernel argument");
 
 // DENSE = true is the same kernel for weights stored as dense 2-bit codes (the packed form of
 // N = M, and what other patterns are rewritten to for decode): a chunk is eight code words, every
@@ -258,7 +260,10 @@ struct GemvTable {
 template <bool DENSE>
 __global__ void __launch_bounds__(1024) gemv_smfmac_kernel(GemvTable tab)
 {
+    extern __shared__ __attribute__((aligned(16))) int8_t xs[];   // self-quantized activations [tokens][d_in + 16]
     __shared__ v4i red[16][64];
+    __shared__ uint32_t amax_s[16][16];   // [token][wavefront]
+    __shared__ float sx_s[16];
     const GemvItem &it = tab.it[blockIdx.y];
     const int row0 = (int)blockIdx.x * 16;
     if (row0 >= it.d_out) return;
@@ -270,22 +275,57 @@ __global__ void __launch_bounds__(1024) gemv_smfmac_kernel(GemvTable tab)
     row = row < it.d_out ? row : it.d_out - 1;   // rows past the end are computed and dropped
     const uint8_t *wrow = it.packed + (int64_t)row * nchunks * 32;
     const bool tok_ok = r < it.tokens;           // as B operand the lane holds token r
-    const int8_t *xrow = it.xq + (int64_t)(tok_ok ? r : 0) * K;
+    const bool self_quant = it.X != nullptr;
+    const int pitch = K + 16;
+    const int8_t *xrow = self_quant ? xs + (tok_ok ? r : 0) * pitch : it.xq + (int64_t)(tok_ok ? r : 0) * K;
 
-    v4i acc = {0, 0, 0, 0};
-    for (int s = wave; s < nsuper; s += nwaves) {
+    // the wavefront's first weight words go out before anything else: they fly while the block quantizes
+    uint4 idx4 = make_uint4(0, 0, 0, 0), code4 = make_uint4(0, 0, 0, 0);
+    auto fetch = [&](int s) {
         const int chunk = 4 * s + c4;
-        uint4 idx4 = make_uint4(0, 0, 0, 0), code4 = make_uint4(0, 0, 0, 0);
-        if (chunk < nchunks) {
+        idx4 = make_uint4(0, 0, 0, 0);
+        code4 = make_uint4(0, 0, 0, 0);
+        if (s < nsuper && chunk < nchunks) {
             idx4 = *reinterpret_cast<const uint4 *>(wrow + (int64_t)chunk * 32);
             code4 = *reinterpret_cast<const uint4 *>(wrow + (int64_t)chunk * 32 + 16);
         }
+    };
+    fetch(wave);
+    if (self_quant) {
+        // every block quantizes the few token rows itself (the quantizer's arithmetic), saving the quantizer's
+        // launch in front of a latency-bound call: pass 1 per-token maxima, pass 2 int8 rows into LDS
+        const int nvec = K / 8, nthreads = (int)blockDim.x;
+        for (int t = 0; t < it.tokens; ++t) {
+            uint32_t m = 0;
+            for (int idx = threadIdx.x; idx < nvec; idx += nthreads) m = absmax_bits_bf16x8(it.X[(int64_t)t * nvec + idx], m);
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) {
+                const uint32_t o = (uint32_t)__shfl_xor((int)m, off, 64);
+                m = o > m ? o : m;
+            }
+            if (lane == 0) amax_s[t][wave] = m;
+        }
+        __syncthreads();
+        for (int t = 0; t < it.tokens; ++t) {
+            uint32_t m = 0;
+            for (int w = 0; w < nwaves; ++w) m = amax_s[t][w] > m ? amax_s[t][w] : m;
+            const float sc = scale_from_absmax_bits(m);
+            if (threadIdx.x == 0) sx_s[t] = sc;
+            for (int idx = threadIdx.x; idx < nvec; idx += nthreads)
+                *reinterpret_cast<uint2 *>(xs + t * pitch + idx * 8) = quantize_bf16x8(it.X[(int64_t)t * nvec + idx], sc);
+        }
+        __syncthreads();
+    }
+
+    v4i acc = {0, 0, 0, 0};
+    for (int s = wave; s < nsuper; s += nwaves) {
         const uint32_t idxw[4] = {idx4.x, idx4.y, idx4.z, idx4.w};
         const uint32_t codew[4] = {code4.x, code4.y, code4.z, code4.w};
+        fetch(s + nwaves);   // the next super-step of this wavefront (zeros past the end)
         // B operand: elements 0..15 pair with the A lanes of quarters 0/1, elements 16..31 with
         // quarters 2/3 (measured operand layout of the instruction)
         if constexpr (DENSE) {
-            const uint32_t w8[8] = {idx4.x, idx4.y, idx4.z, idx4.w, code4.x, code4.y, code4.z, code4.w};
+            const uint32_t w8[8] = {idxw[0], idxw[1], idxw[2], idxw[3], codew[0], codew[1], codew[2], codew[3]};
             const int kd = s * 512 + 128 * c4;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
@@ -314,7 +354,7 @@ __global__ void __launch_bounds__(1024) gemv_smfmac_kernel(GemvTable tab)
         // D layout: lane holds token (lane % 16), rows 4 * (lane / 16) + i
         const int tok = lane & 15, rbase = row0 + 4 * (lane >> 4);
         if (tok < it.tokens) {
-            const float scale = __fdiv_rn(*it.gamma, it.sx[tok]);
+            const float scale = __fdiv_rn(*it.gamma, self_quant ? sx_s[tok] : it.sx[tok]);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int o = rbase + i;
@@ -711,6 +751,7 @@ static void fill_gemv_item(GemvItem &g, const LinearItem &li)
     g.xq = li.xq; g.sx = li.sx; g.packed = static_cast<const uint8_t *>(li.packed);
     g.gamma = li.gamma; g.bias = li.bias; g.Y = li.Y; g.acc_out = li.acc_out;
     g.d_in = (int)li.d_in; g.d_out = (int)li.d_out; g.tokens = (int)li.tokens; g.pad = 0;
+    g.X = nullptr;
 }
 
 // multiprocessors of the current device (cached per thread)
@@ -847,15 +888,33 @@ static sbn_status launch_gemv_as(int count, const LinearItem *items, hipStream_t
         }
         // --- otherwise: one block per 16 rows, wavefronts split the input dimension (lowest latency)
         n = count - first < GEMV_MAX_ITEMS ? count - first : GEMV_MAX_ITEMS;
-        {
+        // the blocks quantize the activations themselves when a problem has few tokens (measured at 6912 x 2560 and
+        // 2560 x 6912: 9.0-10.3 us for 1-4 tokens against 12 us with the quantizer launched in front; at 8
+        // tokens the per-token passes of every block cost more than the launch they save: 13-16 us)
+        constexpr int64_t GEMV_SELF_QUANT_LDS = 112 * 1024;
+        constexpr int64_t GEMV_SELF_QUANT_TOKENS = 4;
+        int64_t dyn_lds = 0;
+        bool self_quant = true;
+        for (int i = 0; i < n; ++i) {
+            const LinearItem &li = items[first + i];
+            if (li.quantized) continue;
+            const int64_t b = li.tokens * (li.d_in + 16);
+            if (b > GEMV_SELF_QUANT_LDS || li.tokens > GEMV_SELF_QUANT_TOKENS ||
+                std::find(written.begin(), written.end(), li.xq) != written.end())
+                self_quant = false;
+            dyn_lds = b > dyn_lds ? b : dyn_lds;
+        }
+        if (!self_quant) {
             sbn_status st = quantize_run(first, n);
             if (st != SBN_OK) return st;
+            dyn_lds = 0;
         }
         GemvTable tab;
         int blocks = 0, max_super = 1;
         for (int i = 0; i < n; ++i) {
             const LinearItem &li = items[first + i];
             fill_gemv_item(tab.it[i], li);
+            if (self_quant && !li.quantized) tab.it[i].X = static_cast<const uint4 *>(li.X);
             const int nb = (int)ceil_div(li.d_out, 16);
             blocks = nb > blocks ? nb : blocks;
             const int nsuper = (int)ceil_div(li.d_in / CHUNK, 4);
@@ -863,7 +922,16 @@ static sbn_status launch_gemv_as(int count, const LinearItem *items, hipStream_t
         }
         // one wavefront per super-step up to 16, so that every wavefront has loads in flight at once
         const int nwaves = max_super < 16 ? max_super : 16;
-        hipLaunchKernelGGL(gemv_smfmac_kernel<DENSE>, dim3(blocks, n), dim3(64 * nwaves), 0, stream, tab);
+        if (dyn_lds > 0) {
+            static thread_local bool raised_single = false;
+            if (!raised_single) {
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemv_smfmac_kernel<DENSE>),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)GEMV_SELF_QUANT_LDS);
+                if (e != hipSuccess) { set_hip_error(e, "hipFuncSetAttribute"); return SBN_EHIP; }
+                raised_single = true;
+            }
+        }
+        hipLaunchKernelGGL(gemv_smfmac_kernel<DENSE>, dim3(blocks, n), dim3(64 * nwaves), (size_t)dyn_lds, stream, tab);
         sbn_status st = check_launch("gemv_smfmac_kernel");
         if (st != SBN_OK) return st;
         first += n;
