@@ -332,18 +332,18 @@ __device__ __forceinline__ Top2 top2_of4(uint32_t k0, uint32_t k1, uint32_t k2, 
     return t;
 }
 
-// What the blocks of the single-read form share through the workspace.
-// Same-address device-scope atomics serialise (one counter per matrix: 2.4 ms for the sweep instead of
-// 1.7), so the units of a matrix count themselves on 32 group counters (unit lb on counter lb % 32) and
-// the finalizing block raises one ready word per group, polled by the units of that group.  Every counter
-// and ready word has a 64-byte line of its own.
+// What the blocks of the single-read form share through the workspace: the partial sums (one slot per
+// unit, preset to a pattern no sum can have, so that a slot's value is also the sign that the unit has
+// arrived) and, per matrix, 32 ready words (unit lb polls word lb % 32: same-address device-scope accesses
+// serialise, a single word per matrix cost 40 % of the sweep).  Every ready word has a 64-byte line of its own.
 constexpr int PACK_SYNC_GROUPS = 32;
-constexpr int PACK_SYNC_STRIDE = 16;                                            // words between two sync words
-constexpr int PACK_SYNC_WORDS = PACK_SYNC_STRIDE * 2 * PACK_SYNC_GROUPS;        // per matrix: group counters, ready words
+constexpr int PACK_SYNC_STRIDE = 16;                                       // words between two ready words
+constexpr int PACK_SYNC_WORDS = PACK_SYNC_STRIDE * PACK_SYNC_GROUPS;       // per matrix
+constexpr unsigned long long PACK_NO_PARTIAL = ~0ull;                      // a NaN pattern: sums of |w| are finite
 struct PackSync {
     double *partials;     // one per block, as in the absmean pass
     float *theta;         // one per matrix
-    unsigned *words;      // PACK_SYNC_WORDS per matrix, cleared before the launch
+    unsigned *words;      // PACK_SYNC_WORDS per matrix, cleared before the launch (the partials are preset with them)
     int spin_limit;       // polls a block spends waiting for its ready word before it derives theta on its own
 };
 
@@ -489,10 +489,10 @@ __global__ void __launch_bounds__(256) pack_fast_kernel(PackTable tab, const flo
 // ---- single-read form ---------------------------------------------------------------------------
 // Persistent blocks, as many as the device holds at once.  The units of the batch (16384 weights each,
 // matrix after matrix) are dealt round-robin: block b takes units b, b + B, b + 2B, ...  For every unit a
-// block loads the weights into registers, publishes their |w| sum and counts itself on one of the matrix's
-// 32 group counters (fire and forget); the block that holds the matrix's first unit waits for the
-// counters, adds the partials in the fixed order of the finalize kernel, derives gamma and theta and
-// raises the matrix's ready words (they carry theta).  A
+// block loads the weights into registers and publishes their |w| sum (one store, fire and forget); the block
+// that holds the matrix's first unit waits until every partial slot of the matrix is filled, adds them in
+// the fixed order of the finalize kernel, derives gamma and theta and raises the matrix's ready words
+// (they carry theta).  A
 // block packs a unit from its registers once the unit's matrix is ready - and before it waits for
 // that, it has already loaded and published its NEXT unit into a second set of registers, so the
 // hand-over of one matrix (four device-scope hops of about 1.5 us) runs under the loads of the
@@ -516,10 +516,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5, 5))
     const int B = (int)gridDim.x;
 
     struct Unit { int lo; int64_t lb; };
-    auto sync_words = [&](int lo, unsigned *&grp, unsigned *&rdy) {
-        grp = sync.words + (int64_t)lo * PACK_SYNC_WORDS;
-        rdy = grp + PACK_SYNC_STRIDE * PACK_SYNC_GROUPS;
-    };
+    auto ready_words = [&](int lo) { return sync.words + (int64_t)lo * PACK_SYNC_WORDS; };
     // load unit g, publish its partial sum, finalize its matrix if this arrival completes it
     auto load_publish = [&](int g, uint4 (&v)[PACK_U]) -> Unit {
         Unit un;
@@ -531,27 +528,19 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5, 5))
 #pragma unroll
         for (int u = 0; u < PACK_U; ++u) acc = abs8(v[u], acc);
         const double mine = block_sum(acc, red);
-        const int nblk = tab.pack_block0[un.lo + 1] - tab.pack_block0[un.lo];
         unsigned long long *const part_bits = reinterpret_cast<unsigned long long *>(sync.partials + tab.sum_block0[un.lo]);
-        unsigned *grp, *rdy;
-        sync_words(un.lo, grp, rdy);
-        const int mygroup = (int)(un.lb % PACK_SYNC_GROUPS);
-        // Everything the blocks exchange (partials, theta, counters, ready words) moves through device-scope
-        // atomic accesses, which are served where the eight L2s meet, and a block orders its own accesses by
-        // waiting for the store to be acknowledged.  Release/acquire fences would do the same with a cache
+        // Everything the blocks exchange (partials, ready words) moves through device-scope atomic accesses,
+        // which are served where the eight L2s meet.  Release/acquire fences would do the same with a cache
         // write-back or invalidation each, a thousand per matrix (measured: 43 us per matrix).
-        if (tid == 0) {
+        if (tid == 0)
             __hip_atomic_store(&part_bits[un.lb], (unsigned long long)__double_as_longlong(mine), __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_AGENT);
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the partial is in place before the arrival is counted
-            atomicAdd(&grp[PACK_SYNC_STRIDE * mygroup], 1u);     // nobody waits for its return
-        }
         __syncthreads();   // red is free again
         return un;
     };
     // theta of the unit's matrix: known, or polled from the group's ready word, or recomputed
     // theta of the unit's matrix.  The block that holds the matrix's first unit finalizes it: it waits until
-    // every group counter is complete, adds the partials in the finalize order, writes gamma and raises the
+    // every partial slot is filled, adds the partials in the finalize order, writes gamma and raises the
     // ready words; every other block polls its group's ready word.  Out of polls, either kind recomputes the
     // partials from HBM (the finalizing block still publishes the result).
     auto theta_of = [&](const Unit &un) -> float {
@@ -559,20 +548,23 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5, 5))
         const int nblk = tab.pack_block0[un.lo + 1] - tab.pack_block0[un.lo];
         const int ngroups = nblk < PACK_SYNC_GROUPS ? nblk : PACK_SYNC_GROUPS;
         const bool finalizer = un.lb == 0;
-        unsigned *grp, *rdy;
-        sync_words(un.lo, grp, rdy);
+        unsigned *const rdy = ready_words(un.lo);
+        const unsigned long long *const part_bits =
+            reinterpret_cast<const unsigned long long *>(sync.partials + tab.sum_block0[un.lo]);
         if (tid == 0) role_s = 0;
         __syncthreads();
+        double a2 = 0.0;   // finalizer: this thread's share of the partials, in the finalize order
         if (finalizer) {
-            if (tid < ngroups) {
-                const unsigned want = (unsigned)((nblk - tid + PACK_SYNC_GROUPS - 1) / PACK_SYNC_GROUPS);
-                int spins = 0, ok = sync.spin_limit >= 0;
-                while (ok && __hip_atomic_load(&grp[PACK_SYNC_STRIDE * tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != want) {
-                    if (++spins > sync.spin_limit) ok = 0;
-                    else __builtin_amdgcn_s_sleep(4);
+            int spins = 0, ok = sync.spin_limit >= 0;
+            for (int b = tid; b < nblk && ok; b += 256) {
+                unsigned long long bits;
+                while ((bits = __hip_atomic_load(&part_bits[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) == PACK_NO_PARTIAL) {
+                    if (++spins > sync.spin_limit) { ok = 0; break; }
+                    __builtin_amdgcn_s_sleep(4);
                 }
-                if (!ok) role_s = 2;   // several threads may write the same value
+                if (ok) a2 += __longlong_as_double((long long)bits);
             }
+            if (!ok) role_s = 2;   // several threads may write the same value
         } else if (tid == 0) {
             int spins = 0, ok = sync.spin_limit >= 0;
             unsigned word = 0u;
@@ -592,7 +584,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5, 5))
             const int64_t total_chunks = it.d_out * (it.d_in / CHUNK);
             const uint16_t *W = static_cast<const uint16_t *>(it.W);
             const int ql = tid >> 4, l16 = tid & 15;
-            double a2 = 0.0;
+            double a3 = 0.0;
             for (int b = 0; b < nblk; ++b) {
                 double pa = 0.0;
 #pragma unroll
@@ -601,15 +593,11 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5, 5))
                     if (q < total_chunks) pa = abs8(*reinterpret_cast<const uint4 *>(W + q * CHUNK + l16 * 8), pa);
                 }
                 const double pb = block_sum(pa, red);
-                if ((b & 255) == tid) a2 += pb;
+                if ((b & 255) == tid) a3 += pb;
                 __syncthreads();   // red is reused by the next round
             }
-            total = block_sum(a2, red);
+            total = block_sum(a3, red);
         } else if (finalizer) {
-            const unsigned long long *part_bits = reinterpret_cast<const unsigned long long *>(sync.partials + tab.sum_block0[un.lo]);
-            double a2 = 0.0;
-            for (int b = tid; b < nblk; b += 256)
-                a2 += __longlong_as_double((long long)__hip_atomic_load(&part_bits[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
             total = block_sum(a2, red);
         }
         if (alone || finalizer) {
@@ -896,10 +884,11 @@ size_t pack_workspace_bytes(int64_t count, int64_t d_out, int64_t d_in)
            align_up((size_t)count * PACK_SYNC_WORDS * sizeof(unsigned), 256);
 }
 
-__global__ void __launch_bounds__(256) pack_sync_clear_kernel(unsigned *words, int n)
+__global__ void __launch_bounds__(256) pack_sync_clear_kernel(unsigned *words, int nwords, unsigned long long *partials, int npartials)
 {
     const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i < n) words[i] = 0u;
+    if (i < nwords) words[i] = 0u;
+    if (i < npartials) partials[i] = PACK_NO_PARTIAL;
 }
 
 // blocks of the single-read pack kernel the device holds at once = its grid (per instantiation, cached per thread)
@@ -977,8 +966,9 @@ sbn_status launch_pack(int count, const PackItem *items, sbn_dtype wdt, const Pa
             for (int i = 0; i < n; ++i) tab.pack_block0[i] = fb[i];
             tab.pack_block0[n] = fb[n];
             unsigned *words = sync_words + (size_t)PACK_SYNC_WORDS * first;
-            hipLaunchKernelGGL(pack_sync_clear_kernel, dim3((n * PACK_SYNC_WORDS + 255) / 256), dim3(256), 0, stream, words,
-                               n * PACK_SYNC_WORDS);
+            const int nclear = n * PACK_SYNC_WORDS > sb ? n * PACK_SYNC_WORDS : sb;
+            hipLaunchKernelGGL(pack_sync_clear_kernel, dim3((nclear + 255) / 256), dim3(256), 0, stream, words, n * PACK_SYNC_WORDS,
+                               reinterpret_cast<unsigned long long *>(part), sb);
             st = check_launch("pack_sync_clear_kernel");
             if (st != SBN_OK) return st;
             PackSync sync{part, th, words, pack_spin_limit()};
