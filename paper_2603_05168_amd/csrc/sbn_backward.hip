@@ -172,6 +172,83 @@ struct GemmBf16Args {
     int mask_wpr;
 };
 
+// Tile order.  Blocks go to the eight XCDs round-robin and every XCD has its own L2, so XCD x takes
+// a contiguous eighth of an order in which consecutive tiles form compact rectangles: super-tiles of
+// 8 x 8 tiles (3072 operand rows for 64 tiles instead of up to all of them), bands of eight tile rows,
+// super-tiles left to right in a band, the row index fastest inside a super-tile.  With plain row-major
+// order the L2s missed on two thirds of their requests.  bid = block index inside the product's
+// range; returns false for the blocks that pad the range to a multiple of eight.
+__device__ __forceinline__ bool bf16_tile_of_block(const GemmBf16Args &g, int bid, int &tn, int &tm)
+{
+    const int nb = g.tiles_n * g.tiles_m;
+    const int per = (nb + 7) >> 3;
+    const int id = (bid & 7) * per + (bid >> 3);
+    if ((bid >> 3) >= per || id >= nb) return false;
+    const int band_tiles = 8 * g.tiles_n;
+    const int nbands = (g.tiles_m + 7) >> 3;
+    int band = id / band_tiles;
+    band = band < nbands - 1 ? band : nbands - 1;
+    const int h = band == nbands - 1 ? g.tiles_m - 8 * band : 8;      // tile rows of this band
+    const int rem = id - band * band_tiles;
+    const int ncols = (g.tiles_n + 7) >> 3;
+    int col = rem / (8 * h);
+    col = col < ncols - 1 ? col : ncols - 1;
+    const int rem2 = rem - col * 8 * h;
+    tn = 8 * col + rem2 / h;
+    tm = 8 * band + rem2 % h;
+    return true;
+}
+
+// Result of a wavefront: 4 x 2 tiles of 32 x 32 at rows (of C) mw + 32 b + .., columns nw + 32 a + ..;
+// tile (a, b): lane holds m = column r, n = rows 8q + 4c + i: four consecutive n of one C row per store.
+__device__ __forceinline__ void bf16_wave_epilogue(const GemmBf16Args &g, const v16f (&acc)[4][2], int nw, int mw, int lane)
+{
+    const int r = lane & 31, c = lane >> 5;
+    const float alpha = g.alpha ? *g.alpha : 1.0f;
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+        const int m = mw + 32 * b + r;
+        if (m >= g.M) continue;
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int n = nw + 32 * a + 8 * q + 4 * c;
+                uint16_t *dst = g.C + (int64_t)m * g.ldc + n;
+                float v[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] = acc[a][b][4 * q + i] * alpha;
+                if (g.mask && n < g.N) {   // n is a multiple of 4: its four mask bits sit in one word
+                    const uint32_t mb = g.mask[(int64_t)m * g.mask_wpr + (n >> 5)] >> (n & 31);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) v[i] = (mb >> i) & 1u ? v[i] : 0.0f;
+                }
+                if (n + 4 <= g.N && (g.ldc & 3) == 0) {
+                    if (g.accumulate) {
+                        const uint2 old = *reinterpret_cast<const uint2 *>(dst);
+                        v[0] += __uint_as_float(old.x << 16);
+                        v[1] += __uint_as_float(old.x & 0xffff0000u);
+                        v[2] += __uint_as_float(old.y << 16);
+                        v[3] += __uint_as_float(old.y & 0xffff0000u);
+                    }
+                    uint2 out;
+                    out.x = f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16);
+                    out.y = f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16);
+                    *reinterpret_cast<uint2 *>(dst) = out;
+                } else {
+                    for (int i = 0; i < 4; ++i) {
+                        if (n + i < g.N) {
+                            float x = v[i];
+                            if (g.accumulate) x += __uint_as_float((uint32_t)dst[i] << 16);
+                            dst[i] = (uint16_t)f32_to_bf16(x);
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
 // Up to two products share one launch (dW and dX of a layer): the block index space is the
 // concatenation of their tiles, the product with the longer contraction first, so that the short
 // tiles of the second fill the multiprocessors the first leaves idle in its last round (dW of a
@@ -189,28 +266,8 @@ __global__ void __launch_bounds__(256, 2) gemm_bf16_nt_kernel(GemmBf16Group grp)
     __shared__ __attribute__((aligned(16))) uint8_t ldsQ[GB_M * GROW];
     const int prob = (grp.count > 1 && (int)blockIdx.x >= grp.block0[1]) ? 1 : 0;
     const GemmBf16Args &g = grp.g[prob];
-    const int nb = g.tiles_n * g.tiles_m;
-    // Tile order.  Blocks go to the eight XCDs round-robin and every XCD has its own L2, so XCD x takes
-    // a contiguous eighth of an order in which consecutive tiles form compact rectangles: super-tiles of
-    // 8 x 8 tiles (the 64 blocks an XCD holds at a time: 3072 operand rows for 64 tiles instead of up to
-    // all of them), bands of eight tile rows, super-tiles left to right in a band, the row index fastest
-    // inside a super-tile.  With plain row-major order the L2s missed on two thirds of their requests
-    // and the miss traffic (4.5 to 7 TB/s) bounded the kernel.
-    const int bid = (int)blockIdx.x - grp.block0[prob];
-    const int per = (nb + 7) >> 3;
-    const int id = (bid & 7) * per + (bid >> 3);
-    if ((bid >> 3) >= per || id >= nb) return;   // padding of the range to a multiple of eight
-    const int band_tiles = 8 * g.tiles_n;
-    const int nbands = (g.tiles_m + 7) >> 3;
-    int band = id / band_tiles;
-    band = band < nbands - 1 ? band : nbands - 1;
-    const int h = band == nbands - 1 ? g.tiles_m - 8 * band : 8;      // tile rows of this band
-    const int rem = id - band * band_tiles;
-    const int ncols = (g.tiles_n + 7) >> 3;
-    int col = rem / (8 * h);
-    col = col < ncols - 1 ? col : ncols - 1;
-    const int rem2 = rem - col * 8 * h;
-    const int tn = 8 * col + rem2 / h, tm = 8 * band + rem2 % h;
+    int tn, tm;
+    if (!bf16_tile_of_block(g, (int)blockIdx.x - grp.block0[prob], tn, tm)) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wn = wave & 1, wm = wave >> 1;
     const int r = lane & 31, c = lane >> 5;
@@ -309,50 +366,120 @@ __global__ void __launch_bounds__(256, 2) gemm_bf16_nt_kernel(GemmBf16Group grp)
     }
     multiply_tile();                   // last step: nothing left to fetch
 
-    // result tile (a, b): lane holds m = column r, n = rows 8q + 4c + i
-    const float alpha = g.alpha ? *g.alpha : 1.0f;
+    bf16_wave_epilogue(g, acc, n0 + wn * 128, m0 + wm * 64, lane);
+}
+
+// ---- the same product with the operands streamed into LDS by the DMA path --------------------------
+// Timing-only ablations of the kernel above (2 x 2 wavefronts, register prefetch, one LDS buffer): LDS
+// reads + matrix instructions alone run at 86 % of what the board sustains; the global-load ->
+// register -> LDS-store path costs the rest (the scheduler sinks the loads to the end of a k step to
+// save registers, and forcing them early costs the LDS read-ahead instead).  Here no operand touches a
+// register on its way in: block tile 256 (n) x 256 (m), 512 threads = 2 x 4 wavefronts of 128 x 64 (one
+// block per multiprocessor, two wavefronts per SIMD), two LDS stages of 64 k (128-byte rows, 64 KB per
+// stage), each wavefront issues eight LDS-DMA loads for the next stage before it multiplies the
+// current one; one barrier per k step.  The 16-byte column of a row is XOR-swizzled with row & 7 (on
+// the global side of the DMA, which deposits lane l at base + 16 l), so the 32 rows x 2 columns of an
+// operand read spread over all banks.  Needs K % 64 == 0 (no partial rows in a stage).
+// The matrix pipe still waits for the DMA about a third of the time: 64 KB in flight per multiprocessor
+// cover about one microsecond.  A ring of four stages of 32 k (96 KB in flight, 64-byte rows, twice the
+// barriers) was measured slower (backward of the block 5.96 against 5.43 ms).
+constexpr int GD_N = 256, GD_M = 256, GD_K = 64;
+constexpr int GD_STAGE = (GD_N + GD_M) * GD_K * 2;   // 64 KB
+constexpr int GD_LDS = 2 * GD_STAGE;
+
+__global__ void __launch_bounds__(512) gemm_bf16_dma_kernel(GemmBf16Group grp)
+{
+    extern __shared__ __attribute__((aligned(1024))) uint8_t dlds[];
+    const int prob = (grp.count > 1 && (int)blockIdx.x >= grp.block0[1]) ? 1 : 0;
+    const GemmBf16Args &g = grp.g[prob];
+    int tn, tm;
+    if (!bf16_tile_of_block(g, (int)blockIdx.x - grp.block0[prob], tn, tm)) return;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wn = wave & 1, wm = wave >> 1;
+    const int r = lane & 31, c = lane >> 5;
+    const int n0 = tn * GD_N, m0 = tm * GD_M;
+    const uint32_t lds0 = lds_address(dlds);
+
+    // DMA roles: one instruction fills 8 rows x 128 bytes (lane l: row l / 8, slot l % 8 holding global
+    // column slot ^ (row & 7)); wavefront w fills rows 32 w .. 32 w + 31 of P and of Q: 4 + 4 instructions
+    const char *pbase = reinterpret_cast<const char *>(g.P + (int64_t)n0 * g.ldp);
+    const char *qbase = reinterpret_cast<const char *>(g.Q + (int64_t)m0 * g.ldq);
+    uint32_t poff[4], qoff[4];
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
-        const int m = m0 + wm * 64 + 32 * b + r;
-        if (m >= g.M) continue;
-#pragma unroll
-        for (int a = 0; a < 4; ++a) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int n = n0 + wn * 128 + 32 * a + 8 * q + 4 * c;
-                uint16_t *dst = g.C + (int64_t)m * g.ldc + n;
-                float v[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) v[i] = acc[a][b][4 * q + i] * alpha;
-                if (g.mask && n < g.N) {   // n is a multiple of 4: its four mask bits sit in one word
-                    const uint32_t mb = g.mask[(int64_t)m * g.mask_wpr + (n >> 5)] >> (n & 31);
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) v[i] = (mb >> i) & 1u ? v[i] : 0.0f;
-                }
-                if (n + 4 <= g.N && (g.ldc & 3) == 0) {
-                    if (g.accumulate) {
-                        const uint2 old = *reinterpret_cast<const uint2 *>(dst);
-                        v[0] += __uint_as_float(old.x << 16);
-                        v[1] += __uint_as_float(old.x & 0xffff0000u);
-                        v[2] += __uint_as_float(old.y << 16);
-                        v[3] += __uint_as_float(old.y & 0xffff0000u);
-                    }
-                    uint2 out;
-                    out.x = f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16);
-                    out.y = f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16);
-                    *reinterpret_cast<uint2 *>(dst) = out;
-                } else {
-                    for (int i = 0; i < 4; ++i) {
-                        if (n + i < g.N) {
-                            float x = v[i];
-                            if (g.accumulate) x += __uint_as_float((uint32_t)dst[i] << 16);
-                            dst[i] = (uint16_t)f32_to_bf16(x);
-                        }
-                    }
-                }
-            }
-        }
+    for (int i = 0; i < 4; ++i) {
+        const int row = 32 * wave + 8 * i + (lane >> 3);
+        const int col = (lane & 7) ^ (row & 7);
+        int n = n0 + row;
+        n = (n < g.N ? n : g.N - 1) - n0;
+        poff[i] = (uint32_t)(((int64_t)n * g.ldp + col * 8) * 2);
+        int m = m0 + row;
+        m = (m < g.M ? m : g.M - 1) - m0;
+        qoff[i] = (uint32_t)(((int64_t)m * g.ldq + col * 8) * 2);
     }
+    auto dma_stage = [&](int kt, int stage) {
+        const char *pb = pbase + (int64_t)kt * (GD_K * 2), *qb = qbase + (int64_t)kt * (GD_K * 2);
+        const uint32_t dp = lds0 + stage * GD_STAGE + wave * 4096, dq = dp + GD_N * GD_K * 2;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) lds_dma16(pb, poff[i], dp + i * 1024);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) lds_dma16(qb, qoff[i], dq + i * 1024);
+    };
+    // LDS read addresses: row * 128 + 16 * ((2u + c) ^ (row & 7)); row & 7 = r & 7 for every tile of the
+    // wavefront, so one lane address per u and operand, tiles and stages are immediate offsets
+    uint32_t pa[4], qa[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int slot = (2 * u + c) ^ (r & 7);
+        pa[u] = lds0 + (wn * 128 + r) * 128 + 16 * slot;
+        qa[u] = lds0 + GD_N * GD_K * 2 + (wm * 64 + r) * 128 + 16 * slot;
+    }
+    typedef __attribute__((address_space(3))) const v8bf *lds_v8bf;
+
+    v16f acc[4][2];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
+
+    auto multiply_stage = [&](const int stage) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            v8bf pf[4], qf[2];
+#pragma unroll
+            for (int a = 0; a < 4; ++a) pf[a] = *(lds_v8bf)(uintptr_t)(pa[u] + stage * GD_STAGE + a * 32 * 128);
+#pragma unroll
+            for (int b = 0; b < 2; ++b) qf[b] = *(lds_v8bf)(uintptr_t)(qa[u] + stage * GD_STAGE + b * 32 * 128);
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[a], qf[b], acc[a][b], 0, 0, 0);
+        }
+    };
+    // step kt reads stage kt & 1 while the DMA fills the other one with step kt + 1 (past the end the last
+    // step is fetched again into a stage nobody reads any more); the barrier at the end of a step publishes
+    // the landed stage and frees the one just read.  Stage numbers are literals: two steps per loop trip.
+    const int nk = g.K / GD_K;
+    auto step = [&](const int kt, const int stage) {
+        dma_stage(kt + 1 < nk ? kt + 1 : nk - 1, stage ^ 1);
+        multiply_stage(stage);
+        SBN_WAIT_VMCNT(0);
+        __syncthreads();
+    };
+    dma_stage(0, 0);
+    SBN_WAIT_VMCNT(0);
+    __syncthreads();
+    int kt = 0;
+    for (; kt + 2 <= nk; kt += 2) {
+        step(kt, 0);
+        step(kt + 1, 1);
+    }
+    if (kt < nk) step(kt, 0);
+
+    bf16_wave_epilogue(g, acc, n0 + wn * 128, m0 + wm * 64, lane);
 }
 
 GemmBf16Args make_bf16_args(const uint16_t *P, int64_t ldp, int N, const uint16_t *Q, int64_t ldq, int M, int K, uint16_t *C,
@@ -361,7 +488,7 @@ GemmBf16Args make_bf16_args(const uint16_t *P, int64_t ldp, int N, const uint16_
     GemmBf16Args g;
     g.P = P; g.Q = Q; g.C = C; g.alpha = alpha; g.ldp = ldp; g.ldq = ldq; g.ldc = ldc;
     g.N = N; g.M = M; g.K = K; g.accumulate = accumulate;
-    g.tiles_n = (int)ceil_div(N, GB_N);
+    g.tiles_n = (int)ceil_div(N, GB_N);   // for the register-prefetch kernel; the launcher recounts for the DMA kernel
     g.tiles_m = (int)ceil_div(M, GB_M);
     g.mask = nullptr;
     g.mask_wpr = 0;
@@ -374,14 +501,33 @@ sbn_status launch_gemm_bf16(int count, const GemmBf16Args *args, hipStream_t str
     GemmBf16Group grp;
     grp.count = count;
     const bool swap = count == 2 && args[1].K > args[0].K;
+    // the DMA kernel takes whole 64-k stages and 16-byte aligned rows; anything else takes the register-prefetch kernel
+    bool dma = true;
+    for (int i = 0; i < count; ++i)
+        dma = dma && args[i].K % GD_K == 0 && args[i].ldp % 8 == 0 && args[i].ldq % 8 == 0 && aligned(args[i].P, 16) && aligned(args[i].Q, 16);
     int blocks = 0;
     for (int i = 0; i < count; ++i) {
         grp.g[i] = args[swap ? 1 - i : i];
+        if (dma) {
+            grp.g[i].tiles_n = (int)ceil_div(grp.g[i].N, GD_N);
+            grp.g[i].tiles_m = (int)ceil_div(grp.g[i].M, GD_M);
+        }
         grp.block0[i] = blocks;
         blocks += (grp.g[i].tiles_n * grp.g[i].tiles_m + 7) / 8 * 8;   // eight equal shares, one per XCD
     }
     for (int i = count; i < 3; ++i) grp.block0[i] = blocks;
     if (count == 1) grp.g[1] = grp.g[0];
+    if (dma) {
+        static thread_local bool raised = false;
+        if (!raised) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_bf16_dma_kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, GD_LDS);
+            if (e != hipSuccess) { set_hip_error(e, "hipFuncSetAttribute"); return SBN_EHIP; }
+            raised = true;
+        }
+        hipLaunchKernelGGL(gemm_bf16_dma_kernel, dim3(blocks), dim3(512), GD_LDS, stream, grp);
+        return check_launch("gemm_bf16_dma_kernel");
+    }
     hipLaunchKernelGGL(gemm_bf16_nt_kernel, dim3(blocks), dim3(256), 0, stream, grp);
     return check_launch("gemm_bf16_nt_kernel");
 }
