@@ -382,7 +382,8 @@ __global__ void __launch_bounds__(256, 2) gemm_bf16_nt_kernel(GemmBf16Group grp)
 // operand read spread over all banks.  Needs K % 64 == 0 (no partial rows in a stage).
 // The matrix pipe still waits for the DMA about a third of the time: 64 KB in flight per multiprocessor
 // cover about one microsecond.  A ring of four stages of 32 k (96 KB in flight, 64-byte rows, twice the
-// barriers) was measured slower (backward of the block 5.96 against 5.43 ms).
+// barriers) was measured slower (backward of the block 5.96 against 5.43 ms), and so was warming L2 two steps
+// ahead with one extra line-touching DMA load per wavefront and step (5.99 ms: it doubles the L2 requests).
 constexpr int GD_N = 256, GD_M = 256, GD_K = 64;
 constexpr int GD_STAGE = (GD_N + GD_M) * GD_K * 2;   // 64 KB
 constexpr int GD_LDS = 2 * GD_STAGE;
