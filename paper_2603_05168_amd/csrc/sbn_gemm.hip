@@ -204,7 +204,6 @@ __global__ void __launch_bounds__(256, 2) gemm_smfmac_kernel(GemmGroup grp)
     constexpr int NDW = 16 / NWAVES;             // weight DMA instructions per wavefront and pair
     static_assert(NDT == TB, "one token DMA instruction is issued under each matrix instruction of a row tile");
     __shared__ __attribute__((aligned(1024))) int8_t lds[STAGES * STAGE_BYTES + 2 * WSLOT_BYTES];
-    int8_t *const wlds = lds + STAGES * STAGE_BYTES;
     const uint32_t lds0 = lds_address(lds), wlds0 = lds0 + STAGES * STAGE_BYTES;
     int to, tt;
     tile_of_block(g, local_id, to, tt);
