@@ -641,9 +641,10 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
                         for (int a = 0; a < RT; ++a) {
                             const int o = cu * 16 * RT + 16 * a + 4 * c4;
                             if (o + 3 < it.d_out && (it.d_out & 3) == 0) {
-                                *reinterpret_cast<float4 *>(it.Y + (int64_t)r * it.d_out + o) =
-                                    make_float4((float)acc[a][0] * scale, (float)acc[a][1] * scale,
-                                                (float)acc[a][2] * scale, (float)acc[a][3] * scale);
+                                const v4f y = {(float)acc[a][0] * scale, (float)acc[a][1] * scale, (float)acc[a][2] * scale,
+                                               (float)acc[a][3] * scale};
+                                // streaming store: Y is not read again here and should not displace the weight stream in L2
+                                __builtin_nontemporal_store(y, reinterpret_cast<v4f *>(it.Y + (int64_t)r * it.d_out + o));
                             } else {
                                 for (int i = 0; i < 4; ++i)
                                     if (o + i < it.d_out) it.Y[(int64_t)r * it.d_out + o + i] = (float)acc[a][i] * scale;
