@@ -526,7 +526,7 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
                 int row = unit * 16 * RT + 16 * a + r;
                 row = row < it.d_out ? row : it.d_out - 1;
                 const uint8_t *p = it.packed + ((int64_t)row * nchunks + ch) * 32;
-                ib[a] = *reinterpret_cast<const uint4 *>(p);
+                ib[a] = *reinterpret_cast<const uint4 *>(p);        // plain loads: nontemporal ones measured 30 % slower
                 cb[a] = *reinterpret_cast<const uint4 *>(p + 16);
             }
             if (++is == nsuper) {
