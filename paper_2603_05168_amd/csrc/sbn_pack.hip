@@ -292,8 +292,13 @@ __global__ void __launch_bounds__(256) pack_kernel(PackTable tab, const float *t
 
 // ---- fast pack kernels: bf16, rows contiguous, d_in % 128 == 0, patterns 2:4, 1:4, 2:8 ----------------
 // A lane owns 8 consecutive weights (one 16-byte load).  Selection runs on integer keys
-// (magnitude << 3 | 7 - position): unique within a group, and the larger key is the larger magnitude or,
-// among equals, the lower position, so max/min networks give the top-N with the tie rule built in.
+//     magnitude << 17 | (M - 1 - position in the group) << 2 | 1 << 1 | sign
+// which are unique within a group, and the larger key is the larger magnitude or, among equals, the lower
+// position, so max/min networks give the top-N with the tie rule built in.  A key is one rotation of the
+// dword that holds its bf16 value (the magnitude lands in bits [17, 32), the sign in bit 0) plus one
+// mask-and-or.  magnitude >= threshold is key >= threshold << 17, and the low two bits of a key, swapped,
+// are the ternary code of its element when that element is nonzero (01 = +1, 11 = -1), so a selected
+// key needs no look-up for its code.
 // The words of a chunk are OR-reduced across lanes with DPP (a DPP row = 16 lanes = one chunk), the
 // group leaders drop them into LDS, and the block stores its chunks with 16 bytes per thread.
 template <int CTRL> __device__ __forceinline__ uint32_t dpp_or_t(uint32_t x)
@@ -313,13 +318,37 @@ template <int LANES> __device__ __forceinline__ uint32_t group_or(uint32_t x)
 __device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
 __device__ __forceinline__ uint32_t umin(uint32_t a, uint32_t b) { return a < b ? a : b; }
 
-// ternary code of the element behind a key: nonzero iff magnitude >= threshold, sign from the raw bits
-__device__ __forceinline__ uint32_t code_of(uint32_t key, uint32_t th_key, uint32_t signs, uint32_t pos)
+template <int M> struct PackKey {
+    static constexpr int SH = 17;                               // magnitude shift
+    static constexpr uint32_t KEEP = 0xfffe0001u;               // magnitude and sign of a rotated dword
+    static constexpr uint32_t POS = (uint32_t)(M - 1) << 2;     // position field
+};
+
+// keys of the eight bf16 values of a vector (four dwords, two values each)
+template <int M>
+__device__ __forceinline__ void make_keys(const uint4 &v, uint32_t (&key)[8])
 {
-    const uint32_t nz = key >= th_key;
-    const uint32_t sg = (signs >> pos) & 1u;
-    return nz ? (1u | (sg << 1)) : 0u;
+    typedef PackKey<M> PK;
+    const uint32_t d[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t clo = ((uint32_t)(M - 1 - (2 * i) % M) << 2) | 2u, chi = ((uint32_t)(M - 1 - (2 * i + 1) % M) << 2) | 2u;
+        key[2 * i] = (__builtin_rotateleft32(d[i], 17) & PK::KEEP) | clo;      // low half: magnitude bits [0, 15), sign bit 15
+        key[2 * i + 1] = (__builtin_rotateleft32(d[i], 1) & PK::KEEP) | chi;   // high half: magnitude bits [16, 31), sign bit 31
+    }
 }
+
+// bits [0, 2) of every byte hold 1 << 1 | sign of a nonzero element or 0: swapped they are the ternary codes
+__device__ __forceinline__ uint32_t codes_of_key_bits(uint32_t x)
+{
+    return ((x & 0x01010101u) << 1) | ((x >> 1) & 0x01010101u);
+}
+
+// a key if its element is nonzero (the code is then its low two bits), else 0
+__device__ __forceinline__ uint32_t nonzero_key(uint32_t key, uint32_t th_key) { return key >= th_key ? key : 0u; }
+
+// byte 0 of lo and of hi side by side in bits [0, 8) and [8, 16)
+__device__ __forceinline__ uint32_t low_bytes(uint32_t lo, uint32_t hi) { return __builtin_amdgcn_perm(hi, lo, 0x0c0c0400u); }
 
 struct Top2 { uint32_t first, second; };
 // largest and second largest of four unique keys
@@ -330,6 +359,15 @@ __device__ __forceinline__ Top2 top2_of4(uint32_t k0, uint32_t k1, uint32_t k2, 
     t.first = umax(h01, h23);
     t.second = umax(umin(h01, h23), umax(l01, l23));
     return t;
+}
+
+// the two keys ordered by position: lower position (= larger position field) first
+template <int M>
+__device__ __forceinline__ void by_position(const Top2 &t, uint32_t &klo, uint32_t &khi)
+{
+    const bool first_lo = (t.first & PackKey<M>::POS) > (t.second & PackKey<M>::POS);
+    klo = first_lo ? t.first : t.second;
+    khi = first_lo ? t.second : t.first;
 }
 
 // What the blocks of the single-read form share through the workspace: the partial sums (one slot per
@@ -368,8 +406,9 @@ __device__ __forceinline__ double abs8(const uint4 &d, double acc)
     const uint32_t w[4] = {d.x, d.y, d.z, d.w};
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-        acc += Raw<uint16_t>::abs_value(w[k] & 0xffffu);
-        acc += Raw<uint16_t>::abs_value(w[k] >> 16);
+        // a bf16 value is the fp32 value with the same upper half; the absolute value is an operand modifier
+        acc += (double)fabsf(__uint_as_float(w[k] << 16));
+        acc += (double)fabsf(__uint_as_float(w[k] & 0xffff0000u));
     }
     return acc;
 }
@@ -384,31 +423,23 @@ __device__ __forceinline__ void pack_unit(const PackItem &it, const int64_t lb, 
     constexpr int CBW = (M == 4 && N == 2) ? 8 : (M == 4 ? 4 : 5);   // dwords per chunk: 32, 16, 20 bytes
     const int64_t total_chunks = it.d_out * (it.d_in / CHUNK);
     const int tid = threadIdx.x, ql = tid >> 4, l16 = tid & 15;
-    const uint32_t th_key = ((__float_as_uint(th_val) + 0xffffu) >> 16) << 3;   // bf16 threshold pattern, key scale
+    typedef PackKey<M> PK;
+    const uint32_t th_key = ((__float_as_uint(th_val) + 0xffffu) >> 16) << PK::SH;   // bf16 threshold pattern, key scale
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const uint32_t d[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
-        uint32_t key[8], signs = 0;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const uint32_t raw = (j & 1) ? (d[j >> 1] >> 16) : (d[j >> 1] & 0xffffu);
-            key[j] = ((raw & 0x7fffu) << 3) | (uint32_t)(7 - (j % M));
-            signs |= (raw >> 15) << j;
-        }
+        uint32_t key[8];
+        make_keys<M>(v[u], key);
         uint32_t *out = lds + (u * 16 + ql) * CBW;
+        // position fields hold M - 1 - position: the index bits are inverted once they are assembled
         if constexpr (N == 2 && M == 4) {
-            uint32_t idxb = 0, codeb = 0;
+            uint32_t klo[2], khi[2];
 #pragma unroll
-            for (int g = 0; g < 2; ++g) {
-                const Top2 t = top2_of4(key[4 * g], key[4 * g + 1], key[4 * g + 2], key[4 * g + 3]);
-                const uint32_t p1 = 7u - (t.first & 7u), p2 = 7u - (t.second & 7u);
-                const bool first_lo = p1 < p2;
-                const uint32_t plo = first_lo ? p1 : p2, phi = first_lo ? p2 : p1;
-                const uint32_t klo = first_lo ? t.first : t.second, khi = first_lo ? t.second : t.first;
-                idxb |= (plo | (phi << 2)) << (4 * g);
-                codeb |= code_of(klo, th_key, signs >> (4 * g), plo) << (16 * g);
-                codeb |= code_of(khi, th_key, signs >> (4 * g), phi) << (16 * g + 8);
-            }
+            for (int g = 0; g < 2; ++g) by_position<M>(top2_of4(key[4 * g], key[4 * g + 1], key[4 * g + 2], key[4 * g + 3]), klo[g], khi[g]);
+            const uint32_t n0 = ((klo[0] >> 2) & 3u) | (khi[0] & 0xcu), n1 = ((klo[1] >> 2) & 3u) | (khi[1] & 0xcu);
+            const uint32_t idxb = (n0 | (n1 << 4)) ^ 0xffu;
+            const uint32_t c0 = low_bytes(nonzero_key(klo[0], th_key), nonzero_key(khi[0], th_key));
+            const uint32_t c1 = low_bytes(nonzero_key(klo[1], th_key), nonzero_key(khi[1], th_key));
+            const uint32_t codeb = codes_of_key_bits(c0 | (c1 << 16));
             const int L = l16 & 3;
             const uint32_t idxw = group_or<4>(idxb << (8 * L));
             const uint32_t codew = group_or<4>(codeb << (2 * L));
@@ -417,14 +448,10 @@ __device__ __forceinline__ void pack_unit(const PackItem &it, const int64_t lb, 
                 out[4 + (l16 >> 2)] = codew;
             }
         } else if constexpr (N == 1 && M == 4) {
-            uint32_t idxb = 0, codeb = 0;
-#pragma unroll
-            for (int g = 0; g < 2; ++g) {
-                const uint32_t top = umax(umax(key[4 * g], key[4 * g + 1]), umax(key[4 * g + 2], key[4 * g + 3]));
-                const uint32_t pos = 7u - (top & 7u);
-                idxb |= pos << (2 * g);
-                codeb |= code_of(top, th_key, signs >> (4 * g), pos) << (8 * g);
-            }
+            const uint32_t t0 = umax(umax(key[0], key[1]), umax(key[2], key[3]));
+            const uint32_t t1 = umax(umax(key[4], key[5]), umax(key[6], key[7]));
+            const uint32_t idxb = (((t0 >> 2) & 3u) | (t1 & 0xcu)) ^ 0xfu;
+            const uint32_t codeb = codes_of_key_bits(low_bytes(nonzero_key(t0, th_key), nonzero_key(t1, th_key)));
             const int L8 = l16 & 7;
             const uint32_t idxw = group_or<8>(idxb << (4 * L8));
             const uint32_t codew = group_or<8>(codeb << (16 * (L8 & 1) + 2 * (L8 >> 1)));
@@ -435,19 +462,18 @@ __device__ __forceinline__ void pack_unit(const PackItem &it, const int64_t lb, 
         } else {   // 2:8
             const Top2 ta = top2_of4(key[0], key[1], key[2], key[3]);
             const Top2 tb = top2_of4(key[4], key[5], key[6], key[7]);
-            // keys of the second half carry positions 4..7 in their low bits (7 - j with j % 8)
-            const uint32_t first = umax(ta.first, tb.first);
-            const uint32_t second = umax(umin(ta.first, tb.first), umax(ta.second, tb.second));
-            const uint32_t p1 = 7u - (first & 7u), p2 = 7u - (second & 7u);
-            const bool first_lo = p1 < p2;
-            const uint32_t plo = first_lo ? p1 : p2, phi = first_lo ? p2 : p1;
-            const uint32_t klo = first_lo ? first : second, khi = first_lo ? second : first;
-            const uint32_t codeb = code_of(klo, th_key, signs, plo) | (code_of(khi, th_key, signs, phi) << 8);
+            Top2 t;
+            t.first = umax(ta.first, tb.first);
+            t.second = umax(umin(ta.first, tb.first), umax(ta.second, tb.second));
+            uint32_t klo, khi;
+            by_position<M>(t, klo, khi);
+            const uint32_t pospair = (((klo >> 2) & 7u) | ((khi & 0x1cu) << 1)) ^ 0x3fu;   // two 3-bit positions
+            const uint32_t codeb = codes_of_key_bits(low_bytes(nonzero_key(klo, th_key), nonzero_key(khi, th_key)));
             const int L8 = l16 & 7;
             const uint32_t codew = group_or<8>(codeb << (16 * (L8 & 1) + 2 * (L8 >> 1)));
-            // two 3-bit positions at bit 6 * l16 of the 96-bit index field
+            // the pair sits at bit 6 * l16 of the 96-bit index field
             const uint32_t off = 6u * (uint32_t)l16, w0 = off >> 5;
-            const uint64_t bits = (uint64_t)(plo | (phi << 3)) << (off & 31u);
+            const uint64_t bits = (uint64_t)pospair << (off & 31u);
             const uint32_t blo = (uint32_t)bits, bhi = (uint32_t)(bits >> 32);
             const uint32_t i0 = group_or<16>(w0 == 0 ? blo : 0u);
             const uint32_t i1 = group_or<16>((w0 == 1 ? blo : 0u) | (w0 == 0 ? bhi : 0u));
