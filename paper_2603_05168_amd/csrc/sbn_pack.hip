@@ -581,14 +581,28 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5, 5))
         __syncthreads();
         double a2 = 0.0;   // finalizer: this thread's share of the partials, in the finalize order
         if (finalizer) {
+            // a thread's slots are read FIN_BATCH at a time, all loads in flight together (a device-scope load
+            // takes about 1.5 us); then the empty ones are polled
+            constexpr int FIN_BATCH = 5;
             int spins = 0, ok = sync.spin_limit >= 0;
-            for (int b = tid; b < nblk && ok; b += 256) {
-                unsigned long long bits;
-                while ((bits = __hip_atomic_load(&part_bits[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) == PACK_NO_PARTIAL) {
-                    if (++spins > sync.spin_limit) { ok = 0; break; }
-                    __builtin_amdgcn_s_sleep(4);
+            for (int b0 = tid; b0 < nblk && ok; b0 += 256 * FIN_BATCH) {
+                unsigned long long bits[FIN_BATCH];
+#pragma unroll
+                for (int j = 0; j < FIN_BATCH; ++j) {
+                    const int b = b0 + 256 * j;
+                    bits[j] = __hip_atomic_load(&part_bits[b < nblk ? b : b0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
-                if (ok) a2 += __longlong_as_double((long long)bits);
+#pragma unroll
+                for (int j = 0; j < FIN_BATCH; ++j) {
+                    const int b = b0 + 256 * j;
+                    if (b >= nblk || !ok) continue;
+                    while (bits[j] == PACK_NO_PARTIAL) {
+                        if (++spins > sync.spin_limit) { ok = 0; break; }
+                        __builtin_amdgcn_s_sleep(4);
+                        bits[j] = __hip_atomic_load(&part_bits[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                    if (ok) a2 += __longlong_as_double((long long)bits[j]);   // in the order b = tid, tid + 256, ...
+                }
             }
             if (!ok) role_s = 2;   // several threads may write the same value
         } else if (tid == 0) {
