@@ -1,8 +1,9 @@
 // quantize_mask_pack: absmean scale, N:M magnitude mask, ternary codes, packed layout.
 //
 // bf16 matrices of whole chunks at 2:4, 1:4 or 2:8 take the single-read form: one persistent kernel
-// (pack_stream_kernel<N, M>, after a small clear of its counters) whose blocks keep 16384 weights
-// in registers between the |w| sum and the packing, so that W crosses HBM once.
+// (pack_stream_kernel, after a small clear of its counters) whose blocks keep units of 16384 weights
+// in registers between the |w| sum and the packing (ranked and compacted while they wait for the
+// threshold), so that W crosses HBM once.
 // Everything else takes three enqueues per batch of up to PACK_MAX_ITEMS matrices:
 //   1. absmean_partial_kernel  one block per 16384 weights, |w| summed in fp64 (every term exact)
 //   2. absmean_finalize_kernel one block per matrix: fixed-order sum of the partials, gamma and
@@ -338,17 +339,24 @@ __device__ __forceinline__ void make_keys(const uint4 &v, uint32_t (&key)[8])
     }
 }
 
-// bits [0, 2) of every byte hold 1 << 1 | sign of a nonzero element or 0: swapped they are the ternary codes
-__device__ __forceinline__ uint32_t codes_of_key_bits(uint32_t x)
+// the bf16 pattern (sign and magnitude) behind a key, in the low (raw_lo) or high (raw_hi) half of a dword
+__device__ __forceinline__ uint32_t pair_of_keys(uint32_t klo, uint32_t khi)
 {
-    return ((x & 0x01010101u) << 1) | ((x >> 1) & 0x01010101u);
+    const uint32_t lo = __builtin_rotateleft32(klo, 15), hi = __builtin_rotateleft32(khi, 31);
+    return (lo & 0xffffu) | (hi & 0xffff0000u);
 }
 
-// a key if its element is nonzero (the code is then its low two bits), else 0
-__device__ __forceinline__ uint32_t nonzero_key(uint32_t key, uint32_t th_key) { return key >= th_key ? key : 0u; }
-
-// byte 0 of lo and of hi side by side in bits [0, 8) and [8, 16)
-__device__ __forceinline__ uint32_t low_bytes(uint32_t lo, uint32_t hi) { return __builtin_amdgcn_perm(hi, lo, 0x0c0c0400u); }
+// ternary codes of the two bf16 patterns of a dword, at bits [0, 2) and [16, 18): nonzero iff magnitude >=
+// threshold, i.e. iff magnitude - (threshold - 1) does not saturate to 0.  thm1x2 = threshold - 1 in both halves.
+__device__ __forceinline__ uint32_t pair_codes(uint32_t p, uint32_t thm1x2)
+{
+    // packed 16-bit saturating subtract and minimum, written out: the compiler splits the vector form into
+    // two 16-bit compares and selects
+    uint32_t over, nz;
+    asm("v_pk_sub_u16 %0, %1, %2 clamp" : "=v"(over) : "v"(p & 0x7fff7fffu), "v"(thm1x2));
+    asm("v_pk_min_u16 %0, %1, %2" : "=v"(nz) : "v"(over), "v"(0x00010001u));
+    return (((p >> 15) & nz) << 1) | nz;
+}
 
 struct Top2 { uint32_t first, second; };
 // largest and second largest of four unique keys
@@ -413,52 +421,40 @@ __device__ __forceinline__ double abs8(const uint4 &d, double acc)
     return acc;
 }
 
-// Packs the unit held in v with threshold th_val and stores its 128 chunks (contiguous in the packed buffer).
-// lds: PACK_U * 16 * CBW words of staging; ends with the block's stores issued, LDS free after the next barrier.
+// What is left of a unit once its groups have been ranked, which needs no threshold: the bf16 patterns of
+// the kept values, two per dword in position order, and one byte of index bits per vector (as they go into
+// the index field).  18, 10 and 10 registers per thread for 2:4, 1:4 and 2:8 against 32 for the weights.
+template <int N, int M> struct PackCompact {
+    static constexpr int SEL = (N == 2 && M == 4) ? 2 * PACK_U : PACK_U;
+    uint32_t sel[SEL];
+    uint32_t idx[PACK_U / 4];
+};
+
 template <int N, int M>
-__device__ __forceinline__ void pack_unit(const PackItem &it, const int64_t lb, const uint4 (&v)[PACK_U], const float th_val,
-                                          uint32_t *lds)
+__device__ __forceinline__ void select_unit(const uint4 (&v)[PACK_U], PackCompact<N, M> &c)
 {
-    constexpr int U = PACK_U;
-    constexpr int CBW = (M == 4 && N == 2) ? 8 : (M == 4 ? 4 : 5);   // dwords per chunk: 32, 16, 20 bytes
-    const int64_t total_chunks = it.d_out * (it.d_in / CHUNK);
-    const int tid = threadIdx.x, ql = tid >> 4, l16 = tid & 15;
-    typedef PackKey<M> PK;
-    const uint32_t th_key = ((__float_as_uint(th_val) + 0xffffu) >> 16) << PK::SH;   // bf16 threshold pattern, key scale
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
+    for (int w = 0; w < PACK_U / 4; ++w) c.idx[w] = 0;
+#pragma unroll
+    for (int u = 0; u < PACK_U; ++u) {
         uint32_t key[8];
         make_keys<M>(v[u], key);
-        uint32_t *out = lds + (u * 16 + ql) * CBW;
+        uint32_t idxb;
         // position fields hold M - 1 - position: the index bits are inverted once they are assembled
         if constexpr (N == 2 && M == 4) {
             uint32_t klo[2], khi[2];
 #pragma unroll
-            for (int g = 0; g < 2; ++g) by_position<M>(top2_of4(key[4 * g], key[4 * g + 1], key[4 * g + 2], key[4 * g + 3]), klo[g], khi[g]);
-            const uint32_t n0 = ((klo[0] >> 2) & 3u) | (khi[0] & 0xcu), n1 = ((klo[1] >> 2) & 3u) | (khi[1] & 0xcu);
-            const uint32_t idxb = (n0 | (n1 << 4)) ^ 0xffu;
-            const uint32_t c0 = low_bytes(nonzero_key(klo[0], th_key), nonzero_key(khi[0], th_key));
-            const uint32_t c1 = low_bytes(nonzero_key(klo[1], th_key), nonzero_key(khi[1], th_key));
-            const uint32_t codeb = codes_of_key_bits(c0 | (c1 << 16));
-            const int L = l16 & 3;
-            const uint32_t idxw = group_or<4>(idxb << (8 * L));
-            const uint32_t codew = group_or<4>(codeb << (2 * L));
-            if (L == 0) {
-                out[l16 >> 2] = idxw;
-                out[4 + (l16 >> 2)] = codew;
+            for (int g = 0; g < 2; ++g) {
+                by_position<M>(top2_of4(key[4 * g], key[4 * g + 1], key[4 * g + 2], key[4 * g + 3]), klo[g], khi[g]);
+                c.sel[2 * u + g] = pair_of_keys(klo[g], khi[g]);
             }
+            const uint32_t n0 = ((klo[0] >> 2) & 3u) | (khi[0] & 0xcu), n1 = ((klo[1] >> 2) & 3u) | (khi[1] & 0xcu);
+            idxb = (n0 | (n1 << 4)) ^ 0xffu;
         } else if constexpr (N == 1 && M == 4) {
             const uint32_t t0 = umax(umax(key[0], key[1]), umax(key[2], key[3]));
             const uint32_t t1 = umax(umax(key[4], key[5]), umax(key[6], key[7]));
-            const uint32_t idxb = (((t0 >> 2) & 3u) | (t1 & 0xcu)) ^ 0xfu;
-            const uint32_t codeb = codes_of_key_bits(low_bytes(nonzero_key(t0, th_key), nonzero_key(t1, th_key)));
-            const int L8 = l16 & 7;
-            const uint32_t idxw = group_or<8>(idxb << (4 * L8));
-            const uint32_t codew = group_or<8>(codeb << (16 * (L8 & 1) + 2 * (L8 >> 1)));
-            if (L8 == 0) {
-                out[l16 >> 3] = idxw;
-                out[2 + (l16 >> 3)] = codew;
-            }
+            c.sel[u] = pair_of_keys(t0, t1);
+            idxb = (((t0 >> 2) & 3u) | (t1 & 0xcu)) ^ 0xfu;
         } else {   // 2:8
             const Top2 ta = top2_of4(key[0], key[1], key[2], key[3]);
             const Top2 tb = top2_of4(key[4], key[5], key[6], key[7]);
@@ -467,19 +463,61 @@ __device__ __forceinline__ void pack_unit(const PackItem &it, const int64_t lb, 
             t.second = umax(umin(ta.first, tb.first), umax(ta.second, tb.second));
             uint32_t klo, khi;
             by_position<M>(t, klo, khi);
-            const uint32_t pospair = (((klo >> 2) & 7u) | ((khi & 0x1cu) << 1)) ^ 0x3fu;   // two 3-bit positions
-            const uint32_t codeb = codes_of_key_bits(low_bytes(nonzero_key(klo, th_key), nonzero_key(khi, th_key)));
+            c.sel[u] = pair_of_keys(klo, khi);
+            idxb = (((klo >> 2) & 7u) | ((khi & 0x1cu) << 1)) ^ 0x3fu;   // two 3-bit positions
+        }
+        c.idx[u / 4] |= idxb << (8 * (u % 4));
+    }
+}
+
+// Codes of the compact unit with threshold th_val, fields assembled, and its 128 chunks (contiguous in the
+// packed buffer) stored.  lds: PACK_U * 16 * CBW words of staging; ends with the block's stores issued, LDS
+// free after the next barrier.
+template <int N, int M>
+__device__ __forceinline__ void finish_unit(const PackItem &it, const int64_t lb, const PackCompact<N, M> &c, const float th_val,
+                                            uint32_t *lds)
+{
+    constexpr int U = PACK_U;
+    constexpr int CBW = (M == 4 && N == 2) ? 8 : (M == 4 ? 4 : 5);   // dwords per chunk: 32, 16, 20 bytes
+    const int64_t total_chunks = it.d_out * (it.d_in / CHUNK);
+    const int tid = threadIdx.x, ql = tid >> 4, l16 = tid & 15;
+    // smallest bf16 magnitude pattern whose value is >= theta (at least 1: theta > 0), minus one, in both halves
+    const uint32_t thm1x2 = (((__float_as_uint(th_val) + 0xffffu) >> 16) - 1u) * 0x10001u;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        uint32_t *out = lds + (u * 16 + ql) * CBW;
+        const uint32_t idxb = (c.idx[u / 4] >> (8 * (u % 4))) & 0xffu;
+        if constexpr (N == 2 && M == 4) {
+            // bytes 0 and 2 of each pair's codes -> the four code bytes of the vector
+            const uint32_t codeb = __builtin_amdgcn_perm(pair_codes(c.sel[2 * u + 1], thm1x2), pair_codes(c.sel[2 * u], thm1x2), 0x06040200u);
+            const int L = l16 & 3;
+            const uint32_t idxw = group_or<4>(idxb << (8 * L));
+            const uint32_t codew = group_or<4>(codeb << (2 * L));
+            if (L == 0) {
+                out[l16 >> 2] = idxw;
+                out[4 + (l16 >> 2)] = codew;
+            }
+        } else {
+            const uint32_t codeb = __builtin_amdgcn_perm(0u, pair_codes(c.sel[u], thm1x2), 0x0c0c0200u);
             const int L8 = l16 & 7;
             const uint32_t codew = group_or<8>(codeb << (16 * (L8 & 1) + 2 * (L8 >> 1)));
-            // the pair sits at bit 6 * l16 of the 96-bit index field
-            const uint32_t off = 6u * (uint32_t)l16, w0 = off >> 5;
-            const uint64_t bits = (uint64_t)pospair << (off & 31u);
-            const uint32_t blo = (uint32_t)bits, bhi = (uint32_t)(bits >> 32);
-            const uint32_t i0 = group_or<16>(w0 == 0 ? blo : 0u);
-            const uint32_t i1 = group_or<16>((w0 == 1 ? blo : 0u) | (w0 == 0 ? bhi : 0u));
-            const uint32_t i2 = group_or<16>((w0 == 2 ? blo : 0u) | (w0 == 1 ? bhi : 0u));
-            if (l16 == 0) { out[0] = i0; out[1] = i1; out[2] = i2; }
-            if (L8 == 0) out[3 + (l16 >> 3)] = codew;
+            if constexpr (M == 4) {
+                const uint32_t idxw = group_or<8>(idxb << (4 * L8));
+                if (L8 == 0) {
+                    out[l16 >> 3] = idxw;
+                    out[2 + (l16 >> 3)] = codew;
+                }
+            } else {
+                // the pair of positions sits at bit 6 * l16 of the 96-bit index field
+                const uint32_t off = 6u * (uint32_t)l16, w0 = off >> 5;
+                const uint64_t bits = (uint64_t)idxb << (off & 31u);
+                const uint32_t blo = (uint32_t)bits, bhi = (uint32_t)(bits >> 32);
+                const uint32_t i0 = group_or<16>(w0 == 0 ? blo : 0u);
+                const uint32_t i1 = group_or<16>((w0 == 1 ? blo : 0u) | (w0 == 0 ? bhi : 0u));
+                const uint32_t i2 = group_or<16>((w0 == 2 ? blo : 0u) | (w0 == 1 ? bhi : 0u));
+                if (l16 == 0) { out[0] = i0; out[1] = i1; out[2] = i2; }
+                if (L8 == 0) out[3 + (l16 >> 3)] = codew;
+            }
         }
     }
     __syncthreads();
@@ -509,7 +547,9 @@ __global__ void __launch_bounds__(256) pack_fast_kernel(PackTable tab, const flo
     const int64_t lb = (int)blockIdx.x - tab.pack_block0[lo];
     uint4 v[PACK_U];
     load_unit(it, lb, v);
-    pack_unit<N, M>(it, lb, v, theta[lo], lds);
+    PackCompact<N, M> c;
+    select_unit<N, M>(v, c);
+    finish_unit<N, M>(it, lb, c, theta[lo], lds);
 }
 
 // ---- single-read form ---------------------------------------------------------------------------
@@ -518,19 +558,23 @@ __global__ void __launch_bounds__(256) pack_fast_kernel(PackTable tab, const flo
 // block loads the weights into registers and publishes their |w| sum (one store, fire and forget); the block
 // that holds the matrix's first unit waits until every partial slot of the matrix is filled, adds them in
 // the fixed order of the finalize kernel, derives gamma and theta and raises the matrix's ready words
-// (they carry theta).  A
-// block packs a unit from its registers once the unit's matrix is ready - and before it waits for
-// that, it has already loaded and published its NEXT unit into a second set of registers, so the
-// hand-over of one matrix (four device-scope hops of about 1.5 us) runs under the loads of the
-// following one.  W crosses HBM once.
+// (they carry theta).  Ranking the groups needs no threshold, so a loaded unit is ranked at once and kept
+// in its compact form (the kept values and their index bits: about half the registers); only the codes
+// wait for theta.  A block has QD + 1 units in flight: QD compact ones wait for their matrices (the oldest
+// is packed next), one more is loaded, summed and published BEFORE the block waits for the oldest - the
+// hand-over of a matrix (four device-scope hops of about 1.5 us) runs under the loads of the following
+// ones.  The smaller compact form also lets more blocks fit (2:4: six per SIMD instead of five).
+// W crosses HBM once.
 // Waits always end: a unit's matrix becomes ready once all its units are published; a block publishes
-// unit k + 1 before it waits for unit k, and the units of a matrix (at most as many as there are
-// blocks: the host checks) all lie within one deal of the round-robin, so every wait depends only on
-// publications that are earlier in the deal order.  The wait is bounded all the same (the grid might
+// every unit it holds before it waits, and the units of a matrix (at most as many as there are
+// blocks: the host checks) all lie within one deal of the round-robin.  Take the block whose oldest unit
+// has the smallest number x: every unit of x's matrix lies below x + B, so the block it belongs to
+// already holds it, hence has published it; the same goes for the matrix's first unit, whose block finalizes.
+// The wait is bounded all the same (the grid might
 // not be fully resident when the device is shared): a block out of polls recomputes every partial of
 // the matrix from HBM itself - same arithmetic, same order, same theta - and goes on.
-template <int N, int M>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5, 5))) pack_stream_kernel(PackTable tab, PackSync sync)
+template <int N, int M, int QD, int WAVES>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WAVES, WAVES))) pack_stream_kernel(PackTable tab, PackSync sync)
 {
     constexpr int CBW = (M == 4 && N == 2) ? 8 : (M == 4 ? 4 : 5);
     __shared__ __attribute__((aligned(16))) uint32_t lds[PACK_U * 16 * CBW];
@@ -543,13 +587,14 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5, 5))
 
     struct Unit { int lo; int64_t lb; };
     auto ready_words = [&](int lo) { return sync.words + (int64_t)lo * PACK_SYNC_WORDS; };
-    // load unit g, publish its partial sum, finalize its matrix if this arrival completes it
-    auto load_publish = [&](int g, uint4 (&v)[PACK_U]) -> Unit {
+    auto unit_of = [&](int g) -> Unit {
         Unit un;
         un.lo = find_item(tab.pack_block0, tab.count, g);
         un.lb = g - tab.pack_block0[un.lo];
-        const PackItem &it = tab.it[un.lo];
-        load_unit(it, un.lb, v);
+        return un;
+    };
+    // the |w| sum of a loaded unit into its partial slot
+    auto publish = [&](const Unit &un, const uint4 (&v)[PACK_U]) {
         double acc = 0.0;
 #pragma unroll
         for (int u = 0; u < PACK_U; ++u) acc = abs8(v[u], acc);
@@ -562,7 +607,6 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5, 5))
             __hip_atomic_store(&part_bits[un.lb], (unsigned long long)__double_as_longlong(mine), __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_AGENT);
         __syncthreads();   // red is free again
-        return un;
     };
     // theta of the unit's matrix: known, or polled from the group's ready word, or recomputed
     // theta of the unit's matrix.  The block that holds the matrix's first unit finalizes it: it waits until
@@ -659,26 +703,50 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5, 5))
         __syncthreads();   // th_s, role_s and red may be rewritten by what follows
         return th;
     };
-    auto pack = [&](const Unit &un, const uint4 (&v)[PACK_U]) {
-        const float th = theta_of(un);
-        pack_unit<N, M>(tab.it[un.lo], un.lb, v, th, lds);
-        __syncthreads();   // the staging area is free for the next unit
+    // A block has up to QD + 1 units in flight: the weights of the youngest in registers (loading), the QD
+    // older ones ranked and compacted, waiting for their matrices' thresholds; q[0] is the oldest.
+    uint4 raw[PACK_U];
+    PackCompact<N, M> q[QD];
+    Unit uq[QD];
+    int queued = 0;
+    auto push = [&](const Unit &un) {   // rank the loaded unit and queue it
+#pragma unroll
+        for (int i = 0; i < QD; ++i)
+            if (queued == i) {   // one copy of the ranking code per slot: through a temporary the registers run out
+                select_unit<N, M>(raw, q[i]);
+                uq[i] = un;
+            }
+        ++queued;
     };
-
-    uint4 va[PACK_U], vb[PACK_U];
     int g = (int)blockIdx.x;
-    if (g >= total_units) return;
-    Unit ua = load_publish(g, va), ub;
-    while (true) {
-        const int g1 = g + B;
-        if (g1 < total_units) ub = load_publish(g1, vb);
-        pack(ua, va);
-        if (g1 >= total_units) break;
-        const int g2 = g1 + B;
-        if (g2 < total_units) ua = load_publish(g2, va);
-        pack(ub, vb);
-        if (g2 >= total_units) break;
-        g = g2;
+    for (int i = 0; i < QD && g < total_units; ++i, g += B) {
+        const Unit un = unit_of(g);
+        load_unit(tab.it[un.lo], un.lb, raw);
+        publish(un, raw);
+        push(un);
+    }
+    while (queued > 0) {
+        const bool more = g < total_units;
+        Unit un;
+        if (more) {   // published before this block waits: no matrix waits for a block that itself waits
+            un = unit_of(g);
+            load_unit(tab.it[un.lo], un.lb, raw);
+            publish(un, raw);
+        }
+        const float th = theta_of(uq[0]);
+        finish_unit<N, M>(tab.it[uq[0].lo], uq[0].lb, q[0], th, lds);
+        __syncthreads();   // the staging area is free for the next unit
+#pragma unroll
+        for (int i = 0; i + 1 < QD; ++i)
+            if (i + 1 < queued) {
+                q[i] = q[i + 1];
+                uq[i] = uq[i + 1];
+            }
+        --queued;
+        if (more) {
+            push(un);
+            g += B;
+        }
     }
 }
 
@@ -932,13 +1000,28 @@ __global__ void __launch_bounds__(256) pack_sync_clear_kernel(unsigned *words, i
 }
 
 // blocks of the single-read pack kernel the device holds at once = its grid (per instantiation, cached per thread)
+// Compact units a block queues and wavefronts per SIMD of the single-read kernel, per pattern.  Measured
+// (sweep of 210 matrices): 2:4 with (queue, wavefronts) = (1, 6) 1.27 ms, (2, 5) 1.39, (1, 7) 1.50 (spills);
+// 1:4 / 2:8 with (2, 5) 1.11 / 1.27 ms, (3, 5) 1.12 / 1.31, (1, 7) 1.14 / 1.31, (2, 6) 1.17 / 1.36.
+template <int N, int M> struct PackStreamShape {
+    static constexpr int QD = (N == 2 && M == 4) ? 1 : 2;
+    static constexpr int WAVES = (N == 2 && M == 4) ? 6 : 5;
+};
+
+template <int N, int M>
+static void launch_pack_stream(int grid, hipStream_t stream, const PackTable &tab, const PackSync &sync)
+{
+    hipLaunchKernelGGL((pack_stream_kernel<N, M, PackStreamShape<N, M>::QD, PackStreamShape<N, M>::WAVES>), dim3(grid), dim3(256), 0,
+                       stream, tab, sync);
+}
+
 template <int N, int M>
 static int fused_capacity()
 {
     static thread_local int cap = 0;
     if (cap == 0) {
         int per_cu = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, pack_stream_kernel<N, M>, 256, 0) != hipSuccess) per_cu = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, pack_stream_kernel<N, M, PackStreamShape<N, M>::QD, PackStreamShape<N, M>::WAVES>, 256, 0) != hipSuccess) per_cu = 0;
         cap = per_cu > 0 ? per_cu * device_cus() : -1;
     }
     return cap;
@@ -1013,9 +1096,9 @@ sbn_status launch_pack(int count, const PackItem *items, sbn_dtype wdt, const Pa
             if (st != SBN_OK) return st;
             PackSync sync{part, th, words, pack_spin_limit()};
             const int grid = fb[n] < cap ? fb[n] : cap;
-            if (pat.M == 4 && pat.N == 2) hipLaunchKernelGGL((pack_stream_kernel<2, 4>), dim3(grid), dim3(256), 0, stream, tab, sync);
-            else if (pat.M == 4) hipLaunchKernelGGL((pack_stream_kernel<1, 4>), dim3(grid), dim3(256), 0, stream, tab, sync);
-            else hipLaunchKernelGGL((pack_stream_kernel<2, 8>), dim3(grid), dim3(256), 0, stream, tab, sync);
+            if (pat.M == 4 && pat.N == 2) launch_pack_stream<2, 4>(grid, stream, tab, sync);
+            else if (pat.M == 4) launch_pack_stream<1, 4>(grid, stream, tab, sync);
+            else launch_pack_stream<2, 8>(grid, stream, tab, sync);
             st = check_launch("pack_stream_kernel");
             if (st != SBN_OK) return st;
             sum_base += sb;
