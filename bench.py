@@ -384,24 +384,44 @@ def main():
                     sbn.sbn_sparse_ternary_linear_backward(dYf if a == F else dYh, pk[i], gl[i], xq_, sxb, N, M, wsb, b,
                                                            dX=dXf if b == F else dXh, dW=dWl[i])
 
+        # backward in the order of backpropagation, the layers whose output gradients arrive together in one call:
+        # down; up and gate; O; Q, K and V (layers of a call that share their input share its transpose)
+        dXg = {i: torch.empty(Tt, b, dtype=torch.bfloat16, device=dev) for i, (_, a, b) in enumerate(mats)}
+        groups = []
+        for idx in ([6], [4, 5], [3], [0, 1, 2]):
+            wsg = sbn.new_workspace(sum(sbn.sbn_workspace_bytes(sbn.SBN_OP_BACKWARD, Tt, mats[i][1], mats[i][2], N, M)
+                                        for i in idx), dev)
+            groups.append(sbn.BackwardGroup([dYf if mats[i][1] == F else dYh for i in idx], [pk[i] for i in idx],
+                                            [gl[i] for i in idx], [xqf if mats[i][2] == F else xqh for i in idx],
+                                            [sxb for _ in idx], N, M, wsg, [mats[i][2] for i in idx],
+                                            [dXg[i] for i in idx], [dWl[i] for i in idx]))
+
+        def backward_grouped():
+            for grp in groups:
+                grp.run()
+
         def train_step():
             remask()
-            forward_backward()
+            forward_backward(True, False)
+            backward_grouped()
 
         ms_all = timed(train_step, 3, 1)
         ms_pack = timed(remask, 5, 1)
         ms_fwd = timed(lambda: forward_backward(True, False), 3, 1)
-        ms_bwd = timed(lambda: forward_backward(False, True), 3, 1)
+        ms_bwd = timed(backward_grouped, 3, 1)
+        ms_bwd_single = timed(lambda: forward_backward(False, True), 3, 1)
         wsum = sum(a * b for _, a, b in mats)
         rows["train_step_block"] = {
             "tokens": Tt, "ms": ms_all, "remask_pack_ms": ms_pack, "forward_ms": ms_fwd, "backward_ms": ms_bwd,
+            "backward_layer_by_layer_ms": ms_bwd_single,
             "forward_tops_dense_equiv": 2.0 * Tt * wsum / (ms_fwd * 1e-3) / 1e12,
             "backward_tflops": 4.0 * Tt * wsum / (ms_bwd * 1e-3) / 1e12,
             "backward_frac_bf16_mfma": 4.0 * Tt * wsum / (ms_bwd * 1e-3) / 1e12 / BF16_DENSE_PEAK_TFLOPS,
             "step_tops_total": 6.0 * Tt * wsum / (ms_all * 1e-3) / 1e12}
-        log(f"[train] block step {ms_all:.2f} ms (pack {ms_pack:.3f}, fwd {ms_fwd:.2f}, bwd {ms_bwd:.2f}); "
+        log(f"[train] block step {ms_all:.2f} ms (pack {ms_pack:.3f}, fwd {ms_fwd:.2f}, bwd {ms_bwd:.2f} in four grouped calls, "
+            f"{ms_bwd_single:.2f} layer by layer); "
             f"bwd {rows['train_step_block']['backward_tflops']:.0f} TFLOP/s")
-        del Wt, Xh, Xo, Xf, dYh, dYf, Yh, Yf, dXh, dXf, dWl, wsl, wsb
+        del Wt, Xh, Xo, Xf, dYh, dYf, Yh, Yf, dXh, dXf, dWl, wsl, wsb, groups, dXg
         torch.cuda.empty_cache()
 
     # ------------------------------------------------------------------ plain copy of known size (scale of the HBM counters)

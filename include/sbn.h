@@ -188,6 +188,24 @@ sbn_status sbn_sparse_ternary_linear_backward(const void *dY, int64_t tokens, in
                                               void *dX, void *dW, int flags, void *workspace,
                                               size_t ws_bytes, void *stream);
 
+/*
+ * The backward products of `count` (<= SBN_BACKWARD_GROUP_MAX) layers whose output gradients are ready at the
+ * same time (Section 2.3: Q/K/V, or up and gate, of one block), in one enqueue: every dW and dX tile of the
+ * call goes into one matrix-multiply launch, longest contraction first, and layers that share their quantized
+ * input (same xq pointer, tokens and d_in) share its transposed copy.  Per layer the results are those of
+ * sbn_sparse_ternary_linear_backward, bit for bit.  HOST arrays of device pointers / sizes, one entry per
+ * layer, meanings as above (dX[i] or dW[i] may be NULL; packed, gamma, xq, sx entries may be NULL where the
+ * single call allows it); all layers share N, M and flags.
+ * workspace >= sum over layers of sbn_workspace_bytes(SBN_OP_BACKWARD, ...).
+ */
+enum { SBN_BACKWARD_GROUP_MAX = 8 };
+sbn_status sbn_sparse_ternary_linear_backward_grouped(int count, const void *const *dY, const int64_t *tokens,
+                                                      const int64_t *d_in, const int64_t *d_out, int N, int M,
+                                                      const void *const *packed, const float *const *gamma,
+                                                      const int8_t *const *xq, const float *const *sx,
+                                                      void *const *dX, void *const *dW, int flags,
+                                                      void *workspace, size_t ws_bytes, void *stream);
+
 /* Test hook, not timed: expands `packed` to dense W_eff (int8 [d_out, d_in]) and the 0/1 mask
  * (uint8 [d_out, d_in]); either output may be NULL. */
 sbn_status sbn_unpack(const void *packed, int64_t d_out, int64_t d_in, int N, int M,

@@ -55,6 +55,9 @@ def _load():
     lib.sbn_sparse_ternary_linear_grouped.argtypes = [cint, pp, pi64, pi64, pi64, cint, cint, pp, pp, pp, cint, vp, sz, vp]
     lib.sbn_sparse_ternary_linear_backward.restype = cint
     lib.sbn_sparse_ternary_linear_backward.argtypes = [vp, i64, i64, i64, cint, cint, vp, vp, vp, vp, vp, vp, cint, vp, sz, vp]
+    lib.sbn_sparse_ternary_linear_backward_grouped.restype = cint
+    lib.sbn_sparse_ternary_linear_backward_grouped.argtypes = [cint, pp, pi64, pi64, pi64, cint, cint, pp, pp, pp, pp, pp, pp, cint,
+                                                               vp, sz, vp]
     lib.sbn_unpack.restype = cint
     lib.sbn_unpack.argtypes = [vp, i64, i64, cint, cint, vp, vp, vp]
     lib.sbn_convert_packed.restype = cint
@@ -129,7 +132,7 @@ def sbn_quantize_mask_pack(W_latent, N: int, M: int, packed, gamma, workspace, l
 def _ptr_array(tensors):
     arr = (ctypes.c_void_p * len(tensors))()
     for i, t in enumerate(tensors):
-        arr[i] = t.data_ptr() if not isinstance(t, int) else t
+        arr[i] = None if t is None else (t.data_ptr() if not isinstance(t, int) else t)
     return arr
 
 
@@ -227,6 +230,42 @@ def sbn_sparse_ternary_linear_backward(dY, packed, gamma, xq, sx, N: int, M: int
                                                    (SBN_BWD_ACCUMULATE if accumulate else 0) | (SBN_BWD_MASK_DW if mask_dw else 0),
                                                    _ptr(workspace), workspace.numel() * workspace.element_size(),
                                                    _stream()), "sbn_sparse_ternary_linear_backward")
+
+
+class BackwardGroup:
+    """Host-side argument arrays of sbn_sparse_ternary_linear_backward_grouped, marshalled once and reusable.
+    Lists hold one entry per layer; entries of dX_list / dW_list may be None."""
+
+    def __init__(self, dY_list, packed_list, gamma_list, xq_list, sx_list, N, M, workspace, d_in_list, dX_list, dW_list,
+                 accumulate=False, mask_dw=False):
+        for dY in dY_list:
+            if dY.dtype != torch.bfloat16:
+                raise TypeError("dY must be bf16")
+        self.count = len(dY_list)
+        self.dY = _ptr_array(dY_list)
+        self.tokens = _i64_array([d.shape[0] for d in dY_list])
+        self.d_out = _i64_array([d.shape[1] for d in dY_list])
+        self.d_in = _i64_array(list(d_in_list))
+        self.packed, self.gamma = _ptr_array(packed_list), _ptr_array(gamma_list)
+        self.xq, self.sx = _ptr_array(xq_list), _ptr_array(sx_list)
+        self.dX, self.dW = _ptr_array(dX_list), _ptr_array(dW_list)
+        self.flags = (SBN_BWD_ACCUMULATE if accumulate else 0) | (SBN_BWD_MASK_DW if mask_dw else 0)
+        self.N, self.M, self.workspace = N, M, workspace
+        self.keep = (dY_list, packed_list, gamma_list, xq_list, sx_list, dX_list, dW_list)
+
+    def run(self):
+        ws = self.workspace
+        _check(_lib.sbn_sparse_ternary_linear_backward_grouped(self.count, self.dY, self.tokens, self.d_in, self.d_out, self.N,
+                                                               self.M, self.packed, self.gamma, self.xq, self.sx, self.dX,
+                                                               self.dW, self.flags, _ptr(ws), ws.numel() * ws.element_size(),
+                                                               _stream()),
+               "sbn_sparse_ternary_linear_backward_grouped")
+
+
+def sbn_sparse_ternary_linear_backward_grouped(dY_list, packed_list, gamma_list, xq_list, sx_list, N, M, workspace, d_in_list,
+                                               dX_list, dW_list, accumulate=False, mask_dw=False):
+    BackwardGroup(dY_list, packed_list, gamma_list, xq_list, sx_list, N, M, workspace, d_in_list, dX_list, dW_list, accumulate,
+                  mask_dw).run()
 
 
 def sbn_unpack(packed, d_out: int, d_in: int, N: int, M: int, W_eff=None, mask=None):

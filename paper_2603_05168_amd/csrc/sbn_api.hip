@@ -299,6 +299,38 @@ sbn_status sbn_sparse_ternary_linear_backward(const void *dY, int64_t tokens, in
                            ws_bytes, static_cast<hipStream_t>(stream));
 }
 
+sbn_status sbn_sparse_ternary_linear_backward_grouped(int count, const void *const *dY, const int64_t *tokens,
+                                                      const int64_t *d_in, const int64_t *d_out, int N, int M,
+                                                      const void *const *packed, const float *const *gamma,
+                                                      const int8_t *const *xq, const float *const *sx, void *const *dX,
+                                                      void *const *dW, int flags, void *workspace, size_t ws_bytes,
+                                                      void *stream)
+{
+    if (count <= 0 || count > SBN_BACKWARD_GROUP_MAX) return SBN_EINVAL;
+    if (!dY || !tokens || !d_in || !d_out || !packed || !gamma || !xq || !sx || !dX || !dW || !workspace) return SBN_EINVAL;
+    if (flags & ~(SBN_BWD_ACCUMULATE | SBN_BWD_MASK_DW)) return SBN_EINVAL;
+    if (!aligned(workspace, 256)) return SBN_EALIGN;
+    Pattern pat;
+    BackwardItem items[SBN_BACKWARD_GROUP_MAX];
+    size_t used = 0;
+    for (int i = 0; i < count; ++i) {
+        if (!dY[i] || tokens[i] <= 0 || (!dX[i] && !dW[i])) return SBN_EINVAL;
+        if (dX[i] && (!packed[i] || !gamma[i])) return SBN_EINVAL;
+        if (dW[i] && (!xq[i] || !sx[i])) return SBN_EINVAL;
+        if ((flags & SBN_BWD_MASK_DW) && dW[i] && !packed[i]) return SBN_EINVAL;
+        sbn_status st = check_shape(d_out[i], d_in[i], N, M, pat);
+        if (st != SBN_OK) return st;
+        if (!aligned(dY[i], 16) || (dX[i] && !aligned(dX[i], 16)) || (dW[i] && !aligned(dW[i], 16)) || (xq[i] && !aligned(xq[i], 16)))
+            return SBN_EALIGN;
+        if (d_in[i] % 8 != 0 || d_out[i] % 8 != 0) return SBN_EUNSUPPORTED;
+        items[i] = BackwardItem{dY[i], tokens[i], d_in[i], d_out[i], packed[i], gamma[i], xq[i], sx[i], dX[i], dW[i],
+                                static_cast<uint8_t *>(workspace) + used};
+        used += backward_workspace_bytes(tokens[i], d_out[i], d_in[i]);
+        if (used > ws_bytes) return SBN_ESIZE;
+    }
+    return launch_backward_grouped(count, items, pat, flags, static_cast<hipStream_t>(stream));
+}
+
 sbn_status sbn_mask_flips(const void *packed_a, const void *packed_b, int64_t d_out, int64_t d_in, int N, int M,
                           uint64_t *flips_out, void *workspace, size_t ws_bytes, void *stream)
 {

@@ -6,6 +6,9 @@
 // structure lies along d_in, which is not the contracted dimension of either product, so the sparse
 // instruction does not apply.  One "NT" GEMM kernel serves both; small layout kernels put the
 // operands contraction-major first (ternary values and int8 activations are exact in bf16).
+#include <algorithm>
+#include <vector>
+
 #include "sbn_internal.hpp"
 #include "sbn_mfma.hpp"
 
@@ -254,17 +257,26 @@ __device__ __forceinline__ void bf16_wave_epilogue(const GemmBf16Args &g, const 
 // tiles of the second fill the multiprocessors the first leaves idle in its last round (dW of a
 // 2560 x 2560 layer is 200 tiles for 512 block slots).  Each range starts at a multiple of 8 (the
 // blocks in between exit at once), which keeps block index mod 8 = XCD for the tile order below.
+// one launch covers the tiles of up to GB_GROUP_MAX products: product p owns the blocks [block0[p], block0[p + 1])
+constexpr int GB_GROUP_MAX = 8;
 struct GemmBf16Group {
-    GemmBf16Args g[2];
-    int block0[3];
+    GemmBf16Args g[GB_GROUP_MAX];
+    int block0[GB_GROUP_MAX + 1];
     int count;
 };
+
+__device__ __forceinline__ int bf16_product_of_block(const GemmBf16Group &grp)
+{
+    int prob = 0;
+    while (prob + 1 < grp.count && (int)blockIdx.x >= grp.block0[prob + 1]) ++prob;
+    return prob;
+}
 
 __global__ void __launch_bounds__(256, 2) gemm_bf16_nt_kernel(GemmBf16Group grp)
 {
     __shared__ __attribute__((aligned(16))) uint8_t ldsP[GB_N * GROW];
     __shared__ __attribute__((aligned(16))) uint8_t ldsQ[GB_M * GROW];
-    const int prob = (grp.count > 1 && (int)blockIdx.x >= grp.block0[1]) ? 1 : 0;
+    const int prob = bf16_product_of_block(grp);
     const GemmBf16Args &g = grp.g[prob];
     int tn, tm;
     if (!bf16_tile_of_block(g, (int)blockIdx.x - grp.block0[prob], tn, tm)) return;
@@ -391,7 +403,7 @@ constexpr int GD_LDS = 2 * GD_STAGE;
 __global__ void __launch_bounds__(512) gemm_bf16_dma_kernel(GemmBf16Group grp)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t dlds[];
-    const int prob = (grp.count > 1 && (int)blockIdx.x >= grp.block0[1]) ? 1 : 0;
+    const int prob = bf16_product_of_block(grp);
     const GemmBf16Args &g = grp.g[prob];
     int tn, tm;
     if (!bf16_tile_of_block(g, (int)blockIdx.x - grp.block0[prob], tn, tm)) return;
@@ -497,40 +509,52 @@ GemmBf16Args make_bf16_args(const uint16_t *P, int64_t ldp, int N, const uint16_
 }
 
 // one launch for one or two products; the one with the longer contraction goes first
+// Products of one launch, longest contraction first: the long tiles start at once and the short ones fill
+// the multiprocessors they leave idle.
 sbn_status launch_gemm_bf16(int count, const GemmBf16Args *args, hipStream_t stream)
 {
-    GemmBf16Group grp;
-    grp.count = count;
-    const bool swap = count == 2 && args[1].K > args[0].K;
-    // the DMA kernel takes whole 64-k stages and 16-byte aligned rows; anything else takes the register-prefetch kernel
-    bool dma = true;
-    for (int i = 0; i < count; ++i)
-        dma = dma && args[i].K % GD_K == 0 && args[i].ldp % 8 == 0 && args[i].ldq % 8 == 0 && aligned(args[i].P, 16) && aligned(args[i].Q, 16);
-    int blocks = 0;
-    for (int i = 0; i < count; ++i) {
-        grp.g[i] = args[swap ? 1 - i : i];
+    for (int first = 0; first < count; first += GB_GROUP_MAX) {
+        GemmBf16Group grp;
+        grp.count = count - first < GB_GROUP_MAX ? count - first : GB_GROUP_MAX;
+        int order[GB_GROUP_MAX];
+        for (int i = 0; i < grp.count; ++i) order[i] = first + i;
+        std::stable_sort(order, order + grp.count, [&](int a, int b) { return args[a].K > args[b].K; });
+        // the DMA kernel takes whole 64-k stages and 16-byte aligned rows; anything else takes the register-prefetch kernel
+        bool dma = true;
+        for (int i = 0; i < grp.count; ++i) {
+            const GemmBf16Args &a = args[order[i]];
+            dma = dma && a.K % GD_K == 0 && a.ldp % 8 == 0 && a.ldq % 8 == 0 && aligned(a.P, 16) && aligned(a.Q, 16);
+        }
+        int blocks = 0;
+        for (int i = 0; i < grp.count; ++i) {
+            grp.g[i] = args[order[i]];
+            if (dma) {
+                grp.g[i].tiles_n = (int)ceil_div(grp.g[i].N, GD_N);
+                grp.g[i].tiles_m = (int)ceil_div(grp.g[i].M, GD_M);
+            }
+            grp.block0[i] = blocks;
+            blocks += (grp.g[i].tiles_n * grp.g[i].tiles_m + 7) / 8 * 8;   // eight equal shares, one per XCD
+        }
+        for (int i = grp.count; i <= GB_GROUP_MAX; ++i) grp.block0[i] = blocks;
+        for (int i = grp.count; i < GB_GROUP_MAX; ++i) grp.g[i] = grp.g[0];
         if (dma) {
-            grp.g[i].tiles_n = (int)ceil_div(grp.g[i].N, GD_N);
-            grp.g[i].tiles_m = (int)ceil_div(grp.g[i].M, GD_M);
+            static thread_local bool raised = false;
+            if (!raised) {
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_bf16_dma_kernel),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, GD_LDS);
+                if (e != hipSuccess) { set_hip_error(e, "hipFuncSetAttribute"); return SBN_EHIP; }
+                raised = true;
+            }
+            hipLaunchKernelGGL(gemm_bf16_dma_kernel, dim3(blocks), dim3(512), GD_LDS, stream, grp);
+            sbn_status st = check_launch("gemm_bf16_dma_kernel");
+            if (st != SBN_OK) return st;
+        } else {
+            hipLaunchKernelGGL(gemm_bf16_nt_kernel, dim3(blocks), dim3(256), 0, stream, grp);
+            sbn_status st = check_launch("gemm_bf16_nt_kernel");
+            if (st != SBN_OK) return st;
         }
-        grp.block0[i] = blocks;
-        blocks += (grp.g[i].tiles_n * grp.g[i].tiles_m + 7) / 8 * 8;   // eight equal shares, one per XCD
     }
-    for (int i = count; i < 3; ++i) grp.block0[i] = blocks;
-    if (count == 1) grp.g[1] = grp.g[0];
-    if (dma) {
-        static thread_local bool raised = false;
-        if (!raised) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_bf16_dma_kernel),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, GD_LDS);
-            if (e != hipSuccess) { set_hip_error(e, "hipFuncSetAttribute"); return SBN_EHIP; }
-            raised = true;
-        }
-        hipLaunchKernelGGL(gemm_bf16_dma_kernel, dim3(blocks), dim3(512), GD_LDS, stream, grp);
-        return check_launch("gemm_bf16_dma_kernel");
-    }
-    hipLaunchKernelGGL(gemm_bf16_nt_kernel, dim3(blocks), dim3(256), 0, stream, grp);
-    return check_launch("gemm_bf16_nt_kernel");
+    return SBN_OK;
 }
 
 inline int64_t pad8(int64_t x) { return (x + 7) / 8 * 8; }
@@ -547,76 +571,93 @@ size_t backward_workspace_bytes(int64_t tokens, int64_t d_out, int64_t d_in)
            align_up((size_t)d_out * ((d_in + 31) / 32) * 4, 256);
 }
 
+// Backward products of `count` layers in one pass: the layout kernels of every layer, then ONE matrix-multiply
+// launch (per GB_GROUP_MAX products) over all dW and dX tiles.  Layers that share their quantized input (Q/K/V,
+// up/gate) share its transpose.
+sbn_status launch_backward_grouped(int count, const BackwardItem *items, const Pattern &pat, int flags, hipStream_t stream)
+{
+    const int accumulate = (flags & SBN_BWD_ACCUMULATE) != 0;
+    std::vector<GemmBf16Args> products;
+    std::vector<const uint16_t *> xt_of(count, nullptr);
+    products.reserve(2 * count);
+    sbn_status st;
+    for (int i = 0; i < count; ++i) {
+        const BackwardItem &it = items[i];
+        const int64_t tokens = it.tokens, d_in = it.d_in, d_out = it.d_out;
+        uint8_t *ws = static_cast<uint8_t *>(it.workspace);
+        uint16_t *wt = reinterpret_cast<uint16_t *>(ws);
+        ws += align_up((size_t)d_in * pad8(d_out) * 2, 256);
+        int8_t *w8 = reinterpret_cast<int8_t *>(ws);
+        ws += align_up((size_t)d_out * d_in, 256);
+        uint16_t *dyt = reinterpret_cast<uint16_t *>(ws);
+        ws += align_up((size_t)d_out * pad8(tokens) * 2, 256);
+        uint16_t *xt = reinterpret_cast<uint16_t *>(ws);
+        ws += align_up((size_t)d_in * pad8(tokens) * 2, 256);
+        uint32_t *mask_bits = reinterpret_cast<uint32_t *>(ws);
+        const uint16_t *dy = static_cast<const uint16_t *>(it.dY);
+
+        if (it.dX) {
+            const int64_t ldw = pad8(d_out);
+            if (pat.N == 2 && pat.M == 4 && d_in % CHUNK == 0) {
+                dim3 grid((unsigned)(d_in / CHUNK), (unsigned)ceil_div(d_out, 64));
+                hipLaunchKernelGGL(unpack_transpose_kernel, grid, dim3(256), 0, stream, static_cast<const uint8_t *>(it.packed),
+                                   (int)d_out, (int)d_in, wt, ldw);
+                st = check_launch("unpack_transpose_kernel");
+            } else {
+                st = launch_expand_groups(it.packed, d_out, d_in, pat, w8, stream);
+                if (st != SBN_OK) return st;
+                dim3 grid((unsigned)ceil_div(d_in, 64), (unsigned)ceil_div(d_out, 64));
+                hipLaunchKernelGGL(transpose_i8_kernel, grid, dim3(256), 0, stream, w8, d_out, d_in, wt, ldw);
+                st = check_launch("transpose_i8_kernel");
+            }
+            if (st != SBN_OK) return st;
+            // dX[t, k] = gamma * sum_o dY[t, o] * W_eff^T[k, o]
+            products.push_back(make_bf16_args(wt, ldw, (int)d_in, dy, d_out, (int)tokens, (int)d_out, static_cast<uint16_t *>(it.dX),
+                                              d_in, it.gamma, 0));
+        }
+        if (it.dW) {
+            const int64_t ldt = pad8(tokens);
+            {
+                dim3 grid((unsigned)ceil_div(d_out, 64), (unsigned)ceil_div(tokens, 64));
+                hipLaunchKernelGGL(transpose_scale_dy_kernel, grid, dim3(256), 0, stream, dy, it.sx, tokens, d_out, dyt, ldt);
+                st = check_launch("transpose_scale_dy_kernel");
+                if (st != SBN_OK) return st;
+            }
+            const uint16_t *xts = nullptr;   // an earlier layer of the call already transposed the same activations
+            for (int j = 0; j < i && !xts; ++j)
+                if (xt_of[j] && items[j].xq == it.xq && items[j].tokens == tokens && items[j].d_in == d_in) xts = xt_of[j];
+            if (!xts) {
+                dim3 grid((unsigned)ceil_div(d_in, 64), (unsigned)ceil_div(tokens, 64));
+                hipLaunchKernelGGL(transpose_i8_kernel, grid, dim3(256), 0, stream, it.xq, tokens, d_in, xt, ldt);
+                st = check_launch("transpose_i8_kernel");
+                if (st != SBN_OK) return st;
+                xts = xt;
+            }
+            xt_of[i] = xts;
+            // dW[o, k] = sum_t (dY/s_x)^T[o, t] * xq^T[k, t]; both operands are zero for t in [tokens, ldt)
+            GemmBf16Args a = make_bf16_args(xts, ldt, (int)d_in, dyt, ldt, (int)d_out, (int)ldt, static_cast<uint16_t *>(it.dW), d_in,
+                                            nullptr, accumulate);
+            if (flags & SBN_BWD_MASK_DW) {
+                // ablation variant: only the weights of the current mask receive the new gradient term
+                st = launch_mask_bitplane(it.packed, d_out, d_in, pat, mask_bits, stream);
+                if (st != SBN_OK) return st;
+                a.mask = mask_bits;
+                a.mask_wpr = (int)((d_in + 31) / 32);
+            }
+            products.push_back(a);
+        }
+    }
+    // all products are independent of each other (dX reads W_eff^T and dY, dW reads the two transposes)
+    return launch_gemm_bf16((int)products.size(), products.data(), stream);
+}
+
 sbn_status launch_backward(const void *dY, int64_t tokens, int64_t d_in, int64_t d_out, const Pattern &pat,
                            const void *packed, const float *gamma, const int8_t *xq, const float *sx, void *dX,
                            void *dW, int flags, void *workspace, size_t ws_bytes, hipStream_t stream)
 {
     (void)ws_bytes;
-    uint8_t *ws = static_cast<uint8_t *>(workspace);
-    uint16_t *wt = reinterpret_cast<uint16_t *>(ws);
-    ws += align_up((size_t)d_in * pad8(d_out) * 2, 256);
-    int8_t *w8 = reinterpret_cast<int8_t *>(ws);
-    ws += align_up((size_t)d_out * d_in, 256);
-    uint16_t *dyt = reinterpret_cast<uint16_t *>(ws);
-    ws += align_up((size_t)d_out * pad8(tokens) * 2, 256);
-    uint16_t *xt = reinterpret_cast<uint16_t *>(ws);
-    ws += align_up((size_t)d_in * pad8(tokens) * 2, 256);
-    uint32_t *mask_bits = reinterpret_cast<uint32_t *>(ws);
-    const int accumulate = (flags & SBN_BWD_ACCUMULATE) != 0;
-    const uint16_t *dy = static_cast<const uint16_t *>(dY);
-    sbn_status st;
-
-    GemmBf16Args products[2];
-    int nprod = 0;
-    if (dX) {
-        const int64_t ldw = pad8(d_out);
-        if (pat.N == 2 && pat.M == 4 && d_in % CHUNK == 0) {
-            dim3 grid((unsigned)(d_in / CHUNK), (unsigned)ceil_div(d_out, 64));
-            hipLaunchKernelGGL(unpack_transpose_kernel, grid, dim3(256), 0, stream, static_cast<const uint8_t *>(packed),
-                               (int)d_out, (int)d_in, wt, ldw);
-            st = check_launch("unpack_transpose_kernel");
-        } else {
-            st = launch_expand_groups(packed, d_out, d_in, pat, w8, stream);
-            if (st != SBN_OK) return st;
-            dim3 grid((unsigned)ceil_div(d_in, 64), (unsigned)ceil_div(d_out, 64));
-            hipLaunchKernelGGL(transpose_i8_kernel, grid, dim3(256), 0, stream, w8, d_out, d_in, wt, ldw);
-            st = check_launch("transpose_i8_kernel");
-        }
-        if (st != SBN_OK) return st;
-        // dX[t, k] = gamma * sum_o dY[t, o] * W_eff^T[k, o]
-        products[nprod++] = make_bf16_args(wt, ldw, (int)d_in, dy, d_out, (int)tokens, (int)d_out, static_cast<uint16_t *>(dX),
-                                           d_in, gamma, 0);
-    }
-    if (dW) {
-        const int64_t ldt = pad8(tokens);
-        {
-            dim3 grid((unsigned)ceil_div(d_out, 64), (unsigned)ceil_div(tokens, 64));
-            hipLaunchKernelGGL(transpose_scale_dy_kernel, grid, dim3(256), 0, stream, dy, sx, tokens, d_out, dyt, ldt);
-            st = check_launch("transpose_scale_dy_kernel");
-            if (st != SBN_OK) return st;
-        }
-        {
-            dim3 grid((unsigned)ceil_div(d_in, 64), (unsigned)ceil_div(tokens, 64));
-            hipLaunchKernelGGL(transpose_i8_kernel, grid, dim3(256), 0, stream, xq, tokens, d_in, xt, ldt);
-            st = check_launch("transpose_i8_kernel");
-            if (st != SBN_OK) return st;
-        }
-        // dW[o, k] = sum_t (dY/s_x)^T[o, t] * xq^T[k, t]; both operands are zero for t in [tokens, ldt)
-        products[nprod] = make_bf16_args(xt, ldt, (int)d_in, dyt, ldt, (int)d_out, (int)ldt, static_cast<uint16_t *>(dW), d_in,
-                                         nullptr, accumulate);
-        if (flags & SBN_BWD_MASK_DW) {
-            // ablation variant: only the weights of the current mask receive the new gradient term
-            st = launch_mask_bitplane(packed, d_out, d_in, pat, mask_bits, stream);
-            if (st != SBN_OK) return st;
-            products[nprod].mask = mask_bits;
-            products[nprod].mask_wpr = (int)((d_in + 31) / 32);
-        }
-        ++nprod;
-    }
-    // both products in one launch: they are independent (dX reads W_eff^T and dY, dW reads the two transposes)
-    st = launch_gemm_bf16(nprod, products, stream);
-    if (st != SBN_OK) return st;
-    return SBN_OK;
+    BackwardItem it{dY, tokens, d_in, d_out, packed, gamma, xq, sx, dX, dW, workspace};
+    return launch_backward_grouped(1, &it, pat, flags, stream);
 }
 
 }  // namespace sbn

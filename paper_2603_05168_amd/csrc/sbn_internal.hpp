@@ -103,6 +103,17 @@ sbn_status launch_ceiling_probe(int kind, void *buf, size_t bytes, int iters, do
 
 // ---- backward (sbn_backward.hip) ---------------------------------------------------------------
 size_t backward_workspace_bytes(int64_t tokens, int64_t d_out, int64_t d_in);
+struct BackwardItem {
+    const void *dY;
+    int64_t tokens, d_in, d_out;
+    const void *packed;
+    const float *gamma;
+    const int8_t *xq;
+    const float *sx;
+    void *dX, *dW;
+    void *workspace;   // this layer's share, backward_workspace_bytes(tokens, d_out, d_in)
+};
+sbn_status launch_backward_grouped(int count, const BackwardItem *items, const Pattern &pat, int flags, hipStream_t stream);
 sbn_status launch_backward(const void *dY, int64_t tokens, int64_t d_in, int64_t d_out,
                            const Pattern &pat, const void *packed, const float *gamma,
                            const int8_t *xq, const float *sx, void *dX, void *dW, int flags,

@@ -25,6 +25,7 @@ def declared_functions():
 def test_header_declares_the_boundary():
     names = declared_functions()
     for must in ("sbn_quantize_mask_pack", "sbn_sparse_ternary_linear", "sbn_sparse_ternary_linear_backward",
+                 "sbn_sparse_ternary_linear_backward_grouped",
                  "sbn_packed_bytes", "sbn_workspace_bytes", "sbn_unpack", "sbn_last_error"):
         assert must in names
 
@@ -109,6 +110,21 @@ def test_argument_errors_come_before_any_launch(sbn):
     assert lib.sbn_sparse_ternary_linear_backward(vp(A), i64(8), i64(256), i64(256), ci(2), ci(4), vp(A), vp(A), vp(A),
                                                   vp(A), vp(A), vp(A), ci(4), vp(A), sz(1 << 24), vp(0)) == sbn.SBN_EINVAL
     assert lin(d_in=200, path=sbn.SBN_PATH_DENSE_MFMA) == sbn.SBN_EUNSUPPORTED   # dense MFMA rows are multiples of 64
+    # grouped backward: count out of range, null array, a layer that asks for nothing, short workspace, misaligned dY
+    lib.sbn_sparse_ternary_linear_backward_grouped.restype = ctypes.c_int
+    def bwd_grouped(count=2, dy=(A, A), dx=(A, A), dw=(A, A), ws=1 << 26, arrays_ok=True, flags=0):
+        P = lambda vals: (vp * 2)(*[vp(v) if v else None for v in vals])   # noqa: E731
+        I = lambda v: (i64 * 2)(v, v)                                       # noqa: E731
+        return lib.sbn_sparse_ternary_linear_backward_grouped(
+            ci(count), P(dy), I(8), I(256), I(256), ci(2), ci(4), P((A, A)), P((A, A)), P((A, A)), P((A, A)),
+            P(dx) if arrays_ok else None, P(dw), ci(flags), vp(A), sz(ws), vp(0))
+    assert bwd_grouped(count=0) == sbn.SBN_EINVAL
+    assert bwd_grouped(count=9) == sbn.SBN_EINVAL
+    assert bwd_grouped(arrays_ok=False) == sbn.SBN_EINVAL
+    assert bwd_grouped(dx=(A, 0), dw=(A, 0)) == sbn.SBN_EINVAL
+    assert bwd_grouped(flags=8) == sbn.SBN_EINVAL
+    assert bwd_grouped(dy=(A, A + 2)) == sbn.SBN_EALIGN
+    assert bwd_grouped(ws=1 << 12) == sbn.SBN_ESIZE
     # mask flips: null input, misaligned count, short workspace
     lib.sbn_mask_flips.restype = ctypes.c_int
     flips = lambda **kw: lib.sbn_mask_flips(  # noqa: E731

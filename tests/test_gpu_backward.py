@@ -86,6 +86,86 @@ def test_backward_gradient_masked_variant(N, M, tokens, shape):
     assert_rel_rms(dWa, r_dw + basef.astype(np.float64), BWD_TOL, "masked dW accumulate")
 
 
+def _forward_state(W, X, N, M):
+    s = sbn()
+    d_out, d_in = W.shape
+    T = X.shape[0]
+    packed, gamma = hip_pack(W, N, M)
+    Y = torch.empty(T, d_out, dtype=torch.float32, device=DEV)
+    xq = torch.empty(T, d_in, dtype=torch.int8, device=DEV)
+    sx = torch.empty(T, dtype=torch.float32, device=DEV)
+    ws = s.new_workspace(s.sbn_workspace_bytes(s.SBN_OP_LINEAR, T, d_out, d_in, N, M))
+    s.sbn_sparse_ternary_linear(X.to(DEV), packed, gamma, Y, N, M, ws, xq_out=xq, sx_out=sx)
+    return packed, gamma, xq, sx
+
+
+@pytest.mark.parametrize("N,M", [(2, 4), (6, 8)])
+@pytest.mark.parametrize("tokens,d_in,d_outs,share", [(192, 256, (256, 320, 256), True), (77, 136, (104, 520), True),
+                                                      (130, 392, (520, 136, 264, 128), False)])
+def test_backward_grouped_matches_single_calls_and_oracle(N, M, tokens, d_in, d_outs, share):
+    # several layers in one call (Q/K/V or up/gate share the quantized input: one transpose serves them);
+    # per layer the outputs equal those of the single call bit for bit, and the oracle within tolerance
+    s = sbn()
+    n = len(d_outs)
+    X = [sbn_synth.activations(tokens, d_in, 960 + (0 if share else i)) for i in range(n)]
+    W = [sbn_synth.latent_weight(d_outs[i], d_in, 970 + i) for i in range(n)]
+    dY = [sbn_synth.grad_output(tokens, d_outs[i], 980 + i).to(DEV) for i in range(n)]
+    st = []
+    for i in range(n):
+        if share and i > 0:
+            packed, gamma = hip_pack(W[i], N, M)
+            st.append((packed, gamma, st[0][2], st[0][3]))      # the same xq / sx tensors as layer 0
+        else:
+            st.append(_forward_state(W[i], X[i], N, M))
+    nan = float("nan")
+    dX = [torch.full((tokens, d_in), nan, dtype=torch.bfloat16, device=DEV) for _ in range(n)]
+    dW = [torch.full((d_outs[i], d_in), nan, dtype=torch.bfloat16, device=DEV) for i in range(n)]
+    dX[-1] = None                                               # one layer asks for dW only
+    ws = s.new_workspace(sum(s.sbn_workspace_bytes(s.SBN_OP_BACKWARD, tokens, d, d_in, N, M) for d in d_outs))
+    s.sbn_sparse_ternary_linear_backward_grouped(dY, [t[0] for t in st], [t[1] for t in st], [t[2] for t in st],
+                                                 [t[3] for t in st], N, M, ws, [d_in] * n, dX, dW)
+    torch.cuda.synchronize()
+    for i in range(n):
+        sX = torch.full((tokens, d_in), nan, dtype=torch.bfloat16, device=DEV) if dX[i] is not None else None
+        sW = torch.full((d_outs[i], d_in), nan, dtype=torch.bfloat16, device=DEV)
+        ws1 = s.new_workspace(s.sbn_workspace_bytes(s.SBN_OP_BACKWARD, tokens, d_outs[i], d_in, N, M))
+        s.sbn_sparse_ternary_linear_backward(dY[i], st[i][0], st[i][1], st[i][2], st[i][3], N, M, ws1, d_in, dX=sX, dW=sW)
+        torch.cuda.synchronize()
+        assert torch.equal(dW[i].view(torch.int16), sW.view(torch.int16))
+        if sX is not None:
+            assert torch.equal(dX[i].view(torch.int16), sX.view(torch.int16))
+        _, gamma, Weff, _ = oracle_pack(W[i], N, M)
+        r_dw = oracle.backward_dw(dY[i].float().cpu().numpy(), st[i][2].cpu().numpy(), st[i][3].cpu().numpy())
+        assert_rel_rms(dW[i].float().cpu().numpy(), r_dw, BWD_TOL, f"grouped dW {i}")
+        if dX[i] is not None:
+            assert_rel_rms(dX[i].float().cpu().numpy(), oracle.backward_dx(dY[i].float().cpu().numpy(), Weff, gamma), BWD_TOL,
+                           f"grouped dX {i}")
+
+
+def test_backward_grouped_more_products_than_one_launch_holds():
+    # five layers = ten products: two matrix-multiply launches; accumulate flag applies to every layer
+    s = sbn()
+    tokens, d_in, n = 64, 128, 5
+    X = sbn_synth.activations(tokens, d_in, 990)
+    W = [sbn_synth.latent_weight(64 + 8 * i, d_in, 991 + i) for i in range(n)]
+    dY = [sbn_synth.grad_output(tokens, 64 + 8 * i, 996 + i).to(DEV) for i in range(n)]
+    st0 = _forward_state(W[0], X, 2, 4)
+    st = [st0] + [hip_pack(W[i], 2, 4) + (st0[2], st0[3]) for i in range(1, n)]
+    base = [(torch.randn(64 + 8 * i, d_in, generator=torch.Generator().manual_seed(i)) * 0.1).to(torch.bfloat16) for i in range(n)]
+    dW = [b.clone().to(DEV) for b in base]
+    dX = [torch.empty(tokens, d_in, dtype=torch.bfloat16, device=DEV) for _ in range(n)]
+    ws = s.new_workspace(sum(s.sbn_workspace_bytes(s.SBN_OP_BACKWARD, tokens, 64 + 8 * i, d_in, 2, 4) for i in range(n)))
+    s.sbn_sparse_ternary_linear_backward_grouped(dY, [t[0] for t in st], [t[1] for t in st], [t[2] for t in st],
+                                                 [t[3] for t in st], 2, 4, ws, [d_in] * n, dX, dW, accumulate=True)
+    torch.cuda.synchronize()
+    xq, sx = st0[2].cpu().numpy(), st0[3].cpu().numpy()
+    for i in range(n):
+        _, gamma, Weff, _ = oracle_pack(W[i], 2, 4)
+        r_dw = oracle.backward_dw(dY[i].float().cpu().numpy(), xq, sx) + base[i].float().numpy().astype(np.float64)
+        assert_rel_rms(dW[i].float().cpu().numpy(), r_dw, BWD_TOL, f"dW {i}")
+        assert_rel_rms(dX[i].float().cpu().numpy(), oracle.backward_dx(dY[i].float().cpu().numpy(), Weff, gamma), BWD_TOL, f"dX {i}")
+
+
 def test_config5_training_step_block_matrices():
     # configs[4]: batch 8 x seq 2048 = 16384 tokens through the block's three matrix shapes.
     # dX is checked on sampled token rows, dW on sampled weight rows (each entry an exact fp64 sum).
