@@ -306,7 +306,10 @@ def main():
         roofline_gemv = {"kernel": "gemv_stream_kernel", "workload": "64 x (6912x2560 packed 2:4), T=8, grouped",
                          "bound": "hbm", "achieved": best["stream_gbps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                          "frac": best["frac_hbm"], "traffic": measured_traffic("gemv_stream_kernel", "64x6912x2560"),
-                         "algorithmic_bytes": R * best["packed_bytes"]}
+                         "algorithmic_bytes": R * best["packed_bytes"],
+                         # the same kernel per matrix shape and token count (packed weight bytes only: at eight tokens the
+                         # fp32 outputs add 5 % of bytes that the figure does not count)
+                         "frac_by_workload": {k: v["frac_hbm"] for k, v in gemv_rows.items()}}
 
     # ------------------------------------------------------------------ configs[3]: quantize_mask_pack sweep, 210 matrices
     if "pack" in sections:
