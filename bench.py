@@ -351,10 +351,13 @@ def main():
         Tt = 8 * 2048
         mats = sbn_synth.BLOCK_MATRICES
         Wt = [sbn_synth.latent_weight(a, b, sbn_synth.seed_for(5, i), device=dev) for i, (_, a, b) in enumerate(mats)]
-        Xh = sbn_synth.activations(Tt, H, sbn_synth.seed_for(5, 20), device=dev)
-        Xo = sbn_synth.activations(Tt, H, sbn_synth.seed_for(5, 21), device=dev)
-        Xf = sbn_synth.activations(Tt, F, sbn_synth.seed_for(5, 22), device=dev)
-        xin = [Xh, Xh, Xh, Xo, Xh, Xh, Xf]
+        # the block's four distinct layer inputs: attention input (Q, K, V), attention output (O), FFN input (up, gate),
+        # FFN hidden (down); each is quantized once per step and the layers that share it reuse the int8 copy
+        inputs = [sbn_synth.activations(Tt, H, sbn_synth.seed_for(5, 20), device=dev),
+                  sbn_synth.activations(Tt, H, sbn_synth.seed_for(5, 21), device=dev),
+                  sbn_synth.activations(Tt, H, sbn_synth.seed_for(5, 23), device=dev),
+                  sbn_synth.activations(Tt, F, sbn_synth.seed_for(5, 22), device=dev)]
+        input_of = [0, 0, 0, 1, 2, 2, 3]                     # per matrix of BLOCK_MATRICES
         dYh = sbn_synth.grad_output(Tt, H, sbn_synth.seed_for(5, 30), device=dev)
         dYf = sbn_synth.grad_output(Tt, F, sbn_synth.seed_for(5, 31), device=dev)
         pk = [torch.empty(sbn.sbn_packed_bytes(a, b, N, M), dtype=torch.uint8, device=dev) for _, a, b in mats]
@@ -362,13 +365,10 @@ def main():
         gl = [gm[i:i + 1] for i in range(len(mats))]
         wsp = sbn.new_workspace(sbn.sbn_workspace_bytes(sbn.SBN_OP_QUANTIZE_MASK_PACK, len(mats), F, H, N, M), dev)
         batch = sbn.PackBatch(Wt, N, M, pk, gl, wsp)
-        Yh = torch.empty(Tt, H, dtype=torch.float32, device=dev)
-        Yf = torch.empty(Tt, F, dtype=torch.float32, device=dev)
-        xqh = torch.empty(Tt, H, dtype=torch.int8, device=dev)
-        xqf = torch.empty(Tt, F, dtype=torch.int8, device=dev)
-        sxb = torch.empty(Tt, dtype=torch.float32, device=dev)
-        dXh = torch.empty(Tt, H, dtype=torch.bfloat16, device=dev)
-        dXf = torch.empty(Tt, F, dtype=torch.bfloat16, device=dev)
+        Yl = [torch.empty(Tt, a, dtype=torch.float32, device=dev) for _, a, b in mats]
+        xql = [torch.empty(Tt, x.shape[1], dtype=torch.int8, device=dev) for x in inputs]
+        sxl = [torch.empty(Tt, dtype=torch.float32, device=dev) for _ in inputs]
+        dXl = [torch.empty(Tt, b, dtype=torch.bfloat16, device=dev) for _, a, b in mats]
         dWl = [torch.empty(a, b, dtype=torch.bfloat16, device=dev) for _, a, b in mats]
         wsl = sbn.new_workspace(sbn.sbn_workspace_bytes(sbn.SBN_OP_LINEAR, Tt, F, F, N, M), dev)
         wsb = sbn.new_workspace(sbn.sbn_workspace_bytes(sbn.SBN_OP_BACKWARD, Tt, F, F, N, M), dev)
@@ -376,28 +376,30 @@ def main():
         def remask():
             batch.run()
 
-        def forward_backward(do_fwd=True, do_bwd=True):
+        def forward():
+            for j, x in enumerate(inputs):
+                sbn.sbn_act_quant(x, xql[j], sxl[j])
+            for i in range(len(mats)):
+                j = input_of[i]
+                sbn.sbn_sparse_ternary_linear(None, pk[i], gl[i], Yl[i], N, M, wsl, xq_out=xql[j], sx_out=sxl[j],
+                                              path=sbn.SBN_PATH_SMFMAC)
+
+        def backward_layer_by_layer():
             for i, (_, a, b) in enumerate(mats):
-                Y = Yf if a == F else Yh
-                xq_ = xqf if b == F else xqh
-                if do_fwd:
-                    sbn.sbn_sparse_ternary_linear(xin[i], pk[i], gl[i], Y, N, M, wsl, xq_out=xq_, sx_out=sxb,
-                                                  path=sbn.SBN_PATH_SMFMAC)
-                if do_bwd:
-                    sbn.sbn_sparse_ternary_linear_backward(dYf if a == F else dYh, pk[i], gl[i], xq_, sxb, N, M, wsb, b,
-                                                           dX=dXf if b == F else dXh, dW=dWl[i])
+                j = input_of[i]
+                sbn.sbn_sparse_ternary_linear_backward(dYf if a == F else dYh, pk[i], gl[i], xql[j], sxl[j], N, M, wsb, b,
+                                                       dX=dXl[i], dW=dWl[i])
 
         # backward in the order of backpropagation, the layers whose output gradients arrive together in one call:
         # down; up and gate; O; Q, K and V (layers of a call that share their input share its transpose)
-        dXg = {i: torch.empty(Tt, b, dtype=torch.bfloat16, device=dev) for i, (_, a, b) in enumerate(mats)}
         groups = []
         for idx in ([6], [4, 5], [3], [0, 1, 2]):
             wsg = sbn.new_workspace(sum(sbn.sbn_workspace_bytes(sbn.SBN_OP_BACKWARD, Tt, mats[i][1], mats[i][2], N, M)
                                         for i in idx), dev)
             groups.append(sbn.BackwardGroup([dYf if mats[i][1] == F else dYh for i in idx], [pk[i] for i in idx],
-                                            [gl[i] for i in idx], [xqf if mats[i][2] == F else xqh for i in idx],
-                                            [sxb for _ in idx], N, M, wsg, [mats[i][2] for i in idx],
-                                            [dXg[i] for i in idx], [dWl[i] for i in idx]))
+                                            [gl[i] for i in idx], [xql[input_of[i]] for i in idx],
+                                            [sxl[input_of[i]] for i in idx], N, M, wsg, [mats[i][2] for i in idx],
+                                            [dXl[i] for i in idx], [dWl[i] for i in idx]))
 
         def backward_grouped():
             for grp in groups:
@@ -405,14 +407,14 @@ def main():
 
         def train_step():
             remask()
-            forward_backward(True, False)
+            forward()
             backward_grouped()
 
         ms_all = timed(train_step, 3, 1)
         ms_pack = timed(remask, 5, 1)
-        ms_fwd = timed(lambda: forward_backward(True, False), 3, 1)
+        ms_fwd = timed(forward, 3, 1)
         ms_bwd = timed(backward_grouped, 3, 1)
-        ms_bwd_single = timed(lambda: forward_backward(False, True), 3, 1)
+        ms_bwd_single = timed(backward_layer_by_layer, 3, 1)
         wsum = sum(a * b for _, a, b in mats)
         rows["train_step_block"] = {
             "tokens": Tt, "ms": ms_all, "remask_pack_ms": ms_pack, "forward_ms": ms_fwd, "backward_ms": ms_bwd,
@@ -424,7 +426,7 @@ def main():
         log(f"[train] block step {ms_all:.2f} ms (pack {ms_pack:.3f}, fwd {ms_fwd:.2f}, bwd {ms_bwd:.2f} in four grouped calls, "
             f"{ms_bwd_single:.2f} layer by layer); "
             f"bwd {rows['train_step_block']['backward_tflops']:.0f} TFLOP/s")
-        del Wt, Xh, Xo, Xf, dYh, dYf, Yh, Yf, dXh, dXf, dWl, wsl, wsb, groups, dXg
+        del Wt, inputs, dYh, dYf, Yl, xql, sxl, dXl, dWl, wsl, wsb, groups
         torch.cuda.empty_cache()
 
     # ------------------------------------------------------------------ plain copy of known size (scale of the HBM counters)

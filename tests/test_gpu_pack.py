@@ -44,6 +44,21 @@ def test_pack_adversarial_ties_and_zeros(N, M, dtype):
     check(sbn_synth.adversarial_weight(64, 512, 70 + N, dtype=dtype), N, M)
 
 
+@pytest.mark.parametrize("N,M", [(2, 4), (1, 4), (2, 8), (6, 8)])
+def test_pack_wide_dynamic_range(N, M):
+    # magnitudes from 2^-10 to 2^6 (bf16 exponent field with its top bit set and clear), both signs, many exact
+    # ties: every bit of the magnitude takes part in the ranking; |w| sums stay exact in fp64 whatever their order
+    g = torch.Generator().manual_seed(90 + N + M)
+    e = torch.randint(-10, 7, (256, 384), generator=g).float()
+    m = 1.0 + torch.randint(0, 4, (256, 384), generator=g).float() / 4.0
+    sgn = torch.randint(0, 2, (256, 384), generator=g).float() * 2.0 - 1.0
+    W = (sgn * m * torch.exp2(e)).to(torch.bfloat16)
+    W[5] = 96.0
+    W[6, ::3] = -0.0
+    _, Weff, mask = check(W, N, M)
+    assert (np.abs(Weff).sum(axis=1) > 0).any()
+
+
 def test_pack_all_zero_matrix_clamps_gamma():
     packed, gamma = hip_pack(torch.zeros(16, 256, dtype=torch.bfloat16), 2, 4)
     assert gamma.item() == np.float32(1e-5)
