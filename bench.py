@@ -239,9 +239,12 @@ def main():
                     sbn.sbn_sparse_ternary_linear(X, packs[r][0], packs[r][1], Yl[r], N, M, ws1, path=sbn.SBN_PATH_GEMV)
                 ms1 = timed(single, 256, 8)
                 gbps = R * pbytes / (ms * 1e-3) / 1e9
+                # every byte the decode of one matrix must move: packed weights, bf16 activations in, fp32 outputs
+                allb = pbytes + 2 * tok * b + 4 * tok * a
                 gemv_rows[f"{name}_T{tok}"] = {"stream_ms_per_matrix": ms / R, "stream_gbps": gbps,
                                                "frac_hbm": gbps / HBM_PEAK_GBPS, "single_call_us": ms1 * 1e3,
-                                               "packed_bytes": pbytes, "copies": R}
+                                               "packed_bytes": pbytes, "copies": R,
+                                               "frac_hbm_with_activation_and_output_bytes": gbps * allb / pbytes / HBM_PEAK_GBPS}
                 log(f"[gemv] {name} T={tok}: stream {gbps:.0f} GB/s ({gbps / HBM_PEAK_GBPS:.1%} of HBM peak), "
                     f"single call {ms1 * 1e3:.1f} us")
                 del Yl, ws, grp
