@@ -13,6 +13,12 @@
  *   - Return value: SBN_OK or a negative sbn_status.  All argument errors are detected before
  *     anything is launched.  After SBN_EHIP, sbn_last_error() returns the HIP error text.
  *   - Inputs must be finite; the result for NaN/Inf inputs is unspecified.
+ *   - Stream capture: every call may be recorded into a HIP graph and replayed (no memory copies or
+ *     memsets are enqueued, descriptor tables travel as kernel arguments, counters are cleared by
+ *     kernels).  Call each entry point once outside capture first: the first use of a kernel sets
+ *     function attributes and queries the device.  While a stream captures, grouped decode calls
+ *     launch the activation quantizer in front of the streaming kernel instead of fusing it (the
+ *     fused form numbers its launches on the host).  Pointers and sizes are frozen in the graph.
  *
  * Packed weight layout (the paper asks only that the N:M metadata have a defined layout; this one
  * is the library's).  b = log2(M) index bits per kept weight (none when N == M).  Each row is cut

@@ -784,6 +784,17 @@ static int gemv_spin_limit()
     return e && *e ? atoi(e) : 1 << 16;
 }
 
+// true while `stream` records into a graph (or when that cannot be told)
+static bool stream_is_capturing(hipStream_t stream)
+{
+    hipStreamCaptureStatus status = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &status) != hipSuccess) {
+        (void)hipGetLastError();
+        return true;
+    }
+    return status != hipStreamCaptureStatusNone;
+}
+
 template <bool DENSE>
 static sbn_status launch_gemv_as(int count, const LinearItem *items, hipStream_t stream)
 {
@@ -828,7 +839,9 @@ static sbn_status launch_gemv_as(int count, const LinearItem *items, hipStream_t
             for (int j = 0; j <= GEMV_STREAM_INPUTS; ++j) tab.tok0[j] = 0;
             // the kernel quantizes up to GEMV_STREAM_INPUTS distinct inputs itself; more than that (or rows too
             // long for one block's registers) go through the quantizer kernel first
-            bool fuse = true;
+            // Not under stream capture: the flags carry a per-launch number that the host hands out, and a replayed
+            // graph would present the previous replay's flags again.  A captured launch takes the quantizer kernels.
+            bool fuse = !stream_is_capturing(stream);
             int nin = 0;
             const int8_t *in_xq[GEMV_STREAM_INPUTS];
             for (int i = 0; i < n && fuse; ++i) {
