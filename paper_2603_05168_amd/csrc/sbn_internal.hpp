@@ -49,7 +49,7 @@ struct PackItem {
     float *gamma;
     int64_t d_out, d_in, ld;
 };
-constexpr int PACK_MAX_ITEMS = 48;     // matrices per launch (descriptor table travels as kernel argument)
+constexpr int PACK_MAX_ITEMS = 70;     // matrices per launch (descriptor table travels as kernel argument: 4 KB at most)
 constexpr int64_t PACK_SUM_ELEMS = 16384;  // elements reduced by one block of the absmean pass
 size_t pack_workspace_bytes(int64_t count, int64_t d_out, int64_t d_in);
 sbn_status launch_pack(int count, const PackItem *items, sbn_dtype wdt, const Pattern &pat,

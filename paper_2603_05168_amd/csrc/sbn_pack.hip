@@ -392,6 +392,7 @@ struct PackSync {
     unsigned *words;      // PACK_SYNC_WORDS per matrix, cleared before the launch (the partials are preset with them)
     int spin_limit;       // polls a block spends waiting for its ready word before it derives theta on its own
 };
+static_assert(sizeof(PackTable) + sizeof(PackSync) <= 4096, "both travel as kernel arguments");
 
 constexpr int PACK_U = 8;   // 16-byte vectors per thread: a unit = 256 threads x 8 vectors = 128 chunks = 16384 weights
 
