@@ -258,6 +258,30 @@ def test_config3_grouped_step_full_size_as_timed():
         assert np.array_equal(Y.cpu().numpy(), Y1)
 
 
+def test_prefill_longest_sequence_sampled_rows():
+    # 65536 tokens (the longest prefill of the throughput table, Section 4.3) against 6912x2560: Y holds
+    # 453 M values = 1.8 GB, so token offsets pass 2^31 bytes; the rows of the first, the last and 40 sampled
+    # tokens are compared with the oracle (each an exact int32 dot product and one rescale)
+    s = sbn()
+    T, d_out, d_in = 65536, 6912, 2560
+    W = sbn_synth.latent_weight(d_out, d_in, sbn_synth.seed_for(3, d_out))
+    packed, gamma = hip_pack(W, 2, 4)
+    Xd = sbn_synth.activations(T, d_in, sbn_synth.seed_for(3, 9), device=DEV)      # generated on the device: 335 MB
+    Y = torch.empty(T, d_out, dtype=torch.float32, device=DEV)
+    ws = s.new_workspace(s.sbn_workspace_bytes(s.SBN_OP_LINEAR, T, d_out, d_in, 2, 4))
+    s.sbn_sparse_ternary_linear(Xd, packed, gamma, Y, 2, 4, ws, path=s.SBN_PATH_SMFMAC)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([[0, 127, 128, T // 2 - 1, T // 2, T - 129, T - 1],
+                                     np.random.default_rng(11).choice(T, size=40, replace=False)]))
+    idx = torch.from_numpy(rows).to(DEV)
+    Xs = Xd[idx].float().cpu().numpy()
+    _, g, Weff, _ = oracle_pack(W, 2, 4)
+    y, *_ = oracle.sparse_ternary_linear(Xs, Weff, g)
+    assert_rel(Y[idx].cpu().numpy(), y, Y_TOL, "Y at 65536 tokens")
+    del Y, Xd, ws
+    torch.cuda.empty_cache()
+
+
 def test_sparse_and_dense_paths_agree_bitwise_full_size():
     s = sbn()
     W = sbn_synth.latent_weight(2560, 2560, sbn_synth.seed_for(3, 7))
