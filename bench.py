@@ -46,7 +46,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=100)
-    ap.add_argument("--sections", default="gemm,gemv,pack,train,dense,ceil,cpu",
+    ap.add_argument("--sections", default="gemm,gemv,pack,train,dense,seq,ceil,cpu",
                     help="comma list of: gemm (always timed), gemv, pack, train, dense, ceil, cpu, copyref")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -213,6 +213,44 @@ def main():
                 log(f"[{n8}:{m8}] {a}x{b}: {ms * 1e3:.1f} us ({rows_p[f'{a}x{b}']['tops']:.0f} TOPS dense-equivalent)")
                 del pk
             rows[key] = rows_p
+    # ------------------------------------------------------------------ the paper's throughput table, by token count
+    # Section 4.3 reports prefill at 512 ... 65536 tokens and decode at batch 64 ... 512 (other hardware, 6:8, whole
+    # model).  The same sweep for one 6912x2560 layer at 2:4: sparse kernel against the dense-ternary comparison kernel
+    # on pre-quantized activations (prefill), and one call through path selection including its quantizer (decode).
+    if "seq" in sections:
+        jF = [j for j, (a, b) in enumerate(shapes) if a == F][0]
+        by_tokens = {}
+        for Ts in (512, 1024, 2048, 4096, 8192, 16384, 32768, 65536):
+            Xs_ = sbn_synth.activations(Ts, H, sbn_synth.seed_for(3, 50), device=dev)
+            xq_ = torch.empty(Ts, H, dtype=torch.int8, device=dev)
+            sx_ = torch.empty(Ts, dtype=torch.float32, device=dev)
+            Y_ = torch.empty(Ts, F, dtype=torch.float32, device=dev)
+            ws_ = sbn.new_workspace(sbn.sbn_workspace_bytes(sbn.SBN_OP_LINEAR, Ts, F, H, N, M), dev)
+            sbn.sbn_act_quant(Xs_, xq_, sx_)
+            reps = max(3, min(100, (1 << 19) // Ts))
+            ms_s = timed(lambda: sbn.sbn_sparse_ternary_linear(None, Wp[jF][0], Wp[jF][1], Y_, N, M, ws_, xq_out=xq_, sx_out=sx_,
+                                                               path=sbn.SBN_PATH_SMFMAC), reps, 2)
+            ms_d = timed(lambda: sbn.sbn_sparse_ternary_linear(None, Wp[jF][0], Wp[jF][1], Y_, N, M, ws_, xq_out=xq_, sx_out=sx_,
+                                                               path=sbn.SBN_PATH_DENSE_MFMA), reps, 2)
+            by_tokens[str(Ts)] = {"sparse_ms": ms_s, "dense_ternary_ms_with_expand": ms_d,
+                                  "sparse_tops_dense_equiv": 2.0 * Ts * F * H / (ms_s * 1e-3) / 1e12,
+                                  "tokens_per_s_sparse": Ts / (ms_s * 1e-3), "sparse_speedup": ms_d / ms_s}
+            del Xs_, xq_, sx_, Y_, ws_
+            torch.cuda.empty_cache()
+        rows["prefill_6912x2560_by_tokens"] = by_tokens
+        log("[seq] prefill 6912x2560, sparse TOPS (speedup over dense-ternary) by tokens: " +
+            ", ".join(f"{k}: {v['sparse_tops_dense_equiv']:.0f} ({v['sparse_speedup']:.2f}x)" for k, v in by_tokens.items()))
+        by_batch = {}
+        for Tb in (16, 64, 128, 256, 512):
+            Xb = sbn_synth.activations(Tb, H, sbn_synth.seed_for(2, 60), device=dev)
+            Yb = torch.empty(Tb, F, dtype=torch.float32, device=dev)
+            wsb_ = sbn.new_workspace(sbn.sbn_workspace_bytes(sbn.SBN_OP_LINEAR, Tb, F, H, N, M), dev)
+            ms_b = timed(lambda: sbn.sbn_sparse_ternary_linear(Xb, Wp[jF][0], Wp[jF][1], Yb, N, M, wsb_), 200, 3)
+            by_batch[str(Tb)] = {"single_call_us": ms_b * 1e3, "tops_dense_equiv": 2.0 * Tb * F * H / (ms_b * 1e-3) / 1e12}
+            del Xb, Yb, wsb_
+        rows["decode_6912x2560_by_batch"] = by_batch
+        log("[seq] decode 6912x2560, one call incl. quantizer, us by batch: " +
+            ", ".join(f"{k}: {v['single_call_us']:.1f}" for k, v in by_batch.items()))
     del Ys, Xs
     torch.cuda.empty_cache()
 
