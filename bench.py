@@ -487,17 +487,19 @@ def main():
                                        ("mfma_i8", sbn.SBN_CEIL_MFMA_I8, 100, 1e12),
                                        ("mfma_bf16", sbn.SBN_CEIL_MFMA_BF16, 100, 1e12),
                                        ("hbm_read", sbn.SBN_CEIL_HBM_READ, 1, 1e9),
-                                       ("hbm_write", sbn.SBN_CEIL_HBM_WRITE, 1, 1e9)):
+                                       ("hbm_write", sbn.SBN_CEIL_HBM_WRITE, 1, 1e9),
+                                       ("lds_read", sbn.SBN_CEIL_LDS_READ, 2000, 1e9)):
             work = [0.0]
 
             def probe(kind=kind, iters=iters):
                 work[0] = sbn.sbn_ceiling_probe(kind, buf, iters)
             ms = timed(probe, 200 if unit == 1e12 else 20, 2)
             ceilings[key] = work[0] / (ms * 1e-3) / unit
-        ceilings["units"] = "TOP/s or TFLOP/s with random operands (matrix kinds), GB/s over 1 GiB (stream kinds)"
+        ceilings["units"] = "TOP/s or TFLOP/s with random operands (matrix kinds), GB/s over 1 GiB (stream kinds), GB/s of conflict-free 16-byte LDS reads summed over all multiprocessors"
         log("[ceil] sustained on this board: sparse int8 MFMA %.0f TOPS dense-equivalent, int8 MFMA %.0f TOPS, bf16 MFMA %.0f "
-            "TFLOP/s, HBM read %.0f GB/s, write %.0f GB/s" % (ceilings["smfmac_i8_dense_equiv"], ceilings["mfma_i8"],
-                                                             ceilings["mfma_bf16"], ceilings["hbm_read"], ceilings["hbm_write"]))
+            "TFLOP/s, HBM read %.0f GB/s, write %.0f GB/s, LDS read %.0f GB/s" % (
+                ceilings["smfmac_i8_dense_equiv"], ceilings["mfma_i8"], ceilings["mfma_bf16"], ceilings["hbm_read"],
+                ceilings["hbm_write"], ceilings["lds_read"]))
         del buf
         torch.cuda.empty_cache()
         roofline["measured_ceiling"] = ceilings["smfmac_i8_dense_equiv"] / 2.0   # executed ops, like `achieved`

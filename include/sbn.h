@@ -252,7 +252,8 @@ sbn_status sbn_convert_packed(const void *packed, int64_t d_out, int64_t d_in, i
  * Measurement support (not a step of the layer): enqueues one kernel that issues a single kind of work
  * at full rate, so that a benchmark can state the rate this board sustains next to the datasheet
  * peak.  Matrix kinds run `iters` rounds of 16 matrix instructions per wavefront on random operands,
- * two wavefronts per SIMD; stream kinds read or write `bytes` - 256 bytes of `buf` once.
+ * two wavefronts per SIMD; stream kinds read or write `bytes` - 256 bytes of `buf` once; the LDS kind runs
+ * `iters` rounds of 16 conflict-free 16-byte LDS reads per lane, two wavefronts per SIMD.
  *   buf       device, >= 256 bytes, 256-byte aligned (matrix kinds touch only its first word)
  *   work_out  HOST, the operations (2 per multiply-add, dense-equivalent for the sparse instruction)
  *             or bytes one call performs
@@ -262,7 +263,8 @@ typedef enum {
     SBN_CEIL_MFMA_I8 = 1,    /* v_mfma_i32_32x32x32_i8 */
     SBN_CEIL_MFMA_BF16 = 2,  /* v_mfma_f32_32x32x16_bf16 */
     SBN_CEIL_HBM_READ = 3,
-    SBN_CEIL_HBM_WRITE = 4
+    SBN_CEIL_HBM_WRITE = 4,
+    SBN_CEIL_LDS_READ = 5    /* ds_read_b128; like the matrix kinds it touches only the first word of buf */
 } sbn_ceiling;
 sbn_status sbn_ceiling_probe(int kind, void *buf, size_t bytes, int iters, double *work_out, void *stream);
 

@@ -284,7 +284,7 @@ def sbn_convert_packed(packed, d_out: int, d_in: int, N: int, M: int, to_N: int,
     _check(_lib.sbn_convert_packed(_ptr(packed), d_out, d_in, N, M, to_N, to_M, _ptr(out), _stream()), "sbn_convert_packed")
 
 
-SBN_CEIL_SMFMAC_I8, SBN_CEIL_MFMA_I8, SBN_CEIL_MFMA_BF16, SBN_CEIL_HBM_READ, SBN_CEIL_HBM_WRITE = range(5)
+SBN_CEIL_SMFMAC_I8, SBN_CEIL_MFMA_I8, SBN_CEIL_MFMA_BF16, SBN_CEIL_HBM_READ, SBN_CEIL_HBM_WRITE, SBN_CEIL_LDS_READ = range(6)
 
 
 def sbn_ceiling_probe(kind: int, buf, iters: int = 1) -> float:

@@ -362,9 +362,10 @@ sbn_status sbn_convert_packed(const void *packed, int64_t d_out, int64_t d_in, i
 
 sbn_status sbn_ceiling_probe(int kind, void *buf, size_t bytes, int iters, double *work_out, void *stream)
 {
-    if (!buf || !work_out || kind < SBN_CEIL_SMFMAC_I8 || kind > SBN_CEIL_HBM_WRITE) return SBN_EINVAL;
+    if (!buf || !work_out || kind < SBN_CEIL_SMFMAC_I8 || kind > SBN_CEIL_LDS_READ) return SBN_EINVAL;
     if (!aligned(buf, 256)) return SBN_EALIGN;
-    if (kind <= SBN_CEIL_MFMA_BF16 ? (iters <= 0 || bytes < 256) : bytes < ((size_t)1 << 20)) return SBN_EINVAL;
+    const bool streams = kind == SBN_CEIL_HBM_READ || kind == SBN_CEIL_HBM_WRITE;
+    if (streams ? bytes < ((size_t)1 << 20) : (iters <= 0 || bytes < 256)) return SBN_EINVAL;
     return launch_ceiling_probe(kind, buf, bytes, iters, work_out, static_cast<hipStream_t>(stream));
 }
 

@@ -110,6 +110,29 @@ __global__ void __launch_bounds__(256) probe_write_kernel(uint4 *buf, int64_t nv
     for (int64_t i = threadIdx.x; i < per_block; i += 256) p[i] = v;
 }
 
+// 16 LDS reads of 16 bytes per lane and round, consecutive lanes at consecutive addresses (no bank conflicts);
+// the addresses move by 16 bytes per round so that no read can be taken out of the loop.  64 KB per block, two blocks
+// per multiprocessor = two wavefronts per SIMD, as in the matrix kernels.
+constexpr int PROBE_LDS_BYTES = 64 * 1024;
+constexpr int PROBE_LDS_READS = 16;
+__global__ void __launch_bounds__(256, 2) probe_lds_kernel(int iters, int *sink)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t lds[PROBE_LDS_BYTES];
+    for (int i = threadIdx.x; i < PROBE_LDS_BYTES / 16; i += 256)
+        reinterpret_cast<uint4 *>(lds)[i] = make_uint4(mix32(i), mix32(i + 77u), blockIdx.x, threadIdx.x);
+    __syncthreads();
+    uint4 x = make_uint4(0, 0, 0, 0);
+    for (int it = 0; it < iters; ++it) {
+        uint4 v[PROBE_LDS_READS];
+#pragma unroll
+        for (int j = 0; j < PROBE_LDS_READS; ++j)
+            v[j] = *reinterpret_cast<const uint4 *>(lds + (((threadIdx.x + it) * 16) & 4095) + j * 4096);
+#pragma unroll
+        for (int j = 0; j < PROBE_LDS_READS; ++j) { x.x ^= v[j].x; x.y ^= v[j].y; x.z ^= v[j].z; x.w ^= v[j].w; }
+    }
+    if ((x.x ^ x.y ^ x.z ^ x.w) == 0x5a17c0deu) *sink = 1;
+}
+
 }  // namespace
 
 sbn_status launch_ceiling_probe(int kind, void *buf, size_t bytes, int iters, double *work_out, hipStream_t stream)
@@ -123,6 +146,12 @@ sbn_status launch_ceiling_probe(int kind, void *buf, size_t bytes, int iters, do
         else if (kind == SBN_CEIL_MFMA_I8) hipLaunchKernelGGL(probe_mma_kernel<1>, dim3(blocks), dim3(256), 0, stream, iters, sink);
         else hipLaunchKernelGGL(probe_mma_kernel<2>, dim3(blocks), dim3(256), 0, stream, iters, sink);
         return check_launch("probe_mma_kernel");
+    }
+    if (kind == SBN_CEIL_LDS_READ) {
+        const int blocks = 2 * device_cus();
+        *work_out = 16.0 * PROBE_LDS_READS * 256.0 * (double)iters * blocks;
+        hipLaunchKernelGGL(probe_lds_kernel, dim3(blocks), dim3(256), 0, stream, iters, sink);
+        return check_launch("probe_lds_kernel");
     }
     const int blocks = 8 * device_cus();
     const int64_t nvec = (int64_t)((bytes - 256) / 16) / blocks * blocks;

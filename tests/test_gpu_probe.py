@@ -17,6 +17,7 @@ def test_ceiling_probes_run_and_report_work():
                       (s.SBN_CEIL_MFMA_BF16, 2 * 32 * 32 * 16)):
         work = s.sbn_ceiling_probe(kind, buf, 3)
         assert work == per * 16 * 3 * 4 * 2 * cus
+    assert s.sbn_ceiling_probe(s.SBN_CEIL_LDS_READ, buf, 5) == 16 * 16 * 256 * 5 * 2 * cus
     work = s.sbn_ceiling_probe(s.SBN_CEIL_HBM_READ, buf, 1)
     torch.cuda.synchronize()
     assert 0 < work <= buf.numel() - 256 and work > buf.numel() - 256 - 16 * 8 * cus
