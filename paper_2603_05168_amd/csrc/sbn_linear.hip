@@ -798,7 +798,7 @@ static bool stream_is_capturing(hipStream_t stream)
 template <bool DENSE>
 static sbn_status launch_gemv_as(int count, const LinearItem *items, hipStream_t stream)
 {
-    constexpr int RT = 2;
+    constexpr int RT = 1;
     static std::atomic<unsigned> epoch{1};
     static thread_local std::vector<const int8_t *> written;   // xq buffers a quantizer kernel of this call has filled
     written.clear();
@@ -830,9 +830,10 @@ static sbn_status launch_gemv_as(int count, const LinearItem *items, hipStream_t
         const int nblocks = device_cus();
         constexpr int GEMV_STREAM_LDS = 160 * 1024 - 256;   // the kernel's counter and scales take a little static LDS
         if (plain && lds_need <= GEMV_STREAM_LDS && units >= 16 * (int64_t)nblocks) {
-            // DEPTH 4 with 8 wavefronts per block measured best among depths 2..8 and 4..16 wavefronts
-            // (more wavefronts finish their shares further apart, fewer leave too few loads in flight)
-            constexpr int DEPTH = 4, NW = 8;
+            // One row tile per unit, DEPTH 5 and 8 wavefronts per block measured best among one or two row tiles,
+            // depths 2..8 and 6..16 wavefronts (more wavefronts finish their shares further apart, fewer leave too
+            // few loads in flight; units of 16 rows balance the wavefronts better than units of 32: +2.5 to +4 %)
+            constexpr int DEPTH = 5, NW = 8;
             GemvStreamTable tab;
             tab.count = n;
             tab.nin = 0;
