@@ -57,8 +57,9 @@ __device__ __forceinline__ uint2 quantize_bf16x8(const uint4 &d, float s)
 }
 
 // ---- activation quantizer -----------------------------------------------------------------------
-// TPT threads share one token (64 = one wavefront per token for prefill, 1024 = one block per token
-// for decode, where only a handful of tokens exist).  A thread keeps its 16-byte vectors of the row
+// TPT threads share one token (256 = a block of four wavefronts per token for prefill, 1024 = a larger
+// block per token for decode, where only a handful of tokens exist; the normalising variant runs one
+// wavefront per token).  A thread keeps its 16-byte vectors of the row
 // in registers, so X is read once; the maximum magnitude is taken on the bf16 bit patterns (exact).
 // s_x = 127 / max(amax, 1e-5) is one IEEE fp32 division, x * s_x one fp32 multiply, rounding is
 // half-to-even.  Rows longer than VMAX * TPT vectors take the two-pass kernel below.
@@ -721,8 +722,12 @@ sbn_status launch_act_quant(const void *X, int64_t tokens, int64_t d_in, int8_t 
     const int nvec = (int)(d_in / 8);
     if (tokens <= 64 && nvec <= 2 * 1024) {
         hipLaunchKernelGGL((act_quant_kernel<1024, 2>), dim3((unsigned)tokens), dim3(1024), 0, stream, x, tokens, nvec, xq, sx);
-    } else if (nvec <= 16 * 64) {
-        hipLaunchKernelGGL((act_quant_kernel<64, 16>), dim3((unsigned)ceil_div(tokens, 4)), dim3(256), 0, stream, x, tokens, nvec, xq, sx);
+    } else if (nvec <= 2 * 256) {
+        // a block of four wavefronts per token (measured against one or two wavefronts per token with longer loops: same
+        // kernel time, but the step that follows starts 1-2 % earlier)
+        hipLaunchKernelGGL((act_quant_kernel<256, 2>), dim3((unsigned)tokens), dim3(256), 0, stream, x, tokens, nvec, xq, sx);
+    } else if (nvec <= 4 * 256) {
+        hipLaunchKernelGGL((act_quant_kernel<256, 4>), dim3((unsigned)tokens), dim3(256), 0, stream, x, tokens, nvec, xq, sx);
     } else {
         hipLaunchKernelGGL(act_quant_two_pass_kernel, dim3((unsigned)ceil_div(tokens, 4)), dim3(256), 0, stream, x, tokens, nvec, xq, sx);
     }
