@@ -58,8 +58,7 @@ __device__ __forceinline__ uint2 quantize_bf16x8(const uint4 &d, float s)
 
 // ---- activation quantizer -----------------------------------------------------------------------
 // TPT threads share one token (256 = a block of four wavefronts per token for prefill, 1024 = a larger
-// block per token for decode, where only a handful of tokens exist; the normalising variant runs one
-// wavefront per token).  A thread keeps its 16-byte vectors of the row
+// block per token for decode, where only a handful of tokens exist).  A thread keeps its 16-byte vectors of the row
 // in registers, so X is read once; the maximum magnitude is taken on the bf16 bit patterns (exact).
 // s_x = 127 / max(amax, 1e-5) is one IEEE fp32 division, x * s_x one fp32 multiply, rounding is
 // half-to-even.  Rows longer than VMAX * TPT vectors take the two-pass kernel below.
@@ -740,9 +739,12 @@ sbn_status launch_rmsnorm_act_quant(const void *X, const float *gain, float eps,
     const uint4 *x = static_cast<const uint4 *>(X);
     uint4 *n = static_cast<uint4 *>(xn);
     const int nvec = (int)(d_in / 8);
-    if (nvec <= 16 * 64 && tokens > 64) {
-        hipLaunchKernelGGL((rmsnorm_act_quant_kernel<64, 16>), dim3((unsigned)ceil_div(tokens, 4)), dim3(256), 0, stream, x, gain, eps,
-                           tokens, nvec, xq, sx, n);
+    if (nvec <= 2 * 256 && tokens > 64) {
+        hipLaunchKernelGGL((rmsnorm_act_quant_kernel<256, 2>), dim3((unsigned)tokens), dim3(256), 0, stream, x, gain, eps, tokens, nvec,
+                           xq, sx, n);
+    } else if (nvec <= 4 * 256 && tokens > 64) {
+        hipLaunchKernelGGL((rmsnorm_act_quant_kernel<256, 4>), dim3((unsigned)tokens), dim3(256), 0, stream, x, gain, eps, tokens, nvec,
+                           xq, sx, n);
     } else if (nvec <= 2 * 1024) {
         hipLaunchKernelGGL((rmsnorm_act_quant_kernel<1024, 2>), dim3((unsigned)tokens), dim3(1024), 0, stream, x, gain, eps, tokens,
                            nvec, xq, sx, n);
