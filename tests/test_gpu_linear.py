@@ -404,7 +404,8 @@ def test_config2_streaming_decode_full_size_as_timed(tokens, shape):
 @pytest.mark.parametrize("tokens", [1, 5, 64, 65, 300])
 @pytest.mark.parametrize("d_in", [8, 256, 2560, 6912, 8200, 16520])
 def test_act_quant_entry_all_kernel_variants(tokens, d_in):
-    # block-per-token (decode), wavefront-per-token (prefill) and the two-pass kernel for very long rows
+    # a block per token (1024 threads: decode; 256 threads with two or four vectors per thread: prefill) and the
+    # two-pass kernel for very long rows
     s = sbn()
     X = sbn_synth.adversarial_activations(tokens, d_in, 840 + tokens) if d_in >= 256 else sbn_synth.activations(tokens, d_in, 841)
     xq = torch.full((tokens, d_in), 77, dtype=torch.int8, device=DEV)
