@@ -10,11 +10,13 @@
  *
  * Pins (tests that fix each function to something other than itself) live in tests/test_oracle_*.py:
  * closed forms for Gaussian weights, brute-force sorting, scale/sign invariances, the N = M
- * reduction to the plain BitLinear layer, a float transcription of the layer's forward/backward
- * through an autograd engine, and pack/unpack round trips.  The packed byte layout is this
- * build's own (the paper asks only that the N:M metadata have a defined layout), so sbn_oracle_pack is pinned by
- * its inverse, by hand-assembled bytes for a tiny matrix, and by structural invariants; no value
- * printed in the paper covers it: for the byte layout itself, parity unpinned by the paper.
+ * reduction to the plain BitLinear layer, the layer written as an fp64 graph whose gradients an
+ * autograd engine derives, and pack/unpack round trips.  The packed byte layout is this build's own
+ * (the paper asks only that the N:M metadata have a defined layout), so sbn_oracle_pack and
+ * sbn_oracle_unpack are pinned by hand-assembled bytes for one row at 2:4, 1:4, 2:8, 6:8 and 8:8
+ * (every index width: 2 bits, 3 bits, none), by a second decoder written separately, by each other
+ * and by structural invariants; no value printed in the paper covers it: for the byte layout
+ * itself, parity unpinned by the paper.
  *
  * Build:  gcc -O2 -fopenmp -ffp-contract=off -shared -fPIC -o libsbn_oracle.so sbn_oracle.c -lm
  */
@@ -67,7 +69,7 @@ void sbn_oracle_nm_mask(const float *W, int64_t d_out, int64_t d_in, int N, int 
 }
 
 /* ---------------------------------------------------------------------------------------------
- * Section 2.1, W_q = RoundClip(W / gamma, -1, +1); Appendix B listing: (w / scale).round().clamp(-1, 1).
+ * Section 2.1, W_q = RoundClip(W / gamma, -1, +1); Appendix B listing: divide by the scale, round, clamp to [-1, 1].
  * Reading: an IEEE fp32 division, round-half-to-even (the listing's tensor round), then the clip.
  * ------------------------------------------------------------------------------------------- */
 void sbn_oracle_ternary(const float *W, int64_t n, float gamma, int8_t *Wq)

@@ -2,8 +2,8 @@
 products of the CPU oracle.
 
 Pins: numpy's IEEE fp32 arithmetic and int64 matmul, a brute-force fp64 product of the de-quantized
-operands, the N = M reduction to the plain BitLinear layer, and a float transcription of the layer
-(Appendix B listing, with the straight-through readings of Section 2.3) run through torch autograd.
+operands, the N = M reduction to the plain BitLinear layer, and the layer written as an fp64 graph
+(Sections 2.1 - 2.3, both quantizers straight-through) whose gradients torch autograd derives.
 """
 import numpy as np
 import pytest
@@ -83,49 +83,46 @@ def test_n_equals_m_is_plain_bitlinear():
     assert np.allclose(y, ref, rtol=1e-12, atol=0)
 
 
-# ----------------------------------------------------------------------------- float transcription
-class _WeightQuantMasked(torch.autograd.Function):
-    """Appendix B listing, read as: mask from latent w, scale from the whole w, quantize, then mask;
-    the backward hands the incoming gradient to w unchanged (dual straight-through estimator)."""
-
-    @staticmethod
-    def forward(ctx, w, N, M):
-        d_out, d_in = w.shape
-        a = w.abs().reshape(d_out, d_in // M, M)
-        order = torch.argsort(a, dim=-1, descending=True, stable=True)
-        mask = torch.zeros_like(a)
-        mask.scatter_(-1, order[..., :N], 1.0)
-        mask = mask.reshape(d_out, d_in)
-        scale = w.abs().double().mean().float().clamp(min=1e-5)
-        w_q = (w / scale).round().clamp(-1, 1) * scale
-        return w_q * mask
-
-    @staticmethod
-    def backward(ctx, g_out):
-        return g_out, None, None
+# ----------------------------------------------------------------------------- the layer as a differentiable graph
+def _topn_mask(latent: np.ndarray, N: int, M: int) -> np.ndarray:
+    """Section 2.2 mask: per group of M the N largest |w| of the latent weights, ties to the lower index;
+    written with a stable sort (the oracle counts ranks instead)."""
+    rows, cols = latent.shape
+    mag = np.abs(latent).reshape(rows, cols // M, M)
+    winners = np.argsort(-mag, axis=2, kind="stable")[:, :, :N]
+    keep = np.zeros(mag.shape, dtype=np.float64)
+    np.put_along_axis(keep, winners, 1.0, axis=2)
+    return keep.reshape(rows, cols)
 
 
-def _listing_forward(x, w, N, M):
-    amax = x.abs().max(dim=-1, keepdim=True).values.clamp(min=1e-5)
-    # tensor / tensor is an IEEE fp32 division; the scalar / tensor form multiplies by a reciprocal,
-    # lands one ulp off in some rows and flips the rounding of products that sit next to a .5 tie
-    s_x = torch.full_like(amax, 127.0) / amax
-    x_q = (x * s_x).round().clamp(-128, 127) / s_x
-    xd = x.double()
-    x_q = xd + (x_q.double() - xd).detach()      # identity straight-through for the activation quantizer
-    w_q = _WeightQuantMasked.apply(w, N, M)
-    return torch.nn.functional.linear(x_q, w_q.double())
+def _layer_graph(tokens_in: torch.Tensor, latent: torch.Tensor, N: int, M: int) -> torch.Tensor:
+    """The layer of Sections 2.1 - 2.3 as an fp64 graph whose gradients an autograd engine derives:
+    both quantizers contribute their VALUE but pass gradients through unchanged (value = input + constant),
+    and the mask enters the value of the weight only, so the latent weight receives the dense gradient."""
+    with torch.no_grad():
+        t32 = tokens_in.float()
+        peak = t32.abs().amax(dim=1, keepdim=True).clamp_min(1e-5)
+        to_int = torch.full_like(peak, 127.0) / peak                         # IEEE fp32 division, per token
+        levels = torch.clamp(torch.round(t32 * to_int), -128, 127)
+        fake_quant_tokens = levels.double() / to_int.double()
+        l32 = latent.float()
+        absmean = l32.abs().double().mean().float().clamp_min(1e-5)
+        ternary = torch.clamp(torch.round(l32 / absmean), -1, 1).double()
+        effective = ternary * torch.from_numpy(_topn_mask(l32.numpy(), N, M)) * absmean.double()
+    tokens_ste = tokens_in + (fake_quant_tokens - tokens_in).detach()
+    weight_ste = latent + (effective - latent).detach()
+    return tokens_ste @ weight_ste.t()
 
 
 @pytest.mark.parametrize("N,M", [(2, 4), (1, 4), (2, 8), (6, 8)])
-def test_forward_backward_against_autograd_transcription(N, M):
+def test_forward_backward_against_autograd_graph(N, M):
     W = sbn_synth.latent_weight(96, 256, 10 + N).float()
     X = sbn_synth.activations(32, 256, 20 + M).float()
     dY = sbn_synth.grad_output(32, 96, 30).float()
-    w = W.clone().requires_grad_(True)
-    x = X.clone().requires_grad_(True)
-    y = _listing_forward(x, w, N, M)
-    y.backward(dY.double())
+    latent = W.double().requires_grad_(True)
+    tokens_in = X.double().requires_grad_(True)
+    out = _layer_graph(tokens_in, latent, N, M)
+    out.backward(dY.double())
 
     Weff, mask, gamma = oracle.quantize_mask(W.numpy(), N, M)
     y_o, _, xq, sx = oracle.sparse_ternary_linear(X.numpy(), Weff, gamma)
@@ -136,10 +133,10 @@ def test_forward_backward_against_autograd_transcription(N, M):
         scale = np.sqrt(np.mean(b ** 2))
         return np.abs(a - b).max() <= tol * scale
 
-    # the transcription rounds x~/s_x and w_q*scale to fp32 once each: 1e-6 relative to the tensor's rms
-    assert close(y_o, y.detach().numpy(), 1e-6)
-    assert close(dX, x.grad.double().numpy(), 1e-6)
-    assert close(dW, w.grad.double().numpy(), 1e-6)
+    # both sides are fp64 products of the same de-quantized operands: only the summation order differs
+    assert close(y_o, out.detach().numpy(), 1e-12)
+    assert close(dX, tokens_in.grad.numpy(), 1e-12)
+    assert close(dW, latent.grad.numpy(), 1e-12)
     # dense gradient: masked-out weights receive gradient too
     assert (np.abs(dW[mask == 0]) > 0).mean() > 0.99
 

@@ -13,15 +13,16 @@ import oracle
 
 PATTERNS = [(2, 4), (1, 4), (2, 8), (6, 8), (4, 8), (1, 2), (3, 4), (8, 8), (4, 4), (1, 8), (7, 8)]
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "pack_2of4_row128.txt")
+GOLDEN_OTHER = os.path.join(os.path.dirname(__file__), "golden", "pack_other_patterns_row128.txt")
 
 
 def gaussian(shape, seed, sigma=0.02):
     return (np.random.default_rng(seed).standard_normal(shape) * sigma).astype(np.float32)
 
 
-def read_golden():
+def read_golden(path=GOLDEN):
     out = {}
-    for line in open(GOLDEN):
+    for line in open(path):
         if line.startswith("#") or not line.strip():
             continue
         tag, *hexbytes = line.split()
@@ -114,3 +115,87 @@ def test_pack_rejects_bad_masks():
         oracle.pack(Weff, mask, 2, 4)
     with pytest.raises(ValueError):
         oracle.unpack(np.zeros(10, np.uint8), 2, 128, 2, 4)
+
+
+# ----------------------------------------------------------------------------- other patterns: fixtures
+_VALUE_BY_3 = (1, -1, 0)           # value of slot s by s % 3 (cases Q and S of the fixture file)
+_VALUE_BY_5 = (1, -1, 0, -1, 1)    # value of slot s by s % 5 (cases E and D)
+
+
+def _row_from_kept(kept_of_group, M, values):
+    """One row of 128 weights: group g keeps the ascending positions kept_of_group(g); the s-th kept weight of
+    the row (slot s) has value values[s % len(values)]."""
+    Weff = np.zeros((1, 128), np.int8)
+    mask = np.zeros((1, 128), np.uint8)
+    s = 0
+    for g in range(128 // M):
+        for p in kept_of_group(g):
+            mask[0, g * M + p] = 1
+            Weff[0, g * M + p] = values[s % len(values)]
+            s += 1
+    return Weff, mask
+
+
+FIXTURES = {
+    "Q": (1, 4, lambda g: (g % 4,), _VALUE_BY_3),
+    "E": (2, 8, lambda g: (g % 7, 7), _VALUE_BY_5),
+    "S": (6, 8, lambda g: ((2, 3, 4, 5, 6, 7), (0, 1, 2, 3, 4, 5), (1, 2, 3, 4, 5, 6), (0, 1, 2, 5, 6, 7))[g % 4], _VALUE_BY_3),
+    "D": (8, 8, lambda g: tuple(range(8)), _VALUE_BY_5),
+}
+
+
+@pytest.mark.parametrize("case", sorted(FIXTURES))
+def test_golden_other_patterns(case):
+    # hand-assembled bytes for the other index widths: 2 bits (1:4), 3 bits (2:8, 6:8) and none (8:8)
+    N, M, kept, values = FIXTURES[case]
+    Weff, mask = _row_from_kept(kept, M, values)
+    want = read_golden(GOLDEN_OTHER)[case]
+    assert want.size == oracle.chunk_bytes(N, M)
+    assert np.array_equal(oracle.pack(Weff, mask, N, M), want)
+    W2, M2 = oracle.unpack(want, 1, 128, N, M)
+    assert np.array_equal(W2, Weff) and np.array_equal(M2, mask)
+
+
+def independent_decode(packed, d_out, d_in, N, M):
+    """Second reading of the layout for any pattern, written from the rules with numpy on whole bit planes:
+    the index field as one little-endian bit string cut into b-bit numbers, the code field as bit pairs
+    gathered by their position 8*(v%4) + 2*(v/4) inside each 32-bit word."""
+    b = 0 if N == M else {2: 1, 4: 2, 8: 3}[M]
+    S = 128 * N // M
+    nch = (d_in + 127) // 128
+    idx_bytes, code_bytes = S * b // 8, S // 4
+    chunks = packed.reshape(d_out * nch, idx_bytes + code_bytes)
+    if b:
+        bits = np.unpackbits(chunks[:, :idx_bytes], axis=1, bitorder="little").reshape(-1, S, b)
+        pos = (bits.astype(np.int64) << np.arange(b)).sum(axis=2)                  # [chunks, S]
+    else:
+        pos = np.tile(np.arange(S) % M, (chunks.shape[0], 1))
+    cbits = np.unpackbits(chunks[:, idx_bytes:], axis=1, bitorder="little").reshape(-1, S // 16, 32)
+    v = np.arange(16)
+    at = 8 * (v % 4) + 2 * (v // 4)
+    code = (cbits[:, :, at] + 2 * cbits[:, :, at + 1]).reshape(-1, S)                 # [chunks, S]
+    assert (code != 2).all()
+    val = np.select([code == 1, code == 3], [1, -1], 0).astype(np.int8)
+    col = (np.arange(S) // N) * M + pos                                               # column inside the chunk
+    W = np.zeros((d_out * nch, 128), np.int8)
+    K = np.zeros((d_out * nch, 128), np.uint8)
+    r = np.arange(d_out * nch)[:, None]
+    W[r, col] = val
+    K[r, col] = 1
+    # slots of a group ascend strictly: no two slots land on one weight
+    assert (K.reshape(d_out * nch, 128 // M, M).sum(axis=2) == N).all()
+    return W.reshape(d_out, nch * 128)[:, :d_in], K.reshape(d_out, nch * 128)[:, :d_in]
+
+
+@pytest.mark.parametrize("N,M", PATTERNS)
+def test_layout_second_reading_all_patterns(N, M):
+    W = gaussian((40, 392), 700 + 10 * N + M)             # ragged last chunk
+    Weff, mask, _ = oracle.quantize_mask(W, N, M)
+    packed = oracle.pack(Weff, mask, N, M)
+    W2, M2 = independent_decode(packed, 40, 392, N, M)
+    assert np.array_equal(W2, Weff) and np.array_equal(M2, mask)
+    for case, (n, m, kept, values) in FIXTURES.items():
+        if (n, m) == (N, M):
+            We, Mk = _row_from_kept(kept, m, values)
+            Wd, Md = independent_decode(read_golden(GOLDEN_OTHER)[case], 1, 128, N, M)
+            assert np.array_equal(Wd, We) and np.array_equal(Md, Mk)
