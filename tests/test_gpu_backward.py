@@ -185,3 +185,88 @@ def test_config5_training_step_block_matrices():
         assert np.array_equal(r_xq, xq) and np.array_equal(r_sx, sx)
         r_dw = oracle.backward_dw(np.ascontiguousarray(dY[:, orow].float().numpy()), r_xq, r_sx)
         assert_rel_rms(dW[orow], r_dw, BWD_TOL, f"dW {d_out}x{d_in}")
+
+
+def test_config5_training_step_as_timed():
+    # configs[4] in the launch configuration the benchmark times: per step the seven matrices of a block are
+    # remasked in one batched call, each of the block's four distinct inputs is quantized once, the seven forwards
+    # run on the shared int8 copies, and the backward runs as four grouped calls (down; up+gate; O; Q+K+V).
+    # Integers in full (packed bytes, gamma, int8 activations, scales); Y and dX on sampled token rows, dW on
+    # sampled weight rows against the fp64 oracle; the grouped calls equal the single calls bit for bit.
+    s = sbn()
+    N, M, T = 2, 4, 8 * 2048
+    H, F = sbn_synth.HIDDEN, sbn_synth.FFN
+    mats = sbn_synth.BLOCK_MATRICES
+    rng = np.random.default_rng(55)
+    Wt = [sbn_synth.latent_weight(a, b, sbn_synth.seed_for(5, i)) for i, (_, a, b) in enumerate(mats)]
+    inputs = [sbn_synth.activations(T, H, sbn_synth.seed_for(5, 20)), sbn_synth.activations(T, H, sbn_synth.seed_for(5, 21)),
+              sbn_synth.activations(T, H, sbn_synth.seed_for(5, 23)), sbn_synth.activations(T, F, sbn_synth.seed_for(5, 22))]
+    input_of = [0, 0, 0, 1, 2, 2, 3]
+    dYh = sbn_synth.grad_output(T, H, sbn_synth.seed_for(5, 30))
+    dYf = sbn_synth.grad_output(T, F, sbn_synth.seed_for(5, 31))
+    Wd = [w.to(DEV) for w in Wt]
+    Xd = [x.to(DEV) for x in inputs]
+    dYd = {H: dYh.to(DEV), F: dYf.to(DEV)}
+    pk = [torch.full((s.sbn_packed_bytes(a, b, N, M),), 0xAA, dtype=torch.uint8, device=DEV) for _, a, b in mats]
+    gm = torch.zeros(len(mats), dtype=torch.float32, device=DEV)
+    gl = [gm[i:i + 1] for i in range(len(mats))]
+    wsp = s.new_workspace(s.sbn_workspace_bytes(s.SBN_OP_QUANTIZE_MASK_PACK, len(mats), F, H, N, M))
+    nan = float("nan")
+    Yl = [torch.full((T, a), nan, dtype=torch.float32, device=DEV) for _, a, b in mats]
+    xql = [torch.zeros(T, x.shape[1], dtype=torch.int8, device=DEV) for x in inputs]
+    sxl = [torch.zeros(T, dtype=torch.float32, device=DEV) for _ in inputs]
+    dXl = [torch.full((T, b), nan, dtype=torch.bfloat16, device=DEV) for _, a, b in mats]
+    dWl = [torch.full((a, b), nan, dtype=torch.bfloat16, device=DEV) for _, a, b in mats]
+    wsl = s.new_workspace(s.sbn_workspace_bytes(s.SBN_OP_LINEAR, T, F, F, N, M))
+    batch = s.PackBatch(Wd, N, M, pk, gl, wsp)
+    groups = []
+    for idx in ([6], [4, 5], [3], [0, 1, 2]):
+        wsg = s.new_workspace(sum(s.sbn_workspace_bytes(s.SBN_OP_BACKWARD, T, mats[i][1], mats[i][2], N, M) for i in idx))
+        groups.append(s.BackwardGroup([dYd[mats[i][1]] for i in idx], [pk[i] for i in idx], [gl[i] for i in idx],
+                                      [xql[input_of[i]] for i in idx], [sxl[input_of[i]] for i in idx], N, M, wsg,
+                                      [mats[i][2] for i in idx], [dXl[i] for i in idx], [dWl[i] for i in idx]))
+    for _ in range(2):   # two steps back to back on the same buffers and workspaces, as the timed loop does
+        batch.run()
+        for j, x in enumerate(Xd):
+            s.sbn_act_quant(x, xql[j], sxl[j])
+        for i in range(len(mats)):
+            j = input_of[i]
+            s.sbn_sparse_ternary_linear(None, pk[i], gl[i], Yl[i], N, M, wsl, xq_out=xql[j], sx_out=sxl[j], path=s.SBN_PATH_SMFMAC)
+        for grp in groups:
+            grp.run()
+    torch.cuda.synchronize()
+
+    refs = [oracle_pack(W, N, M) for W in Wt]                     # (packed, gamma, W_eff, mask)
+    for i in range(len(mats)):
+        assert gm[i].item() == refs[i][1], f"gamma of {mats[i][0]}"
+        assert np.array_equal(pk[i].cpu().numpy(), refs[i][0]), f"packed bytes of {mats[i][0]}"
+    quant = [oracle.act_quant(x.float().numpy()) for x in inputs]
+    for j in range(len(inputs)):
+        assert np.array_equal(xql[j].cpu().numpy(), quant[j][0]) and np.array_equal(sxl[j].cpu().numpy(), quant[j][1])
+    trow = np.unique(np.concatenate([[0, 127, 128, T - 1], rng.choice(T, 20, replace=False)]))
+    tsel = torch.from_numpy(trow).to(DEV)
+    wsb = s.new_workspace(s.sbn_workspace_bytes(s.SBN_OP_BACKWARD, T, F, F, N, M))
+    for i, (name, a, b) in enumerate(mats):
+        _, gamma, Weff, _ = refs[i]
+        r_xq, r_sx = quant[input_of[i]]
+        dY = dYf if a == F else dYh
+        # forward on the shared int8 copy
+        r_acc = oracle.acc(Weff, r_xq[trow])
+        r_y = oracle.rescale(r_acc, gamma, r_sx[trow], None)
+        got = Yl[i][tsel].cpu().numpy()
+        assert (np.abs(got - r_y) <= 1e-3 * np.abs(r_y)).all(), f"Y of {name}"
+        # dX on sampled token rows, dW on sampled weight rows
+        r_dx = oracle.backward_dx(np.ascontiguousarray(dY[trow].float().numpy()), Weff, gamma)
+        assert_rel_rms(dXl[i][tsel].float().cpu().numpy(), r_dx, BWD_TOL, f"dX of {name}")
+        orow = np.unique(np.concatenate([[0, a - 1], rng.choice(a, 4, replace=False)]))
+        r_dw = oracle.backward_dw(np.ascontiguousarray(dY[:, orow].float().numpy()), r_xq, r_sx)
+        assert_rel_rms(dWl[i][torch.from_numpy(orow).to(DEV)].float().cpu().numpy(), r_dw, BWD_TOL, f"dW of {name}")
+        # the same layer through the single backward call: identical bits
+        sX = torch.full((T, b), nan, dtype=torch.bfloat16, device=DEV)
+        sW = torch.full((a, b), nan, dtype=torch.bfloat16, device=DEV)
+        s.sbn_sparse_ternary_linear_backward(dYd[a], pk[i], gl[i], xql[input_of[i]], sxl[input_of[i]], N, M, wsb, b, dX=sX, dW=sW)
+        torch.cuda.synchronize()
+        assert torch.equal(dXl[i].view(torch.int16), sX.view(torch.int16)), f"grouped dX of {name} differs from the single call"
+        assert torch.equal(dWl[i].view(torch.int16), sW.view(torch.int16)), f"grouped dW of {name} differs from the single call"
+        del sX, sW
+    torch.cuda.empty_cache()

@@ -220,46 +220,61 @@ def test_gemm_adversarial_inputs(path_name):
     check_forward(W, X, 2, 4, getattr(s, path_name))
 
 
+_CONFIG3_ORACLE = {}
+
+
+def _config3_oracle(d_out):
+    """Oracle forward of configs[2] for one matrix, all 4096 tokens (dense brute-force accumulate), computed once."""
+    if d_out not in _CONFIG3_ORACLE:
+        W = sbn_synth.latent_weight(d_out, 2560, sbn_synth.seed_for(3, d_out))
+        X = sbn_synth.activations(4096, 2560, sbn_synth.seed_for(3, 1))
+        _, g, Weff, _ = oracle_pack(W, 2, 4)
+        y, acc, xq, sx = oracle.sparse_ternary_linear(X.float().numpy(), Weff, g)
+        _CONFIG3_ORACLE[d_out] = (W, X, y, acc, xq, sx)
+    return _CONFIG3_ORACLE[d_out]
+
+
 @pytest.mark.parametrize("path_name", ["SBN_PATH_SMFMAC", "SBN_PATH_DENSE_MFMA"])
 @pytest.mark.parametrize("d_out", [2560, 6912])
 def test_config3_prefill_gemm_full_size(path_name, d_out):
-    # configs[2]: X 4096x2560 against 2560x2560 and 6912x2560; activations checked in full,
-    # accumulators and Y on 96 sampled token rows (each row is d_out exact dot products)
+    # configs[2]: X 4096x2560 against 2560x2560 and 6912x2560, both matrix paths: int8 activations, scales and
+    # the int32 accumulators of ALL 4096 token rows bit-exact, every Y within 1e-3
     s = sbn()
-    W = sbn_synth.latent_weight(d_out, 2560, sbn_synth.seed_for(3, d_out))
-    X = sbn_synth.activations(4096, 2560, sbn_synth.seed_for(3, 1))
-    rows = np.sort(np.random.default_rng(3).choice(4096, size=96, replace=False))
-    rows[:3] = (0, 1, 4095)
-    check_forward(W, X, 2, 4, getattr(s, path_name), token_sample=np.unique(rows))
+    W, X, r_y, r_acc, r_xq, r_sx = _config3_oracle(d_out)
+    packed, gamma = hip_pack(W, 2, 4)
+    Y, acc, xq, sx = hip_linear(X, packed, gamma, d_out, 2, 4, getattr(s, path_name))
+    assert np.array_equal(xq, r_xq) and np.array_equal(sx, r_sx)
+    assert np.array_equal(acc, r_acc), f"{(acc != r_acc).sum()} accumulators differ"
+    assert_rel(Y, r_y, Y_TOL, "Y")
+    # the launch the benchmark times has no accumulator output (whole-row epilogue): same Y, bit for bit
+    Y2, *_ = hip_linear(X, packed, gamma, d_out, 2, 4, getattr(s, path_name), want_acc=False)
+    assert np.array_equal(Y2, Y)
 
 
 def test_config3_grouped_step_full_size_as_timed():
     # the launch configuration the benchmark times: one grouped call for X 4096x2560 against 6912x2560 and
-    # 2560x2560 (largest first), one quantization, one sparse GEMM launch, LDS-transposed epilogue.
-    # Y on 64 sampled token rows of both outputs; Y of the grouped call equals the single calls bit for bit.
+    # 2560x2560 (largest first), one quantization, one sparse GEMM launch, whole-row epilogue.
+    # Every Y of both outputs against the oracle; Y of the grouped call equals the single calls bit for bit.
     s = sbn()
     shapes = [(6912, 2560), (2560, 2560)]
-    Ws = [sbn_synth.latent_weight(a, b, sbn_synth.seed_for(3, a)) for a, b in shapes]
-    X = sbn_synth.activations(4096, 2560, sbn_synth.seed_for(3, 1))
-    packs = [hip_pack(W, 2, 4) for W in Ws]
+    refs = [_config3_oracle(a) for a, _ in shapes]
+    X = refs[0][1]
+    packs = [hip_pack(r[0], 2, 4) for r in refs]
     Xd = X.to(DEV)
     Ys = [torch.full((4096, a), float("nan"), dtype=torch.float32, device=DEV) for a, _ in shapes]
     ws = s.new_workspace(sum(s.sbn_workspace_bytes(s.SBN_OP_LINEAR, 4096, a, b, 2, 4) for a, b in shapes))
-    s.sbn_sparse_ternary_linear_grouped([Xd, Xd], [p for p, _ in packs], [g for _, g in packs], Ys, 2, 4, ws,
-                                        path=s.SBN_PATH_SMFMAC)
+    grp = s.LinearGroup([Xd, Xd], [p for p, _ in packs], [g for _, g in packs], Ys, 2, 4, ws, s.SBN_PATH_SMFMAC)
+    grp.run()
+    grp.run()            # the timed loop calls it back to back on one workspace
     torch.cuda.synchronize()
-    rows = np.unique(np.concatenate([[0, 1, 127, 128, 4095], np.random.default_rng(5).choice(4096, size=59, replace=False)]))
-    Xf = X.float().numpy()
-    for (a, b), W, (packed, gamma), Y in zip(shapes, Ws, packs, Ys):
-        _, g, Weff, _ = oracle_pack(W, 2, 4)
-        y, *_ = oracle.sparse_ternary_linear(Xf[rows], Weff, g)
-        assert_rel(Y.cpu().numpy()[rows], y, Y_TOL, f"grouped Y {a}x{b}")
+    for (a, b), ref, (packed, gamma), Y in zip(shapes, refs, packs, Ys):
+        assert_rel(Y.cpu().numpy(), ref[2], Y_TOL, f"grouped Y {a}x{b}")
         Y1, *_ = hip_linear(X, packed, gamma, a, 2, 4, s.SBN_PATH_SMFMAC, want_acc=False)
         assert np.array_equal(Y.cpu().numpy(), Y1)
 
 
 def test_prefill_longest_sequence_sampled_rows():
-    # 65536 tokens (the longest prefill of the throughput table, Section 4.3) against 6912x2560: Y holds
+    # 65536 tokens (the longest prefill of the throughput table, Section 3.2) against 6912x2560: Y holds
     # 453 M values = 1.8 GB, so token offsets pass 2^31 bytes; the rows of the first, the last and 40 sampled
     # tokens are compared with the oracle (each an exact int32 dot product and one rescale)
     s = sbn()
@@ -292,16 +307,24 @@ def test_sparse_and_dense_paths_agree_bitwise_full_size():
     assert np.array_equal(acca, accb) and np.array_equal(Ya, Yb)
 
 
-@pytest.mark.parametrize("spin_limit", [None, "-1", "0"])
+@pytest.fixture
+def spin_limits():
+    """Sets the bounds of the library's bounded waits for one test and restores the defaults afterwards."""
+    s = sbn()
+    yield s.sbn_test_set_spin_limits
+    s.sbn_test_set_spin_limits()
+
+
+@pytest.mark.parametrize("spin_limit", [None, -1, 0])
 @pytest.mark.parametrize("tokens", [1, 8, 16])
-def test_grouped_streaming_gemv_against_oracle(tokens, spin_limit, monkeypatch):
+def test_grouped_streaming_gemv_against_oracle(tokens, spin_limit, spin_limits):
     # enough rows in one grouped call to take the persistent streaming kernel; shapes with ragged
     # row counts and a partial last super-step (K = 768 = 6 chunks).  The kernel quantizes the three
     # inputs itself: its first blocks publish the rows, the others wait for them; spin limit -1 makes
     # every block quantize for itself without looking, 0 allows one look (either branch may run)
     s = sbn()
     if spin_limit is not None:
-        monkeypatch.setenv("SBN_GEMV_SPIN_LIMIT", spin_limit)
+        spin_limits(gemv_polls=spin_limit)
     shapes = [(4100, 768), (4096, 256), (5000, 640)] * 14
     Ws = {sh: sbn_synth.latent_weight(sh[0], sh[1], 650 + sh[0]) for sh in set(shapes)}
     packs = {sh: hip_pack(W, 2, 4) for sh, W in Ws.items()}
@@ -490,3 +513,28 @@ def test_sparse_gemm_more_tiles_than_block_slots_ragged(tokens, d_out):
     X = sbn_synth.activations(tokens, 256, 2001)
     sample = np.unique(np.concatenate([np.arange(0, 200), np.arange(tokens - 400, tokens), np.arange(3000, 3100)]))
     check_forward(W, X, 2, 4, s.SBN_PATH_SMFMAC, token_sample=sample)
+
+
+def test_streaming_decode_alternating_weight_forms_on_one_workspace():
+    # 2:4 weights (sparse instruction) and dense 2-bit codes (N = M) are two instantiations of the streaming kernel;
+    # alternating grouped calls on ONE workspace, with the same token and row layout and a different X every call,
+    # leave each other's per-token flags behind: every call must wait for its own producers and see its own x~
+    s = sbn()
+    tokens, R = 8, 20
+    shape = (6912, 512)
+    Ws = [sbn_synth.latent_weight(shape[0], shape[1], 2100 + r) for r in range(R)]
+    forms = {(2, 4): [hip_pack(W, 2, 4) for W in Ws], (8, 8): [hip_pack(W, 8, 8) for W in Ws]}
+    refs = {nm: [oracle_pack(W, *nm) for W in Ws] for nm in forms}
+    ws = s.new_workspace(R * max(s.sbn_workspace_bytes(s.SBN_OP_LINEAR, tokens, shape[0], shape[1], n, m) for n, m in forms))
+    for call in range(6):
+        nm = (2, 4) if call % 2 == 0 else (8, 8)
+        X = sbn_synth.activations(tokens, shape[1], 2150 + call)
+        Xd = X.to(DEV)
+        Ys = [torch.full((tokens, shape[0]), float("nan"), dtype=torch.float32, device=DEV) for _ in range(R)]
+        s.sbn_sparse_ternary_linear_grouped([Xd] * R, [p for p, _ in forms[nm]], [g for _, g in forms[nm]], Ys, nm[0], nm[1], ws,
+                                            path=s.SBN_PATH_GEMV)
+        torch.cuda.synchronize()
+        Xf = X.float().numpy()
+        for r in range(R):
+            y, *_ = oracle.sparse_ternary_linear(Xf, refs[nm][r][2], refs[nm][r][1])
+            assert_rel(Ys[r].cpu().numpy(), y, Y_TOL, f"call {call} ({nm[0]}:{nm[1]}), copy {r}")

@@ -118,24 +118,47 @@ def test_pack_batched_equals_single():
         assert np.array_equal(packed[i].cpu().numpy(), ref)
 
 
+@pytest.fixture(scope="module")
+def sweep_latents():
+    """The 210 latent matrices of the 30-layer sweep, generated on the device exactly as the benchmark does
+    (4.76 GB); freed when the module's tests are done."""
+    Wl = []
+    for layer in range(sbn_synth.LAYERS):
+        for mi, (_, a, b) in enumerate(sbn_synth.BLOCK_MATRICES):
+            Wl.append(sbn_synth.latent_weight(a, b, sbn_synth.seed_for(4, 10 * layer + mi), device=DEV))
+    yield Wl
+    del Wl
+    torch.cuda.empty_cache()
+
+
 @pytest.mark.parametrize("N,M", [(2, 4), (1, 4), (2, 8)])
-def test_config4_sweep_batched_as_timed(N, M):
-    # the launch configuration the benchmark times for the sweep: one batched call over full-size
-    # matrices (two transformer blocks = 14 matrices here, the sweep's three shapes), every byte and gamma
+def test_config4_full_sweep_as_timed(N, M, sweep_latents):
+    # configs[3] in the launch configuration the benchmark times: ONE batched call over all 210 matrices of the
+    # 30-layer model (the library cuts it into three launches of 70), one workspace; every gamma and every
+    # packed byte of every matrix against the oracle (the oracle's weight side runs on a few host threads,
+    # matrix by matrix)
+    from concurrent.futures import ThreadPoolExecutor
     s = sbn()
-    shapes = [(a, b) for _, a, b in sbn_synth.BLOCK_MATRICES] * 2
-    Ws = [sbn_synth.latent_weight(a, b, sbn_synth.seed_for(4, 10 * (i // 7) + i % 7)) for i, (a, b) in enumerate(shapes)]
-    Wd = [W.to(DEV) for W in Ws]
-    packed = [torch.zeros(s.sbn_packed_bytes(a, b, N, M), dtype=torch.uint8, device=DEV) for a, b in shapes]
-    gammas = torch.zeros(len(shapes), dtype=torch.float32, device=DEV)
-    glist = [gammas[i:i + 1] for i in range(len(shapes))]
-    ws = s.new_workspace(s.sbn_workspace_bytes(s.SBN_OP_QUANTIZE_MASK_PACK, len(shapes), 6912, 2560, N, M))
-    s.sbn_quantize_mask_pack_batched(Wd, N, M, packed, glist, ws)
+    Wl = sweep_latents
+    assert len(Wl) == 210 and sum(w.numel() for w in Wl) == 2378956800
+    packed = [torch.full((s.sbn_packed_bytes(w.shape[0], w.shape[1], N, M),), 0xAA, dtype=torch.uint8, device=DEV) for w in Wl]
+    gammas = torch.zeros(len(Wl), dtype=torch.float32, device=DEV)
+    glist = [gammas[i:i + 1] for i in range(len(Wl))]
+    ws = s.new_workspace(s.sbn_workspace_bytes(s.SBN_OP_QUANTIZE_MASK_PACK, len(Wl), sbn_synth.FFN, sbn_synth.HIDDEN, N, M))
+    batch = s.PackBatch(Wl, N, M, packed, glist, ws)
+    batch.run()
+    batch.run()          # the timed loop calls it back to back on one workspace: counters and flags start clean
     torch.cuda.synchronize()
-    for i, W in enumerate(Ws):
-        ref, g, *_ = oracle_pack(W, N, M)
-        assert gammas[i].item() == g, f"gamma of matrix {i}"
-        assert np.array_equal(packed[i].cpu().numpy(), ref), f"packed bytes of matrix {i}"
+    got_gamma = gammas.cpu().numpy()
+
+    def one(i):
+        ref, g, *_ = oracle_pack(Wl[i].cpu(), N, M)
+        return i, g == got_gamma[i], np.array_equal(packed[i].cpu().numpy(), ref)
+
+    with ThreadPoolExecutor(4) as pool:
+        for i, gamma_ok, bytes_ok in pool.map(one, range(len(Wl))):
+            assert gamma_ok, f"gamma of matrix {i}"
+            assert bytes_ok, f"packed bytes of matrix {i}"
 
 
 @pytest.mark.parametrize("N,M", [(2, 4), (1, 4), (2, 8), (6, 8), (3, 8), (1, 2), (4, 4)])
@@ -165,13 +188,21 @@ def test_mask_flips_between_two_steps(N, M, shape):
     assert flips.item() == 0
 
 
-@pytest.mark.parametrize("spin_limit", ["-1", "0", "3"])
+@pytest.fixture
+def spin_limits():
+    """Sets the bounds of the library's bounded waits for one test and restores the defaults afterwards."""
+    s = sbn()
+    yield s.sbn_test_set_spin_limits
+    s.sbn_test_set_spin_limits()
+
+
+@pytest.mark.parametrize("spin_limit", [-1, 0, 3])
 @pytest.mark.parametrize("N,M", [(2, 4), (1, 4), (2, 8)])
-def test_single_read_pack_when_blocks_do_not_wait(N, M, spin_limit, monkeypatch):
+def test_single_read_pack_when_blocks_do_not_wait(N, M, spin_limit, spin_limits):
     # the single-read form of the pack kernel with its wait cut short: -1 = no block waits for the matrix's
     # last block (each derives the threshold from HBM itself), 0 and 3 = a few polls, then the same;
     # bytes and gamma must not depend on which way a block took
-    monkeypatch.setenv("SBN_PACK_SPIN_LIMIT", spin_limit)
+    spin_limits(pack_polls=spin_limit)
     s = sbn()
     shapes = [(640, 1280), (100, 384), (256, 256), (1024, 2560)]
     Ws = [sbn_synth.latent_weight(a, b, 1800 + i) for i, (a, b) in enumerate(shapes)]
