@@ -214,7 +214,7 @@ def main():
                 del pk
             rows[key] = rows_p
     # ------------------------------------------------------------------ the paper's throughput table, by token count
-    # Section 4.3 reports prefill at 512 ... 65536 tokens and decode at batch 64 ... 512 (other hardware, 6:8, whole
+    # Section 3.2 reports prefill at 512 ... 65536 tokens and decode at batch 64 ... 512 (other hardware, 6:8, whole
     # model).  The same sweep for one 6912x2560 layer at 2:4: sparse kernel against the dense-ternary comparison kernel
     # on pre-quantized activations (prefill), and one call through path selection including its quantizer (decode).
     if "seq" in sections:
@@ -481,18 +481,19 @@ def main():
     # ------------------------------------------------------------------ ceilings this board sustains, next to the datasheet peaks
     ceilings = None
     if "ceil" in sections:
+        from paper_2603_05168_amd import probe as sbn_probe   # libsbn_probe.so: measurement support, not the layer's library
         buf = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)   # 1 GiB: four times the Infinity Cache
         ceilings = {}
-        for key, kind, iters, unit in (("smfmac_i8_dense_equiv", sbn.SBN_CEIL_SMFMAC_I8, 100, 1e12),
-                                       ("mfma_i8", sbn.SBN_CEIL_MFMA_I8, 100, 1e12),
-                                       ("mfma_bf16", sbn.SBN_CEIL_MFMA_BF16, 100, 1e12),
-                                       ("hbm_read", sbn.SBN_CEIL_HBM_READ, 1, 1e9),
-                                       ("hbm_write", sbn.SBN_CEIL_HBM_WRITE, 1, 1e9),
-                                       ("lds_read", sbn.SBN_CEIL_LDS_READ, 2000, 1e9)):
+        for key, kind, iters, unit in (("smfmac_i8_dense_equiv", sbn_probe.SBN_CEIL_SMFMAC_I8, 100, 1e12),
+                                       ("mfma_i8", sbn_probe.SBN_CEIL_MFMA_I8, 100, 1e12),
+                                       ("mfma_bf16", sbn_probe.SBN_CEIL_MFMA_BF16, 100, 1e12),
+                                       ("hbm_read", sbn_probe.SBN_CEIL_HBM_READ, 1, 1e9),
+                                       ("hbm_write", sbn_probe.SBN_CEIL_HBM_WRITE, 1, 1e9),
+                                       ("lds_read", sbn_probe.SBN_CEIL_LDS_READ, 2000, 1e9)):
             work = [0.0]
 
             def probe(kind=kind, iters=iters):
-                work[0] = sbn.sbn_ceiling_probe(kind, buf, iters)
+                work[0] = sbn_probe.sbn_ceiling_probe(kind, buf, iters)
             ms = timed(probe, 200 if unit == 1e12 else 20, 2)
             ceilings[key] = work[0] / (ms * 1e-3) / unit
         ceilings["units"] = "TOP/s or TFLOP/s with random operands (matrix kinds), GB/s over 1 GiB (stream kinds), GB/s of conflict-free 16-byte LDS reads summed over all multiprocessors"

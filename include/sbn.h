@@ -19,6 +19,7 @@
  *     function attributes and queries the device.  While a stream captures, grouped decode calls
  *     launch the activation quantizer in front of the streaming kernel instead of fusing it (the
  *     fused form numbers its launches on the host).  Pointers and sizes are frozen in the graph.
+ *   - No environment variable changes what a call does.
  *
  * Packed weight layout (the paper asks only that the N:M metadata have a defined layout; this one
  * is the library's).  b = log2(M) index bits per kept weight (none when N == M).  Each row is cut
@@ -232,7 +233,7 @@ sbn_status sbn_mask_flips(const void *packed_a, const void *packed_b, int64_t d_
 /*
  * Rewrites a packed N:M matrix into the packed form of another pattern that can hold the same
  * W_eff, so that decode calls stream the weights as stored instead of rewriting them per call
- * ("weights pre-packed once"; Section 4.3 measures decode on the 6:8 model):
+ * ("weights pre-packed once"; Section 3.2 measures decode on the 6:8 model):
  *   to_N:to_M = 2:4  for patterns that keep at most two weights of every aligned four (1:2, 1:4, 1:8, 2:8):
  *                    the operand form of the sparse matrix instruction, with zero-code padding slots;
  *   to_N == to_M     for any pattern: dense 2-bit codes with explicit zeros at the dropped positions
@@ -249,24 +250,15 @@ sbn_status sbn_convert_packed(const void *packed, int64_t d_out, int64_t d_in, i
                               void *out, void *stream);
 
 /*
- * Measurement support (not a step of the layer): enqueues one kernel that issues a single kind of work
- * at full rate, so that a benchmark can state the rate this board sustains next to the datasheet
- * peak.  Matrix kinds run `iters` rounds of 16 matrix instructions per wavefront on random operands,
- * two wavefronts per SIMD; stream kinds read or write `bytes` - 256 bytes of `buf` once; the LDS kind runs
- * `iters` rounds of 16 conflict-free 16-byte LDS reads per lane, two wavefronts per SIMD.
- *   buf       device, >= 256 bytes, 256-byte aligned (matrix kinds touch only its first word)
- *   work_out  HOST, the operations (2 per multiply-add, dense-equivalent for the sparse instruction)
- *             or bytes one call performs
+ * Test hook: bounds of the library's two bounded inter-block waits, in polls.  The streaming decode kernel lets
+ * its first blocks quantize the activations while the others wait for their flags, and the single-read pack
+ * kernel lets one block finalize a matrix's scale while the others wait for its ready word; a block out of polls
+ * does the awaited work itself, so results never depend on these numbers (the tests set them to 0 and below to
+ * force that branch).  A negative value means "never wait"; INT_MIN restores the default (about a millisecond of
+ * polling, far above any wait of a launch whose blocks are co-resident).  Process-wide; not for use while calls
+ * are being enqueued from other threads.
  */
-typedef enum {
-    SBN_CEIL_SMFMAC_I8 = 0,  /* v_smfmac_i32_32x32x64_i8, ternary A, int8 B */
-    SBN_CEIL_MFMA_I8 = 1,    /* v_mfma_i32_32x32x32_i8 */
-    SBN_CEIL_MFMA_BF16 = 2,  /* v_mfma_f32_32x32x16_bf16 */
-    SBN_CEIL_HBM_READ = 3,
-    SBN_CEIL_HBM_WRITE = 4,
-    SBN_CEIL_LDS_READ = 5    /* ds_read_b128; like the matrix kinds it touches only the first word of buf */
-} sbn_ceiling;
-sbn_status sbn_ceiling_probe(int kind, void *buf, size_t bytes, int iters, double *work_out, void *stream);
+void sbn_test_set_spin_limits(int gemv_polls, int pack_polls);
 
 /* Text of the last HIP error seen by this thread ("" if none). */
 const char *sbn_last_error(void);

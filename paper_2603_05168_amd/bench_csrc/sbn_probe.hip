@@ -2,13 +2,19 @@
 // the rate this board sustains next to the datasheet peak it divides by.  Matrix probes use random
 // operands on purpose: with constant operands the same loop runs at a much higher clock (the part is
 // power-managed), and the layer's operands are not constant.  Measurement support, not on the path
-// of Section 2.2.
-#include "sbn_internal.hpp"
-#include "sbn_mfma.hpp"
+// of Section 2.2.  Built into libsbn_probe.so, apart from the layer's library.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
 
-namespace sbn {
+#include "../../include/sbn_probe.h"
 
 namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
 __device__ __forceinline__ uint32_t mix32(uint32_t x)
 {
@@ -133,33 +139,44 @@ __global__ void __launch_bounds__(256, 2) probe_lds_kernel(int iters, int *sink)
     if ((x.x ^ x.y ^ x.z ^ x.w) == 0x5a17c0deu) *sink = 1;
 }
 
+int multiprocessors()
+{
+    int dev = 0, cus = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) cus = prop.multiProcessorCount;
+    return cus > 0 ? cus : 256;
+}
+
 }  // namespace
 
-sbn_status launch_ceiling_probe(int kind, void *buf, size_t bytes, int iters, double *work_out, hipStream_t stream)
+extern "C" int sbn_ceiling_probe(int kind, void *buf, size_t bytes, int iters, double *work_out, void *stream_)
 {
+    if (!buf || !work_out || kind < SBN_CEIL_SMFMAC_I8 || kind > SBN_CEIL_LDS_READ) return -1;
+    if (reinterpret_cast<uintptr_t>(buf) % 256 != 0) return -4;
+    const bool streams = kind == SBN_CEIL_HBM_READ || kind == SBN_CEIL_HBM_WRITE;
+    if (streams ? bytes < ((size_t)1 << 20) : (iters <= 0 || bytes < 256)) return -1;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    static thread_local int cus = 0;
+    if (cus == 0) cus = multiprocessors();
     int *sink = static_cast<int *>(buf);
     if (kind <= SBN_CEIL_MFMA_BF16) {
-        const int blocks = 2 * device_cus();   // two wavefronts per SIMD
+        const int blocks = 2 * cus;   // two wavefronts per SIMD
         const double per_mma = kind == SBN_CEIL_SMFMAC_I8 ? 2.0 * 32 * 32 * 64 : kind == SBN_CEIL_MFMA_I8 ? 2.0 * 32 * 32 * 32 : 2.0 * 32 * 32 * 16;
         *work_out = per_mma * PROBE_MMA_PER_ITER * (double)iters * 4.0 * blocks;
         if (kind == SBN_CEIL_SMFMAC_I8) hipLaunchKernelGGL(probe_mma_kernel<0>, dim3(blocks), dim3(256), 0, stream, iters, sink);
         else if (kind == SBN_CEIL_MFMA_I8) hipLaunchKernelGGL(probe_mma_kernel<1>, dim3(blocks), dim3(256), 0, stream, iters, sink);
         else hipLaunchKernelGGL(probe_mma_kernel<2>, dim3(blocks), dim3(256), 0, stream, iters, sink);
-        return check_launch("probe_mma_kernel");
-    }
-    if (kind == SBN_CEIL_LDS_READ) {
-        const int blocks = 2 * device_cus();
+    } else if (kind == SBN_CEIL_LDS_READ) {
+        const int blocks = 2 * cus;
         *work_out = 16.0 * PROBE_LDS_READS * 256.0 * (double)iters * blocks;
         hipLaunchKernelGGL(probe_lds_kernel, dim3(blocks), dim3(256), 0, stream, iters, sink);
-        return check_launch("probe_lds_kernel");
+    } else {
+        const int blocks = 8 * cus;
+        const int64_t nvec = (int64_t)((bytes - 256) / 16) / blocks * blocks;
+        *work_out = (double)nvec * 16.0;
+        uint4 *data = reinterpret_cast<uint4 *>(static_cast<uint8_t *>(buf) + 256);   // the first 256 bytes hold the sink
+        if (kind == SBN_CEIL_HBM_READ) hipLaunchKernelGGL(probe_read_kernel, dim3(blocks), dim3(256), 0, stream, data, nvec, sink);
+        else hipLaunchKernelGGL(probe_write_kernel, dim3(blocks), dim3(256), 0, stream, data, nvec);
     }
-    const int blocks = 8 * device_cus();
-    const int64_t nvec = (int64_t)((bytes - 256) / 16) / blocks * blocks;
-    *work_out = (double)nvec * 16.0;
-    uint4 *data = reinterpret_cast<uint4 *>(static_cast<uint8_t *>(buf) + 256);   // the first 256 bytes hold the sink
-    if (kind == SBN_CEIL_HBM_READ) hipLaunchKernelGGL(probe_read_kernel, dim3(blocks), dim3(256), 0, stream, data, nvec, sink);
-    else hipLaunchKernelGGL(probe_write_kernel, dim3(blocks), dim3(256), 0, stream, data, nvec);
-    return check_launch("probe_stream_kernel");
+    return hipGetLastError() == hipSuccess ? 0 : -5;
 }
-
-}  // namespace sbn

@@ -64,8 +64,8 @@ def _load():
     lib.sbn_convert_packed.argtypes = [vp, i64, i64, cint, cint, cint, cint, vp, vp]
     lib.sbn_rmsnorm_act_quant.restype = cint
     lib.sbn_rmsnorm_act_quant.argtypes = [vp, i64, i64, vp, ctypes.c_float, vp, vp, vp, vp]
-    lib.sbn_ceiling_probe.restype = cint
-    lib.sbn_ceiling_probe.argtypes = [cint, vp, sz, cint, ctypes.POINTER(ctypes.c_double), vp]
+    lib.sbn_test_set_spin_limits.restype = None
+    lib.sbn_test_set_spin_limits.argtypes = [cint, cint]
     lib.sbn_mask_flips.restype = cint
     lib.sbn_mask_flips.argtypes = [vp, vp, i64, i64, cint, cint, vp, vp, sz, vp]
     return lib
@@ -284,15 +284,12 @@ def sbn_convert_packed(packed, d_out: int, d_in: int, N: int, M: int, to_N: int,
     _check(_lib.sbn_convert_packed(_ptr(packed), d_out, d_in, N, M, to_N, to_M, _ptr(out), _stream()), "sbn_convert_packed")
 
 
-SBN_CEIL_SMFMAC_I8, SBN_CEIL_MFMA_I8, SBN_CEIL_MFMA_BF16, SBN_CEIL_HBM_READ, SBN_CEIL_HBM_WRITE, SBN_CEIL_LDS_READ = range(6)
+SBN_SPIN_DEFAULT = -2 ** 31
 
 
-def sbn_ceiling_probe(kind: int, buf, iters: int = 1) -> float:
-    """Enqueue one ceiling-probe kernel; returns the operations or bytes it performs."""
-    work = ctypes.c_double(0.0)
-    _check(_lib.sbn_ceiling_probe(kind, _ptr(buf), buf.numel() * buf.element_size(), iters, ctypes.byref(work), _stream()),
-           "sbn_ceiling_probe")
-    return work.value
+def sbn_test_set_spin_limits(gemv_polls: int = SBN_SPIN_DEFAULT, pack_polls: int = SBN_SPIN_DEFAULT):
+    """Test hook: polls of the two bounded inter-block waits (negative: never wait; SBN_SPIN_DEFAULT restores)."""
+    _lib.sbn_test_set_spin_limits(gemv_polls, pack_polls)
 
 
 def sbn_mask_flips(packed_a, packed_b, d_out: int, d_in: int, N: int, M: int, flips_out, workspace):

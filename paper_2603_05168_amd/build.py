@@ -1,4 +1,5 @@
-"""Compile the HIP sources under csrc/ into paper_2603_05168_amd/libsbn.so for gfx950."""
+"""Compile the HIP sources for gfx950: csrc/ into paper_2603_05168_amd/libsbn.so (the layer) and bench_csrc/ into
+paper_2603_05168_amd/libsbn_probe.so (ceiling probes of the benchmark, apart from the layer's library)."""
 import glob
 import os
 import subprocess
@@ -7,6 +8,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsbn.so")
+PROBE_SRC = os.path.join(HERE, "bench_csrc")
+PROBE_LIB = os.path.join(HERE, "libsbn_probe.so")
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -22,14 +25,16 @@ def sources():
 
 def build(force: bool = True, verbose: bool = False) -> str:
     srcs = sources()
-    deps = srcs + glob.glob(os.path.join(CSRC, "*.hpp")) + [os.path.join(HERE, "..", "include", "sbn.h")]
-    if not force and os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(d) for d in deps):
+    probe_srcs = sorted(glob.glob(os.path.join(PROBE_SRC, "*.hip")))
+    deps = srcs + probe_srcs + glob.glob(os.path.join(CSRC, "*.hpp")) + glob.glob(os.path.join(HERE, "..", "include", "*.h"))
+    if not force and all(os.path.exists(l) and all(os.path.getmtime(l) >= os.path.getmtime(d) for d in deps) for l in (LIB, PROBE_LIB)):
         return LIB
     objs = []
+    probe_objs = []
     procs = []
-    for s in srcs:
-        o = os.path.join(CSRC, os.path.basename(s)[:-4] + ".o")
-        objs.append(o)
+    for s in srcs + probe_srcs:
+        o = s[:-4] + ".o"
+        (probe_objs if s in probe_srcs else objs).append(o)
         cmd = ["hipcc", "-c"] + [f for f in FLAGS if f != "-shared"] + ["-o", o, s]
         procs.append((s, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
     failed = False
@@ -44,6 +49,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
     if failed:
         raise RuntimeError("hipcc failed")
     subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs, check=True)
+    subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", PROBE_LIB] + probe_objs, check=True)
     return LIB
 
 

@@ -1,5 +1,7 @@
 // extern "C" entry points of libsbn: argument validation on the host, workspace carving, dispatch.
 // Nothing here allocates or synchronises; every check happens before the first launch.
+#include <atomic>
+#include <climits>
 #include <string>
 #include <vector>
 
@@ -23,6 +25,10 @@ sbn_status check_launch(const char *what)
     }
     return SBN_OK;
 }
+
+static std::atomic<int> g_gemv_spin{GEMV_SPIN_DEFAULT}, g_pack_spin{PACK_SPIN_DEFAULT};
+int gemv_spin_limit() { return g_gemv_spin.load(std::memory_order_relaxed); }
+int pack_spin_limit() { return g_pack_spin.load(std::memory_order_relaxed); }
 
 static sbn_status check_shape(int64_t d_out, int64_t d_in, int N, int M, Pattern &pat)
 {
@@ -53,6 +59,12 @@ using namespace sbn;
 extern "C" {
 
 const char *sbn_last_error(void) { return g_last_error.c_str(); }
+
+void sbn_test_set_spin_limits(int gemv_polls, int pack_polls)
+{
+    g_gemv_spin.store(gemv_polls == INT_MIN ? GEMV_SPIN_DEFAULT : gemv_polls, std::memory_order_relaxed);
+    g_pack_spin.store(pack_polls == INT_MIN ? PACK_SPIN_DEFAULT : pack_polls, std::memory_order_relaxed);
+}
 
 sbn_status sbn_packed_bytes(int64_t d_out, int64_t d_in, int N, int M, size_t *bytes)
 {
@@ -358,15 +370,6 @@ sbn_status sbn_convert_packed(const void *packed, int64_t d_out, int64_t d_in, i
     if (to_N == 2 && to_M == 4 && embeds_in_2of4(pat)) return launch_repack_2of4(packed, d_out, d_in, pat, static_cast<uint8_t *>(out), s);
     if (to_N == to_M) return launch_repack_dense_codes(packed, d_out, d_in, pat, static_cast<uint8_t *>(out), s);
     return SBN_EUNSUPPORTED;
-}
-
-sbn_status sbn_ceiling_probe(int kind, void *buf, size_t bytes, int iters, double *work_out, void *stream)
-{
-    if (!buf || !work_out || kind < SBN_CEIL_SMFMAC_I8 || kind > SBN_CEIL_LDS_READ) return SBN_EINVAL;
-    if (!aligned(buf, 256)) return SBN_EALIGN;
-    const bool streams = kind == SBN_CEIL_HBM_READ || kind == SBN_CEIL_HBM_WRITE;
-    if (streams ? bytes < ((size_t)1 << 20) : (iters <= 0 || bytes < 256)) return SBN_EINVAL;
-    return launch_ceiling_probe(kind, buf, bytes, iters, work_out, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

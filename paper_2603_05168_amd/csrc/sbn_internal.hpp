@@ -98,8 +98,13 @@ sbn_status launch_linear_generic(const LinearItem &it, const Pattern &pat, hipSt
 
 int device_cus();   // multiprocessors of the current device
 
-// ---- ceiling probes (sbn_probe.hip) ---------------------------------------------------------------
-sbn_status launch_ceiling_probe(int kind, void *buf, size_t bytes, int iters, double *work_out, hipStream_t stream);
+// Bounds of the two bounded inter-block waits (streaming decode: flags of the fused quantizer; single-read pack:
+// the matrix's ready word), in polls; negative = never wait.  Process-wide, changed only by the test hook
+// sbn_test_set_spin_limits; the launchers read them once per launch.
+constexpr int GEMV_SPIN_DEFAULT = 1 << 10;
+constexpr int PACK_SPIN_DEFAULT = 1 << 12;
+int gemv_spin_limit();
+int pack_spin_limit();
 
 // ---- backward (sbn_backward.hip) ---------------------------------------------------------------
 size_t backward_workspace_bytes(int64_t tokens, int64_t d_out, int64_t d_in);

@@ -783,13 +783,10 @@ sbn_status launch_gemv(int count, const LinearItem *items, bool dense_codes, hip
     return dense_codes ? launch_gemv_as<true>(count, items, stream) : launch_gemv_as<false>(count, items, stream);
 }
 
-// Polls a block of the streaming kernel spends on the flags of an input before it quantizes the rows itself.
-// SBN_GEMV_SPIN_LIMIT overrides; negative: never look (the tests use it to exercise that branch).
-static int gemv_spin_limit()
-{
-    const char *e = getenv("SBN_GEMV_SPIN_LIMIT");
-    return e && *e ? atoi(e) : 1 << 16;
-}
+// Launch number of the streaming kernel with the fused quantizer: it tags the per-token flags a launch raises in
+// the caller's workspace (never cleared), so that flags left by any earlier launch - of either instantiation of
+// the kernel, on any workspace - can never be taken for this launch's.  One counter for the whole library.
+static std::atomic<unsigned> g_gemv_stream_epoch{1};
 
 // true while `stream` records into a graph (or when that cannot be told)
 static bool stream_is_capturing(hipStream_t stream)
@@ -806,7 +803,6 @@ template <bool DENSE>
 static sbn_status launch_gemv_as(int count, const LinearItem *items, hipStream_t stream)
 {
     constexpr int RT = 1;
-    static std::atomic<unsigned> epoch{1};
     static thread_local std::vector<const int8_t *> written;   // xq buffers a quantizer kernel of this call has filled
     written.clear();
     // quantizer launches for the problems first .. first + n - 1 that still need one (shared inputs once)
@@ -893,7 +889,7 @@ static sbn_status launch_gemv_as(int count, const LinearItem *items, hipStream_t
             }
             tab.unit0[n] = u;
             for (int j = tab.nin; j < GEMV_STREAM_INPUTS; ++j) tab.tok0[j + 1] = tab.tok0[tab.nin];
-            tab.epoch = epoch.fetch_add(1, std::memory_order_relaxed);
+            tab.epoch = g_gemv_stream_epoch.fetch_add(1, std::memory_order_relaxed);
             tab.spin_limit = gemv_spin_limit();
             static thread_local bool raised = false;
             if (!raised) {

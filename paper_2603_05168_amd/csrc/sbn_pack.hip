@@ -1028,14 +1028,6 @@ static int fused_capacity()
     return cap;
 }
 
-// polls a block of the single-read form spends on the matrix's "ready" word before it derives theta alone;
-// SBN_PACK_SPIN_LIMIT overrides (negative: never look, every block derives theta alone: exercised by the tests)
-static int pack_spin_limit()
-{
-    const char *e = getenv("SBN_PACK_SPIN_LIMIT");
-    return e && *e ? atoi(e) : 1 << 18;
-}
-
 sbn_status launch_pack(int count, const PackItem *items, sbn_dtype wdt, const Pattern &pat, void *workspace,
                        size_t ws_bytes, hipStream_t stream)
 {

@@ -8,6 +8,7 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "sbn.h")
+PROBE_HEADER = os.path.join(ROOT, "include", "sbn_probe.h")
 
 
 @pytest.fixture(scope="module")
@@ -16,8 +17,8 @@ def sbn():
     return m
 
 
-def declared_functions():
-    text = open(HEADER).read()
+def declared_functions(header=HEADER):
+    text = open(header).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(sbn_[a-z0-9_]+)\s*\(", text)))
 
@@ -36,6 +37,23 @@ def test_library_exports_every_declared_symbol(sbn):
         assert hasattr(lib, name), f"{name} is declared in include/sbn.h but not exported"
     for name in declared_functions():
         assert hasattr(sbn, name), f"{name} has no Python binding of the same name"
+
+
+def test_every_header_is_covered_and_the_probe_library_exports_its_symbol():
+    # include/ holds exactly the layer's header and the benchmark probes' header, each with a library of its own
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["sbn.h", "sbn_probe.h"]
+    from paper_2603_05168_amd import probe
+    lib = ctypes.CDLL(probe.lib_path())
+    names = declared_functions(PROBE_HEADER)
+    assert names == ["sbn_ceiling_probe"]
+    for name in names:
+        assert hasattr(lib, name) and hasattr(probe, name)
+    assert "sbn_ceiling_probe" not in declared_functions()       # measurement support stays out of the layer's boundary
+
+
+def test_spin_limit_hook_is_callable_without_a_gpu(sbn):
+    sbn.sbn_test_set_spin_limits(0, -1)
+    sbn.sbn_test_set_spin_limits()
 
 
 def test_packed_bytes(sbn):
@@ -144,12 +162,14 @@ def test_argument_errors_come_before_any_launch(sbn):
     assert conv(to_N=1, to_M=4) == sbn.SBN_EUNSUPPORTED          # only 2:4 and N = M are decode forms
     assert conv(d_in=200) == sbn.SBN_EUNSUPPORTED                # whole 128-weight chunks only
     assert conv(to_N=9, to_M=8) == sbn.SBN_EINVAL
-    # ceiling probe: unknown kind, missing host output, buffer too small to stream
-    lib.sbn_ceiling_probe.restype = ctypes.c_int
+    # ceiling probes (their own library): unknown kind, missing host output, buffer too small to stream
+    from paper_2603_05168_amd import probe
+    plib = ctypes.CDLL(probe.lib_path())
+    plib.sbn_ceiling_probe.restype = ctypes.c_int
     work = ctypes.c_double(0.0)
-    assert lib.sbn_ceiling_probe(ci(7), vp(A), sz(1 << 22), ci(1), ctypes.byref(work), vp(0)) == sbn.SBN_EINVAL
-    assert lib.sbn_ceiling_probe(ci(0), vp(A), sz(1 << 22), ci(1), vp(0), vp(0)) == sbn.SBN_EINVAL
-    assert lib.sbn_ceiling_probe(ci(0), vp(A), sz(1 << 22), ci(0), ctypes.byref(work), vp(0)) == sbn.SBN_EINVAL
-    assert lib.sbn_ceiling_probe(ci(3), vp(A), sz(4096), ci(1), ctypes.byref(work), vp(0)) == sbn.SBN_EINVAL
-    assert lib.sbn_ceiling_probe(ci(3), vp(A + 16), sz(1 << 22), ci(1), ctypes.byref(work), vp(0)) == sbn.SBN_EALIGN
+    assert plib.sbn_ceiling_probe(ci(7), vp(A), sz(1 << 22), ci(1), ctypes.byref(work), vp(0)) == -1
+    assert plib.sbn_ceiling_probe(ci(0), vp(A), sz(1 << 22), ci(1), vp(0), vp(0)) == -1
+    assert plib.sbn_ceiling_probe(ci(0), vp(A), sz(1 << 22), ci(0), ctypes.byref(work), vp(0)) == -1
+    assert plib.sbn_ceiling_probe(ci(3), vp(A), sz(4096), ci(1), ctypes.byref(work), vp(0)) == -1
+    assert plib.sbn_ceiling_probe(ci(3), vp(A + 16), sz(1 << 22), ci(1), ctypes.byref(work), vp(0)) == -4
     assert sbn.sbn_last_error() == ""

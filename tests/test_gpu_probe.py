@@ -3,13 +3,13 @@
 import pytest
 import torch
 
-from gpu_util import DEV, sbn
+from gpu_util import DEV
 
 pytestmark = pytest.mark.gpu
 
 
 def test_ceiling_probes_run_and_report_work():
-    s = sbn()
+    from paper_2603_05168_amd import probe as s
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     buf = torch.zeros(8 << 20, dtype=torch.uint8, device=DEV)
     buf[256:] = 7
