@@ -163,6 +163,28 @@ sbn_status sbn_sparse_ternary_linear(const void *X, int64_t tokens, int64_t d_in
                                      size_t ws_bytes, void *stream);
 
 /*
+ * The forward call for callers that cannot allocate or carry a workspace (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): sbn_sparse_ternary_linear without the workspace arguments.
+ * Its scratch (the int8 activations and per-token scales of the call) lives in a buffer of
+ * SBN_STATIC_SCRATCH_MIB MiB inside the library's device image; every GPU the library runs on holds its own copy
+ * until the process ends.  The call allocates and frees nothing and enqueues the same kernels as the call above,
+ * so Y, xq_out, sx_out and acc_out are the same bit for bit.
+ *   arguments   as sbn_sparse_ternary_linear
+ *   limits      align256(tokens * d_in) + align256(4 * tokens) <= SBN_STATIC_SCRATCH_MIB MiB, else SBN_ESIZE
+ *               (sbn_last_error() then says how much was needed); only paths that read the weights as stored:
+ *               2:4 on SBN_PATH_GEMV / SBN_PATH_SMFMAC, N = M on SBN_PATH_GEMV, any pattern on SBN_PATH_GENERIC
+ *               (SBN_PATH_AUTO when it resolves to one of these); every other case SBN_EUNSUPPORTED
+ *   sharing     all calls on a GPU use that GPU's one buffer, which keeps the last call's contents (nothing in it has
+ *               to start at zero: flags left behind carry the number of the launch that raised them).  Calls that
+ *               overlap on one GPU (two streams, two threads) race on it: serialise them, or use the call above.
+ */
+enum { SBN_STATIC_SCRATCH_MIB = 16 };
+sbn_status sbn_sparse_ternary_linear_static(const void *X, int64_t tokens, int64_t d_in, int64_t d_out,
+                                            int N, int M, const void *packed, const float *gamma,
+                                            const float *bias, float *Y, int8_t *xq_out, float *sx_out,
+                                            int32_t *acc_out, sbn_path path, void *stream);
+
+/*
  * `count` independent forward problems in one enqueue (decode: every projection that is ready at
  * the same time; also used to stream many matrices through the GEMV kernel).  HOST arrays of
  * device pointers / sizes; all problems share N, M and path; bias is not applied.

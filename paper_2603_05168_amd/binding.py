@@ -51,6 +51,8 @@ def _load():
     lib.sbn_act_quant.argtypes = [vp, i64, i64, vp, vp, vp]
     lib.sbn_sparse_ternary_linear.restype = cint
     lib.sbn_sparse_ternary_linear.argtypes = [vp, i64, i64, i64, cint, cint, vp, vp, vp, vp, vp, vp, vp, cint, vp, sz, vp]
+    lib.sbn_sparse_ternary_linear_static.restype = cint
+    lib.sbn_sparse_ternary_linear_static.argtypes = [vp, i64, i64, i64, cint, cint, vp, vp, vp, vp, vp, vp, vp, cint, vp]
     lib.sbn_sparse_ternary_linear_grouped.restype = cint
     lib.sbn_sparse_ternary_linear_grouped.argtypes = [cint, pp, pi64, pi64, pi64, cint, cint, pp, pp, pp, cint, vp, sz, vp]
     lib.sbn_sparse_ternary_linear_backward.restype = cint
@@ -188,6 +190,22 @@ def sbn_sparse_ternary_linear(X, packed, gamma, Y, N: int, M: int, workspace, bi
                                           _ptr(Y), _ptr(xq_out), _ptr(sx_out), _ptr(acc_out), path, _ptr(workspace),
                                           workspace.numel() * workspace.element_size(), _stream()),
            "sbn_sparse_ternary_linear")
+
+
+SBN_STATIC_SCRATCH_MIB = 16
+
+
+def sbn_sparse_ternary_linear_static(X, packed, gamma, Y, N: int, M: int, bias=None, xq_out=None, sx_out=None, acc_out=None,
+                                     path: int = SBN_PATH_AUTO):
+    """sbn_sparse_ternary_linear on the library's own scratch: no workspace argument, nothing allocated."""
+    tokens, d_in = X.shape if X is not None else xq_out.shape
+    d_out = Y.shape[1]
+    if (X is not None and X.dtype != torch.bfloat16) or Y.dtype != torch.float32:
+        raise TypeError("X must be bf16 and Y fp32")
+    status = _lib.sbn_sparse_ternary_linear_static(_ptr(X), tokens, d_in, d_out, N, M, _ptr(packed), _ptr(gamma), _ptr(bias),
+                                                   _ptr(Y), _ptr(xq_out), _ptr(sx_out), _ptr(acc_out), path, _stream())
+    if status != SBN_OK:
+        raise SbnError(status, "sbn_sparse_ternary_linear_static", _lib.sbn_last_error().decode() if status in (SBN_EHIP, SBN_ESIZE) else "")
 
 
 class LinearGroup:

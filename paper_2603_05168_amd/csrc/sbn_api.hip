@@ -156,8 +156,10 @@ sbn_status sbn_rmsnorm_act_quant(const void *X, int64_t tokens, int64_t d_in, co
     return launch_rmsnorm_act_quant(X, gain, eps, tokens, d_in, xq, sx, xn_out, static_cast<hipStream_t>(stream));
 }
 
+// activations_only: the workspace holds the activation regions only (the entry point with the library's own scratch);
+// paths that rewrite or expand the weights into the workspace are then refused
 static sbn_status linear_one(const LinearItem &it_in, const Pattern &pat, sbn_path path, void *workspace,
-                             size_t ws_bytes, hipStream_t stream)
+                             size_t ws_bytes, hipStream_t stream, bool activations_only = false)
 {
     LinearItem it = it_in;
     const bool is24 = pat.N == 2 && pat.M == 4;
@@ -167,11 +169,18 @@ static sbn_status linear_one(const LinearItem &it_in, const Pattern &pat, sbn_pa
     if (path == SBN_PATH_GEMV && it.tokens > 16) return SBN_EUNSUPPORTED;
     if ((path == SBN_PATH_GEMV || path == SBN_PATH_SMFMAC) && it.d_in % CHUNK != 0) return SBN_EUNSUPPORTED;
     if (path == SBN_PATH_DENSE_MFMA && it.d_in % 64 != 0) return SBN_EUNSUPPORTED;
-    if (ws_bytes < linear_workspace_bytes(it.tokens, it.d_out, it.d_in)) return SBN_ESIZE;
-    // workspace: [xq int8 tokens*d_in][sx fp32 tokens][dense int8 W for the comparison path]
-    uint8_t *ws = static_cast<uint8_t *>(workspace);
     const size_t xq_bytes = align_up((size_t)it.tokens * it.d_in, 256);
     const size_t sx_bytes = align_up((size_t)it.tokens * sizeof(float), 256);
+    if (activations_only) {
+        const bool weights_as_stored = path == SBN_PATH_GENERIC || (path == SBN_PATH_SMFMAC && is24) ||
+                                       (path == SBN_PATH_GEMV && (is24 || pat.N == pat.M));
+        if (!weights_as_stored) return SBN_EUNSUPPORTED;
+        if (ws_bytes < xq_bytes + sx_bytes) return SBN_ESIZE;
+    } else if (ws_bytes < linear_workspace_bytes(it.tokens, it.d_out, it.d_in)) {
+        return SBN_ESIZE;
+    }
+    // workspace: [xq int8 tokens*d_in][sx fp32 tokens][dense int8 W for the comparison path]
+    uint8_t *ws = static_cast<uint8_t *>(workspace);
     if (!it.xq) it.xq = reinterpret_cast<int8_t *>(ws);
     if (!it.sx) it.sx = reinterpret_cast<float *>(ws + xq_bytes);
     int8_t *w_dense = reinterpret_cast<int8_t *>(ws + xq_bytes + sx_bytes);
@@ -222,6 +231,59 @@ sbn_status sbn_sparse_ternary_linear(const void *X, int64_t tokens, int64_t d_in
     if (d_in % 8 != 0) return SBN_EUNSUPPORTED;   // bf16 rows are read in 16-byte vectors
     LinearItem it{X, packed, gamma, bias, Y, xq_out, sx_out, acc_out, tokens, d_in, d_out};
     return linear_one(it, pat, path, workspace, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+// ---- the forward call for callers that cannot allocate --------------------------------------------------------
+// Scratch of sbn_sparse_ternary_linear_static: int8 activations and per-token scales of one call.  Every GPU the
+// library runs on holds its own copy of the array until the process ends.  In host code the array's name is
+// only a handle: the device address is looked up once per device (that device current) and kept.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)SBN_STATIC_SCRATCH_MIB << 20;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+constexpr int STATIC_MAX_DEVICES = 64;
+static std::atomic<void *> g_scratch_ptr[STATIC_MAX_DEVICES];
+
+static sbn_status static_scratch(void **out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) { set_hip_error(e, "hipGetDevice"); return SBN_EHIP; }
+    if (dev < 0 || dev >= STATIC_MAX_DEVICES) { g_last_error = "sbn_sparse_ternary_linear_static: device ordinal beyond 63"; return SBN_EUNSUPPORTED; }
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));   // the current device's copy
+        if (e != hipSuccess || !p) { set_hip_error(e, "hipGetSymbolAddress(scratch)"); return SBN_EHIP; }
+        g_scratch_ptr[dev].store(p, std::memory_order_release);   // two threads racing here store the same address
+    }
+    *out = p;
+    return SBN_OK;
+}
+
+sbn_status sbn_sparse_ternary_linear_static(const void *X, int64_t tokens, int64_t d_in, int64_t d_out, int N, int M,
+                                            const void *packed, const float *gamma, const float *bias, float *Y,
+                                            int8_t *xq_out, float *sx_out, int32_t *acc_out, sbn_path path, void *stream)
+{
+    Pattern pat;
+    if (!packed || !gamma || !Y || tokens <= 0) return SBN_EINVAL;
+    if (!X && (!xq_out || !sx_out)) return SBN_EINVAL;
+    if (path < SBN_PATH_AUTO || path > SBN_PATH_GENERIC) return SBN_EINVAL;
+    sbn_status st = check_shape(d_out, d_in, N, M, pat);
+    if (st != SBN_OK) return st;
+    if (tokens * d_out >= (int64_t)1 << 40) return SBN_EUNSUPPORTED;
+    if (!aligned(X, 16) || !aligned(packed, 16) || !aligned(Y, 16)) return SBN_EALIGN;
+    if (xq_out && !aligned(xq_out, 16)) return SBN_EALIGN;
+    if (acc_out && !aligned(acc_out, 16)) return SBN_EALIGN;
+    if (d_in % 8 != 0) return SBN_EUNSUPPORTED;
+    const size_t need = align_up((size_t)tokens * d_in, 256) + align_up((size_t)tokens * sizeof(float), 256);
+    if (need > STATIC_SCRATCH_BYTES) {
+        g_last_error = "sbn_sparse_ternary_linear_static: tokens * d_in + 4 * tokens = " + std::to_string(need) +
+                       " bytes of scratch needed, the library's buffer holds " + std::to_string(STATIC_SCRATCH_BYTES);
+        return SBN_ESIZE;
+    }
+    void *ws = nullptr;
+    st = static_scratch(&ws);
+    if (st != SBN_OK) return st;
+    LinearItem it{X, packed, gamma, bias, Y, xq_out, sx_out, acc_out, tokens, d_in, d_out};
+    return linear_one(it, pat, path, ws, STATIC_SCRATCH_BYTES, static_cast<hipStream_t>(stream), true);
 }
 
 sbn_status sbn_sparse_ternary_linear_grouped(int count, const void *const *X, const int64_t *tokens,
