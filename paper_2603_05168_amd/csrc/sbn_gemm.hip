@@ -5,6 +5,9 @@
 //           16 int8 values, index word -> the instruction's index register), tokens are B;
 //   dense   v_mfma_i32_32x32x32_i8 on W_eff expanded to int8 with explicit zeros: the in-run
 //           comparison a dense ternary layer would run.
+#include <algorithm>
+#include <vector>
+
 #include "sbn_internal.hpp"
 #include "sbn_mfma.hpp"
 
@@ -29,17 +32,24 @@ struct GemmArgs {
     int tiles_o, tiles_t;
 };
 
-// A grouped launch covers the tiles of up to GEMM_GROUP_MAX problems: problem p owns the blocks
-// [block0[p], block0[p+1]); every block0 is a multiple of 8 so that a problem's block i still runs on
-// XCD i % 8 (blocks beyond a problem's last tile exit at once).  Problems that share tokens run
-// back to back: the tail of one fills the machine together with the head of the next.
+// A launch of the sparse kernel covers up to GEMM_GROUP_MAX problems.
 constexpr int GEMM_GROUP_MAX = 8;
 struct GemmGroup {
     GemmArgs g[GEMM_GROUP_MAX];
-    int block0[GEMM_GROUP_MAX + 1];
     int count;
 };
 
+// Work list of a launch of the sparse kernel, made on the host: block b runs the pieces piece[b * per_block + i],
+// i < per_block, up to the first empty one (width 0).  A piece = (problem, row tile of 512, first token unit of 32 tokens,
+// width in units 1 .. 4).  per_block == 0: no list, the kernel splits the units by formula.
+constexpr int PIECE_TABLE_MAX = 768;
+struct PieceTable {
+    int per_block;
+    uint32_t piece[PIECE_TABLE_MAX];   // bits [2:0] width, [15:3] first unit, [24:16] row tile, [27:25] problem
+};
+static_assert(sizeof(GemmGroup) + sizeof(PieceTable) <= 4000, "both travel as kernel arguments");
+
+// Tile order of the dense comparison kernel.
 // Blocks are dealt round-robin to the 8 XCDs, each with its own 4 MB L2.  XCD x takes the token
 // tiles [x, x+1) * tiles_t/8 and walks them in groups of four: inside a group the token tile is the
 // fastest index, then the row tile.  The 64 blocks an XCD runs at a time then share four token tiles
@@ -174,90 +184,211 @@ __device__ __forceinline__ void load_scales(const GemmArgs &g, int tok0, int lan
 }
 
 // ---- sparse path --------------------------------------------------------------------------------
-// 4 wavefronts, one per 64 rows of the block; each owns 64 rows x 128 tokens = 2 x 4 tiles of 32x32,
-// so one code expansion (VALU) feeds four matrix instructions.
-// Both operands reach LDS through LDS-DMA loads (lane l of a wavefront deposits its 16 bytes at
-// base + 16*l), so no staging registers are needed and every load instruction reads whole cache lines:
-//   tokens   128 tokens x 128 int8 per iteration, ring of 3 stages; one instruction fills 8 token
-//            rows of 128 bytes; the 16-byte column a lane fetches is XOR-swizzled with
-//            (row >> 1) & 7 so that 16-byte reads of 16 consecutive rows fall in distinct banks;
-//   weights  256 rows x 64 bytes (two 32-byte chunks = two iterations) per refill, ring of 2 slots;
-//            one instruction fills 16 rows; 16-byte granules swizzled with (row >> 2) & 3.
-// A lane (row r = lane % 32, half c = lane / 32) reads index words 2c, 2c+1 and code words 2c, 2c+1
-// of its row's chunk (two 8-byte LDS reads per row tile); sub-step u = 0, 1 uses word 2c + u, i.e.
-// the lane supplies weights [64c + 32u, +32) of the chunk.
-constexpr int STAGES = 3;
-constexpr int WSLOT_BYTES = BO * 64;      // 16 KB: two chunks of every row of the block
-constexpr int RA = 2;                     // row tiles per wavefront
-constexpr int TB = BT / 32;               // token tiles per wavefront: all of the block's
+// One persistent block of eight wavefronts per multiprocessor; block tile 512 rows x 128 tokens.  Wavefront w owns the
+// rows 64 w .. 64 w + 63 (two row tiles of 32) and all tokens of the piece (TB = 1 .. 4 token tiles of 32), so one code
+// expansion (nine vector instructions) feeds TB matrix instructions: measured on this part, up to four vector
+// instructions per matrix instruction hide under it, more cost their full time.  The two wavefronts of a SIMD cover
+// each other's waits.  What bounds the main loop is LDS time: per 128-k step the wavefronts read 144 KB of operand
+// fragments and the DMA deposits 32 KB, and the two do not overlap; against two independent blocks of 256 x 128 the
+// shared token tile saves a third of the DMA bytes (256 instead of 384 bytes per matrix instruction).
+// Both operands reach LDS through LDS-DMA loads (lane l of a wavefront deposits its 16 bytes at base + 16*l), so no
+// staging registers are needed and every load instruction reads whole cache lines:
+//   tokens   128 tokens x 128 int8 per stage, ring of NST stages; one instruction fills 8 token rows of 128 bytes; the
+//            16-byte column a lane fetches is XOR-swizzled with (row >> 1) & 7 so that 16-byte reads of 16
+//            consecutive rows fall in distinct banks;
+//   weights  512 rows x 64 bytes (two 32-byte chunks = two iterations) per pair slot, ring of NWP slots; one instruction
+//            fills 16 rows; 16-byte granules swizzled with (row >> 2) & 3.
+// A lane (row r = lane % 32, half c = lane / 32) reads index words 2c, 2c+1 and code words 2c, 2c+1 of its row's chunk
+// (two 8-byte LDS reads per row tile); sub-step u = 0, 1 uses word 2c + u, i.e. the lane supplies weights
+// [64c + 32u, +32) of the chunk.
+// Pieces follow one another without draining the pipeline: when the main loop of a piece ends, the first stages of the
+// block's next piece are requested BEFORE the epilogue of the finished one runs, and the epilogue transposes through a
+// staging area of its own, so the ring is never idle.
+namespace sp {
 
-__global__ void __launch_bounds__(256, 2) gemm_smfmac_kernel(GemmGroup grp)
+constexpr int ROWS = 512;                      // rows of W per block tile
+constexpr int NW = 8;                          // wavefronts
+constexpr int RA = 2;                          // row tiles per wavefront
+constexpr int NST = 3;                         // token stages (16 KB each)
+constexpr int NWP = 2;                         // weight pair slots (32 KB each)
+constexpr int TSTAGE = 128 * KSTEP;
+constexpr int WPAIR = ROWS * 64;
+constexpr int RING_BYTES = NST * TSTAGE + NWP * WPAIR;
+// epilogue staging, one area per wavefront: 16 tokens x (64 rows of fp32 + 16 bytes of padding)
+constexpr int STG_TOKENS = 16;
+constexpr int EROW = 128 * RA + 16;
+constexpr int STG_WAVE = STG_TOKENS * EROW;
+// per-token scales of a piece (128 floats), fetched by DMA with its first stages; two areas, used alternately, because
+// the scales of the next piece arrive while the epilogue of the current one still reads its own
+constexpr int SCALES_OFF = RING_BYTES + NW * STG_WAVE;
+constexpr int LDS_BYTES = SCALES_OFF + 2 * 512;
+static_assert(LDS_BYTES <= 160 * 1024, "ring, staging and scales share the multiprocessor's LDS");
+constexpr int NDW = 32 / NW;                   // weight DMA instructions per wavefront and pair (16 rows each)
+constexpr int token_dma(int TB) { return (4 * TB + NW - 1) / NW; }   // token DMA instructions per wavefront and stage (8 rows each)
+constexpr int cmin(int a, int b) { return a < b ? a : b; }
+
+// Bookkeeping of the DMA ring at compile time.  Iteration j (negative j = the prologue) issues, in this order,
+// weight pair (j - 1) / 2 + NWP if j is odd (NDW instructions), then token stage j + NST (NDT instructions); items with
+// a negative number do not exist.  Returns how many DMA instructions of a wavefront are issued after the given item
+// in iterations jlo .. jhi: the count a wait for that item may leave outstanding (the loads of a wavefront complete
+// in issue order).
+constexpr int issued_after(int NDT, int jlo, int jhi, bool want_pair, int id)
 {
-    int prob = 0;
-    while (prob + 1 < grp.count && (int)blockIdx.x >= grp.block0[prob + 1]) ++prob;
-    const GemmArgs &g = grp.g[prob];
-    const int local_id = blockIdx.x - grp.block0[prob];
-    if (local_id >= g.tiles_o * g.tiles_t) return;   // padding block
-    constexpr int NWAVES = 4;
-    constexpr int STAGE_BYTES = BT * KSTEP;      // 16 KB
-    constexpr int NDT = BT / 8 / NWAVES;         // token DMA instructions per wavefront and stage
-    constexpr int NDW = 16 / NWAVES;             // weight DMA instructions per wavefront and pair
-    static_assert(NDT == TB, "one token DMA instruction is issued under each matrix instruction of a row tile");
-    __shared__ __attribute__((aligned(1024))) int8_t lds[STAGES * STAGE_BYTES + 2 * WSLOT_BYTES];
-    const uint32_t lds0 = lds_address(lds), wlds0 = lds0 + STAGES * STAGE_BYTES;
-    int to, tt;
-    tile_of_block(g, local_id, to, tt);
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int r = lane & 31, c = lane >> 5;
-    const int K = g.d_in, nchunks = K / KSTEP, npairs = (nchunks + 1) / 2;
-    const int o0 = to * BO, t0 = tt * BT;
+    int n = -1;
+    for (int j = jlo; j <= jhi; ++j) {
+        if (j & 1) {
+            const int pid = (j - 1) / 2 + NWP;
+            if (pid >= 0) {
+                if (n >= 0) n += NDW;
+                else if (want_pair && pid == id) n = 0;
+            }
+        }
+        const int sid = j + NST;
+        if (sid >= 0) {
+            if (n >= 0) n += NDT;
+            else if (!want_pair && sid == id) n = 0;
+        }
+    }
+    return n;
+}
+constexpr int LEAD = NST > 2 * NWP - 1 ? NST : 2 * NWP - 1;          // prologue iterations -LEAD .. -1
 
-    // DMA sources as uniform base + 32-bit lane offset, so the per-iteration advance is scalar arithmetic.
-    // tokens: instruction i (0..NDT-1) of this wavefront fills tile rows (NDT*wave + i)*8 .. +7
-    const int8_t *const xbase = g.xq + (int64_t)t0 * K;
-    uint32_t xoff[NDT];
+// What a wavefront needs to issue the DMA of one piece: uniform bases and 32-bit lane offsets (the per-iteration
+// advance is scalar arithmetic).  Token instruction i of wavefront w fills tile rows (NDT w + i) 8 .. + 7, weight
+// instruction i fills block rows (NDW w + i) 16 .. + 15.
+template <int NDT>
+struct PieceDma {
+    const int8_t *xbase;
+    const uint8_t *wbase;
+    uint32_t xoff[NDT], woff[NDW];
+    uint32_t wclip;            // bit i: instruction i fetches granules 2, 3 of its rows, which do not exist in an odd last pair
+    int nchunks, npairs;
+};
+
+template <int NDT>
+__device__ __forceinline__ void dma_setup(PieceDma<NDT> &d, const GemmArgs &g, int to, int t0, int tb, int wave, int lane)
+{
+    const int K = g.d_in;
+    d.nchunks = K / KSTEP;
+    d.npairs = (d.nchunks + 1) / 2;
+    d.xbase = g.xq + (int64_t)t0 * K;
 #pragma unroll
     for (int i = 0; i < NDT; ++i) {
-        const int row = (NDT * wave + i) * 8 + (lane >> 3);
-        const int t = t0 + row < g.tokens ? row : g.tokens - 1 - t0;
-        xoff[i] = (uint32_t)t * (uint32_t)K + 16u * ((lane & 7) ^ ((row >> 1) & 7));
+        int row = (NDT * wave + i) * 8 + (lane >> 3);
+        const int sw = (row >> 1) & 7;
+        row = row < 32 * tb ? row : 32 * tb - 1;                      // rows past the piece: its last row again (never read)
+        const int t = t0 + row < g.tokens ? row : g.tokens - 1 - t0;   // tokens past the matrix: its last token again
+        d.xoff[i] = (uint32_t)t * (uint32_t)K + 16u * ((lane & 7) ^ sw);
     }
-    auto dma_tokens = [&](int kc, int stage) {
-        const int8_t *src = xbase + (int64_t)kc * KSTEP;
-        const uint32_t dst = lds0 + stage * STAGE_BYTES + wave * (NDT * 1024);
-#pragma unroll
-        for (int i = 0; i < NDT; ++i) lds_dma16(src, xoff[i], dst + i * 1024);
-    };
-    // weights: instruction i (0..NDW-1) of this wavefront fills block rows (NDW*wave + i)*16 .. +15
-    const uint8_t *const wbase = g.packed + (int64_t)o0 * nchunks * 32;
-    uint32_t woff[NDW];
-    bool wclip[NDW];
-    const bool odd_tail = (nchunks & 1) != 0;   // the last pair then holds one chunk: its second half is never read
+    const int o0 = to * ROWS;
+    d.wbase = g.packed + (int64_t)o0 * d.nchunks * 32;
+    const bool odd_tail = (d.nchunks & 1) != 0;
+    d.wclip = 0;
 #pragma unroll
     for (int i = 0; i < NDW; ++i) {
         const int row = (NDW * wave + i) * 16 + (lane >> 2);
-        const int o = o0 + row < g.d_out ? row : g.d_out - 1 - o0;
+        const int o = o0 + row < g.d_out ? row : g.d_out - 1 - o0;     // rows past the matrix: its last row again
         const int gran = (lane & 3) ^ ((row >> 2) & 3);
-        woff[i] = (uint32_t)o * (uint32_t)(nchunks * 32) + 16u * gran;
-        wclip[i] = odd_tail && gran >= 2;
+        d.woff[i] = (uint32_t)o * (uint32_t)(d.nchunks * 32) + 16u * gran;
+        if (odd_tail && gran >= 2) d.wclip |= 1u << i;
     }
-    auto dma_weights = [&](int pair, int slot) {
-        const uint8_t *src = wbase + (int64_t)pair * 64;
-        const uint32_t dst = wlds0 + slot * WSLOT_BYTES + wave * (NDW * 1024);
-        const bool last = pair == npairs - 1;
+}
+
+// stages and pairs past the end are fetched again from the last one (into a slot nobody reads): the DMA is
+// unconditional, so that the wait counts are the same in every iteration
+template <int NDT>
+__device__ __forceinline__ void dma_token(const PieceDma<NDT> &d, uint32_t lds0, int wave, int kc, int slot, int i)
+{
+    kc = kc < d.nchunks ? kc : d.nchunks - 1;
+    lds_dma16(d.xbase + (int64_t)kc * KSTEP, d.xoff[i], lds0 + slot * TSTAGE + wave * (NDT * 1024) + i * 1024);
+}
+
+template <int NDT>
+__device__ __forceinline__ void dma_weight(const PieceDma<NDT> &d, uint32_t lds0, int wave, int pair, int slot, int i)
+{
+    pair = pair < d.npairs ? pair : d.npairs - 1;
+    // granules 2, 3 of a clipped pair lie past the row: fetch granule 0/1 again instead (never read)
+    const uint32_t off = (pair == d.npairs - 1 && ((d.wclip >> i) & 1u)) ? d.woff[i] - 32u : d.woff[i];
+    lds_dma16(d.wbase + (int64_t)pair * 64, off, lds0 + NST * TSTAGE + slot * WPAIR + wave * (NDW * 1024) + i * 1024);
+}
+
+// the items of iterations -LEAD .. -1, in the order the wait counts assume
+template <int NDT>
+__device__ __forceinline__ void dma_prologue(const PieceDma<NDT> &d, uint32_t lds0, int wave)
+{
 #pragma unroll
-        for (int i = 0; i < NDW; ++i) {
-            // granules 2, 3 of a clipped pair lie past the row: fetch granule 0/1 again instead (never read)
-            const uint32_t off = (last && wclip[i]) ? woff[i] - 32u : woff[i];
-            lds_dma16(src, off, dst + i * 1024);
+    for (int j = -LEAD; j <= -1; ++j) {
+        if ((j & 1) && (j - 1) / 2 + NWP >= 0) {
+#pragma unroll
+            for (int i = 0; i < NDW; ++i) dma_weight(d, lds0, wave, (j - 1) / 2 + NWP, ((j - 1) / 2 + NWP) % NWP, i);
         }
-    };
-    // LDS read addresses, swizzles folded in.  tokens: row * 128 + 16 * (chunk16 ^ ((row >> 1) & 7));
-    // the row's swizzle does not depend on the token tile (32 b), so tile and ring stage are immediate
-    // offsets of four lane addresses.  weights: row * 64 + 16 * (granule ^ ((row >> 2) & 3)) + 8c,
-    // eight lane addresses that are moved to the other slot once per pair.
-    uint32_t b_lo[2], b_hi[2];   // [sub-step]
+        if (j + NST >= 0) {
+#pragma unroll
+            for (int i = 0; i < NDT; ++i) dma_token(d, lds0, wave, j + NST, (j + NST) % NST, i);
+        }
+    }
+}
+
+// A piece of the work list: (problem, row tile, first token, width in token tiles); width 0 = none.
+struct Piece {
+    int prob, to, t0, tb;
+    int parity;   // which of the two scale areas the piece uses
+};
+
+// requests the first stages of a piece (called with the ring idle: before the first piece and between the main loop
+// and the epilogue of the piece before)
+__device__ __forceinline__ void piece_prologue(const GemmGroup &grp, const Piece &p, int8_t *lds, int wave, int lane)
+{
+    const uint32_t lds0 = lds_address(lds);
+    const GemmArgs &g = grp.g[p.prob];
+    // s_x of the piece's tokens, by the first wavefront and in front of everything else: the oldest request of the
+    // piece, so every wait for a stage covers it and no wait count changes
+    if (wave == 0) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int t = p.t0 + 64 * i + lane;
+            lds_dma4(g.sx, 4u * (uint32_t)(t < g.tokens ? t : g.tokens - 1), lds0 + SCALES_OFF + 512 * p.parity + 256 * i);
+        }
+    }
+    if (token_dma(p.tb) == 2) {
+        PieceDma<2> d;
+        dma_setup(d, g, p.to, p.t0, p.tb, wave, lane);
+        dma_prologue(d, lds0, wave);
+    } else {
+        PieceDma<1> d;
+        dma_setup(d, g, p.to, p.t0, p.tb, wave, lane);
+        dma_prologue(d, lds0, wave);
+    }
+}
+
+// Main loop and epilogue of one piece whose prologue is already in flight: rows [512 to, +512) of W against tokens
+// [t0, t0 + 32 TB), the whole input dimension.  LIVE = false: a wavefront whose rows lie past the matrix (ragged last
+// row tile) only moves data and keeps the barriers.
+template <int TB, bool LIVE>
+__device__ __forceinline__ void piece_body(const GemmGroup &grp, const Piece &p, const Piece &next, int8_t *lds, const int wave,
+                                           int lane)
+{
+    // everything derived from the lane number is computed anew for every piece: hoisted out of the loop over pieces,
+    // the lane addresses of all instantiations would be live at once and spill
+    asm volatile("" : "+v"(lane));
+    constexpr int NDT = token_dma(TB);
+    constexpr int WAIT_TOP = cmin(issued_after(NDT, -LEAD, -1, false, 0), issued_after(NDT, -LEAD, -1, true, 0));
+    // in the middle of iteration kc: token stage kc + 1 and, for odd kc, weight pair (kc + 1) / 2 must have landed
+    constexpr int WAIT_EVEN = issued_after(NDT, -LEAD, 99, false, 101);
+    constexpr int WAIT_ODD = cmin(issued_after(NDT, -LEAD, 100, false, 102), issued_after(NDT, -LEAD, 100, true, 51));
+    static_assert(WAIT_TOP >= 0 && WAIT_EVEN >= 0 && WAIT_ODD >= 0 && WAIT_TOP < 64 && WAIT_EVEN < 64 && WAIT_ODD < 64,
+                  "ring bookkeeping");
+    const GemmArgs &g = grp.g[p.prob];
+    const int to = p.to, t0 = p.t0;
+    const uint32_t lds0 = lds_address(lds), wlds0 = lds0 + NST * TSTAGE;
+    const int r = lane & 31, c = lane >> 5;
+    const int nchunks = g.d_in / KSTEP;
+    const int o0 = to * ROWS;
+    PieceDma<NDT> d;
+    dma_setup(d, g, to, t0, TB, wave, lane);
+
+    // ---- LDS read addresses (swizzles as in the DMA patterns above)
+    uint32_t b_lo[2], b_hi[2];   // [sub-step]; the token tile is an immediate offset, the ring slot a scalar
     {
         const int sw = (r >> 1) & 7;
 #pragma unroll
@@ -266,7 +397,7 @@ __global__ void __launch_bounds__(256, 2) gemm_smfmac_kernel(GemmGroup grp)
             b_hi[u] = lds0 + r * KSTEP + 16 * ((4 + 2 * u + c) ^ sw);
         }
     }
-    uint32_t a_idx[2][RA], a_code[2][RA];   // [chunk of the pair][row tile], in the slot of the pair being read
+    uint32_t a_idx[2][RA], a_code[2][RA];   // [chunk of the pair][row tile], slot 0
 #pragma unroll
     for (int a = 0; a < RA; ++a) {
         const int row = wave * (32 * RA) + 32 * a + r, sw = (row >> 2) & 3;
@@ -289,120 +420,281 @@ __global__ void __launch_bounds__(256, 2) gemm_smfmac_kernel(GemmGroup grp)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0;
 
-    // Software pipeline, one barrier per iteration placed between its two sub-steps:
-    //   sub-step 0 of iteration kc   compute (kc, 0); the LDS reads of the tokens of (kc, 1) go out
-    //                                under its first matrix instructions;
-    //   middle                       wait for token stage kc+1 (and, for odd kc, the weight pair of
-    //                                kc+1), barrier.  Every wavefront now holds all of stage kc in
-    //                                registers, so its slot can take token stage kc+3 and, for odd
-    //                                kc, the slot of pair (kc-1)/2 can take pair (kc+1)/2 + 1;
-    //   sub-step 1                   compute (kc, 1); under its matrix instructions go those DMA
-    //                                instructions and the LDS reads of the weights and tokens of (kc+1, 0).
-    // A wavefront issues at most one instruction every few cycles, so what is placed between matrix
-    // instructions is free while the matrix pipe is busy, and a block of other instructions after
-    // them leaves the pipe idle: the source order is the intended issue order and a scheduling
-    // barrier after every matrix instruction keeps it.  The DMA is unconditional (past the end it
-    // fetches the last chunk again into a slot nobody reads), so the loop body has no branches and
-    // the wait counts are the same every iteration; they rely on vector-memory operations of a
-    // wavefront completing in issue order (tokens are issued before weights).
-    float sxv[TB + 1];
-    load_scales<TB>(g, t0, lane, sxv);
-    // prologue in an order that leaves the ring in the state the loop's wait counts assume: behind
-    // token stage 1 only token stage 2 and weight pair 1 are younger
-    dma_weights(0, 0);
-    dma_tokens(0, 0);
-    dma_tokens(nchunks > 1 ? 1 : 0, 1);
-    dma_tokens(nchunks > 2 ? 2 : nchunks - 1, 2);
-    dma_weights(npairs > 1 ? 1 : 0, 1);
-
     v2u icur[RA], ccur[RA], inext[RA], cnext[RA];
     v8i bq[2][TB];
-    auto read_weights = [&](const int h, v2u (&iv)[RA], v2u (&cv)[RA]) {
+    auto read_weights = [&](const int slot, const int h, const int a, v2u (&iv)[RA], v2u (&cv)[RA]) {
+        iv[a] = *(lds_u2)(uintptr_t)(a_idx[h][a] + slot * WPAIR);
+        cv[a] = *(lds_u2)(uintptr_t)(a_code[h][a] + slot * WPAIR);
+    };
+    auto token_read = [&](const int slot, const int u, const int b, v8i &bf) {
+        bf.lo = *(lds_v4i)(uintptr_t)(b_lo[u] + slot * TSTAGE + 32 * b * KSTEP);
+        bf.hi = *(lds_v4i)(uintptr_t)(b_hi[u] + slot * TSTAGE + 32 * b * KSTEP);
+    };
+    // One sub-step: RA x TB matrix instructions; side(s) is issued after instruction s (s = 0 .. RA * TB - 1).  A
+    // wavefront issues at most one instruction every few cycles, so what is placed between matrix instructions is free
+    // while the matrix pipe is busy, and a block of other instructions after them leaves the pipe idle: the source order
+    // is the intended issue order and a scheduling barrier after every matrix instruction keeps it.
+    constexpr int NSLOT = RA * TB;
+    auto substep = [&](const int u, const v8i (&bf)[TB], auto &&side) {
 #pragma unroll
         for (int a = 0; a < RA; ++a) {
-            iv[a] = *(lds_u2)(uintptr_t)a_idx[h][a];
-            cv[a] = *(lds_u2)(uintptr_t)a_code[h][a];
-        }
-    };
-    auto token_read = [&](const int stage, const int u, const int b, v8i &bf) {
-        bf.lo = *(lds_v4i)(uintptr_t)(b_lo[u] + stage * STAGE_BYTES + 32 * b * KSTEP);
-        bf.hi = *(lds_v4i)(uintptr_t)(b_hi[u] + stage * STAGE_BYTES + 32 * b * KSTEP);
-    };
-    auto mma_row = [&](const int u, const int a, const v8i (&bf)[TB], auto &&between) {
-        const int iv = (int)(u ? icur[a].y : icur[a].x);
-        const v4i av = expand_codes(u ? ccur[a].y : ccur[a].x, ones);
+            if constexpr (LIVE) {
+                const int iv = (int)(u ? icur[a].y : icur[a].x);
+                const v4i av = expand_codes(u ? ccur[a].y : ccur[a].x, ones);
 #pragma unroll
-        for (int b = 0; b < TB; ++b) {
-            acc[a][b] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(av, bf[b], acc[a][b], iv, 0, 0);
-            between(b);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    };
-
-    SBN_WAIT_VMCNT(NDW + 2 * NDT);   // weight pair 0 and token stage 0 are in; the three younger groups may fly
-    __syncthreads();
-    read_weights(0, icur, ccur);
+                for (int b = 0; b < TB; ++b) {
+                    acc[a][b] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(av, bf[b], acc[a][b], iv, 0, 0);
+                    side(a * TB + b);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            } else {
 #pragma unroll
-    for (int b = 0; b < TB; ++b) token_read(0, 0, b, bq[0][b]);
-    // one iteration that has a successor; stage = kc % 3 and h = kc & 1 are literals at every call
-    auto iteration = [&](const int kc, const int stage, const int h) {
-        mma_row(0, 0, bq[0], [&](const int b) { token_read(stage, 1, b, bq[1][b]); });
-        mma_row(0, 1, bq[0], [&](const int) {});
-        if (h == 0) SBN_WAIT_VMCNT(NDT + NDW); else SBN_WAIT_VMCNT(NDT);   // what the previous iteration issued may still fly
-        __syncthreads();
-        if (h == 1) {   // the reads below start a new pair: move the lane addresses to its slot
-            const uint32_t delta = (((kc + 1) >> 1) & 1) ? (uint32_t)WSLOT_BYTES : (uint32_t)-WSLOT_BYTES;
-#pragma unroll
-            for (int a = 0; a < RA; ++a) {
-                a_idx[0][a] += delta; a_idx[1][a] += delta; a_code[0][a] += delta; a_code[1][a] += delta;
+                for (int b = 0; b < TB; ++b) side(a * TB + b);
             }
         }
-        read_weights(h ^ 1, inext, cnext);
-        __builtin_amdgcn_sched_barrier(0);
-        const int kt = kc + 3 < nchunks ? kc + 3 : nchunks - 1;
-        const int8_t *tsrc = xbase + (int64_t)kt * KSTEP;
-        const uint32_t tdst = lds0 + stage * STAGE_BYTES + wave * (NDT * 1024);
-        mma_row(1, 0, bq[1], [&](const int b) { lds_dma16(tsrc, xoff[b], tdst + b * 1024); });
-        if (h == 1) {
-            const int pw = (kc + 1) / 2 + 1;
-            dma_weights(pw < npairs ? pw : npairs - 1, pw & 1);
-        }
-        mma_row(1, 1, bq[1], [&](const int b) { token_read(stage == 2 ? 0 : stage + 1, 0, b, bq[0][b]); });
+    };
+
+    // Weight pair 0 and token stage 0 are in; what was requested after them may fly.  The count is of ALL outstanding
+    // vector-memory operations: loads complete in issue order among themselves, but stores (the epilogue of the piece
+    // before, issued after this piece's first requests) may be acknowledged before older loads, so they cannot be
+    // granted as outstanding - with at most WAIT_TOP operations of any kind in flight, at most WAIT_TOP loads are.
+    SBN_WAIT_VMCNT(WAIT_TOP);
+    __syncthreads();
+    if constexpr (LIVE) {
 #pragma unroll
-        for (int a = 0; a < RA; ++a) { icur[a] = inext[a]; ccur[a] = cnext[a]; }
+        for (int a = 0; a < RA; ++a) read_weights(0, 0, a, icur, ccur);
+#pragma unroll
+        for (int b = 0; b < TB; ++b) token_read(0, 0, b, bq[0][b]);
+    }
+    // One iteration that has a successor; ts = kc % NST and ps = (kc / 2) % NWP are scalars, h = kc & 1 is a literal.
+    //   sub-step 0   compute (kc, first half); the token fragments of the second half are read under it
+    //   middle       wait for token stage kc + 1 (odd kc: and weight pair (kc + 1) / 2), barrier: every wavefront
+    //                now holds all of stage kc in registers, so its slot takes stage kc + NST, and for odd kc the
+    //                slot of pair kc / 2 takes pair kc / 2 + NWP
+    //   sub-step 1   compute (kc, second half); under it go the DMA instructions, the weight words of chunk kc + 1
+    //                and the token fragments of (kc + 1, first half), one per matrix instruction
+    // The wait counts hold the outstanding DMA of this wavefront only; stores of the epilogue before that are still in
+    // flight in the first iterations make a wait longer, never shorter.
+    auto iteration = [&](const int kc, const int ts, const int ps, const int h) {
+        substep(0, bq[0], [&](const int s) {
+            if constexpr (LIVE) { if (s < TB) token_read(ts, 1, s, bq[1][s]); }
+        });
+        if (h == 0) SBN_WAIT_VMCNT(WAIT_EVEN); else SBN_WAIT_VMCNT(WAIT_ODD);
+        __syncthreads();
+        const int nts = ts + 1 == NST ? 0 : ts + 1;                         // slot of token stage kc + 1
+        const int nps = h == 1 ? (ps + 1 == NWP ? 0 : ps + 1) : ps;         // slot of the pair of chunk kc + 1
+        substep(1, bq[1], [&](const int s) {
+            // side operations in issue order: weight DMA (odd kc), token DMA, weight words, token fragments;
+            // operation k goes to slot k, the last slot takes what is left over
+            constexpr int NOPS = NDW + NDT + RA + TB;
+#pragma unroll
+            for (int k = 0; k < NOPS; ++k) {
+                if ((k < NSLOT ? k : NSLOT - 1) != s) continue;
+                if (k < NDW) { if (h == 1) dma_weight(d, lds0, wave, kc / 2 + NWP, ps, k); }
+                else if (k < NDW + NDT) dma_token(d, lds0, wave, kc + NST, ts, k - NDW);
+                else if constexpr (LIVE) {
+                    if (k < NDW + NDT + RA) read_weights(nps, h ^ 1, k - NDW - NDT, inext, cnext);
+                    else token_read(nts, 0, k - NDW - NDT - RA, bq[0][k - NDW - NDT - RA]);
+                }
+            }
+        });
+        if constexpr (LIVE) {
+#pragma unroll
+            for (int a = 0; a < RA; ++a) { icur[a] = inext[a]; ccur[a] = cnext[a]; }
+        }
     };
     const int nsteady = nchunks - 1;   // iterations with a successor
-    int kc = 0;
-    for (; kc + 6 <= nsteady; kc += 6) {
-        iteration(kc, 0, 0);
-        iteration(kc + 1, 1, 1);
-        iteration(kc + 2, 2, 0);
-        iteration(kc + 3, 0, 1);
-        iteration(kc + 4, 1, 0);
-        iteration(kc + 5, 2, 1);
+    int kc = 0, ts = 0, ps = 0;
+    for (; kc + 2 <= nsteady; kc += 2) {
+        iteration(kc, ts, ps, 0);
+        ts = ts + 1 == NST ? 0 : ts + 1;
+        iteration(kc + 1, ts, ps, 1);
+        ts = ts + 1 == NST ? 0 : ts + 1;
+        ps = ps + 1 == NWP ? 0 : ps + 1;
     }
-    // up to five more, selected so that stage and h stay literals (kc is a multiple of 6 here)
-    if (kc < nsteady) { iteration(kc, 0, 0); ++kc; }
-    if (kc < nsteady) { iteration(kc, 1, 1); ++kc; }
-    if (kc < nsteady) { iteration(kc, 2, 0); ++kc; }
-    if (kc < nsteady) { iteration(kc, 0, 1); ++kc; }
-    if (kc < nsteady) { iteration(kc, 1, 0); ++kc; }
+    if (kc < nsteady) {
+        iteration(kc, ts, ps, 0);
+        ts = ts + 1 == NST ? 0 : ts + 1;
+    }
     // last chunk: nothing left to fetch
     {
-        const int stage = kc % STAGES;
+        if constexpr (LIVE) {
 #pragma unroll
-        for (int b = 0; b < TB; ++b) {
-            bq[1][b].lo = *(lds_v4i)(uintptr_t)(b_lo[1] + stage * STAGE_BYTES + 32 * b * KSTEP);
-            bq[1][b].hi = *(lds_v4i)(uintptr_t)(b_hi[1] + stage * STAGE_BYTES + 32 * b * KSTEP);
+            for (int b = 0; b < TB; ++b) token_read(ts, 1, b, bq[1][b]);
         }
-        mma_row(0, 0, bq[0], [&](const int) {});
-        mma_row(0, 1, bq[0], [&](const int) {});
-        mma_row(1, 0, bq[1], [&](const int) {});
-        mma_row(1, 1, bq[1], [&](const int) {});
+        substep(0, bq[0], [&](const int) {});
+        substep(1, bq[1], [&](const int) {});
     }
-    SBN_WAIT_VMCNT(0);   // surplus DMA of the last iterations must not land in the epilogue's staging area
+    __syncthreads();     // every wavefront has read the last stage: the ring can take the next piece
+    // The surplus DMA of the last iterations is still in flight: it lands in ring slots that nobody reads any more and
+    // that the same wavefront's later requests overwrite in issue order; the staging area lies outside the ring.
+    if (next.tb > 0) piece_prologue(grp, next, lds, wave, lane);
 
-    block_epilogue<RA, TB>(g, acc, sxv, lds, o0, o0 + wave * (32 * RA), t0, wave, lane);
+    // ---- epilogue: rescale, transpose through the wavefront's staging area (16 tokens x 64 rows of fp32 per pass) and
+    // write whole rows of 256 bytes with streaming stores (Y is not read again here and must not push the operands out
+    // of L2; per-lane stores of 32 contiguous bytes measured 1.5x the write traffic); ragged edges and the int32
+    // accumulator output store per lane
+    // The epilogue issues no vector loads: one would make the compiler wait for everything outstanding, the requests
+    // for the next piece included.  gamma is a scalar load, the s_x of the piece came into LDS with its first stages.
+    if constexpr (LIVE) {
+        float sxv[TB + 1];
+        sxv[TB] = *g.gamma;
+#pragma unroll
+        for (int b = 0; b < TB; ++b) sxv[b] = *reinterpret_cast<const float *>(lds + SCALES_OFF + 512 * p.parity + 4 * (32 * b + r));
+        const int orow = o0 + wave * (32 * RA);
+        const bool fast_store = (g.d_out & 3) == 0 && orow + 32 * RA <= g.d_out && !g.acc_out;
+        if (fast_store) {
+            constexpr int LPR = 8 * RA;              // lanes (16 bytes each) per token row
+            constexpr int RPI = 64 / LPR;            // token rows per store instruction
+            int8_t *const est = lds + RING_BYTES + wave * STG_WAVE;
+            const int tokens = g.tokens;
+            const int64_t d_out = g.d_out;
+            const bool all_tokens = t0 + 32 * TB <= tokens;
+            const bool has_bias = g.bias != nullptr;
+            v4f bias4 = {0.f, 0.f, 0.f, 0.f};
+            if (has_bias) bias4 = *reinterpret_cast<const v4f *>(g.bias + orow + 4 * (lane % LPR));
+            float *const ybase = g.Y + (int64_t)(t0 + lane / LPR) * d_out + orow + 4 * (lane % LPR);
+#pragma unroll
+            for (int b = 0; b < TB; ++b) {
+                const float scale = __fdiv_rn(sxv[TB], sxv[b]);
+#pragma unroll
+                for (int half = 0; half < 32 / STG_TOKENS; ++half) {
+                    // the lanes that hold tokens 16 half .. + 15 of the tile stage their 32 values
+                    if ((r >> 4) == half) {
+#pragma unroll
+                        for (int a = 0; a < RA; ++a)
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) {
+                                const v4f y = {(float)acc[a][b][4 * q + 0] * scale, (float)acc[a][b][4 * q + 1] * scale,
+                                               (float)acc[a][b][4 * q + 2] * scale, (float)acc[a][b][4 * q + 3] * scale};
+                                *reinterpret_cast<v4f *>(est + (r & 15) * EROW + (32 * a + 8 * q + 4 * c) * 4) = y;
+                            }
+                    }
+                    asm volatile("" ::: "memory");   // the reads below are of what the lanes above have just written
+                    // the wavefront reads back what it wrote itself (its LDS operations complete in order):
+                    // all reads of the pass first, then the stores, so that the LDS latency is paid once
+                    v4f yv[STG_TOKENS / RPI];
+#pragma unroll
+                    for (int j = 0; j < STG_TOKENS / RPI; ++j)
+                        yv[j] = *reinterpret_cast<const v4f *>(est + (RPI * j + lane / LPR) * EROW + (lane % LPR) * 16);
+#pragma unroll
+                    for (int j = 0; j < STG_TOKENS / RPI; ++j) {
+                        if (has_bias) yv[j] += bias4;
+                        const int trow = 32 * b + STG_TOKENS * half + RPI * j;
+                        if (all_tokens || t0 + trow + lane / LPR < tokens)
+                            __builtin_nontemporal_store(yv[j], reinterpret_cast<v4f *>(ybase + (int64_t)trow * d_out));
+                    }
+                    asm volatile("" ::: "memory");   // the next pass overwrites the staging area only after these reads
+                }
+            }
+        } else if (orow < g.d_out) {
+#pragma unroll
+            for (int b = 0; b < TB; ++b) {
+                const int t = t0 + 32 * b + r;
+#pragma unroll
+                for (int a = 0; a < RA; ++a) store_tile(g, acc[a][b], orow + 32 * a + 4 * c, t, __fdiv_rn(sxv[TB], sxv[b]));
+            }
+        }
+    }
+}
+
+template <int TB>
+__device__ __forceinline__ void piece_live(const GemmGroup &grp, const Piece &p, const Piece &next, int8_t *lds, int wave, int lane)
+{
+    const bool live = p.to * ROWS + wave * (32 * RA) < grp.g[p.prob].d_out;   // a ragged last row tile leaves whole wavefronts idle
+    if (live) piece_body<TB, true>(grp, p, next, lds, wave, lane);
+    else piece_body<TB, false>(grp, p, next, lds, wave, lane);
+}
+
+__device__ __forceinline__ void piece_run(const GemmGroup &grp, const Piece &p, const Piece &next, int8_t *lds, int wave, int lane)
+{
+    if (p.tb == 4) piece_live<4>(grp, p, next, lds, wave, lane);
+    else if (p.tb == 3) piece_live<3>(grp, p, next, lds, wave, lane);
+    else if (p.tb == 2) piece_live<2>(grp, p, next, lds, wave, lane);
+    else piece_live<1>(grp, p, next, lds, wave, lane);
+}
+
+}  // namespace sp
+
+// The work of a launch is counted in units of 512 rows x 32 tokens.  Blocks go round-robin to the 8 XCDs (each with
+// its own 4 MB L2); XCD x owns the token units [x, x + 1) * ceil(units / 8) of every problem, cut into groups of 16
+// units (512 tokens: their int8 activations stay in its L2 while the packed weights stream through once per group).
+// A strip = (problem, group, row tile).  Launches small enough for a work list (made on the host, see
+// make_piece_table) run the pieces listed for each block; larger ones give every block of an XCD a consecutive run of
+// the XCD's units in the order strip, unit (the same number of units each, +-1), cut into pieces of at most four units
+// that do not cross a strip.
+__global__ void __launch_bounds__(64 * sp::NW) gemm_smfmac_kernel(GemmGroup grp, PieceTable tab)
+{
+    __shared__ __attribute__((aligned(1024))) int8_t lds[sp::LDS_BYTES];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const sp::Piece none{0, 0, 0, 0, 0};
+    if (tab.per_block > 0) {
+        auto decode = [&](int i) {
+            if (i >= tab.per_block) return none;
+            const uint32_t pc = tab.piece[blockIdx.x * tab.per_block + i];
+            return sp::Piece{(int)(pc >> 25), (int)((pc >> 16) & 0x1ff), (int)((pc >> 3) & 0x1fff) * 32, (int)(pc & 7), i & 1};
+        };
+        // the pieces of a block are listed without gaps: the first empty entry ends the list
+        sp::Piece cur = decode(0);
+        if (cur.tb == 0) return;
+        sp::piece_prologue(grp, cur, lds, wave, lane);
+        for (int i = 1; cur.tb > 0; ++i) {
+            const sp::Piece next = decode(i);
+            sp::piece_run(grp, cur, next, lds, wave, lane);
+            cur = next;
+        }
+        return;
+    }
+    const int x = blockIdx.x & 7, j = blockIdx.x >> 3, nb = gridDim.x >> 3;
+    constexpr int GROUP_UNITS = 16;
+    // units of problem p that XCD x owns: [x * upx, min((x + 1) * upx, units)), upx = ceil(units / 8)
+    auto own_units = [&](int p, int &first) {
+        const int units = (grp.g[p].tokens + 31) >> 5, upx = (units + 7) >> 3;
+        first = x * upx;
+        const int n = units - first;
+        return n < 0 ? 0 : n < upx ? n : upx;
+    };
+    int total = 0;
+    for (int p = 0; p < grp.count; ++p) {
+        int first;
+        total += (int)((grp.g[p].d_out + sp::ROWS - 1) / sp::ROWS) * own_units(p, first);
+    }
+    const int q = total / nb, rem = total % nb;
+    int f = j * q + (j < rem ? j : rem);
+    const int end = f + q + (j < rem ? 1 : 0);
+    int prob = 0, group = 0, base = 0, parity = 0;
+    // the piece that starts at flat unit f (f only grows, so the search for its strip resumes where it stopped)
+    auto piece_at = [&](int &f) {
+        if (f >= end) return none;
+        int first, n, gsz, tiles_o;
+        for (;;) {
+            n = own_units(prob, first);
+            tiles_o = (grp.g[prob].d_out + sp::ROWS - 1) / sp::ROWS;
+            gsz = n - group * GROUP_UNITS;
+            gsz = gsz > GROUP_UNITS ? GROUP_UNITS : gsz;
+            const int cnt = gsz > 0 ? tiles_o * gsz : 0;
+            if (gsz > 0 && f < base + cnt) break;
+            base += cnt;
+            if (gsz <= 0 || (group + 1) * GROUP_UNITS >= n) { ++prob; group = 0; } else ++group;
+        }
+        const int local = f - base;
+        const int to = local / gsz, u = local % gsz;
+        int w = gsz - u;
+        w = w > 4 ? 4 : w;
+        w = w > end - f ? end - f : w;
+        f += w;
+        parity ^= 1;
+        return sp::Piece{prob, to, (first + group * GROUP_UNITS + u) * 32, w, parity};
+    };
+    sp::Piece cur = piece_at(f);
+    if (cur.tb == 0) return;
+    sp::piece_prologue(grp, cur, lds, wave, lane);
+    while (cur.tb > 0) {
+        const sp::Piece next = piece_at(f);
+        sp::piece_run(grp, cur, next, lds, wave, lane);
+        cur = next;
+    }
 }
 
 // ---- dense comparison path ---------------------------------------------------------------------
@@ -434,6 +726,7 @@ __global__ void __launch_bounds__(256) expand_dense_kernel(const uint8_t *__rest
 // (no index register, no code expansion) into v_mfma_i32_32x32x32_i8, twice as many of them.
 // Stage = 64 k of the 256 weight rows and 128 token rows (64-byte rows, 24 KB), ring of 3 stages;
 // one DMA instruction fills 16 rows, 16-byte granules swizzled with (row >> 2) & 3.
+constexpr int STAGES = 3;
 constexpr int DK = 64;
 constexpr int DSTAGE = (BO + BT) * DK;   // 24 KB
 
@@ -576,19 +869,102 @@ GemmArgs make_args(const LinearItem &it, int block_tokens = BT)
 
 }  // namespace
 
+// Deals the work of a launch to the blocks (host side).  Per XCD: the strips (problem, token group of 16 units, row
+// tile of 512) are cut into exactly m * nb pieces of at most four units, as even as the strip lengths allow; the pieces
+// are sorted by width and dealt to the nb blocks of the XCD in snake order, so that every block gets m pieces whose
+// widths add up to the same number of units (+-1) and no block is left with single-unit crumbs (a piece of one unit
+// pays nine vector instructions per matrix instruction).  Every other block runs its pieces in reverse order, so that
+// neighbours do not reach their epilogues (bursts of Y stores) together.  Returns blocks per XCD; leaves
+// tab.per_block = 0 (formula split in the kernel) when the list would not fit.
+static int make_piece_table(const GemmGroup &grp, PieceTable &tab)
+{
+    constexpr int GROUP_UNITS = 16;
+    struct Strip { int prob, to, unit0, len, npieces; };
+    static thread_local std::vector<Strip> strips;
+    static thread_local std::vector<uint32_t> pieces;
+    static thread_local std::vector<std::vector<uint32_t>> per_block;
+    int nb = device_cus() / 8;
+    nb = nb < 1 ? 1 : nb;
+    int most = 0;   // units of the XCD with the most work
+    for (int x = 0; x < 8; ++x) {
+        int total = 0;
+        for (int p = 0; p < grp.count; ++p) {
+            const int units = (grp.g[p].tokens + 31) / 32, upx = (units + 7) / 8;
+            const int n = units - x * upx;
+            total += (int)ceil_div(grp.g[p].d_out, sp::ROWS) * (n < 0 ? 0 : n < upx ? n : upx);
+        }
+        most = total > most ? total : most;
+    }
+    nb = most < nb ? most : nb;
+    nb = nb < 1 ? 1 : nb;
+    const int m = (int)ceil_div(ceil_div(most, nb), 4);   // pieces per block: the busiest XCD's units per block, four at a time
+    tab.per_block = 0;
+    if (m * nb * 8 > PIECE_TABLE_MAX) return nb;
+    for (int i = 0; i < m * nb * 8; ++i) tab.piece[i] = 0;
+    per_block.resize(nb);
+    for (int x = 0; x < 8; ++x) {
+        strips.clear();
+        int minpieces = 0;
+        for (int p = 0; p < grp.count; ++p) {
+            const int units = (grp.g[p].tokens + 31) / 32, upx = (units + 7) / 8;
+            int n = units - x * upx;
+            n = n < 0 ? 0 : n < upx ? n : upx;
+            const int tiles_o = (int)ceil_div(grp.g[p].d_out, sp::ROWS);
+            for (int g0 = 0; g0 < n; g0 += GROUP_UNITS)
+                for (int to = 0; to < tiles_o; ++to) {
+                    const int len = n - g0 < GROUP_UNITS ? n - g0 : GROUP_UNITS;
+                    strips.push_back(Strip{p, to, x * upx + g0, len, (len + 3) / 4});
+                    minpieces += (len + 3) / 4;
+                }
+        }
+        if (strips.empty()) continue;
+        // more pieces than the minimum: cut the strips with the widest pieces finer, one more piece at a time
+        int extra = m * nb - minpieces;
+        while (extra > 0) {
+            int best = -1;
+            for (size_t i = 0; i < strips.size(); ++i)
+                if (strips[i].npieces < strips[i].len &&
+                    (best < 0 || strips[i].len * strips[best].npieces > strips[best].len * strips[i].npieces))
+                    best = (int)i;
+            if (best < 0) break;
+            ++strips[best].npieces;
+            --extra;
+        }
+        pieces.clear();
+        for (const Strip &st : strips) {
+            int u = 0;
+            for (int k = 0; k < st.npieces; ++k) {
+                const int w = st.len / st.npieces + (k < st.len % st.npieces ? 1 : 0);
+                pieces.push_back((uint32_t)w | ((uint32_t)(st.unit0 + u) << 3) | ((uint32_t)st.to << 16) | ((uint32_t)st.prob << 25));
+                u += w;
+            }
+        }
+        std::stable_sort(pieces.begin(), pieces.end(), [](uint32_t a, uint32_t b) { return (a & 7) > (b & 7); });
+        for (int j = 0; j < nb; ++j) per_block[j].clear();
+        for (size_t k = 0; k < pieces.size(); ++k) {
+            const int round = (int)(k / nb), pos = (int)(k % nb);
+            per_block[(round & 1) ? nb - 1 - pos : pos].push_back(pieces[k]);
+        }
+        for (int j = 0; j < nb; ++j) {
+            std::vector<uint32_t> &l = per_block[j];
+            if ((int)l.size() > m) return nb;   // cannot happen: every round gives a block at most one piece
+            if (j & 1) std::reverse(l.begin(), l.end());
+            for (size_t i = 0; i < l.size(); ++i) tab.piece[(size_t)(j * 8 + x) * m + i] = l[i];
+        }
+    }
+    tab.per_block = m;
+    return nb;
+}
+
 sbn_status launch_gemm_smfmac(int count, const LinearItem *items, hipStream_t stream)
 {
     for (int first = 0; first < count; first += GEMM_GROUP_MAX) {
         GemmGroup grp;
         grp.count = count - first < GEMM_GROUP_MAX ? count - first : GEMM_GROUP_MAX;
-        int blocks = 0;
-        for (int i = 0; i < grp.count; ++i) {
-            grp.g[i] = make_args(items[first + i]);
-            grp.block0[i] = blocks;
-            blocks += (grp.g[i].tiles_o * grp.g[i].tiles_t + 7) & ~7;
-        }
-        grp.block0[grp.count] = blocks;
-        hipLaunchKernelGGL(gemm_smfmac_kernel, dim3(blocks), dim3(256), 0, stream, grp);
+        for (int i = 0; i < grp.count; ++i) grp.g[i] = make_args(items[first + i]);
+        static thread_local PieceTable tab;
+        const int per_xcd = make_piece_table(grp, tab);
+        hipLaunchKernelGGL(gemm_smfmac_kernel, dim3(8 * per_xcd), dim3(64 * sp::NW), 0, stream, grp, tab);
         sbn_status st = check_launch("gemm_smfmac_kernel");
         if (st != SBN_OK) return st;
     }

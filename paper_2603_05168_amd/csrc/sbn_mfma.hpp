@@ -71,6 +71,15 @@ __device__ __forceinline__ void lds_dma16(const void *base, uint32_t voff, uint3
                  : "memory", "m0");
 }
 
+// the same with one dword per lane: lane l deposits its 4 bytes at lds_addr + 4*l
+__device__ __forceinline__ void lds_dma4(const void *base, uint32_t voff, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(base)
+                 : "memory", "m0");
+}
+
 __device__ __forceinline__ uint32_t lds_address(const void *p)
 {
     return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
