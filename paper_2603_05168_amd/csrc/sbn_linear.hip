@@ -389,9 +389,9 @@ struct GemvStreamItem {
 // grid take one token row each (same arithmetic as the quantizer kernels), write the int8 row and its
 // scale to the workspace and raise a per-token flag; every block waits for the flags of an input, with
 // its first weight loads already in flight, before it stages that input - the quantizer then costs no
-// launch of its own.  Rows, scales and flags move through device-scope atomic accesses (served where
-// the eight L2s meet) ordered by waiting for the stores' acknowledgement: with release/acquire fences,
-// an L2 write-back or invalidation each, the same scheme was slower than the separate launch.
+// launch of its own.  Rows and scales are ordinary stores and loads; the flag is stored with release
+// and, once seen, followed by an acquire fence, both at device scope, so the hand-over rests on the
+// language's memory model alone (one L2 write-back per producer block, one invalidation per consumer).
 // The wait is bounded: a block out of polls quantizes the rows itself into LDS (same result).
 struct GemvStreamInput {
     const uint4 *X;              // bf16 [tokens, d_in]
@@ -403,6 +403,7 @@ struct GemvStreamInput {
 constexpr int GEMV_STREAM_MAX = 64;
 constexpr int GEMV_STREAM_INPUTS = 4;
 constexpr int GEMV_QUANT_VEC = 4;    // 16-byte vectors of a row per thread when a block quantizes it
+constexpr int STAGE_BATCH = 8;       // activation loads a thread has in flight while it stages a block's input in LDS
 struct GemvStreamTable {
     GemvStreamItem it[GEMV_STREAM_MAX];
     int unit0[GEMV_STREAM_MAX + 1];   // first unit of each problem
@@ -453,7 +454,7 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
         for (int w = 0; w < NW; ++w) m = wave_amax[w] > m ? wave_amax[w] : m;
         const float s = scale_from_absmax_bits(m);
         if (threadIdx.x == 0) {
-            if (publish) __hip_atomic_store(&in.sx[t], __float_as_uint(s), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (publish) in.sx[t] = __float_as_uint(s);
             else sx_lds[t] = s;
         }
 #pragma unroll
@@ -462,8 +463,7 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
             if (idx >= nvec) continue;
             const uint2 q = quantize_bf16x8(v[i], s);
             if (publish)
-                __hip_atomic_store(&in.xq[(int64_t)t * nvec + idx], ((unsigned long long)q.y << 32) | q.x, __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
+                reinterpret_cast<uint2 *>(in.xq)[(int64_t)t * nvec + idx] = q;
             else
                 reinterpret_cast<uint2 *>(lds_row)[idx] = q;
         }
@@ -474,10 +474,11 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
         const GemvStreamInput &in = tab.in[j];
         const int t = (int)blockIdx.x - tab.tok0[j];
         quantize_row(in, t, nullptr, true);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's part of the row is in place ...
+        // The row and its scale are ordinary stores. The barrier orders every thread's part before thread 0,
+        // whose release store of the flag makes all of it visible to the whole device before the flag is.
         __syncthreads();
-        if (threadIdx.x == 0)                                // ... before the flag is raised
-            __hip_atomic_store(&in.flags[t], gemv_flag_value(tab.epoch, t), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (threadIdx.x == 0)
+            __hip_atomic_store(&in.flags[t], gemv_flag_value(tab.epoch, t), __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
     }
     const int total = tab.unit0[tab.count];
     const int b0 = (int)((int64_t)total * blockIdx.x / gridDim.x), b1 = (int)((int64_t)total * (blockIdx.x + 1) / gridDim.x);
@@ -543,12 +544,25 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
         // that share an input, Q/K/V or up/gate, come one after the other).
         const bool restage = it.xq != staged_xq || it.tokens != staged_tokens || K != staged_k;
         const bool self_quant = it.input >= 0;
-        if (restage && !self_quant) {
-            for (int v = threadIdx.x; v < it.tokens * (K / 16); v += 64 * NW) {
-                const int t = v / (K / 16), k = (v % (K / 16)) * 16;
-                *reinterpret_cast<uint4 *>(&xlds[t * pitch + k]) = *reinterpret_cast<const uint4 *>(it.xq + (int64_t)t * K + k);
+        // copy tokens x K quantized activations into the LDS rows; the loads go out in batches so that
+        // their latencies overlap instead of adding up
+        auto stage = [&](const int8_t *src, int tokens) {
+            const int n16 = tokens * (K / 16);
+            for (int v0 = threadIdx.x; v0 < n16; v0 += 64 * NW * STAGE_BATCH) {
+                uint4 q[STAGE_BATCH];
+#pragma unroll
+                for (int b = 0; b < STAGE_BATCH; ++b) {
+                    const int v = v0 + 64 * NW * b;
+                    q[b] = *reinterpret_cast<const uint4 *>(src + (int64_t)(v < n16 ? v : n16 - 1) * 16);
+                }
+#pragma unroll
+                for (int b = 0; b < STAGE_BATCH; ++b) {
+                    const int v = v0 + 64 * NW * b;
+                    if (v < n16) *reinterpret_cast<uint4 *>(&xlds[(v / (K / 16)) * pitch + (v % (K / 16)) * 16]) = q[b];
+                }
             }
-        }
+        };
+        if (restage && !self_quant) stage(it.xq, it.tokens);
         __syncthreads();   // counter and activations in place
         if (dyn && lane == 0) grabbed = atomicAdd(&unit_ctr, 1);
         if (wa < wb) {
@@ -568,18 +582,16 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
                     else __builtin_amdgcn_s_sleep(4);
                 }
                 if (!ok) stage_ok = 0;   // several lanes may write the same value
+                // acquire: what the producers stored before their flags is what the loads below see; the
+                // barrier hands that on to the block's other threads
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
             }
             __syncthreads();
             if (!stage_ok) {   // out of patience: quantize the rows here, straight into LDS (same arithmetic, same result)
                 for (int t = 0; t < in.tokens; ++t) quantize_row(in, t, xlds + t * pitch, false);
             } else {
-                if ((int)threadIdx.x < in.tokens)
-                    sx_lds[threadIdx.x] = __uint_as_float(__hip_atomic_load(&in.sx[threadIdx.x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-                for (int v = threadIdx.x; v < in.tokens * (K / 8); v += 64 * NW) {
-                    const int t = v / (K / 8), k = (v % (K / 8)) * 8;
-                    const unsigned long long q = __hip_atomic_load(&in.xq[v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    *reinterpret_cast<uint2 *>(&xlds[t * pitch + k]) = make_uint2((uint32_t)q, (uint32_t)(q >> 32));
-                }
+                if ((int)threadIdx.x < in.tokens) sx_lds[threadIdx.x] = __uint_as_float(in.sx[threadIdx.x]);
+                stage(reinterpret_cast<const int8_t *>(in.xq), in.tokens);
             }
             __syncthreads();
         }
