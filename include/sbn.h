@@ -57,16 +57,20 @@ typedef enum {
 typedef enum { SBN_F32 = 0, SBN_BF16 = 1 } sbn_dtype;
 
 typedef enum {
-    SBN_PATH_AUTO = 0,       /* d_in % 128 == 0 and tokens <= 16: GEMV.  2:4 and its instances (1:2, 1:4, 1:8, 2:8) with
-                                d_in % 128 == 0 and more tokens: sparse MFMA GEMM.  Any other case: dense MFMA if
-                                d_in % 64 == 0, generic else */
+    SBN_PATH_AUTO = 0,       /* d_in % 128 == 0: GEMV for tokens <= 16, sparse MFMA GEMM for more.  Any other case: dense
+                                MFMA if d_in % 64 == 0, generic else */
     SBN_PATH_GEMV = 1,       /* decode kernel: streams the packed weights once; tokens <= 16, d_in % 128 == 0.  2:4 runs
                                 on the sparse instruction and N = M (dense 2-bit codes) on the dense one as stored; other
                                 patterns are rewritten per call into one of the two (a pass over the packed weights:
                                 sbn_convert_packed does it once instead) */
-    SBN_PATH_SMFMAC = 2,     /* prefill/training GEMM on sparse int8 MFMA (v_smfmac); 2:4 and its instances, d_in % 128 == 0 */
-    SBN_PATH_DENSE_MFMA = 3, /* W_eff expanded to int8 with explicit zeros, dense int8 MFMA: the comparison path for 2:4
-                                and the matrix-core path of every other pattern (6:8, N:8, 1:4, ...); d_in % 64 == 0 */
+    SBN_PATH_SMFMAC = 2,     /* prefill/training GEMM on sparse int8 MFMA (v_smfmac); d_in % 128 == 0.  2:4 runs as
+                                stored, its instances (1:2, 1:4, 1:8, 2:8) after a rewrite into the 2:4 operand form.
+                                Every other pattern (6:8, N:8, ...) runs as dense 2-bit codes - N = M as stored, the
+                                rest converted per call (sbn_convert_packed to N = M does it once instead) - with two
+                                sparse instructions per group of four weights (positions 0, 1 and positions 2, 3): the
+                                matrix-core time of a dense int8 product at a quarter of its weight bytes */
+    SBN_PATH_DENSE_MFMA = 3, /* W_eff expanded to int8 with explicit zeros, dense int8 MFMA: the comparison path;
+                                d_in % 64 == 0 */
     SBN_PATH_GENERIC = 4     /* any supported pattern, plain integer kernel (reference speed only) */
 } sbn_path;
 
@@ -172,7 +176,7 @@ sbn_status sbn_sparse_ternary_linear(const void *X, int64_t tokens, int64_t d_in
  *   arguments   as sbn_sparse_ternary_linear
  *   limits      align256(tokens * d_in) + align256(4 * tokens) <= SBN_STATIC_SCRATCH_MIB MiB, else SBN_ESIZE
  *               (sbn_last_error() then says how much was needed); only paths that read the weights as stored:
- *               2:4 on SBN_PATH_GEMV / SBN_PATH_SMFMAC, N = M on SBN_PATH_GEMV, any pattern on SBN_PATH_GENERIC
+ *               2:4 and N = M on SBN_PATH_GEMV / SBN_PATH_SMFMAC, any pattern on SBN_PATH_GENERIC
  *               (SBN_PATH_AUTO when it resolves to one of these); every other case SBN_EUNSUPPORTED
  *   sharing     all calls on a GPU use that GPU's one buffer, which keeps the last call's contents (nothing in it has
  *               to start at zero: flags left behind carry the number of the launch that raised them).  Calls that
@@ -270,6 +274,21 @@ sbn_status sbn_mask_flips(const void *packed_a, const void *packed_b, int64_t d_
  */
 sbn_status sbn_convert_packed(const void *packed, int64_t d_out, int64_t d_in, int N, int M, int to_N, int to_M,
                               void *out, void *stream);
+
+/*
+ * The dense comparison kernel on its own (Section 3.2 compares the sparse layer with a dense one of the same
+ * precision): the same product on the dense int8 matrix cores with W_eff given as int8 with explicit zeros, so that
+ * a benchmark can time it without the expansion pass that SBN_PATH_DENSE_MFMA runs in front of it.
+ *   xq, sx      device, int8 [tokens, d_in] row-major and fp32 [tokens] as written by sbn_act_quant, 16-byte aligned
+ *   W_eff       device, int8 [d_out, d_in] row-major, values in {-1, 0, +1} as written by sbn_unpack, 16-byte aligned
+ *   gamma       device, one fp32;  bias: device fp32 [d_out] or NULL
+ *   Y           device, fp32 [tokens, d_out], overwritten: Y = acc * gamma / s_x[t] (+ bias), the same arithmetic as
+ *               sbn_sparse_ternary_linear; acc_out: device int32 [tokens, d_out] or NULL
+ * d_in % 64 == 0, else SBN_EUNSUPPORTED.  Errors as above.  Enqueues one kernel; nothing is owned or freed.
+ */
+sbn_status sbn_dense_ternary_linear(const int8_t *xq, const float *sx, int64_t tokens, int64_t d_in, int64_t d_out,
+                                    const int8_t *W_eff, const float *gamma, const float *bias, float *Y,
+                                    int32_t *acc_out, void *stream);
 
 /*
  * Test hook: bounds of the library's two bounded inter-block waits, in polls.  The streaming decode kernel lets

@@ -60,6 +60,8 @@ def _load():
     lib.sbn_sparse_ternary_linear_backward_grouped.restype = cint
     lib.sbn_sparse_ternary_linear_backward_grouped.argtypes = [cint, pp, pi64, pi64, pi64, cint, cint, pp, pp, pp, pp, pp, pp, cint,
                                                                vp, sz, vp]
+    lib.sbn_dense_ternary_linear.restype = cint
+    lib.sbn_dense_ternary_linear.argtypes = [vp, vp, i64, i64, i64, vp, vp, vp, vp, vp, vp]
     lib.sbn_unpack.restype = cint
     lib.sbn_unpack.argtypes = [vp, i64, i64, cint, cint, vp, vp, vp]
     lib.sbn_convert_packed.restype = cint
@@ -300,6 +302,13 @@ def sbn_rmsnorm_act_quant(X, xq, sx, gain=None, eps: float = 1e-6, xn_out=None):
 def sbn_convert_packed(packed, d_out: int, d_in: int, N: int, M: int, to_N: int, to_M: int, out):
     """Rewrite a packed N:M matrix into the packed form of to_N:to_M (2:4 or M:M) for decode."""
     _check(_lib.sbn_convert_packed(_ptr(packed), d_out, d_in, N, M, to_N, to_M, _ptr(out), _stream()), "sbn_convert_packed")
+
+
+def sbn_dense_ternary_linear(xq, sx, W_eff, gamma, Y, bias=None, acc_out=None):
+    """The dense comparison kernel alone: Y = (xq @ W_eff^T) * gamma / s_x (+ bias) with W_eff int8 [d_out, d_in]."""
+    tokens, d_in = xq.shape
+    _check(_lib.sbn_dense_ternary_linear(_ptr(xq), _ptr(sx), tokens, d_in, W_eff.shape[0], _ptr(W_eff), _ptr(gamma), _ptr(bias),
+                                         _ptr(Y), _ptr(acc_out), _stream()), "sbn_dense_ternary_linear")
 
 
 SBN_SPIN_DEFAULT = -2 ** 31

@@ -44,11 +44,13 @@ static sbn_path resolve_path(sbn_path path, int64_t tokens, int64_t d_in, const 
 {
     if (path != SBN_PATH_AUTO) return path;
     const bool is24 = pat.N == 2 && pat.M == 4;
-    // other patterns (the paper's 6:8 among them) have no sparse matrix instruction on this part: beyond
-    // decode sizes they run on the dense int8 matrix cores with explicit zeros
-    // 2:4 and its instances (1:4, 2:8, ...: rewritten into the 2:4 operand form first) take the sparse instruction
-    if ((is24 || embeds_in_2of4(pat)) && d_in % CHUNK == 0) return tokens <= 16 ? SBN_PATH_GEMV : SBN_PATH_SMFMAC;
-    if (tokens <= 16 && d_in % CHUNK == 0) return SBN_PATH_GEMV;   // decode of every other pattern: dense 2-bit codes
+    // 2:4 and its instances (1:4, 2:8, ...: rewritten into the 2:4 operand form first) take the sparse instruction as
+    // it is meant.  Every other pattern (the paper's 6:8 among them) has no sparse matrix instruction of its own on
+    // this part: its weights run as dense 2-bit codes (N = M is stored that way, the rest is converted first), in
+    // decode through the streaming kernel and beyond decode sizes through the same sparse instruction, issued twice
+    // per group of four weights (positions 0, 1 and positions 2, 3 - the matrix-core time of a dense int8 product, at
+    // a quarter of its weight bytes)
+    if (d_in % CHUNK == 0) return tokens <= 16 ? SBN_PATH_GEMV : SBN_PATH_SMFMAC;
     return d_in % 64 == 0 ? SBN_PATH_DENSE_MFMA : SBN_PATH_GENERIC;
 }
 
@@ -165,15 +167,14 @@ static sbn_status linear_one(const LinearItem &it_in, const Pattern &pat, sbn_pa
     const bool is24 = pat.N == 2 && pat.M == 4;
     path = resolve_path(path, it.tokens, it.d_in, pat);
     const bool sparse_form = is24 || embeds_in_2of4(pat);   // runs on the sparse instruction (after a rewrite unless 2:4)
-    if (path == SBN_PATH_SMFMAC && !sparse_form) return SBN_EUNSUPPORTED;
     if (path == SBN_PATH_GEMV && it.tokens > 16) return SBN_EUNSUPPORTED;
     if ((path == SBN_PATH_GEMV || path == SBN_PATH_SMFMAC) && it.d_in % CHUNK != 0) return SBN_EUNSUPPORTED;
     if (path == SBN_PATH_DENSE_MFMA && it.d_in % 64 != 0) return SBN_EUNSUPPORTED;
     const size_t xq_bytes = align_up((size_t)it.tokens * it.d_in, 256);
     const size_t sx_bytes = align_up((size_t)it.tokens * sizeof(float), 256);
     if (activations_only) {
-        const bool weights_as_stored = path == SBN_PATH_GENERIC || (path == SBN_PATH_SMFMAC && is24) ||
-                                       (path == SBN_PATH_GEMV && (is24 || pat.N == pat.M));
+        const bool weights_as_stored = path == SBN_PATH_GENERIC ||
+                                       ((path == SBN_PATH_SMFMAC || path == SBN_PATH_GEMV) && (is24 || pat.N == pat.M));
         if (!weights_as_stored) return SBN_EUNSUPPORTED;
         if (ws_bytes < xq_bytes + sx_bytes) return SBN_ESIZE;
     } else if (ws_bytes < linear_workspace_bytes(it.tokens, it.d_out, it.d_in)) {
@@ -198,15 +199,15 @@ static sbn_status linear_one(const LinearItem &it_in, const Pattern &pat, sbn_pa
         if (st != SBN_OK) return st;
         it.packed = w_dense;
     }
-    if (path == SBN_PATH_GEMV && !sparse_form && pat.N != pat.M) {
-        // no sparse instruction for this pattern: decode streams dense 2-bit codes (N = M is stored that way already)
+    if ((path == SBN_PATH_GEMV || path == SBN_PATH_SMFMAC) && !sparse_form && pat.N != pat.M) {
+        // no sparse instruction for this pattern: the kernels take dense 2-bit codes (N = M is stored that way already)
         st = launch_repack_dense_codes(it.packed, it.d_out, it.d_in, pat, reinterpret_cast<uint8_t *>(w_dense), stream);
         if (st != SBN_OK) return st;
         it.packed = w_dense;
     }
     switch (path) {
     case SBN_PATH_GEMV: return launch_gemv(1, &it, !sparse_form, stream);
-    case SBN_PATH_SMFMAC: return launch_gemm_smfmac(1, &it, stream);
+    case SBN_PATH_SMFMAC: return launch_gemm_smfmac(1, &it, !sparse_form, stream);
     case SBN_PATH_DENSE_MFMA: return launch_gemm_dense(it, pat, w_dense, stream);
     case SBN_PATH_GENERIC: return launch_linear_generic(it, pat, stream);
     default: return SBN_EINVAL;
@@ -286,6 +287,20 @@ sbn_status sbn_sparse_ternary_linear_static(const void *X, int64_t tokens, int64
     return linear_one(it, pat, path, ws, STATIC_SCRATCH_BYTES, static_cast<hipStream_t>(stream), true);
 }
 
+sbn_status sbn_dense_ternary_linear(const int8_t *xq, const float *sx, int64_t tokens, int64_t d_in, int64_t d_out,
+                                    const int8_t *W_eff, const float *gamma, const float *bias, float *Y,
+                                    int32_t *acc_out, void *stream)
+{
+    if (!xq || !sx || !W_eff || !gamma || !Y || tokens <= 0 || d_in <= 0 || d_out <= 0) return SBN_EINVAL;
+    if (d_in % 64 != 0 || tokens * d_out >= (int64_t)1 << 40 || d_out * d_in >= (int64_t)1 << 32 ||
+        tokens * d_in >= (int64_t)1 << 32)
+        return SBN_EUNSUPPORTED;
+    if (!aligned(xq, 16) || !aligned(sx, 4) || !aligned(W_eff, 16) || !aligned(Y, 16) || (acc_out && !aligned(acc_out, 16)))
+        return SBN_EALIGN;
+    LinearItem it{nullptr, nullptr, gamma, bias, Y, const_cast<int8_t *>(xq), const_cast<float *>(sx), acc_out, tokens, d_in, d_out};
+    return launch_gemm_dense_expanded(it, W_eff, static_cast<hipStream_t>(stream));
+}
+
 sbn_status sbn_sparse_ternary_linear_grouped(int count, const void *const *X, const int64_t *tokens,
                                              const int64_t *d_in, const int64_t *d_out, int N, int M,
                                              const void *const *packed, const float *const *gamma, float *const *Y,
@@ -309,7 +324,7 @@ sbn_status sbn_sparse_ternary_linear_grouped(int count, const void *const *X, co
         if (resolve_path(path, tokens[i], d_in[i], pat) != SBN_PATH_GEMV || !(is24 || pat.N == pat.M) || tokens[i] > 16 ||
             d_in[i] % CHUNK != 0)
             all_gemv = false;   // one launch streams 2:4 or dense-code (N = M) weights as stored; other patterns need a rewrite each
-        if (resolve_path(path, tokens[i], d_in[i], pat) != SBN_PATH_SMFMAC || !is24 || d_in[i] % CHUNK != 0 ||
+        if (resolve_path(path, tokens[i], d_in[i], pat) != SBN_PATH_SMFMAC || !(is24 || pat.N == pat.M) || d_in[i] % CHUNK != 0 ||
             tokens[i] * d_out[i] >= (int64_t)1 << 40)
             all_smfmac = false;
     }
@@ -349,7 +364,8 @@ sbn_status sbn_sparse_ternary_linear_grouped(int count, const void *const *X, co
             if (st != SBN_OK) return st;
         }
     }
-    return all_gemv ? launch_gemv(count, tl_items.data(), pat.N == pat.M, s) : launch_gemm_smfmac(count, tl_items.data(), s);
+    return all_gemv ? launch_gemv(count, tl_items.data(), pat.N == pat.M, s)
+                    : launch_gemm_smfmac(count, tl_items.data(), pat.N == pat.M, s);
 }
 
 sbn_status sbn_sparse_ternary_linear_backward(const void *dY, int64_t tokens, int64_t d_in, int64_t d_out, int N,

@@ -364,7 +364,7 @@ __device__ __forceinline__ void piece_prologue(const GemmGroup &grp, const Piece
 // Main loop and epilogue of one piece whose prologue is already in flight: rows [512 to, +512) of W against tokens
 // [t0, t0 + 32 TB), the whole input dimension.  LIVE = false: a wavefront whose rows lie past the matrix (ragged last
 // row tile) only moves data and keeps the barriers.
-template <int TB, bool LIVE>
+template <int TB, bool LIVE, bool DENSE>
 __device__ __forceinline__ void piece_body(const GemmGroup &grp, const Piece &p, const Piece &next, int8_t *lds, const int wave,
                                            int lane)
 {
@@ -397,14 +397,21 @@ __device__ __forceinline__ void piece_body(const GemmGroup &grp, const Piece &p,
             b_hi[u] = lds0 + r * KSTEP + 16 * ((4 + 2 * u + c) ^ sw);
         }
     }
-    uint32_t a_idx[2][RA], a_code[2][RA];   // [chunk of the pair][row tile], slot 0
+    // [chunk of the pair][row tile], slot 0.  2:4: index words 2c, 2c+1 and code words 2c, 2c+1 of the chunk (8 bytes
+    // each); dense codes: words 4c .. 4c+3 of the chunk's eight code words (a_idx alone, 16 bytes)
+    uint32_t a_idx[2][RA], a_code[2][RA];
 #pragma unroll
     for (int a = 0; a < RA; ++a) {
         const int row = wave * (32 * RA) + 32 * a + r, sw = (row >> 2) & 3;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            a_idx[h][a] = wlds0 + row * 64 + 8 * c + 16 * ((2 * h) ^ sw);
-            a_code[h][a] = wlds0 + row * 64 + 8 * c + 16 * ((2 * h + 1) ^ sw);
+            if constexpr (DENSE) {
+                a_idx[h][a] = wlds0 + row * 64 + 16 * ((2 * h + c) ^ sw);
+                a_code[h][a] = 0;
+            } else {
+                a_idx[h][a] = wlds0 + row * 64 + 8 * c + 16 * ((2 * h) ^ sw);
+                a_code[h][a] = wlds0 + row * 64 + 8 * c + 16 * ((2 * h + 1) ^ sw);
+            }
         }
     }
     typedef __attribute__((address_space(3))) const v4i *lds_v4i;
@@ -420,11 +427,19 @@ __device__ __forceinline__ void piece_body(const GemmGroup &grp, const Piece &p,
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0;
 
+    // 2:4: (icur, ccur) = the lane's two index and two code words of the current chunk; dense codes: its four code words
     v2u icur[RA], ccur[RA], inext[RA], cnext[RA];
     v8i bq[2][TB];
     auto read_weights = [&](const int slot, const int h, const int a, v2u (&iv)[RA], v2u (&cv)[RA]) {
-        iv[a] = *(lds_u2)(uintptr_t)(a_idx[h][a] + slot * WPAIR);
-        cv[a] = *(lds_u2)(uintptr_t)(a_code[h][a] + slot * WPAIR);
+        if constexpr (DENSE) {
+            typedef unsigned v4u __attribute__((ext_vector_type(4)));
+            const v4u w = *(__attribute__((address_space(3))) const v4u *)(uintptr_t)(a_idx[h][a] + slot * WPAIR);
+            iv[a] = v2u{w.x, w.y};
+            cv[a] = v2u{w.z, w.w};
+        } else {
+            iv[a] = *(lds_u2)(uintptr_t)(a_idx[h][a] + slot * WPAIR);
+            cv[a] = *(lds_u2)(uintptr_t)(a_code[h][a] + slot * WPAIR);
+        }
     };
     auto token_read = [&](const int slot, const int u, const int b, v8i &bf) {
         bf.lo = *(lds_v4i)(uintptr_t)(b_lo[u] + slot * TSTAGE + 32 * b * KSTEP);
@@ -434,11 +449,28 @@ __device__ __forceinline__ void piece_body(const GemmGroup &grp, const Piece &p,
     // wavefront issues at most one instruction every few cycles, so what is placed between matrix instructions is free
     // while the matrix pipe is busy, and a block of other instructions after them leaves the pipe idle: the source order
     // is the intended issue order and a scheduling barrier after every matrix instruction keeps it.
-    constexpr int NSLOT = RA * TB;
+    // Dense codes: every group of four weights is the sum of a 2:4 group holding its positions 0, 1 and one holding its
+    // positions 2, 3, so the same B fragment feeds two sparse instructions with constant index words.
+    constexpr int NSLOT = (DENSE ? 2 : 1) * RA * TB;
     auto substep = [&](const int u, const v8i (&bf)[TB], auto &&side) {
 #pragma unroll
         for (int a = 0; a < RA; ++a) {
-            if constexpr (LIVE) {
+            if constexpr (LIVE && DENSE) {
+                v4i a01, a23;   // sub-step u covers the lane's code words 2u, 2u + 1
+                expand_dense_codes(u ? ccur[a].x : icur[a].x, u ? ccur[a].y : icur[a].y, a01, a23);
+#pragma unroll
+                for (int b = 0; b < TB; ++b) {
+                    acc[a][b] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(a01, bf[b], acc[a][b], 0x44444444, 0, 0);
+                    side(2 * a * TB + b);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+#pragma unroll
+                for (int b = 0; b < TB; ++b) {
+                    acc[a][b] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(a23, bf[b], acc[a][b], (int)0xeeeeeeeeu, 0, 0);
+                    side((2 * a + 1) * TB + b);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            } else if constexpr (LIVE) {
                 const int iv = (int)(u ? icur[a].y : icur[a].x);
                 const v4i av = expand_codes(u ? ccur[a].y : ccur[a].x, ones);
 #pragma unroll
@@ -449,7 +481,7 @@ __device__ __forceinline__ void piece_body(const GemmGroup &grp, const Piece &p,
                 }
             } else {
 #pragma unroll
-                for (int b = 0; b < TB; ++b) side(a * TB + b);
+                for (int s = 0; s < NSLOT / RA; ++s) side(a * (NSLOT / RA) + s);
             }
         }
     };
@@ -598,20 +630,21 @@ __device__ __forceinline__ void piece_body(const GemmGroup &grp, const Piece &p,
     }
 }
 
-template <int TB>
+template <int TB, bool DENSE>
 __device__ __forceinline__ void piece_live(const GemmGroup &grp, const Piece &p, const Piece &next, int8_t *lds, int wave, int lane)
 {
     const bool live = p.to * ROWS + wave * (32 * RA) < grp.g[p.prob].d_out;   // a ragged last row tile leaves whole wavefronts idle
-    if (live) piece_body<TB, true>(grp, p, next, lds, wave, lane);
-    else piece_body<TB, false>(grp, p, next, lds, wave, lane);
+    if (live) piece_body<TB, true, DENSE>(grp, p, next, lds, wave, lane);
+    else piece_body<TB, false, DENSE>(grp, p, next, lds, wave, lane);
 }
 
+template <bool DENSE>
 __device__ __forceinline__ void piece_run(const GemmGroup &grp, const Piece &p, const Piece &next, int8_t *lds, int wave, int lane)
 {
-    if (p.tb == 4) piece_live<4>(grp, p, next, lds, wave, lane);
-    else if (p.tb == 3) piece_live<3>(grp, p, next, lds, wave, lane);
-    else if (p.tb == 2) piece_live<2>(grp, p, next, lds, wave, lane);
-    else piece_live<1>(grp, p, next, lds, wave, lane);
+    if (p.tb == 4) piece_live<4, DENSE>(grp, p, next, lds, wave, lane);
+    else if (p.tb == 3) piece_live<3, DENSE>(grp, p, next, lds, wave, lane);
+    else if (p.tb == 2) piece_live<2, DENSE>(grp, p, next, lds, wave, lane);
+    else piece_live<1, DENSE>(grp, p, next, lds, wave, lane);
 }
 
 }  // namespace sp
@@ -623,6 +656,8 @@ __device__ __forceinline__ void piece_run(const GemmGroup &grp, const Piece &p, 
 // make_piece_table) run the pieces listed for each block; larger ones give every block of an XCD a consecutive run of
 // the XCD's units in the order strip, unit (the same number of units each, +-1), cut into pieces of at most four units
 // that do not cross a strip.
+// DENSE = the weights are dense 2-bit codes (the stored form of N = M, or any pattern converted to it) instead of 2:4.
+template <bool DENSE>
 __global__ void __launch_bounds__(64 * sp::NW) gemm_smfmac_kernel(GemmGroup grp, PieceTable tab)
 {
     __shared__ __attribute__((aligned(1024))) int8_t lds[sp::LDS_BYTES];
@@ -641,7 +676,7 @@ __global__ void __launch_bounds__(64 * sp::NW) gemm_smfmac_kernel(GemmGroup grp,
         sp::piece_prologue(grp, cur, lds, wave, lane);
         for (int i = 1; cur.tb > 0; ++i) {
             const sp::Piece next = decode(i);
-            sp::piece_run(grp, cur, next, lds, wave, lane);
+            sp::piece_run<DENSE>(grp, cur, next, lds, wave, lane);
             cur = next;
         }
         return;
@@ -692,7 +727,7 @@ __global__ void __launch_bounds__(64 * sp::NW) gemm_smfmac_kernel(GemmGroup grp,
     sp::piece_prologue(grp, cur, lds, wave, lane);
     while (cur.tb > 0) {
         const sp::Piece next = piece_at(f);
-        sp::piece_run(grp, cur, next, lds, wave, lane);
+        sp::piece_run<DENSE>(grp, cur, next, lds, wave, lane);
         cur = next;
     }
 }
@@ -956,7 +991,7 @@ static int make_piece_table(const GemmGroup &grp, PieceTable &tab)
     return nb;
 }
 
-sbn_status launch_gemm_smfmac(int count, const LinearItem *items, hipStream_t stream)
+sbn_status launch_gemm_smfmac(int count, const LinearItem *items, bool dense_codes, hipStream_t stream)
 {
     for (int first = 0; first < count; first += GEMM_GROUP_MAX) {
         GemmGroup grp;
@@ -964,11 +999,20 @@ sbn_status launch_gemm_smfmac(int count, const LinearItem *items, hipStream_t st
         for (int i = 0; i < grp.count; ++i) grp.g[i] = make_args(items[first + i]);
         static thread_local PieceTable tab;
         const int per_xcd = make_piece_table(grp, tab);
-        hipLaunchKernelGGL(gemm_smfmac_kernel, dim3(8 * per_xcd), dim3(64 * sp::NW), 0, stream, grp, tab);
+        if (dense_codes) hipLaunchKernelGGL(gemm_smfmac_kernel<true>, dim3(8 * per_xcd), dim3(64 * sp::NW), 0, stream, grp, tab);
+        else hipLaunchKernelGGL(gemm_smfmac_kernel<false>, dim3(8 * per_xcd), dim3(64 * sp::NW), 0, stream, grp, tab);
         sbn_status st = check_launch("gemm_smfmac_kernel");
         if (st != SBN_OK) return st;
     }
     return SBN_OK;
+}
+
+sbn_status launch_gemm_dense_expanded(const LinearItem &it, const int8_t *w_dense, hipStream_t stream)
+{
+    GemmArgs g = make_args(it);
+    g.w_dense = w_dense;
+    hipLaunchKernelGGL(gemm_dense_kernel, dim3(g.tiles_o * g.tiles_t), dim3(256), 0, stream, g);
+    return check_launch("gemm_dense_kernel");
 }
 
 sbn_status launch_gemm_dense(const LinearItem &it, const Pattern &pat, int8_t *w_dense, hipStream_t stream)
@@ -984,10 +1028,7 @@ sbn_status launch_gemm_dense(const LinearItem &it, const Pattern &pat, int8_t *w
         st = launch_expand_groups(it.packed, it.d_out, it.d_in, pat, w_dense, stream);
     }
     if (st != SBN_OK) return st;
-    GemmArgs g = make_args(it);
-    g.w_dense = w_dense;
-    hipLaunchKernelGGL(gemm_dense_kernel, dim3(g.tiles_o * g.tiles_t), dim3(256), 0, stream, g);
-    return check_launch("gemm_dense_kernel");
+    return launch_gemm_dense_expanded(it, w_dense, stream);
 }
 
 }  // namespace sbn

@@ -92,8 +92,9 @@ sbn_status launch_rmsnorm_act_quant(const void *X, const float *gain, float eps,
                                     float *sx, void *xn, hipStream_t stream);
 // dense_codes: the weights are dense 2-bit codes (packed form of N = M) instead of the 2:4 form
 sbn_status launch_gemv(int count, const LinearItem *items, bool dense_codes, hipStream_t stream);
-sbn_status launch_gemm_smfmac(int count, const LinearItem *items, hipStream_t stream);
+sbn_status launch_gemm_smfmac(int count, const LinearItem *items, bool dense_codes, hipStream_t stream);
 sbn_status launch_gemm_dense(const LinearItem &it, const Pattern &pat, int8_t *w_dense, hipStream_t stream);
+sbn_status launch_gemm_dense_expanded(const LinearItem &it, const int8_t *w_dense, hipStream_t stream);
 sbn_status launch_linear_generic(const LinearItem &it, const Pattern &pat, hipStream_t stream);
 
 int device_cus();   // multiprocessors of the current device

@@ -56,6 +56,24 @@ __device__ __forceinline__ v4i expand_codes(uint32_t cw, uint32_t ones)
     return a;
 }
 
+// Two words of dense 2-bit codes (32 consecutive weights = 8 groups of four; weight 16 w + 4 p + b of word w at bits
+// [8 b + 2 p, +2)) -> the operands of two sparse matrix instructions: a01 holds positions 0, 1 of every group, a23
+// positions 2, 3, in the byte order of expand_codes (group 2 j in bytes 0, 1 of register j, group 2 j + 1 in bytes 2, 3).
+__device__ __forceinline__ void expand_dense_codes(uint32_t w0, uint32_t w1, v4i &a01, v4i &a23)
+{
+    const uint32_t lut = 0xff000100u, m = 0x03030303u;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const uint32_t w = i ? w1 : w0;
+        const uint32_t lo = w & 0xffffu, hi = w >> 16;
+        const uint32_t tl = (lo << 14) | lo, th = (hi << 14) | hi;   // bytes 0, 1 of pair p and, 16 bits up, of pair p + 1
+        a01[2 * i] = (int)__builtin_amdgcn_perm(lut, lut, tl & m);
+        a01[2 * i + 1] = (int)__builtin_amdgcn_perm(lut, lut, (tl >> 4) & m);
+        a23[2 * i] = (int)__builtin_amdgcn_perm(lut, lut, th & m);
+        a23[2 * i + 1] = (int)__builtin_amdgcn_perm(lut, lut, (th >> 4) & m);
+    }
+}
+
 // One LDS-DMA load: lane l of the wavefront fetches 16 bytes at base + voff and the hardware
 // deposits them at LDS byte address lds_addr + 16*l (M0 carries the LDS address).  Written as
 // inline assembly on purpose: after the compiler's own LDS-DMA builtin every later LDS read is

@@ -1168,34 +1168,74 @@ sbn_status launch_repack_2of4(const void *packed, int64_t d_out, int64_t d_in, c
 // Any pattern -> dense 2-bit codes (the packed form of N = M: eight code words per 128-weight chunk,
 // weight p of the chunk in word p / 16 at bits 8 * (p % 4) + 2 * ((p % 16) / 4)), zero codes at the
 // dropped positions.  One thread per output word (16 weights = 16 / M groups).  Whole chunks only.
+// PN, PM = the pattern as compile-time constants (bit positions become literals, the loops unroll), or 0, 0 = read it
+// from pat
+template <int PN, int PM>
 __global__ void __launch_bounds__(256) repack_dense_codes_kernel(const uint8_t *__restrict__ packed, int64_t nwords, Pattern pat,
                                                                  uint32_t *__restrict__ out)
 {
     const int64_t wid = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (wid >= nwords) return;
+    const int N = PN ? PN : pat.N, M = PM ? PM : pat.M;
+    const int b = PM ? (PM == PN ? 0 : PM == 2 ? 1 : PM == 4 ? 2 : 3) : pat.b;
     const int64_t chunk = wid >> 3;
     const int w = (int)(wid & 7);
     const uint8_t *idx_field = packed + chunk * pat.chunk_bytes;
     const uint8_t *code_field = idx_field + pat.idx_bytes;
-    const int gpw = 16 / pat.M;   // groups per word
+    const int gpw = 16 / M;   // groups per word
+    const int slot0 = w * gpw * N;
     uint32_t word = 0;
+#pragma unroll
     for (int gl = 0; gl < gpw; ++gl) {
-        for (int n = 0; n < pat.N; ++n) {
-            const int slot = (w * gpw + gl) * pat.N + n;
+#pragma unroll
+        for (int n = 0; n < N; ++n) {
+            const int slot = slot0 + gl * N + n;
             int j = n;
-            if (pat.b) {
-                const int p = slot * pat.b;
+            if (b) {
+                const int p = slot * b;
                 const uint32_t two = (uint32_t)idx_field[p >> 3] | ((uint32_t)idx_field[(p >> 3) + 1] << 8);   // the next byte is still inside the chunk
-                j = (int)((two >> (p & 7)) & ((1u << pat.b) - 1u));
+                j = (int)((two >> (p & 7)) & ((1u << b) - 1u));
             }
             const int sv = slot & 15;
             const int cp = 32 * (slot >> 4) + 8 * (sv & 3) + 2 * (sv >> 2);
             const uint32_t code = (code_field[cp >> 3] >> (cp & 7)) & 3u;
-            const int v = gl * pat.M + j;
+            const int v = gl * M + j;
             word |= code << (8 * (v & 3) + 2 * (v >> 2));
         }
     }
     out[wid] = word;
+}
+
+// 6:8, the paper's main pattern, with one thread per chunk: 60 bytes in as 15 words (36 bytes of 3-bit indices, 24 of
+// codes), 32 bytes out; every bit position is a literal after unrolling, and no byte-sized loads are left.
+__global__ void __launch_bounds__(256) repack_6of8_dense_codes_kernel(const uint8_t *__restrict__ packed, int64_t nchunks,
+                                                                      uint4 *__restrict__ out)
+{
+    const int64_t chunk = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (chunk >= nchunks) return;
+    const uint32_t *in = reinterpret_cast<const uint32_t *>(packed + chunk * 60);
+    uint32_t d[16];
+#pragma unroll
+    for (int i = 0; i < 15; ++i) d[i] = in[i];
+    d[15] = 0;
+    uint32_t o[8];
+#pragma unroll
+    for (int w = 0; w < 8; ++w) {
+        uint32_t word = 0;
+#pragma unroll
+        for (int k = 0; k < 12; ++k) {   // the two groups of the word: slots 12 w .. 12 w + 11
+            const int slot = 12 * w + k, p = 3 * slot;
+            const uint32_t j = (p & 31) <= 29 ? (d[p >> 5] >> (p & 31)) & 7u
+                                              : __funnelshift_r(d[p >> 5], d[(p >> 5) + 1], p & 31) & 7u;
+            const int sv = slot & 15;
+            const uint32_t code = (d[9 + (slot >> 4)] >> (8 * (sv & 3) + 2 * (sv >> 2))) & 3u;
+            // weight v = 8 (k / 6) + j of the word sits at bits 8 (v % 4) + 2 (v / 4)
+            word |= code << (8 * (j & 3u) + 2 * (j >> 2) + 4 * (k / 6));
+        }
+        o[w] = word;
+    }
+    out[2 * chunk] = make_uint4(o[0], o[1], o[2], o[3]);
+    out[2 * chunk + 1] = make_uint4(o[4], o[5], o[6], o[7]);
 }
 
 sbn_status launch_mask_bitplane(const void *packed, int64_t d_out, int64_t d_in, const Pattern &pat, uint32_t *bits,
@@ -1211,8 +1251,13 @@ sbn_status launch_repack_dense_codes(const void *packed, int64_t d_out, int64_t 
                                      hipStream_t stream)
 {
     const int64_t nwords = d_out * (d_in / CHUNK) * 8;
-    hipLaunchKernelGGL(repack_dense_codes_kernel, dim3((unsigned)ceil_div(nwords, 256)), dim3(256), 0, stream,
-                       static_cast<const uint8_t *>(packed), nwords, pat, reinterpret_cast<uint32_t *>(out));
+    const dim3 grid((unsigned)ceil_div(nwords, 256));
+    const uint8_t *in = static_cast<const uint8_t *>(packed);
+    uint32_t *o = reinterpret_cast<uint32_t *>(out);
+    if (pat.N == 6 && pat.M == 8)
+        hipLaunchKernelGGL(repack_6of8_dense_codes_kernel, dim3((unsigned)ceil_div(nwords / 8, 256)), dim3(256), 0, stream, in,
+                           nwords / 8, reinterpret_cast<uint4 *>(out));
+    else hipLaunchKernelGGL((repack_dense_codes_kernel<0, 0>), grid, dim3(256), 0, stream, in, nwords, pat, o);
     return check_launch("repack_dense_codes_kernel");
 }
 

@@ -118,7 +118,6 @@ def test_argument_errors_come_before_any_launch(sbn):
     assert lin(X=A + 2) == sbn.SBN_EALIGN
     assert lin(path=9) == sbn.SBN_EINVAL
     assert lin(ws=16) == sbn.SBN_ESIZE
-    assert lin(N=3, path=sbn.SBN_PATH_SMFMAC) == sbn.SBN_EUNSUPPORTED      # sparse MFMA path: 2:4 and its instances only
     assert lin(tokens=64, path=sbn.SBN_PATH_GEMV) == sbn.SBN_EUNSUPPORTED  # decode kernel takes <= 16 tokens
     assert lin(d_in=200, path=sbn.SBN_PATH_SMFMAC) == sbn.SBN_EUNSUPPORTED
     # backward: nothing requested

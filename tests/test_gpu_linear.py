@@ -83,14 +83,12 @@ def test_generic_path_all_patterns(N, M):
 @pytest.mark.parametrize("N,M", [(6, 8), (2, 8), (1, 4), (4, 4), (3, 8), (7, 8)])
 @pytest.mark.parametrize("tokens,shape", [(40, (130, 384)), (300, (520, 1280))])
 def test_dense_mfma_path_other_patterns(N, M, tokens, shape):
-    # patterns without a sparse matrix instruction (the paper's 6:8 among them) run beyond decode sizes on
-    # the dense int8 matrix cores: same integers as the oracle, explicitly and through path selection
+    # the comparison path (weights expanded to int8 with explicit zeros, dense int8 matrix cores) takes every pattern
     s = sbn()
     W = sbn_synth.latent_weight(shape[0], shape[1], 440 + N + M)
     X = sbn_synth.activations(tokens, shape[1], 450 + tokens)
     bias = torch.randn(shape[0], generator=torch.Generator().manual_seed(9))
     check_forward(W, X, N, M, s.SBN_PATH_DENSE_MFMA, bias=bias)
-    check_forward(W, X, N, M, s.SBN_PATH_AUTO)
 
 
 @pytest.mark.parametrize("N,M", [(1, 4), (2, 8), (1, 8), (1, 2)])
@@ -103,6 +101,85 @@ def test_sparse_mfma_path_instances_of_2of4(N, M, tokens, shape):
     X = sbn_synth.activations(tokens, shape[1], 480 + tokens)
     check_forward(W, X, N, M, s.SBN_PATH_SMFMAC)
     check_forward(W, X, N, M, s.SBN_PATH_AUTO)
+
+
+@pytest.mark.parametrize("N,M", [(6, 8), (8, 8), (3, 4), (7, 8), (5, 8), (4, 4), (3, 8)])
+@pytest.mark.parametrize("tokens,shape", [(40, (130, 384)), (300, (520, 1280)), (129, (1100, 128)), (97, (64, 2560))])
+def test_sparse_mfma_path_dense_codes(N, M, tokens, shape):
+    # patterns that keep more than two of an aligned four run beyond decode sizes as dense 2-bit codes (N = M as
+    # stored, the rest converted first) through two sparse instructions per group of four: ragged edges in rows and
+    # tokens, one chunk (128) and an odd number of chunks (384 = 3), bias; same integers as the oracle
+    s = sbn()
+    W = sbn_synth.latent_weight(shape[0], shape[1], 2440 + 10 * N + M)
+    X = sbn_synth.activations(tokens, shape[1], 2450 + tokens)
+    bias = torch.randn(shape[0], generator=torch.Generator().manual_seed(19))
+    check_forward(W, X, N, M, s.SBN_PATH_SMFMAC, bias=bias)
+    check_forward(W, X, N, M, s.SBN_PATH_AUTO)
+
+
+def test_sparse_mfma_path_dense_codes_adversarial():
+    s = sbn()
+    W = sbn_synth.adversarial_weight(256, 512, 2460)
+    X = sbn_synth.adversarial_activations(64, 512, 2461)
+    for N, M in ((6, 8), (8, 8)):
+        check_forward(W, X, N, M, s.SBN_PATH_SMFMAC)
+
+
+@pytest.mark.parametrize("N,M", [(6, 8), (8, 8)])
+def test_config3_prefill_dense_codes_full_size_as_timed(N, M):
+    # configs[2] at the paper's main pattern: 4096 tokens against 6912x2560, as the benchmark times it (no accumulator
+    # output); sampled token rows against the oracle, and the launch with accumulators bit for bit the same Y
+    s = sbn()
+    W = sbn_synth.latent_weight(6912, 2560, sbn_synth.seed_for(3, 6912))
+    X = sbn_synth.activations(4096, 2560, sbn_synth.seed_for(3, 1))
+    sample = np.unique(np.concatenate([np.arange(0, 4096, 97), [31, 32, 127, 128, 4095]]))
+    Y = check_forward(W, X, N, M, s.SBN_PATH_SMFMAC, token_sample=sample)
+    packed, gamma = hip_pack(W, N, M)
+    Y2, *_ = hip_linear(X, packed, gamma, 6912, N, M, s.SBN_PATH_SMFMAC, want_acc=False)
+    assert np.array_equal(Y, Y2)
+
+
+@pytest.mark.parametrize("N,M", [(2, 4), (6, 8)])
+def test_dense_comparison_kernel_alone(N, M):
+    # the dense int8 kernel on weights expanded beforehand (sbn_unpack) gives what the comparison path gives with its
+    # own expansion pass, bit for bit, with and without the accumulator output, and the oracle's integers
+    s = sbn()
+    W = sbn_synth.latent_weight(520, 640, 2490 + N)
+    X = sbn_synth.activations(300, 640, 2491)
+    bias = torch.randn(520, generator=torch.Generator().manual_seed(23))
+    packed, gamma = hip_pack(W, N, M)
+    Y1, acc1, xq, sx = hip_linear(X, packed, gamma, 520, N, M, s.SBN_PATH_DENSE_MFMA, bias)
+    Weff = torch.empty(520, 640, dtype=torch.int8, device=DEV)
+    s.sbn_unpack(packed, 520, 640, N, M, W_eff=Weff)
+    _, _, ref_Weff, _ = oracle_pack(W, N, M)
+    assert np.array_equal(Weff.cpu().numpy(), ref_Weff)
+    for want_acc in (True, False):
+        Y = torch.full((300, 520), float("nan"), dtype=torch.float32, device=DEV)
+        acc = torch.full((300, 520), -7, dtype=torch.int32, device=DEV)
+        s.sbn_dense_ternary_linear(torch.from_numpy(xq).to(DEV), torch.from_numpy(sx).to(DEV), Weff, gamma, Y,
+                                   bias=bias.to(DEV), acc_out=acc if want_acc else None)
+        torch.cuda.synchronize()
+        assert np.array_equal(Y.cpu().numpy(), Y1)
+        if want_acc:
+            assert np.array_equal(acc.cpu().numpy(), acc1)
+            assert np.array_equal(acc1, oracle.acc(ref_Weff, xq))
+
+
+def test_grouped_prefill_dense_codes_matches_single():
+    # N = M problems of different shapes in one grouped launch of the GEMM kernel
+    s = sbn()
+    shapes = [(520, 384), (100, 128), (1030, 640)]
+    tokens = [200, 40, 333]
+    packs = [hip_pack(sbn_synth.latent_weight(a, b, 2470 + i), 8, 8) for i, (a, b) in enumerate(shapes)]
+    Xs = [sbn_synth.activations(t, b, 2480 + i).to(DEV) for i, (t, (_, b)) in enumerate(zip(tokens, shapes))]
+    Ys = [torch.zeros(t, a, dtype=torch.float32, device=DEV) for t, (a, _) in zip(tokens, shapes)]
+    need = sum(s.sbn_workspace_bytes(s.SBN_OP_LINEAR, t, a, b, 8, 8) for t, (a, b) in zip(tokens, shapes))
+    ws = s.new_workspace(need)
+    s.sbn_sparse_ternary_linear_grouped(Xs, [p for p, _ in packs], [g for _, g in packs], Ys, 8, 8, ws, path=s.SBN_PATH_SMFMAC)
+    torch.cuda.synchronize()
+    for i, (a, b) in enumerate(shapes):
+        Y1, *_ = hip_linear(Xs[i].cpu(), packs[i][0], packs[i][1], a, 8, 8, s.SBN_PATH_SMFMAC, want_acc=False)
+        assert np.array_equal(Ys[i].cpu().numpy(), Y1)
 
 
 @pytest.mark.parametrize("N,M", [(1, 4), (2, 8), (6, 8), (3, 8)])
