@@ -204,12 +204,13 @@ __device__ __forceinline__ bool bf16_tile_of_block(const GemmBf16Args &g, int bi
 
 // Result of a wavefront: 4 x 2 tiles of 32 x 32 at rows (of C) mw + 32 b + .., columns nw + 32 a + ..;
 // tile (a, b): lane holds m = column r, n = rows 8q + 4c + i: four consecutive n of one C row per store.
-__device__ __forceinline__ void bf16_wave_epilogue(const GemmBf16Args &g, const v16f (&acc)[4][2], int nw, int mw, int lane)
+template <int TBM>
+__device__ __forceinline__ void bf16_wave_epilogue(const GemmBf16Args &g, const v16f (&acc)[4][TBM], int nw, int mw, int lane)
 {
     const int r = lane & 31, c = lane >> 5;
     const float alpha = g.alpha ? *g.alpha : 1.0f;
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
+    for (int b = 0; b < TBM; ++b) {
         const int m = mw + 32 * b + r;
         if (m >= g.M) continue;
 #pragma unroll
@@ -378,7 +379,7 @@ __global__ void __launch_bounds__(256, 2) gemm_bf16_nt_kernel(GemmBf16Group grp)
     }
     multiply_tile();                   // last step: nothing left to fetch
 
-    bf16_wave_epilogue(g, acc, n0 + wn * 128, m0 + wm * 64, lane);
+    bf16_wave_epilogue<2>(g, acc, n0 + wn * 128, m0 + wm * 64, lane);
 }
 
 // ---- the same product with the operands streamed into LDS by the DMA path --------------------------
@@ -389,13 +390,19 @@ __global__ void __launch_bounds__(256, 2) gemm_bf16_nt_kernel(GemmBf16Group grp)
 // register on its way in: block tile 256 (n) x 256 (m), 512 threads = 2 x 4 wavefronts of 128 x 64 (one
 // block per multiprocessor, two wavefronts per SIMD), two LDS stages of 64 k (128-byte rows, 64 KB per
 // stage), each wavefront issues eight LDS-DMA loads for the next stage before it multiplies the
-// current one; one barrier per k step.  The 16-byte column of a row is XOR-swizzled with row & 7 (on
+// current one; one barrier per k step.  The 16-byte column of a row is XOR-swizzled with (row >> 1) & 7 (on
 // the global side of the DMA, which deposits lane l at base + 16 l), so the 32 rows x 2 columns of an
 // operand read spread over all banks.  Needs K % 64 == 0 (no partial rows in a stage).
-// The matrix pipe still waits for the DMA about a third of the time: 64 KB in flight per multiprocessor
-// cover about one microsecond.  A ring of four stages of 32 k (96 KB in flight, 64-byte rows, twice the
-// barriers) was measured slower (backward of the block 5.96 against 5.43 ms), and so was warming L2 two steps
-// ahead with one extra line-touching DMA load per wavefront and step (5.99 ms: it doubles the L2 requests).
+// The matrix pipe still waits for the operands about a third of the time.  Measured on the backward of one 6912 x 2560
+// layer at 16384 tokens (1.05 ms in this kernel): without the DMA requests (LDS reads, matrix instructions and
+// barriers only) 0.75 ms, 80 % of what the board sustains; with every block fetching the same 512 operand rows (all
+// requests hit L2) 0.95 ms; the L2 miss rate of the real launch is 19.5 %, what 32 multiprocessors sharing a 4 x 8
+// rectangle of tiles must miss ((4 + 8) / 64).  So it is the deposit path into LDS, not L2 or HBM, that costs most: at
+// 64 bytes per clock the 64 KB of a stage take half of the stage's matrix time, and the fragment reads (192 KB at 256
+// bytes per clock) take most of the other half.  Tried and measured slower: a ring of four stages of 32 k with eight
+// wavefronts (5.96 against 5.43 ms for the backward of the block); one wavefront per SIMD with 128 x 128 wave tiles,
+// four stages of 32 k and counted waits (a third fewer LDS reads, no conflicts: 1.13 ms against 1.05); warming L2 two
+// steps ahead with one extra line-touching DMA load per wavefront and step (5.99 ms: it doubles the L2 requests).
 constexpr int GD_N = 256, GD_M = 256, GD_K = 64;
 constexpr int GD_STAGE = (GD_N + GD_M) * GD_K * 2;   // 64 KB
 constexpr int GD_LDS = 2 * GD_STAGE;
@@ -415,14 +422,14 @@ __global__ void __launch_bounds__(512) gemm_bf16_dma_kernel(GemmBf16Group grp)
     const uint32_t lds0 = lds_address(dlds);
 
     // DMA roles: one instruction fills 8 rows x 128 bytes (lane l: row l / 8, slot l % 8 holding global
-    // column slot ^ (row & 7)); wavefront w fills rows 32 w .. 32 w + 31 of P and of Q: 4 + 4 instructions
+    // column slot ^ ((row >> 1) & 7)); wavefront w fills rows 32 w .. 32 w + 31 of P and of Q: 4 + 4 instructions
     const char *pbase = reinterpret_cast<const char *>(g.P + (int64_t)n0 * g.ldp);
     const char *qbase = reinterpret_cast<const char *>(g.Q + (int64_t)m0 * g.ldq);
     uint32_t poff[4], qoff[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int row = 32 * wave + 8 * i + (lane >> 3);
-        const int col = (lane & 7) ^ (row & 7);
+        const int col = (lane & 7) ^ ((row >> 1) & 7);
         int n = n0 + row;
         n = (n < g.N ? n : g.N - 1) - n0;
         poff[i] = (uint32_t)(((int64_t)n * g.ldp + col * 8) * 2);
@@ -438,12 +445,13 @@ __global__ void __launch_bounds__(512) gemm_bf16_dma_kernel(GemmBf16Group grp)
 #pragma unroll
         for (int i = 0; i < 4; ++i) lds_dma16(qb, qoff[i], dq + i * 1024);
     };
-    // LDS read addresses: row * 128 + 16 * ((2u + c) ^ (row & 7)); row & 7 = r & 7 for every tile of the
-    // wavefront, so one lane address per u and operand, tiles and stages are immediate offsets
+    // LDS read addresses: row * 128 + 16 * ((2u + c) ^ ((row >> 1) & 7)); (row >> 1) & 7 = (r >> 1) & 7 for every
+    // tile of the wavefront, so one lane address per u and operand, tiles and stages are immediate offsets.  (With
+    // row & 7 as the swizzle, rows r and r + 8 of a 16-lane group met in the same banks: four conflict cycles per read.)
     uint32_t pa[4], qa[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-        const int slot = (2 * u + c) ^ (r & 7);
+        const int slot = (2 * u + c) ^ ((r >> 1) & 7);
         pa[u] = lds0 + (wn * 128 + r) * 128 + 16 * slot;
         qa[u] = lds0 + GD_N * GD_K * 2 + (wm * 64 + r) * 128 + 16 * slot;
     }
@@ -492,7 +500,7 @@ __global__ void __launch_bounds__(512) gemm_bf16_dma_kernel(GemmBf16Group grp)
     }
     if (kt < nk) step(kt, 0);
 
-    bf16_wave_epilogue(g, acc, n0 + wn * 128, m0 + wm * 64, lane);
+    bf16_wave_epilogue<2>(g, acc, n0 + wn * 128, m0 + wm * 64, lane);
 }
 
 GemmBf16Args make_bf16_args(const uint16_t *P, int64_t ldp, int N, const uint16_t *Q, int64_t ldq, int M, int K, uint16_t *C,
