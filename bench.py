@@ -48,7 +48,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--sections", default="gemm,gemv,pack,train,dense,seq,ceil,cpu",
                     help="comma list of: gemm (always timed), gemv, pack, train, dense, ceil, cpu, copyref")
+    ap.add_argument("--only", default="",
+                    help="counter runs only: restrict the prefill shapes to one (e.g. 6912x2560) and/or the decode "
+                         "workloads to one (e.g. down_2560x6912_T8), so that every dispatch of a persistent kernel "
+                         "in the run is the same workload (their grids do not tell them apart)")
     args = ap.parse_args()
+    only = set(x for x in args.only.split(",") if x)
     if args.gpus != 1:
         log("bench.py: this build measures one GPU only (across GPUs the layer would shard by rows of W, with "
             "one scalar all-reduce for the weight scale); run with --gpus 1")
@@ -104,7 +109,7 @@ def main():
     # ------------------------------------------------------------------ configs[2]: prefill GEMM (the timed step)
     T = 4096
     NSETS = 4
-    shapes = [(H, H), (F, H)]
+    shapes = [(a, b) for a, b in [(H, H), (F, H)] if not only & {"2560x2560", "6912x2560"} or f"{a}x{b}" in only]
     Wp = [pack_one(sbn_synth.latent_weight(a, b, sbn_synth.seed_for(3, a), device=dev)) for a, b in shapes]
     Xs = [sbn_synth.activations(T, H, sbn_synth.seed_for(3, 10 + i), device=dev) for i in range(NSETS)]
     Ys = [[torch.empty(T, a, dtype=torch.float32, device=dev) for a, _ in shapes] for _ in range(NSETS)]
@@ -171,7 +176,7 @@ def main():
     log(f"[gemm] act_quant {ms_aq * 1e3:.1f} us ({rows['act_quant_4096x2560']['gbps']:.0f} GB/s); with RMS norm fused "
         f"{ms_nq * 1e3:.1f} us ({rows['rmsnorm_act_quant_4096x2560']['gbps']:.0f} GB/s)")
     rows["gemm_sparse"] = gemm_rows
-    big = gemm_rows[f"{F}x{H}"]
+    big = gemm_rows[f"{F}x{H}"] if f"{F}x{H}" in gemm_rows else next(iter(gemm_rows.values()))
     roofline = {"kernel": "gemm_smfmac_kernel", "workload": f"T={T} K={H} d_out={F}", "bound": "mfma",
                 "achieved": big["executed_tops"], "peak": INT8_DENSE_PEAK_TOPS, "unit": "TOP/s",
                 "frac": big["frac_int8_mfma"], "traffic": measured_traffic("gemm_smfmac_kernel", f"{F}x{H}"),
@@ -304,6 +309,8 @@ def main():
             packs = [pack_one(sbn_synth.latent_weight(a, b, sbn_synth.seed_for(2, 100 * r + a % 7), device=dev)) for r in range(R)]
             pbytes = sbn.sbn_packed_bytes(a, b, N, M)
             for tok in (1, 8):
+                if any(o.startswith(("up_", "down_")) for o in only) and f"{name}_T{tok}" not in only:
+                    continue
                 X = sbn_synth.activations(tok, b, sbn_synth.seed_for(2, tok), device=dev)
                 Yl = [torch.empty(tok, a, dtype=torch.float32, device=dev) for _ in range(R)]
                 ws = sbn.new_workspace(R * sbn.sbn_workspace_bytes(sbn.SBN_OP_LINEAR, tok, a, b, N, M), dev)

@@ -905,12 +905,14 @@ GemmArgs make_args(const LinearItem &it, int block_tokens = BT)
 }  // namespace
 
 // Deals the work of a launch to the blocks (host side).  Per XCD: the strips (problem, token group of 16 units, row
-// tile of 512) are cut into exactly m * nb pieces of at most four units, as even as the strip lengths allow; the pieces
-// are sorted by width and dealt to the nb blocks of the XCD in snake order, so that every block gets m pieces whose
-// widths add up to the same number of units (+-1) and no block is left with single-unit crumbs (a piece of one unit
-// pays nine vector instructions per matrix instruction).  Every other block runs its pieces in reverse order, so that
-// neighbours do not reach their epilogues (bursts of Y stores) together.  Returns blocks per XCD; leaves
-// tab.per_block = 0 (formula split in the kernel) when the list would not fit.
+// tile of 512) are cut into exactly m * nb pieces of at most four units, as even as the strip lengths allow (no block
+// is left with single-unit crumbs: a piece of one unit pays nine vector instructions per matrix instruction).  The
+// pieces stay in strip order and are dealt in m rounds of nb: the pieces that run at about the same time belong to a
+// few neighbouring strips, whose weights and tokens fit the XCD's L2 together (dealt by width alone, across all strips,
+// the same launch fetched 88 MB instead of 50 at 6912 x 2560 x 4096).  Inside a round the widest pieces go to the
+// blocks with the least work so far, so every block ends up with the same number of units (+-1).  Odd XCDs run their
+// rounds in reverse order, so that the chip's XCDs do not all reach their epilogues (bursts of Y stores) together.
+// Returns blocks per XCD; leaves tab.per_block = 0 (formula split in the kernel) when the list would not fit.
 static int make_piece_table(const GemmGroup &grp, PieceTable &tab)
 {
     constexpr int GROUP_UNITS = 16;
@@ -974,16 +976,30 @@ static int make_piece_table(const GemmGroup &grp, PieceTable &tab)
                 u += w;
             }
         }
-        std::stable_sort(pieces.begin(), pieces.end(), [](uint32_t a, uint32_t b) { return (a & 7) > (b & 7); });
+        // Pieces stay in strip order: round i (the i-th piece of every block, roughly the same stretch of time) takes
+        // the pieces [i * nb, (i + 1) * nb), i.e. a few neighbouring strips whose weights and tokens fit the XCD's L2
+        // together.  Inside a round the widest pieces go to the blocks with the least work so far.
         for (int j = 0; j < nb; ++j) per_block[j].clear();
-        for (size_t k = 0; k < pieces.size(); ++k) {
-            const int round = (int)(k / nb), pos = (int)(k % nb);
-            per_block[(round & 1) ? nb - 1 - pos : pos].push_back(pieces[k]);
+        static thread_local std::vector<int> load, by_load, by_width;
+        load.assign(nb, 0);
+        const int rounds = ((int)pieces.size() + nb - 1) / nb;
+        if (rounds > m) return nb;   // cannot happen: the strips were cut into at most m * nb pieces
+        for (int i = 0; i < rounds; ++i) {
+            const int first = i * nb, n = (int)pieces.size() - first < nb ? (int)pieces.size() - first : nb;
+            by_width.resize(n);
+            for (int k = 0; k < n; ++k) by_width[k] = first + k;
+            std::stable_sort(by_width.begin(), by_width.end(), [&](int a, int b) { return (pieces[a] & 7) > (pieces[b] & 7); });
+            by_load.resize(nb);
+            for (int j = 0; j < nb; ++j) by_load[j] = j;
+            std::stable_sort(by_load.begin(), by_load.end(), [&](int a, int b) { return load[a] < load[b]; });
+            for (int k = 0; k < n; ++k) {
+                per_block[by_load[k]].push_back(pieces[by_width[k]]);
+                load[by_load[k]] += (int)(pieces[by_width[k]] & 7);
+            }
         }
         for (int j = 0; j < nb; ++j) {
             std::vector<uint32_t> &l = per_block[j];
-            if ((int)l.size() > m) return nb;   // cannot happen: every round gives a block at most one piece
-            if (j & 1) std::reverse(l.begin(), l.end());
+            if (x & 1) std::reverse(l.begin(), l.end());   // odd XCDs run their rounds last to first
             for (size_t i = 0; i < l.size(); ++i) tab.piece[(size_t)(j * 8 + x) * m + i] = l[i];
         }
     }
