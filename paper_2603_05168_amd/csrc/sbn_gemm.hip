@@ -188,9 +188,11 @@ __device__ __forceinline__ void load_scales(const GemmArgs &g, int tok0, int lan
 // rows 64 w .. 64 w + 63 (two row tiles of 32) and all tokens of the piece (TB = 1 .. 4 token tiles of 32), so one code
 // expansion (nine vector instructions) feeds TB matrix instructions: measured on this part, up to four vector
 // instructions per matrix instruction hide under it, more cost their full time.  The two wavefronts of a SIMD cover
-// each other's waits.  What bounds the main loop is LDS time: per 128-k step the wavefronts read 144 KB of operand
-// fragments and the DMA deposits 32 KB, and the two do not overlap; against two independent blocks of 256 x 128 the
-// shared token tile saves a third of the DMA bytes (256 instead of 384 bytes per matrix instruction).
+// each other's waits.  Per 128-k step the wavefronts read 144 KB of operand fragments from LDS and the DMA deposits
+// 32 KB; measured with a microbenchmark, reads (475 bytes/ns) and deposits (105 bytes/ns from L2) overlap, so it is
+// the deposit path that is scarce: a step's 32 KB are 0.3 us of it against 0.5 us of matrix work.  Against two
+// independent blocks of 256 x 128 the shared token tile saves a third of those bytes (256 instead of 384 bytes per
+// matrix instruction).
 // Both operands reach LDS through LDS-DMA loads (lane l of a wavefront deposits its 16 bytes at base + 16*l), so no
 // staging registers are needed and every load instruction reads whole cache lines:
 //   tokens   128 tokens x 128 int8 per stage, ring of NST stages; one instruction fills 8 token rows of 128 bytes; the
