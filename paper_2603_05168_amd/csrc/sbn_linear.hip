@@ -376,6 +376,13 @@ __global__ void __launch_bounds__(1024) gemv_smfmac_kernel(GemvTable tab)
 // of the current problem (tokens x d_in) are staged in LDS once per block and problem; the packed weights
 // go straight from HBM to registers through a queue of DEPTH super-steps (512 weights each) per
 // wavefront, so that several 16-byte loads per lane are always in flight.  No cross-wave reduction.
+// The blocks' shares are equal and fixed.  Measured with timestamps (64 x (2560 x 6912), eight tokens, 52 us): the
+// blocks finish between 43 and 52 us - multiprocessors in alternate positions of an XCD run about 10 % apart, and so
+// do the older and the younger wavefronts of a SIMD - and the wavefronts idle 7 us on average before the kernel ends.
+// Holding back a sixth of the units as a device-wide pool for wavefronts out of work did not recover that (52.7 us):
+// a unit of 16 rows is 10 us of one wavefront's time at K = 6912, as coarse as the imbalance itself, and a counter
+// that 2048 wavefronts ask per unit is far too hot (5800 returning atomics on one word: 55 us), so the pool had to be
+// drawn per block, eight units at a time.  Finer balancing would need units split along K across wavefronts.
 struct GemvStreamItem {
     const int8_t *xq;
     const float *sx;
@@ -518,8 +525,13 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
         // compiler places before a slot is consumed leaves the DEPTH - 1 younger super-steps in
         // flight (a load inside a branch makes it wait for everything).  Past the end of the
         // wavefront's work the last unit is fetched again (cache hits, no HBM traffic) and ignored.
+        // A ragged unit is walked from its partial last super-step: rows of 13.5 cache lines (K = 6912) share a line
+        // between the tail of one row and the head of the next, and with the tail first the two halves are asked for
+        // by consecutive load instructions instead of a whole unit apart (measured: 64 bytes per row fetched twice,
+        // 3.7 % of the stream, when the tail came last).  Integer sums do not care about the order.
+        auto super_of = [&](int s) { return ragged ? (s == 0 ? nsuper - 1 : s - 1) : s; };
         auto issue = [&](uint4(&ib)[RT], uint4(&cb)[RT]) {
-            int ch = 4 * is + c4;
+            int ch = 4 * super_of(is) + c4;
             ch = ch < nchunks ? ch : nchunks - 1;
             const int unit = iu < wb ? iu : ub - 1;
 #pragma unroll
@@ -615,7 +627,8 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
 #pragma unroll
                 for (int a = 0; a < RT; ++a) { ic[a] = qi[d][a]; cc[a] = qc[d][a]; }
                 issue(qi[d], qc[d]);
-                if ((ragged && cs == nsuper - 1 && 4 * cs + c4 >= nchunks) || cu >= wb) {
+                const int ps = super_of(cs);   // the super-step of the unit that slot d holds
+                if ((ragged && ps == nsuper - 1 && 4 * ps + c4 >= nchunks) || cu >= wb) {
 #pragma unroll
                     for (int a = 0; a < RT; ++a) {
                         cc[a] = make_uint4(0, 0, 0, 0);
@@ -625,7 +638,7 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
                 if constexpr (DENSE) {
 #pragma unroll
                     for (int j = 0; j < 8; ++j) {
-                        const v4i b = *reinterpret_cast<const v4i *>(&xlds[xoff + cs * 512 + 16 * j]);
+                        const v4i b = *reinterpret_cast<const v4i *>(&xlds[xoff + ps * 512 + 16 * j]);
 #pragma unroll
                         for (int a = 0; a < RT; ++a) {
                             const uint4 &half = j < 4 ? ic[a] : cc[a];
@@ -636,8 +649,8 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
                 }
 #pragma unroll
                 for (int j = 0; j < (DENSE ? 0 : 4); ++j) {
-                    const uint4 blo = *reinterpret_cast<const uint4 *>(&xlds[xoff + cs * 512 + 32 * j]);
-                    const uint4 bhi = *reinterpret_cast<const uint4 *>(&xlds[xoff + cs * 512 + 32 * j + 256]);
+                    const uint4 blo = *reinterpret_cast<const uint4 *>(&xlds[xoff + ps * 512 + 32 * j]);
+                    const uint4 bhi = *reinterpret_cast<const uint4 *>(&xlds[xoff + ps * 512 + 32 * j + 256]);
                     const v8i b = {(int)blo.x, (int)blo.y, (int)blo.z, (int)blo.w, (int)bhi.x, (int)bhi.y, (int)bhi.z, (int)bhi.w};
 #pragma unroll
                     for (int a = 0; a < RT; ++a) {
@@ -848,7 +861,7 @@ static sbn_status launch_gemv_as(int count, const LinearItem *items, hipStream_t
             // One row tile per unit, DEPTH 5 and 8 wavefronts per block measured best among one or two row tiles,
             // depths 2..8 and 6..16 wavefronts (more wavefronts finish their shares further apart, fewer leave too
             // few loads in flight; units of 16 rows balance the wavefronts better than units of 32: +2.5 to +4 %)
-            constexpr int DEPTH = 5, NW = 8;
+                        constexpr int DEPTH = 5, NW = 8;
             GemvStreamTable tab;
             tab.count = n;
             tab.nin = 0;
