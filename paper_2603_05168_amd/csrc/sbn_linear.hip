@@ -525,13 +525,8 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
         // compiler places before a slot is consumed leaves the DEPTH - 1 younger super-steps in
         // flight (a load inside a branch makes it wait for everything).  Past the end of the
         // wavefront's work the last unit is fetched again (cache hits, no HBM traffic) and ignored.
-        // A ragged unit is walked from its partial last super-step: rows of 13.5 cache lines (K = 6912) share a line
-        // between the tail of one row and the head of the next, and with the tail first the two halves are asked for
-        // by consecutive load instructions instead of a whole unit apart (measured: 64 bytes per row fetched twice,
-        // 3.7 % of the stream, when the tail came last).  Integer sums do not care about the order.
-        auto super_of = [&](int s) { return ragged ? (s == 0 ? nsuper - 1 : s - 1) : s; };
         auto issue = [&](uint4(&ib)[RT], uint4(&cb)[RT]) {
-            int ch = 4 * super_of(is) + c4;
+            int ch = 4 * is + c4;
             ch = ch < nchunks ? ch : nchunks - 1;
             const int unit = iu < wb ? iu : ub - 1;
 #pragma unroll
@@ -627,8 +622,7 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
 #pragma unroll
                 for (int a = 0; a < RT; ++a) { ic[a] = qi[d][a]; cc[a] = qc[d][a]; }
                 issue(qi[d], qc[d]);
-                const int ps = super_of(cs);   // the super-step of the unit that slot d holds
-                if ((ragged && ps == nsuper - 1 && 4 * ps + c4 >= nchunks) || cu >= wb) {
+                if ((ragged && cs == nsuper - 1 && 4 * cs + c4 >= nchunks) || cu >= wb) {
 #pragma unroll
                     for (int a = 0; a < RT; ++a) {
                         cc[a] = make_uint4(0, 0, 0, 0);
@@ -638,7 +632,7 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
                 if constexpr (DENSE) {
 #pragma unroll
                     for (int j = 0; j < 8; ++j) {
-                        const v4i b = *reinterpret_cast<const v4i *>(&xlds[xoff + ps * 512 + 16 * j]);
+                        const v4i b = *reinterpret_cast<const v4i *>(&xlds[xoff + cs * 512 + 16 * j]);
 #pragma unroll
                         for (int a = 0; a < RT; ++a) {
                             const uint4 &half = j < 4 ? ic[a] : cc[a];
@@ -649,8 +643,8 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
                 }
 #pragma unroll
                 for (int j = 0; j < (DENSE ? 0 : 4); ++j) {
-                    const uint4 blo = *reinterpret_cast<const uint4 *>(&xlds[xoff + ps * 512 + 32 * j]);
-                    const uint4 bhi = *reinterpret_cast<const uint4 *>(&xlds[xoff + ps * 512 + 32 * j + 256]);
+                    const uint4 blo = *reinterpret_cast<const uint4 *>(&xlds[xoff + cs * 512 + 32 * j]);
+                    const uint4 bhi = *reinterpret_cast<const uint4 *>(&xlds[xoff + cs * 512 + 32 * j + 256]);
                     const v8i b = {(int)blo.x, (int)blo.y, (int)blo.z, (int)blo.w, (int)bhi.x, (int)bhi.y, (int)bhi.z, (int)bhi.w};
 #pragma unroll
                     for (int a = 0; a < RT; ++a) {
