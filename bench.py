@@ -337,9 +337,10 @@ def main():
             del packs
             torch.cuda.empty_cache()
         rows["gemv"] = gemv_rows
-        # decode of other patterns at 6912x2560, T = 8, through automatic path selection: instances of 2:4 are
-        # rewritten into the 2:4 operand form per call, everything else into dense 2-bit codes (6:8 is the
-        # paper's main pattern); N = M is stored as dense codes, so it also streams in a grouped call
+        # decode of other patterns at 6912x2560, T = 8, through automatic path selection: 1:4 is read as stored (the
+        # kernel builds the sparse operands in registers), the other instances of 2:4 are rewritten into the 2:4
+        # operand form per call, everything else into dense 2-bit codes (6:8 is the paper's main pattern); N = M is
+        # stored as dense codes; 1:4 and N = M also stream in a grouped call
         other = {}
         X8 = sbn_synth.activations(8, H, sbn_synth.seed_for(2, 8), device=dev)
         Y8 = [torch.empty(8, F, dtype=torch.float32, device=dev) for _ in range(8)]
@@ -353,7 +354,8 @@ def main():
                 k[0] += 1
                 sbn.sbn_sparse_ternary_linear(X8, pk[r][0], pk[r][1], Y8[r], n8, m8, ws1, path=sbn.SBN_PATH_AUTO)
             us = timed(single_p, 256, 8) * 1e3
-            other[f"{n8}of{m8}"] = {"single_call_us_with_rewrite": us, "packed_bytes": sbn.sbn_packed_bytes(F, H, n8, m8)}
+            other[f"{n8}of{m8}"] = {"single_call_us": us, "rewritten_per_call": (n8, m8) in ((6, 8), (2, 8)),
+                                    "packed_bytes": sbn.sbn_packed_bytes(F, H, n8, m8)}
             log(f"[gemv] {n8}:{m8} 6912x2560 T=8 single call {us:.1f} us")
             del pk, ws1
         packs = [pack_one(sbn_synth.latent_weight(F, H, sbn_synth.seed_for(2, 400 + r), device=dev), 8, 8) for r in range(R)]
@@ -365,6 +367,18 @@ def main():
         gbps = R * pbytes / (ms * 1e-3) / 1e9
         other["8of8"].update({"stream_gbps": gbps, "frac_hbm": gbps / HBM_PEAK_GBPS, "copies": R})
         log(f"[gemv] 8:8 (dense 2-bit codes) 6912x2560 T=8: stream {gbps:.0f} GB/s ({gbps / HBM_PEAK_GBPS:.1%} of HBM peak)")
+        del packs, grp
+        # 1:4 as stored (one bit per weight), counted on its own packed bytes
+        packs = [pack_one(sbn_synth.latent_weight(F, H, sbn_synth.seed_for(2, 450 + r), device=dev), 1, 4) for r in range(R)]
+        pb14 = sbn.sbn_packed_bytes(F, H, 1, 4)
+        grp = sbn.LinearGroup([X8] * R, [p for p, _ in packs], [g for _, g in packs], Yl, 1, 4, ws, sbn.SBN_PATH_GEMV)
+        ms = timed(grp.run, 100, 3)
+        gbps = R * pb14 / (ms * 1e-3) / 1e9
+        other["1of4"].update({"stream_gbps": gbps, "frac_hbm": gbps / HBM_PEAK_GBPS, "copies": R, "stream_ms_per_matrix": ms / R,
+                              "stream_time_vs_2of4": ms / R / gemv_rows["up_6912x2560_T8"]["stream_ms_per_matrix"]
+                              if "up_6912x2560_T8" in gemv_rows else None})
+        log(f"[gemv] 1:4 as stored 6912x2560 T=8: stream {gbps:.0f} GB/s of its packed bytes ({gbps / HBM_PEAK_GBPS:.1%} of HBM peak), "
+            f"{ms / R * 1e3:.2f} us per matrix")
         del packs, grp
         # 6:8 converted once into dense codes (sbn_convert_packed), then streamed like any pre-packed weight
         convs = []

@@ -60,9 +60,10 @@ typedef enum {
     SBN_PATH_AUTO = 0,       /* d_in % 128 == 0: GEMV for tokens <= 16, sparse MFMA GEMM for more.  Any other case: dense
                                 MFMA if d_in % 64 == 0, generic else */
     SBN_PATH_GEMV = 1,       /* decode kernel: streams the packed weights once; tokens <= 16, d_in % 128 == 0.  2:4 runs
-                                on the sparse instruction and N = M (dense 2-bit codes) on the dense one as stored; other
-                                patterns are rewritten per call into one of the two (a pass over the packed weights:
-                                sbn_convert_packed does it once instead) */
+                                on the sparse instruction and N = M (dense 2-bit codes) on the dense one as stored; 1:4
+                                is read as stored too (one bit per weight: the kernel builds the sparse instruction's
+                                operands in registers); other patterns are rewritten per call into one of the two forms
+                                (a pass over the packed weights: sbn_convert_packed does it once instead) */
     SBN_PATH_SMFMAC = 2,     /* prefill/training GEMM on sparse int8 MFMA (v_smfmac); d_in % 128 == 0.  2:4 runs as
                                 stored, its instances (1:2, 1:4, 1:8, 2:8) after a rewrite into the 2:4 operand form.
                                 Every other pattern (6:8, N:8, ...) runs as dense 2-bit codes - N = M as stored, the
@@ -176,7 +177,7 @@ sbn_status sbn_sparse_ternary_linear(const void *X, int64_t tokens, int64_t d_in
  *   arguments   as sbn_sparse_ternary_linear
  *   limits      align256(tokens * d_in) + align256(4 * tokens) <= SBN_STATIC_SCRATCH_MIB MiB, else SBN_ESIZE
  *               (sbn_last_error() then says how much was needed); only paths that read the weights as stored:
- *               2:4 and N = M on SBN_PATH_GEMV / SBN_PATH_SMFMAC, any pattern on SBN_PATH_GENERIC
+ *               2:4 and N = M on SBN_PATH_GEMV / SBN_PATH_SMFMAC, 1:4 on SBN_PATH_GEMV, any pattern on SBN_PATH_GENERIC
  *               (SBN_PATH_AUTO when it resolves to one of these); every other case SBN_EUNSUPPORTED
  *   sharing     all calls on a GPU use that GPU's one buffer, which keeps the last call's contents (nothing in it has
  *               to start at zero: flags left behind carry the number of the launch that raised them).  Calls that

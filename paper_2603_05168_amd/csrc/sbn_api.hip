@@ -167,6 +167,7 @@ static sbn_status linear_one(const LinearItem &it_in, const Pattern &pat, sbn_pa
     const bool is24 = pat.N == 2 && pat.M == 4;
     path = resolve_path(path, it.tokens, it.d_in, pat);
     const bool sparse_form = is24 || embeds_in_2of4(pat);   // runs on the sparse instruction (after a rewrite unless 2:4)
+    const bool one4_decode = pat.N == 1 && pat.M == 4 && path == SBN_PATH_GEMV;   // the decode kernels read 1:4 as stored
     if (path == SBN_PATH_GEMV && it.tokens > 16) return SBN_EUNSUPPORTED;
     if ((path == SBN_PATH_GEMV || path == SBN_PATH_SMFMAC) && it.d_in % CHUNK != 0) return SBN_EUNSUPPORTED;
     if (path == SBN_PATH_DENSE_MFMA && it.d_in % 64 != 0) return SBN_EUNSUPPORTED;
@@ -174,7 +175,8 @@ static sbn_status linear_one(const LinearItem &it_in, const Pattern &pat, sbn_pa
     const size_t sx_bytes = align_up((size_t)it.tokens * sizeof(float), 256);
     if (activations_only) {
         const bool weights_as_stored = path == SBN_PATH_GENERIC ||
-                                       ((path == SBN_PATH_SMFMAC || path == SBN_PATH_GEMV) && (is24 || pat.N == pat.M));
+                                       ((path == SBN_PATH_SMFMAC || path == SBN_PATH_GEMV) && (is24 || pat.N == pat.M)) ||
+                                       one4_decode;
         if (!weights_as_stored) return SBN_EUNSUPPORTED;
         if (ws_bytes < xq_bytes + sx_bytes) return SBN_ESIZE;
     } else if (ws_bytes < linear_workspace_bytes(it.tokens, it.d_out, it.d_in)) {
@@ -193,7 +195,7 @@ static sbn_status linear_one(const LinearItem &it_in, const Pattern &pat, sbn_pa
     it.quantized = !defer;
     if (it.X && !defer) st = launch_act_quant(it.X, it.tokens, it.d_in, it.xq, it.sx, stream);
     if (st != SBN_OK) return st;
-    if ((path == SBN_PATH_GEMV || path == SBN_PATH_SMFMAC) && !is24 && sparse_form) {
+    if ((path == SBN_PATH_GEMV || path == SBN_PATH_SMFMAC) && !is24 && sparse_form && !one4_decode) {
         // an instance of 2:4: the dense-weight region of the workspace takes its 2:4 operand form (a quarter of the size)
         st = launch_repack_2of4(it.packed, it.d_out, it.d_in, pat, reinterpret_cast<uint8_t *>(w_dense), stream);
         if (st != SBN_OK) return st;
@@ -206,7 +208,7 @@ static sbn_status linear_one(const LinearItem &it_in, const Pattern &pat, sbn_pa
         it.packed = w_dense;
     }
     switch (path) {
-    case SBN_PATH_GEMV: return launch_gemv(1, &it, !sparse_form, stream);
+    case SBN_PATH_GEMV: return launch_gemv(1, &it, one4_decode ? GEMV_1OF4 : sparse_form ? GEMV_2OF4 : GEMV_DENSE, stream);
     case SBN_PATH_SMFMAC: return launch_gemm_smfmac(1, &it, !sparse_form, stream);
     case SBN_PATH_DENSE_MFMA: return launch_gemm_dense(it, pat, w_dense, stream);
     case SBN_PATH_GENERIC: return launch_linear_generic(it, pat, stream);
@@ -321,9 +323,10 @@ sbn_status sbn_sparse_ternary_linear_grouped(int count, const void *const *X, co
         if (d_in[i] % 8 != 0) return SBN_EUNSUPPORTED;
         need += linear_workspace_bytes(tokens[i], d_out[i], d_in[i]);
         const bool is24 = pat.N == 2 && pat.M == 4;
-        if (resolve_path(path, tokens[i], d_in[i], pat) != SBN_PATH_GEMV || !(is24 || pat.N == pat.M) || tokens[i] > 16 ||
+        const bool one4 = pat.N == 1 && pat.M == 4;
+        if (resolve_path(path, tokens[i], d_in[i], pat) != SBN_PATH_GEMV || !(is24 || one4 || pat.N == pat.M) || tokens[i] > 16 ||
             d_in[i] % CHUNK != 0)
-            all_gemv = false;   // one launch streams 2:4 or dense-code (N = M) weights as stored; other patterns need a rewrite each
+            all_gemv = false;   // one launch streams 2:4, 1:4 or dense-code (N = M) weights as stored; other patterns need a rewrite each
         if (resolve_path(path, tokens[i], d_in[i], pat) != SBN_PATH_SMFMAC || !(is24 || pat.N == pat.M) || d_in[i] % CHUNK != 0 ||
             tokens[i] * d_out[i] >= (int64_t)1 << 40)
             all_smfmac = false;
@@ -364,7 +367,7 @@ sbn_status sbn_sparse_ternary_linear_grouped(int count, const void *const *X, co
             if (st != SBN_OK) return st;
         }
     }
-    return all_gemv ? launch_gemv(count, tl_items.data(), pat.N == pat.M, s)
+    return all_gemv ? launch_gemv(count, tl_items.data(), pat.N == pat.M ? GEMV_DENSE : pat.M == 4 && pat.N == 1 ? GEMV_1OF4 : GEMV_2OF4, s)
                     : launch_gemm_smfmac(count, tl_items.data(), pat.N == pat.M, s);
 }
 

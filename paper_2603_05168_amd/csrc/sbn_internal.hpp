@@ -90,8 +90,11 @@ sbn_status launch_act_quant(const void *X, int64_t tokens, int64_t d_in, int8_t 
                             hipStream_t stream);
 sbn_status launch_rmsnorm_act_quant(const void *X, const float *gain, float eps, int64_t tokens, int64_t d_in, int8_t *xq,
                                     float *sx, void *xn, hipStream_t stream);
+// how the decode kernels read the packed weights: the 2:4 operand form, dense 2-bit codes (N = M), or the 1:4
+// packed form as stored (rewritten into sparse operands in registers)
+enum GemvForm : int { GEMV_2OF4 = 0, GEMV_DENSE = 1, GEMV_1OF4 = 2 };
+sbn_status launch_gemv(int count, const LinearItem *items, GemvForm form, hipStream_t stream);
 // dense_codes: the weights are dense 2-bit codes (packed form of N = M) instead of the 2:4 form
-sbn_status launch_gemv(int count, const LinearItem *items, bool dense_codes, hipStream_t stream);
 sbn_status launch_gemm_smfmac(int count, const LinearItem *items, bool dense_codes, hipStream_t stream);
 sbn_status launch_gemm_dense(const LinearItem &it, const Pattern &pat, int8_t *w_dense, hipStream_t stream);
 sbn_status launch_gemm_dense_expanded(const LinearItem &it, const int8_t *w_dense, hipStream_t stream);

@@ -257,9 +257,13 @@ static_assert(sizeof(GemvTable) <= 4096, "the table travels as a kernel argument
 // N = M, and what other patterns are rewritten to for decode): a chunk is eight code words, every
 // word is the A operand of one v_mfma_i32_16x16x64_i8 (lane quarter c holds k = 16c .. 16c+15 of
 // the instruction on both operands), so a super-step is eight dense instructions instead of four sparse.
-template <bool DENSE>
+// FORM = GEMV_1OF4 reads the 1:4 packed form as stored (16-byte chunks, one load per lane and super-step) and builds
+// the sparse instruction's operands in registers (expand_1of4): half the weight bytes for three times the vector work.
+template <int FORM>
 __global__ void __launch_bounds__(1024) gemv_smfmac_kernel(GemvTable tab)
 {
+    constexpr bool DENSE = FORM == GEMV_DENSE, ONE4 = FORM == GEMV_1OF4;
+    constexpr int CB = ONE4 ? 16 : 32;   // bytes of a chunk
     extern __shared__ __attribute__((aligned(16))) int8_t xs[];   // self-quantized activations [tokens][d_in + 16]
     __shared__ v4i red[16][64];
     __shared__ uint32_t amax_s[16][16];   // [token][wavefront]
@@ -273,7 +277,7 @@ __global__ void __launch_bounds__(1024) gemv_smfmac_kernel(GemvTable tab)
     const int K = it.d_in, nchunks = K / CHUNK, nsuper = (nchunks + 3) / 4;
     int row = row0 + r;
     row = row < it.d_out ? row : it.d_out - 1;   // rows past the end are computed and dropped
-    const uint8_t *wrow = it.packed + (int64_t)row * nchunks * 32;
+    const uint8_t *wrow = it.packed + (int64_t)row * nchunks * CB;
     const bool tok_ok = r < it.tokens;           // as B operand the lane holds token r
     const bool self_quant = it.X != nullptr;
     const int pitch = K + 16;
@@ -286,8 +290,8 @@ __global__ void __launch_bounds__(1024) gemv_smfmac_kernel(GemvTable tab)
         idx4 = make_uint4(0, 0, 0, 0);
         code4 = make_uint4(0, 0, 0, 0);
         if (s < nsuper && chunk < nchunks) {
-            idx4 = *reinterpret_cast<const uint4 *>(wrow + (int64_t)chunk * 32);
-            code4 = *reinterpret_cast<const uint4 *>(wrow + (int64_t)chunk * 32 + 16);
+            idx4 = *reinterpret_cast<const uint4 *>(wrow + (int64_t)chunk * CB);
+            if constexpr (!ONE4) code4 = *reinterpret_cast<const uint4 *>(wrow + (int64_t)chunk * CB + 16);
         }
     };
     fetch(wave);
@@ -337,6 +341,12 @@ __global__ void __launch_bounds__(1024) gemv_smfmac_kernel(GemvTable tab)
             continue;
         }
         const int kb = s * 512 + 128 * (c4 >> 1) + 16 * (c4 & 1);
+        uint32_t iw1[2][2];
+        v4i a1[2][2];
+        if constexpr (ONE4) {   // the chunk is two index words and two code words
+            expand_1of4(idxw[0], idxw[2], ones, iw1[0], a1[0]);
+            expand_1of4(idxw[1], idxw[3], ones, iw1[1], a1[1]);
+        }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int k_lo = kb + 32 * j, k_hi = k_lo + 256;
@@ -344,7 +354,10 @@ __global__ void __launch_bounds__(1024) gemv_smfmac_kernel(GemvTable tab)
             if (tok_ok && k_lo < K) blo = *reinterpret_cast<const uint4 *>(xrow + k_lo);
             if (tok_ok && k_hi < K) bhi = *reinterpret_cast<const uint4 *>(xrow + k_hi);
             const v8i b = {(int)blo.x, (int)blo.y, (int)blo.z, (int)blo.w, (int)bhi.x, (int)bhi.y, (int)bhi.z, (int)bhi.w};
-            acc = __builtin_amdgcn_smfmac_i32_16x16x128_i8(expand_codes(codew[j], ones), b, acc, (int)idxw[j], 0, 0);
+            if constexpr (ONE4)
+                acc = __builtin_amdgcn_smfmac_i32_16x16x128_i8(a1[j >> 1][j & 1], b, acc, (int)iw1[j >> 1][j & 1], 0, 0);
+            else
+                acc = __builtin_amdgcn_smfmac_i32_16x16x128_i8(expand_codes(codew[j], ones), b, acc, (int)idxw[j], 0, 0);
         }
     }
     red[wave][lane] = acc;
@@ -428,9 +441,11 @@ __device__ __forceinline__ unsigned long long gemv_flag_value(unsigned epoch, in
     return ((unsigned long long)epoch << 32) | (0x5bd1e995u ^ (unsigned)t);
 }
 
-template <int RT, int DEPTH, int NW, bool DENSE>
+template <int RT, int DEPTH, int NW, int FORM>
 __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable tab)
 {
+    constexpr bool DENSE = FORM == GEMV_DENSE, ONE4 = FORM == GEMV_1OF4;
+    constexpr int CB = ONE4 ? 16 : 32;   // bytes of a chunk: the 1:4 form is one 16-byte load per lane and super-step
     extern __shared__ __attribute__((aligned(16))) int8_t xlds[];   // [tokens][d_in + 16]
     __shared__ int unit_ctr;                                        // next unit of the current problem nobody has taken
     __shared__ float sx_lds[16];                                    // s_x of the staged tokens of a self-quantized input
@@ -525,17 +540,27 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
         // compiler places before a slot is consumed leaves the DEPTH - 1 younger super-steps in
         // flight (a load inside a branch makes it wait for everything).  Past the end of the
         // wavefront's work the last unit is fetched again (cache hits, no HBM traffic) and ignored.
-        auto issue = [&](uint4(&ib)[RT], uint4(&cb)[RT]) {
-            int ch = 4 * is + c4;
-            ch = ch < nchunks ? ch : nchunks - 1;
-            const int unit = iu < wb ? iu : ub - 1;
+        // The lane's packed rows of the unit being loaded: the 64-bit address arithmetic runs once per unit, a load
+        // adds the chunk's offset (the vector unit is the scarce resource of the 1:4 form).
+        const uint8_t *prow[RT];
+        auto locate = [&](int unit) {
 #pragma unroll
             for (int a = 0; a < RT; ++a) {
                 int row = unit * 16 * RT + 16 * a + r;
                 row = row < it.d_out ? row : it.d_out - 1;
-                const uint8_t *p = it.packed + ((int64_t)row * nchunks + ch) * 32;
+                prow[a] = it.packed + (int64_t)row * nchunks * CB;
+            }
+        };
+        locate(wa < wb ? wa : ub - 1);
+        auto issue = [&](uint4(&ib)[RT], uint4(&cb)[RT]) {
+            int ch = 4 * is + c4;
+            ch = ch < nchunks ? ch : nchunks - 1;
+#pragma unroll
+            for (int a = 0; a < RT; ++a) {
+                const uint8_t *p = prow[a] + (uint32_t)ch * CB;
                 ib[a] = *reinterpret_cast<const uint4 *>(p);        // plain loads: nontemporal ones measured 30 % slower
-                cb[a] = *reinterpret_cast<const uint4 *>(p + 16);
+                if constexpr (ONE4) cb[a] = make_uint4(0, 0, 0, 0);
+                else cb[a] = *reinterpret_cast<const uint4 *>(p + 16);
             }
             if (++is == nsuper) {
                 is = 0;
@@ -545,6 +570,7 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
                 } else {
                     ++iu;
                 }
+                locate(iu < wb ? iu : ub - 1);
             }
         };
         // Activations are staged only when they differ from what the block already holds (projections
@@ -627,6 +653,7 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
                     for (int a = 0; a < RT; ++a) {
                         cc[a] = make_uint4(0, 0, 0, 0);
                         if constexpr (DENSE) ic[a] = make_uint4(0, 0, 0, 0);   // all eight words are codes
+                        if constexpr (ONE4) ic[a].z = ic[a].w = 0;             // the chunk's two code words
                     }
                 }
                 if constexpr (DENSE) {
@@ -641,16 +668,35 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
                         }
                     }
                 }
+                // sparse forms: the super-step's activations are asked for first, so that the LDS latency passes under
+                // the vector work that builds the A operands
+                v8i bq[DENSE ? 1 : 4];
 #pragma unroll
                 for (int j = 0; j < (DENSE ? 0 : 4); ++j) {
                     const uint4 blo = *reinterpret_cast<const uint4 *>(&xlds[xoff + cs * 512 + 32 * j]);
                     const uint4 bhi = *reinterpret_cast<const uint4 *>(&xlds[xoff + cs * 512 + 32 * j + 256]);
-                    const v8i b = {(int)blo.x, (int)blo.y, (int)blo.z, (int)blo.w, (int)bhi.x, (int)bhi.y, (int)bhi.z, (int)bhi.w};
+                    bq[j] = v8i{(int)blo.x, (int)blo.y, (int)blo.z, (int)blo.w, (int)bhi.x, (int)bhi.y, (int)bhi.z, (int)bhi.w};
+                }
+                uint32_t iw1[RT][2][2];
+                v4i a1[RT][2][2];
+                if constexpr (ONE4) {
 #pragma unroll
                     for (int a = 0; a < RT; ++a) {
+                        expand_1of4(ic[a].x, ic[a].z, ones, iw1[a][0], a1[a][0]);
+                        expand_1of4(ic[a].y, ic[a].w, ones, iw1[a][1], a1[a][1]);
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < (DENSE ? 0 : 4); ++j) {
+#pragma unroll
+                    for (int a = 0; a < RT; ++a) {
+                        if constexpr (ONE4) {
+                            acc[a] = __builtin_amdgcn_smfmac_i32_16x16x128_i8(a1[a][j >> 1][j & 1], bq[j], acc[a], (int)iw1[a][j >> 1][j & 1], 0, 0);
+                            continue;
+                        }
                         const uint32_t cw = j == 0 ? cc[a].x : j == 1 ? cc[a].y : j == 2 ? cc[a].z : cc[a].w;
                         const uint32_t iw = j == 0 ? ic[a].x : j == 1 ? ic[a].y : j == 2 ? ic[a].z : ic[a].w;
-                        acc[a] = __builtin_amdgcn_smfmac_i32_16x16x128_i8(expand_codes(cw, ones), b, acc[a], (int)iw, 0, 0);
+                        acc[a] = __builtin_amdgcn_smfmac_i32_16x16x128_i8(expand_codes(cw, ones), bq[j], acc[a], (int)iw, 0, 0);
                     }
                 }
                 if (++cs == nsuper) {
@@ -794,12 +840,17 @@ int device_cus()
     return cus;
 }
 
-template <bool DENSE>
+template <int FORM>
 static sbn_status launch_gemv_as(int count, const LinearItem *items, hipStream_t stream);
 
-sbn_status launch_gemv(int count, const LinearItem *items, bool dense_codes, hipStream_t stream)
+sbn_status launch_gemv(int count, const LinearItem *items, GemvForm form, hipStream_t stream)
 {
-    return dense_codes ? launch_gemv_as<true>(count, items, stream) : launch_gemv_as<false>(count, items, stream);
+    switch (form) {
+    case GEMV_2OF4: return launch_gemv_as<GEMV_2OF4>(count, items, stream);
+    case GEMV_DENSE: return launch_gemv_as<GEMV_DENSE>(count, items, stream);
+    case GEMV_1OF4: return launch_gemv_as<GEMV_1OF4>(count, items, stream);
+    }
+    return SBN_EINVAL;
 }
 
 // Launch number of the streaming kernel with the fused quantizer: it tags the per-token flags a launch raises in
@@ -818,7 +869,7 @@ static bool stream_is_capturing(hipStream_t stream)
     return status != hipStreamCaptureStatusNone;
 }
 
-template <bool DENSE>
+template <int FORM>
 static sbn_status launch_gemv_as(int count, const LinearItem *items, hipStream_t stream)
 {
     constexpr int RT = 1;
@@ -855,7 +906,8 @@ static sbn_status launch_gemv_as(int count, const LinearItem *items, hipStream_t
             // One row tile per unit, DEPTH 5 and 8 wavefronts per block measured best among one or two row tiles,
             // depths 2..8 and 6..16 wavefronts (more wavefronts finish their shares further apart, fewer leave too
             // few loads in flight; units of 16 rows balance the wavefronts better than units of 32: +2.5 to +4 %)
-                        constexpr int DEPTH = 5, NW = 8;
+            // (the 1:4 form has half the bytes per super-step: twice the depth keeps the same bytes in flight)
+            constexpr int DEPTH = FORM == GEMV_1OF4 ? 10 : 5, NW = 8;
             GemvStreamTable tab;
             tab.count = n;
             tab.nin = 0;
@@ -912,12 +964,12 @@ static sbn_status launch_gemv_as(int count, const LinearItem *items, hipStream_t
             tab.spin_limit = gemv_spin_limit();
             static thread_local bool raised = false;
             if (!raised) {
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemv_stream_kernel<RT, DEPTH, NW, DENSE>),
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemv_stream_kernel<RT, DEPTH, NW, FORM>),
                                                    hipFuncAttributeMaxDynamicSharedMemorySize, GEMV_STREAM_LDS);
                 if (e != hipSuccess) { set_hip_error(e, "hipFuncSetAttribute"); return SBN_EHIP; }
                 raised = true;
             }
-            hipLaunchKernelGGL((gemv_stream_kernel<RT, DEPTH, NW, DENSE>), dim3(nblocks), dim3(64 * NW), (size_t)lds_need, stream, tab);
+            hipLaunchKernelGGL((gemv_stream_kernel<RT, DEPTH, NW, FORM>), dim3(nblocks), dim3(64 * NW), (size_t)lds_need, stream, tab);
             sbn_status st = check_launch("gemv_stream_kernel");
             if (st != SBN_OK) return st;
             first += n;
@@ -962,13 +1014,13 @@ static sbn_status launch_gemv_as(int count, const LinearItem *items, hipStream_t
         if (dyn_lds > 0) {
             static thread_local bool raised_single = false;
             if (!raised_single) {
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemv_smfmac_kernel<DENSE>),
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemv_smfmac_kernel<FORM>),
                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)GEMV_SELF_QUANT_LDS);
                 if (e != hipSuccess) { set_hip_error(e, "hipFuncSetAttribute"); return SBN_EHIP; }
                 raised_single = true;
             }
         }
-        hipLaunchKernelGGL(gemv_smfmac_kernel<DENSE>, dim3(blocks, n), dim3(64 * nwaves), (size_t)dyn_lds, stream, tab);
+        hipLaunchKernelGGL(gemv_smfmac_kernel<FORM>, dim3(blocks, n), dim3(64 * nwaves), (size_t)dyn_lds, stream, tab);
         sbn_status st = check_launch("gemv_smfmac_kernel");
         if (st != SBN_OK) return st;
         first += n;

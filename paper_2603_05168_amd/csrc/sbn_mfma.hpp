@@ -74,6 +74,53 @@ __device__ __forceinline__ void expand_dense_codes(uint32_t w0, uint32_t w1, v4i
     }
 }
 
+// One index word and one code word of the 1:4 packed form (16 slots = 64 consecutive weights: slot s keeps position
+// bits [2s, 2s+2) of `iw14` in its group of four and has its code at bits [8(s%4) + 2(s/4), +2) of `cw14`) -> the
+// operands of two sparse matrix instructions (32 weights each), built in registers.  A group with one kept weight
+// at position p becomes the 2:4 group that keeps the aligned pair holding p - positions (0, 1) or (2, 3), index
+// nibble 0x4 or 0xe - with the code in slot p & 1 and code 0 in the other slot, so positions stay ascending.
+//   index:  bit 1 of every position selects the nibble (a byte-wise table lookup on pairs of groups);
+//   codes:  a mask of the odd positions in the code word's own layout (one 24-bit multiply per byte of positions
+//           moves bit 2b of the byte to bit 8b) splits the code word into the codes bound for slot 0 and those
+//           bound for slot 1; two byte permutes interleave the two words byte by byte into the order of the
+//           instruction's A registers, and the table lookups of expand_codes finish the job.
+// About 25 vector operations per instruction against 9 for the 2:4 form.
+__device__ __forceinline__ void expand_1of4(uint32_t iw14, uint32_t cw14, uint32_t ones, uint32_t (&iw)[2], v4i (&a)[2])
+{
+    const uint32_t lut = 0xff000100u;
+    const uint32_t odd = iw14 & 0x55555555u;
+    // (the multiply is written out: left to itself the compiler folds the later shift into the constant, which then
+    // no longer fits 24 bits and costs a full-width multiply at a quarter of the rate)
+    uint32_t e1 = 0;
+#pragma unroll
+    for (int f = 0; f < 4; ++f) {
+        uint32_t m;
+        asm("v_mul_u32_u24 %0, %1, %2" : "=v"(m) : "s"(0x41041u), "v"((odd >> (8 * f)) & 0x55u));
+        e1 |= (m & 0x01010101u) << (2 * f);
+    }
+    const uint32_t c_odd = cw14 & (e1 | (e1 << 1)), c_even = cw14 ^ c_odd;
+    // bytes: (slot-0 codes of groups b, slot-1 codes of groups b) for b = 0, 1 and for b = 2, 3
+    const uint32_t y0 = __builtin_amdgcn_perm(c_odd, c_even, 0x05010400u), y1 = __builtin_amdgcn_perm(c_odd, c_even, 0x07030602u);
+    const uint32_t hi = (iw14 >> 1) & 0x55555555u;   // a nibble = bit 1 of two positions, at its bits 0 and 2
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        // the four nibbles of this half go to the low halves of four bytes; as selector bytes (0, 1, 4 or 5) they look
+        // up the two index nibbles of their groups: 0x4 for the pair (0, 1), 0xe for (2, 3)
+        uint32_t x = q ? hi >> 16 : hi & 0xffffu;
+        x = (x | (x << 8)) & 0x00ff00ffu;
+        x = (x | (x << 4)) & 0x0f0f0f0fu;
+        iw[q] = __builtin_amdgcn_perm(0x0000eee4u, 0x00004e44u, x);
+        const uint32_t z0 = q ? y0 >> 4 : y0, z1 = q ? y1 >> 4 : y1;
+        uint32_t s2, s3;
+        asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(s2) : "v"(z0), "s"(0x0c0c0c0cu), "v"(ones));
+        asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(s3) : "v"(z1), "s"(0x0c0c0c0cu), "v"(ones));
+        a[q][0] = (int)__builtin_amdgcn_perm(lut, lut, z0 & 0x03030303u);
+        a[q][1] = (int)__builtin_amdgcn_perm(lut, lut, z1 & 0x03030303u);
+        a[q][2] = (int)__builtin_amdgcn_perm(0x00000100u, 0u, s2);
+        a[q][3] = (int)__builtin_amdgcn_perm(0x00000100u, 0u, s3);
+    }
+}
+
 // One LDS-DMA load: lane l of the wavefront fetches 16 bytes at base + voff and the hardware
 // deposits them at LDS byte address lds_addr + 16*l (M0 carries the LDS address).  Written as
 // inline assembly on purpose: after the compiler's own LDS-DMA builtin every later LDS read is

@@ -194,6 +194,62 @@ def test_decode_sizes_other_patterns_through_path_selection(N, M, tokens):
     check_forward(W, X, N, M, s.SBN_PATH_GEMV)
 
 
+@pytest.mark.parametrize("tokens,shape", [(1, (48, 128)), (5, (100, 640)), (16, (250, 1792)), (8, (33, 2560)), (3, (16, 256))])
+def test_decode_1of4_as_stored_shapes(tokens, shape):
+    # the decode kernel reads the 1:4 packed form as stored (one bit per weight) and builds the sparse
+    # instruction's operands in registers: ragged row counts, a partial last super-step, bias
+    s = sbn()
+    W = sbn_synth.latent_weight(shape[0], shape[1], 1700 + shape[0])
+    X = sbn_synth.activations(tokens, shape[1], 1701 + tokens)
+    bias = torch.randn(shape[0], generator=torch.Generator().manual_seed(13))
+    check_forward(W, X, 1, 4, s.SBN_PATH_GEMV, bias=bias)
+
+
+def test_decode_1of4_as_stored_adversarial_and_full_size():
+    # ties inside groups, signed zeros, extreme magnitudes; then one kept position for the whole matrix (each of
+    # the four in turn: both aligned pairs and both slots of the rewrite); then the decode shapes of configs[1]
+    s = sbn()
+    W = sbn_synth.adversarial_weight(64, 512, 1710)
+    X = sbn_synth.adversarial_activations(8, 512, 1711)
+    check_forward(W, X, 1, 4, s.SBN_PATH_GEMV)
+    base = sbn_synth.latent_weight(48, 1024, 1712)
+    for pos in range(4):
+        W = base * 1e-3
+        W[:, pos::4] = base[:, pos::4] + torch.sign(base[:, pos::4])   # the largest of every group by a wide margin
+        _, _, _, mask = oracle_pack(W, 1, 4)
+        assert mask.reshape(-1, 4)[:, pos].all()
+        check_forward(W, sbn_synth.activations(5, 1024, 1713 + pos), 1, 4, s.SBN_PATH_GEMV)
+    for shape, tokens in (((6912, 2560), 8), ((2560, 6912), 1)):
+        W = sbn_synth.latent_weight(shape[0], shape[1], sbn_synth.seed_for(2, 14 + shape[0]))
+        X = sbn_synth.activations(tokens, shape[1], sbn_synth.seed_for(2, 114 + tokens))
+        check_forward(W, X, 1, 4, s.SBN_PATH_AUTO)
+
+
+@pytest.mark.parametrize("tokens", [1, 8, 16])
+def test_grouped_streaming_1of4_against_oracle(tokens):
+    # 1:4 in one grouped call: the persistent streaming kernel on the packed form as stored (ragged row counts,
+    # a partial last super-step at K = 768 and 640, three inputs quantized by the kernel)
+    s = sbn()
+    shapes = [(4100, 768), (4096, 256), (5000, 640)] * 14
+    Ws = {sh: sbn_synth.latent_weight(sh[0], sh[1], 1750 + sh[0]) for sh in set(shapes)}
+    packs = {sh: hip_pack(W, 1, 4) for sh, W in Ws.items()}
+    Xs = {k: sbn_synth.activations(tokens, k, 1760 + k) for k in (768, 256, 640)}
+    Xd = {k: x.to(DEV) for k, x in Xs.items()}
+    Y_list = [torch.full((tokens, a), float("nan"), dtype=torch.float32, device=DEV) for a, _ in shapes]
+    need = sum(s.sbn_workspace_bytes(s.SBN_OP_LINEAR, tokens, a, b, 1, 4) for a, b in shapes)
+    ws = s.new_workspace(need)
+    s.sbn_sparse_ternary_linear_grouped([Xd[b] for _, b in shapes], [packs[sh][0] for sh in shapes],
+                                        [packs[sh][1] for sh in shapes], Y_list, 1, 4, ws, path=s.SBN_PATH_GEMV)
+    torch.cuda.synchronize()
+    ref = {}
+    for sh, W in Ws.items():
+        _, g, Weff, _ = oracle_pack(W, 1, 4)
+        y, *_ = oracle.sparse_ternary_linear(Xs[sh[1]].float().numpy(), Weff, g)
+        ref[sh] = y
+    for i, sh in enumerate(shapes):
+        assert_rel(Y_list[i].cpu().numpy(), ref[sh], Y_TOL, f"Y of problem {i}")
+
+
 @pytest.mark.parametrize("N,M", [(6, 8), (3, 8), (7, 8), (5, 8), (4, 8), (3, 4), (8, 8), (4, 4), (2, 2)])
 @pytest.mark.parametrize("tokens,shape", [(1, (48, 128)), (5, (100, 640)), (16, (250, 1792)), (8, (33, 2560))])
 def test_decode_dense_codes_shapes(N, M, tokens, shape):
@@ -477,26 +533,27 @@ def test_grouped_sparse_gemm_against_oracle():
         assert_rel(Y_list[i].cpu().numpy(), y, Y_TOL, f"Y of problem {i}")
 
 
+@pytest.mark.parametrize("N,M", [(2, 4), (1, 4)])
 @pytest.mark.parametrize("tokens,shape", [(8, (6912, 2560)), (1, (2560, 6912))])
-def test_config2_streaming_decode_full_size_as_timed(tokens, shape):
+def test_config2_streaming_decode_full_size_as_timed(tokens, shape, N, M):
     # the launch configuration the benchmark times for decode: independently seeded copies of a full-size
     # matrix in one grouped call on the persistent streaming kernel (20 copies: enough rows to select it),
-    # every output of every copy against the oracle
+    # every output of every copy against the oracle; 2:4 and the 1:4 form the kernel reads as stored
     s = sbn()
     a, b = shape
     R = 20
     Ws = [sbn_synth.latent_weight(a, b, sbn_synth.seed_for(2, 100 * r + a % 7)) for r in range(R)]
-    packs = [hip_pack(W, 2, 4) for W in Ws]
+    packs = [hip_pack(W, N, M) for W in Ws]
     X = sbn_synth.activations(tokens, b, sbn_synth.seed_for(2, tokens))
     Xd = X.to(DEV)
     Ys = [torch.full((tokens, a), float("nan"), dtype=torch.float32, device=DEV) for _ in range(R)]
-    ws = s.new_workspace(R * s.sbn_workspace_bytes(s.SBN_OP_LINEAR, tokens, a, b, 2, 4))
-    s.sbn_sparse_ternary_linear_grouped([Xd] * R, [p for p, _ in packs], [g for _, g in packs], Ys, 2, 4, ws,
+    ws = s.new_workspace(R * s.sbn_workspace_bytes(s.SBN_OP_LINEAR, tokens, a, b, N, M))
+    s.sbn_sparse_ternary_linear_grouped([Xd] * R, [p for p, _ in packs], [g for _, g in packs], Ys, N, M, ws,
                                         path=s.SBN_PATH_GEMV)
     torch.cuda.synchronize()
     Xf = X.float().numpy()
     for r in range(R):
-        _, g, Weff, _ = oracle_pack(Ws[r], 2, 4)
+        _, g, Weff, _ = oracle_pack(Ws[r], N, M)
         y, *_ = oracle.sparse_ternary_linear(Xf, Weff, g)
         assert_rel(Ys[r].cpu().numpy(), y, Y_TOL, f"Y of copy {r}")
 

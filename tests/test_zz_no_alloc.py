@@ -81,3 +81,11 @@ def test_static_scratch_entry_limits_and_refusals():
     torch.cuda.synchronize()
     Y1, *_ = hip_linear(X.cpu(), packed, gamma, 64, 2, 4, s.SBN_PATH_AUTO, want_acc=False)
     assert np.array_equal(Y.cpu().numpy(), Y1)
+    # 1:4 at a decode size: the kernel reads that packed form as stored, so it needs no expansion region either
+    p14, g14 = hip_pack(W, 1, 4)
+    X = sbn_synth.activations(8, 128, 3023).to(DEV)
+    Y = torch.zeros(8, 64, dtype=torch.float32, device=DEV)
+    s.sbn_sparse_ternary_linear_static(X, p14, g14, Y, 1, 4)
+    torch.cuda.synchronize()
+    Y1, *_ = hip_linear(X.cpu(), p14, g14, 64, 1, 4, s.SBN_PATH_AUTO, want_acc=False)
+    assert np.array_equal(Y.cpu().numpy(), Y1)
