@@ -441,7 +441,16 @@ def main():
                                      "frac_hbm": bytes_alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
             log(f"[pack] {n}:{m} sweep of {len(Wl)} matrices: {ms:.3f} ms, {pack_rows[f'{n}:{m}']['gbps']:.0f} GB/s "
                 f"on single-read bytes")
-            del pl, batch
+            # the same sweep in place over the previous packed forms, counting every matrix's mask flips on the way
+            # (it also reads the old index fields: N * log2(M) / (8 M) bytes per weight more)
+            fl = torch.zeros(len(Wl), dtype=torch.int64, device=dev)
+            batch_f = sbn.PackBatch(Wl, n, m, pl, glist, wsp, fl)
+            ms_f = timed(batch_f.run, 5, 1)
+            idx_bytes = sum(p.numel() for p in pl) * {4: 2, 8: 3}[m] // ({4: 2, 8: 3}[m] + 2)
+            pack_rows[f"{n}:{m}"].update({"with_flip_counts_ms": ms_f, "with_flip_counts_gbps": (bytes_alg + idx_bytes) / (ms_f * 1e-3) / 1e9,
+                                          "flip_count_extra_ms": ms_f - ms})
+            log(f"[pack] {n}:{m} sweep in place with flip counts: {ms_f:.3f} ms (+{(ms_f / ms - 1) * 100:.1f} %)")
+            del pl, batch, batch_f
         rows["quantize_mask_pack"] = pack_rows
         # mask flips between two packed forms of the largest matrix (ablation study, mask flip rate equation)
         pa = pack_one(Wl[4])
@@ -451,7 +460,7 @@ def main():
         ms = timed(lambda: sbn.sbn_mask_flips(pa[0], pb[0], F, H, N, M, flips, wsf), 100, 3)
         rows["mask_flips_6912x2560"] = {"us": ms * 1e3, "flip_rate": flips.item() / (F * H),
                                         "gbps_index_bytes": 2 * (F * H // 8) / (ms * 1e-3) / 1e9}
-        log(f"[flips] 6912x2560 2:4: {ms * 1e3:.1f} us, flip rate {flips.item() / (F * H):.4f}")
+        log(f"[flips] 6912x2560 2:4, separate pass over two packed forms: {ms * 1e3:.1f} us, flip rate {flips.item() / (F * H):.4f}")
         del Wl
         torch.cuda.empty_cache()
 

@@ -240,6 +240,26 @@ sbn_status sbn_sparse_ternary_linear_backward_grouped(int count, const void *con
                                                       void *const *dX, void *const *dW, int flags,
                                                       void *workspace, size_t ws_bytes, void *stream);
 
+/*
+ * The per-step remask with the mask flip count as a by-product (Section 2.3: the mask is recomputed every step;
+ * ablation study, mask flip rate equation): sbn_quantize_mask_pack_batched IN PLACE over the previous step's packed
+ * forms.  On entry packed[i] holds the packed form an earlier call wrote for a matrix of the same shape at the same
+ * N:M; on return it holds the new one (bytes and gamma exactly as sbn_quantize_mask_pack_batched writes them) and
+ *   flips_out[i] = || m(W_t) - m(W_{t-1}) ||_1  of matrix i   (as sbn_mask_flips counts it; the caller divides).
+ * The kernel that packs a block of weights compares its new index words with the old ones it is about to replace: no
+ * second pass over the packed forms.
+ *   flips_out  device, `count` uint64, overwritten (integer sums in a fixed order)
+ *   supported  bf16 weights, rows contiguous (ld_w = d_in), d_in % 128 == 0, 16-byte aligned, N:M = 2:4, 1:4 or 2:8;
+ *              anything else SBN_EUNSUPPORTED (pack, then sbn_mask_flips on two buffers).  If packed[i] does not
+ *              hold a valid packed form on entry the new form is still written correctly and flips_out[i] is
+ *              meaningless.
+ * Everything else as sbn_quantize_mask_pack_batched.
+ */
+sbn_status sbn_quantize_mask_pack_flips_batched(int count, const void *const *W_latent, sbn_dtype wdt,
+                                                const int64_t *d_out, const int64_t *d_in, int N, int M,
+                                                void *const *packed, float *const *gamma, uint64_t *flips_out,
+                                                void *workspace, size_t ws_bytes, void *stream);
+
 /* Test hook, not timed: expands `packed` to dense W_eff (int8 [d_out, d_in]) and the 0/1 mask
  * (uint8 [d_out, d_in]); either output may be NULL. */
 sbn_status sbn_unpack(const void *packed, int64_t d_out, int64_t d_in, int N, int M,

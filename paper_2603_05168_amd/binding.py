@@ -47,6 +47,8 @@ def _load():
     lib.sbn_quantize_mask_pack.argtypes = [vp, cint, i64, i64, i64, cint, cint, vp, vp, vp, sz, vp]
     lib.sbn_quantize_mask_pack_batched.restype = cint
     lib.sbn_quantize_mask_pack_batched.argtypes = [cint, pp, cint, pi64, pi64, cint, cint, pp, pp, vp, sz, vp]
+    lib.sbn_quantize_mask_pack_flips_batched.restype = cint
+    lib.sbn_quantize_mask_pack_flips_batched.argtypes = [cint, pp, cint, pi64, pi64, cint, cint, pp, pp, vp, vp, sz, vp]
     lib.sbn_act_quant.restype = cint
     lib.sbn_act_quant.argtypes = [vp, i64, i64, vp, vp, vp]
     lib.sbn_sparse_ternary_linear.restype = cint
@@ -150,7 +152,8 @@ def _i64_array(values):
 class PackBatch:
     """Host-side argument arrays of sbn_quantize_mask_pack_batched, marshalled once and reusable."""
 
-    def __init__(self, W_list, N, M, packed_list, gamma_list, workspace):
+    def __init__(self, W_list, N, M, packed_list, gamma_list, workspace, flips_out=None):
+        self.flips_out = flips_out   # int64 device tensor of len(W_list): pack in place over the old forms and count flips
         self.count = len(W_list)
         self.dtype = _dtype_code(W_list[0])
         self.W = _ptr_array(W_list)
@@ -164,6 +167,12 @@ class PackBatch:
 
     def run(self):
         ws = self.workspace
+        if self.flips_out is not None:
+            _check(_lib.sbn_quantize_mask_pack_flips_batched(self.count, self.W, self.dtype, self.d_out, self.d_in, self.N,
+                                                             self.M, self.packed, self.gamma, _ptr(self.flips_out), _ptr(ws),
+                                                             ws.numel() * ws.element_size(), _stream()),
+                   "sbn_quantize_mask_pack_flips_batched")
+            return
         _check(_lib.sbn_quantize_mask_pack_batched(self.count, self.W, self.dtype, self.d_out, self.d_in, self.N,
                                                    self.M, self.packed, self.gamma, _ptr(ws),
                                                    ws.numel() * ws.element_size(), _stream()),
@@ -172,6 +181,11 @@ class PackBatch:
 
 def sbn_quantize_mask_pack_batched(W_list, N: int, M: int, packed_list, gamma_list, workspace):
     PackBatch(W_list, N, M, packed_list, gamma_list, workspace).run()
+
+
+def sbn_quantize_mask_pack_flips_batched(W_list, N: int, M: int, packed_list, gamma_list, flips_out, workspace):
+    """Packs in place over the previous packed forms; flips_out (int64 device tensor, one per matrix) gets the mask flips."""
+    PackBatch(W_list, N, M, packed_list, gamma_list, workspace, flips_out).run()
 
 
 def sbn_act_quant(X, xq, sx):

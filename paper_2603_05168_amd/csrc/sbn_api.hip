@@ -130,6 +130,29 @@ sbn_status sbn_quantize_mask_pack_batched(int count, const void *const *W_latent
     return launch_pack(count, tl_items.data(), wdt, pat, workspace, ws_bytes, static_cast<hipStream_t>(stream));
 }
 
+sbn_status sbn_quantize_mask_pack_flips_batched(int count, const void *const *W_latent, sbn_dtype wdt, const int64_t *d_out,
+                                                const int64_t *d_in, int N, int M, void *const *packed,
+                                                float *const *gamma, uint64_t *flips_out, void *workspace, size_t ws_bytes,
+                                                void *stream)
+{
+    if (count <= 0 || count > 4096 || !W_latent || !d_out || !d_in || !packed || !gamma || !flips_out || !workspace) return SBN_EINVAL;
+    if (wdt != SBN_F32 && wdt != SBN_BF16) return SBN_EINVAL;
+    if (!aligned(workspace, 256) || !aligned(flips_out, 8)) return SBN_EALIGN;
+    Pattern pat;
+    static thread_local std::vector<PackItem> tl_items;   // host-side descriptor list, reused between calls
+    tl_items.resize(count);
+    for (int i = 0; i < count; ++i) {
+        if (!W_latent[i] || !packed[i] || !gamma[i]) return SBN_EINVAL;
+        sbn_status st = check_shape(d_out[i], d_in[i], N, M, pat);
+        if (st != SBN_OK) return st;
+        if (!aligned(packed[i], 16) || !aligned(gamma[i], 4)) return SBN_EALIGN;
+        if (!aligned(W_latent[i], 2)) return SBN_EALIGN;
+        tl_items[i] = PackItem{W_latent[i], static_cast<uint8_t *>(packed[i]), gamma[i], d_out[i], d_in[i], d_in[i]};
+    }
+    return launch_pack(count, tl_items.data(), wdt, pat, workspace, ws_bytes, static_cast<hipStream_t>(stream),
+                       reinterpret_cast<unsigned long long *>(flips_out));
+}
+
 sbn_status sbn_unpack(const void *packed, int64_t d_out, int64_t d_in, int N, int M, int8_t *W_eff, uint8_t *mask,
                       void *stream)
 {

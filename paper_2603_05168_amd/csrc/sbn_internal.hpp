@@ -53,7 +53,7 @@ constexpr int PACK_MAX_ITEMS = 70;     // matrices per launch (descriptor table 
 constexpr int64_t PACK_SUM_ELEMS = 16384;  // elements reduced by one block of the absmean pass
 size_t pack_workspace_bytes(int64_t count, int64_t d_out, int64_t d_in);
 sbn_status launch_pack(int count, const PackItem *items, sbn_dtype wdt, const Pattern &pat,
-                       void *workspace, size_t ws_bytes, hipStream_t stream);
+                       void *workspace, size_t ws_bytes, hipStream_t stream, unsigned long long *flips = nullptr);
 size_t mask_flips_workspace_bytes(int64_t d_out, int64_t d_in, int M);
 sbn_status launch_mask_flips(const void *packed_a, const void *packed_b, int64_t d_out, int64_t d_in, const Pattern &pat,
                              uint64_t *flips_out, void *workspace, hipStream_t stream);

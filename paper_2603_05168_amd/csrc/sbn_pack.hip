@@ -391,6 +391,7 @@ struct PackSync {
     float *theta;         // one per matrix
     unsigned *words;      // PACK_SYNC_WORDS per matrix, cleared before the launch (the partials are preset with them)
     int spin_limit;       // polls a block spends waiting for its ready word before it derives theta on its own
+    uint32_t *unit_flips;  // when the launch counts mask flips: one slot per unit of the launch (every slot is written), else null
 };
 static_assert(sizeof(PackTable) + sizeof(PackSync) <= 4096, "both travel as kernel arguments");
 
@@ -471,17 +472,69 @@ __device__ __forceinline__ void select_unit(const uint4 (&v)[PACK_U], PackCompac
     }
 }
 
+// Mask flips between the index fields of a new and an old packed form (mask flip rate equation of the ablation
+// study): positions kept by exactly one of the two.  Both forms keep N positions per group, so a group flips
+// 2 * (N - common) positions; the common ones are found by comparing the position fields, all groups of a word at once.
+// 2:4, one index word = eight groups (nibble = pos0 | pos1 << 2, pos0 < pos1)
+__device__ __forceinline__ uint32_t flips_2of4_word(uint32_t n, uint32_t o)
+{
+    const uint32_t x = n ^ o;
+    const uint32_t same = ~(x | (x >> 1)) & 0x55555555u;                        // pos0 = pos0', pos1 = pos1'
+    const uint32_t os = ((o & 0x33333333u) << 2) | ((o >> 2) & 0x33333333u);    // the old positions swapped
+    const uint32_t y = n ^ os;
+    const uint32_t cross = ~(y | (y >> 1)) & 0x55555555u;                       // pos0 = pos1', pos1 = pos0'
+    return 32u - 2u * (uint32_t)(__popc(same) + __popc(cross));
+}
+// 1:4, one index word = sixteen groups of one 2-bit position
+__device__ __forceinline__ uint32_t flips_1of4_word(uint32_t n, uint32_t o)
+{
+    const uint32_t x = n ^ o;
+    return 2u * (uint32_t)__popc((x | (x >> 1)) & 0x55555555u);
+}
+// 2:8, half an index field = 48 bits = eight groups of two 3-bit positions (pos0 < pos1)
+__device__ __forceinline__ uint32_t flips_2of8_half(uint64_t n, uint64_t o)
+{
+    constexpr uint64_t ONE = 0x249249249249ull;    // bit 0 of every 3-bit field
+    constexpr uint64_t EVEN = 0x1c71c71c71c7ull;   // the first field of every group
+    const uint64_t x = n ^ o;
+    const uint64_t same = ~(x | (x >> 1) | (x >> 2)) & ONE;
+    const uint64_t os = ((o & EVEN) << 3) | ((o >> 3) & EVEN);
+    const uint64_t y = n ^ os;
+    const uint64_t cross = ~(y | (y >> 1) | (y >> 2)) & ONE;
+    return 32u - 2u * (uint32_t)(__popcll(same) + __popcll(cross));
+}
+
 // Codes of the compact unit with threshold th_val, fields assembled, and its 128 chunks (contiguous in the
 // packed buffer) stored.  lds: PACK_U * 16 * CBW words of staging; ends with the block's stores issued, LDS
 // free after the next barrier.
-template <int N, int M>
-__device__ __forceinline__ void finish_unit(const PackItem &it, const int64_t lb, const PackCompact<N, M> &c, const float th_val,
-                                            uint32_t *lds)
+// FLIPS: the packed buffer still holds the matrix's previous packed form, which the unit replaces; the return value
+// is the number of mask positions that differ between the two in this thread's share of the unit (thread t: half
+// t % 2 of the index field of chunk t / 2).  The old index words are asked for first and have arrived before the
+// barrier behind which the block's stores begin: no thread overwrites a word another thread has yet to read.
+template <int N, int M, bool FLIPS>
+__device__ __forceinline__ uint32_t finish_unit(const PackItem &it, const int64_t lb, const PackCompact<N, M> &c, const float th_val,
+                                                uint32_t *lds)
 {
     constexpr int U = PACK_U;
     constexpr int CBW = (M == 4 && N == 2) ? 8 : (M == 4 ? 4 : 5);   // dwords per chunk: 32, 16, 20 bytes
     const int64_t total_chunks = it.d_out * (it.d_in / CHUNK);
     const int tid = threadIdx.x, ql = tid >> 4, l16 = tid & 15;
+    // the block's chunks are contiguous in the packed buffer
+    const int64_t chunk0 = lb * U * 16;
+    int64_t nch = total_chunks - chunk0;
+    nch = nch > U * 16 ? U * 16 : nch;
+    uint32_t *dst = reinterpret_cast<uint32_t *>(it.packed) + chunk0 * CBW;
+    // index words of the old form: two words per thread (one at 1:4)
+    constexpr int FW0 = (M == 4 && N == 2) ? 2 : 1;   // first word of half h is FW0 * h
+    const bool fl_on = FLIPS && (tid >> 1) < nch;
+    uint32_t old0 = 0, old1 = 0;
+    if constexpr (FLIPS) {
+        if (fl_on) {
+            const uint32_t *po = dst + (tid >> 1) * CBW + FW0 * (tid & 1);
+            old0 = po[0];
+            if constexpr (!(M == 4 && N == 1)) old1 = po[1];
+        }
+    }
     // smallest bf16 magnitude pattern whose value is >= theta (at least 1: theta > 0), minus one, in both halves
     const uint32_t thm1x2 = (((__float_as_uint(th_val) + 0xffffu) >> 16) - 1u) * 0x10001u;
 #pragma unroll
@@ -521,13 +574,25 @@ __device__ __forceinline__ void finish_unit(const PackItem &it, const int64_t lb
             }
         }
     }
+    if constexpr (FLIPS) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the old words are in registers: see above
     __syncthreads();
-    // the block's chunks are contiguous in the packed buffer
-    const int64_t chunk0 = lb * U * 16;
-    int64_t nch = total_chunks - chunk0;
-    nch = nch > U * 16 ? U * 16 : nch;
+    uint32_t flips = 0;
+    if constexpr (FLIPS) {
+        if (fl_on) {
+            const uint32_t *pn = lds + (tid >> 1) * CBW + FW0 * (tid & 1);
+            if constexpr (M == 4 && N == 2) {
+                flips = flips_2of4_word(pn[0], old0) + flips_2of4_word(pn[1], old1);
+            } else if constexpr (M == 4) {
+                flips = flips_1of4_word(pn[0], old0);
+            } else {
+                const bool up = tid & 1;   // bits [48, 96) of the field: the upper half of word 1 and word 2
+                const uint64_t n48 = up ? (uint64_t)(pn[0] >> 16) | ((uint64_t)pn[1] << 16) : (uint64_t)pn[0] | ((uint64_t)(pn[1] & 0xffffu) << 32);
+                const uint64_t o48 = up ? (uint64_t)(old0 >> 16) | ((uint64_t)old1 << 16) : (uint64_t)old0 | ((uint64_t)(old1 & 0xffffu) << 32);
+                flips = flips_2of8_half(n48, o48);
+            }
+        }
+    }
     const int ndw = (int)nch * CBW;
-    uint32_t *dst = reinterpret_cast<uint32_t *>(it.packed) + chunk0 * CBW;
     for (int w = tid * 4; w < ndw; w += 1024) {
         if (w + 4 <= ndw) {
             *reinterpret_cast<uint4 *>(dst + w) = *reinterpret_cast<const uint4 *>(lds + w);
@@ -535,14 +600,50 @@ __device__ __forceinline__ void finish_unit(const PackItem &it, const int64_t lb
             for (int k = w; k < ndw; ++k) dst[k] = lds[k];
         }
     }
+    return flips;
+}
+
+// A unit's flip count goes to the unit's slot in the workspace (wavefront sums through LDS, one plain store), and a
+// small kernel behind the pack kernel adds up the slots of every matrix in a fixed order.  One atomic per unit on a
+// counter per matrix was tried first: the 145 000 atomics of the 210-matrix sweep queue up at the one L2 channel that
+// holds the counters (about 6 ns each) and the sweep took 2.1 ms instead of 1.25.
+// flips_wave_sum is called by all threads before the barrier that follows finish_unit, flips_commit after it;
+// wave_flips is rewritten only behind the next unit's barriers.
+__device__ __forceinline__ void flips_wave_sum(uint32_t flips, uint32_t *wave_flips)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) flips += (uint32_t)__shfl_xor((int)flips, o, 64);
+    if ((threadIdx.x & 63) == 0) wave_flips[threadIdx.x >> 6] = flips;
+}
+__device__ __forceinline__ void flips_commit(const uint32_t *wave_flips, uint32_t *slot)
+{
+    if (threadIdx.x == 0) *slot = wave_flips[0] + wave_flips[1] + wave_flips[2] + wave_flips[3];
+}
+
+// one block per matrix: the flip counts of its units added up
+__global__ void __launch_bounds__(256) pack_flips_sum_kernel(PackTable tab, const uint32_t *__restrict__ unit_flips,
+                                                             unsigned long long *__restrict__ flips)
+{
+    __shared__ unsigned long long sums[256];
+    const int lo = blockIdx.x;
+    unsigned long long acc = 0;
+    for (int g = tab.pack_block0[lo] + (int)threadIdx.x; g < tab.pack_block0[lo + 1]; g += 256) acc += unit_flips[g];
+    sums[threadIdx.x] = acc;
+    __syncthreads();
+    for (int step = 128; step > 0; step >>= 1) {
+        if ((int)threadIdx.x < step) sums[threadIdx.x] += sums[threadIdx.x + step];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) flips[lo] = sums[0];
 }
 
 // third kernel of the three-pass form: theta comes from the finalize kernel
-template <int N, int M>
-__global__ void __launch_bounds__(256) pack_fast_kernel(PackTable tab, const float *theta)
+template <int N, int M, bool FLIPS>
+__global__ void __launch_bounds__(256) pack_fast_kernel(PackTable tab, const float *theta, uint32_t *unit_flips)
 {
     constexpr int CBW = (M == 4 && N == 2) ? 8 : (M == 4 ? 4 : 5);
     __shared__ __attribute__((aligned(16))) uint32_t lds[PACK_U * 16 * CBW];
+    __shared__ uint32_t wave_flips[4];
     const int lo = find_item(tab.pack_block0, tab.count, blockIdx.x);
     const PackItem &it = tab.it[lo];
     const int64_t lb = (int)blockIdx.x - tab.pack_block0[lo];
@@ -550,7 +651,12 @@ __global__ void __launch_bounds__(256) pack_fast_kernel(PackTable tab, const flo
     load_unit(it, lb, v);
     PackCompact<N, M> c;
     select_unit<N, M>(v, c);
-    finish_unit<N, M>(it, lb, c, theta[lo], lds);
+    const uint32_t fl = finish_unit<N, M, FLIPS>(it, lb, c, theta[lo], lds);
+    if constexpr (FLIPS) {
+        flips_wave_sum(fl, wave_flips);
+        __syncthreads();
+        flips_commit(wave_flips, unit_flips + blockIdx.x);
+    }
 }
 
 // ---- single-read form ---------------------------------------------------------------------------
@@ -574,11 +680,12 @@ __global__ void __launch_bounds__(256) pack_fast_kernel(PackTable tab, const flo
 // The wait is bounded all the same (the grid might
 // not be fully resident when the device is shared): a block out of polls recomputes every partial of
 // the matrix from HBM itself - same arithmetic, same order, same theta - and goes on.
-template <int N, int M, int QD, int WAVES>
+template <int N, int M, int QD, int WAVES, bool FLIPS>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WAVES, WAVES))) pack_stream_kernel(PackTable tab, PackSync sync)
 {
     constexpr int CBW = (M == 4 && N == 2) ? 8 : (M == 4 ? 4 : 5);
     __shared__ __attribute__((aligned(16))) uint32_t lds[PACK_U * 16 * CBW];
+    __shared__ uint32_t wave_flips[4];
     __shared__ double red[256];
     __shared__ int role_s;      // 2: waited in vain
     __shared__ float th_s;
@@ -735,8 +842,10 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WAVES,
             publish(un, raw);
         }
         const float th = theta_of(uq[0]);
-        finish_unit<N, M>(tab.it[uq[0].lo], uq[0].lb, q[0], th, lds);
+        const uint32_t fl = finish_unit<N, M, FLIPS>(tab.it[uq[0].lo], uq[0].lb, q[0], th, lds);
+        if constexpr (FLIPS) flips_wave_sum(fl, wave_flips);
         __syncthreads();   // the staging area is free for the next unit
+        if constexpr (FLIPS) flips_commit(wave_flips, sync.unit_flips + tab.pack_block0[uq[0].lo] + uq[0].lb);
 #pragma unroll
         for (int i = 0; i + 1 < QD; ++i)
             if (i + 1 < queued) {
@@ -989,8 +1098,9 @@ sbn_status launch_pack_kernel(const PackTable &tab, int nblocks, const float *th
 size_t pack_workspace_bytes(int64_t count, int64_t d_out, int64_t d_in)
 {
     const int64_t blocks = ceil_div(d_out * d_in, PACK_SUM_ELEMS);
+    // partial sums, thresholds, ready words, and the per-unit flip counts of the flip-counting call
     return align_up((size_t)count * (size_t)blocks * sizeof(double), 256) + align_up((size_t)count * sizeof(float), 256) +
-           align_up((size_t)count * PACK_SYNC_WORDS * sizeof(unsigned), 256);
+           align_up((size_t)count * PACK_SYNC_WORDS * sizeof(unsigned), 256) + align_up((size_t)count * (size_t)blocks * sizeof(uint32_t), 256);
 }
 
 __global__ void __launch_bounds__(256) pack_sync_clear_kernel(unsigned *words, int nwords, unsigned long long *partials, int npartials)
@@ -1012,8 +1122,19 @@ template <int N, int M> struct PackStreamShape {
 template <int N, int M>
 static void launch_pack_stream(int grid, hipStream_t stream, const PackTable &tab, const PackSync &sync)
 {
-    hipLaunchKernelGGL((pack_stream_kernel<N, M, PackStreamShape<N, M>::QD, PackStreamShape<N, M>::WAVES>), dim3(grid), dim3(256), 0,
-                       stream, tab, sync);
+    if (sync.unit_flips)
+        hipLaunchKernelGGL((pack_stream_kernel<N, M, PackStreamShape<N, M>::QD, PackStreamShape<N, M>::WAVES, true>), dim3(grid), dim3(256), 0,
+                           stream, tab, sync);
+    else
+        hipLaunchKernelGGL((pack_stream_kernel<N, M, PackStreamShape<N, M>::QD, PackStreamShape<N, M>::WAVES, false>), dim3(grid), dim3(256), 0,
+                           stream, tab, sync);
+}
+
+template <int N, int M>
+static void launch_pack_fast(int grid, hipStream_t stream, const PackTable &tab, const float *theta, uint32_t *unit_flips)
+{
+    if (unit_flips) hipLaunchKernelGGL((pack_fast_kernel<N, M, true>), dim3(grid), dim3(256), 0, stream, tab, theta, unit_flips);
+    else hipLaunchKernelGGL((pack_fast_kernel<N, M, false>), dim3(grid), dim3(256), 0, stream, tab, theta, unit_flips);
 }
 
 template <int N, int M>
@@ -1022,25 +1143,36 @@ static int fused_capacity()
     static thread_local int cap = 0;
     if (cap == 0) {
         int per_cu = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, pack_stream_kernel<N, M, PackStreamShape<N, M>::QD, PackStreamShape<N, M>::WAVES>, 256, 0) != hipSuccess) per_cu = 0;
+        // (the flip-counting instantiation has the same launch bounds, wavefronts per SIMD and LDS plus 16 bytes)
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, pack_stream_kernel<N, M, PackStreamShape<N, M>::QD, PackStreamShape<N, M>::WAVES, true>, 256, 0) != hipSuccess) per_cu = 0;
         cap = per_cu > 0 ? per_cu * device_cus() : -1;
     }
     return cap;
 }
 
+// flips: null, or one counter per matrix: the packed buffers then hold the previous packed forms, which are replaced, and
+// the counters receive the mask flips between the two (only in the forms that keep a unit's chunks in one block)
 sbn_status launch_pack(int count, const PackItem *items, sbn_dtype wdt, const Pattern &pat, void *workspace,
-                       size_t ws_bytes, hipStream_t stream)
+                       size_t ws_bytes, hipStream_t stream, unsigned long long *flips)
 {
+    if (flips) {
+        const bool fast_pattern = (pat.M == 4 && (pat.N == 1 || pat.N == 2)) || (pat.M == 8 && pat.N == 2);
+        if (wdt != SBN_BF16 || !fast_pattern) return SBN_EUNSUPPORTED;
+        for (int i = 0; i < count; ++i)
+            if (items[i].ld != items[i].d_in || items[i].d_in % CHUNK != 0 || !aligned(items[i].W, 16)) return SBN_EUNSUPPORTED;
+    }
     // workspace: [partials: one double per absmean block of every matrix][theta: one float per matrix]
     int64_t total_sum_blocks = 0;
     for (int i = 0; i < count; ++i) total_sum_blocks += ceil_div(items[i].d_out * items[i].d_in, PACK_SUM_ELEMS);
     // + [arrival counters and ready words of the single-read form: PACK_SYNC_WORDS per matrix]
     const size_t need = align_up((size_t)total_sum_blocks * sizeof(double), 256) + align_up((size_t)count * sizeof(float), 256) +
                         align_up((size_t)count * PACK_SYNC_WORDS * sizeof(unsigned), 256);
-    if (ws_bytes < need) return SBN_ESIZE;
+    // + [flip counts of the units of one launch, when flips are counted]
+    if (ws_bytes < need + (flips ? align_up((size_t)total_sum_blocks * sizeof(uint32_t), 256) : 0)) return SBN_ESIZE;
     double *partials = static_cast<double *>(workspace);
     float *theta = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + align_up((size_t)total_sum_blocks * sizeof(double), 256));
     unsigned *sync_words = reinterpret_cast<unsigned *>(reinterpret_cast<uint8_t *>(theta) + align_up((size_t)count * sizeof(float), 256));
+    uint32_t *unit_flips = flips ? reinterpret_cast<uint32_t *>(static_cast<uint8_t *>(workspace) + need) : nullptr;
 
     const size_t esz = wdt == SBN_BF16 ? 2 : 4;
     int64_t sum_base = 0;
@@ -1087,13 +1219,18 @@ sbn_status launch_pack(int count, const PackItem *items, sbn_dtype wdt, const Pa
                                reinterpret_cast<unsigned long long *>(part), sb);
             st = check_launch("pack_sync_clear_kernel");
             if (st != SBN_OK) return st;
-            PackSync sync{part, th, words, pack_spin_limit()};
+            PackSync sync{part, th, words, pack_spin_limit(), unit_flips};
             const int grid = fb[n] < cap ? fb[n] : cap;
             if (pat.M == 4 && pat.N == 2) launch_pack_stream<2, 4>(grid, stream, tab, sync);
             else if (pat.M == 4) launch_pack_stream<1, 4>(grid, stream, tab, sync);
             else launch_pack_stream<2, 8>(grid, stream, tab, sync);
             st = check_launch("pack_stream_kernel");
             if (st != SBN_OK) return st;
+            if (flips) {
+                hipLaunchKernelGGL(pack_flips_sum_kernel, dim3(n), dim3(256), 0, stream, tab, unit_flips, flips + first);
+                st = check_launch("pack_flips_sum_kernel");
+                if (st != SBN_OK) return st;
+            }
             sum_base += sb;
             continue;
         }
@@ -1109,10 +1246,14 @@ sbn_status launch_pack(int count, const PackItem *items, sbn_dtype wdt, const Pa
         if (fast) {
             for (int i = 0; i < n; ++i) tab.pack_block0[i] = fb[i];
             tab.pack_block0[n] = fb[n];
-            if (pat.M == 4 && pat.N == 2) hipLaunchKernelGGL((pack_fast_kernel<2, 4>), dim3(fb[n]), dim3(256), 0, stream, tab, th);
-            else if (pat.M == 4) hipLaunchKernelGGL((pack_fast_kernel<1, 4>), dim3(fb[n]), dim3(256), 0, stream, tab, th);
-            else hipLaunchKernelGGL((pack_fast_kernel<2, 8>), dim3(fb[n]), dim3(256), 0, stream, tab, th);
+            if (pat.M == 4 && pat.N == 2) launch_pack_fast<2, 4>(fb[n], stream, tab, th, unit_flips);
+            else if (pat.M == 4) launch_pack_fast<1, 4>(fb[n], stream, tab, th, unit_flips);
+            else launch_pack_fast<2, 8>(fb[n], stream, tab, th, unit_flips);
             st = check_launch("pack_fast_kernel");
+            if (st == SBN_OK && flips) {
+                hipLaunchKernelGGL(pack_flips_sum_kernel, dim3(n), dim3(256), 0, stream, tab, unit_flips, flips + first);
+                st = check_launch("pack_flips_sum_kernel");
+            }
         } else {
             st = wdt == SBN_BF16 ? launch_pack_kernel<uint16_t>(tab, pb, th, vec_ok, pat, stream)
                                  : launch_pack_kernel<float>(tab, pb, th, vec_ok, pat, stream);

@@ -142,6 +142,19 @@ def test_argument_errors_come_before_any_launch(sbn):
     assert bwd_grouped(flags=8) == sbn.SBN_EINVAL
     assert bwd_grouped(dy=(A, A + 2)) == sbn.SBN_EALIGN
     assert bwd_grouped(ws=1 << 12) == sbn.SBN_ESIZE
+    # in-place pack with flip counts: null counters, misaligned counters, fp32 weights, a pattern and a row length
+    # outside what the flip-counting kernels cover
+    lib.sbn_quantize_mask_pack_flips_batched.restype = ctypes.c_int
+    one_p, one_i = (vp * 1), (i64 * 1)
+
+    def pflips(wdt=1, d_out=16, d_in=256, N=2, M=4, fl=A):
+        return lib.sbn_quantize_mask_pack_flips_batched(ci(1), one_p(A), ci(wdt), one_i(d_out), one_i(d_in), ci(N), ci(M), one_p(A),
+                                                        one_p(A), vp(fl), vp(A), sz(1 << 20), vp(0))
+    assert pflips(fl=0) == sbn.SBN_EINVAL
+    assert pflips(fl=A + 4) == sbn.SBN_EALIGN
+    assert pflips(wdt=0) == sbn.SBN_EUNSUPPORTED
+    assert pflips(N=6, M=8) == sbn.SBN_EUNSUPPORTED
+    assert pflips(d_in=200) == sbn.SBN_EUNSUPPORTED
     # mask flips: null input, misaligned count, short workspace
     lib.sbn_mask_flips.restype = ctypes.c_int
     flips = lambda **kw: lib.sbn_mask_flips(  # noqa: E731

@@ -188,6 +188,106 @@ def test_mask_flips_between_two_steps(N, M, shape):
     assert flips.item() == 0
 
 
+def noisy_step(W0, seed, scale=0.25):
+    """The next step's latent weights: a noisy update under which some masks flip and most stay."""
+    step = sbn_synth.latent_weight(W0.shape[0], W0.shape[1], seed, device=W0.device)
+    return (W0.float() + scale * step.float()).to(torch.bfloat16)
+
+
+def oracle_flips(W0, W1, N, M):
+    m0 = oracle.nm_mask(W0.float().cpu().numpy(), N, M)
+    m1 = oracle.nm_mask(W1.float().cpu().numpy(), N, M)
+    return int((m0 != m1).sum())
+
+
+@pytest.mark.parametrize("N,M", [(2, 4), (1, 4), (2, 8)])
+def test_pack_in_place_counts_mask_flips(N, M):
+    # the per-step remask in place over the previous packed forms with the flip count as a by-product: a batch
+    # of matrices whose last unit is partial (111, 1500 chunks) or whole, three steps in a row on one set of
+    # buffers (the counters start from zero every call); bytes and gamma against the oracle's pack of the new
+    # weights, flips against the oracle's masks of both steps and against the separate flip kernels
+    s = sbn()
+    shapes = [(37, 384), (256, 1280), (300, 640), (512, 4096), (16, 128)] * 3
+    Ws = [sbn_synth.latent_weight(a, b, 2000 + i).to(DEV) for i, (a, b) in enumerate(shapes)]
+    packed = [torch.zeros(s.sbn_packed_bytes(a, b, N, M), dtype=torch.uint8, device=DEV) for a, b in shapes]
+    gammas = torch.zeros(len(shapes), dtype=torch.float32, device=DEV)
+    glist = [gammas[i:i + 1] for i in range(len(shapes))]
+    ws = s.new_workspace(s.sbn_workspace_bytes(s.SBN_OP_QUANTIZE_MASK_PACK, len(shapes), 512, 4096, N, M))
+    s.sbn_quantize_mask_pack_batched(Ws, N, M, packed, glist, ws)
+    torch.cuda.synchronize()
+    flips = torch.full((len(shapes),), -7, dtype=torch.int64, device=DEV)
+    for step in range(3):
+        Wn = [noisy_step(W, 2100 + 50 * step + i, scale=0.25 if step < 2 else 0.0) for i, W in enumerate(Ws)]
+        old = [p.clone() for p in packed]
+        s.sbn_quantize_mask_pack_flips_batched(Wn, N, M, packed, glist, flips, ws)
+        torch.cuda.synchronize()
+        got = flips.cpu().numpy()
+        for i, (W0, W1) in enumerate(zip(Ws, Wn)):
+            ref, g, *_ = oracle_pack(W1.cpu(), N, M)
+            assert gammas[i].item() == g, f"step {step}, gamma of matrix {i}"
+            assert np.array_equal(packed[i].cpu().numpy(), ref), f"step {step}, packed bytes of matrix {i}"
+            expected = oracle_flips(W0, W1, N, M)
+            assert got[i] == expected, f"step {step}, flips of matrix {i}: {got[i]} != {expected}"
+            assert (expected > 0) == (step < 2)        # the third step repeats the second's weights: nothing flips
+            one = torch.zeros(1, dtype=torch.int64, device=DEV)
+            wsf = s.new_workspace(s.sbn_workspace_bytes(s.SBN_OP_MASK_FLIPS, 1, shapes[i][0], shapes[i][1], N, M))
+            s.sbn_mask_flips(old[i], packed[i], shapes[i][0], shapes[i][1], N, M, one, wsf)
+            assert one.item() == expected
+        Ws = Wn
+
+
+@pytest.mark.parametrize("N,M", [(2, 4), (1, 4), (2, 8)])
+def test_pack_in_place_counts_mask_flips_three_pass_form(N, M):
+    # a matrix of more units than the persistent grid holds blocks takes the three-pass form (sum, finalize, pack):
+    # its pack kernel counts the flips the same way
+    s = sbn()
+    a, b = 6912, 4096
+    W0 = sbn_synth.latent_weight(a, b, 2300 + N, device=DEV)
+    W1 = noisy_step(W0, 2301 + N)
+    packed = torch.zeros(s.sbn_packed_bytes(a, b, N, M), dtype=torch.uint8, device=DEV)
+    gamma = torch.zeros(1, dtype=torch.float32, device=DEV)
+    ws = s.new_workspace(s.sbn_workspace_bytes(s.SBN_OP_QUANTIZE_MASK_PACK, 1, a, b, N, M))
+    s.sbn_quantize_mask_pack(W0, N, M, packed, gamma, ws)
+    flips = torch.full((1,), -7, dtype=torch.int64, device=DEV)
+    s.sbn_quantize_mask_pack_flips_batched([W1], N, M, [packed], [gamma], flips, ws)
+    torch.cuda.synchronize()
+    ref, g, *_ = oracle_pack(W1.cpu(), N, M)
+    assert gamma.item() == g
+    assert np.array_equal(packed.cpu().numpy(), ref)
+    assert flips.item() == oracle_flips(W0, W1, N, M)
+
+
+def test_config4_sweep_in_place_with_flips_as_timed(sweep_latents):
+    # the 210-matrix sweep of configs[3] at 2:4 as the benchmark times its flip-counting form: one batched call in
+    # place over the previous step's packed forms; every packed byte, gamma and flip count against the oracle
+    from concurrent.futures import ThreadPoolExecutor
+    s = sbn()
+    N, M = 2, 4
+    Wl = sweep_latents
+    W1 = [noisy_step(w, 2400 + i) for i, w in enumerate(Wl)]
+    packed = [torch.zeros(s.sbn_packed_bytes(w.shape[0], w.shape[1], N, M), dtype=torch.uint8, device=DEV) for w in Wl]
+    gammas = torch.zeros(len(Wl), dtype=torch.float32, device=DEV)
+    glist = [gammas[i:i + 1] for i in range(len(Wl))]
+    ws = s.new_workspace(s.sbn_workspace_bytes(s.SBN_OP_QUANTIZE_MASK_PACK, len(Wl), sbn_synth.FFN, sbn_synth.HIDDEN, N, M))
+    s.PackBatch(Wl, N, M, packed, glist, ws).run()
+    flips = torch.full((len(Wl),), -7, dtype=torch.int64, device=DEV)
+    s.PackBatch(W1, N, M, packed, glist, ws, flips).run()
+    torch.cuda.synchronize()
+    got_gamma, got_flips = gammas.cpu().numpy(), flips.cpu().numpy()
+
+    def one(i):
+        ref, g, *_ = oracle_pack(W1[i].cpu(), N, M)
+        return i, g == got_gamma[i], np.array_equal(packed[i].cpu().numpy(), ref), got_flips[i] == oracle_flips(Wl[i], W1[i], N, M)
+
+    with ThreadPoolExecutor(4) as pool:
+        for i, gamma_ok, bytes_ok, flips_ok in pool.map(one, range(len(Wl))):
+            assert gamma_ok, f"gamma of matrix {i}"
+            assert bytes_ok, f"packed bytes of matrix {i}"
+            assert flips_ok, f"flips of matrix {i}"
+    del W1
+    torch.cuda.empty_cache()
+
+
 @pytest.fixture
 def spin_limits():
     """Sets the bounds of the library's bounded waits for one test and restores the defaults afterwards."""
