@@ -14,16 +14,21 @@ namespace sbn {
 namespace {
 
 // ---- pieces of the activation quantizer shared by its kernels -------------------------------------
-// largest 15-bit magnitude pattern among eight bf16 values and a running maximum (bf16 magnitudes order like integers)
+// largest 15-bit magnitude pattern among eight bf16 values and a running maximum (bf16 magnitudes order like integers);
+// the two halves of a word are compared as a pair of 16-bit integers
+typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t absmax_bits_bf16x8(const uint4 &d, uint32_t m)
 {
     const uint32_t w[4] = {d.x, d.y, d.z, d.w};
+    ushort2_t best = {0, 0};
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-        const uint32_t lo = w[k] & 0x7fffu, hi = (w[k] >> 16) & 0x7fffu;
-        m = lo > m ? lo : m;
-        m = hi > m ? hi : m;
+        const uint32_t mag = w[k] & 0x7fff7fffu;
+        best = __builtin_elementwise_max(best, __builtin_bit_cast(ushort2_t, mag));
     }
+    const uint32_t both = __builtin_bit_cast(uint32_t, best), lo = both & 0xffffu, hi = both >> 16;
+    m = lo > m ? lo : m;
+    m = hi > m ? hi : m;
     return m;
 }
 
@@ -35,23 +40,26 @@ __device__ __forceinline__ float scale_from_absmax_bits(uint32_t m)
     return __fdiv_rn(127.0f, amax);
 }
 
-// eight bf16 values -> eight int8: clip(rint(x * s)) with one fp32 multiply and half-to-even rounding
+// eight bf16 values of a row -> eight int8: clip(rint(x * s)) with one fp32 multiply and half-to-even rounding, s the
+// scale of that same row.  The rounding is an addition of 1.5 * 2^23: the sum has an ulp of 1, so the (round-to-nearest-
+// even) addition rounds the product exactly as rint does, and the low byte of the sum's bit pattern is the integer in
+// two's complement.  No clip is needed: |x| <= amax <= max(amax, 1e-5) and s = fl(127 / max(amax, 1e-5)), so
+// |fl(x * s)| <= 127 (1 + 2^-24)^2 < 127.5 and the rounded value already lies in [-127, 127].
 __device__ __forceinline__ uint2 quantize_bf16x8(const uint4 &d, float s)
 {
     const uint32_t w[4] = {d.x, d.y, d.z, d.w};
-    uint32_t packed[2] = {0, 0};
+    uint32_t z[8];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
+        z[2 * k] = __float_as_uint(__fadd_rn(__fmul_rn(__uint_as_float(w[k] << 16), s), 12582912.0f));
+        z[2 * k + 1] = __float_as_uint(__fadd_rn(__fmul_rn(__uint_as_float(w[k] & 0xffff0000u), s), 12582912.0f));
+    }
+    uint32_t packed[2];
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const float x = __uint_as_float(h ? (w[k] & 0xffff0000u) : (w[k] << 16));
-            float q = rintf(__fmul_rn(x, s));
-            q = q > 127.0f ? 127.0f : q;
-            q = q < -128.0f ? -128.0f : q;
-            const uint32_t byte = (uint32_t)(int)q & 0xffu;
-            const int e = 2 * k + h;
-            packed[e >> 2] |= byte << (8 * (e & 3));
-        }
+    for (int h = 0; h < 2; ++h) {
+        const uint32_t lo = __builtin_amdgcn_perm(z[4 * h + 1], z[4 * h], 0x0c0c0400u);      // bytes 0, 1
+        const uint32_t hi = __builtin_amdgcn_perm(z[4 * h + 3], z[4 * h + 2], 0x04000c0cu);  // bytes 2, 3
+        packed[h] = lo | hi;
     }
     return make_uint2(packed[0], packed[1]);
 }
@@ -424,6 +432,7 @@ constexpr int GEMV_STREAM_MAX = 64;
 constexpr int GEMV_STREAM_INPUTS = 4;
 constexpr int GEMV_QUANT_VEC = 4;    // 16-byte vectors of a row per thread when a block quantizes it
 constexpr int STAGE_BATCH = 8;       // activation loads a thread has in flight while it stages a block's input in LDS
+constexpr int GEMV_OWN_VEC = 14;     // 16-byte vectors of a token row per lane when a wavefront quantizes a row for its own block
 struct GemvStreamTable {
     GemvStreamItem it[GEMV_STREAM_MAX];
     int unit0[GEMV_STREAM_MAX + 1];   // first unit of each problem
@@ -434,7 +443,21 @@ struct GemvStreamTable {
     unsigned epoch;                   // distinguishes this launch's flags from whatever the workspace held
     int spin_limit;
 };
-static_assert(sizeof(GemvStreamTable) <= 4096, "the table travels as a kernel argument");
+static_assert(sizeof(GemvStreamTable) <= 4096 && sizeof(GemvStreamTable) % 8 == 0, "the table travels as a kernel argument");
+
+// A value every lane holds alike, moved to a scalar register: what is read from the LDS copy of a launch table decides
+// loop bounds and branches, which must stay scalar.
+__device__ __forceinline__ int uni(int x) { return __builtin_amdgcn_readfirstlane(x); }
+__device__ __forceinline__ unsigned uni(unsigned x) { return (unsigned)__builtin_amdgcn_readfirstlane((int)x); }
+template <typename T> __device__ __forceinline__ T *uni(T *p)
+{
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
+    // rebuilt as a pointer into global memory, so that what is read through it stays a global (not a flat) access
+    typedef T __attribute__((address_space(1))) *global_ptr;
+    return (T *)(global_ptr)(((uint64_t)hi << 32) | lo);
+}
 
 __device__ __forceinline__ unsigned long long gemv_flag_value(unsigned epoch, int t)
 {
@@ -442,11 +465,22 @@ __device__ __forceinline__ unsigned long long gemv_flag_value(unsigned epoch, in
 }
 
 template <int RT, int DEPTH, int NW, int FORM>
-__global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable tab)
+__global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable tab_arg)
 {
     constexpr bool DENSE = FORM == GEMV_DENSE, ONE4 = FORM == GEMV_1OF4;
     constexpr int CB = ONE4 ? 16 : 32;   // bytes of a chunk: the 1:4 form is one 16-byte load per lane and super-step
     extern __shared__ __attribute__((aligned(16))) int8_t xlds[];   // [tokens][d_in + 16]
+    // The launch table is fetched once, by the whole block in one round trip, into LDS.  Read through the kernel
+    // argument it costs a chain of dependent scalar loads before the first weight load can go out (which problem, its
+    // shape, its pointers: a dozen, each a trip to memory: measured 5.6 us from the block's start to its first load).
+    __shared__ __attribute__((aligned(16))) GemvStreamTable tab;
+    {
+        (void)tab_arg;
+        const uint2 *src = (const uint2 *)__builtin_amdgcn_kernarg_segment_ptr();   // the table is the only argument
+        uint2 *dst = reinterpret_cast<uint2 *>(&tab);
+        for (int i = threadIdx.x; i < (int)(sizeof(GemvStreamTable) / 8); i += 64 * NW) dst[i] = src[i];
+        __syncthreads();
+    }
     __shared__ int unit_ctr;                                        // next unit of the current problem nobody has taken
     __shared__ float sx_lds[16];                                    // s_x of the staged tokens of a self-quantized input
     __shared__ uint32_t wave_amax[NW];
@@ -490,31 +524,58 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
                 reinterpret_cast<uint2 *>(lds_row)[idx] = q;
         }
     };
-    if ((int)blockIdx.x < tab.tok0[tab.nin]) {   // producer role: one token row of one input
+    auto load_input = [&](int j) {
+        const GemvStreamInput &src = tab.in[j];
+        GemvStreamInput d;
+        d.X = uni(src.X); d.xq = uni(src.xq); d.sx = uni(src.sx); d.flags = uni(src.flags);
+        d.tokens = uni(src.tokens); d.d_in = uni(src.d_in);
+        return d;
+    };
+    auto load_item = [&](int i) {
+        const GemvStreamItem &src = tab.it[i];
+        GemvStreamItem d;
+        d.xq = uni(src.xq); d.sx = uni(src.sx); d.packed = uni(src.packed); d.gamma = uni(src.gamma); d.Y = uni(src.Y);
+        d.d_in = uni(src.d_in); d.d_out = uni(src.d_out); d.tokens = uni(src.tokens); d.input = uni(src.input);
+        return d;
+    };
+    auto unit0 = [&](int i) { return uni(tab.unit0[i]); };
+    const unsigned epoch = uni(tab.epoch);
+    const int spin_limit = uni(tab.spin_limit);
+    if ((int)blockIdx.x < uni(tab.tok0[uni(tab.nin)])) {   // producer role: one token row of one input
         int j = 0;
-        while ((int)blockIdx.x >= tab.tok0[j + 1]) ++j;
-        const GemvStreamInput &in = tab.in[j];
-        const int t = (int)blockIdx.x - tab.tok0[j];
+        while ((int)blockIdx.x >= uni(tab.tok0[j + 1])) ++j;
+        const GemvStreamInput in = load_input(j);
+        const int t = (int)blockIdx.x - uni(tab.tok0[j]);
         quantize_row(in, t, nullptr, true);
         // The row and its scale are ordinary stores. The barrier orders every thread's part before thread 0,
         // whose release store of the flag makes all of it visible to the whole device before the flag is.
         __syncthreads();
         if (threadIdx.x == 0)
-            __hip_atomic_store(&in.flags[t], gemv_flag_value(tab.epoch, t), __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&in.flags[t], gemv_flag_value(epoch, t), __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
     }
-    const int total = tab.unit0[tab.count];
+    const int total = unit0(uni(tab.count));
     const int b0 = (int)((int64_t)total * blockIdx.x / gridDim.x), b1 = (int)((int64_t)total * (blockIdx.x + 1) / gridDim.x);
     const int r = lane & 15, c4 = lane >> 4;
     const uint32_t ones = vgpr_ones();
+    // the block's first problem by bisection (a linear scan is up to 64 dependent reads for the last blocks of a full table)
     int item = 0;
+    {
+        int hi = uni(tab.count);
+        while (hi - item > 1) {
+            const int mid = (item + hi) >> 1;
+            if (b0 >= unit0(mid)) item = mid; else hi = mid;
+        }
+    }
     int u = b0;
     const int8_t *staged_xq = nullptr;   // what the LDS copy currently holds (block-uniform)
     int staged_tokens = 0, staged_k = 0;
+    bool first_problem = true;
     while (u < b1) {
-        while (u >= tab.unit0[item + 1]) ++item;
-        const GemvStreamItem &it = tab.it[item];
-        const int seg_end = b1 < tab.unit0[item + 1] ? b1 : tab.unit0[item + 1];
-        const int ua = u - tab.unit0[item], ub = seg_end - tab.unit0[item];   // units of this problem for the block
+        while (u >= unit0(item + 1)) ++item;
+        const GemvStreamItem it = load_item(item);
+        const int item_u0 = unit0(item), item_u1 = unit0(item + 1);
+        const int seg_end = b1 < item_u1 ? b1 : item_u1;
+        const int ua = u - item_u0, ub = seg_end - item_u0;   // units of this problem for the block
         u = seg_end;
         const int K = it.d_in, nchunks = K / CHUNK, nsuper = (nchunks + 3) / 4, pitch = K + 16;
         const bool tok_ok = r < it.tokens;
@@ -577,6 +638,46 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
         // that share an input, Q/K/V or up/gate, come one after the other).
         const bool restage = it.xq != staged_xq || it.tokens != staged_tokens || K != staged_k;
         const bool self_quant = it.input >= 0;
+        // The input of a block's FIRST problem is quantized by the block itself, a wavefront per token row with the
+        // whole row in registers: one trip to memory for the bf16 rows (requested before the weight queue fills),
+        // a wavefront-level maximum, the int8 row written straight into LDS.  Waiting for the producer blocks
+        // instead put the staged activations 8-10 us behind the block's start (row read, release, poll, acquire,
+        // staging read: five trips in a row) with only the DEPTH queued super-steps of weights to cover them.
+        // Inputs that a block meets later were published by the producer blocks long before.
+        const bool own = restage && self_quant && first_problem && K <= 8 * 64 * GEMV_OWN_VEC;
+        first_problem = false;
+        uint4 xv[GEMV_OWN_VEC];
+        const uint4 *own_X = nullptr;
+        auto own_request = [&](int t) {
+            const uint4 *row = own_X + (int64_t)t * (K / 8);
+#pragma unroll
+            for (int i = 0; i < GEMV_OWN_VEC; ++i) {
+                const int idx = lane + 64 * i;
+                xv[i] = row[idx < K / 8 ? idx : K / 8 - 1];   // past the end the last vector again: the maximum is the same
+            }
+        };
+        auto own_quantize = [&](int t) {
+            uint32_t m = 0;
+#pragma unroll
+            for (int i = 0; i < GEMV_OWN_VEC; ++i) m = absmax_bits_bf16x8(xv[i], m);
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) {
+                const uint32_t o = (uint32_t)__shfl_xor((int)m, off, 64);
+                m = o > m ? o : m;
+            }
+            const float s = scale_from_absmax_bits(m);
+            if (lane == 0) sx_lds[t] = s;
+            uint2 *lds_row = reinterpret_cast<uint2 *>(xlds + t * pitch);
+#pragma unroll
+            for (int i = 0; i < GEMV_OWN_VEC; ++i) {
+                const int idx = lane + 64 * i;
+                if (idx < K / 8) lds_row[idx] = quantize_bf16x8(xv[i], s);
+            }
+        };
+        if (own) {
+            own_X = uni(tab.in[it.input].X);
+            if (wave < it.tokens) own_request(wave);
+        }
         // copy tokens x K quantized activations into the LDS rows; the loads go out in batches so that
         // their latencies overlap instead of adding up
         auto stage = [&](const int8_t *src, int tokens) {
@@ -590,8 +691,10 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
                 }
 #pragma unroll
                 for (int b = 0; b < STAGE_BATCH; ++b) {
-                    const int v = v0 + 64 * NW * b;
-                    if (v < n16) *reinterpret_cast<uint4 *>(&xlds[(v / (K / 16)) * pitch + (v % (K / 16)) * 16]) = q[b];
+                    // past the end the last vector is written again (same bytes, same place): no branch, so the batch
+                    // stays in registers
+                    const int v = v0 + 64 * NW * b < n16 ? v0 + 64 * NW * b : n16 - 1;
+                    *reinterpret_cast<uint4 *>(&xlds[(v / (K / 16)) * pitch + (v % (K / 16)) * 16]) = q[b];
                 }
             }
         };
@@ -602,16 +705,22 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) issue(qi[d], qc[d]);
         }
-        if (restage && self_quant) {
+        if (own) {
+            for (int t = wave; t < it.tokens; t += NW) {
+                if (t != wave) own_request(t);
+                own_quantize(t);
+            }
+            __syncthreads();
+        } else if (restage && self_quant) {
             // the first weight loads are in flight; now wait (bounded) for the blocks that quantize this input
-            const GemvStreamInput &in = tab.in[it.input];
+            const GemvStreamInput in = load_input(it.input);
             if (threadIdx.x == 0) stage_ok = 1;
             __syncthreads();
             if ((int)threadIdx.x < in.tokens) {
-                const unsigned long long want = gemv_flag_value(tab.epoch, threadIdx.x);
-                int spins = 0, ok = tab.spin_limit >= 0;
+                const unsigned long long want = gemv_flag_value(epoch, threadIdx.x);
+                int spins = 0, ok = spin_limit >= 0;
                 while (ok && __hip_atomic_load(&in.flags[threadIdx.x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != want) {
-                    if (++spins > tab.spin_limit) ok = 0;
+                    if (++spins > spin_limit) ok = 0;
                     else __builtin_amdgcn_s_sleep(4);
                 }
                 if (!ok) stage_ok = 0;   // several lanes may write the same value
@@ -901,7 +1010,7 @@ static sbn_status launch_gemv_as(int count, const LinearItem *items, hipStream_t
         }
         // one block of NW wavefronts per multiprocessor, sharing one staged copy of the activations
         const int nblocks = device_cus();
-        constexpr int GEMV_STREAM_LDS = 160 * 1024 - 256;   // the kernel's counter and scales take a little static LDS
+        constexpr int GEMV_STREAM_LDS = 160 * 1024 - 4608;   // the kernel's copy of the launch table, its counter and scales are static LDS
         if (plain && lds_need <= GEMV_STREAM_LDS && units >= 16 * (int64_t)nblocks) {
             // One row tile per unit, DEPTH 5 and 8 wavefronts per block measured best among one or two row tiles,
             // depths 2..8 and 6..16 wavefronts (more wavefronts finish their shares further apart, fewer leave too
@@ -916,19 +1025,25 @@ static sbn_status launch_gemv_as(int count, const LinearItem *items, hipStream_t
             // long for one block's registers) go through the quantizer kernel first
             // Not under stream capture: the flags carry a per-launch number that the host hands out, and a replayed
             // graph would present the previous replay's flags again.  A captured launch takes the quantizer kernels.
-            bool fuse = !stream_is_capturing(stream);
+            // One case needs neither flags nor producer blocks and is taken under capture as well: every problem of
+            // the launch reads the same unquantized input and its rows fit a wavefront's registers; each block then
+            // quantizes that input once, for itself, in front of its first problem and never stages anything else.
+            bool fuse = true, one_input = true;
             int nin = 0;
             const int8_t *in_xq[GEMV_STREAM_INPUTS];
             for (int i = 0; i < n && fuse; ++i) {
                 const LinearItem &li = items[first + i];
-                if (li.quantized || std::find(written.begin(), written.end(), li.xq) != written.end()) continue;
+                if (li.quantized || std::find(written.begin(), written.end(), li.xq) != written.end()) { one_input = false; continue; }
                 if (li.d_in > 8 * GEMV_QUANT_VEC * 64 * NW || li.tokens > 16) { fuse = false; break; }
+                if (li.d_in > 8 * 64 * GEMV_OWN_VEC) one_input = false;
                 bool seen = false;
                 for (int j = 0; j < nin; ++j) seen = seen || in_xq[j] == li.xq;
                 if (seen) continue;
                 if (nin == GEMV_STREAM_INPUTS) { fuse = false; break; }
                 in_xq[nin++] = li.xq;
             }
+            one_input = one_input && fuse && nin == 1;
+            if (fuse && !one_input && stream_is_capturing(stream)) fuse = false;
             if (!fuse) {
                 sbn_status st = quantize_run(first, n);
                 if (st != SBN_OK) return st;
@@ -960,6 +1075,8 @@ static sbn_status launch_gemv_as(int count, const LinearItem *items, hipStream_t
             }
             tab.unit0[n] = u;
             for (int j = tab.nin; j < GEMV_STREAM_INPUTS; ++j) tab.tok0[j + 1] = tab.tok0[tab.nin];
+            if (one_input)   // no producer blocks: nobody would read what they publish
+                for (int j = 0; j <= GEMV_STREAM_INPUTS; ++j) tab.tok0[j] = 0;
             tab.epoch = g_gemv_stream_epoch.fetch_add(1, std::memory_order_relaxed);
             tab.spin_limit = gemv_spin_limit();
             static thread_local bool raised = false;

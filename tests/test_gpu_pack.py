@@ -318,3 +318,13 @@ def test_single_read_pack_when_blocks_do_not_wait(N, M, spin_limit, spin_limits)
             ref, g, *_ = oracle_pack(W, N, M)
             assert gammas[i].item() == g
             assert np.array_equal(packed[i].cpu().numpy(), ref)
+    # the flip-counting form on the same branches: in place over what the loop above left, with the next step's weights
+    W1 = [noisy_step(W, 1850 + i) for i, W in enumerate(Wd)]
+    flips = torch.full((len(shapes),), -7, dtype=torch.int64, device=DEV)
+    s.sbn_quantize_mask_pack_flips_batched(W1, N, M, packed, glist, flips, ws)
+    torch.cuda.synchronize()
+    for i, (W0, Wn) in enumerate(zip(Wd, W1)):
+        ref, g, *_ = oracle_pack(Wn.cpu(), N, M)
+        assert gammas[i].item() == g
+        assert np.array_equal(packed[i].cpu().numpy(), ref)
+        assert flips[i].item() == oracle_flips(W0, Wn, N, M)
