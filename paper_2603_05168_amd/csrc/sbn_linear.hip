@@ -442,6 +442,8 @@ struct GemvStreamTable {
     int nin;
     unsigned epoch;                   // distinguishes this launch's flags from whatever the workspace held
     int spin_limit;
+    int share, share_rem;             // units per block: the first share_rem blocks take share + 1, the others share
+    int pad;
 };
 static_assert(sizeof(GemvStreamTable) <= 4096 && sizeof(GemvStreamTable) % 8 == 0, "the table travels as a kernel argument");
 
@@ -539,9 +541,14 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
         return d;
     };
     auto unit0 = [&](int i) { return uni(tab.unit0[i]); };
+    // What stands between a block's start and its first requests is a chain of dependent reads of this table, so the
+    // chain is kept short: the block's share from two numbers the host divided out, its first problem from one read
+    // of all problem boundaries and a vote.
     const unsigned epoch = uni(tab.epoch);
     const int spin_limit = uni(tab.spin_limit);
-    if ((int)blockIdx.x < uni(tab.tok0[uni(tab.nin)])) {   // producer role: one token row of one input
+    const int share = uni(tab.share), share_rem = uni(tab.share_rem);
+    const int bound = tab.unit0[1 + lane];   // boundaries past the last problem hold the total
+    if ((int)blockIdx.x < uni(tab.tok0[GEMV_STREAM_INPUTS])) {   // producer role: one token row of one input
         int j = 0;
         while ((int)blockIdx.x >= uni(tab.tok0[j + 1])) ++j;
         const GemvStreamInput in = load_input(j);
@@ -553,19 +560,12 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
         if (threadIdx.x == 0)
             __hip_atomic_store(&in.flags[t], gemv_flag_value(epoch, t), __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
     }
-    const int total = unit0(uni(tab.count));
-    const int b0 = (int)((int64_t)total * blockIdx.x / gridDim.x), b1 = (int)((int64_t)total * (blockIdx.x + 1) / gridDim.x);
+    const int b0 = share * (int)blockIdx.x + ((int)blockIdx.x < share_rem ? (int)blockIdx.x : share_rem);
+    const int b1 = b0 + share + ((int)blockIdx.x < share_rem ? 1 : 0);
     const int r = lane & 15, c4 = lane >> 4;
     const uint32_t ones = vgpr_ones();
-    // the block's first problem by bisection (a linear scan is up to 64 dependent reads for the last blocks of a full table)
-    int item = 0;
-    {
-        int hi = uni(tab.count);
-        while (hi - item > 1) {
-            const int mid = (item + hi) >> 1;
-            if (b0 >= unit0(mid)) item = mid; else hi = mid;
-        }
-    }
+    // the block's first problem: as many problems end at or before its first unit
+    int item = __builtin_popcountll(__ballot(bound <= b0));
     int u = b0;
     const int8_t *staged_xq = nullptr;   // what the LDS copy currently holds (block-uniform)
     int staged_tokens = 0, staged_k = 0;
@@ -652,6 +652,7 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
             const uint4 *row = own_X + (int64_t)t * (K / 8);
 #pragma unroll
             for (int i = 0; i < GEMV_OWN_VEC; ++i) {
+                if (64 * i >= K / 8) break;   // the same for every lane
                 const int idx = lane + 64 * i;
                 xv[i] = row[idx < K / 8 ? idx : K / 8 - 1];   // past the end the last vector again: the maximum is the same
             }
@@ -659,7 +660,10 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
         auto own_quantize = [&](int t) {
             uint32_t m = 0;
 #pragma unroll
-            for (int i = 0; i < GEMV_OWN_VEC; ++i) m = absmax_bits_bf16x8(xv[i], m);
+            for (int i = 0; i < GEMV_OWN_VEC; ++i) {
+                if (64 * i >= K / 8) break;
+                m = absmax_bits_bf16x8(xv[i], m);
+            }
 #pragma unroll
             for (int off = 32; off > 0; off >>= 1) {
                 const uint32_t o = (uint32_t)__shfl_xor((int)m, off, 64);
@@ -670,6 +674,7 @@ __global__ void __launch_bounds__(64 * NW) gemv_stream_kernel(GemvStreamTable ta
             uint2 *lds_row = reinterpret_cast<uint2 *>(xlds + t * pitch);
 #pragma unroll
             for (int i = 0; i < GEMV_OWN_VEC; ++i) {
+                if (64 * i >= K / 8) break;
                 const int idx = lane + 64 * i;
                 if (idx < K / 8) lds_row[idx] = quantize_bf16x8(xv[i], s);
             }
@@ -1073,7 +1078,10 @@ static sbn_status launch_gemv_as(int count, const LinearItem *items, hipStream_t
                 tab.unit0[i] = u;
                 u += (int)ceil_div(li.d_out, 16 * RT);
             }
-            tab.unit0[n] = u;
+            for (int i = n; i <= GEMV_STREAM_MAX; ++i) tab.unit0[i] = u;
+            tab.share = u / nblocks;
+            tab.share_rem = u % nblocks;
+            tab.pad = 0;
             for (int j = tab.nin; j < GEMV_STREAM_INPUTS; ++j) tab.tok0[j + 1] = tab.tok0[tab.nin];
             if (one_input)   // no producer blocks: nobody would read what they publish
                 for (int j = 0; j <= GEMV_STREAM_INPUTS; ++j) tab.tok0[j] = 0;

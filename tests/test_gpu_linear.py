@@ -449,7 +449,7 @@ def spin_limits():
 
 
 @pytest.mark.parametrize("spin_limit", [None, -1, 0])
-@pytest.mark.parametrize("tokens", [1, 8, 16])
+@pytest.mark.parametrize("tokens", [1, 2, 3, 5, 8, 11, 16])   # a block's own quantizer splits a row over 8, 4, 2 or 1 wavefronts
 def test_grouped_streaming_gemv_against_oracle(tokens, spin_limit, spin_limits):
     # enough rows in one grouped call to take the persistent streaming kernel; shapes with ragged
     # row counts and a partial last super-step (K = 768 = 6 chunks).  The kernel quantizes the three
