@@ -32,22 +32,32 @@ struct GemmArgs {
     int tiles_o, tiles_t;
 };
 
-// A launch of the sparse kernel covers up to GEMM_GROUP_MAX problems.
-constexpr int GEMM_GROUP_MAX = 8;
-struct GemmGroup {
-    GemmArgs g[GEMM_GROUP_MAX];
+// A launch of the sparse kernel covers up to GEMM_GROUP_MAX problems with a work list, or up to GEMM_GROUP_WIDE
+// problems of few tokens each (decode batches), whose work is dealt by row tile (see gemm_smfmac_kernel).
+constexpr int GEMM_GROUP_MAX = 8, GEMM_GROUP_WIDE = 32;
+template <int NP>
+struct GemmGroupT {
+    GemmArgs g[NP];
     int count;
 };
+using GemmGroup = GemmGroupT<GEMM_GROUP_MAX>;
+using GemmGroupWide = GemmGroupT<GEMM_GROUP_WIDE>;
 
 // Work list of a launch of the sparse kernel, made on the host: block b runs the pieces piece[b * per_block + i],
 // i < per_block, up to the first empty one (width 0).  A piece = (problem, row tile of 512, first token unit of 32 tokens,
 // width in units 1 .. 4).  per_block == 0: no list, the kernel splits the units by formula.
+// per_block < 0: no list either, the problems have few tokens and the pieces are (problem, row tile, four token units),
+// -per_block of them in all, dealt to the blocks in contiguous runs.
 constexpr int PIECE_TABLE_MAX = 768;
-struct PieceTable {
+template <int NE>
+struct PieceTableT {
     int per_block;
-    uint32_t piece[PIECE_TABLE_MAX];   // bits [2:0] width, [15:3] first unit, [24:16] row tile, [27:25] problem
+    uint32_t piece[NE];   // bits [2:0] width, [15:3] first unit, [24:16] row tile, [27:25] problem
 };
+using PieceTable = PieceTableT<PIECE_TABLE_MAX>;
+using PieceTableNone = PieceTableT<1>;
 static_assert(sizeof(GemmGroup) + sizeof(PieceTable) <= 4000, "both travel as kernel arguments");
+static_assert(sizeof(GemmGroupWide) + sizeof(PieceTableNone) <= 4000, "both travel as kernel arguments");
 
 // Tile order of the dense comparison kernel.
 // Blocks are dealt round-robin to the 8 XCDs, each with its own 4 MB L2.  XCD x takes the token
@@ -339,7 +349,8 @@ struct Piece {
 
 // requests the first stages of a piece (called with the ring idle: before the first piece and between the main loop
 // and the epilogue of the piece before)
-__device__ __forceinline__ void piece_prologue(const GemmGroup &grp, const Piece &p, int8_t *lds, int wave, int lane)
+template <class Group>
+__device__ __forceinline__ void piece_prologue(const Group &grp, const Piece &p, int8_t *lds, int wave, int lane)
 {
     const uint32_t lds0 = lds_address(lds);
     const GemmArgs &g = grp.g[p.prob];
@@ -366,8 +377,8 @@ __device__ __forceinline__ void piece_prologue(const GemmGroup &grp, const Piece
 // Main loop and epilogue of one piece whose prologue is already in flight: rows [512 to, +512) of W against tokens
 // [t0, t0 + 32 TB), the whole input dimension.  LIVE = false: a wavefront whose rows lie past the matrix (ragged last
 // row tile) only moves data and keeps the barriers.
-template <int TB, bool LIVE, bool DENSE>
-__device__ __forceinline__ void piece_body(const GemmGroup &grp, const Piece &p, const Piece &next, int8_t *lds, const int wave,
+template <int TB, bool LIVE, bool DENSE, class Group>
+__device__ __forceinline__ void piece_body(const Group &grp, const Piece &p, const Piece &next, int8_t *lds, const int wave,
                                            int lane)
 {
     // everything derived from the lane number is computed anew for every piece: hoisted out of the loop over pieces,
@@ -632,16 +643,16 @@ __device__ __forceinline__ void piece_body(const GemmGroup &grp, const Piece &p,
     }
 }
 
-template <int TB, bool DENSE>
-__device__ __forceinline__ void piece_live(const GemmGroup &grp, const Piece &p, const Piece &next, int8_t *lds, int wave, int lane)
+template <int TB, bool DENSE, class Group>
+__device__ __forceinline__ void piece_live(const Group &grp, const Piece &p, const Piece &next, int8_t *lds, int wave, int lane)
 {
     const bool live = p.to * ROWS + wave * (32 * RA) < grp.g[p.prob].d_out;   // a ragged last row tile leaves whole wavefronts idle
     if (live) piece_body<TB, true, DENSE>(grp, p, next, lds, wave, lane);
     else piece_body<TB, false, DENSE>(grp, p, next, lds, wave, lane);
 }
 
-template <bool DENSE>
-__device__ __forceinline__ void piece_run(const GemmGroup &grp, const Piece &p, const Piece &next, int8_t *lds, int wave, int lane)
+template <bool DENSE, class Group>
+__device__ __forceinline__ void piece_run(const Group &grp, const Piece &p, const Piece &next, int8_t *lds, int wave, int lane)
 {
     if (p.tb == 4) piece_live<4, DENSE>(grp, p, next, lds, wave, lane);
     else if (p.tb == 3) piece_live<3, DENSE>(grp, p, next, lds, wave, lane);
@@ -659,13 +670,50 @@ __device__ __forceinline__ void piece_run(const GemmGroup &grp, const Piece &p, 
 // the XCD's units in the order strip, unit (the same number of units each, +-1), cut into pieces of at most four units
 // that do not cross a strip.
 // DENSE = the weights are dense 2-bit codes (the stored form of N = M, or any pattern converted to it) instead of 2:4.
-template <bool DENSE>
-__global__ void __launch_bounds__(64 * sp::NW) gemm_smfmac_kernel(GemmGroup grp, PieceTable tab)
+template <bool DENSE, class Group, class Table>
+__global__ void __launch_bounds__(64 * sp::NW) gemm_smfmac_kernel(Group grp, Table tab)
 {
     __shared__ __attribute__((aligned(1024))) int8_t lds[sp::LDS_BYTES];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const sp::Piece none{0, 0, 0, 0, 0};
+    if constexpr (sizeof(Table) == sizeof(PieceTableNone)) {
+        // Decode batches (every problem at most 16 token units): a piece = (problem, row tile, a share of the token
+        // units of at most four), in that order, -per_block pieces in all; block b runs a contiguous run of them, so
+        // the pieces of a row tile that has more than one follow each other on one multiprocessor while its weights
+        // are still in L2.  Dealing token units to XCDs, as below, would leave most XCDs without work here.
+        const int P = -tab.per_block, nbk = (int)gridDim.x, b = (int)blockIdx.x;
+        const int q = P / nbk, rem = P % nbk;
+        int f = b * q + (b < rem ? b : rem);
+        const int end = f + q + (b < rem ? 1 : 0);
+        int prob = 0, base = 0, parity = 0;
+        auto piece_at = [&](int &f) {
+            if (f >= end) return none;
+            int units, groups;
+            for (;;) {
+                units = (grp.g[prob].tokens + 31) >> 5;
+                groups = (units + 3) >> 2;
+                const int cnt = ((grp.g[prob].d_out + sp::ROWS - 1) / sp::ROWS) * groups;
+                if (f < base + cnt) break;
+                base += cnt;
+                ++prob;
+            }
+            const int local = f - base, to = local / groups, g = local % groups;
+            const int wide = units / groups, more = units % groups;   // the first `more` shares hold one unit more
+            ++f;
+            parity ^= 1;
+            return sp::Piece{prob, to, (g * wide + (g < more ? g : more)) * 32, wide + (g < more ? 1 : 0), parity};
+        };
+        sp::Piece cur = piece_at(f);
+        if (cur.tb == 0) return;
+        sp::piece_prologue(grp, cur, lds, wave, lane);
+        while (cur.tb > 0) {
+            const sp::Piece next = piece_at(f);
+            sp::piece_run<DENSE>(grp, cur, next, lds, wave, lane);
+            cur = next;
+        }
+        return;
+    } else {
     if (tab.per_block > 0) {
         auto decode = [&](int i) {
             if (i >= tab.per_block) return none;
@@ -731,6 +779,7 @@ __global__ void __launch_bounds__(64 * sp::NW) gemm_smfmac_kernel(GemmGroup grp,
         const sp::Piece next = piece_at(f);
         sp::piece_run<DENSE>(grp, cur, next, lds, wave, lane);
         cur = next;
+    }
     }
 }
 
@@ -1011,16 +1060,39 @@ static int make_piece_table(const GemmGroup &grp, PieceTable &tab)
 
 sbn_status launch_gemm_smfmac(int count, const LinearItem *items, bool dense_codes, hipStream_t stream)
 {
-    for (int first = 0; first < count; first += GEMM_GROUP_MAX) {
-        GemmGroup grp;
-        grp.count = count - first < GEMM_GROUP_MAX ? count - first : GEMM_GROUP_MAX;
-        for (int i = 0; i < grp.count; ++i) grp.g[i] = make_args(items[first + i]);
-        static thread_local PieceTable tab;
-        const int per_xcd = make_piece_table(grp, tab);
-        if (dense_codes) hipLaunchKernelGGL(gemm_smfmac_kernel<true>, dim3(8 * per_xcd), dim3(64 * sp::NW), 0, stream, grp, tab);
-        else hipLaunchKernelGGL(gemm_smfmac_kernel<false>, dim3(8 * per_xcd), dim3(64 * sp::NW), 0, stream, grp, tab);
+    // problems of at most 16 token units (512 tokens: decode batches) are dealt by row tile, up to GEMM_GROUP_WIDE per launch
+    auto few_tokens = [&](int i) { return items[i].tokens <= 16 * 32; };
+    for (int first = 0; first < count;) {
+        const bool few = few_tokens(first);
+        const int most = few ? GEMM_GROUP_WIDE : GEMM_GROUP_MAX;
+        int n = 1;
+        while (first + n < count && n < most && few_tokens(first + n) == few) ++n;
+        if (few) {
+            GemmGroupWide grp;
+            grp.count = n;
+            int pieces = 0;
+            for (int i = 0; i < n; ++i) {
+                grp.g[i] = make_args(items[first + i]);
+                pieces += (int)ceil_div(items[first + i].d_out, sp::ROWS) * (int)ceil_div(ceil_div(items[first + i].tokens, 32), 4);
+            }
+            PieceTableNone tab;
+            tab.per_block = -pieces;
+            tab.piece[0] = 0;
+            const int blocks = pieces < device_cus() ? pieces : device_cus();
+            if (dense_codes) hipLaunchKernelGGL((gemm_smfmac_kernel<true, GemmGroupWide, PieceTableNone>), dim3(blocks), dim3(64 * sp::NW), 0, stream, grp, tab);
+            else hipLaunchKernelGGL((gemm_smfmac_kernel<false, GemmGroupWide, PieceTableNone>), dim3(blocks), dim3(64 * sp::NW), 0, stream, grp, tab);
+        } else {
+            GemmGroup grp;
+            grp.count = n;
+            for (int i = 0; i < n; ++i) grp.g[i] = make_args(items[first + i]);
+            static thread_local PieceTable tab;
+            const int per_xcd = make_piece_table(grp, tab);
+            if (dense_codes) hipLaunchKernelGGL((gemm_smfmac_kernel<true, GemmGroup, PieceTable>), dim3(8 * per_xcd), dim3(64 * sp::NW), 0, stream, grp, tab);
+            else hipLaunchKernelGGL((gemm_smfmac_kernel<false, GemmGroup, PieceTable>), dim3(8 * per_xcd), dim3(64 * sp::NW), 0, stream, grp, tab);
+        }
         sbn_status st = check_launch("gemm_smfmac_kernel");
         if (st != SBN_OK) return st;
+        first += n;
     }
     return SBN_OK;
 }

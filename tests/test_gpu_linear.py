@@ -533,6 +533,35 @@ def test_grouped_sparse_gemm_against_oracle():
         assert_rel(Y_list[i].cpu().numpy(), y, Y_TOL, f"Y of problem {i}")
 
 
+@pytest.mark.parametrize("N,M", [(2, 4), (8, 8)])
+def test_grouped_decode_batches_on_the_gemm_kernel(N, M):
+    # Decode batches of 17 .. 512 tokens (the batch sizes of the throughput table, Section 3.2): more problems than one
+    # launch of the row-tile work split holds (32), token counts that are no multiple of a token unit, one and several
+    # pieces per row tile, ragged last row tiles, one problem with enough tokens for the work-list split in between
+    s = sbn()
+    tokens_of = [17, 64, 100, 128, 200, 257, 512, 33, 40]
+    shapes = [((1100, 256) if i % 3 == 0 else (520, 384) if i % 3 == 1 else (64, 128)) for i in range(38)]
+    toks = [tokens_of[i % len(tokens_of)] for i in range(38)]
+    toks[20] = 600   # breaks the run of small problems
+    Ws = {sh: sbn_synth.latent_weight(sh[0], sh[1], 2100 + sh[0]) for sh in set(shapes)}
+    packs = {sh: hip_pack(W, N, M) for sh, W in Ws.items()}
+    refs = {sh: oracle_pack(W, N, M) for sh, W in Ws.items()}
+    Xs = {(t, k): sbn_synth.activations(t, k, 2200 + 7 * t + k) for t, (_, k) in set(zip(toks, shapes))}
+    Xd = {key: x.to(DEV) for key, x in Xs.items()}
+    Y_list = [torch.full((t, a), float("nan"), dtype=torch.float32, device=DEV) for t, (a, _) in zip(toks, shapes)]
+    need = sum(s.sbn_workspace_bytes(s.SBN_OP_LINEAR, t, a, b, N, M) for t, (a, b) in zip(toks, shapes))
+    ws = s.new_workspace(need)
+    s.sbn_sparse_ternary_linear_grouped([Xd[(t, sh[1])] for t, sh in zip(toks, shapes)], [packs[sh][0] for sh in shapes],
+                                        [packs[sh][1] for sh in shapes], Y_list, N, M, ws, path=s.SBN_PATH_SMFMAC)
+    torch.cuda.synchronize()
+    done = {}
+    for i, (t, sh) in enumerate(zip(toks, shapes)):
+        if (t, sh) not in done:
+            _, g, Weff, _ = refs[sh]
+            done[(t, sh)] = oracle.sparse_ternary_linear(Xs[(t, sh[1])].float().numpy(), Weff, g)[0]
+        assert_rel(Y_list[i].cpu().numpy(), done[(t, sh)], Y_TOL, f"Y of problem {i} ({t} tokens, {sh})")
+
+
 @pytest.mark.parametrize("N,M", [(2, 4), (1, 4)])
 @pytest.mark.parametrize("tokens,shape", [(8, (6912, 2560)), (1, (2560, 6912))])
 def test_config2_streaming_decode_full_size_as_timed(tokens, shape, N, M):
