@@ -305,6 +305,7 @@ def main():
     if "gemv" in sections:
         R = 64
         gemv_rows = {}
+        batch_rows = {}
         for name, (a, b) in (("up_6912x2560", (F, H)), ("down_2560x6912", (H, F))):
             packs = [pack_one(sbn_synth.latent_weight(a, b, sbn_synth.seed_for(2, 100 * r + a % 7), device=dev)) for r in range(R)]
             pbytes = sbn.sbn_packed_bytes(a, b, N, M)
@@ -334,9 +335,36 @@ def main():
                 log(f"[gemv] {name} T={tok}: stream {gbps:.0f} GB/s ({gbps / HBM_PEAK_GBPS:.1%} of HBM peak), "
                     f"single call {ms1 * 1e3:.1f} us")
                 del Yl, ws, grp
+            # decode at the batch sizes of the paper's throughput table (Section 3.2): the same R copies in one grouped
+            # call on automatic path selection (17 .. 64 tokens: the streaming kernel for decode batches; more: the
+            # sparse GEMM kernel with its work dealt by row tile), and one call alone
+            if not any(o.startswith(("up_", "down_")) for o in only):
+                for tok in (32, 64, 128, 256, 512):
+                    X = sbn_synth.activations(tok, b, sbn_synth.seed_for(2, tok), device=dev)
+                    Yl = [torch.empty(tok, a, dtype=torch.float32, device=dev) for _ in range(R)]
+                    ws = sbn.new_workspace(R * sbn.sbn_workspace_bytes(sbn.SBN_OP_LINEAR, tok, a, b, N, M), dev)
+                    grp = sbn.LinearGroup([X] * R, [p for p, _ in packs], [g for _, g in packs], Yl, N, M, ws, sbn.SBN_PATH_AUTO)
+                    ms = timed(grp.run, 50, 3)
+                    ws1 = sbn.new_workspace(sbn.sbn_workspace_bytes(sbn.SBN_OP_LINEAR, tok, a, b, N, M), dev)
+                    k = [0]
+
+                    def single_b():
+                        r = k[0] % R
+                        k[0] += 1
+                        sbn.sbn_sparse_ternary_linear(X, packs[r][0], packs[r][1], Yl[r], N, M, ws1, path=sbn.SBN_PATH_AUTO)
+                    ms1 = timed(single_b, 128, 8)
+                    gbps = R * pbytes / (ms * 1e-3) / 1e9
+                    batch_rows[f"{name}_B{tok}"] = {"stream_us_per_matrix": ms / R * 1e3, "stream_gbps_packed_bytes": gbps,
+                                                    "frac_hbm": gbps / HBM_PEAK_GBPS,
+                                                    "tops_dense_equiv": 2.0 * tok * a * b * R / (ms * 1e-3) / 1e12,
+                                                    "single_call_us": ms1 * 1e3, "copies": R}
+                    log(f"[batch] {name} batch {tok}: stream {ms / R * 1e3:.2f} us per matrix ({gbps / HBM_PEAK_GBPS:.1%} of HBM peak "
+                        f"on packed bytes, {2.0 * tok * a * b * R / (ms * 1e-3) / 1e12:.0f} TOPS dense-equivalent), single call {ms1 * 1e3:.1f} us")
+                    del Yl, ws, grp, ws1
             del packs
             torch.cuda.empty_cache()
         rows["gemv"] = gemv_rows
+        rows["decode_batches"] = batch_rows
         # decode of other patterns at 6912x2560, T = 8, through automatic path selection: 1:4 is read as stored (the
         # kernel builds the sparse operands in registers), the other instances of 2:4 are rewritten into the 2:4
         # operand form per call, everything else into dense 2-bit codes (6:8 is the paper's main pattern); N = M is

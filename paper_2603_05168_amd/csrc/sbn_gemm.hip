@@ -679,10 +679,11 @@ __global__ void __launch_bounds__(64 * sp::NW) gemm_smfmac_kernel(Group grp, Tab
     const sp::Piece none{0, 0, 0, 0, 0};
     if constexpr (sizeof(Table) == sizeof(PieceTableNone)) {
         // Decode batches (every problem at most 16 token units): a piece = (problem, row tile, a share of the token
-        // units of at most four), in that order, -per_block pieces in all; block b runs a contiguous run of them, so
-        // the pieces of a row tile that has more than one follow each other on one multiprocessor while its weights
-        // are still in L2.  Dealing token units to XCDs, as below, would leave most XCDs without work here.
-        const int P = -tab.per_block, nbk = (int)gridDim.x, b = (int)blockIdx.x;
+        // units of at most tab.piece[0] = 4, 2 or 1: the widest that still gives every multiprocessor a piece), in that
+        // order, -per_block pieces in all; block b runs a contiguous run of them, so the pieces of a row tile that has
+        // more than one follow each other on one multiprocessor while its weights are still in L2.  Dealing token
+        // units to XCDs, as below, would leave most XCDs without work here.
+        const int P = -tab.per_block, nbk = (int)gridDim.x, b = (int)blockIdx.x, wmax = (int)tab.piece[0];
         const int q = P / nbk, rem = P % nbk;
         int f = b * q + (b < rem ? b : rem);
         const int end = f + q + (b < rem ? 1 : 0);
@@ -692,7 +693,7 @@ __global__ void __launch_bounds__(64 * sp::NW) gemm_smfmac_kernel(Group grp, Tab
             int units, groups;
             for (;;) {
                 units = (grp.g[prob].tokens + 31) >> 5;
-                groups = (units + 3) >> 2;
+                groups = (units + wmax - 1) / wmax;
                 const int cnt = ((grp.g[prob].d_out + sp::ROWS - 1) / sp::ROWS) * groups;
                 if (f < base + cnt) break;
                 base += cnt;
@@ -1061,23 +1062,37 @@ static int make_piece_table(const GemmGroup &grp, PieceTable &tab)
 sbn_status launch_gemm_smfmac(int count, const LinearItem *items, bool dense_codes, hipStream_t stream)
 {
     // problems of at most 16 token units (512 tokens: decode batches) are dealt by row tile, up to GEMM_GROUP_WIDE per launch
-    auto few_tokens = [&](int i) { return items[i].tokens <= 16 * 32; };
+    // (2: at most 64 tokens and nothing but Y asked for: the streaming kernel for decode batches.  Also for a single
+    // layer: with weights that come from HBM it measured 13.8 / 23.5 us at 32 tokens against 19.6 / 43.8 us on the
+    // pieces below, 6912 x 2560 / 2560 x 6912; a piece streams its 512 rows through one multiprocessor's shallow ring)
+    auto few_tokens = [&](int i) { return gemv_batch_takes(items[i]) ? 2 : items[i].tokens <= 16 * 32 ? 1 : 0; };
     for (int first = 0; first < count;) {
-        const bool few = few_tokens(first);
-        const int most = few ? GEMM_GROUP_WIDE : GEMM_GROUP_MAX;
+        const int few = few_tokens(first);
+        const int most = few == 2 ? count : few ? GEMM_GROUP_WIDE : GEMM_GROUP_MAX;
         int n = 1;
         while (first + n < count && n < most && few_tokens(first + n) == few) ++n;
+        if (few == 2) {
+            sbn_status st = launch_gemv_batch(n, items + first, dense_codes, stream);
+            if (st != SBN_OK) return st;
+            first += n;
+            continue;
+        }
         if (few) {
             GemmGroupWide grp;
             grp.count = n;
-            int pieces = 0;
-            for (int i = 0; i < n; ++i) {
-                grp.g[i] = make_args(items[first + i]);
-                pieces += (int)ceil_div(items[first + i].d_out, sp::ROWS) * (int)ceil_div(ceil_div(items[first + i].tokens, 32), 4);
+            for (int i = 0; i < n; ++i) grp.g[i] = make_args(items[first + i]);
+            // pieces of four token units feed the matrix pipe best; a launch with fewer pieces than multiprocessors (one
+            // layer of a decode step) is cut finer, down to single units, so that its latency is that of a small piece
+            int wmax = 4, pieces = 0;
+            for (;; wmax >>= 1) {
+                pieces = 0;
+                for (int i = 0; i < n; ++i)
+                    pieces += (int)ceil_div(items[first + i].d_out, sp::ROWS) * (int)ceil_div(ceil_div(items[first + i].tokens, 32), wmax);
+                if (wmax == 1 || pieces >= device_cus()) break;
             }
             PieceTableNone tab;
             tab.per_block = -pieces;
-            tab.piece[0] = 0;
+            tab.piece[0] = (uint32_t)wmax;
             const int blocks = pieces < device_cus() ? pieces : device_cus();
             if (dense_codes) hipLaunchKernelGGL((gemm_smfmac_kernel<true, GemmGroupWide, PieceTableNone>), dim3(blocks), dim3(64 * sp::NW), 0, stream, grp, tab);
             else hipLaunchKernelGGL((gemm_smfmac_kernel<false, GemmGroupWide, PieceTableNone>), dim3(blocks), dim3(64 * sp::NW), 0, stream, grp, tab);

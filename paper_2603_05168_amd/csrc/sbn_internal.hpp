@@ -96,6 +96,10 @@ enum GemvForm : int { GEMV_2OF4 = 0, GEMV_DENSE = 1, GEMV_1OF4 = 2 };
 sbn_status launch_gemv(int count, const LinearItem *items, GemvForm form, hipStream_t stream);
 // dense_codes: the weights are dense 2-bit codes (packed form of N = M) instead of the 2:4 form
 sbn_status launch_gemm_smfmac(int count, const LinearItem *items, bool dense_codes, hipStream_t stream);
+// decode batches (sbn_batch.hip): problems of at most 64 tokens without bias or accumulator output stream their weights
+// once through a kernel of their own; launch_gemm_smfmac hands them over
+bool gemv_batch_takes(const LinearItem &it);
+sbn_status launch_gemv_batch(int count, const LinearItem *items, bool dense_codes, hipStream_t stream);
 sbn_status launch_gemm_dense(const LinearItem &it, const Pattern &pat, int8_t *w_dense, hipStream_t stream);
 sbn_status launch_gemm_dense_expanded(const LinearItem &it, const int8_t *w_dense, hipStream_t stream);
 sbn_status launch_linear_generic(const LinearItem &it, const Pattern &pat, hipStream_t stream);

@@ -562,6 +562,36 @@ def test_grouped_decode_batches_on_the_gemm_kernel(N, M):
         assert_rel(Y_list[i].cpu().numpy(), done[(t, sh)], Y_TOL, f"Y of problem {i} ({t} tokens, {sh})")
 
 
+@pytest.mark.parametrize("N,M", [(2, 4), (8, 8), (6, 8)])
+def test_grouped_decode_batches_streaming_kernel(N, M):
+    # Problems of at most 64 tokens with nothing but Y asked for take the streaming kernel for decode batches: 1 .. 64 tokens (two and four token tiles in separate launches), strips of 128 and of
+    # 256 rows (second call: enough rows for the wide strips), ragged last strips, an input dimension that is no
+    # multiple of a super-step (768 = 6 chunks), problems that share an input and problems that do not
+    s = sbn()
+    for reps in (1, 4):
+        tokens_of = [17, 64, 33, 20, 48, 32, 1, 16]
+        base = [(1100, 256), (520, 384), (4100, 768), (2052, 128)]
+        shapes = [base[i % 4] for i in range(10 * reps)]
+        toks = [tokens_of[i % len(tokens_of)] for i in range(len(shapes))]
+        Ws = {sh: sbn_synth.latent_weight(sh[0], sh[1], 2300 + sh[0]) for sh in set(shapes)}
+        packs = {sh: hip_pack(W, N, M) for sh, W in Ws.items()}
+        refs = {sh: oracle_pack(W, N, M) for sh, W in Ws.items()}
+        Xs = {(t, k): sbn_synth.activations(t, k, 2400 + 7 * t + k) for t, (_, k) in set(zip(toks, shapes))}
+        Xd = {key: x.to(DEV) for key, x in Xs.items()}
+        Y_list = [torch.full((t, a), float("nan"), dtype=torch.float32, device=DEV) for t, (a, _) in zip(toks, shapes)]
+        need = sum(s.sbn_workspace_bytes(s.SBN_OP_LINEAR, t, a, b, N, M) for t, (a, b) in zip(toks, shapes))
+        ws = s.new_workspace(need)
+        s.sbn_sparse_ternary_linear_grouped([Xd[(t, sh[1])] for t, sh in zip(toks, shapes)], [packs[sh][0] for sh in shapes],
+                                            [packs[sh][1] for sh in shapes], Y_list, N, M, ws, path=s.SBN_PATH_SMFMAC)
+        torch.cuda.synchronize()
+        done = {}
+        for i, (t, sh) in enumerate(zip(toks, shapes)):
+            if (t, sh) not in done:
+                _, g, Weff, _ = refs[sh]
+                done[(t, sh)] = oracle.sparse_ternary_linear(Xs[(t, sh[1])].float().numpy(), Weff, g)[0]
+            assert_rel(Y_list[i].cpu().numpy(), done[(t, sh)], Y_TOL, f"Y of problem {i} ({t} tokens, {sh}), {reps}")
+
+
 @pytest.mark.parametrize("N,M", [(2, 4), (1, 4)])
 @pytest.mark.parametrize("tokens,shape", [(8, (6912, 2560)), (1, (2560, 6912))])
 def test_config2_streaming_decode_full_size_as_timed(tokens, shape, N, M):
