@@ -354,12 +354,17 @@ def main():
                         sbn.sbn_sparse_ternary_linear(X, packs[r][0], packs[r][1], Yl[r], N, M, ws1, path=sbn.SBN_PATH_AUTO)
                     ms1 = timed(single_b, 128, 8)
                     gbps = R * pbytes / (ms * 1e-3) / 1e9
+                    # what a layer of the batch must move: packed weights, bf16 activations in, fp32 outputs (the outputs
+                    # are 40 % of the weights' bytes at 64 tokens and 3.2 times them at 512)
+                    allb = pbytes + 2 * tok * b + 4 * tok * a
                     batch_rows[f"{name}_B{tok}"] = {"stream_us_per_matrix": ms / R * 1e3, "stream_gbps_packed_bytes": gbps,
                                                     "frac_hbm": gbps / HBM_PEAK_GBPS,
+                                                    "frac_hbm_with_activation_and_output_bytes": gbps * allb / pbytes / HBM_PEAK_GBPS,
                                                     "tops_dense_equiv": 2.0 * tok * a * b * R / (ms * 1e-3) / 1e12,
                                                     "single_call_us": ms1 * 1e3, "copies": R}
                     log(f"[batch] {name} batch {tok}: stream {ms / R * 1e3:.2f} us per matrix ({gbps / HBM_PEAK_GBPS:.1%} of HBM peak "
-                        f"on packed bytes, {2.0 * tok * a * b * R / (ms * 1e-3) / 1e12:.0f} TOPS dense-equivalent), single call {ms1 * 1e3:.1f} us")
+                        f"on packed bytes, {gbps * allb / pbytes / HBM_PEAK_GBPS:.1%} with activations and outputs, "
+                        f"{2.0 * tok * a * b * R / (ms * 1e-3) / 1e12:.0f} TOPS dense-equivalent), single call {ms1 * 1e3:.1f} us")
                     del Yl, ws, grp, ws1
             del packs
             torch.cuda.empty_cache()
