@@ -69,7 +69,11 @@ typedef enum {
                                 Every other pattern (6:8, N:8, ...) runs as dense 2-bit codes - N = M as stored, the
                                 rest converted per call (sbn_convert_packed to N = M does it once instead) - with two
                                 sparse instructions per group of four weights (positions 0, 1 and positions 2, 3): the
-                                matrix-core time of a dense int8 product at a quarter of its weight bytes */
+                                matrix-core time of a dense int8 product at a quarter of its weight bytes.
+                                Decode batches (Section 3.2 measures decoding at batch 64 .. 512) take this path too:
+                                up to 64 tokens with neither bias nor acc_out a kernel that streams the weights once
+                                into registers (same instructions on 16 x 16 tiles), up to 512 tokens the GEMM kernel
+                                with its work dealt by row tile */
     SBN_PATH_DENSE_MFMA = 3, /* W_eff expanded to int8 with explicit zeros, dense int8 MFMA: the comparison path;
                                 d_in % 64 == 0 */
     SBN_PATH_GENERIC = 4     /* any supported pattern, plain integer kernel (reference speed only) */
