@@ -26,9 +26,10 @@ def _capture(fn):
     return g
 
 
-@pytest.mark.parametrize("tokens", [1, 8])
+@pytest.mark.parametrize("tokens", [1, 8, 32, 100])
 def test_replayed_streaming_decode_follows_its_inputs(tokens):
     # enough rows for the persistent streaming kernel; the activations change between the replays
+    # (32 tokens: the streaming kernel for decode batches; 100: the sparse GEMM kernel with its work dealt by row tile)
     s = sbn()
     shapes = [(4096, 512), (6144, 512)] * 16
     Ws = {sh: sbn_synth.latent_weight(sh[0], sh[1], 1500 + sh[0]) for sh in set(shapes)}
@@ -38,7 +39,7 @@ def test_replayed_streaming_decode_follows_its_inputs(tokens):
     Ys = [torch.full((tokens, a), float("nan"), dtype=torch.float32, device=DEV) for a, _ in shapes]
     ws = s.new_workspace(sum(s.sbn_workspace_bytes(s.SBN_OP_LINEAR, tokens, a, b, 2, 4) for a, b in shapes))
     grp = s.LinearGroup([X] * len(shapes), [packs[sh][0] for sh in shapes], [packs[sh][1] for sh in shapes], Ys, 2, 4, ws,
-                        s.SBN_PATH_GEMV)
+                        s.SBN_PATH_GEMV if tokens <= 16 else s.SBN_PATH_AUTO)
     X.copy_(sbn_synth.activations(tokens, 512, 1510).to(DEV))
     graph = _capture(grp.run)
     for replay in range(4):
