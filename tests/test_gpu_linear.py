@@ -590,6 +590,9 @@ def test_grouped_decode_batches_streaming_kernel(N, M):
                 _, g, Weff, _ = refs[sh]
                 done[(t, sh)] = oracle.sparse_ternary_linear(Xs[(t, sh[1])].float().numpy(), Weff, g)[0]
             assert_rel(Y_list[i].cpu().numpy(), done[(t, sh)], Y_TOL, f"Y of problem {i} ({t} tokens, {sh}), {reps}")
+            # this kernel has no accumulator output; Y within 1e-6 relative says the same: one unit of an accumulator
+            # is more than 2e-5 of |Y| at these input dimensions, the fp32 rescale errs by less than 2e-7
+            assert_rel(Y_list[i].cpu().numpy(), done[(t, sh)], 1e-6, f"accumulators behind Y of problem {i} ({t} tokens, {sh}), {reps}")
 
 
 @pytest.mark.parametrize("N,M", [(2, 4), (1, 4)])
