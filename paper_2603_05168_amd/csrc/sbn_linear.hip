@@ -4,6 +4,7 @@
 #include <algorithm>
 #include <atomic>
 #include <cstdlib>
+#include <type_traits>
 #include <vector>
 
 #include "sbn_internal.hpp"
@@ -256,6 +257,7 @@ struct GemvItem {
     int d_in, d_out, tokens, pad;
 };
 constexpr int GEMV_MAX_ITEMS = 40;
+constexpr int GEMV_ROW_VEC = 14;   // 16-byte vectors of a token row per lane when a wavefront of the single-call kernel quantizes it
 struct GemvTable {
     GemvItem it[GEMV_MAX_ITEMS];   // problem = blockIdx.y; row tile = blockIdx.x (surplus blocks exit at once)
 };
@@ -305,26 +307,74 @@ __global__ void __launch_bounds__(1024) gemv_smfmac_kernel(GemvTable tab)
     fetch(wave);
     if (self_quant) {
         // every block quantizes the few token rows itself (the quantizer's arithmetic), saving the quantizer's
-        // launch in front of a latency-bound call: pass 1 per-token maxima, pass 2 int8 rows into LDS
+        // launch in front of a latency-bound call
         const int nvec = K / 8, nthreads = (int)blockDim.x;
-        for (int t = 0; t < it.tokens; ++t) {
-            uint32_t m = 0;
-            for (int idx = threadIdx.x; idx < nvec; idx += nthreads) m = absmax_bits_bf16x8(it.X[(int64_t)t * nvec + idx], m);
+        if (nvec <= 64 * GEMV_ROW_VEC) {
+            // a wavefront per token row, the row in registers (two short rows at a time): the rows of a block cost one
+            // or two trips to memory in all, the maximum needs no barrier, the int8 row goes straight into LDS
+            auto finish = [&](int t, uint32_t m, auto &xv, auto nv) {
 #pragma unroll
-            for (int off = 32; off > 0; off >>= 1) {
-                const uint32_t o = (uint32_t)__shfl_xor((int)m, off, 64);
-                m = o > m ? o : m;
+                for (int off = 32; off > 0; off >>= 1) {
+                    const uint32_t o = (uint32_t)__shfl_xor((int)m, off, 64);
+                    m = o > m ? o : m;
+                }
+                const float sc = scale_from_absmax_bits(m);
+                if (lane == 0) sx_s[t] = sc;
+#pragma unroll
+                for (int i = 0; i < nv(); ++i) {
+                    const int idx = lane + 64 * i;
+                    if (idx < nvec) *reinterpret_cast<uint2 *>(xs + t * pitch + idx * 8) = quantize_bf16x8(xv[i], sc);
+                }
+            };
+            auto request = [&](int t, auto &xv, auto nv) {
+                uint32_t m = 0;
+#pragma unroll
+                for (int i = 0; i < nv(); ++i) {
+                    const int idx = lane + 64 * i;
+                    xv[i] = it.X[(int64_t)t * nvec + (idx < nvec ? idx : nvec - 1)];   // past the end the last vector again
+                }
+#pragma unroll
+                for (int i = 0; i < nv(); ++i) m = absmax_bits_bf16x8(xv[i], m);
+                return m;
+            };
+            if (nvec <= 64 * (GEMV_ROW_VEC / 2)) {
+                std::integral_constant<int, GEMV_ROW_VEC / 2> nv;
+                for (int t = wave; t < it.tokens; t += 2 * nwaves) {
+                    uint4 xa[GEMV_ROW_VEC / 2], xb[GEMV_ROW_VEC / 2];
+                    const int t2 = t + nwaves < it.tokens ? t + nwaves : t;   // the last row alone: quantized twice, alike
+                    const uint32_t ma = request(t, xa, nv), mb = request(t2, xb, nv);
+                    finish(t, ma, xa, nv);
+                    finish(t2, mb, xb, nv);
+                }
+            } else {
+                std::integral_constant<int, GEMV_ROW_VEC> nv;
+                for (int t = wave; t < it.tokens; t += nwaves) {
+                    uint4 xa[GEMV_ROW_VEC];
+                    const uint32_t ma = request(t, xa, nv);
+                    finish(t, ma, xa, nv);
+                }
             }
-            if (lane == 0) amax_s[t][wave] = m;
-        }
-        __syncthreads();
-        for (int t = 0; t < it.tokens; ++t) {
-            uint32_t m = 0;
-            for (int w = 0; w < nwaves; ++w) m = amax_s[t][w] > m ? amax_s[t][w] : m;
-            const float sc = scale_from_absmax_bits(m);
-            if (threadIdx.x == 0) sx_s[t] = sc;
-            for (int idx = threadIdx.x; idx < nvec; idx += nthreads)
-                *reinterpret_cast<uint2 *>(xs + t * pitch + idx * 8) = quantize_bf16x8(it.X[(int64_t)t * nvec + idx], sc);
+        } else {
+            // long rows: pass 1 per-token maxima, pass 2 int8 rows into LDS
+            for (int t = 0; t < it.tokens; ++t) {
+                uint32_t m = 0;
+                for (int idx = threadIdx.x; idx < nvec; idx += nthreads) m = absmax_bits_bf16x8(it.X[(int64_t)t * nvec + idx], m);
+#pragma unroll
+                for (int off = 32; off > 0; off >>= 1) {
+                    const uint32_t o = (uint32_t)__shfl_xor((int)m, off, 64);
+                    m = o > m ? o : m;
+                }
+                if (lane == 0) amax_s[t][wave] = m;
+            }
+            __syncthreads();
+            for (int t = 0; t < it.tokens; ++t) {
+                uint32_t m = 0;
+                for (int w = 0; w < nwaves; ++w) m = amax_s[t][w] > m ? amax_s[t][w] : m;
+                const float sc = scale_from_absmax_bits(m);
+                if (threadIdx.x == 0) sx_s[t] = sc;
+                for (int idx = threadIdx.x; idx < nvec; idx += nthreads)
+                    *reinterpret_cast<uint2 *>(xs + t * pitch + idx * 8) = quantize_bf16x8(it.X[(int64_t)t * nvec + idx], sc);
+            }
         }
         __syncthreads();
     }
@@ -1106,7 +1156,7 @@ static sbn_status launch_gemv_as(int count, const LinearItem *items, hipStream_t
         // 2560 x 6912: 9.0-10.3 us for 1-4 tokens against 12 us with the quantizer launched in front; at 8
         // tokens the per-token passes of every block cost more than the launch they save: 13-16 us)
         constexpr int64_t GEMV_SELF_QUANT_LDS = 112 * 1024;
-        constexpr int64_t GEMV_SELF_QUANT_TOKENS = 4;
+        constexpr int64_t GEMV_SELF_QUANT_TOKENS = 16;
         int64_t dyn_lds = 0;
         bool self_quant = true;
         for (int i = 0; i < n; ++i) {
