@@ -215,11 +215,13 @@ __global__ void __launch_bounds__(64 * BNW) gemv_batch_kernel(BatchTable tab_arg
             fetch_tile(cf, xs[d]);
             advance(cf);
             issue(qi[d], qc[d]);
-            if (4 * cp.ks + c4 >= cp.nchunks) {   // chunks past a ragged input dimension
+            if (4 * cp.ks + 4 > cp.nchunks) {   // the last super-step of a ragged input dimension (the same for the whole block)
+                if (4 * cp.ks + c4 >= cp.nchunks) {   // chunks past its end
 #pragma unroll
-                for (int a = 0; a < RT; ++a) {
-                    cc[a] = make_uint4(0, 0, 0, 0);
-                    if constexpr (DENSE) ic[a] = make_uint4(0, 0, 0, 0);   // all eight words are codes
+                    for (int a = 0; a < RT; ++a) {
+                        cc[a] = make_uint4(0, 0, 0, 0);
+                        if constexpr (DENSE) ic[a] = make_uint4(0, 0, 0, 0);   // all eight words are codes
+                    }
                 }
             }
             const int8_t *xt = lds + parity * XBUF + r * XP + boff;
@@ -305,7 +307,7 @@ __global__ void __launch_bounds__(64 * BNW) gemv_batch_kernel(BatchTable tab_arg
 // tokens <= 64, d_out % 4 == 0, d_in % 128 == 0, activations quantized; the problems of a launch share a token-tile count
 bool gemv_batch_takes(const LinearItem &it)
 {
-    return it.tokens <= 64 && it.d_out % 4 == 0 && it.d_in % CHUNK == 0 && !it.bias && !it.acc_out;
+    return it.tokens <= 64 && it.d_out % 4 == 0 && it.d_in % CHUNK == 0 && it.d_in <= (1 << 24) && !it.bias && !it.acc_out;
 }
 
 template <int TT, int RT, bool DENSE>
