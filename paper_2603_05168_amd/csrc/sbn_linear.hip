@@ -1152,9 +1152,9 @@ static sbn_status launch_gemv_as(int count, const LinearItem *items, hipStream_t
         }
         // --- otherwise: one block per 16 rows, wavefronts split the input dimension (lowest latency)
         n = count - first < GEMV_MAX_ITEMS ? count - first : GEMV_MAX_ITEMS;
-        // the blocks quantize the activations themselves when a problem has few tokens (measured at 6912 x 2560 and
-        // 2560 x 6912: 9.0-10.3 us for 1-4 tokens against 12 us with the quantizer launched in front; at 8
-        // tokens the per-token passes of every block cost more than the launch they save: 13-16 us)
+        // the blocks quantize the activations themselves (measured at 6912 x 2560 and 2560 x 6912: 9.3-9.7 us for
+        // 1-16 tokens against 12 us with the quantizer launched in front; a wavefront per token row with the row in
+        // registers - walking the tokens one after the other cost a trip to memory per token and pass: 13-16 us at 8)
         constexpr int64_t GEMV_SELF_QUANT_LDS = 112 * 1024;
         constexpr int64_t GEMV_SELF_QUANT_TOKENS = 16;
         int64_t dyn_lds = 0;
