@@ -478,6 +478,32 @@ def test_grouped_streaming_gemv_against_oracle(tokens, spin_limit, spin_limits):
         assert_rel(Y_list[i].cpu().numpy(), ref[sh], Y_TOL, f"Y of problem {i}")
 
 
+@pytest.mark.parametrize("N,M", [(2, 4), (8, 8)])
+@pytest.mark.parametrize("tokens", [1, 8, 13])
+def test_grouped_streaming_rows_that_end_mid_line(tokens, N, M):
+    # Input dimensions whose packed rows end 64 bytes past a cache line (22 and 54 chunks of 32 bytes: 2816 and 6912),
+    # with more super-steps than the load queue holds (units handed out one at a time) and a partial last super-step;
+    # row counts that are no multiple of 32, 16 or 4; every output against the oracle.
+    s = sbn()
+    shapes = [(2050, 2816), (1030, 6912)] * 32
+    Ws = {sh: sbn_synth.latent_weight(sh[0], sh[1], 2500 + sh[0]) for sh in set(shapes)}
+    packs = {sh: hip_pack(W, N, M) for sh, W in Ws.items()}
+    Xs = {k: sbn_synth.activations(tokens, k, 2600 + k) for k in (2816, 6912)}
+    Xd = {k: x.to(DEV) for k, x in Xs.items()}
+    Y_list = [torch.full((tokens, a), float("nan"), dtype=torch.float32, device=DEV) for a, _ in shapes]
+    ws = s.new_workspace(sum(s.sbn_workspace_bytes(s.SBN_OP_LINEAR, tokens, a, b, N, M) for a, b in shapes))
+    s.sbn_sparse_ternary_linear_grouped([Xd[b] for _, b in shapes], [packs[sh][0] for sh in shapes],
+                                        [packs[sh][1] for sh in shapes], Y_list, N, M, ws, path=s.SBN_PATH_GEMV)
+    torch.cuda.synchronize()
+    ref = {}
+    for sh, W in Ws.items():
+        _, g, Weff, _ = oracle_pack(W, N, M)
+        ref[sh] = oracle.sparse_ternary_linear(Xs[sh[1]].float().numpy(), Weff, g)[0]
+    for i, sh in enumerate(shapes):
+        assert_rel(Y_list[i].cpu().numpy(), ref[sh], Y_TOL, f"Y of problem {i} {sh}")
+        assert_rel(Y_list[i].cpu().numpy(), ref[sh], 2e-6, f"accumulators behind Y of problem {i} {sh}")
+
+
 def test_streaming_gemv_workspace_reuse_and_many_inputs():
     # (a) the same workspace serves calls with different inputs one after the other: every call
     # must see its own quantized activations; (b) six distinct inputs interleaved over the problems
